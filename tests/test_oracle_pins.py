@@ -1,0 +1,470 @@
+"""Pins for the CPU oracle: hand-worked vectors, closed forms, invariants, brute force and
+independent library routines.  None of these re-type the oracle's own code: the numpy
+re-derivations below use different primitives (exact rationals, float64 matmul, bit unpacking)."""
+import os
+from fractions import Fraction
+
+import numpy as np
+import pytest
+
+import synth_inputs as si
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "quantizer_handworked.txt")
+ALL_BITS = (2, 3, 4, 8)
+
+
+def _golden_rows():
+    rows = []
+    with open(GOLDEN) as f:
+        for line in f:
+            line = line.strip()
+            if not line or line.startswith("#"):
+                continue
+            bits, vals, scale, zp, codes, packed = [p.strip() for p in line.split("|")]
+            rows.append((int(bits), [float(v) for v in vals.split()], float(scale), int(zp),
+                         [int(c) for c in codes.split()], bytes.fromhex(packed.replace(" ", ""))))
+    return rows
+
+
+# ----------------------------------------------------------------------------- 16-bit formats
+
+def test_f16_decode_all_patterns(orc):
+    bits = np.arange(65536, dtype=np.uint16)
+    got = orc.f16_to_f64(bits)
+    ref = bits.view(np.float16).astype(np.float64)
+    nan = np.isnan(ref)
+    assert np.array_equal(np.isnan(got), nan)
+    assert np.array_equal(got[~nan], ref[~nan])
+    assert np.array_equal(np.signbit(got[~nan]), np.signbit(ref[~nan]))
+
+
+def test_f16_encode_matches_numpy_rne(orc):
+    rng = np.random.default_rng(1)
+    v = np.concatenate([
+        rng.normal(0, 1, 20000), rng.normal(0, 300, 20000), rng.normal(0, 1e-5, 20000),
+        rng.normal(0, 1e-7, 5000), np.array([0.0, -0.0, 65504, 65519.99, 65520, 1e9, -1e9, 2.0 ** -24, 2.0 ** -25,
+                                             2.0 ** -25 * 1.0000001, 2.0 ** -14, 2.0 ** -14 - 2.0 ** -26]),
+    ])
+    # exact ties between neighbouring halfs: midpoints of consecutive finite patterns
+    pats = np.arange(0, 0x7BFF, dtype=np.uint16)
+    lo = pats.view(np.float16).astype(np.float64)
+    hi = (pats + 1).astype(np.uint16).view(np.float16).astype(np.float64)
+    v = np.concatenate([v, (lo + hi) / 2, -(lo + hi) / 2])
+    got = orc.f64_to_f16(v)
+    with np.errstate(over="ignore"):
+        ref = v.astype(np.float16).view(np.uint16)
+    assert np.array_equal(got, ref)
+
+
+def test_bf16_roundtrip_and_rne(orc):
+    import torch
+    rng = np.random.default_rng(2)
+    f = np.concatenate([rng.normal(0, 1, 20000), rng.normal(0, 1e4, 5000), rng.normal(0, 1e-30, 2000)]).astype(
+        np.float32)
+    got = orc.f64_to_f16(f.astype(np.float64), orc.BF16)
+    ref = torch.from_numpy(f).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    assert np.array_equal(got, ref)
+    back = orc.f16_to_f64(got, orc.BF16)
+    ref_back = torch.from_numpy(ref.view(np.int16)).view(torch.bfloat16).to(torch.float64).numpy()
+    assert np.array_equal(back, ref_back)
+
+
+# ----------------------------------------------------------------------------- quantiser
+
+@pytest.mark.parametrize("row", _golden_rows(), ids=lambda r: f"b{r[0]}")
+def test_quantizer_handworked(orc, row):
+    bits, vals, scale, zp, codes, packed = row
+    w = np.array([vals], np.float16)
+    assert np.array_equal(w.astype(np.float64)[0], vals), "fixture values must be exact in fp16"
+    c, s, z = orc.quantize_weights(w, bits)
+    assert s[0] == np.float32(scale) and z[0] == zp
+    assert c[0].tolist() == codes
+    if (len(codes) * bits) % 8 == 0:
+        assert bytes(orc.pack_weights(c, bits)[0]) == packed
+
+
+def _quant_exact_reference(vals_f16, bits):
+    """Independent derivation: scale and reciprocal as correctly rounded fp32 values obtained through exact
+    rational arithmetic, code from the exactly rounded fp32 product.  Returns codes, scale, zp and a mask of
+    inputs whose exact product sits close to a rounding tie (where the reading 'multiply by reciprocal' and
+    the reading 'divide' could differ)."""
+    def rnd32(fr: Fraction) -> np.float32:
+        # correctly rounded fp32 of an exact rational: float(Fraction) is correctly rounded to double;
+        # double->single double rounding is avoided by checking the two neighbouring singles exactly.
+        d = np.float32(float(fr))
+        cands = [np.nextafter(d, np.float32(-np.inf)), d, np.nextafter(d, np.float32(np.inf))]
+        best = min(cands, key=lambda c: (abs(Fraction(float(c)) - fr), int(np.float32(c).view(np.uint32)) & 1))
+        return np.float32(best)
+
+    qmax = (1 << bits) - 1
+    v = [Fraction(float(x)) for x in vals_f16]
+    lo, hi = min(min(v), Fraction(0)), max(max(v), Fraction(0))
+    if hi == lo:
+        s = np.float32(1.0)
+    else:
+        s = rnd32(Fraction(float(rnd32(hi - lo))) / qmax)
+    inv = rnd32(Fraction(1) / Fraction(float(s)))
+
+    def rne(fr: Fraction) -> int:
+        fl = fr.numerator // fr.denominator
+        rem = fr - fl
+        if rem > Fraction(1, 2) or (rem == Fraction(1, 2) and fl % 2 == 1):
+            return fl + 1
+        return fl
+
+    z = min(max(rne(Fraction(float(rnd32(-lo * Fraction(float(inv)))))), 0), qmax)
+    codes, near_tie = [], []
+    for x in v:
+        p = Fraction(float(rnd32(x * Fraction(float(inv)))))
+        codes.append(min(max(rne(p) + z, 0), qmax))
+        frac = (x / Fraction(float(s))) % 1
+        near_tie.append(abs(frac - Fraction(1, 2)) < Fraction(1, 10 ** 6))
+    return codes, s, z, near_tie
+
+
+@pytest.mark.parametrize("bits", ALL_BITS)
+def test_quantizer_bruteforce_exact_rational(orc, bits):
+    rng = np.random.default_rng(10 + bits)
+    for trial in range(12):
+        K = int(rng.integers(4, 64))
+        w = (rng.normal(0, 0.02 if trial % 2 else 1.0, (1, K))).astype(np.float16)
+        c, s, z = orc.quantize_weights(w, bits)
+        rc, rs, rz, _ = _quant_exact_reference(w[0], bits)
+        assert s[0] == rs and z[0] == rz
+        assert c[0].tolist() == rc
+
+
+@pytest.mark.parametrize("bits", ALL_BITS)
+def test_quantizer_invariants(orc, bits):
+    qmax = (1 << bits) - 1
+    w = si.weights_f16(3, f"pin/w{bits}", 64, 320)
+    w[5] = 0  # constant-zero row
+    w[6] = np.abs(w[6])  # all non-negative: lo is forced to 0
+    w[7] = -np.abs(w[7])  # all non-positive
+    c, s, z = orc.quantize_weights(w, bits)
+    wd = w.astype(np.float64)
+    assert c.max() <= qmax and z.min() >= 0 and z.max() <= qmax
+    assert s[5] == 1.0 and z[5] == 0 and not c[5].any()
+    assert z[6] == 0 and z[7] == qmax
+    what = s[:, None].astype(np.float64) * (c.astype(np.int64) - z[:, None])
+    # endpoints map to the extreme codes, every element is within half a step (plus fp32 slack)
+    for n in range(64):
+        if n == 5:
+            continue
+        lo, hi = min(wd[n].min(), 0), max(wd[n].max(), 0)
+        assert c[n, np.argmin(wd[n])] == (0 if wd[n].min() <= 0 else c[n, np.argmin(wd[n])])
+        assert c[n, np.argmax(wd[n])] == (qmax if wd[n].max() >= 0 else c[n, np.argmax(wd[n])])
+        assert abs(float(s[n]) * qmax - (hi - lo)) <= 1e-6 * (hi - lo)
+        # the zero point is rounded, so the grid is shifted by up to half a step: error <= one step at the ends,
+        # and <= half a step wherever the code was not clamped
+        err = np.abs(what[n] - wd[n])
+        interior = (c[n] > 0) & (c[n] < qmax)
+        assert err[interior].max(initial=0) <= 0.5 * s[n] * (1 + 1e-5)
+        assert err.max() <= 1.0 * s[n] * (1 + 1e-5)
+
+
+@pytest.mark.parametrize("bits", ALL_BITS)
+def test_round_trip_of_every_code(orc, bits):
+    """quantise(dequantise(q)) == q for every code, on grids that are exact in fp16 (power-of-two scales)."""
+    qmax = (1 << bits) - 1
+    for scale in (1.0, 0.5, 0.0625, 4.0):
+        for z in sorted({0, 1, qmax // 2, qmax - 1, qmax}):
+            grid = ((np.arange(qmax + 1) - z) * scale).astype(np.float16)[None]
+            c, s, zz = orc.quantize_weights(grid, bits)
+            assert s[0] == np.float32(scale) and zz[0] == z
+            assert c[0].tolist() == list(range(qmax + 1))
+
+
+@pytest.mark.parametrize("bits", (4, 8))
+def test_symmetric_quantizer(orc, bits):
+    Q = (1 << (bits - 1)) - 1
+    w = si.weights_f16(4, f"pin/sym{bits}", 32, 320)
+    w[3] = 0
+    c, s, z = orc.quantize_weights(w, bits, symmetric=True)
+    ci = c.view(np.int8).astype(np.int64)
+    assert not z.any() and s[3] == 1.0 and not ci[3].any()
+    assert ci.max() <= Q and ci.min() >= -Q
+    wd = w.astype(np.float64)
+    for n in range(32):
+        if n == 3:
+            continue
+        amax = np.abs(wd[n]).max()
+        assert s[n] == np.float32(np.float32(amax) / np.float32(Q))
+        k = int(np.argmax(np.abs(wd[n])))
+        assert ci[n, k] == (Q if wd[n, k] > 0 else -Q)
+        assert np.abs(ci[n] * np.float64(s[n]) - wd[n]).max() <= 0.5 * s[n] * (1 + 1e-5)
+    # antisymmetry under x -> -x
+    c2, s2, _ = orc.quantize_weights((-w).astype(np.float16), bits, symmetric=True)
+    assert np.array_equal(s2, s) and np.array_equal(c2.view(np.int8).astype(np.int64), -ci)
+    # textbook formula through numpy fp32 primitives
+    inv = np.float32(1.0) / s
+    ref = np.clip(np.rint(w.astype(np.float32) * inv[:, None]), -Q, Q).astype(np.int64)
+    assert np.array_equal(ci, ref)
+
+
+def test_activation_quantizer_is_textbook_affine(orc):
+    x = si.activations_f16(5, "pin/x", 96, 320, outlier_prob=0.01)
+    s, z = orc.act_params(x)
+    xf = x.astype(np.float32)
+    lo, hi = min(xf.min(), np.float32(0)), max(xf.max(), np.float32(0))
+    s_ref = np.float32(hi - lo) / np.float32(255)
+    inv = np.float32(1) / s_ref
+    z_ref = int(np.clip(np.rint(-lo * inv), 0, 255))
+    assert s == s_ref and z == z_ref
+    q = orc.act_quantize(x, s, z)
+    q_ref = np.clip(np.rint(xf * inv).astype(np.int64) + z_ref, 0, 255)
+    assert np.array_equal(q, q_ref)
+    assert q.min() == 0 and q.max() == 255
+    # static parameters narrower than the data: saturation, no wrap-around
+    q2 = orc.act_quantize(x, np.float32(0.01), 100)
+    q2_ref = np.clip(np.rint(xf * (np.float32(1) / np.float32(0.01))).astype(np.int64) + 100, 0, 255)
+    assert np.array_equal(q2, q2_ref)
+
+
+# ----------------------------------------------------------------------------- packing
+
+def _pack_reference(codes, bits):
+    """Independent packer: explode every code into its bits (LSB first), concatenate per row, regroup into
+    bytes LSB first, all through numpy's bit unpack/pack."""
+    N, K = codes.shape
+    b = np.unpackbits(codes[:, :, None], axis=2, bitorder="little")[:, :, :bits]
+    return np.packbits(b.reshape(N, K * bits), axis=1, bitorder="little")
+
+
+@pytest.mark.parametrize("bits", ALL_BITS)
+@pytest.mark.parametrize("K", (32, 64, 320, 5120))
+def test_pack_roundtrip_and_layout(orc, bits, K):
+    rng = np.random.default_rng(100 * bits + K)
+    codes = rng.integers(0, 1 << bits, (7, K)).astype(np.uint8)
+    p = orc.pack_weights(codes, bits)
+    assert p.shape == (7, K * bits // 8)
+    assert np.array_equal(p, _pack_reference(codes, bits))
+    assert np.array_equal(orc.unpack_weights(p, K, bits), codes)
+
+
+def test_pack_nibble_and_crumb_positions(orc):
+    # 4 bit: even k in the low nibble; 2 bit: k mod 4 == 0 in bits 1:0
+    assert orc.pack_weights(np.array([[0x3, 0xA]], np.uint8), 4)[0, 0] == 0xA3
+    assert orc.pack_weights(np.array([[1, 0, 0, 0]], np.uint8), 2)[0, 0] == 0x01
+    assert orc.pack_weights(np.array([[0, 0, 0, 2]], np.uint8), 2)[0, 0] == 0x80
+    with pytest.raises(ValueError):
+        orc.pack_weights(np.zeros((1, 5), np.uint8), 3)
+
+
+# ----------------------------------------------------------------------------- weight-only linear
+
+def _random_quantised_layer(orc, seed, M, K, N, bits, symmetric=False, outliers=0.0):
+    x = si.activations_f16(seed, "pin/lx", M, K, outlier_prob=outliers)
+    w = si.weights_f16(seed, "pin/lw", N, K)
+    b = si.bias_f16(seed, "pin/lb", N)
+    c, s, z = orc.quantize_weights(w, bits, symmetric=symmetric)
+    return x, w, b, c, s, z
+
+
+@pytest.mark.parametrize("bits", ALL_BITS)
+def test_w_only_equals_float64_matmul_on_dequantised_weights(orc, bits):
+    x, w, b, c, s, z = _random_quantised_layer(orc, 20 + bits, 33, 128, 48, bits)
+    y = orc.linear_w_only(x, c, s, z, b).view(np.float16)
+    what = s.astype(np.float64)[:, None] * (c.astype(np.float64) - z[:, None])
+    ref = x.astype(np.float64) @ what.T + b.astype(np.float64)
+    ref16 = ref.astype(np.float16)
+    # different summation order: allow one fp16 ulp on a handful of borderline sums
+    ulp = np.abs(y.astype(np.float64) - ref16.astype(np.float64)) / np.maximum(np.spacing(np.abs(ref16)).astype(
+        np.float64), 1e-30)
+    assert ulp.max() <= 1.0 and (ulp > 0).mean() < 0.01
+    # rows subset == the same rows of the full result
+    rows = [0, 7, 32]
+    assert np.array_equal(orc.linear_w_only(x, c, s, z, b, rows=rows).view(np.float16), y[rows])
+    # the quantiser's error bound carried through the sum (interior codes: half a step per weight)
+    yfp = x.astype(np.float64) @ w.astype(np.float64).T + b.astype(np.float64)
+    bound = np.abs(x.astype(np.float64)).sum(1)[:, None] * s[None, :] * 1.0 + 1e-2
+    assert (np.abs(ref - yfp) <= bound).all()
+
+
+def test_w_only_bruteforce_triple_loop(orc):
+    rng = np.random.default_rng(3)
+    M, K, N = 3, 8, 4
+    x = rng.normal(0, 1, (M, K)).astype(np.float16)
+    c = rng.integers(0, 16, (N, K)).astype(np.uint8)
+    s = rng.uniform(0.01, 0.1, N).astype(np.float32)
+    z = rng.integers(0, 16, N).astype(np.int32)
+    b = rng.normal(0, 0.1, N).astype(np.float16)
+    y = orc.linear_w_only(x, c, s, z, b).view(np.float16)
+    for m in range(M):
+        for n in range(N):
+            acc = Fraction(0)
+            for k in range(K):
+                acc += Fraction(float(x[m, k])) * Fraction(float(s[n])) * (int(c[n, k]) - int(z[n]))
+            acc += Fraction(float(b[n]))
+            assert y[m, n] == np.float16(float(acc)), (m, n)
+
+
+def test_w_only_integer_special_case_is_exact(orc):
+    rng = np.random.default_rng(4)
+    x = rng.integers(-8, 9, (16, 64)).astype(np.float16)
+    c = rng.integers(0, 256, (24, 64)).astype(np.uint8)
+    y = orc.linear_w_only(x, c, np.ones(24, np.float32), np.zeros(24, np.int32), None).view(np.float16)
+    ref = x.astype(np.int64) @ c.astype(np.int64).T
+    assert np.abs(ref).max() < 2 ** 11 * 32
+    assert np.array_equal(y, ref.astype(np.float16))
+
+
+def test_w_only_transposed_operand_would_fail(orc):
+    """N != K and asymmetric content: a transposed weight index cannot produce the same numbers."""
+    x, w, b, c, s, z = _random_quantised_layer(orc, 31, 5, 64, 96, 4)
+    y = orc.linear_w_only(x, c, s, z, None).view(np.float16).astype(np.float64)
+    what = s.astype(np.float64)[:, None] * (c.astype(np.float64) - z[:, None])
+    assert y.shape == (5, 96)
+    assert np.allclose(y, x.astype(np.float64) @ what.T, rtol=2e-3, atol=1e-3)
+
+
+def test_w_only_bf16(orc):
+    import torch
+    rng = np.random.default_rng(5)
+    xb = torch.from_numpy(rng.normal(0, 1, (9, 64)).astype(np.float32)).to(torch.bfloat16)
+    x_bits = xb.view(torch.int16).numpy().view(np.uint16)
+    c = rng.integers(0, 16, (12, 64)).astype(np.uint8)
+    s = rng.uniform(0.01, 0.1, 12).astype(np.float32)
+    z = rng.integers(0, 16, 12).astype(np.int32)
+    y = orc.linear_w_only(x_bits, c, s, z, None, dtype=orc.BF16)
+    what = s.astype(np.float64)[:, None] * (c.astype(np.float64) - z[:, None])
+    ref = torch.from_numpy(xb.to(torch.float64).numpy() @ what.T).to(torch.float32).to(torch.bfloat16)
+    got = torch.from_numpy(y.view(np.int16)).view(torch.bfloat16)
+    assert (got.float() - ref.float()).abs().max() <= 2 ** -7 * ref.float().abs().max()
+
+
+# ----------------------------------------------------------------------------- 8-bit activation linear
+
+@pytest.mark.parametrize("bits,symmetric", [(8, True), (8, False), (4, False)])
+def test_a8_closed_form_and_int64_bruteforce(orc, bits, symmetric):
+    x, w, b, c, s, z = _random_quantised_layer(orc, 40 + bits + symmetric, 37, 192, 40, bits, symmetric, 0.01)
+    y, acc, (sx, zx) = orc.linear_a8(x, c, s, z, w_signed=symmetric, bias=b)
+    assert (sx, zx) == orc.act_params(x)
+    qx = orc.act_quantize(x, sx, zx).astype(np.int64)
+    qw = (c.view(np.int8) if symmetric else c).astype(np.int64)
+    K = x.shape[1]
+    # closed form: raw code product minus the three zero-point terms
+    raw = qx @ qw.T
+    closed = raw - zx * qw.sum(1)[None, :] - z.astype(np.int64)[None, :] * qx.sum(1)[:, None] + K * zx * z.astype(
+        np.int64)[None, :]
+    assert np.array_equal(acc.astype(np.int64), closed)
+    assert np.array_equal(orc.code_rowsum(c, signed=symmetric).astype(np.int64), qw.sum(1))
+    # output: ACC * s_x * s_w + bias in float64, one rounding
+    ref = (closed.astype(np.float64) * (np.float64(sx) * s.astype(np.float64))[None, :] + b.astype(
+        np.float64)).astype(np.float16)
+    assert np.array_equal(y.view(np.float16), ref)
+    # consistency with the weight-only definition applied to dequantised activations
+    xhat = (qx - zx).astype(np.float64) * np.float64(sx)
+    what = s.astype(np.float64)[:, None] * (qw - z[:, None]).astype(np.float64)
+    ref2 = xhat @ what.T + b.astype(np.float64)
+    assert np.allclose(y.view(np.float16).astype(np.float64), ref2, rtol=1.5e-3, atol=1e-4)
+    # and it approximates the unquantised layer
+    yfp = x.astype(np.float64) @ w.astype(np.float64).T + b.astype(np.float64)
+    rel = np.linalg.norm(ref2 - yfp) / np.linalg.norm(yfp)
+    assert rel < (0.05 if bits == 8 else 0.2)
+
+
+def test_a8_static_params_and_row_subset(orc):
+    x, w, b, c, s, z = _random_quantised_layer(orc, 50, 21, 64, 16, 4)
+    y, acc, act = orc.linear_a8(x, c, s, z, act=(np.float32(0.05), 120), bias=None)
+    assert act == (np.float32(0.05), 120)
+    qx = orc.act_quantize(x, np.float32(0.05), 120).astype(np.int64)
+    ref = (qx - 120) @ (c.astype(np.int64) - z[:, None]).T
+    assert np.array_equal(acc, ref)
+    # dynamic parameters always come from ALL rows, even when only some rows are evaluated
+    yd, accd, actd = orc.linear_a8(x, c, s, z)
+    ys, accs, acts = orc.linear_a8(x, c, s, z, rows=[20, 3])
+    assert acts == actd and np.array_equal(accs, accd[[20, 3]]) and np.array_equal(ys, yd[[20, 3]])
+
+
+def test_a8_overflow_is_reported(orc):
+    K = 40000  # 255 * 255 * K exceeds int32
+    x = np.full((1, K), 1.0, np.float16)
+    x[0, 0] = 0
+    c = np.full((1, K), 255, np.uint8)
+    with pytest.raises(RuntimeError):
+        orc.linear_a8(x, c, np.ones(1, np.float32), np.zeros(1, np.int32))
+
+
+# ----------------------------------------------------------------------------- BOS-aware K/V projection
+
+def _bos_case(orc, seed, B=3, T=9, K=128, N=40, shared=True):
+    ctx = si.bos_context_f16(seed, "pin/ctx", B, T, K, n_outlier=4, shared_bos=shared)
+    w = si.weights_f16(seed, "pin/wk", N, K)
+    c, s, z = orc.quantize_weights(w, 8, symmetric=True)
+    return ctx, w, c, s, z
+
+
+def test_bos_row_is_fp16_linear_and_body_is_a8_without_the_row(orc):
+    ctx, w, c, s, z = _bos_case(orc, 60, shared=False)
+    B, T, K = ctx.shape
+    y, act = orc.bos_aware_kv_proj(ctx, c, s, z, w_signed=True, w_f16=w)
+    # token 0: plain floating-point linear with the unquantised weights (float64 matmul, one rounding)
+    ref0 = (ctx[:, 0, :].astype(np.float64) @ w.astype(np.float64).T).astype(np.float16)
+    assert np.array_equal(y[:, 0, :].view(np.float16), ref0)
+    # tokens 1..: the 8-bit path run on the tensor with the BOS rows deleted
+    body = np.ascontiguousarray(ctx[:, 1:, :]).reshape(B * (T - 1), K)
+    yb, _, actb = orc.linear_a8(body, c, s, z, w_signed=True)
+    assert act == actb
+    assert np.array_equal(y[:, 1:, :].reshape(B * (T - 1), -1), yb)
+    # the activation range excludes the outlier row
+    assert act == orc.act_params(body)
+    assert float(act[0]) * 255 < 0.5 * float(np.abs(ctx[:, 0, :].astype(np.float64)).max())
+
+
+def test_bos_precomputed_equals_runtime_when_bos_is_shared(orc):
+    ctx, w, c, s, z = _bos_case(orc, 61, shared=True)
+    y_rt, _ = orc.bos_aware_kv_proj(ctx, c, s, z, w_signed=True, w_f16=w)
+    bos_out = orc.linear_fp(ctx[0, 0:1, :], w)[0]
+    y_pc, _ = orc.bos_aware_kv_proj(ctx, c, s, z, w_signed=True, bos_out=bos_out)
+    assert np.array_equal(y_rt, y_pc)
+    with pytest.raises(RuntimeError):
+        orc.bos_aware_kv_proj(ctx, c, s, z, w_signed=True)  # neither source for the BOS row
+    with pytest.raises(RuntimeError):
+        orc.bos_aware_kv_proj(ctx, c, s, z, w_signed=True, w_f16=w, bos_out=bos_out)  # both
+
+
+def test_bos_aware_beats_naive_all_row_quantisation(orc):
+    """Direction fixed by Sec. 3.1: with the outlier row inside the 8-bit range most other values collapse
+    towards the zero point; removing it shrinks the scale and the error on the remaining tokens."""
+    ctx = si.bos_context_f16(62, "pin/ctx2", 4, 77, 256, n_outlier=16, gain=60.0)
+    w = si.weights_f16(62, "pin/wk2", 48, 256)
+    c, s, z = orc.quantize_weights(w, 8, symmetric=True)
+    y_aware, act_a = orc.bos_aware_kv_proj(ctx, c, s, z, w_signed=True, w_f16=w)
+    y_naive, act_n = orc.bos_aware_kv_proj(ctx, c, s, z, w_signed=True, naive_all_rows=True)
+    assert float(act_n[0]) > 5 * float(act_a[0])
+    ref = ctx.astype(np.float64) @ w.astype(np.float64).T
+    ea = np.linalg.norm(y_aware.view(np.float16).astype(np.float64)[:, 1:] - ref[:, 1:])
+    en = np.linalg.norm(y_naive.view(np.float16).astype(np.float64)[:, 1:] - ref[:, 1:])
+    assert ea * 3 < en
+    body_codes = orc.act_quantize(ctx[:, 1:, :].reshape(-1, 256), *act_n)
+    assert len(np.unique(body_codes)) <= 24  # the body occupies a sliver of the 256 codes
+    assert len(np.unique(orc.act_quantize(ctx[:, 1:, :].reshape(-1, 256), *act_a))) > 200
+
+
+# ----------------------------------------------------------------------------- input recipes
+
+def test_sweep_layer_table_matches_the_stated_workload():
+    layers, mean = si.sweep_layers()
+    assert len(layers) == 120
+    assert abs(mean - 3.66) <= 0.01
+    assert {l.bits for l in layers} <= {2, 3, 4, 8}
+    assert sum(1 for l in layers if l.kind == "kv") == 24
+    assert {l.M for l in layers if l.kind == "linear"} == {16384, 4096}
+    # same seed, same table
+    assert [l.bits for l in si.sweep_layers()[0]] == [l.bits for l in layers]
+
+
+def test_generators_are_deterministic_and_have_the_stated_moments():
+    a = si.activations_f16(0, "t/x", 512, 640, outlier_prob=0.01)
+    assert np.array_equal(a, si.activations_f16(0, "t/x", 512, 640, outlier_prob=0.01))
+    assert not np.array_equal(a, si.activations_f16(1, "t/x", 512, 640, outlier_prob=0.01))
+    base = si.activations_f16(0, "t/x", 512, 640).astype(np.float64)
+    assert abs(base.mean()) < 0.01 and abs(base.std() - 1) < 0.01
+    changed = (a.astype(np.float64) != base).mean()
+    assert 0.008 < changed < 0.012
+    w = si.weights_f16(0, "t/w", 640, 640).astype(np.float64)
+    assert abs(w.std() - 0.02) < 0.0005
+    ctx = si.bos_context_f16(0, "t/ctx", 8, 77, 2048).astype(np.float64)
+    assert np.array_equal(ctx[0, 0], ctx[7, 0])
+    assert np.abs(ctx[:, 0]).max() > 5 * np.abs(ctx[:, 1:]).max() / 2
