@@ -1,0 +1,153 @@
+/*
+ * mixdq.h — C ABI of the MI355X (gfx950) quantized-linear library.
+ *
+ * The library implements the deployment hot path that the MixDQ paper (arxiv 2405.17873)
+ * configures: mixed-precision quantized linear layers of a text-to-image UNet.
+ *
+ * Conventions (all entry points)
+ *   - Return value: MQ_OK (0) or a negative MQ_ERR_* code.  Nothing is printed, nothing aborts.
+ *   - Every pointer is a DEVICE pointer unless its name ends in _host.  The caller owns every buffer;
+ *     the library allocates no device memory.  Scratch memory is a caller-provided workspace whose
+ *     size comes from the matching *_workspace_bytes() query.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls enqueue work on
+ *     that stream and return without synchronising.  Arguments are validated on the host before any
+ *     launch; a call that returns an error has launched nothing.
+ *   - Weights are W[N,K] (output channel x input channel, K contiguous), activations X[M,K] with row
+ *     stride ldx (elements), outputs Y[M,N] with row stride ldy (elements).
+ *   - Quantisation parameters follow the paper's problem statement (Sec. 4.1 "Quantization Scheme"):
+ *     one bit-width per layer, scale (float32) and zero point (int32) per output channel for weights,
+ *     one scale and zero point per tensor for activations (device pointers to one element each).
+ *   - 16-bit floats are IEEE binary16 (MQ_F16) or bfloat16 (MQ_BF16), passed as raw 2-byte elements.
+ */
+#ifndef MIXDQ_H
+#define MIXDQ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define MQ_OK 0
+#define MQ_ERR_BAD_ARG (-1)             /* null required pointer, contradictory options, misaligned pointer */
+#define MQ_ERR_BAD_SHAPE (-2)           /* non-positive size, stride smaller than the row, K not a multiple of the pack group */
+#define MQ_ERR_UNSUPPORTED_BITS (-3)    /* bits outside {2,3,4,8} (or outside {4,8} where stated) */
+#define MQ_ERR_WORKSPACE_TOO_SMALL (-4)
+#define MQ_ERR_HIP (-5)                 /* a HIP runtime call failed; see mq_last_hip_error() */
+#define MQ_ERR_UNSUPPORTED_LAYOUT (-6)  /* the GEMM entry points take MQ_LAYOUT_KERNEL only */
+#define MQ_ERR_OVERFLOW_RISK (-7)       /* K so large that an int32 accumulator could overflow (255*255*K >= 2^31) */
+
+#define MQ_LAYOUT_CANONICAL 0 /* interchange format: each row a little-endian bit stream, code k at bits [k*b, k*b+b) */
+#define MQ_LAYOUT_KERNEL 1    /* opaque tile-major format consumed by the GEMMs; needs K % 64 == 0 */
+
+#define MQ_F16 0
+#define MQ_BF16 1
+
+/* Library version and the last HIP error code seen by a failing call (0 if none). */
+int mq_version(void);
+int mq_last_hip_error(void);
+
+/* Tuning and test hook: force the GEMM workgroup tile (0: 256x256, 1: 128x128, 2: 64x64; -1: automatic choice
+ * from the problem shape).  Process-wide, not thread safe; results do not depend on the tile. */
+void mq_tune_force_tile(int tile);
+
+/* ------------------------------------------------------------------------------------------------
+ * Offline preparation
+ * ---------------------------------------------------------------------------------------------- */
+
+/* Uniform min-max quantisation of a weight matrix, one (scale, zero point) per output channel
+ * (paper Sec. 4.1 "Quantization Scheme"; bit-widths per layer, Sec. 3.3).
+ *   w        [N,K] 16-bit floats (dtype MQ_F16 or MQ_BF16), K contiguous.
+ *   bits     2, 3, 4 or 8.
+ *   symmetric == 0: asymmetric; the range is widened to contain 0; scale = (hi-lo)/(2^bits-1),
+ *                   zp = clamp(rne(-lo/scale)), code = clamp(rne(x/scale) + zp, 0, 2^bits-1); all fp32,
+ *                   x/scale taken as one multiply by the fp32 reciprocal; an all-zero row gets scale 1.
+ *   symmetric != 0: scale = absmax/(2^(bits-1)-1), code = clamp(rne(x/scale), -Q, Q) stored as two's
+ *                   complement int8, zp = 0.
+ *   codes    [N,K] uint8 out (one code per byte), scale [N] float out, zp [N] int32 out.
+ * Errors: MQ_ERR_BAD_ARG (null pointer, bad dtype), MQ_ERR_BAD_SHAPE, MQ_ERR_UNSUPPORTED_BITS, MQ_ERR_HIP. */
+int mq_quantize_weights(const void* w, int N, int K, int bits, int symmetric, int dtype, uint8_t* codes,
+                        float* scale, int32_t* zp, void* stream);
+
+/* Size in bytes of the packed form of an N x K code matrix.  Canonical: N*K*bits/8 (needs K*bits % 8 == 0).
+ * Kernel layout: ceil(N/32)*32 rows are stored (padding rows hold code 0), K % 64 == 0 is required.
+ * Returns 0 for an unsupported combination. */
+size_t mq_packed_bytes(int N, int K, int bits, int layout);
+
+/* Bit-pack one-code-per-byte weights (storage accounting of the paper's Tab. 1 "Storage Opt.").
+ *   codes   [N,K] uint8; only the low `bits` bits of each code are used.
+ *   packed  mq_packed_bytes(...) bytes out.
+ *   colsum  nullable [N] int32 out: sum over k of the code, read as two's complement int8 when
+ *           codes_signed != 0 (8-bit symmetric weights), else as unsigned.  The integer GEMMs need it.
+ * Errors: as above plus MQ_ERR_BAD_SHAPE when K is not a multiple of the layout's group. */
+int mq_pack_weights(const uint8_t* codes, int N, int K, int bits, int layout, int codes_signed, void* packed,
+                    int32_t* colsum, void* stream);
+
+/* Inverse of mq_pack_weights for either layout (a test aid; also converts between layouts). */
+int mq_unpack_weights(const void* packed, int N, int K, int bits, int layout, uint8_t* codes, void* stream);
+
+/* ------------------------------------------------------------------------------------------------
+ * Hot path
+ * ---------------------------------------------------------------------------------------------- */
+
+/* Weight-only linear, W{2,3,4,8}A16 (paper App. C item 2: low-bit weights, 16-bit floating-point compute):
+ *     Y[m,n] = round16( sum_k X[m,k] * scale[n] * (code[n,k] - zp[n]) + bias[n] ),  fp32 accumulation.
+ *   x      [M,K] row stride ldx, 16-byte aligned, ldx % 8 == 0.     y [M,N] row stride ldy, ldy % 4 == 0.
+ *   packed MQ_LAYOUT_KERNEL, unsigned codes.   bias nullable [N] (same 16-bit dtype as x and y).
+ *   K % 64 == 0, N % 4 == 0.  No workspace is needed. */
+int mq_qlinear_w_only(const void* x, int M, int K, int ldx, const void* packed, int N, int bits, int layout,
+                      const float* w_scale, const int32_t* w_zp, const void* bias, void* y, int ldy, int dtype,
+                      void* stream);
+
+/* Workspace for the 8-bit-activation entry points below (M rows of K activations). */
+size_t mq_qlinear_a8_workspace_bytes(int M, int K);
+
+/* W8A8 linear (paper Sec. 4.3 / App. C item 4: integer GEMM behind an FP16->INT8 conversion):
+ *     qx  = clamp(rne(x/s_x) + z_x, 0, 255)               per-tensor, unsigned 8 bit
+ *     ACC = sum_k (qx[m,k] - z_x) * (qw[n,k] - z_w[n])    int32
+ *     Y   = fp16( ACC * s_x * s_w[n] + bias[n] )
+ *   x        [M,K] fp16, row stride ldx (ldx % 8 == 0, 16-byte aligned).
+ *   packed   8-bit weights, MQ_LAYOUT_KERNEL; w_signed != 0: two's complement codes (symmetric scheme),
+ *            else unsigned codes with zero points w_zp.
+ *   w_colsum [N] from mq_pack_weights.
+ *   act_scale/act_zp  both NULL: dynamic — min/max of X is reduced on the device; otherwise static
+ *            (calibrated, Sec. 4.1) parameters are read from these device scalars.
+ *   acc_debug         nullable [M,N] int32 out: ACC, for bit-exact checks.
+ *   act_scale_out/act_zp_out  nullable device scalars out: the parameters that were used.
+ *   K % 64 == 0 and K <= 33024; N % 4 == 0.
+ * Errors: MQ_ERR_BAD_ARG when exactly one of act_scale/act_zp is NULL; MQ_ERR_OVERFLOW_RISK;
+ *         MQ_ERR_WORKSPACE_TOO_SMALL; and the common ones. */
+int mq_qlinear_w8a8(const void* x, int M, int K, int ldx, const void* packed, int N, int layout, int w_signed,
+                    const float* w_scale, const int32_t* w_zp, const int32_t* w_colsum, const float* act_scale,
+                    const int32_t* act_zp, const void* bias, void* y, int ldy, int32_t* acc_debug,
+                    float* act_scale_out, int32_t* act_zp_out, void* ws, size_t ws_bytes, void* stream);
+
+/* W4A8 linear: as above with asymmetric unsigned 4-bit weight codes (the INT4 operator the paper leaves as
+ * future work, App. C item 4); the codes are widened to int8 in registers ahead of the int8 MFMA. */
+int mq_qlinear_w4a8(const void* x, int M, int K, int ldx, const void* packed, int N, int layout,
+                    const float* w_scale, const int32_t* w_zp, const int32_t* w_colsum, const float* act_scale,
+                    const int32_t* act_zp, const void* bias, void* y, int ldy, int32_t* acc_debug,
+                    float* act_scale_out, int32_t* act_zp_out, void* ws, size_t ws_bytes, void* stream);
+
+size_t mq_bos_aware_kv_proj_workspace_bytes(int B, int T, int K);
+
+/* BOS-aware cross-attention K/V projection (paper Sec. 3.1).  ctx is the text embedding [B,T,K] fp16,
+ * contiguous; token 0 of every prompt is the outlier BOS row.
+ *   - tokens 1..T-1: 8-bit-activation linear as above (w_bits 8 or 4); dynamic activation parameters are the
+ *     min/max over those tokens only.
+ *   - token 0: exactly one of
+ *         w_f16   [N,K] unquantised fp16 weights -> Y[b,0,:] = fp16(ctx[b,0,:] . w_f16^T + bias), fp32 accumulate
+ *         bos_out [N]   pre-computed fp16 output, copied to Y[b,0,:] for every prompt.
+ *   - naive_all_rows != 0: comparator that quantises all B*T rows, BOS included (w_f16/bos_out ignored).
+ *   y [B,T,N] fp16 contiguous. */
+int mq_bos_aware_kv_proj(const void* ctx, int B, int T, int K, const void* packed, int N, int w_bits, int layout,
+                         int w_signed, const float* w_scale, const int32_t* w_zp, const int32_t* w_colsum,
+                         const void* w_f16, const void* bos_out, const float* act_scale, const int32_t* act_zp,
+                         const void* bias, void* y, int naive_all_rows, float* act_scale_out, int32_t* act_zp_out,
+                         void* ws, size_t ws_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MIXDQ_H */

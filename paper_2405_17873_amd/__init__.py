@@ -1,0 +1,9 @@
+"""MI355X-native quantized linear layers (the deployment hot path of MixDQ, arxiv 2405.17873).
+
+Thin Python binding over the C ABI declared in include/mixdq.h.  Every step of the path runs in the
+HIP kernels of libmixdq.so; this package only marshals arguments.  There is no CPU fallback.
+"""
+from .binding import (  # noqa: F401
+    BF16, F16, LAYOUT_CANONICAL, LAYOUT_KERNEL, MixdqError, PackedWeight, bos_aware_kv_proj,
+    bos_aware_kv_proj_workspace_bytes, lib_path, load, pack_weights, packed_bytes, qlinear_a8_workspace_bytes,
+    qlinear_w4a8, qlinear_w8a8, qlinear_w_only, quantize_weights, tune_force_tile, unpack_weights, version)

@@ -1,0 +1,212 @@
+"""ctypes marshalling for libmixdq.so.  Tensors are torch tensors on the GPU; torch supplies device memory
+and the current stream, nothing else.  Function names and argument meaning follow include/mixdq.h."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+from typing import Optional
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libmixdq.so")
+
+F16, BF16 = 0, 1
+LAYOUT_CANONICAL, LAYOUT_KERNEL = 0, 1
+
+_ERRORS = {
+    -1: "MQ_ERR_BAD_ARG", -2: "MQ_ERR_BAD_SHAPE", -3: "MQ_ERR_UNSUPPORTED_BITS", -4: "MQ_ERR_WORKSPACE_TOO_SMALL",
+    -5: "MQ_ERR_HIP", -6: "MQ_ERR_UNSUPPORTED_LAYOUT", -7: "MQ_ERR_OVERFLOW_RISK",
+}
+
+EXPORTS = ("mq_version", "mq_last_hip_error", "mq_tune_force_tile", "mq_quantize_weights", "mq_packed_bytes", "mq_pack_weights",
+           "mq_unpack_weights", "mq_qlinear_w_only", "mq_qlinear_a8_workspace_bytes", "mq_qlinear_w8a8",
+           "mq_qlinear_w4a8", "mq_bos_aware_kv_proj_workspace_bytes", "mq_bos_aware_kv_proj")
+
+
+class MixdqError(RuntimeError):
+    def __init__(self, code: int, what: str):
+        self.code = code
+        super().__init__(f"{what}: {_ERRORS.get(code, code)}")
+
+
+_lib = None
+
+
+def lib_path() -> str:
+    return _LIB_PATH
+
+
+def load():
+    """Loads the HIP library; raises if it has not been built (there is no fallback path)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise RuntimeError(f"{_LIB_PATH} is missing: run `python -c 'import __graft_entry__ as g; g.build()'`")
+        _lib = C.CDLL(_LIB_PATH)
+        for name in ("mq_packed_bytes", "mq_qlinear_a8_workspace_bytes", "mq_bos_aware_kv_proj_workspace_bytes"):
+            getattr(_lib, name).restype = C.c_size_t
+    return _lib
+
+
+def version() -> int:
+    return load().mq_version()
+
+
+def tune_force_tile(tile: int) -> None:
+    load().mq_tune_force_tile(int(tile))
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return C.c_void_p(0 if t is None else t.data_ptr())
+
+
+def _stream():
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _check(rc: int, what: str):
+    if rc != 0:
+        raise MixdqError(rc, what)
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float16:
+        return F16
+    if t.dtype == torch.bfloat16:
+        return BF16
+    raise TypeError(f"expected a 16-bit float tensor, got {t.dtype}")
+
+
+@dataclass
+class PackedWeight:
+    """A quantised, packed weight matrix resident on the GPU (what the offline step hands to the hot path)."""
+    packed: torch.Tensor      # uint8 bytes
+    scale: torch.Tensor       # float32 [N]
+    zp: torch.Tensor          # int32 [N]
+    colsum: Optional[torch.Tensor]  # int32 [N]
+    N: int
+    K: int
+    bits: int
+    layout: int
+    signed: bool
+
+
+def quantize_weights(w: torch.Tensor, bits: int, symmetric: bool = False):
+    """W [N,K] fp16/bf16 -> (codes uint8 [N,K], scale float32 [N], zp int32 [N])."""
+    assert w.is_cuda and w.dim() == 2 and w.is_contiguous()
+    N, K = w.shape
+    codes = torch.empty((N, K), dtype=torch.uint8, device=w.device)
+    scale = torch.empty(N, dtype=torch.float32, device=w.device)
+    zp = torch.empty(N, dtype=torch.int32, device=w.device)
+    _check(load().mq_quantize_weights(_ptr(w), N, K, bits, int(symmetric), _dtype_code(w), _ptr(codes), _ptr(scale),
+                                      _ptr(zp), _stream()), "mq_quantize_weights")
+    return codes, scale, zp
+
+
+def packed_bytes(N: int, K: int, bits: int, layout: int) -> int:
+    return int(load().mq_packed_bytes(N, K, bits, layout))
+
+
+def pack_weights(codes: torch.Tensor, bits: int, layout: int = LAYOUT_KERNEL, codes_signed: bool = False,
+                 want_colsum: bool = True):
+    """codes uint8 [N,K] -> (packed uint8 [bytes], colsum int32 [N] or None)."""
+    assert codes.is_cuda and codes.dtype == torch.uint8 and codes.is_contiguous()
+    N, K = codes.shape
+    nbytes = packed_bytes(N, K, bits, layout)
+    packed = torch.empty(max(nbytes, 1), dtype=torch.uint8, device=codes.device)
+    colsum = torch.empty(N, dtype=torch.int32, device=codes.device) if want_colsum else None
+    _check(load().mq_pack_weights(_ptr(codes), N, K, bits, layout, int(codes_signed), _ptr(packed), _ptr(colsum),
+                                  _stream()), "mq_pack_weights")
+    return packed, colsum
+
+
+def unpack_weights(packed: torch.Tensor, N: int, K: int, bits: int, layout: int) -> torch.Tensor:
+    codes = torch.empty((N, K), dtype=torch.uint8, device=packed.device)
+    _check(load().mq_unpack_weights(_ptr(packed), N, K, bits, layout, _ptr(codes), _stream()), "mq_unpack_weights")
+    return codes
+
+
+def qlinear_w_only(x: torch.Tensor, w: PackedWeight, bias: Optional[torch.Tensor] = None,
+                   out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Y = X . dequant(W)^T + bias with 16-bit floating-point compute (weight-only quantisation)."""
+    assert x.is_cuda and x.dim() == 2 and x.stride(1) == 1
+    M, K = x.shape
+    assert K == w.K
+    y = out if out is not None else torch.empty((M, w.N), dtype=x.dtype, device=x.device)
+    _check(load().mq_qlinear_w_only(_ptr(x), M, K, x.stride(0), _ptr(w.packed), w.N, w.bits, w.layout, _ptr(w.scale),
+                                    _ptr(w.zp), _ptr(bias), _ptr(y), y.stride(0), _dtype_code(x), _stream()),
+           "mq_qlinear_w_only")
+    return y
+
+
+def qlinear_a8_workspace_bytes(M: int, K: int) -> int:
+    return int(load().mq_qlinear_a8_workspace_bytes(M, K))
+
+
+def _workspace(nbytes: int, device, ws: Optional[torch.Tensor]):
+    if ws is None:
+        ws = torch.empty(nbytes, dtype=torch.uint8, device=device)
+    return ws
+
+
+def _qlinear_a8(fn_name, x, w: PackedWeight, act, bias, out, ws, want_acc, want_act):
+    assert x.is_cuda and x.dim() == 2 and x.stride(1) == 1 and x.dtype == torch.float16
+    M, K = x.shape
+    assert K == w.K
+    dev = x.device
+    y = out if out is not None else torch.empty((M, w.N), dtype=torch.float16, device=dev)
+    ws = _workspace(qlinear_a8_workspace_bytes(M, K), dev, ws)
+    acc = torch.empty((M, w.N), dtype=torch.int32, device=dev) if want_acc else None
+    s_out = torch.empty(1, dtype=torch.float32, device=dev) if want_act else None
+    z_out = torch.empty(1, dtype=torch.int32, device=dev) if want_act else None
+    a_s, a_z = (None, None) if act is None else act
+    L = load()
+    if fn_name == "mq_qlinear_w8a8":
+        rc = L.mq_qlinear_w8a8(_ptr(x), M, K, x.stride(0), _ptr(w.packed), w.N, w.layout, int(w.signed), _ptr(w.scale),
+                               _ptr(w.zp), _ptr(w.colsum), _ptr(a_s), _ptr(a_z), _ptr(bias), _ptr(y), y.stride(0),
+                               _ptr(acc), _ptr(s_out), _ptr(z_out), _ptr(ws), C.c_size_t(ws.numel()), _stream())
+    else:
+        rc = L.mq_qlinear_w4a8(_ptr(x), M, K, x.stride(0), _ptr(w.packed), w.N, w.layout, _ptr(w.scale), _ptr(w.zp),
+                               _ptr(w.colsum), _ptr(a_s), _ptr(a_z), _ptr(bias), _ptr(y), y.stride(0), _ptr(acc),
+                               _ptr(s_out), _ptr(z_out), _ptr(ws), C.c_size_t(ws.numel()), _stream())
+    _check(rc, fn_name)
+    return y, acc, (s_out, z_out)
+
+
+def qlinear_w8a8(x, w: PackedWeight, act=None, bias=None, out=None, ws=None, want_acc=False, want_act=False):
+    """act=None: dynamic per-tensor min-max on the device; else (scale tensor[1] f32, zp tensor[1] i32).
+    Returns (y, acc or None, (act_scale, act_zp) device scalars or (None, None))."""
+    assert w.bits == 8
+    return _qlinear_a8("mq_qlinear_w8a8", x, w, act, bias, out, ws, want_acc, want_act)
+
+
+def qlinear_w4a8(x, w: PackedWeight, act=None, bias=None, out=None, ws=None, want_acc=False, want_act=False):
+    assert w.bits == 4 and not w.signed
+    return _qlinear_a8("mq_qlinear_w4a8", x, w, act, bias, out, ws, want_acc, want_act)
+
+
+def bos_aware_kv_proj_workspace_bytes(B: int, T: int, K: int) -> int:
+    return int(load().mq_bos_aware_kv_proj_workspace_bytes(B, T, K))
+
+
+def bos_aware_kv_proj(ctx: torch.Tensor, w: PackedWeight, w_f16: Optional[torch.Tensor] = None,
+                      bos_out: Optional[torch.Tensor] = None, act=None, bias=None, naive_all_rows: bool = False,
+                      out=None, ws=None, want_act=False):
+    """ctx [B,T,K] fp16 -> y [B,T,N] fp16; token 0 of each prompt bypasses activation quantisation."""
+    assert ctx.is_cuda and ctx.dim() == 3 and ctx.is_contiguous() and ctx.dtype == torch.float16
+    B, T, K = ctx.shape
+    assert K == w.K
+    dev = ctx.device
+    y = out if out is not None else torch.empty((B, T, w.N), dtype=torch.float16, device=dev)
+    ws = _workspace(bos_aware_kv_proj_workspace_bytes(B, T, K), dev, ws)
+    s_out = torch.empty(1, dtype=torch.float32, device=dev) if want_act else None
+    z_out = torch.empty(1, dtype=torch.int32, device=dev) if want_act else None
+    a_s, a_z = (None, None) if act is None else act
+    rc = load().mq_bos_aware_kv_proj(_ptr(ctx), B, T, K, _ptr(w.packed), w.N, w.bits, w.layout, int(w.signed),
+                                     _ptr(w.scale), _ptr(w.zp), _ptr(w.colsum), _ptr(w_f16), _ptr(bos_out), _ptr(a_s),
+                                     _ptr(a_z), _ptr(bias), _ptr(y), int(naive_all_rows), _ptr(s_out), _ptr(z_out),
+                                     _ptr(ws), C.c_size_t(ws.numel()), _stream())
+    _check(rc, "mq_bos_aware_kv_proj")
+    return y, (s_out, z_out)

@@ -1,0 +1,190 @@
+// C ABI of the library: argument validation on the host, workspace carving, launch sequencing.
+// No entry point allocates device memory or synchronises.
+#include <atomic>
+
+#include "mq_common.h"
+
+namespace mq {
+static std::atomic<int> g_last_hip_error{0};
+void set_hip_error(int e) { g_last_hip_error.store(e); }
+
+static inline bool aligned(const void* p, size_t a) { return ((uintptr_t)p % a) == 0; }
+static inline size_t up256(size_t v) { return (v + 255) / 256 * 256; }
+static inline bool bits_ok(int b) { return b == 2 || b == 3 || b == 4 || b == 8; }
+
+// Workspace of the 8-bit-activation path.
+struct A8Workspace {
+    ActParams* params;
+    float* partials;
+    int32_t* rowsum;
+    int8_t* a8;
+    static size_t bytes(long M, long K) {
+        return 256 + up256(sizeof(float) * 2 * (size_t)act_quant_partial_slots()) + up256(4 * (size_t)M) +
+               up256((size_t)M * K) + 256;
+    }
+    A8Workspace(void* ws, long M, long K) {
+        uint8_t* p = (uint8_t*)ws;
+        params = (ActParams*)p;
+        p += 256;
+        partials = (float*)p;
+        p += up256(sizeof(float) * 2 * (size_t)act_quant_partial_slots());
+        rowsum = (int32_t*)p;
+        p += up256(4 * (size_t)M);
+        a8 = (int8_t*)p;
+        (void)K;
+    }
+};
+
+static int check_linear_common(const void* x, int M, int K, int ldx, const void* packed, int N, int layout,
+                               const float* w_scale, const int32_t* w_zp, const void* bias, const void* y, int ldy) {
+    if (!x || !packed || !w_scale || !w_zp || !y) return MQ_ERR_BAD_ARG;
+    if (M <= 0 || K <= 0 || N <= 0 || ldx < K || ldy < N) return MQ_ERR_BAD_SHAPE;
+    if (layout != MQ_LAYOUT_KERNEL) return MQ_ERR_UNSUPPORTED_LAYOUT;
+    if (K % 64 != 0 || N % 4 != 0 || ldx % 8 != 0 || ldy % 4 != 0) return MQ_ERR_BAD_SHAPE;
+    if (!aligned(x, 16) || !aligned(packed, 16) || !aligned(w_scale, 16) || !aligned(w_zp, 16) || !aligned(y, 8) ||
+        (bias && !aligned(bias, 8)))
+        return MQ_ERR_BAD_ARG;
+    return MQ_OK;
+}
+
+static int qlinear_a8(const void* x, int M, int K, int ldx, RowMap in_map, const void* packed, int N, int layout,
+                      int w_bits, int w_signed, const float* w_scale, const int32_t* w_zp, const int32_t* w_colsum,
+                      const float* act_scale, const int32_t* act_zp, const void* bias, void* y, int ldy, RowMap out_map,
+                      int32_t* acc_debug, float* act_scale_out, int32_t* act_zp_out, void* ws, size_t ws_bytes,
+                      hipStream_t st) {
+    int rc = check_linear_common(x, M, K, ldx, packed, N, layout, w_scale, w_zp, bias, y, ldy);
+    if (rc) return rc;
+    if (!w_colsum || !ws) return MQ_ERR_BAD_ARG;
+    if ((act_scale == nullptr) != (act_zp == nullptr)) return MQ_ERR_BAD_ARG;
+    if (!aligned(w_colsum, 16) || !aligned(ws, 256) || (acc_debug && !aligned(acc_debug, 16))) return MQ_ERR_BAD_ARG;
+    if ((long)255 * 255 * K >= (1L << 31)) return MQ_ERR_OVERFLOW_RISK;
+    if (ws_bytes < A8Workspace::bytes(M, K)) return MQ_ERR_WORKSPACE_TOO_SMALL;
+    A8Workspace w(ws, M, K);
+    rc = launch_act_quant(x, M, K, ldx, in_map, act_scale, act_zp, w.a8, w.rowsum, w.params, w.partials,
+                          act_scale_out, act_zp_out, st);
+    if (rc) return rc;
+    return launch_gemm_a8(w.a8, w.rowsum, w.params, M, K, packed, N, w_bits, w_signed, w_scale, w_zp, w_colsum, bias,
+                          y, ldy, out_map, acc_debug, st);
+}
+}  // namespace mq
+
+using namespace mq;
+
+extern "C" {
+
+int mq_version(void) { return 1; }
+int mq_last_hip_error(void) { return g_last_hip_error.load(); }
+void mq_tune_force_tile(int tile) { set_force_tile(tile); }
+
+int mq_quantize_weights(const void* w, int N, int K, int bits, int symmetric, int dtype, uint8_t* codes, float* scale,
+                        int32_t* zp, void* stream) {
+    if (!w || !codes || !scale || !zp) return MQ_ERR_BAD_ARG;
+    if (dtype != MQ_F16 && dtype != MQ_BF16) return MQ_ERR_BAD_ARG;
+    if (N <= 0 || K <= 0) return MQ_ERR_BAD_SHAPE;
+    if (!bits_ok(bits)) return MQ_ERR_UNSUPPORTED_BITS;
+    return launch_quantize_weights(w, N, K, bits, symmetric ? 1 : 0, dtype, codes, scale, zp, (hipStream_t)stream);
+}
+
+size_t mq_packed_bytes(int N, int K, int bits, int layout) {
+    if (N <= 0 || K <= 0 || !bits_ok(bits)) return 0;
+    if (layout == MQ_LAYOUT_CANONICAL) {
+        if (((long)K * bits) % 8 != 0) return 0;
+        return (size_t)N * ((size_t)K * bits / 8);
+    }
+    if (layout == MQ_LAYOUT_KERNEL) {
+        if (K % 64 != 0) return 0;
+        return (size_t)((N + 31) / 32) * (K / 64) * kl_tile_bytes(bits);
+    }
+    return 0;
+}
+
+int mq_pack_weights(const uint8_t* codes, int N, int K, int bits, int layout, int codes_signed, void* packed,
+                    int32_t* colsum, void* stream) {
+    if (!codes || !packed) return MQ_ERR_BAD_ARG;
+    if (N <= 0 || K <= 0) return MQ_ERR_BAD_SHAPE;
+    if (!bits_ok(bits)) return MQ_ERR_UNSUPPORTED_BITS;
+    if (layout != MQ_LAYOUT_CANONICAL && layout != MQ_LAYOUT_KERNEL) return MQ_ERR_UNSUPPORTED_LAYOUT;
+    if (codes_signed && bits != 8) return MQ_ERR_BAD_ARG;
+    if (mq_packed_bytes(N, K, bits, layout) == 0) return MQ_ERR_BAD_SHAPE;
+    if (layout == MQ_LAYOUT_KERNEL && !aligned(packed, 16)) return MQ_ERR_BAD_ARG;
+    return launch_pack(codes, N, K, bits, layout, codes_signed ? 1 : 0, packed, colsum, (hipStream_t)stream);
+}
+
+int mq_unpack_weights(const void* packed, int N, int K, int bits, int layout, uint8_t* codes, void* stream) {
+    if (!codes || !packed) return MQ_ERR_BAD_ARG;
+    if (N <= 0 || K <= 0) return MQ_ERR_BAD_SHAPE;
+    if (!bits_ok(bits)) return MQ_ERR_UNSUPPORTED_BITS;
+    if (layout != MQ_LAYOUT_CANONICAL && layout != MQ_LAYOUT_KERNEL) return MQ_ERR_UNSUPPORTED_LAYOUT;
+    if (mq_packed_bytes(N, K, bits, layout) == 0) return MQ_ERR_BAD_SHAPE;
+    if (layout == MQ_LAYOUT_KERNEL && !aligned(packed, 16)) return MQ_ERR_BAD_ARG;
+    return launch_unpack(packed, N, K, bits, layout, codes, (hipStream_t)stream);
+}
+
+int mq_qlinear_w_only(const void* x, int M, int K, int ldx, const void* packed, int N, int bits, int layout,
+                      const float* w_scale, const int32_t* w_zp, const void* bias, void* y, int ldy, int dtype,
+                      void* stream) {
+    if (!bits_ok(bits)) return MQ_ERR_UNSUPPORTED_BITS;
+    if (dtype != MQ_F16 && dtype != MQ_BF16) return MQ_ERR_BAD_ARG;
+    int rc = check_linear_common(x, M, K, ldx, packed, N, layout, w_scale, w_zp, bias, y, ldy);
+    if (rc) return rc;
+    return launch_gemm_w_only(x, M, K, ldx, packed, N, bits, w_scale, w_zp, bias, y, ldy, dtype, (hipStream_t)stream);
+}
+
+size_t mq_qlinear_a8_workspace_bytes(int M, int K) {
+    if (M <= 0 || K <= 0) return 0;
+    return A8Workspace::bytes(M, K);
+}
+
+int mq_qlinear_w8a8(const void* x, int M, int K, int ldx, const void* packed, int N, int layout, int w_signed,
+                    const float* w_scale, const int32_t* w_zp, const int32_t* w_colsum, const float* act_scale,
+                    const int32_t* act_zp, const void* bias, void* y, int ldy, int32_t* acc_debug, float* act_scale_out,
+                    int32_t* act_zp_out, void* ws, size_t ws_bytes, void* stream) {
+    return qlinear_a8(x, M, K, ldx, RowMap{0, 0, 0}, packed, N, layout, 8, w_signed ? 1 : 0, w_scale, w_zp, w_colsum,
+                      act_scale, act_zp, bias, y, ldy, RowMap{0, 0, 0}, acc_debug, act_scale_out, act_zp_out, ws,
+                      ws_bytes, (hipStream_t)stream);
+}
+
+int mq_qlinear_w4a8(const void* x, int M, int K, int ldx, const void* packed, int N, int layout, const float* w_scale,
+                    const int32_t* w_zp, const int32_t* w_colsum, const float* act_scale, const int32_t* act_zp,
+                    const void* bias, void* y, int ldy, int32_t* acc_debug, float* act_scale_out, int32_t* act_zp_out,
+                    void* ws, size_t ws_bytes, void* stream) {
+    return qlinear_a8(x, M, K, ldx, RowMap{0, 0, 0}, packed, N, layout, 4, 0, w_scale, w_zp, w_colsum, act_scale,
+                      act_zp, bias, y, ldy, RowMap{0, 0, 0}, acc_debug, act_scale_out, act_zp_out, ws, ws_bytes,
+                      (hipStream_t)stream);
+}
+
+size_t mq_bos_aware_kv_proj_workspace_bytes(int B, int T, int K) {
+    if (B <= 0 || T <= 0 || K <= 0) return 0;
+    return A8Workspace::bytes((long)B * T, K);
+}
+
+int mq_bos_aware_kv_proj(const void* ctx, int B, int T, int K, const void* packed, int N, int w_bits, int layout,
+                         int w_signed, const float* w_scale, const int32_t* w_zp, const int32_t* w_colsum,
+                         const void* w_f16, const void* bos_out, const float* act_scale, const int32_t* act_zp,
+                         const void* bias, void* y, int naive_all_rows, float* act_scale_out, int32_t* act_zp_out,
+                         void* ws, size_t ws_bytes, void* stream) {
+    if (B <= 0 || T <= 0) return MQ_ERR_BAD_SHAPE;
+    if (w_bits != 4 && w_bits != 8) return MQ_ERR_UNSUPPORTED_BITS;
+    if (w_bits == 4 && w_signed) return MQ_ERR_BAD_ARG;
+    hipStream_t st = (hipStream_t)stream;
+    if (naive_all_rows)
+        return qlinear_a8(ctx, B * T, K, K, RowMap{0, 0, 0}, packed, N, layout, w_bits, w_signed ? 1 : 0, w_scale, w_zp,
+                          w_colsum, act_scale, act_zp, bias, y, N, RowMap{0, 0, 0}, nullptr, act_scale_out, act_zp_out,
+                          ws, ws_bytes, st);
+    if ((w_f16 == nullptr) == (bos_out == nullptr)) return MQ_ERR_BAD_ARG;
+    if (w_f16 && !aligned(w_f16, 16)) return MQ_ERR_BAD_ARG;
+    if (ws_bytes < mq_bos_aware_kv_proj_workspace_bytes(B, T, K)) return MQ_ERR_WORKSPACE_TOO_SMALL;
+    if (T > 1) {
+        const RowMap body{T - 1, T, 1};  // logical row r -> token 1 + r % (T-1) of prompt r / (T-1)
+        int rc = qlinear_a8(ctx, B * (T - 1), K, K, body, packed, N, layout, w_bits, w_signed ? 1 : 0, w_scale, w_zp,
+                            w_colsum, act_scale, act_zp, bias, y, N, body, nullptr, act_scale_out, act_zp_out, ws,
+                            ws_bytes, st);
+        if (rc) return rc;
+    } else {
+        int rc = check_linear_common(ctx, B, K, K, packed, N, layout, w_scale, w_zp, bias, y, N);
+        if (rc) return rc;
+    }
+    return launch_bos_rows(ctx, B, T, K, w_f16, bos_out, bias, y, N, st);
+}
+
+}  // extern "C"

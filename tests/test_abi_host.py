@@ -1,0 +1,109 @@
+"""Host-only checks of the C ABI: the library loads without a GPU, exports every declared symbol, and
+rejects bad arguments before launching anything."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    import paper_2405_17873_amd as mq
+    if not os.path.exists(mq.lib_path()):
+        from paper_2405_17873_amd import build
+        build.build()
+    return mq.load()
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "mixdq.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(mq_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    from paper_2405_17873_amd import binding
+    names = _declared_symbols()
+    assert len(names) >= 12
+    for n in names:
+        assert hasattr(lib, n), n
+    assert sorted(binding.EXPORTS) == names
+
+
+def test_size_queries(lib):
+    import paper_2405_17873_amd as mq
+    assert mq.packed_bytes(320, 320, 4, mq.LAYOUT_CANONICAL) == 320 * 160
+    assert mq.packed_bytes(320, 320, 3, mq.LAYOUT_CANONICAL) == 320 * 120
+    assert mq.packed_bytes(320, 320, 2, mq.LAYOUT_KERNEL) == 320 * 80
+    assert mq.packed_bytes(33, 64, 8, mq.LAYOUT_KERNEL) == 64 * 64  # padded to 64 channels
+    assert mq.packed_bytes(320, 100, 4, mq.LAYOUT_KERNEL) == 0      # K % 64
+    assert mq.packed_bytes(320, 5, 3, mq.LAYOUT_CANONICAL) == 0     # 15 bits is not whole bytes
+    assert mq.packed_bytes(320, 320, 5, mq.LAYOUT_CANONICAL) == 0
+    assert mq.qlinear_a8_workspace_bytes(4096, 1280) >= 4096 * 1280 + 4 * 4096
+    assert mq.bos_aware_kv_proj_workspace_bytes(8, 77, 2048) >= 8 * 77 * 2048
+
+
+def test_error_codes_without_a_gpu(lib):
+    """Validation happens on the host, so these calls never reach the device."""
+    buf = (C.c_uint8 * 4096)()
+    base = C.addressof(buf)
+    p = C.c_void_p((base + 255) // 256 * 256)  # aligned fake pointer; never dereferenced: every call below fails first
+    null = C.c_void_p(0)
+    st = C.c_void_p(0)
+    # quantize_weights
+    assert lib.mq_quantize_weights(null, 4, 64, 4, 0, 0, p, p, p, st) == -1
+    assert lib.mq_quantize_weights(p, 4, 64, 5, 0, 0, p, p, p, st) == -3
+    assert lib.mq_quantize_weights(p, 0, 64, 4, 0, 0, p, p, p, st) == -2
+    assert lib.mq_quantize_weights(p, 4, 64, 4, 0, 7, p, p, p, st) == -1
+    # pack
+    assert lib.mq_pack_weights(p, 4, 5, 3, 0, 0, p, null, st) == -2
+    assert lib.mq_pack_weights(p, 4, 96, 4, 1, 0, p, null, st) == -2
+    assert lib.mq_pack_weights(p, 4, 64, 4, 9, 0, p, null, st) == -6
+    assert lib.mq_pack_weights(p, 4, 64, 4, 1, 1, p, null, st) == -1  # signed codes only at 8 bit
+    assert lib.mq_unpack_weights(p, 4, 64, 6, 1, p, st) == -3
+    # w_only
+    args = lambda **o: [o.get("x", p), o.get("M", 8), o.get("K", 64), o.get("ldx", 64), p, o.get("N", 32),
+                        o.get("bits", 4), o.get("layout", 1), p, p, null, p, o.get("ldy", 32), 0, st]
+    assert lib.mq_qlinear_w_only(*args(x=null)) == -1
+    assert lib.mq_qlinear_w_only(*args(bits=5)) == -3
+    assert lib.mq_qlinear_w_only(*args(K=96, ldx=96)) == -2
+    assert lib.mq_qlinear_w_only(*args(M=0)) == -2
+    assert lib.mq_qlinear_w_only(*args(ldx=32)) == -2
+    assert lib.mq_qlinear_w_only(*args(layout=0)) == -6
+    assert lib.mq_qlinear_w_only(*args(x=C.c_void_p(p.value + 2))) == -1  # misaligned
+    # a8
+    a8 = lambda **o: [p, 8, o.get("K", 64), o.get("K", 64), p, 32, 1, 1, p, p, o.get("colsum", p),
+                      o.get("a_s", null), o.get("a_z", null), null, p, 32, null, null, null, o.get("ws", p),
+                      C.c_size_t(o.get("wsb", 1 << 20)), st]
+    assert lib.mq_qlinear_w8a8(*a8(colsum=null)) == -1
+    assert lib.mq_qlinear_w8a8(*a8(a_s=p)) == -1       # scale without zero point
+    assert lib.mq_qlinear_w8a8(*a8(wsb=16)) == -4
+    assert lib.mq_qlinear_w8a8(*a8(K=33088)) == -7     # 255*255*K >= 2^31
+    assert lib.mq_qlinear_w8a8(*a8(ws=null)) == -1
+    # bos
+    bos = lambda **o: [p, o.get("B", 2), 5, 64, p, 32, o.get("wb", 8), 1, 1, p, p, p, o.get("wf", null),
+                       o.get("bo", null), null, null, null, p, 0, null, null, p, C.c_size_t(1 << 20), st]
+    assert lib.mq_bos_aware_kv_proj(*bos()) == -1            # neither BOS source
+    assert lib.mq_bos_aware_kv_proj(*bos(wf=p, bo=p)) == -1  # both
+    assert lib.mq_bos_aware_kv_proj(*bos(wb=2, wf=p)) == -3
+    assert lib.mq_bos_aware_kv_proj(*bos(B=0, wf=p)) == -2
+
+
+def test_missing_library_is_loud(monkeypatch):
+    from paper_2405_17873_amd import binding
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(binding, "_LIB_PATH", "/nonexistent/libmixdq.so")
+    with pytest.raises(RuntimeError):
+        binding.load()
+
+
+def test_product_package_does_not_import_the_oracle():
+    pkg = os.path.join(ROOT, "paper_2405_17873_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h", ".cpp")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "oracle" not in text.lower().replace("no cpu fallback", ""), f

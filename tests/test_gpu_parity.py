@@ -1,0 +1,315 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same seeded inputs.
+
+Bar: integer results (codes, packed bytes, zero points, int32 accumulators) bit-exact, fp32 scales bit-exact;
+16-bit outputs within relative Frobenius error 1e-3 and |err| <= 1e-2 * max|ref| per element."""
+import numpy as np
+import pytest
+import torch
+
+import synth_inputs as si
+
+pytestmark = pytest.mark.gpu
+
+FRO_TOL = 1e-3
+ELT_TOL = 1e-2
+ALL_BITS = (2, 3, 4, 8)
+
+
+@pytest.fixture(scope="module")
+def mq():
+    import paper_2405_17873_amd as m
+    m.load()
+    assert torch.cuda.is_available()
+    yield m
+    m.tune_force_tile(-1)
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def host(t):
+    torch.cuda.synchronize()
+    return t.cpu().numpy()
+
+
+def assert_close16(y, ref_bits, what=""):
+    y = np.asarray(y).astype(np.float64)
+    ref = np.asarray(ref_bits).view(np.float16).astype(np.float64)
+    assert y.shape == ref.shape, (y.shape, ref.shape)
+    assert np.isfinite(y).all(), what
+    fro = np.linalg.norm(y - ref) / max(np.linalg.norm(ref), 1e-30)
+    elt = np.abs(y - ref).max() / max(np.abs(ref).max(), 1e-30)
+    assert fro <= FRO_TOL and elt <= ELT_TOL, f"{what}: fro={fro:.3e} elt={elt:.3e}"
+
+
+def make_weight(mq, orc, w, bits, symmetric=False):
+    """Quantise + pack on the GPU, checking both against the oracle bit for bit; returns (PackedWeight, codes...)."""
+    wd = dev(w)
+    c, s, z = mq.quantize_weights(wd, bits, symmetric)
+    oc, os_, oz = orc.quantize_weights(w, bits, symmetric)
+    assert np.array_equal(host(c), oc), "codes"
+    assert np.array_equal(host(s).view(np.uint32), os_.view(np.uint32)), "scale bits"
+    assert np.array_equal(host(z), oz), "zero points"
+    packed, colsum = mq.pack_weights(c, bits, mq.LAYOUT_KERNEL, codes_signed=symmetric)
+    assert np.array_equal(host(colsum), orc.code_rowsum(oc, signed=symmetric))
+    N, K = w.shape
+    return mq.PackedWeight(packed, s, z, colsum, N, K, bits, mq.LAYOUT_KERNEL, symmetric), oc, os_, oz
+
+
+# ----------------------------------------------------------------------------------------------- quantiser / packers
+
+@pytest.mark.parametrize("bits", ALL_BITS)
+@pytest.mark.parametrize("symmetric", (False, True))
+def test_quantize_weights_bit_exact(mq, orc, bits, symmetric):
+    if symmetric and bits not in (4, 8):
+        pytest.skip("symmetric scheme is used at 4 and 8 bits")
+    for (N, K, std) in ((320, 320, 0.02), (37, 1000, 1.0), (5, 64, 0.02), (640, 2560, 0.02)):
+        w = si.weights_f16(7, f"q/{N}x{K}", N, K, std)
+        if N > 4:
+            w[1] = 0
+            w[2] = np.abs(w[2])
+            w[3] = -np.abs(w[3])
+        c, s, z = mq.quantize_weights(dev(w), bits, symmetric)
+        oc, os_, oz = orc.quantize_weights(w, bits, symmetric)
+        assert np.array_equal(host(c), oc)
+        assert np.array_equal(host(s).view(np.uint32), os_.view(np.uint32))
+        assert np.array_equal(host(z), oz)
+
+
+def test_quantize_weights_bf16(mq, orc):
+    w = torch.from_numpy(si.normal(8, "q/bf16", (64, 320), 0.02).astype(np.float32)).to(torch.bfloat16)
+    bits16 = w.view(torch.int16).numpy().view(np.uint16)
+    c, s, z = mq.quantize_weights(w.cuda(), 4)
+    oc, os_, oz = orc.quantize_weights(bits16, 4, dtype=orc.BF16)
+    assert np.array_equal(host(c), oc) and np.array_equal(host(s), os_) and np.array_equal(host(z), oz)
+
+
+@pytest.mark.parametrize("bits", ALL_BITS)
+def test_pack_canonical_bytes_bit_exact(mq, orc, bits):
+    rng = np.random.default_rng(bits)
+    for (N, K) in ((7, 32), (320, 320), (33, 5120), (1, 8)):
+        codes = rng.integers(0, 1 << bits, (N, K)).astype(np.uint8)
+        p, cs = mq.pack_weights(dev(codes), bits, mq.LAYOUT_CANONICAL)
+        assert np.array_equal(host(p).reshape(N, -1), orc.pack_weights(codes, bits))
+        assert np.array_equal(host(cs), codes.astype(np.int64).sum(1))
+        back = mq.unpack_weights(p, N, K, bits, mq.LAYOUT_CANONICAL)
+        assert np.array_equal(host(back), codes)
+
+
+@pytest.mark.parametrize("bits", ALL_BITS)
+def test_pack_kernel_layout_round_trip(mq, orc, bits):
+    rng = np.random.default_rng(10 + bits)
+    for (N, K) in ((32, 64), (320, 320), (33, 128), (4, 5120), (100, 2048)):
+        codes = rng.integers(0, 1 << bits, (N, K)).astype(np.uint8)
+        p, _ = mq.pack_weights(dev(codes), bits, mq.LAYOUT_KERNEL)
+        assert p.numel() == mq.packed_bytes(N, K, bits, mq.LAYOUT_KERNEL) == (N + 31) // 32 * 32 * K * bits // 8
+        assert np.array_equal(host(mq.unpack_weights(p, N, K, bits, mq.LAYOUT_KERNEL)), codes)
+        # same multiset of bits as the canonical form (a permutation, nothing lost): compare popcounts per tile row group
+        if N % 32 == 0:
+            can = orc.pack_weights(codes, bits)
+            assert int(np.unpackbits(host(p)).sum()) == int(np.unpackbits(can).sum())
+    signed = rng.integers(-127, 128, (64, 128)).astype(np.int8).view(np.uint8)
+    p, cs = mq.pack_weights(dev(signed), 8, mq.LAYOUT_KERNEL, codes_signed=True)
+    assert np.array_equal(host(cs), signed.view(np.int8).astype(np.int64).sum(1))
+
+
+# ----------------------------------------------------------------------------------------------- weight-only
+
+W_ONLY_SHAPES = [
+    # M, K, N
+    (256, 320, 320),   # stated small configuration (b)
+    (1, 64, 32),
+    (77, 128, 36),     # N not a multiple of the tile, M ragged
+    (608, 2048, 640),
+    (300, 640, 640),
+    (513, 192, 260),
+]
+
+
+@pytest.mark.parametrize("bits", ALL_BITS)
+@pytest.mark.parametrize("tile", (-1, 0, 1, 2))
+def test_w_only_small_shapes(mq, orc, bits, tile):
+    mq.tune_force_tile(tile)
+    for (M, K, N) in W_ONLY_SHAPES:
+        if tile == 0 and M * N > 400000:
+            continue
+        x = si.activations_f16(11, f"wo/x{M}x{K}", M, K, outlier_prob=0.01)
+        w = si.weights_f16(11, f"wo/w{N}x{K}", N, K)
+        b = si.bias_f16(11, f"wo/b{N}", N)
+        pw, oc, os_, oz = make_weight(mq, orc, w, bits)
+        for bias in (b, None):
+            y = mq.qlinear_w_only(dev(x), pw, None if bias is None else dev(bias))
+            ref = orc.linear_w_only(x, oc, os_, oz, bias)
+            assert_close16(host(y), ref, f"w_only b{bits} tile{tile} {M}x{K}x{N}")
+    mq.tune_force_tile(-1)
+
+
+def test_w_only_exact_integer_case(mq, orc):
+    """Integer activations, scale 1: every product and sum is exact in fp32, so the result is exact."""
+    rng = np.random.default_rng(5)
+    for bits in ALL_BITS:
+        M, K, N = 96, 256, 64
+        x = rng.integers(-4, 5, (M, K)).astype(np.float16)
+        codes = rng.integers(0, 1 << bits, (N, K)).astype(np.uint8)
+        zp = rng.integers(0, 1 << bits, N).astype(np.int32)
+        packed, cs = mq.pack_weights(dev(codes), bits, mq.LAYOUT_KERNEL)
+        pw = mq.PackedWeight(packed, dev(np.ones(N, np.float32)), dev(zp), cs, N, K, bits, mq.LAYOUT_KERNEL, False)
+        y = host(mq.qlinear_w_only(dev(x), pw))
+        ref = x.astype(np.int64) @ (codes.astype(np.int64) - zp[:, None]).T
+        assert np.array_equal(y.astype(np.float64), ref.astype(np.float16).astype(np.float64)), bits
+
+
+def test_w_only_strided_views(mq, orc):
+    M, K, N = 130, 128, 64
+    xbig = si.activations_f16(12, "wo/xs", M, K + 64)
+    w = si.weights_f16(12, "wo/ws", N, K)
+    pw, oc, os_, oz = make_weight(mq, orc, w, 4)
+    xd = dev(xbig)[:, :K]
+    out = torch.zeros((M, N + 12), dtype=torch.float16, device="cuda")
+    mq.qlinear_w_only(xd, pw, out=out[:, :N])
+    ref = orc.linear_w_only(np.ascontiguousarray(xbig[:, :K]), oc, os_, oz)
+    assert_close16(host(out)[:, :N], ref, "strided")
+    assert not host(out)[:, N:].any()
+
+
+@pytest.mark.parametrize("M,K,N", [(4096, 640, 640), (4096, 640, 5120), (4096, 2560, 640)])
+def test_w_only_transformer_block_shapes_sampled_rows(mq, orc, M, K, N):
+    """64x64-level block linears (batch 1) at full size, in the launch configuration the benchmark uses;
+    the oracle evaluates a seeded sample of rows including the first, the last and the rows of extreme values."""
+    x = si.activations_f16(0, f"c2/x{K}", M, K, outlier_prob=0.01)
+    w = si.weights_f16(0, f"c2/w{N}x{K}", N, K)
+    b = si.bias_f16(0, f"c2/b{N}", N)
+    rng = np.random.default_rng(M + K + N)
+    rows = np.unique(np.concatenate([[0, M - 1, int(np.argmax(x.max(1))), int(np.argmin(x.min(1)))],
+                                     rng.integers(0, M, 60)]))
+    for bits in (8, 4, 3):
+        pw, oc, os_, oz = make_weight(mq, orc, w, bits)
+        y = host(mq.qlinear_w_only(dev(x), pw, dev(b)))
+        ref = orc.linear_w_only(x, oc, os_, oz, b, rows=rows)
+        assert_close16(y[rows], ref, f"c2 b{bits} {M}x{K}x{N}")
+        # rows the oracle did not visit: finite and of plausible magnitude
+        assert np.isfinite(y).all() and np.abs(y.astype(np.float64)).max() < 4 * np.abs(
+            ref.view(np.float16).astype(np.float64)).max() + 1
+
+
+# ----------------------------------------------------------------------------------------------- 8-bit activations
+
+A8_SHAPES = [(256, 320, 320), (1, 64, 32), (77, 128, 36), (608, 2048, 640), (300, 1280, 260), (130, 192, 64)]
+
+
+@pytest.mark.parametrize("mode", ("w8s", "w8a", "w4"))
+@pytest.mark.parametrize("tile", (-1, 0, 1, 2))
+def test_a8_small_shapes(mq, orc, mode, tile):
+    mq.tune_force_tile(tile)
+    bits, sym = {"w8s": (8, True), "w8a": (8, False), "w4": (4, False)}[mode]
+    fn = mq.qlinear_w8a8 if bits == 8 else mq.qlinear_w4a8
+    for (M, K, N) in A8_SHAPES:
+        x = si.activations_f16(13, f"a8/x{M}x{K}", M, K, outlier_prob=0.01)
+        w = si.weights_f16(13, f"a8/w{N}x{K}", N, K)
+        b = si.bias_f16(13, f"a8/b{N}", N)
+        pw, oc, os_, oz = make_weight(mq, orc, w, bits, sym)
+        # dynamic activation parameters
+        y, acc, (s_out, z_out) = fn(dev(x), pw, bias=dev(b), want_acc=True, want_act=True)
+        ry, racc, (rs, rz) = orc.linear_a8(x, oc, os_, oz, w_signed=sym, bias=b)
+        assert host(s_out)[0] == rs and host(z_out)[0] == rz, "dynamic activation parameters"
+        assert np.array_equal(host(acc), racc), f"acc {mode} tile{tile} {M}x{K}x{N}"
+        assert_close16(host(y), ry, f"a8 {mode} tile{tile} {M}x{K}x{N}")
+        # static (calibrated) parameters, narrower than the data so that codes saturate
+        act = (np.float32(0.03), 117)
+        y, acc, _ = fn(dev(x), pw, act=(dev(np.array([act[0]], np.float32)), dev(np.array([act[1]], np.int32))),
+                       want_acc=True)
+        ry, racc, _ = orc.linear_a8(x, oc, os_, oz, w_signed=sym, act=act)
+        assert np.array_equal(host(acc), racc)
+        assert_close16(host(y), ry, f"a8 static {mode}")
+    mq.tune_force_tile(-1)
+
+
+def test_a8_is_deterministic(mq, orc):
+    M, K, N = 608, 2048, 640
+    x = dev(si.activations_f16(14, "a8/det", M, K))
+    pw, *_ = make_weight(mq, orc, si.weights_f16(14, "a8/detw", N, K), 4)
+    y0, a0, _ = mq.qlinear_w4a8(x, pw, want_acc=True)
+    for _ in range(3):
+        y1, a1, _ = mq.qlinear_w4a8(x, pw, want_acc=True)
+        assert torch.equal(a0, a1) and torch.equal(y0, y1)
+
+
+@pytest.mark.parametrize("K,N", [(1280, 1280), (1280, 10240), (5120, 1280)])
+def test_a8_transformer_block_shapes_sampled_rows(mq, orc, K, N):
+    """32x32-level block linears (batch 4, M = 4096) at full size; oracle on sampled rows, accumulators bit-exact."""
+    M = 4096
+    x = si.activations_f16(0, f"c3/x{K}", M, K)
+    w = si.weights_f16(0, f"c3/w{N}x{K}", N, K)
+    b = si.bias_f16(0, f"c3/b{N}", N)
+    rng = np.random.default_rng(K + N)
+    rows = np.unique(np.concatenate([[0, M - 1, int(np.argmax(x.max(1))), int(np.argmin(x.min(1)))],
+                                     rng.integers(0, M, 28)]))
+    for bits, sym, fn in ((4, False, mq.qlinear_w4a8), (8, True, mq.qlinear_w8a8)):
+        pw, oc, os_, oz = make_weight(mq, orc, w, bits, sym)
+        y, acc, (s_out, z_out) = fn(dev(x), pw, bias=dev(b), want_acc=True, want_act=True)
+        ry, racc, (rs, rz) = orc.linear_a8(x, oc, os_, oz, w_signed=sym, bias=b, rows=rows)
+        assert host(s_out)[0] == rs and host(z_out)[0] == rz
+        assert np.array_equal(host(acc)[rows], racc)
+        assert_close16(host(y)[rows], ry, f"c3 W{bits}A8 {K}->{N}")
+
+
+# ----------------------------------------------------------------------------------------------- BOS-aware K/V
+
+@pytest.mark.parametrize("N", (640, 1280))
+@pytest.mark.parametrize("bits,sym", [(8, True), (4, False)])
+def test_bos_aware_kv_projection(mq, orc, N, bits, sym):
+    B, T, K = 8, 77, 2048
+    ctx = si.bos_context_f16(0, "c4/ctx", B, T, K)
+    w = si.weights_f16(0, f"c4/w{N}", N, K)
+    pw, oc, os_, oz = make_weight(mq, orc, w, bits, sym)
+    # run-time fp16 BOS row
+    y, (s_out, z_out) = mq.bos_aware_kv_proj(dev(ctx), pw, w_f16=dev(w), want_act=True)
+    ry, (rs, rz) = orc.bos_aware_kv_proj(ctx, oc, os_, oz, w_signed=sym, w_f16=w)
+    assert host(s_out)[0] == rs and host(z_out)[0] == rz
+    yh = host(y)
+    assert_close16(yh[:, 1:], ry[:, 1:], "body rows")
+    assert_close16(yh[:, 0], ry[:, 0], "BOS rows")
+    # pre-computed BOS vector: copied verbatim
+    bos_out = orc.linear_fp(ctx[0, 0:1], w)[0]
+    y2, _ = mq.bos_aware_kv_proj(dev(ctx), pw, bos_out=dev(bos_out.view(np.float16)))
+    y2h = host(y2)
+    assert np.array_equal(y2h[:, 0].view(np.uint16), np.broadcast_to(bos_out, (B, N)))
+    assert np.array_equal(y2h[:, 1:], yh[:, 1:])
+    # comparator: all rows through the 8-bit path
+    y3, (s3, _) = mq.bos_aware_kv_proj(dev(ctx), pw, naive_all_rows=True, want_act=True)
+    ry3, (rs3, _) = orc.bos_aware_kv_proj(ctx, oc, os_, oz, w_signed=sym, naive_all_rows=True)
+    assert host(s3)[0] == rs3 and rs3 > 5 * rs
+    assert_close16(host(y3), ry3, "naive all rows")
+
+
+def test_bos_distinct_rows_small_and_degenerate(mq, orc):
+    for (B, T, K, N) in ((3, 9, 128, 36), (1, 2, 64, 32), (2, 1, 64, 32)):
+        ctx = si.bos_context_f16(3, f"bos/{B}{T}", B, T, K, n_outlier=4, shared_bos=False)
+        w = si.weights_f16(3, f"bos/w{N}", N, K)
+        b = si.bias_f16(3, f"bos/b{N}", N)
+        pw, oc, os_, oz = make_weight(mq, orc, w, 8, True)
+        y, _ = mq.bos_aware_kv_proj(dev(ctx), pw, w_f16=dev(w), bias=dev(b))
+        ry, _ = orc.bos_aware_kv_proj(ctx, oc, os_, oz, w_signed=True, w_f16=w, bias=b)
+        assert_close16(host(y), ry, f"bos {B}x{T}")
+
+
+# ----------------------------------------------------------------------------------------------- full-size sweep shapes
+
+@pytest.mark.parametrize("K,N", [(640, 5120), (2560, 640)])
+def test_sweep_640_level_shapes_sampled_rows(mq, orc, K, N):
+    """M = 16384 (latent 128x128, batch 4): weight-only at 2 bits and W4A8, oracle on sampled rows."""
+    M = 16384
+    x = si.activations_f16(0, f"c5/x{K}", M, K, outlier_prob=0.01)
+    w = si.weights_f16(0, f"c5/w{N}x{K}", N, K)
+    rows = np.unique(np.concatenate([[0, M - 1, int(np.argmax(x.max(1))), int(np.argmin(x.min(1)))],
+                                     np.random.default_rng(K).integers(0, M, 28)]))
+    xd = dev(x)
+    pw, oc, os_, oz = make_weight(mq, orc, w, 2)
+    y = host(mq.qlinear_w_only(xd, pw))
+    assert_close16(y[rows], orc.linear_w_only(x, oc, os_, oz, rows=rows), "c5 W2A16")
+    pw, oc, os_, oz = make_weight(mq, orc, w, 4)
+    y, acc, _ = mq.qlinear_w4a8(xd, pw, want_acc=True)
+    ry, racc, _ = orc.linear_a8(x, oc, os_, oz, rows=rows)
+    assert np.array_equal(host(acc)[rows], racc)
+    assert_close16(host(y)[rows], ry, "c5 W4A8")
