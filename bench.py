@@ -1,0 +1,212 @@
+#!/usr/bin/env python3
+"""Benchmark of the quantized-linear hot path on one MI355X.
+
+Workload (the configuration the metric is quoted on): the full SDXL-turbo UNet linear sweep at 1024 px, batch 4
+(latent 128x128): the ten linears of each of 2 transformer blocks at the 640-channel level (M = 16384) and of
+10 blocks at the 1280-channel level (M = 4096), cross-attention K/V projections on the [4,77,2048] text context
+included; 120 layers, 367 M weights.  One step = one pass of the whole hot path over that batch:
+  pass 1  weight-only W{2,3,4,8}A16 at seeded per-layer bit-widths averaging 3.66 bits (parameter weighted),
+  pass 2  W4A8 everywhere with dynamic per-tensor activation quantisation (min/max reduce + quantise + int8 GEMM);
+          the K/V projections run BOS-aware (token 0 of each prompt in fp16).
+All inputs are synthetic, seeded and resident in HBM before the timed region.
+
+Prints one JSON line: whole-step throughput in TOP/s plus the roofline figures of the dominant kernel (timed with
+HIP events on the launch stream inside the timed region) and the CPU oracle timed on a bounded sample.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK = {"f16": 2500.0, "int8": 5000.0}  # dense MFMA peaks of MI355X, TFLOP/s and TOP/s
+HBM_PEAK_GBS = 8000.0
+
+
+def build_workload(mq, torch, si, seed=0):
+    dev = torch.device("cuda:0")
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(seed)
+    layers, mean_bits = si.sweep_layers(seed)
+    work = []
+    ws_bytes = 0
+    for L in layers:
+        w = (torch.randn(L.N, L.K, generator=gen, device=dev) * 0.02).to(torch.float16)
+        packs = {}
+        for bits in sorted({L.bits, 4}):
+            c, s, z = mq.quantize_weights(w, bits)
+            p, cs = mq.pack_weights(c, bits, mq.LAYOUT_KERNEL)
+            packs[bits] = mq.PackedWeight(p, s, z, cs, L.N, L.K, bits, mq.LAYOUT_KERNEL, False)
+        bias = (torch.randn(L.N, generator=gen, device=dev) * 0.01).to(torch.float16) if L.bias else None
+        if L.kind == "kv":
+            x = torch.randn(L.B, L.T, L.K, generator=gen, device=dev)
+            bos = torch.randn(L.K, generator=gen, device=dev)
+            ch = torch.randperm(L.K, generator=gen, device=dev)[:16]
+            bos[ch] = torch.randn(16, generator=gen, device=dev) * 60.0
+            x[:, 0, :] = bos  # the BOS feature does not depend on the prompt
+            x = x.to(torch.float16)
+            ws_bytes = max(ws_bytes, mq.bos_aware_kv_proj_workspace_bytes(L.B, L.T, L.K))
+            wf16 = w
+        else:
+            x = torch.randn(L.M, L.K, generator=gen, device=dev)
+            outl = torch.rand(L.M, L.K, generator=gen, device=dev) < 0.01
+            x = torch.where(outl, x * 10.0, x).to(torch.float16)
+            ws_bytes = max(ws_bytes, mq.qlinear_a8_workspace_bytes(L.M, L.K))
+            wf16 = None
+            del outl
+        y = torch.empty(L.M, L.N, dtype=torch.float16, device=dev)
+        work.append(dict(L=L, x=x, w_mixed=packs[L.bits], w4=packs[4], bias=bias, y=y, wf16=wf16))
+        if wf16 is None:
+            del w
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+    torch.cuda.synchronize()
+    return work, ws, mean_bits
+
+
+def run_step(mq, work, ws):
+    # pass 1: weight-only at the mixed per-layer bit-widths
+    for it in work:
+        L = it["L"]
+        x2 = it["x"].view(L.M, L.K)
+        mq.qlinear_w_only(x2, it["w_mixed"], it["bias"], out=it["y"])
+    # pass 2: W4A8, dynamic activation quantisation; K/V projections BOS-aware
+    for it in work:
+        L = it["L"]
+        if L.kind == "kv":
+            mq.bos_aware_kv_proj(it["x"], it["w4"], w_f16=it["wf16"], bias=it["bias"],
+                                 out=it["y"].view(L.B, L.T, L.N), ws=ws)
+        else:
+            mq.qlinear_w4a8(it["x"], it["w4"], bias=it["bias"], out=it["y"], ws=ws)
+
+
+def cpu_baseline(si):
+    """The CPU oracle, as it stands, on a bounded sample of the same workload: the 1280->10240 GEGLU projection
+    of one 1280-level block (M = 4096), W4A8 on all rows and weight-only on the first 1024 rows."""
+    import numpy as np
+
+    import oracle
+    M, K, N = 4096, 1280, 10240
+    x = si.activations_f16(0, "bench/cpu/x", M, K, outlier_prob=0.01)
+    w = si.weights_f16(0, "bench/cpu/w", N, K)
+    b = si.bias_f16(0, "bench/cpu/b", N)
+    c, s, z = oracle.quantize_weights(w, 4)
+    t0 = time.perf_counter()
+    oracle.linear_a8(x, c, s, z, bias=b, want_acc=False)
+    rows = np.arange(1024)
+    oracle.linear_w_only(x, c, s, z, b, rows=rows)
+    dt = time.perf_counter() - t0
+    ops = 2.0 * M * N * K + 2.0 * len(rows) * N * K
+    cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+    cores = min(cores, os.cpu_count() or cores)
+    return {"value": ops / dt / 1e12, "unit": "TOP/s", "cores": cores, "kind": "oracle",
+            "sample": f"ff.proj 4096x1280->10240: W4A8 all rows + W4A16 first 1024 rows, {dt:.1f} s"}
+
+
+def read_traffic(kernel_name):
+    """HBM bytes per launch of the named kernel from the committed counter summary, if there is one."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic_sweep.txt")
+    if not os.path.exists(path):
+        return None
+    for line in open(path):
+        if line.startswith("traffic_bytes_per_launch") and kernel_name in line:
+            try:
+                return float(line.split("=")[-1])
+            except ValueError:
+                return None
+    return None
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-prof", action="store_true", help="do not bracket kernels with events (roofline is null)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU; --gpus N with N > 1 is not supported", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    import paper_2405_17873_amd as mq
+    import synth_inputs as si
+    mq.load()  # raises if the HIP library is missing: there is no fallback
+    assert torch.cuda.is_available()
+
+    work, ws, mean_bits = build_workload(mq, torch, si)
+    ops_step = 2.0 * sum(2.0 * it["L"].M * it["L"].N * it["L"].K for it in work)
+
+    for _ in range(args.warmup):
+        run_step(mq, work, ws)
+    torch.cuda.synchronize()
+    if not args.no_prof:
+        mq.prof_reset()
+        mq.prof_enable(True)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        run_step(mq, work, ws)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    roofline = None
+    kernels = []
+    if not args.no_prof:
+        mq.prof_enable(False)
+        kernels = mq.prof_read()
+        if kernels:
+            dom = max(kernels, key=lambda k: k["ms"])
+            is_int8 = "gemm_a8" in dom["kernel"]
+            is_gemm = "gemm" in dom["kernel"]
+            avg_ms = dom["ms"] / dom["launches"]
+            if is_gemm:
+                peak = PEAK["int8" if is_int8 else "f16"]
+                achieved = dom["ops"] / dom["launches"] / (avg_ms * 1e-3) / 1e12
+                roofline = {"bound": "mfma", "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
+                            "frac": achieved / peak, "traffic": read_traffic(dom["kernel"]),
+                            "kernel": dom["kernel"], "launches_per_step": dom["launches"] / args.steps,
+                            "avg_launch_us": avg_ms * 1e3, "ops_kind": "int8" if is_int8 else "fp16",
+                            "alg_GBps": dom["bytes"] / dom["launches"] / (avg_ms * 1e-3) / 1e9}
+            else:
+                achieved = dom["bytes"] / dom["launches"] / (avg_ms * 1e-3) / 1e9
+                roofline = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                            "frac": achieved / HBM_PEAK_GBS, "traffic": read_traffic(dom["kernel"]),
+                            "kernel": dom["kernel"], "launches_per_step": dom["launches"] / args.steps,
+                            "avg_launch_us": avg_ms * 1e3}
+            for k in kernels:
+                k["ms_per_step"] = k.pop("ms") / args.steps
+                k["TOPs"] = k["ops"] / args.steps / (k["ms_per_step"] * 1e-3) / 1e12 if k["ops"] else 0.0
+                k["GBps"] = k["bytes"] / args.steps / (k["ms_per_step"] * 1e-3) / 1e9
+                k["launches"] = k["launches"] / args.steps
+                del k["ops"], k["bytes"]
+
+    out = {
+        "metric": "quantized-GEMM TOPS & HBM GB/s (fraction of roofline) on SDXL-turbo UNet linear sweep",
+        "value": ops_step * args.steps / dt / 1e12,
+        "unit": "TOP/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": dt / args.steps * 1e3,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f16+int8",
+        "data": "synthetic",
+        "config": {"workload": "SDXL-turbo UNet linear sweep, 1024px batch 4 (latent 128x128): 120 linears, "
+                               "pass 1 W%.2fA16 mixed {2,3,4,8} bits + pass 2 W4A8 dynamic, BOS-aware K/V" % mean_bits,
+                   "layers": len(work), "ops_per_step": ops_step, "mean_weight_bits": mean_bits},
+        "roofline": roofline,
+        "cpu_baseline": None if args.no_cpu_baseline else cpu_baseline(si),
+        "kernels": kernels,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -52,6 +52,18 @@ int mq_last_hip_error(void);
  * from the problem shape).  Process-wide, not thread safe; results do not depend on the tile. */
 void mq_tune_force_tile(int tile);
 
+/* Per-kernel timing for benchmarks.  While enabled, every kernel launch of the library is bracketed by two HIP
+ * events recorded on the stream it is launched on.  mq_prof_read waits for the pending events of one slot and
+ * returns, accumulated since the last reset: the kernel's name (host buffer), number of launches, elapsed
+ * milliseconds, algorithmic operations (2*M*N*K per GEMM launch) and algorithmic bytes (activations read once,
+ * packed weights, per-channel vectors, output written once).  Host bookkeeping only; costs two event records per
+ * launch.  Slots 0..mq_prof_num_slots()-1; slots that never ran report zero launches. */
+int mq_prof_enable(int on);
+int mq_prof_num_slots(void);
+int mq_prof_read(int slot, char* name_host, int name_cap, long long* launches_host, double* ms_host,
+                 double* ops_host, double* bytes_host);
+int mq_prof_reset(void);
+
 /* ------------------------------------------------------------------------------------------------
  * Offline preparation
  * ---------------------------------------------------------------------------------------------- */

@@ -20,7 +20,8 @@ _ERRORS = {
     -5: "MQ_ERR_HIP", -6: "MQ_ERR_UNSUPPORTED_LAYOUT", -7: "MQ_ERR_OVERFLOW_RISK",
 }
 
-EXPORTS = ("mq_version", "mq_last_hip_error", "mq_tune_force_tile", "mq_quantize_weights", "mq_packed_bytes", "mq_pack_weights",
+EXPORTS = ("mq_version", "mq_last_hip_error", "mq_tune_force_tile", "mq_prof_enable", "mq_prof_num_slots", "mq_prof_read",
+           "mq_prof_reset", "mq_quantize_weights", "mq_packed_bytes", "mq_pack_weights",
            "mq_unpack_weights", "mq_qlinear_w_only", "mq_qlinear_a8_workspace_bytes", "mq_qlinear_w8a8",
            "mq_qlinear_w4a8", "mq_bos_aware_kv_proj_workspace_bytes", "mq_bos_aware_kv_proj")
 
@@ -56,6 +57,29 @@ def version() -> int:
 
 def tune_force_tile(tile: int) -> None:
     load().mq_tune_force_tile(int(tile))
+
+
+def prof_enable(on: bool) -> None:
+    _check(load().mq_prof_enable(int(on)), "mq_prof_enable")
+
+
+def prof_reset() -> None:
+    _check(load().mq_prof_reset(), "mq_prof_reset")
+
+
+def prof_read():
+    """Per-kernel totals since the last reset: list of dicts (only kernels that ran)."""
+    L = load()
+    out = []
+    for slot in range(L.mq_prof_num_slots()):
+        name = C.create_string_buffer(128)
+        n = C.c_longlong()
+        ms, ops, byts = C.c_double(), C.c_double(), C.c_double()
+        _check(L.mq_prof_read(slot, name, 128, C.byref(n), C.byref(ms), C.byref(ops), C.byref(byts)), "mq_prof_read")
+        if n.value:
+            out.append({"kernel": name.value.decode(), "launches": n.value, "ms": ms.value, "ops": ops.value,
+                        "bytes": byts.value})
+    return out
 
 
 def _ptr(t: Optional[torch.Tensor]):

@@ -20,7 +20,7 @@ PER_FILE = {
     "quant_pack.hip": ["-ffp-contract=off"],
     "act_quant.hip": ["-ffp-contract=off"],
 }
-SOURCES = ["api.hip", "quant_pack.hip", "act_quant.hip", "gemm.hip", "bos.hip"]
+SOURCES = ["api.hip", "quant_pack.hip", "act_quant.hip", "gemm.hip", "bos.hip", "prof.hip"]
 
 
 def _compile(src: str, force: bool) -> str:

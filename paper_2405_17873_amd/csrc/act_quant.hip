@@ -138,12 +138,14 @@ int launch_act_quant(const void* x, int M, int K, int ldx, RowMap in_map, const 
     if (grid > kPartialSlots) grid = kPartialSlots;
     const bool dynamic = act_scale == nullptr;
     if (dynamic) {
+        ProfScope prof(st, PROF_ACT_MINMAX, 0.0, 2.0 * M * K);
         hipLaunchKernelGGL(act_minmax_kernel, dim3(grid), dim3(256), 0, st, (const _Float16*)x, M, K, (long)ldx, in_map,
                            partials);
         MQ_HIP_CHECK_LAUNCH();
     }
     int qgrid = (M + 3) / 4;
     if (qgrid > 4096) qgrid = 4096;
+    ProfScope prof(st, PROF_ACT_QUANTIZE, 0.0, 3.0 * M * K + 4.0 * M);
     hipLaunchKernelGGL(act_quantize_kernel, dim3(qgrid), dim3(256), 0, st, (const _Float16*)x, M, K, (long)ldx, in_map,
                        dynamic ? partials : (const float*)nullptr, grid, act_scale, act_zp, a8, rowsum, params,
                        act_scale_out, act_zp_out);

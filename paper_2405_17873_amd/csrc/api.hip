@@ -75,6 +75,13 @@ extern "C" {
 int mq_version(void) { return 1; }
 int mq_last_hip_error(void) { return g_last_hip_error.load(); }
 void mq_tune_force_tile(int tile) { set_force_tile(tile); }
+int mq_prof_enable(int on) { return prof_enable(on); }
+int mq_prof_num_slots(void) { return prof_num_slots(); }
+int mq_prof_read(int slot, char* name_host, int name_cap, long long* launches_host, double* ms_host,
+                 double* ops_host, double* bytes_host) {
+    return prof_read(slot, name_host, name_cap, launches_host, ms_host, ops_host, bytes_host);
+}
+int mq_prof_reset(void) { return prof_reset(); }
 
 int mq_quantize_weights(const void* w, int N, int K, int bits, int symmetric, int dtype, uint8_t* codes, float* scale,
                         int32_t* zp, void* stream) {

@@ -59,6 +59,7 @@ int launch_bos_rows(const void* ctx, int B, int T, int K, const void* w_f16, con
         hipLaunchKernelGGL(bos_copy_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
                            (const _Float16*)bos_out, (_Float16*)y, B, T, N);
     } else {
+        ProfScope prof(st, PROF_BOS_ROWS, 2.0 * B * N * K, 2.0 * N * K + 2.0 * B * K + 2.0 * B * N);
         hipLaunchKernelGGL(bos_rows_kernel<8>, dim3((N + 3) / 4), dim3(256), 0, st, (const _Float16*)ctx, B, T, K,
                            (const _Float16*)w_f16, (const _Float16*)bias, (_Float16*)y, N);
     }

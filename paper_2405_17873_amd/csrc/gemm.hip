@@ -503,6 +503,9 @@ static int run_w_only(const void* x, int M, int K, int ldx, const void* packed, 
     constexpr int BM = WGM * TM * 32, BN = WGN * TN * 32;
     const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
     auto kern = gemm_w_only_kernel<BITS, WGM, WGN, TM, TN>;
+    // algorithmic traffic: X read once, packed W, scale + zp + bias, Y written once
+    ProfScope prof(st, prof_gemm_slot(0, BITS, TM == 4 ? 0 : TM == 2 ? 1 : 2), 2.0 * M * N * K,
+                   2.0 * M * K + (double)N * K * BITS / 8 + 10.0 * N + 2.0 * M * N);
     hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n), dim3(256), 2 * BM * 128, st, (const _Float16*)x, M, K, (long)ldx,
                        (const uint8_t*)packed, N, w_scale, w_zp, (const _Float16*)bias, (_Float16*)y, (long)ldy,
                        tiles_n);
@@ -516,8 +519,6 @@ void set_force_tile(int t) { g_force_tile = t; }
 
 static int pick_tile(int M, int N) {
     if (g_force_tile >= 0 && g_force_tile <= 2) return g_force_tile;
-    const long t256 = (long)((M + 255) / 256) * ((N + 255) / 256);
-    if (t256 >= 512) return 0;
     const long t128 = (long)((M + 127) / 128) * ((N + 127) / 128);
     if (t128 >= 256) return 1;
     return 2;
@@ -553,6 +554,9 @@ static int run_a8(const int8_t* a8, const int32_t* rowsum, const ActParams* para
     constexpr int BM = WGM * TM * 32, BN = WGN * TN * 32;
     const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
     auto kern = gemm_a8_kernel<WBITS, WGM, WGN, TM, TN>;
+    // algorithmic traffic of the integer GEMM itself: int8 activations, packed W, per-channel vectors, Y
+    ProfScope prof(st, prof_gemm_slot(1, WBITS, TM == 4 ? 0 : TM == 2 ? 1 : 2), 2.0 * M * N * K,
+                   1.0 * M * K + 4.0 * M + (double)N * K * WBITS / 8 + 14.0 * N + 2.0 * M * N);
     hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n), dim3(256), 2 * BM * 128, st, a8, rowsum, params, M, K,
                        (const uint8_t*)packed, N, w_off, w_scale, w_zp, w_colsum, (const _Float16*)bias, (_Float16*)y,
                        (long)ldy, out_map, acc_debug, tiles_n);

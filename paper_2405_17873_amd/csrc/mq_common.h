@@ -88,6 +88,31 @@ int launch_gemm_a8(const int8_t* a8, const int32_t* rowsum, const ActParams* par
 
 void set_force_tile(int t);
 
+// ---- optional per-kernel event timing (prof.hip) ----
+enum { PROF_ACT_MINMAX = 24, PROF_ACT_QUANTIZE = 25, PROF_BOS_ROWS = 26 };
+int prof_num_slots();
+int prof_gemm_slot(int family /*0 weight-only, 1 int8*/, int bits, int tile);
+bool prof_enabled();
+int prof_enable(int on);
+bool prof_begin(hipStream_t st, hipEvent_t* a, hipEvent_t* b);
+void prof_end(hipEvent_t a, hipEvent_t b, hipStream_t st, int slot, double ops, double bytes);
+int prof_read(int slot, char* name, int name_cap, long long* launches, double* ms, double* ops, double* bytes);
+int prof_reset();
+
+struct ProfScope {
+    bool open = false;
+    hipEvent_t a, b;
+    int slot;
+    hipStream_t st;
+    double ops, bytes;
+    ProfScope(hipStream_t s, int slot_, double ops_, double bytes_) : slot(slot_), st(s), ops(ops_), bytes(bytes_) {
+        if (prof_enabled()) open = prof_begin(st, &a, &b);
+    }
+    ~ProfScope() {
+        if (open) prof_end(a, b, st, slot, ops, bytes);
+    }
+};
+
 int launch_bos_rows(const void* ctx, int B, int T, int K, const void* w_f16, const void* bos_out, const void* bias,
                     void* y, int N, hipStream_t st);
 

@@ -1,0 +1,135 @@
+// Optional per-kernel timing: while enabled, every kernel launch of the library is bracketed by two HIP
+// events recorded on the caller's stream.  Reading a slot waits for its events and accumulates elapsed time,
+// launch count and the algorithmic operations and bytes of those launches.  Host-side bookkeeping only.
+#include <mutex>
+#include <string>
+#include <vector>
+
+#include "mq_common.h"
+
+namespace mq {
+
+namespace {
+struct Pair {
+    hipEvent_t a, b;
+};
+struct Slot {
+    std::string name;
+    long long launches = 0;
+    double ms = 0, ops = 0, bytes = 0;
+    std::vector<Pair> pending;
+};
+std::mutex g_mu;
+bool g_on = false;
+std::vector<Slot> g_slots;
+std::vector<Pair> g_free;
+
+const int kBits[4] = {2, 3, 4, 8};
+const int kTile[3][2] = {{4, 4}, {2, 2}, {1, 1}};
+
+void init_slots() {
+    if (!g_slots.empty()) return;
+    g_slots.resize(prof_num_slots());
+    for (int fam = 0; fam < 2; ++fam)
+        for (int b = 0; b < 4; ++b)
+            for (int t = 0; t < 3; ++t) {
+                char buf[96];
+                snprintf(buf, sizeof buf, "mq::%s<%d, 2, 2, %d, %d>", fam ? "gemm_a8_kernel" : "gemm_w_only_kernel",
+                         kBits[b], kTile[t][0], kTile[t][1]);
+                g_slots[prof_gemm_slot(fam, kBits[b], t)].name = buf;
+            }
+    g_slots[PROF_ACT_MINMAX].name = "mq::act_minmax_kernel";
+    g_slots[PROF_ACT_QUANTIZE].name = "mq::act_quantize_kernel";
+    g_slots[PROF_BOS_ROWS].name = "mq::bos_rows_kernel<8>";
+}
+}  // namespace
+
+int prof_num_slots() { return 27; }
+
+int prof_gemm_slot(int family, int bits, int tile) {
+    const int b = bits == 2 ? 0 : bits == 3 ? 1 : bits == 4 ? 2 : 3;
+    return (family * 4 + b) * 3 + tile;
+}
+
+bool prof_enabled() { return g_on; }
+
+int prof_enable(int on) {
+    std::lock_guard<std::mutex> lk(g_mu);
+    init_slots();
+    g_on = on != 0;
+    return MQ_OK;
+}
+
+bool prof_begin(hipStream_t st, hipEvent_t* a, hipEvent_t* b) {
+    std::lock_guard<std::mutex> lk(g_mu);
+    Pair p;
+    if (!g_free.empty()) {
+        p = g_free.back();
+        g_free.pop_back();
+    } else {
+        if (hipEventCreate(&p.a) != hipSuccess) return false;
+        if (hipEventCreate(&p.b) != hipSuccess) {
+            (void)hipEventDestroy(p.a);
+            return false;
+        }
+    }
+    if (hipEventRecord(p.a, st) != hipSuccess) {
+        g_free.push_back(p);
+        return false;
+    }
+    *a = p.a;
+    *b = p.b;
+    return true;
+}
+
+void prof_end(hipEvent_t a, hipEvent_t b, hipStream_t st, int slot, double ops, double bytes) {
+    std::lock_guard<std::mutex> lk(g_mu);
+    (void)hipEventRecord(b, st);
+    Slot& s = g_slots[slot];
+    s.pending.push_back(Pair{a, b});
+    s.launches += 1;
+    s.ops += ops;
+    s.bytes += bytes;
+}
+
+int prof_read(int slot, char* name, int name_cap, long long* launches, double* ms, double* ops, double* bytes) {
+    std::lock_guard<std::mutex> lk(g_mu);
+    init_slots();
+    if (slot < 0 || slot >= (int)g_slots.size()) return MQ_ERR_BAD_ARG;
+    Slot& s = g_slots[slot];
+    for (Pair& p : s.pending) {
+        float t = 0;
+        if (hipEventSynchronize(p.b) != hipSuccess || hipEventElapsedTime(&t, p.a, p.b) != hipSuccess) {
+            set_hip_error((int)hipGetLastError());
+            return MQ_ERR_HIP;
+        }
+        s.ms += t;
+        g_free.push_back(p);
+    }
+    s.pending.clear();
+    if (name && name_cap > 0) {
+        snprintf(name, name_cap, "%s", s.name.c_str());
+    }
+    if (launches) *launches = s.launches;
+    if (ms) *ms = s.ms;
+    if (ops) *ops = s.ops;
+    if (bytes) *bytes = s.bytes;
+    return MQ_OK;
+}
+
+int prof_reset() {
+    std::lock_guard<std::mutex> lk(g_mu);
+    init_slots();
+    for (Slot& s : g_slots) {
+        for (Pair& p : s.pending) {
+            (void)hipEventSynchronize(p.b);
+            g_free.push_back(p);
+        }
+        s.pending.clear();
+        s.launches = 0;
+        s.ms = s.ops = s.bytes = 0;
+    }
+    return MQ_OK;
+}
+
+}  // namespace mq
