@@ -105,9 +105,9 @@ int mq_unpack_weights(const void* packed, int N, int K, int bits, int layout, ui
 
 /* Weight-only linear, W{2,3,4,8}A16 (paper App. C item 2: low-bit weights, 16-bit floating-point compute):
  *     Y[m,n] = round16( sum_k X[m,k] * scale[n] * (code[n,k] - zp[n]) + bias[n] ),  fp32 accumulation.
- *   x      [M,K] row stride ldx, 16-byte aligned, ldx % 8 == 0.     y [M,N] row stride ldy, ldy % 4 == 0.
+ *   x      [M,K] row stride ldx, 16-byte aligned, ldx % 8 == 0.     y [M,N] row stride ldy, 16-byte aligned, ldy % 8 == 0.
  *   packed MQ_LAYOUT_KERNEL, unsigned codes.   bias nullable [N] (same 16-bit dtype as x and y).
- *   K % 64 == 0, N % 4 == 0.  No workspace is needed. */
+ *   K % 64 == 0, N % 8 == 0, M*ldx*2 < 2^31 bytes.  No workspace is needed. */
 int mq_qlinear_w_only(const void* x, int M, int K, int ldx, const void* packed, int N, int bits, int layout,
                       const float* w_scale, const int32_t* w_zp, const void* bias, void* y, int ldy, int dtype,
                       void* stream);
@@ -127,7 +127,7 @@ size_t mq_qlinear_a8_workspace_bytes(int M, int K);
  *            (calibrated, Sec. 4.1) parameters are read from these device scalars.
  *   acc_debug         nullable [M,N] int32 out: ACC, for bit-exact checks.
  *   act_scale_out/act_zp_out  nullable device scalars out: the parameters that were used.
- *   K % 64 == 0 and K <= 33024; N % 4 == 0.
+ *   K % 64 == 0 and K <= 33024; N % 8 == 0.
  * Errors: MQ_ERR_BAD_ARG when exactly one of act_scale/act_zp is NULL; MQ_ERR_OVERFLOW_RISK;
  *         MQ_ERR_WORKSPACE_TOO_SMALL; and the common ones. */
 int mq_qlinear_w8a8(const void* x, int M, int K, int ldx, const void* packed, int N, int layout, int w_signed,

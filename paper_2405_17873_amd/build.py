@@ -32,7 +32,8 @@ def _compile(src: str, force: bool) -> str:
     cmd = [HIPCC, *COMMON, *PER_FILE.get(src, []), "-c", path, "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
-        sys.stderr.write(r.stdout + r.stderr)
+        errs = [l for l in (r.stdout + r.stderr).splitlines() if "error" in l]
+        sys.stderr.write("\n".join(errs[:20]) + "\n")
         raise RuntimeError(f"hipcc failed on {src}")
     warn = [l for l in r.stderr.splitlines() if "packed-fp32-ops" not in l and l.strip()]
     if warn:

@@ -6,7 +6,7 @@
 //   pass 2: every workgroup re-reduces the partials (a few KB, L2 resident), derives (scale, zp) with the
 //           same fp32 operations as the weight quantiser, then converts its rows:
 //               a'[m,k] = clamp(rne(x*inv) + zp, 0, 255) - 128   stored as int8, groups of 8 k in the order
-//               0,4,1,5,2,6,3,7, and rowsum[m] = sum_k a'[m,k].
+//               0,4,1,5,2,6,3,7, rows padded with zeros to a multiple of 128, and rowsum[m] = sum_k a'[m,k].
 //
 // Compiled with -ffp-contract=off: each fp32 operation rounds once.
 #include "mq_common.h"
@@ -104,10 +104,12 @@ __global__ __launch_bounds__(256) void act_quantize_kernel(const _Float16* __res
         if (act_zp_out) *act_zp_out = (int)zf;
     }
     const int K8 = K >> 3;
+    const int Kp = (K + 127) / 128 * 128;  // row stride of the int8 copy; the padding is zero
     for (long r = (long)blockIdx.x * 4 + wv; r < M; r += (long)gridDim.x * 4) {
         const half8* row = (const half8*)(x + map.phys(r) * ldx);
-        uint2* out = (uint2*)(a8 + r * (long)K);
+        uint2* out = (uint2*)(a8 + r * (long)Kp);
         int sum = 0;
+        for (int p = K8 + lane; p < (Kp >> 3); p += 64) out[p] = make_uint2(0u, 0u);
         for (int p = lane; p < K8; p += 64) {
             const half8 v = row[p];
             int q[8];

@@ -19,8 +19,9 @@ struct A8Workspace {
     int32_t* rowsum;
     int8_t* a8;
     static size_t bytes(long M, long K) {
+        const size_t Kp = ((size_t)K + 127) / 128 * 128;  // int8 rows are padded to whole 128-k stages
         return 256 + up256(sizeof(float) * 2 * (size_t)act_quant_partial_slots()) + up256(4 * (size_t)M) +
-               up256((size_t)M * K) + 256;
+               up256((size_t)M * Kp) + 256;
     }
     A8Workspace(void* ws, long M, long K) {
         uint8_t* p = (uint8_t*)ws;
@@ -40,8 +41,10 @@ static int check_linear_common(const void* x, int M, int K, int ldx, const void*
     if (!x || !packed || !w_scale || !w_zp || !y) return MQ_ERR_BAD_ARG;
     if (M <= 0 || K <= 0 || N <= 0 || ldx < K || ldy < N) return MQ_ERR_BAD_SHAPE;
     if (layout != MQ_LAYOUT_KERNEL) return MQ_ERR_UNSUPPORTED_LAYOUT;
-    if (K % 64 != 0 || N % 4 != 0 || ldx % 8 != 0 || ldy % 4 != 0) return MQ_ERR_BAD_SHAPE;
-    if (!aligned(x, 16) || !aligned(packed, 16) || !aligned(w_scale, 16) || !aligned(w_zp, 16) || !aligned(y, 8) ||
+    if (K % 64 != 0 || N % 8 != 0 || ldx % 8 != 0 || ldy % 8 != 0) return MQ_ERR_BAD_SHAPE;
+    // lane offsets into X and into the packed weights are 32-bit
+    if ((long)M * ldx * 2 >= (1L << 31) || (long)(N + 31) * K >= (1L << 31)) return MQ_ERR_BAD_SHAPE;
+    if (!aligned(x, 16) || !aligned(packed, 16) || !aligned(w_scale, 16) || !aligned(w_zp, 16) || !aligned(y, 16) ||
         (bias && !aligned(bias, 8)))
         return MQ_ERR_BAD_ARG;
     return MQ_OK;

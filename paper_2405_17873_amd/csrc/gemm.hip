@@ -6,16 +6,19 @@
 //                 (paper Sec. 4.3 / App. C item 4: integer GEMM for W8A8; 4-bit codes widened for W4A8)
 //
 // Shared structure
-//   * One workgroup = 4 waves arranged WGM x WGN; each wave owns TM x TN MFMA tiles of 32x32.
-//   * The activation operand goes HBM -> registers -> LDS (double buffered, 128 bytes of K per row per
-//     stage, 16-byte pieces XOR-swizzled so that ds_read_b128 of 32 consecutive rows is conflict free).
+//   * One workgroup = WGM x WGN waves; each wave owns TM x TN MFMA tiles of 32x32.
+//   * The activation operand goes HBM -> LDS directly (buffer loads with the LDS bit: no staging registers),
+//     double buffered, 128 bytes of K per row per stage, 16-byte pieces XOR-swizzled so that ds_read_b128 of
+//     32 consecutive rows is conflict free.
 //   * The weight operand never touches LDS: the packed kernel layout stores, for every 32-channel x 64-k
-//     tile, the 64 lane chunks in lane order, so one global_load per 16 bytes of chunk is a fully contiguous
+//     tile, the 64 lane chunks in lane order, so one buffer load per 16 bytes of chunk is a fully contiguous
 //     wave access and lands directly in the MFMA operand's lane.  Codes are widened in registers.
 //   * The MFMA is issued with the weight fragment as the first operand: the 32x32 result then holds, per
 //     lane, 4 consecutive output channels of one activation row, i.e. an 8-byte fp16 store.
 //   * k-order inside a stage is permuted identically for both operands (a sum does not care), chosen so
 //     that every lane's global and LDS accesses are 16 bytes wide.
+#include <type_traits>
+
 #include "mq_common.h"
 
 namespace mq {
@@ -29,6 +32,7 @@ typedef int int16v __attribute__((ext_vector_type(16)));
 typedef int int4v __attribute__((ext_vector_type(4)));
 typedef uint32_t uint4v __attribute__((ext_vector_type(4)));
 typedef uint32_t uint2v __attribute__((ext_vector_type(2)));
+typedef uint32_t uint3v __attribute__((ext_vector_type(3)));
 
 // Swizzle of the 16-byte piece index inside a 128-byte LDS row.  Distinct over any 8 consecutive rows and,
 // together with the row parity, over any 16 consecutive rows.
@@ -144,189 +148,46 @@ __device__ __forceinline__ half8 dequant_step<8>(const WChunk<8>& c, int s, int 
     return half8{p0[0], p0[1], p1[0], p1[1], p2[0], p2[1], p3[0], p3[1]};
 }
 
+// ---------------------------------------------------------------------------------------------
+// Buffer addressing.  Both operands are read through buffer resources: a lane's offset is a 32-bit
+// register computed once, the k advance is a scalar offset, and anything past the end of the buffer reads
+// as zero instead of faulting (rows beyond M, the k padding of the int8 activation copy).
+// ---------------------------------------------------------------------------------------------
+typedef __attribute__((address_space(3))) void* lds_ptr_t;
+
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p, uint32_t bytes) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, (int)bytes, 0x00020000);
+}
+
+// 16 bytes per lane from the buffer straight into LDS: lane L of the wave writes lds_wave_base + 16 * L.
+// (Device pass only: the host pass of hipcc does not know the gfx950 form of the builtin.)
+__device__ __forceinline__ void load_to_lds_b128(__amdgpu_buffer_rsrc_t r, uint32_t lds_wave_base, int voff, int soff) {
+#if defined(__HIP_DEVICE_COMPILE__)
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (lds_ptr_t)(uintptr_t)lds_wave_base, 16, voff, soff, 0, 0);
+#else
+    (void)r; (void)lds_wave_base; (void)voff; (void)soff;
+#endif
+}
+
 template <int BITS>
-__device__ __forceinline__ void load_chunk(WChunk<BITS>& c, const uint8_t* tile, int lane) {
+__device__ __forceinline__ void load_chunk(WChunk<BITS>& c, __amdgpu_buffer_rsrc_t r, int voff, int soff) {
     if constexpr (BITS == 4) {
-        const uint4v v = *(const uint4v*)(tile + lane * 16);
+        const uint4v v = __builtin_amdgcn_raw_buffer_load_b128(r, voff, soff, 0);
         c.w[0] = v[0]; c.w[1] = v[1]; c.w[2] = v[2]; c.w[3] = v[3];
     } else if constexpr (BITS == 2) {
-        const uint2v v = *(const uint2v*)(tile + lane * 8);
+        const uint2v v = __builtin_amdgcn_raw_buffer_load_b64(r, voff, soff, 0);
         c.w[0] = v[0]; c.w[1] = v[1];
     } else if constexpr (BITS == 3) {
-        const uint32_t* p = (const uint32_t*)(tile + lane * 12);
-        c.w[0] = p[0]; c.w[1] = p[1]; c.w[2] = p[2];
+        const uint3v v = __builtin_amdgcn_raw_buffer_load_b96(r, voff, soff, 0);
+        c.w[0] = v[0]; c.w[1] = v[1]; c.w[2] = v[2];
     } else {
-        const uint4v v0 = *(const uint4v*)(tile + lane * 16);
-        const uint4v v1 = *(const uint4v*)(tile + 1024 + lane * 16);
+        const uint4v v0 = __builtin_amdgcn_raw_buffer_load_b128(r, voff, soff, 0);
+        const uint4v v1 = __builtin_amdgcn_raw_buffer_load_b128(r, voff + 1024, soff, 0);
         c.w[0] = v0[0]; c.w[1] = v0[1]; c.w[2] = v0[2]; c.w[3] = v0[3];
         c.w[4] = v1[0]; c.w[5] = v1[1]; c.w[6] = v1[2]; c.w[7] = v1[3];
     }
 }
 
-// Chunk of a k range that does not exist: every byte must widen to 0, i.e. hold `fill` = the flip mask.
-template <int BITS>
-__device__ __forceinline__ void zero_chunk(WChunk<BITS>& c, uint32_t fill) {
-#pragma unroll
-    for (int i = 0; i < WChunk<BITS>::WORDS; ++i) c.w[i] = fill;
-}
-
-// ---------------------------------------------------------------------------------------------
-// Activation tile: BM rows x 128 bytes, staged through registers into swizzled LDS.
-// ---------------------------------------------------------------------------------------------
-template <int BM>
-struct AStage {
-    static constexpr int LOADS = BM / 32;  // 16-byte loads per thread (256 threads)
-    uint4v v[LOADS];
-};
-
-// row_bytes: byte stride of a source row; col_byte: byte offset of this stage inside the row;
-// valid_bytes: bytes of the row that exist from col_byte on (pieces beyond are re-read from column 0:
-// their products meet zero weights).
-template <int BM>
-__device__ __forceinline__ void a_stage_load(AStage<BM>& st, const uint8_t* src, long row_bytes, int m0, int M,
-                                            long col_byte, long row_len_bytes) {
-    const int tid = threadIdx.x;
-#pragma unroll
-    for (int r = 0; r < AStage<BM>::LOADS; ++r) {
-        const int q = tid + 256 * r;
-        const int row = q >> 3, piece = q & 7;
-        int gr = m0 + row;
-        gr = gr < M ? gr : M - 1;
-        long cb = col_byte + piece * 16;
-        cb = cb < row_len_bytes ? cb : 0;
-        st.v[r] = *(const uint4v*)(src + (long)gr * row_bytes + cb);
-    }
-}
-
-template <int BM>
-__device__ __forceinline__ void a_stage_store(const AStage<BM>& st, uint8_t* lds) {
-    const int tid = threadIdx.x;
-#pragma unroll
-    for (int r = 0; r < AStage<BM>::LOADS; ++r) {
-        const int q = tid + 256 * r;
-        const int row = q >> 3, piece = q & 7;
-        *(uint4v*)(lds + row * 128 + ((piece ^ swz(row)) << 4)) = st.v[r];
-    }
-}
-
-// ---------------------------------------------------------------------------------------------
-// Weight-only GEMM
-// ---------------------------------------------------------------------------------------------
-template <int BITS, int WGM, int WGN, int TM, int TN>
-__global__ __launch_bounds__(256) void gemm_w_only_kernel(const _Float16* __restrict__ x, int M, int K, long ldx,
-                                                          const uint8_t* __restrict__ packed, int N,
-                                                          const float* __restrict__ w_scale,
-                                                          const int32_t* __restrict__ w_zp,
-                                                          const _Float16* __restrict__ bias,
-                                                          _Float16* __restrict__ y, long ldy, int tiles_n) {
-    static_assert(WGM * WGN == 4, "four waves per workgroup");
-    constexpr int BM = WGM * TM * 32, BN = WGN * TN * 32;
-    extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
-    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
-    const int wm = wv / WGN, wn = wv % WGN;
-    const int bn = blockIdx.x % tiles_n, bm = blockIdx.x / tiles_n;
-    const int m0 = bm * BM, n0 = bn * BN;
-    const int KC = K >> 6;
-    const int G = (N + 31) >> 5;
-    const int l31 = lane & 31, kb = lane >> 5;
-
-    // per-lane zero points of the TN weight fragments and their tile pointers
-    int zc[TN];
-    const uint8_t* wtile[TN];
-#pragma unroll
-    for (int tn = 0; tn < TN; ++tn) {
-        int g = (n0 >> 5) + wn * TN + tn;
-        g = g < G ? g : G - 1;
-        const int n = g * 32 + l31;
-        zc[tn] = w_zp[n < N ? n : N - 1];
-        wtile[tn] = packed + (size_t)g * KC * kl_tile_bytes(BITS);
-    }
-
-    float16v acc[TM][TN];
-#pragma unroll
-    for (int tm = 0; tm < TM; ++tm)
-#pragma unroll
-        for (int tn = 0; tn < TN; ++tn)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) acc[tm][tn][i] = 0.0f;
-
-    AStage<BM> ast;
-    WChunk<BITS> wcur[TN], wnxt[TN];
-    const uint8_t* xsrc = (const uint8_t*)x;
-    const long row_bytes = ldx * 2, row_len = (long)K * 2;
-
-    a_stage_load<BM>(ast, xsrc, row_bytes, m0, M, 0, row_len);
-#pragma unroll
-    for (int tn = 0; tn < TN; ++tn) load_chunk<BITS>(wcur[tn], wtile[tn], lane);
-    a_stage_store<BM>(ast, lds);
-    __syncthreads();
-
-    const int sw = swz(l31);
-    int cur = 0;
-    for (int kc = 0; kc < KC; ++kc) {
-        const bool more = kc + 1 < KC;
-        if (more) {
-            a_stage_load<BM>(ast, xsrc, row_bytes, m0, M, (long)(kc + 1) * 128, row_len);
-#pragma unroll
-            for (int tn = 0; tn < TN; ++tn)
-                load_chunk<BITS>(wnxt[tn], wtile[tn] + (size_t)(kc + 1) * kl_tile_bytes(BITS), lane);
-        }
-        const uint8_t* abuf = lds + cur * (BM * 128);
-#pragma unroll
-        for (int s = 0; s < 4; ++s) {
-            half8 wf[TN], xf[TM];
-#pragma unroll
-            for (int tn = 0; tn < TN; ++tn) wf[tn] = dequant_step<BITS>(wcur[tn], s, zc[tn]);
-#pragma unroll
-            for (int tm = 0; tm < TM; ++tm) {
-                const int row = (wm * TM + tm) * 32 + l31;
-                xf[tm] = *(const half8*)(abuf + row * 128 + (((kb * 4 + s) ^ sw) << 4));
-            }
-#pragma unroll
-            for (int tm = 0; tm < TM; ++tm)
-#pragma unroll
-                for (int tn = 0; tn < TN; ++tn)
-                    acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_f16(wf[tn], xf[tm], acc[tm][tn], 0, 0, 0);
-        }
-        if (more) a_stage_store<BM>(ast, lds + (cur ^ 1) * (BM * 128));
-        __syncthreads();
-        if (more) {
-#pragma unroll
-            for (int tn = 0; tn < TN; ++tn) wcur[tn] = wnxt[tn];
-        }
-        cur ^= 1;
-    }
-
-    // epilogue: result element v of a lane is channel 8*(v/4) + 4*kb + v%4 of the tile, row l31
-#pragma unroll
-    for (int tn = 0; tn < TN; ++tn) {
-        const int nb = n0 + (wn * TN + tn) * 32;
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const int n = nb + 8 * q + 4 * kb;
-            if (n >= N) continue;
-            const float4v sc = *(const float4v*)(w_scale + n);
-            float4v bs = {0.f, 0.f, 0.f, 0.f};
-            if (bias) {
-                const half4 b = *(const half4*)(bias + n);
-                bs = float4v{(float)b[0], (float)b[1], (float)b[2], (float)b[3]};
-            }
-#pragma unroll
-            for (int tm = 0; tm < TM; ++tm) {
-                const int m = m0 + (wm * TM + tm) * 32 + l31;
-                if (m >= M) continue;
-                half4 o;
-#pragma unroll
-                for (int r = 0; r < 4; ++r) o[r] = (_Float16)(acc[tm][tn][4 * q + r] * sc[r] + bs[r]);
-                *(half4*)(y + (long)m * ldy + n) = o;
-            }
-        }
-    }
-}
-
-// ---------------------------------------------------------------------------------------------
-// 8-bit-activation GEMM.  A stage is 128 k (128 bytes of int8 per row) = two 64-k weight tiles.
-// ---------------------------------------------------------------------------------------------
 // xflip = 0x80808080 turns unsigned 8-bit codes q into the signed bytes q - 128 (0 for signed codes).
 template <int WBITS>
 __device__ __forceinline__ int4v widen_step(const WChunk<WBITS>& c, int s /*0..1 inside the 64-k tile*/,
@@ -341,39 +202,102 @@ __device__ __forceinline__ int4v widen_step(const WChunk<WBITS>& c, int s /*0..1
     }
 }
 
-template <int WBITS, int WGM, int WGN, int TM, int TN>
-__global__ __launch_bounds__(256) void gemm_a8_kernel(const int8_t* __restrict__ a8,
-                                                      const int32_t* __restrict__ rowsum,
-                                                      const ActParams* __restrict__ params, int M, int K,
-                                                      const uint8_t* __restrict__ packed, int N, int w_off,
-                                                      const float* __restrict__ w_scale,
-                                                      const int32_t* __restrict__ w_zp,
-                                                      const int32_t* __restrict__ w_colsum,
-                                                      const _Float16* __restrict__ bias, _Float16* __restrict__ y,
-                                                      long ldy, RowMap out_map, int32_t* __restrict__ acc_debug,
-                                                      int tiles_n) {
-    static_assert(WGM * WGN == 4, "four waves per workgroup");
+// ---------------------------------------------------------------------------------------------
+// The GEMM kernel.  I8 == false: weight-only, fp16 activations straight from X, 64 k per stage.
+//                   I8 == true : int8 activation copy (row stride Kp = K rounded up to 128, padding zero),
+//                                128 k per stage = two 64-k weight tiles.
+// A stage of the activation operand is BM rows x 128 bytes.  It is brought in by buffer loads that write LDS
+// directly (each lane 16 bytes, a wave instruction fills 8 rows), XOR-swizzled on the global side so that the
+// later ds_read_b128 of 32 consecutive rows is conflict free.  Two LDS stages; the loads of stage k+1 are in
+// flight while stage k is multiplied.
+// ---------------------------------------------------------------------------------------------
+struct GemmArgs {
+    const void* a;        // X fp16 [M, lda] or int8 copy [M, Kp]
+    long a_row_bytes;     // byte stride between rows of a
+    uint32_t a_bytes;     // valid extent of a in bytes
+    const uint8_t* packed;
+    uint32_t packed_bytes;
+    int M, N, K;          // K: true reduction length
+    int k_stages;         // number of 128-byte stages
+    const float* w_scale;
+    const int32_t* w_zp;
+    const _Float16* bias;
+    _Float16* y;
+    long ldy;
+    int tiles_m, tiles_n;
+    // int8 only
+    const int32_t* rowsum;
+    const ActParams* params;
+    const int32_t* w_colsum;
+    int w_off;
+    RowMap out_map;
+    int32_t* acc_debug;
+};
+
+// Workgroup id -> tile.  Consecutive workgroup ids land on different XCDs (8 of them, each with its own L2),
+// so the ids an XCD receives are mapped onto a contiguous run of tiles that walks N inside one row block:
+// the activation rows of a block stay in that XCD's L2 while all their column tiles are produced.
+__device__ __forceinline__ void tile_of_block(int bid, int tiles_m, int tiles_n, int& bm, int& bn) {
+    const int total = tiles_m * tiles_n;
+    const int per = total >> 3;  // tiles of the leftover (total % 8) keep their own index
+    const int t = bid < (per << 3) ? (bid & 7) * per + (bid >> 3) : bid;
+    bm = t / tiles_n;
+    bn = t - bm * tiles_n;
+}
+
+template <bool I8, int BITS, int WGM, int WGN, int TM, int TN>
+__global__ __launch_bounds__(WGM* WGN * 64, (TM * TN <= 8 ? 2 : 1)) void gemm_kernel(const GemmArgs g) {
+    constexpr int NW = WGM * WGN, NT = NW * 64;
     constexpr int BM = WGM * TM * 32, BN = WGN * TN * 32;
+    constexpr int STAGE_BYTES = BM * 128;
+    constexpr int DMA = BM / (8 * NW);  // LDS-writing loads per wave per stage
+    constexpr int CH = I8 ? 2 : 1;      // 64-k weight tiles per stage
+    static_assert(BM % (8 * NW) == 0, "tile rows must split over the waves");
+    using acc_t = typename std::conditional<I8, int16v, float16v>::type;
+    using frag_t = typename std::conditional<I8, int4v, half8>::type;
+
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
     const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
     const int wm = wv / WGN, wn = wv % WGN;
-    const int bn = blockIdx.x % tiles_n, bm = blockIdx.x / tiles_n;
+    int bm, bn;
+    tile_of_block(blockIdx.x, g.tiles_m, g.tiles_n, bm, bn);
     const int m0 = bm * BM, n0 = bn * BN;
-    const int KC = K >> 6;
-    const int KT = (KC + 1) >> 1;
-    const int G = (N + 31) >> 5;
+    const int KC = g.K >> 6;
+    const int G = (g.N + 31) >> 5;
     const int l31 = lane & 31, kb = lane >> 5;
-    const uint32_t xflip = w_off ? 0x80808080u : 0u;
+    const uint32_t xflip = (I8 && g.w_off) ? 0x80808080u : 0u;
+    constexpr int TILE_B = 256 * BITS;
 
-    const uint8_t* wtile[TN];
+    const __amdgpu_buffer_rsrc_t ra = make_rsrc(g.a, g.a_bytes);
+    const __amdgpu_buffer_rsrc_t rb = make_rsrc(g.packed, g.packed_bytes);
+
+    // activation loads: lane -> (row, physical slot) of an 8-row group; it fetches the logical piece slot ^ swz(row)
+    int a_voff[DMA];
+    uint32_t a_lds[DMA];
+#pragma unroll
+    for (int i = 0; i < DMA; ++i) {
+        const int row0 = (i * NW + wv) * 8;
+        const int row = row0 + (lane >> 3);
+        const int piece = (lane & 7) ^ swz(row);
+        a_voff[i] = (int)((long)(m0 + row) * g.a_row_bytes + piece * 16);
+        // rows past M must read as zero: push them past the end of the buffer
+        if (m0 + row >= g.M) a_voff[i] = (int)0x7FFFFFF0;
+        a_lds[i] = (uint32_t)(row0 * 128);
+    }
+    const uint32_t lds_base = (uint32_t)(uintptr_t)lds;
+
+    // weight loads: one lane chunk per fragment and 64-k tile
+    int b_voff[TN], zc[TN];
 #pragma unroll
     for (int tn = 0; tn < TN; ++tn) {
-        int g = (n0 >> 5) + wn * TN + tn;
-        g = g < G ? g : G - 1;
-        wtile[tn] = packed + (size_t)g * KC * kl_tile_bytes(WBITS);
+        int gi = (n0 >> 5) + wn * TN + tn;
+        gi = gi < G ? gi : G - 1;
+        b_voff[tn] = gi * KC * TILE_B + lane * (BITS == 8 ? 16 : 4 * BITS);
+        const int n = gi * 32 + l31;
+        zc[tn] = I8 ? 0 : g.w_zp[n < g.N ? n : g.N - 1];
     }
 
-    int16v acc[TM][TN];
+    acc_t acc[TM][TN];
 #pragma unroll
     for (int tm = 0; tm < TM; ++tm)
 #pragma unroll
@@ -381,156 +305,187 @@ __global__ __launch_bounds__(256) void gemm_a8_kernel(const int8_t* __restrict__
 #pragma unroll
             for (int i = 0; i < 16; ++i) acc[tm][tn][i] = 0;
 
-    AStage<BM> ast;
-    WChunk<WBITS> wcur[TN][2], wnxt[TN][2];
-    const uint8_t* asrc = (const uint8_t*)a8;
+    WChunk<BITS> wcur[TN][CH], wnxt[TN][CH];
 
-    auto load_w = [&](WChunk<WBITS>(&dst)[TN][2], int kt) {
+    auto issue = [&](int stage, int buf, WChunk<BITS>(&w)[TN][CH]) {
+        // the k advance is wave-uniform: keep it in a scalar register
+        const int soff = __builtin_amdgcn_readfirstlane(stage * 128);
+#pragma unroll
+        for (int i = 0; i < DMA; ++i)
+            load_to_lds_b128(ra, lds_base + buf * STAGE_BYTES + a_lds[i], a_voff[i], soff);
+        const int soff_b = __builtin_amdgcn_readfirstlane(stage * CH * TILE_B);
 #pragma unroll
         for (int tn = 0; tn < TN; ++tn)
 #pragma unroll
-            for (int cc = 0; cc < 2; ++cc) {
-                const int ch = 2 * kt + cc;
-                if (ch < KC)
-                    load_chunk<WBITS>(dst[tn][cc], wtile[tn] + (size_t)ch * kl_tile_bytes(WBITS), lane);
-                else
-                    zero_chunk<WBITS>(dst[tn][cc], xflip);
-            }
+            for (int cc = 0; cc < CH; ++cc) load_chunk<BITS>(w[tn][cc], rb, b_voff[tn] + cc * TILE_B, soff_b);
     };
 
-    a_stage_load<BM>(ast, asrc, (long)K, m0, M, 0, (long)K);
-    load_w(wcur, 0);
-    a_stage_store<BM>(ast, lds);
-    __syncthreads();
-
+    // LDS read offsets of this lane: row l31 of the wave's first tile, one register per MFMA step
     const int sw = swz(l31);
-    int cur = 0;
+    uint32_t rd[4];
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+        const int piece = I8 ? ((s >> 1) * 4 + kb * 2 + (s & 1)) : (kb * 4 + s);
+        rd[s] = (uint32_t)(wm * TM * 32 * 128 + l31 * 128 + ((piece ^ sw) << 4));
+    }
+
+    const int KT = g.k_stages;
+    issue(0, 0, wcur);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    int buf = 0;
     for (int kt = 0; kt < KT; ++kt) {
-        const bool more = kt + 1 < KT;
-        if (more) {
-            a_stage_load<BM>(ast, asrc, (long)K, m0, M, (long)(kt + 1) * 128, (long)K);
-            load_w(wnxt, kt + 1);
-        }
-        const uint8_t* abuf = lds + cur * (BM * 128);
+        if (kt + 1 < KT) issue(kt + 1, buf ^ 1, wnxt);
+        const uint8_t* abuf = lds + buf * STAGE_BYTES;
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
-            const int cc = s >> 1, sp = s & 1;
-            int4v wf[TN], xf[TM];
+            frag_t wf[TN], xf[TM];
 #pragma unroll
-            for (int tn = 0; tn < TN; ++tn) wf[tn] = widen_step<WBITS>(wcur[tn][cc], sp, xflip);
+            for (int tm = 0; tm < TM; ++tm) xf[tm] = *(const frag_t*)(abuf + rd[s] + tm * 32 * 128);
 #pragma unroll
-            for (int tm = 0; tm < TM; ++tm) {
-                const int row = (wm * TM + tm) * 32 + l31;
-                xf[tm] = *(const int4v*)(abuf + row * 128 + (((cc * 4 + kb * 2 + sp) ^ sw) << 4));
+            for (int tn = 0; tn < TN; ++tn) {
+                if constexpr (I8)
+                    wf[tn] = widen_step<BITS>(wcur[tn][s >> 1], s & 1, xflip);
+                else
+                    wf[tn] = dequant_step<BITS>(wcur[tn][0], s, zc[tn]);
             }
 #pragma unroll
             for (int tm = 0; tm < TM; ++tm)
 #pragma unroll
-                for (int tn = 0; tn < TN; ++tn)
-                    acc[tm][tn] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wf[tn], xf[tm], acc[tm][tn], 0, 0, 0);
+                for (int tn = 0; tn < TN; ++tn) {
+                    if constexpr (I8)
+                        acc[tm][tn] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wf[tn], xf[tm], acc[tm][tn], 0, 0, 0);
+                    else
+                        acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_f16(wf[tn], xf[tm], acc[tm][tn], 0, 0, 0);
+                }
         }
-        if (more) a_stage_store<BM>(ast, lds + (cur ^ 1) * (BM * 128));
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
-        if (more) {
 #pragma unroll
-            for (int tn = 0; tn < TN; ++tn) {
-                wcur[tn][0] = wnxt[tn][0];
-                wcur[tn][1] = wnxt[tn][1];
-            }
-        }
-        cur ^= 1;
+        for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+            for (int cc = 0; cc < CH; ++cc) wcur[tn][cc] = wnxt[tn][cc];
+        buf ^= 1;
     }
 
-    // epilogue.  Stored operands are a' = qx - 128 and b' = qw - w_off, so with dx = 128 - z_x and
-    // dw[n] = w_off - z_w[n]:   ACC = raw + dw[n] * rowsum_a'[m] + dx * (colsum_b'[n] + K * dw[n]),
-    // colsum_b'[n] = colsum_code[n] - K * w_off.  Wrap-around int32 arithmetic is exact because ACC fits.
-    const float sx = params->scale;
-    const int dx = 128 - params->zp;
-    int ra[TM];
+    // ---------------------------------------------------------------- epilogue
+    // Result element v of a lane is channel 8*(v/4) + 4*kb + v%4 of its 32-channel tile, activation row l31:
+    // four consecutive channels of ONE row per lane, so a direct store would scatter 8-byte pieces over 32 rows.
+    // Instead every wave transposes through its own slice of the (now idle) LDS stages, 32 rows at a time:
+    // finished fp16 values are written as 8-byte pieces into a [32 rows][TN*32 channels] image (16-byte chunks
+    // XOR-swizzled by row), read back as 16 bytes per lane along rows, and stored with 16 lanes covering one
+    // contiguous row segment of TN*64 bytes.
+    constexpr int CPR = TN * 4;                 // 16-byte chunks per staged row
+    constexpr int ROWS_PER_PASS = 64 / CPR;     // rows one store instruction covers
+    static_assert(64 % CPR == 0, "TN must be 1, 2 or 4");
+    constexpr int EP_BYTES = 32 * CPR * 16;     // staging bytes per wave
+    static_assert(NW * EP_BYTES <= 2 * STAGE_BYTES, "epilogue staging must fit the LDS stages");
+    uint8_t* ep = lds + wv * EP_BYTES;
+
+    float sx = 1.0f;
+    int dx = 0;
+    if constexpr (I8) {
+        sx = g.params->scale;
+        dx = 128 - g.params->zp;
+    }
+    const int nw0 = n0 + wn * TN * 32;  // first channel of this wave
 #pragma unroll
     for (int tm = 0; tm < TM; ++tm) {
-        const int m = m0 + (wm * TM + tm) * 32 + l31;
-        ra[tm] = rowsum[m < M ? m : M - 1];
-    }
+        const int mt0 = m0 + (wm * TM + tm) * 32;  // first row of this 32-row slab
+        int rsum = 0;
+        if constexpr (I8) {
+            const int m = mt0 + l31;
+            rsum = g.rowsum[m < g.M ? m : g.M - 1];
+        }
 #pragma unroll
-    for (int tn = 0; tn < TN; ++tn) {
-        const int nb = n0 + (wn * TN + tn) * 32;
+        for (int tn = 0; tn < TN; ++tn)
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const int n = nb + 8 * q + 4 * kb;
-            if (n >= N) continue;
-            const float4v sc = *(const float4v*)(w_scale + n);
-            const int4v zw = *(const int4v*)(w_zp + n);
-            const int4v cs = *(const int4v*)(w_colsum + n);
-            float4v bs = {0.f, 0.f, 0.f, 0.f};
-            if (bias) {
-                const half4 b = *(const half4*)(bias + n);
-                bs = float4v{(float)b[0], (float)b[1], (float)b[2], (float)b[3]};
-            }
-            int dw[4], cn[4];
-            float sf[4];
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                dw[r] = w_off - zw[r];
-                cn[r] = dx * (cs[r] - K * w_off + K * dw[r]);
-                sf[r] = sx * sc[r];
-            }
-#pragma unroll
-            for (int tm = 0; tm < TM; ++tm) {
-                const int m = m0 + (wm * TM + tm) * 32 + l31;
-                if (m >= M) continue;
-                int4v a;
+            for (int q = 0; q < 4; ++q) {
+                // channels n .. n+3 of this lane (clamped lanes are never stored)
+                const int n_real = nw0 + tn * 32 + 8 * q + 4 * kb;
+                const int n = n_real < g.N ? n_real : g.N - 4;
+                const float4v s4 = *(const float4v*)(g.w_scale + n);
+                half4 b4 = {(_Float16)0, (_Float16)0, (_Float16)0, (_Float16)0};
+                if (g.bias) b4 = *(const half4*)(g.bias + n);
                 half4 o;
+                if constexpr (I8) {
+                    // stored operands are a' = qx - 128 and b' = qw - w_off; with dx = 128 - z_x, dw = w_off - z_w[n]:
+                    //   ACC = raw + dw * rowsum_a'[m] + dx * (colsum_b'[n] + K * dw),  colsum_b' = colsum - K * w_off.
+                    // Wrap-around int32 arithmetic is exact because ACC itself fits.
+                    const int4v zw = *(const int4v*)(g.w_zp + n);
+                    const int4v cs = *(const int4v*)(g.w_colsum + n);
+                    int4v a;
 #pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    a[r] = acc[tm][tn][4 * q + r] + dw[r] * ra[tm] + cn[r];
-                    o[r] = (_Float16)((float)a[r] * sf[r] + bs[r]);
+                    for (int r = 0; r < 4; ++r) {
+                        const int dw = g.w_off - zw[r];
+                        a[r] = acc[tm][tn][4 * q + r] + dw * rsum + dx * (cs[r] - g.K * g.w_off + g.K * dw);
+                        o[r] = (_Float16)((float)a[r] * (sx * s4[r]) + (float)b4[r]);
+                    }
+                    if (g.acc_debug) {
+                        const int m = mt0 + l31;
+                        if (m < g.M && n_real < g.N) *(int4v*)(g.acc_debug + (long)m * g.N + n_real) = a;
+                    }
+                } else {
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) o[r] = (_Float16)(acc[tm][tn][4 * q + r] * s4[r] + (float)b4[r]);
                 }
-                const long yr = out_map.phys(m);
-                *(half4*)(y + yr * ldy + n) = o;
-                if (acc_debug) *(int4v*)(acc_debug + (long)m * N + n) = a;
+                const int chunk = tn * 4 + q;
+                *(half4*)(ep + l31 * (CPR * 16) + (((chunk ^ l31) & (CPR - 1)) << 4) + kb * 8) = o;
+            }
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int i = 0; i < 32 / ROWS_PER_PASS; ++i) {
+            const int row = i * ROWS_PER_PASS + lane / CPR, c = lane % CPR;
+            const uint4v v = *(const uint4v*)(ep + row * (CPR * 16) + (((c ^ row) & (CPR - 1)) << 4));
+            const int m = mt0 + row, n = nw0 + c * 8;
+            if (m < g.M && n < g.N) {
+                long yr = m;
+                if constexpr (I8) yr = g.out_map.phys(m);
+                *(uint4v*)(g.y + yr * g.ldy + n) = v;
             }
         }
+        __builtin_amdgcn_wave_barrier();
     }
 }
 
 // ---------------------------------------------------------------------------------------------
 // Launchers
 // ---------------------------------------------------------------------------------------------
-template <int BITS, int WGM, int WGN, int TM, int TN>
-static int run_w_only(const void* x, int M, int K, int ldx, const void* packed, int N, const float* w_scale,
-                      const int32_t* w_zp, const void* bias, void* y, int ldy, hipStream_t st) {
-    constexpr int BM = WGM * TM * 32, BN = WGN * TN * 32;
-    const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
-    auto kern = gemm_w_only_kernel<BITS, WGM, WGN, TM, TN>;
-    // algorithmic traffic: X read once, packed W, scale + zp + bias, Y written once
-    ProfScope prof(st, prof_gemm_slot(0, BITS, TM == 4 ? 0 : TM == 2 ? 1 : 2), 2.0 * M * N * K,
-                   2.0 * M * K + (double)N * K * BITS / 8 + 10.0 * N + 2.0 * M * N);
-    hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n), dim3(256), 2 * BM * 128, st, (const _Float16*)x, M, K, (long)ldx,
-                       (const uint8_t*)packed, N, w_scale, w_zp, (const _Float16*)bias, (_Float16*)y, (long)ldy,
-                       tiles_n);
-    MQ_HIP_CHECK_LAUNCH();
-    return MQ_OK;
-}
-
-// Tile choice: the largest tile that still gives every compute unit about two workgroups.
+// Tile table.  index -> (WGM, WGN, TM, TN): 0: 128x256 (2x2 waves of 64x128), 1: 128x128 (2x2 of 64x64),
+// 2: 64x64 (2x2 of 32x32).
 static int g_force_tile = -1;
 void set_force_tile(int t) { g_force_tile = t; }
 
 static int pick_tile(int M, int N) {
     if (g_force_tile >= 0 && g_force_tile <= 2) return g_force_tile;
-    const long t128 = (long)((M + 127) / 128) * ((N + 127) / 128);
-    if (t128 >= 256) return 1;
+    const long t0 = (long)((M + 127) / 128) * ((N + 255) / 256);
+    if (t0 >= 512) return 0;
+    const long t1 = (long)((M + 127) / 128) * ((N + 127) / 128);
+    if (t1 >= 256) return 1;
     return 2;
 }
 
-template <int BITS>
-static int dispatch_w_only(const void* x, int M, int K, int ldx, const void* packed, int N, const float* w_scale,
-                           const int32_t* w_zp, const void* bias, void* y, int ldy, hipStream_t st) {
-    switch (pick_tile(M, N)) {
-        case 0: return run_w_only<BITS, 2, 2, 4, 4>(x, M, K, ldx, packed, N, w_scale, w_zp, bias, y, ldy, st);
-        case 1: return run_w_only<BITS, 2, 2, 2, 2>(x, M, K, ldx, packed, N, w_scale, w_zp, bias, y, ldy, st);
-        default: return run_w_only<BITS, 2, 2, 1, 1>(x, M, K, ldx, packed, N, w_scale, w_zp, bias, y, ldy, st);
+template <bool I8, int BITS, int WGM, int WGN, int TM, int TN>
+static int run_gemm(GemmArgs& g, int tile_index, hipStream_t st) {
+    constexpr int BM = WGM * TM * 32, BN = WGN * TN * 32;
+    g.tiles_m = (g.M + BM - 1) / BM;
+    g.tiles_n = (g.N + BN - 1) / BN;
+    auto kern = gemm_kernel<I8, BITS, WGM, WGN, TM, TN>;
+    const double abytes = I8 ? 1.0 * g.M * g.K + 4.0 * g.M : 2.0 * g.M * g.K;
+    ProfScope prof(st, prof_gemm_slot(I8 ? 1 : 0, BITS, tile_index), 2.0 * g.M * g.N * g.K,
+                   abytes + (double)g.N * g.K * BITS / 8 + (I8 ? 14.0 : 10.0) * g.N + 2.0 * g.M * g.N);
+    hipLaunchKernelGGL(kern, dim3(g.tiles_m * g.tiles_n), dim3(WGM * WGN * 64), 2 * BM * 128, st, g);
+    MQ_HIP_CHECK_LAUNCH();
+    return MQ_OK;
+}
+
+template <bool I8, int BITS>
+static int dispatch_gemm(GemmArgs& g, hipStream_t st) {
+    const int t = pick_tile(g.M, g.N);
+    switch (t) {
+        case 0: return run_gemm<I8, BITS, 2, 2, 2, 4>(g, 0, st);
+        case 1: return run_gemm<I8, BITS, 2, 2, 2, 2>(g, 1, st);
+        default: return run_gemm<I8, BITS, 2, 2, 1, 1>(g, 2, st);
     }
 }
 
@@ -538,62 +493,51 @@ int launch_gemm_w_only(const void* x, int M, int K, int ldx, const void* packed,
                        const float* w_scale, const int32_t* w_zp, const void* bias, void* y, int ldy, int dtype,
                        hipStream_t st) {
     (void)dtype;
+    GemmArgs g{};
+    g.a = x;
+    g.a_row_bytes = (long)ldx * 2;
+    g.a_bytes = (uint32_t)(((long)(M - 1) * ldx + K) * 2);
+    g.packed = (const uint8_t*)packed;
+    g.packed_bytes = (uint32_t)((long)((N + 31) / 32) * (K / 64) * 256 * bits);
+    g.M = M; g.N = N; g.K = K;
+    g.k_stages = K / 64;
+    g.w_scale = w_scale; g.w_zp = w_zp; g.bias = (const _Float16*)bias;
+    g.y = (_Float16*)y; g.ldy = ldy;
     switch (bits) {
-        case 2: return dispatch_w_only<2>(x, M, K, ldx, packed, N, w_scale, w_zp, bias, y, ldy, st);
-        case 3: return dispatch_w_only<3>(x, M, K, ldx, packed, N, w_scale, w_zp, bias, y, ldy, st);
-        case 4: return dispatch_w_only<4>(x, M, K, ldx, packed, N, w_scale, w_zp, bias, y, ldy, st);
-        case 8: return dispatch_w_only<8>(x, M, K, ldx, packed, N, w_scale, w_zp, bias, y, ldy, st);
+        case 2: return dispatch_gemm<false, 2>(g, st);
+        case 3: return dispatch_gemm<false, 3>(g, st);
+        case 4: return dispatch_gemm<false, 4>(g, st);
+        case 8: return dispatch_gemm<false, 8>(g, st);
     }
     return MQ_ERR_UNSUPPORTED_BITS;
-}
-
-template <int WBITS, int WGM, int WGN, int TM, int TN>
-static int run_a8(const int8_t* a8, const int32_t* rowsum, const ActParams* params, int M, int K, const void* packed,
-                  int N, int w_off, const float* w_scale, const int32_t* w_zp, const int32_t* w_colsum,
-                  const void* bias, void* y, int ldy, RowMap out_map, int32_t* acc_debug, hipStream_t st) {
-    constexpr int BM = WGM * TM * 32, BN = WGN * TN * 32;
-    const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
-    auto kern = gemm_a8_kernel<WBITS, WGM, WGN, TM, TN>;
-    // algorithmic traffic of the integer GEMM itself: int8 activations, packed W, per-channel vectors, Y
-    ProfScope prof(st, prof_gemm_slot(1, WBITS, TM == 4 ? 0 : TM == 2 ? 1 : 2), 2.0 * M * N * K,
-                   1.0 * M * K + 4.0 * M + (double)N * K * WBITS / 8 + 14.0 * N + 2.0 * M * N);
-    hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n), dim3(256), 2 * BM * 128, st, a8, rowsum, params, M, K,
-                       (const uint8_t*)packed, N, w_off, w_scale, w_zp, w_colsum, (const _Float16*)bias, (_Float16*)y,
-                       (long)ldy, out_map, acc_debug, tiles_n);
-    MQ_HIP_CHECK_LAUNCH();
-    return MQ_OK;
-}
-
-template <int WBITS>
-static int dispatch_a8(const int8_t* a8, const int32_t* rowsum, const ActParams* params, int M, int K,
-                       const void* packed, int N, int w_off, const float* w_scale, const int32_t* w_zp,
-                       const int32_t* w_colsum, const void* bias, void* y, int ldy, RowMap out_map,
-                       int32_t* acc_debug, hipStream_t st) {
-    switch (pick_tile(M, N)) {
-        case 0:
-            return run_a8<WBITS, 2, 2, 4, 4>(a8, rowsum, params, M, K, packed, N, w_off, w_scale, w_zp, w_colsum, bias,
-                                            y, ldy, out_map, acc_debug, st);
-        case 1:
-            return run_a8<WBITS, 2, 2, 2, 2>(a8, rowsum, params, M, K, packed, N, w_off, w_scale, w_zp, w_colsum, bias,
-                                            y, ldy, out_map, acc_debug, st);
-        default:
-            return run_a8<WBITS, 2, 2, 1, 1>(a8, rowsum, params, M, K, packed, N, w_off, w_scale, w_zp, w_colsum, bias,
-                                            y, ldy, out_map, acc_debug, st);
-    }
 }
 
 int launch_gemm_a8(const int8_t* a8, const int32_t* rowsum, const ActParams* params, int M, int K,
                    const void* packed, int N, int w_bits, int w_signed, const float* w_scale, const int32_t* w_zp,
                    const int32_t* w_colsum, const void* bias, void* y, int ldy, RowMap out_map, int32_t* acc_debug,
                    hipStream_t st) {
-    if (w_bits == 4)
-        return dispatch_a8<4>(a8, rowsum, params, M, K, packed, N, 0, w_scale, w_zp, w_colsum, bias, y, ldy, out_map,
-                              acc_debug, st);
+    const int Kp = (K + 127) / 128 * 128;
+    GemmArgs g{};
+    g.a = a8;
+    g.a_row_bytes = Kp;
+    g.a_bytes = (uint32_t)((long)M * Kp);
+    g.packed = (const uint8_t*)packed;
+    g.packed_bytes = (uint32_t)((long)((N + 31) / 32) * (K / 64) * 256 * w_bits);
+    g.M = M; g.N = N; g.K = K;
+    g.k_stages = Kp / 128;
+    g.w_scale = w_scale; g.w_zp = w_zp; g.bias = (const _Float16*)bias;
+    g.y = (_Float16*)y; g.ldy = ldy;
+    g.rowsum = rowsum; g.params = params; g.w_colsum = w_colsum;
+    g.out_map = out_map; g.acc_debug = acc_debug;
+    if (w_bits == 4) {
+        g.w_off = 0;
+        return dispatch_gemm<true, 4>(g, st);
+    }
     if (w_bits == 8) {
         // Unsigned 8-bit codes do not fit a signed MFMA operand: the kernel flips their top bit in registers,
         // which reads them as q - 128 (w_off = 128); signed (symmetric) codes are used as they are.
-        return dispatch_a8<8>(a8, rowsum, params, M, K, packed, N, w_signed ? 0 : 128, w_scale, w_zp, w_colsum, bias,
-                              y, ldy, out_map, acc_debug, st);
+        g.w_off = w_signed ? 0 : 128;
+        return dispatch_gemm<true, 8>(g, st);
     }
     return MQ_ERR_UNSUPPORTED_BITS;
 }

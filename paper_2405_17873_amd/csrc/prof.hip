@@ -25,7 +25,7 @@ std::vector<Slot> g_slots;
 std::vector<Pair> g_free;
 
 const int kBits[4] = {2, 3, 4, 8};
-const int kTile[3][2] = {{4, 4}, {2, 2}, {1, 1}};
+const char* kTile[3] = {"2, 2, 2, 4", "2, 2, 2, 2", "2, 2, 1, 1"};
 
 void init_slots() {
     if (!g_slots.empty()) return;
@@ -34,8 +34,7 @@ void init_slots() {
         for (int b = 0; b < 4; ++b)
             for (int t = 0; t < 3; ++t) {
                 char buf[96];
-                snprintf(buf, sizeof buf, "mq::%s<%d, 2, 2, %d, %d>", fam ? "gemm_a8_kernel" : "gemm_w_only_kernel",
-                         kBits[b], kTile[t][0], kTile[t][1]);
+                snprintf(buf, sizeof buf, "mq::gemm_kernel<%s, %d, %s>", fam ? "true" : "false", kBits[b], kTile[t]);
                 g_slots[prof_gemm_slot(fam, kBits[b], t)].name = buf;
             }
     g_slots[PROF_ACT_MINMAX].name = "mq::act_minmax_kernel";
