@@ -64,6 +64,12 @@ int mq_prof_read(int slot, char* name_host, int name_cap, long long* launches_ho
                  double* ops_host, double* bytes_host);
 int mq_prof_reset(void);
 
+/* Phase timing inside the GEMM kernels: while clk != NULL every GEMM launch with at most `workgroups` workgroups
+ * writes four shader-clock samples per workgroup (start, main loop entered, epilogue entered, end) to
+ * clk[4*workgroup .. 4*workgroup+3] (device memory, caller owned).  Clocks of different XCDs are not comparable;
+ * differences inside one workgroup are.  Pass NULL to switch it off. */
+void mq_prof_phase_buffer(long long* clk, long workgroups);
+
 /* ------------------------------------------------------------------------------------------------
  * Offline preparation
  * ---------------------------------------------------------------------------------------------- */

@@ -21,7 +21,7 @@ _ERRORS = {
 }
 
 EXPORTS = ("mq_version", "mq_last_hip_error", "mq_tune_force_tile", "mq_prof_enable", "mq_prof_num_slots", "mq_prof_read",
-           "mq_prof_reset", "mq_quantize_weights", "mq_packed_bytes", "mq_pack_weights",
+           "mq_prof_reset", "mq_prof_phase_buffer", "mq_quantize_weights", "mq_packed_bytes", "mq_pack_weights",
            "mq_unpack_weights", "mq_qlinear_w_only", "mq_qlinear_a8_workspace_bytes", "mq_qlinear_w8a8",
            "mq_qlinear_w4a8", "mq_bos_aware_kv_proj_workspace_bytes", "mq_bos_aware_kv_proj")
 
@@ -57,6 +57,11 @@ def version() -> int:
 
 def tune_force_tile(tile: int) -> None:
     load().mq_tune_force_tile(int(tile))
+
+
+def prof_phase_buffer(buf: Optional[torch.Tensor]) -> None:
+    """buf: int64 device tensor with 4 entries per workgroup, or None to switch phase timing off."""
+    load().mq_prof_phase_buffer(_ptr(buf), C.c_long(0 if buf is None else buf.numel() // 4))
 
 
 def prof_enable(on: bool) -> None:

@@ -230,6 +230,7 @@ struct GemmArgs {
     const ActParams* params;
     const int32_t* w_colsum;
     int w_off;
+    long long* phase_clk;  // optional: 4 shader-clock samples per workgroup (start, loop, epilogue, end)
     RowMap out_map;
     int32_t* acc_debug;
 };
@@ -329,10 +330,13 @@ __global__ __launch_bounds__(WGM* WGN * 64, (TM * TN <= 8 ? 2 : 1)) void gemm_ke
         rd[s] = (uint32_t)(wm * TM * 32 * 128 + l31 * 128 + ((piece ^ sw) << 4));
     }
 
+    long long t0 = 0, t1 = 0, t2 = 0;
+    if (g.phase_clk) t0 = clock64();
     const int KT = g.k_stages;
     issue(0, 0, wcur);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
+    if (g.phase_clk) t1 = clock64();
     int buf = 0;
     for (int kt = 0; kt < KT; ++kt) {
         if (kt + 1 < KT) issue(kt + 1, buf ^ 1, wnxt);
@@ -368,6 +372,7 @@ __global__ __launch_bounds__(WGM* WGN * 64, (TM * TN <= 8 ? 2 : 1)) void gemm_ke
         buf ^= 1;
     }
 
+    if (g.phase_clk) t2 = clock64();
     // ---------------------------------------------------------------- epilogue
     // Result element v of a lane is channel 8*(v/4) + 4*kb + v%4 of its 32-channel tile, activation row l31:
     // four consecutive channels of ONE row per lane, so a direct store would scatter 8-byte pieces over 32 rows.
@@ -382,12 +387,33 @@ __global__ __launch_bounds__(WGM* WGN * 64, (TM * TN <= 8 ? 2 : 1)) void gemm_ke
     static_assert(NW * EP_BYTES <= 2 * STAGE_BYTES, "epilogue staging must fit the LDS stages");
     uint8_t* ep = lds + wv * EP_BYTES;
 
-    float sx = 1.0f;
-    int dx = 0;
-    if constexpr (I8) {
-        sx = g.params->scale;
-        dx = 128 - g.params->zp;
+    // Per-channel epilogue constants of the workgroup's BN channels, computed once by BN threads and parked in
+    // LDS behind the stages: multiplier, additive term and (int8) the two zero-point corrections.
+    //   weight-only: y = acc * s_w[n] + bias[n]
+    //   int8: stored operands are a' = qx - 128 and b' = qw - w_off; with dx = 128 - z_x, dw = w_off - z_w[n]:
+    //         ACC = raw + dw * rowsum_a'[m] + dx * (colsum_b'[n] + K * dw),  colsum_b' = colsum - K * w_off,
+    //         y = ACC * (s_x * s_w[n]) + bias[n].  Wrap-around int32 arithmetic is exact because ACC itself fits.
+    float* ch_mul = (float*)(lds + 2 * STAGE_BYTES);
+    float* ch_add = ch_mul + BN;
+    int* ch_dw = (int*)(ch_add + BN);
+    int* ch_cn = ch_dw + BN;
+    for (int t = threadIdx.x; t < BN; t += NT) {
+        int n = n0 + t;
+        n = n < g.N ? n : g.N - 1;
+        float mul = g.w_scale[n];
+        if constexpr (I8) {
+            const float sx = g.params->scale;
+            const int dx = 128 - g.params->zp;
+            const int dw = g.w_off - g.w_zp[n];
+            ch_dw[t] = dw;
+            ch_cn[t] = dx * (g.w_colsum[n] - g.K * g.w_off + g.K * dw);
+            mul *= sx;
+        }
+        ch_mul[t] = mul;
+        ch_add[t] = g.bias ? (float)g.bias[n] : 0.0f;
     }
+    __syncthreads();
+
     const int nw0 = n0 + wn * TN * 32;  // first channel of this wave
 #pragma unroll
     for (int tm = 0; tm < TM; ++tm) {
@@ -401,33 +427,26 @@ __global__ __launch_bounds__(WGM* WGN * 64, (TM * TN <= 8 ? 2 : 1)) void gemm_ke
         for (int tn = 0; tn < TN; ++tn)
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
-                // channels n .. n+3 of this lane (clamped lanes are never stored)
-                const int n_real = nw0 + tn * 32 + 8 * q + 4 * kb;
-                const int n = n_real < g.N ? n_real : g.N - 4;
-                const float4v s4 = *(const float4v*)(g.w_scale + n);
-                half4 b4 = {(_Float16)0, (_Float16)0, (_Float16)0, (_Float16)0};
-                if (g.bias) b4 = *(const half4*)(g.bias + n);
+                const int cl = (wn * TN + tn) * 32 + 8 * q + 4 * kb;  // channel inside the workgroup tile
+                const float4v mul = *(const float4v*)(ch_mul + cl);
+                const float4v add = *(const float4v*)(ch_add + cl);
                 half4 o;
                 if constexpr (I8) {
-                    // stored operands are a' = qx - 128 and b' = qw - w_off; with dx = 128 - z_x, dw = w_off - z_w[n]:
-                    //   ACC = raw + dw * rowsum_a'[m] + dx * (colsum_b'[n] + K * dw),  colsum_b' = colsum - K * w_off.
-                    // Wrap-around int32 arithmetic is exact because ACC itself fits.
-                    const int4v zw = *(const int4v*)(g.w_zp + n);
-                    const int4v cs = *(const int4v*)(g.w_colsum + n);
+                    const int4v dw = *(const int4v*)(ch_dw + cl);
+                    const int4v cn = *(const int4v*)(ch_cn + cl);
                     int4v a;
 #pragma unroll
                     for (int r = 0; r < 4; ++r) {
-                        const int dw = g.w_off - zw[r];
-                        a[r] = acc[tm][tn][4 * q + r] + dw * rsum + dx * (cs[r] - g.K * g.w_off + g.K * dw);
-                        o[r] = (_Float16)((float)a[r] * (sx * s4[r]) + (float)b4[r]);
+                        a[r] = acc[tm][tn][4 * q + r] + dw[r] * rsum + cn[r];
+                        o[r] = (_Float16)((float)a[r] * mul[r] + add[r]);
                     }
                     if (g.acc_debug) {
-                        const int m = mt0 + l31;
+                        const int m = mt0 + l31, n_real = n0 + cl;
                         if (m < g.M && n_real < g.N) *(int4v*)(g.acc_debug + (long)m * g.N + n_real) = a;
                     }
                 } else {
 #pragma unroll
-                    for (int r = 0; r < 4; ++r) o[r] = (_Float16)(acc[tm][tn][4 * q + r] * s4[r] + (float)b4[r]);
+                    for (int r = 0; r < 4; ++r) o[r] = (_Float16)(acc[tm][tn][4 * q + r] * mul[r] + add[r]);
                 }
                 const int chunk = tn * 4 + q;
                 *(half4*)(ep + l31 * (CPR * 16) + (((chunk ^ l31) & (CPR - 1)) << 4) + kb * 8) = o;
@@ -446,6 +465,13 @@ __global__ __launch_bounds__(WGM* WGN * 64, (TM * TN <= 8 ? 2 : 1)) void gemm_ke
         }
         __builtin_amdgcn_wave_barrier();
     }
+    if (g.phase_clk && threadIdx.x == 0) {
+        long long* o = g.phase_clk + (long)blockIdx.x * 4;
+        o[0] = t0;
+        o[1] = t1;
+        o[2] = t2;
+        o[3] = clock64();
+    }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -454,6 +480,12 @@ __global__ __launch_bounds__(WGM* WGN * 64, (TM * TN <= 8 ? 2 : 1)) void gemm_ke
 // Tile table.  index -> (WGM, WGN, TM, TN): 0: 128x256 (2x2 waves of 64x128), 1: 128x128 (2x2 of 64x64),
 // 2: 64x64 (2x2 of 32x32).
 static int g_force_tile = -1;
+static long long* g_phase_clk = nullptr;
+static long g_phase_cap = 0;
+void set_phase_buffer(long long* p, long workgroups) {
+    g_phase_clk = p;
+    g_phase_cap = workgroups;
+}
 void set_force_tile(int t) { g_force_tile = t; }
 
 static int pick_tile(int M, int N) {
@@ -470,11 +502,12 @@ static int run_gemm(GemmArgs& g, int tile_index, hipStream_t st) {
     constexpr int BM = WGM * TM * 32, BN = WGN * TN * 32;
     g.tiles_m = (g.M + BM - 1) / BM;
     g.tiles_n = (g.N + BN - 1) / BN;
+    g.phase_clk = ((long)g.tiles_m * g.tiles_n <= g_phase_cap) ? g_phase_clk : nullptr;
     auto kern = gemm_kernel<I8, BITS, WGM, WGN, TM, TN>;
     const double abytes = I8 ? 1.0 * g.M * g.K + 4.0 * g.M : 2.0 * g.M * g.K;
     ProfScope prof(st, prof_gemm_slot(I8 ? 1 : 0, BITS, tile_index), 2.0 * g.M * g.N * g.K,
                    abytes + (double)g.N * g.K * BITS / 8 + (I8 ? 14.0 : 10.0) * g.N + 2.0 * g.M * g.N);
-    hipLaunchKernelGGL(kern, dim3(g.tiles_m * g.tiles_n), dim3(WGM * WGN * 64), 2 * BM * 128, st, g);
+    hipLaunchKernelGGL(kern, dim3(g.tiles_m * g.tiles_n), dim3(WGM * WGN * 64), 2 * BM * 128 + BN * 16, st, g);
     MQ_HIP_CHECK_LAUNCH();
     return MQ_OK;
 }
