@@ -161,7 +161,7 @@ def main():
         kernels = mq.prof_read()
         if kernels:
             dom = max(kernels, key=lambda k: k["ms"])
-            is_int8 = "gemm_a8" in dom["kernel"]
+            is_int8 = "<true" in dom["kernel"]
             is_gemm = "gemm" in dom["kernel"]
             avg_ms = dom["ms"] / dom["launches"]
             if is_gemm:

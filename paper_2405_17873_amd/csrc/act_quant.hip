@@ -25,22 +25,33 @@ __device__ inline T wave_reduce(T v, Op op) {
     return v;
 }
 
-// One wave per row at a time; 16-byte loads.
+// A wave walks RPW rows at a time with 16-byte loads, so that every lane keeps RPW (or more) loads in flight.
+static constexpr int RPW = 4;
+
 __global__ __launch_bounds__(256) void act_minmax_kernel(const _Float16* __restrict__ x, int M, int K, long ldx,
                                                          RowMap map, float* __restrict__ partials) {
     const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
     const int K8 = K >> 3;
     float mn = INFINITY, mx = -INFINITY;
-    for (long r = (long)blockIdx.x * 4 + wv; r < M; r += (long)gridDim.x * 4) {
-        const half8* row = (const half8*)(x + map.phys(r) * ldx);
-        for (int p = lane; p < K8; p += 64) {
-            const half8 v = row[p];
+    for (long r0 = ((long)blockIdx.x * 4 + wv) * RPW; r0 < M; r0 += (long)gridDim.x * 4 * RPW) {
+        const half8* row[RPW];
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const float f = (float)v[e];
-                mn = fminf(mn, f);
-                mx = fmaxf(mx, f);
-            }
+        for (int j = 0; j < RPW; ++j) {
+            const long r = r0 + j < M ? r0 + j : M - 1;  // a repeated row does not change a min or a max
+            row[j] = (const half8*)(x + map.phys(r) * ldx);
+        }
+        for (int p = lane; p < K8; p += 64) {
+            half8 v[RPW];
+#pragma unroll
+            for (int j = 0; j < RPW; ++j) v[j] = row[j][p];
+#pragma unroll
+            for (int j = 0; j < RPW; ++j)
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const float f = (float)v[j][e];
+                    mn = fminf(mn, f);
+                    mx = fmaxf(mx, f);
+                }
         }
     }
     mn = wave_reduce(mn, [](float a, float b) { return fminf(a, b); });
@@ -105,38 +116,54 @@ __global__ __launch_bounds__(256) void act_quantize_kernel(const _Float16* __res
     }
     const int K8 = K >> 3;
     const int Kp = (K + 127) / 128 * 128;  // row stride of the int8 copy; the padding is zero
-    for (long r = (long)blockIdx.x * 4 + wv; r < M; r += (long)gridDim.x * 4) {
-        const half8* row = (const half8*)(x + map.phys(r) * ldx);
-        uint2* out = (uint2*)(a8 + r * (long)Kp);
-        int sum = 0;
-        for (int p = K8 + lane; p < (Kp >> 3); p += 64) out[p] = make_uint2(0u, 0u);
-        for (int p = lane; p < K8; p += 64) {
-            const half8 v = row[p];
-            int q[8];
+    for (long r0 = ((long)blockIdx.x * 4 + wv) * RPW; r0 < M; r0 += (long)gridDim.x * 4 * RPW) {
+        const half8* row[RPW];
+        int sum[RPW];
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                float t = rintf((float)v[e] * inv) + zf;
-                t = fminf(fmaxf(t, 0.0f), 255.0f);
-                q[e] = (int)t - 128;
-                sum += q[e];
-            }
-            uint32_t w0 = 0, w1 = 0;
-#pragma unroll
-            for (int b = 0; b < 4; ++b) {
-                w0 |= ((uint32_t)(q[k8_perm(b)] & 255)) << (8 * b);
-                w1 |= ((uint32_t)(q[k8_perm(4 + b)] & 255)) << (8 * b);
-            }
-            out[p] = make_uint2(w0, w1);
+        for (int j = 0; j < RPW; ++j) {
+            const long r = r0 + j < M ? r0 + j : M - 1;
+            row[j] = (const half8*)(x + map.phys(r) * ldx);
+            sum[j] = 0;
         }
-        sum = wave_reduce(sum, [](int a, int b) { return a + b; });
-        if (lane == 0) rowsum[r] = sum;
+        for (int p = lane; p < (Kp >> 3); p += 64) {
+            half8 v[RPW];
+            if (p < K8) {
+#pragma unroll
+                for (int j = 0; j < RPW; ++j) v[j] = row[j][p];
+            }
+#pragma unroll
+            for (int j = 0; j < RPW; ++j) {
+                uint32_t w0 = 0, w1 = 0;
+                if (p < K8) {
+                    int q[8];
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        float t = rintf((float)v[j][e] * inv) + zf;
+                        t = fminf(fmaxf(t, 0.0f), 255.0f);
+                        q[e] = (int)t - 128;
+                        sum[j] += q[e];
+                    }
+#pragma unroll
+                    for (int b = 0; b < 4; ++b) {
+                        w0 |= ((uint32_t)(q[k8_perm(b)] & 255)) << (8 * b);
+                        w1 |= ((uint32_t)(q[k8_perm(4 + b)] & 255)) << (8 * b);
+                    }
+                }
+                if (r0 + j < M) ((uint2*)(a8 + (r0 + j) * (long)Kp))[p] = make_uint2(w0, w1);
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < RPW; ++j) {
+            const int t = wave_reduce(sum[j], [](int a, int b) { return a + b; });
+            if (lane == 0 && r0 + j < M) rowsum[r0 + j] = t;
+        }
     }
 }
 
 int launch_act_quant(const void* x, int M, int K, int ldx, RowMap in_map, const float* act_scale,
                      const int32_t* act_zp, int8_t* a8, int32_t* rowsum, ActParams* params, float* partials,
                      float* act_scale_out, int32_t* act_zp_out, hipStream_t st) {
-    int grid = (M + 3) / 4;
+    int grid = (M + 4 * RPW - 1) / (4 * RPW);
     if (grid > kPartialSlots) grid = kPartialSlots;
     const bool dynamic = act_scale == nullptr;
     if (dynamic) {
@@ -145,7 +172,7 @@ int launch_act_quant(const void* x, int M, int K, int ldx, RowMap in_map, const 
                            partials);
         MQ_HIP_CHECK_LAUNCH();
     }
-    int qgrid = (M + 3) / 4;
+    int qgrid = (M + 4 * RPW - 1) / (4 * RPW);
     if (qgrid > 4096) qgrid = 4096;
     ProfScope prof(st, PROF_ACT_QUANTIZE, 0.0, 3.0 * M * K + 4.0 * M);
     hipLaunchKernelGGL(act_quantize_kernel, dim3(qgrid), dim3(256), 0, st, (const _Float16*)x, M, K, (long)ldx, in_map,

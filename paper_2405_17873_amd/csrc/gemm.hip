@@ -7,16 +7,19 @@
 //
 // Shared structure
 //   * One workgroup = WGM x WGN waves; each wave owns TM x TN MFMA tiles of 32x32.
-//   * The activation operand goes HBM -> LDS directly (buffer loads with the LDS bit: no staging registers),
-//     double buffered, 128 bytes of K per row per stage, 16-byte pieces XOR-swizzled so that ds_read_b128 of
-//     32 consecutive rows is conflict free.
-//   * The weight operand never touches LDS: the packed kernel layout stores, for every 32-channel x 64-k
-//     tile, the 64 lane chunks in lane order, so one buffer load per 16 bytes of chunk is a fully contiguous
-//     wave access and lands directly in the MFMA operand's lane.  Codes are widened in registers.
+//   * Both operands go HBM -> LDS directly (buffer loads with the LDS bit: no staging registers) through a
+//     pipeline of 2..4 LDS stages with hand-placed vmcnt waits and one barrier per stage.
+//   * Activations: 128 bytes of K per row per stage, 16-byte pieces XOR-swizzled (on the global side of the
+//     copy) so that ds_read_b128 of 32 consecutive rows is conflict free.
+//   * Weights stay PACKED in LDS: the kernel layout stores, for every 32-channel x 64-k tile, the 64 lane
+//     chunks in lane order, so a tile is copied with one contiguous wave access and a lane later reads its own
+//     chunk with one conflict-free ds_read; codes are widened in registers, right before the MFMA.
 //   * The MFMA is issued with the weight fragment as the first operand: the 32x32 result then holds, per
 //     lane, 4 consecutive output channels of one activation row, i.e. an 8-byte fp16 store.
 //   * k-order inside a stage is permuted identically for both operands (a sum does not care), chosen so
 //     that every lane's global and LDS accesses are 16 bytes wide.
+#include <stdio.h>
+
 #include <type_traits>
 
 #include "mq_common.h"
@@ -155,34 +158,57 @@ __device__ __forceinline__ half8 dequant_step<8>(const WChunk<8>& c, int s, int 
 // ---------------------------------------------------------------------------------------------
 typedef __attribute__((address_space(3))) void* lds_ptr_t;
 
-__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p, uint32_t bytes) {
-    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, (int)bytes, 0x00020000);
+// Raw buffer resource (stride 0): base address, byte extent, gfx9-family format word.
+typedef int int4s __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ int4s make_rsrc(const void* p, uint32_t bytes) {
+    const uint64_t a = (uint64_t)(uintptr_t)p;
+    int4s r;
+    r[0] = (int)(uint32_t)a;
+    r[1] = (int)(uint32_t)((a >> 32) & 0xFFFFu);
+    r[2] = (int)bytes;
+    r[3] = 0x00020000;
+    // the descriptor is wave-uniform: keep it in scalar registers
+    r[0] = __builtin_amdgcn_readfirstlane(r[0]);
+    r[1] = __builtin_amdgcn_readfirstlane(r[1]);
+    r[2] = __builtin_amdgcn_readfirstlane(r[2]);
+    return r;
 }
 
-// 16 bytes per lane from the buffer straight into LDS: lane L of the wave writes lds_wave_base + 16 * L.
-// (Device pass only: the host pass of hipcc does not know the gfx950 form of the builtin.)
-__device__ __forceinline__ void load_to_lds_b128(__amdgpu_buffer_rsrc_t r, uint32_t lds_wave_base, int voff, int soff) {
-#if defined(__HIP_DEVICE_COMPILE__)
-    __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (lds_ptr_t)(uintptr_t)lds_wave_base, 16, voff, soff, 0, 0);
-#else
-    (void)r; (void)lds_wave_base; (void)voff; (void)soff;
-#endif
+// 16 bytes per lane from the buffer straight into LDS: lane L of the wave writes lds_wave_base + 16 * L; a lane
+// whose offset lies past the end of the buffer writes zeros.  Issued as inline assembly on purpose: the compiler
+// would otherwise order every later LDS read behind ALL pending loads of this kind (it cannot tell the stage being
+// filled from the stage being read), which serialises the pipeline.  The waits are placed by hand (vmcnt below).
+__device__ __forceinline__ void dma_to_lds_b128(int4s rsrc, uint32_t lds_wave_base, int voff, int soff) {
+    asm volatile(
+        "s_mov_b32 m0, %0\n\t"
+        "s_nop 0\n\t"
+        "buffer_load_dwordx4 %1, %2, %3 offen lds"
+        :
+        : "s"(lds_wave_base), "v"(voff), "s"(rsrc), "s"(soff)
+        : "memory");  // m0 is a reserved register: the compiler rewrites it before each of its own uses
 }
 
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
+// A lane's chunk of one 64-k weight tile, read from the tile's LDS copy (lane order, so consecutive lanes read
+// consecutive addresses).
 template <int BITS>
-__device__ __forceinline__ void load_chunk(WChunk<BITS>& c, __amdgpu_buffer_rsrc_t r, int voff, int soff) {
+__device__ __forceinline__ void read_chunk(WChunk<BITS>& c, const uint8_t* tile, int lane) {
     if constexpr (BITS == 4) {
-        const uint4v v = __builtin_amdgcn_raw_buffer_load_b128(r, voff, soff, 0);
+        const uint4v v = *(const uint4v*)(tile + lane * 16);
         c.w[0] = v[0]; c.w[1] = v[1]; c.w[2] = v[2]; c.w[3] = v[3];
     } else if constexpr (BITS == 2) {
-        const uint2v v = __builtin_amdgcn_raw_buffer_load_b64(r, voff, soff, 0);
+        const uint2v v = *(const uint2v*)(tile + lane * 8);
         c.w[0] = v[0]; c.w[1] = v[1];
     } else if constexpr (BITS == 3) {
-        const uint3v v = __builtin_amdgcn_raw_buffer_load_b96(r, voff, soff, 0);
-        c.w[0] = v[0]; c.w[1] = v[1]; c.w[2] = v[2];
+        const uint32_t* p = (const uint32_t*)(tile + lane * 12);
+        c.w[0] = p[0]; c.w[1] = p[1]; c.w[2] = p[2];
     } else {
-        const uint4v v0 = __builtin_amdgcn_raw_buffer_load_b128(r, voff, soff, 0);
-        const uint4v v1 = __builtin_amdgcn_raw_buffer_load_b128(r, voff + 1024, soff, 0);
+        const uint4v v0 = *(const uint4v*)(tile + lane * 16);
+        const uint4v v1 = *(const uint4v*)(tile + 1024 + lane * 16);
         c.w[0] = v0[0]; c.w[1] = v0[1]; c.w[2] = v0[2]; c.w[3] = v0[3];
         c.w[4] = v1[0]; c.w[5] = v1[1]; c.w[6] = v1[2]; c.w[7] = v1[3];
     }
@@ -246,14 +272,34 @@ __device__ __forceinline__ void tile_of_block(int bid, int tiles_m, int tiles_n,
     bn = t - bm * tiles_n;
 }
 
-template <bool I8, int BITS, int WGM, int WGN, int TM, int TN>
-__global__ __launch_bounds__(WGM* WGN * 64, (TM * TN <= 8 ? 2 : 1)) void gemm_kernel(const GemmArgs g) {
-    constexpr int NW = WGM * WGN, NT = NW * 64;
-    constexpr int BM = WGM * TM * 32, BN = WGN * TN * 32;
-    constexpr int STAGE_BYTES = BM * 128;
-    constexpr int DMA = BM / (8 * NW);  // LDS-writing loads per wave per stage
-    constexpr int CH = I8 ? 2 : 1;      // 64-k weight tiles per stage
+// LDS plan of one workgroup: S stages of [activation tile BM x 128 B][weight tiles], a 1 KB sink for padding
+// loads, the per-channel epilogue constants.  The epilogue staging reuses the stages.
+template <bool I8, int BITS, int WGM, int WGN, int TM, int TN, int S>
+struct GemmPlan {
+    static constexpr int NW = WGM * WGN, NT = NW * 64;
+    static constexpr int BM = WGM * TM * 32, BN = WGN * TN * 32;
+    static constexpr int CH = I8 ? 2 : 1;                     // 64-k weight tiles per stage
+    static constexpr int A_BYTES = BM * 128;
+    static constexpr int BSLOT = BITS == 8 ? 2048 : 1024;     // LDS slot of one weight tile
+    static constexpr int NBT = (BN / 32) * CH;                // weight tiles per stage
+    static constexpr int B_BYTES = NBT * BSLOT;
+    static constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
+    static constexpr int DMA_A = BM / (8 * NW);               // LDS-writing loads per wave per stage, activations
+    static constexpr int NBI = NBT * (BITS == 8 ? 2 : 1);     // LDS-writing loads per stage, weights
+    static constexpr int DMA_B = (NBI + NW - 1) / NW;         // per wave (padded with loads into the sink)
+    static constexpr int OPS = DMA_A + DMA_B;                 // vector-memory operations per wave per stage
+    static constexpr int SINK = S * STAGE_BYTES;
+    static constexpr int CONSTS = SINK + 1024;
+    static constexpr int LDS_BYTES = CONSTS + BN * 16;
     static_assert(BM % (8 * NW) == 0, "tile rows must split over the waves");
+    static_assert((S - 2) * OPS <= 63 || S < 3, "vmcnt is a 6-bit counter");
+};
+
+template <bool I8, int BITS, int WGM, int WGN, int TM, int TN, int S>
+__global__ __launch_bounds__(WGM* WGN * 64, (TM * TN <= 8 ? 2 : 1)) void gemm_kernel(const GemmArgs g) {
+    using P = GemmPlan<I8, BITS, WGM, WGN, TM, TN, S>;
+    constexpr int NW = P::NW, NT = P::NT, BM = P::BM, BN = P::BN, CH = P::CH;
+    constexpr int STAGE_BYTES = P::STAGE_BYTES;
     using acc_t = typename std::conditional<I8, int16v, float16v>::type;
     using frag_t = typename std::conditional<I8, int4v, half8>::type;
 
@@ -268,32 +314,46 @@ __global__ __launch_bounds__(WGM* WGN * 64, (TM * TN <= 8 ? 2 : 1)) void gemm_ke
     const int l31 = lane & 31, kb = lane >> 5;
     const uint32_t xflip = (I8 && g.w_off) ? 0x80808080u : 0u;
     constexpr int TILE_B = 256 * BITS;
+    constexpr int OOB = 0x7FFFF000;  // an offset past the end of any buffer this library accepts
 
-    const __amdgpu_buffer_rsrc_t ra = make_rsrc(g.a, g.a_bytes);
-    const __amdgpu_buffer_rsrc_t rb = make_rsrc(g.packed, g.packed_bytes);
+    const int4s ra = make_rsrc(g.a, g.a_bytes);
+    const int4s rb = make_rsrc(g.packed, g.packed_bytes);
+    const uint32_t lds_base = (uint32_t)(uintptr_t)lds;
 
-    // activation loads: lane -> (row, physical slot) of an 8-row group; it fetches the logical piece slot ^ swz(row)
-    int a_voff[DMA];
-    uint32_t a_lds[DMA];
+    // activation loads: lane -> (row, physical slot) of an 8-row group; it fetches the logical piece slot ^ swz(row).
+    // Rows past M get an offset past the end of the buffer and therefore read as zero.
+    int a_voff[P::DMA_A];
+    uint32_t a_lds[P::DMA_A];
 #pragma unroll
-    for (int i = 0; i < DMA; ++i) {
+    for (int i = 0; i < P::DMA_A; ++i) {
         const int row0 = (i * NW + wv) * 8;
         const int row = row0 + (lane >> 3);
         const int piece = (lane & 7) ^ swz(row);
-        a_voff[i] = (int)((long)(m0 + row) * g.a_row_bytes + piece * 16);
-        // rows past M must read as zero: push them past the end of the buffer
-        if (m0 + row >= g.M) a_voff[i] = (int)0x7FFFFFF0;
+        a_voff[i] = m0 + row < g.M ? (int)((long)(m0 + row) * g.a_row_bytes + piece * 16) : OOB;
         a_lds[i] = (uint32_t)(row0 * 128);
     }
-    const uint32_t lds_base = (uint32_t)(uintptr_t)lds;
+    // weight loads: instruction j of a stage copies piece j % PCS of weight tile j / PCS (tile = channel group, chunk)
+    constexpr int PCS = BITS == 8 ? 2 : 1;
+    constexpr int VALID_LANES = BITS == 8 ? 64 : 16 * BITS;  // lanes of a 16-byte-per-lane copy that hold tile data
+    int b_voff[P::DMA_B];
+    uint32_t b_lds[P::DMA_B];
+#pragma unroll
+    for (int i = 0; i < P::DMA_B; ++i) {
+        const int j = i * NW + wv;
+        const int t = j / PCS, piece = j % PCS;
+        const int gt = t / CH, cc = t % CH;
+        int gi = (n0 >> 5) + gt;
+        gi = gi < G ? gi : G - 1;
+        const bool on = j < P::NBI && lane < VALID_LANES;
+        b_voff[i] = on ? (gi * KC + cc) * TILE_B + piece * 1024 + lane * 16 : OOB;
+        b_lds[i] = j < P::NBI ? (uint32_t)(P::A_BYTES + t * P::BSLOT + piece * 1024) : (uint32_t)0xFFFFFFFFu;
+    }
 
-    // weight loads: one lane chunk per fragment and 64-k tile
-    int b_voff[TN], zc[TN];
+    int zc[TN];
 #pragma unroll
     for (int tn = 0; tn < TN; ++tn) {
         int gi = (n0 >> 5) + wn * TN + tn;
         gi = gi < G ? gi : G - 1;
-        b_voff[tn] = gi * KC * TILE_B + lane * (BITS == 8 ? 16 : 4 * BITS);
         const int n = gi * 32 + l31;
         zc[tn] = I8 ? 0 : g.w_zp[n < g.N ? n : g.N - 1];
     }
@@ -306,19 +366,20 @@ __global__ __launch_bounds__(WGM* WGN * 64, (TM * TN <= 8 ? 2 : 1)) void gemm_ke
 #pragma unroll
             for (int i = 0; i < 16; ++i) acc[tm][tn][i] = 0;
 
-    WChunk<BITS> wcur[TN][CH], wnxt[TN][CH];
-
-    auto issue = [&](int stage, int buf, WChunk<BITS>(&w)[TN][CH]) {
-        // the k advance is wave-uniform: keep it in a scalar register
-        const int soff = __builtin_amdgcn_readfirstlane(stage * 128);
-#pragma unroll
-        for (int i = 0; i < DMA; ++i)
-            load_to_lds_b128(ra, lds_base + buf * STAGE_BYTES + a_lds[i], a_voff[i], soff);
+    // Every wave issues exactly OPS loads per stage (padding loads go to the sink), so that "at most
+    // (S-2)*OPS loads outstanding" means "the oldest stage in flight has landed" for every wave alike.
+    auto issue = [&](int stage, int buf) {
+        const int soff_a = __builtin_amdgcn_readfirstlane(stage * 128);
         const int soff_b = __builtin_amdgcn_readfirstlane(stage * CH * TILE_B);
+        const uint32_t sb = lds_base + buf * STAGE_BYTES;
 #pragma unroll
-        for (int tn = 0; tn < TN; ++tn)
+        for (int i = 0; i < P::DMA_A; ++i)
+            dma_to_lds_b128(ra, __builtin_amdgcn_readfirstlane(sb + a_lds[i]), a_voff[i], soff_a);
 #pragma unroll
-            for (int cc = 0; cc < CH; ++cc) load_chunk<BITS>(w[tn][cc], rb, b_voff[tn] + cc * TILE_B, soff_b);
+        for (int i = 0; i < P::DMA_B; ++i) {
+            const uint32_t dst = b_lds[i] == 0xFFFFFFFFu ? lds_base + P::SINK : sb + b_lds[i];
+            dma_to_lds_b128(rb, __builtin_amdgcn_readfirstlane(dst), b_voff[i], soff_b);
+        }
     };
 
     // LDS read offsets of this lane: row l31 of the wave's first tile, one register per MFMA step
@@ -333,14 +394,31 @@ __global__ __launch_bounds__(WGM* WGN * 64, (TM * TN <= 8 ? 2 : 1)) void gemm_ke
     long long t0 = 0, t1 = 0, t2 = 0;
     if (g.phase_clk) t0 = clock64();
     const int KT = g.k_stages;
-    issue(0, 0, wcur);
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();
+#pragma unroll
+    for (int s = 0; s < S - 1; ++s)
+        if (s < KT) issue(s, s);
     if (g.phase_clk) t1 = clock64();
     int buf = 0;
     for (int kt = 0; kt < KT; ++kt) {
-        if (kt + 1 < KT) issue(kt + 1, buf ^ 1, wnxt);
+        // stage kt must have landed; the S-2 younger stages may stay in flight while they exist
+        if (S > 2 && kt + (S - 2) < KT)
+            wait_vmcnt<(S > 2 ? (S - 2) * P::OPS : 0)>();
+        else
+            wait_vmcnt<0>();
+        __syncthreads();
+        // refill the buffer that was multiplied in the previous iteration (everyone is past it now)
+        if (kt + S - 1 < KT) {
+            int nb = buf + S - 1;
+            nb = nb >= S ? nb - S : nb;
+            issue(kt + S - 1, nb);
+        }
         const uint8_t* abuf = lds + buf * STAGE_BYTES;
+        WChunk<BITS> wq[TN][CH];
+#pragma unroll
+        for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+            for (int cc = 0; cc < CH; ++cc)
+                read_chunk<BITS>(wq[tn][cc], abuf + P::A_BYTES + ((wn * TN + tn) * CH + cc) * P::BSLOT, lane);
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
             frag_t wf[TN], xf[TM];
@@ -349,9 +427,9 @@ __global__ __launch_bounds__(WGM* WGN * 64, (TM * TN <= 8 ? 2 : 1)) void gemm_ke
 #pragma unroll
             for (int tn = 0; tn < TN; ++tn) {
                 if constexpr (I8)
-                    wf[tn] = widen_step<BITS>(wcur[tn][s >> 1], s & 1, xflip);
+                    wf[tn] = widen_step<BITS>(wq[tn][s >> 1], s & 1, xflip);
                 else
-                    wf[tn] = dequant_step<BITS>(wcur[tn][0], s, zc[tn]);
+                    wf[tn] = dequant_step<BITS>(wq[tn][0], s, zc[tn]);
             }
 #pragma unroll
             for (int tm = 0; tm < TM; ++tm)
@@ -363,14 +441,9 @@ __global__ __launch_bounds__(WGM* WGN * 64, (TM * TN <= 8 ? 2 : 1)) void gemm_ke
                         acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_f16(wf[tn], xf[tm], acc[tm][tn], 0, 0, 0);
                 }
         }
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        __syncthreads();
-#pragma unroll
-        for (int tn = 0; tn < TN; ++tn)
-#pragma unroll
-            for (int cc = 0; cc < CH; ++cc) wcur[tn][cc] = wnxt[tn][cc];
-        buf ^= 1;
+        buf = buf + 1 == S ? 0 : buf + 1;
     }
+    __syncthreads();  // every wave is done reading the stages: the epilogue may overwrite them
 
     if (g.phase_clk) t2 = clock64();
     // ---------------------------------------------------------------- epilogue
@@ -384,7 +457,7 @@ __global__ __launch_bounds__(WGM* WGN * 64, (TM * TN <= 8 ? 2 : 1)) void gemm_ke
     constexpr int ROWS_PER_PASS = 64 / CPR;     // rows one store instruction covers
     static_assert(64 % CPR == 0, "TN must be 1, 2 or 4");
     constexpr int EP_BYTES = 32 * CPR * 16;     // staging bytes per wave
-    static_assert(NW * EP_BYTES <= 2 * STAGE_BYTES, "epilogue staging must fit the LDS stages");
+    static_assert(NW * EP_BYTES <= S * STAGE_BYTES, "epilogue staging must fit the LDS stages");
     uint8_t* ep = lds + wv * EP_BYTES;
 
     // Per-channel epilogue constants of the workgroup's BN channels, computed once by BN threads and parked in
@@ -393,7 +466,7 @@ __global__ __launch_bounds__(WGM* WGN * 64, (TM * TN <= 8 ? 2 : 1)) void gemm_ke
     //   int8: stored operands are a' = qx - 128 and b' = qw - w_off; with dx = 128 - z_x, dw = w_off - z_w[n]:
     //         ACC = raw + dw * rowsum_a'[m] + dx * (colsum_b'[n] + K * dw),  colsum_b' = colsum - K * w_off,
     //         y = ACC * (s_x * s_w[n]) + bias[n].  Wrap-around int32 arithmetic is exact because ACC itself fits.
-    float* ch_mul = (float*)(lds + 2 * STAGE_BYTES);
+    float* ch_mul = (float*)(lds + P::CONSTS);
     float* ch_add = ch_mul + BN;
     int* ch_dw = (int*)(ch_add + BN);
     int* ch_cn = ch_dw + BN;
@@ -477,8 +550,11 @@ __global__ __launch_bounds__(WGM* WGN * 64, (TM * TN <= 8 ? 2 : 1)) void gemm_ke
 // ---------------------------------------------------------------------------------------------
 // Launchers
 // ---------------------------------------------------------------------------------------------
-// Tile table.  index -> (WGM, WGN, TM, TN): 0: 128x256 (2x2 waves of 64x128), 1: 128x128 (2x2 of 64x64),
-// 2: 64x64 (2x2 of 32x32).
+// Tile table.  index -> workgroup tile (rows x channels), waves, wave tile:
+//   0: 256x256, 8 waves (4x2) of 64x128      1: 128x256, 4 waves (2x2) of 64x128
+//   2: 128x128, 4 waves (2x2) of 64x64       3: 64x64,   4 waves (2x2) of 32x32
+// The number of LDS stages is the largest (<= 4) that fits the LDS budget of the tile: the whole 160 KB for
+// tile 0 (one workgroup per compute unit), half of it for tiles 1 and 2 (two per compute unit), a third for tile 3.
 static int g_force_tile = -1;
 static long long* g_phase_clk = nullptr;
 static long g_phase_cap = 0;
@@ -489,36 +565,61 @@ void set_phase_buffer(long long* p, long workgroups) {
 void set_force_tile(int t) { g_force_tile = t; }
 
 static int pick_tile(int M, int N) {
-    if (g_force_tile >= 0 && g_force_tile <= 2) return g_force_tile;
-    const long t0 = (long)((M + 127) / 128) * ((N + 255) / 256);
+    if (g_force_tile >= 0 && g_force_tile <= 3) return g_force_tile;
+    const long t0 = (long)((M + 255) / 256) * ((N + 255) / 256);
     if (t0 >= 512) return 0;
-    const long t1 = (long)((M + 127) / 128) * ((N + 127) / 128);
-    if (t1 >= 256) return 1;
-    return 2;
+    const long t1 = (long)((M + 127) / 128) * ((N + 255) / 256);
+    if (t1 >= 512) return 1;
+    const long t2 = (long)((M + 127) / 128) * ((N + 127) / 128);
+    if (t2 >= 256) return 2;
+    return 3;
 }
 
 template <bool I8, int BITS, int WGM, int WGN, int TM, int TN>
+constexpr int pick_stages(int budget) {
+    if (GemmPlan<I8, BITS, WGM, WGN, TM, TN, 4>::LDS_BYTES <= budget) return 4;
+    if (GemmPlan<I8, BITS, WGM, WGN, TM, TN, 3>::LDS_BYTES <= budget) return 3;
+    return 2;
+}
+
+template <bool I8, int BITS, int WGM, int WGN, int TM, int TN, int BUDGET>
 static int run_gemm(GemmArgs& g, int tile_index, hipStream_t st) {
-    constexpr int BM = WGM * TM * 32, BN = WGN * TN * 32;
-    g.tiles_m = (g.M + BM - 1) / BM;
-    g.tiles_n = (g.N + BN - 1) / BN;
+    constexpr int S = pick_stages<I8, BITS, WGM, WGN, TM, TN>(BUDGET);
+    using P = GemmPlan<I8, BITS, WGM, WGN, TM, TN, S>;
+    static_assert(P::LDS_BYTES <= 160 * 1024, "LDS plan exceeds the compute unit");
+    g.tiles_m = (g.M + P::BM - 1) / P::BM;
+    g.tiles_n = (g.N + P::BN - 1) / P::BN;
     g.phase_clk = ((long)g.tiles_m * g.tiles_n <= g_phase_cap) ? g_phase_clk : nullptr;
-    auto kern = gemm_kernel<I8, BITS, WGM, WGN, TM, TN>;
+    auto kern = gemm_kernel<I8, BITS, WGM, WGN, TM, TN, S>;
+    static bool prepared = false;  // once per instantiation: allow more than 64 KB of dynamic LDS, name the slot
+    const int slot = prof_gemm_slot(I8 ? 1 : 0, BITS, tile_index);
+    if (!prepared) {
+        if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, P::LDS_BYTES) !=
+            hipSuccess) {
+            set_hip_error((int)hipGetLastError());
+            return MQ_ERR_HIP;
+        }
+        char name[96];
+        snprintf(name, sizeof name, "mq::gemm_kernel<%s, %d, %d, %d, %d, %d, %d>", I8 ? "true" : "false", BITS, WGM,
+                 WGN, TM, TN, S);
+        prof_name_slot(slot, name);
+        prepared = true;
+    }
     const double abytes = I8 ? 1.0 * g.M * g.K + 4.0 * g.M : 2.0 * g.M * g.K;
-    ProfScope prof(st, prof_gemm_slot(I8 ? 1 : 0, BITS, tile_index), 2.0 * g.M * g.N * g.K,
+    ProfScope prof(st, slot, 2.0 * g.M * g.N * g.K,
                    abytes + (double)g.N * g.K * BITS / 8 + (I8 ? 14.0 : 10.0) * g.N + 2.0 * g.M * g.N);
-    hipLaunchKernelGGL(kern, dim3(g.tiles_m * g.tiles_n), dim3(WGM * WGN * 64), 2 * BM * 128 + BN * 16, st, g);
+    hipLaunchKernelGGL(kern, dim3(g.tiles_m * g.tiles_n), dim3(P::NT), P::LDS_BYTES, st, g);
     MQ_HIP_CHECK_LAUNCH();
     return MQ_OK;
 }
 
 template <bool I8, int BITS>
 static int dispatch_gemm(GemmArgs& g, hipStream_t st) {
-    const int t = pick_tile(g.M, g.N);
-    switch (t) {
-        case 0: return run_gemm<I8, BITS, 2, 2, 2, 4>(g, 0, st);
-        case 1: return run_gemm<I8, BITS, 2, 2, 2, 2>(g, 1, st);
-        default: return run_gemm<I8, BITS, 2, 2, 1, 1>(g, 2, st);
+    switch (pick_tile(g.M, g.N)) {
+        case 0: return run_gemm<I8, BITS, 4, 2, 2, 4, 160 * 1024>(g, 0, st);
+        case 1: return run_gemm<I8, BITS, 2, 2, 2, 4, 80 * 1024>(g, 1, st);
+        case 2: return run_gemm<I8, BITS, 2, 2, 2, 2, 80 * 1024>(g, 2, st);
+        default: return run_gemm<I8, BITS, 2, 2, 1, 1, 53 * 1024>(g, 3, st);
     }
 }
 

@@ -24,33 +24,29 @@ bool g_on = false;
 std::vector<Slot> g_slots;
 std::vector<Pair> g_free;
 
-const int kBits[4] = {2, 3, 4, 8};
-const char* kTile[3] = {"2, 2, 2, 4", "2, 2, 2, 2", "2, 2, 1, 1"};
-
 void init_slots() {
     if (!g_slots.empty()) return;
     g_slots.resize(prof_num_slots());
-    for (int fam = 0; fam < 2; ++fam)
-        for (int b = 0; b < 4; ++b)
-            for (int t = 0; t < 3; ++t) {
-                char buf[96];
-                snprintf(buf, sizeof buf, "mq::gemm_kernel<%s, %d, %s>", fam ? "true" : "false", kBits[b], kTile[t]);
-                g_slots[prof_gemm_slot(fam, kBits[b], t)].name = buf;
-            }
     g_slots[PROF_ACT_MINMAX].name = "mq::act_minmax_kernel";
     g_slots[PROF_ACT_QUANTIZE].name = "mq::act_quantize_kernel";
     g_slots[PROF_BOS_ROWS].name = "mq::bos_rows_kernel<8>";
 }
 }  // namespace
 
-int prof_num_slots() { return 27; }
+int prof_num_slots() { return 35; }
 
 int prof_gemm_slot(int family, int bits, int tile) {
     const int b = bits == 2 ? 0 : bits == 3 ? 1 : bits == 4 ? 2 : 3;
-    return (family * 4 + b) * 3 + tile;
+    return (family * 4 + b) * 4 + tile;
 }
 
 bool prof_enabled() { return g_on; }
+
+void prof_name_slot(int slot, const char* name) {
+    std::lock_guard<std::mutex> lk(g_mu);
+    init_slots();
+    g_slots[slot].name = name;
+}
 
 int prof_enable(int on) {
     std::lock_guard<std::mutex> lk(g_mu);
