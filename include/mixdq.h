@@ -48,7 +48,7 @@ extern "C" {
 int mq_version(void);
 int mq_last_hip_error(void);
 
-/* Tuning and test hook: force the GEMM workgroup tile (0: 256x256, 1: 128x256, 2: 128x128, 3: 64x64; -1: automatic choice
+/* Tuning and test hook: force the GEMM workgroup tile (0: 128x256, 1: 128x128, 2: 64x64; -1: automatic choice
  * from the problem shape).  Process-wide, not thread safe; results do not depend on the tile. */
 void mq_tune_force_tile(int tile);
 

@@ -292,7 +292,6 @@ struct GemmPlan {
     static constexpr int CONSTS = SINK + 1024;
     static constexpr int LDS_BYTES = CONSTS + BN * 16;
     static_assert(BM % (8 * NW) == 0, "tile rows must split over the waves");
-    static_assert((S - 2) * OPS <= 63 || S < 3, "vmcnt is a 6-bit counter");
 };
 
 template <bool I8, int BITS, int WGM, int WGN, int TM, int TN, int S>
@@ -412,18 +411,33 @@ __global__ __launch_bounds__(WGM* WGN * 64, (TM * TN <= 8 ? 2 : 1)) void gemm_ke
             nb = nb >= S ? nb - S : nb;
             issue(kt + S - 1, nb);
         }
+        // Multiply the stage.  On this hardware an LDS read into registers, a vector ALU instruction and an MFMA
+        // all take turns on the SIMD, so the only latency worth hiding is that of the LDS reads: the fragments of
+        // step s+1 are requested before the MFMAs of step s are issued (two register sets for the activations).
         const uint8_t* abuf = lds + buf * STAGE_BYTES;
         WChunk<BITS> wq[TN][CH];
+        frag_t xf[2][TM];
 #pragma unroll
         for (int tn = 0; tn < TN; ++tn)
+            read_chunk<BITS>(wq[tn][0], abuf + P::A_BYTES + ((wn * TN + tn) * CH) * P::BSLOT, lane);
 #pragma unroll
-            for (int cc = 0; cc < CH; ++cc)
-                read_chunk<BITS>(wq[tn][cc], abuf + P::A_BYTES + ((wn * TN + tn) * CH + cc) * P::BSLOT, lane);
+        for (int tm = 0; tm < TM; ++tm) xf[0][tm] = *(const frag_t*)(abuf + rd[0] + tm * 32 * 128);
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
-            frag_t wf[TN], xf[TM];
+            if constexpr (CH == 2) {
+                if (s == 0) {
 #pragma unroll
-            for (int tm = 0; tm < TM; ++tm) xf[tm] = *(const frag_t*)(abuf + rd[s] + tm * 32 * 128);
+                    for (int tn = 0; tn < TN; ++tn)
+                        read_chunk<BITS>(wq[tn][1], abuf + P::A_BYTES + ((wn * TN + tn) * CH + 1) * P::BSLOT, lane);
+                }
+            }
+            if (s < 3) {
+#pragma unroll
+                for (int tm = 0; tm < TM; ++tm)
+                    xf[(s + 1) & 1][tm] = *(const frag_t*)(abuf + rd[s + 1] + tm * 32 * 128);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            frag_t wf[TN];
 #pragma unroll
             for (int tn = 0; tn < TN; ++tn) {
                 if constexpr (I8)
@@ -436,10 +450,13 @@ __global__ __launch_bounds__(WGM* WGN * 64, (TM * TN <= 8 ? 2 : 1)) void gemm_ke
 #pragma unroll
                 for (int tn = 0; tn < TN; ++tn) {
                     if constexpr (I8)
-                        acc[tm][tn] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wf[tn], xf[tm], acc[tm][tn], 0, 0, 0);
+                        acc[tm][tn] =
+                            __builtin_amdgcn_mfma_i32_32x32x32_i8(wf[tn], xf[s & 1][tm], acc[tm][tn], 0, 0, 0);
                     else
-                        acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_f16(wf[tn], xf[tm], acc[tm][tn], 0, 0, 0);
+                        acc[tm][tn] =
+                            __builtin_amdgcn_mfma_f32_32x32x16_f16(wf[tn], xf[s & 1][tm], acc[tm][tn], 0, 0, 0);
                 }
+            __builtin_amdgcn_sched_barrier(0);
         }
         buf = buf + 1 == S ? 0 : buf + 1;
     }
@@ -551,10 +568,12 @@ __global__ __launch_bounds__(WGM* WGN * 64, (TM * TN <= 8 ? 2 : 1)) void gemm_ke
 // Launchers
 // ---------------------------------------------------------------------------------------------
 // Tile table.  index -> workgroup tile (rows x channels), waves, wave tile:
-//   0: 256x256, 8 waves (4x2) of 64x128      1: 128x256, 4 waves (2x2) of 64x128
-//   2: 128x128, 4 waves (2x2) of 64x64       3: 64x64,   4 waves (2x2) of 32x32
-// The number of LDS stages is the largest (<= 4) that fits the LDS budget of the tile: the whole 160 KB for
-// tile 0 (one workgroup per compute unit), half of it for tiles 1 and 2 (two per compute unit), a third for tile 3.
+//   0: 128x256, 4 waves (1x4) of 128x64     1: 128x128, 4 waves (2x2) of 64x64     2: 64x64, 4 waves of 32x32
+// A tall wave tile pays: every widened weight fragment then feeds 4 MFMAs (measured: LDS reads into registers,
+// vector ALU instructions and MFMAs take turns on a SIMD, they do not overlap).  256x256 tiles with one wave per
+// SIMD and 128x128 tiles with two-wave workgroups were measured slower on every configured shape.
+// The number of LDS stages is the largest (<= 4; <= 8 for tile 2, whose problems are latency bound) that lets two
+// workgroups share a compute unit and keeps the hand-counted loads within the 6-bit vmcnt.
 static int g_force_tile = -1;
 static long long* g_phase_clk = nullptr;
 static long g_phase_cap = 0;
@@ -565,26 +584,32 @@ void set_phase_buffer(long long* p, long workgroups) {
 void set_force_tile(int t) { g_force_tile = t; }
 
 static int pick_tile(int M, int N) {
-    if (g_force_tile >= 0 && g_force_tile <= 3) return g_force_tile;
-    const long t0 = (long)((M + 255) / 256) * ((N + 255) / 256);
+    if (g_force_tile >= 0 && g_force_tile <= 2) return g_force_tile;
+    const long t0 = (long)((M + 127) / 128) * ((N + 255) / 256);
     if (t0 >= 512) return 0;
-    const long t1 = (long)((M + 127) / 128) * ((N + 255) / 256);
-    if (t1 >= 512) return 1;
-    const long t2 = (long)((M + 127) / 128) * ((N + 127) / 128);
-    if (t2 >= 256) return 2;
-    return 3;
-}
-
-template <bool I8, int BITS, int WGM, int WGN, int TM, int TN>
-constexpr int pick_stages(int budget) {
-    if (GemmPlan<I8, BITS, WGM, WGN, TM, TN, 4>::LDS_BYTES <= budget) return 4;
-    if (GemmPlan<I8, BITS, WGM, WGN, TM, TN, 3>::LDS_BYTES <= budget) return 3;
+    const long t1 = (long)((M + 127) / 128) * ((N + 127) / 128);
+    if (t1 >= 128) return 1;
     return 2;
 }
 
-template <bool I8, int BITS, int WGM, int WGN, int TM, int TN, int BUDGET>
+template <bool I8, int BITS, int WGM, int WGN, int TM, int TN, int S>
+constexpr bool stages_fit(int budget) {
+    using P = GemmPlan<I8, BITS, WGM, WGN, TM, TN, S>;
+    return P::LDS_BYTES <= budget && (S - 2) * P::OPS <= 63;
+}
+
+template <bool I8, int BITS, int WGM, int WGN, int TM, int TN>
+constexpr int pick_stages(int budget, int max_stages) {
+    if (max_stages >= 8 && stages_fit<I8, BITS, WGM, WGN, TM, TN, 8>(budget)) return 8;
+    if (max_stages >= 6 && stages_fit<I8, BITS, WGM, WGN, TM, TN, 6>(budget)) return 6;
+    if (max_stages >= 4 && stages_fit<I8, BITS, WGM, WGN, TM, TN, 4>(budget)) return 4;
+    if (stages_fit<I8, BITS, WGM, WGN, TM, TN, 3>(budget)) return 3;
+    return 2;
+}
+
+template <bool I8, int BITS, int WGM, int WGN, int TM, int TN, int BUDGET, int MAXS>
 static int run_gemm(GemmArgs& g, int tile_index, hipStream_t st) {
-    constexpr int S = pick_stages<I8, BITS, WGM, WGN, TM, TN>(BUDGET);
+    constexpr int S = pick_stages<I8, BITS, WGM, WGN, TM, TN>(BUDGET, MAXS);
     using P = GemmPlan<I8, BITS, WGM, WGN, TM, TN, S>;
     static_assert(P::LDS_BYTES <= 160 * 1024, "LDS plan exceeds the compute unit");
     g.tiles_m = (g.M + P::BM - 1) / P::BM;
@@ -616,10 +641,9 @@ static int run_gemm(GemmArgs& g, int tile_index, hipStream_t st) {
 template <bool I8, int BITS>
 static int dispatch_gemm(GemmArgs& g, hipStream_t st) {
     switch (pick_tile(g.M, g.N)) {
-        case 0: return run_gemm<I8, BITS, 4, 2, 2, 4, 160 * 1024>(g, 0, st);
-        case 1: return run_gemm<I8, BITS, 2, 2, 2, 4, 80 * 1024>(g, 1, st);
-        case 2: return run_gemm<I8, BITS, 2, 2, 2, 2, 80 * 1024>(g, 2, st);
-        default: return run_gemm<I8, BITS, 2, 2, 1, 1, 53 * 1024>(g, 3, st);
+        case 0: return run_gemm<I8, BITS, 1, 4, 4, 2, 80 * 1024, 4>(g, 0, st);
+        case 1: return run_gemm<I8, BITS, 2, 2, 2, 2, 80 * 1024, 4>(g, 1, st);
+        default: return run_gemm<I8, BITS, 2, 2, 1, 1, 80 * 1024, 8>(g, 2, st);
     }
 }
 

@@ -90,7 +90,7 @@ void set_force_tile(int t);
 void set_phase_buffer(long long* p, long workgroups);
 
 // ---- optional per-kernel event timing (prof.hip) ----
-enum { PROF_ACT_MINMAX = 32, PROF_ACT_QUANTIZE = 33, PROF_BOS_ROWS = 34 };
+enum { PROF_ACT_MINMAX = 24, PROF_ACT_QUANTIZE = 25, PROF_BOS_ROWS = 26 };
 int prof_num_slots();
 int prof_gemm_slot(int family /*0 weight-only, 1 int8*/, int bits, int tile);
 bool prof_enabled();

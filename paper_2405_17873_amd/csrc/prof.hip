@@ -33,11 +33,11 @@ void init_slots() {
 }
 }  // namespace
 
-int prof_num_slots() { return 35; }
+int prof_num_slots() { return 27; }
 
 int prof_gemm_slot(int family, int bits, int tile) {
     const int b = bits == 2 ? 0 : bits == 3 ? 1 : bits == 4 ? 2 : 3;
-    return (family * 4 + b) * 4 + tile;
+    return (family * 4 + b) * 3 + tile;
 }
 
 bool prof_enabled() { return g_on; }
