@@ -48,7 +48,8 @@ extern "C" {
 int mq_version(void);
 int mq_last_hip_error(void);
 
-/* Tuning and test hook: force the GEMM workgroup tile (0: 128x256, 1: 128x128, 2: 64x64; -1: automatic choice
+/* Tuning and test hook: force the GEMM workgroup tile (0: 128x256, 1: 128x128, 2: 64x64, 3 and 4: as 1 and 2 with the
+ * reduction split over two wave groups inside the workgroup; -1: automatic choice
  * from the problem shape).  Process-wide, not thread safe; results do not depend on the tile. */
 void mq_tune_force_tile(int tile);
 
@@ -63,6 +64,10 @@ int mq_prof_num_slots(void);
 int mq_prof_read(int slot, char* name_host, int name_cap, long long* launches_host, double* ms_host,
                  double* ops_host, double* bytes_host);
 int mq_prof_reset(void);
+/* An event pair costs a few microseconds of stream time and breaks back-to-back dispatch, so a benchmark that also
+ * reports whole-run throughput restricts the bracketing: only launches of `slot` (-1: every kernel), and of those
+ * only every `stride`-th.  Totals then cover the bracketed launches only. */
+int mq_prof_filter(int slot, int stride);
 
 /* Phase timing inside the GEMM kernels: while clk != NULL every GEMM launch with at most `workgroups` workgroups
  * writes four shader-clock samples per workgroup (start, main loop entered, epilogue entered, end) to

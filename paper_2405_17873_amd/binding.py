@@ -21,7 +21,7 @@ _ERRORS = {
 }
 
 EXPORTS = ("mq_version", "mq_last_hip_error", "mq_tune_force_tile", "mq_prof_enable", "mq_prof_num_slots", "mq_prof_read",
-           "mq_prof_reset", "mq_prof_phase_buffer", "mq_quantize_weights", "mq_packed_bytes", "mq_pack_weights",
+           "mq_prof_reset", "mq_prof_phase_buffer", "mq_prof_filter", "mq_quantize_weights", "mq_packed_bytes", "mq_pack_weights",
            "mq_unpack_weights", "mq_qlinear_w_only", "mq_qlinear_a8_workspace_bytes", "mq_qlinear_w8a8",
            "mq_qlinear_w4a8", "mq_bos_aware_kv_proj_workspace_bytes", "mq_bos_aware_kv_proj")
 
@@ -68,6 +68,10 @@ def prof_enable(on: bool) -> None:
     _check(load().mq_prof_enable(int(on)), "mq_prof_enable")
 
 
+def prof_filter(slot: int = -1, stride: int = 1) -> None:
+    _check(load().mq_prof_filter(int(slot), int(stride)), "mq_prof_filter")
+
+
 def prof_reset() -> None:
     _check(load().mq_prof_reset(), "mq_prof_reset")
 
@@ -82,7 +86,7 @@ def prof_read():
         ms, ops, byts = C.c_double(), C.c_double(), C.c_double()
         _check(L.mq_prof_read(slot, name, 128, C.byref(n), C.byref(ms), C.byref(ops), C.byref(byts)), "mq_prof_read")
         if n.value:
-            out.append({"kernel": name.value.decode(), "launches": n.value, "ms": ms.value, "ops": ops.value,
+            out.append({"slot": slot, "kernel": name.value.decode(), "launches": n.value, "ms": ms.value, "ops": ops.value,
                         "bytes": byts.value})
     return out
 
@@ -239,3 +243,56 @@ def bos_aware_kv_proj(ctx: torch.Tensor, w: PackedWeight, w_f16: Optional[torch.
                                      _ptr(ws), C.c_size_t(ws.numel()), _stream())
     _check(rc, "mq_bos_aware_kv_proj")
     return y, (s_out, z_out)
+
+
+# ---------------------------------------------------------------------------------------------------------------
+# Pre-marshalled calls.  A serving loop runs the same layer on the same buffers over and over; marshalling two
+# dozen arguments in Python each time costs more than some of the kernels.  plan_*() does the marshalling once and
+# returns a zero-argument callable that only performs the C call (on the stream that was current at plan time).
+# ---------------------------------------------------------------------------------------------------------------
+
+def _planned(fn, what, args, keep):
+    def call():
+        rc = fn(*args)
+        if rc != 0:
+            raise MixdqError(rc, what)
+    call.keepalive = keep  # the tensors must outlive the plan
+    return call
+
+
+def plan_qlinear_w_only(x, w: PackedWeight, bias, out):
+    assert x.is_cuda and x.dim() == 2 and x.stride(1) == 1 and out.shape == (x.shape[0], w.N)
+    M, K = x.shape
+    args = (_ptr(x), M, K, x.stride(0), _ptr(w.packed), w.N, w.bits, w.layout, _ptr(w.scale), _ptr(w.zp), _ptr(bias),
+            _ptr(out), out.stride(0), _dtype_code(x), _stream())
+    return _planned(load().mq_qlinear_w_only, "mq_qlinear_w_only", args, (x, w, bias, out))
+
+
+def plan_qlinear_a8(x, w: PackedWeight, bias, out, ws, act=None):
+    """W8A8 or W4A8 by the weight's bit-width; dynamic activation parameters unless act=(scale, zp) tensors."""
+    assert x.is_cuda and x.dim() == 2 and x.stride(1) == 1 and x.dtype == torch.float16
+    M, K = x.shape
+    a_s, a_z = (None, None) if act is None else act
+    null = C.c_void_p(0)
+    if w.bits == 8:
+        fn, what = load().mq_qlinear_w8a8, "mq_qlinear_w8a8"
+        args = (_ptr(x), M, K, x.stride(0), _ptr(w.packed), w.N, w.layout, int(w.signed), _ptr(w.scale), _ptr(w.zp),
+                _ptr(w.colsum), _ptr(a_s), _ptr(a_z), _ptr(bias), _ptr(out), out.stride(0), null, null, null, _ptr(ws),
+                C.c_size_t(ws.numel()), _stream())
+    else:
+        fn, what = load().mq_qlinear_w4a8, "mq_qlinear_w4a8"
+        args = (_ptr(x), M, K, x.stride(0), _ptr(w.packed), w.N, w.layout, _ptr(w.scale), _ptr(w.zp), _ptr(w.colsum),
+                _ptr(a_s), _ptr(a_z), _ptr(bias), _ptr(out), out.stride(0), null, null, null, _ptr(ws),
+                C.c_size_t(ws.numel()), _stream())
+    return _planned(fn, what, args, (x, w, bias, out, ws, act))
+
+
+def plan_bos_aware_kv_proj(ctx, w: PackedWeight, out, ws, w_f16=None, bos_out=None, bias=None, act=None):
+    assert ctx.is_cuda and ctx.dim() == 3 and ctx.is_contiguous() and ctx.dtype == torch.float16
+    B, T, K = ctx.shape
+    a_s, a_z = (None, None) if act is None else act
+    null = C.c_void_p(0)
+    args = (_ptr(ctx), B, T, K, _ptr(w.packed), w.N, w.bits, w.layout, int(w.signed), _ptr(w.scale), _ptr(w.zp),
+            _ptr(w.colsum), _ptr(w_f16), _ptr(bos_out), _ptr(a_s), _ptr(a_z), _ptr(bias), _ptr(out), 0, null, null,
+            _ptr(ws), C.c_size_t(ws.numel()), _stream())
+    return _planned(load().mq_bos_aware_kv_proj, "mq_bos_aware_kv_proj", args, (ctx, w, out, ws, w_f16, bos_out, bias, act))

@@ -86,6 +86,7 @@ int mq_prof_read(int slot, char* name_host, int name_cap, long long* launches_ho
     return prof_read(slot, name_host, name_cap, launches_host, ms_host, ops_host, bytes_host);
 }
 int mq_prof_reset(void) { return prof_reset(); }
+int mq_prof_filter(int slot, int stride) { return prof_filter(slot, stride); }
 
 int mq_quantize_weights(const void* w, int N, int K, int bits, int symmetric, int dtype, uint8_t* codes, float* scale,
                         int32_t* zp, void* stream) {

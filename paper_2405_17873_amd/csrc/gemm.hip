@@ -272,31 +272,42 @@ __device__ __forceinline__ void tile_of_block(int bid, int tiles_m, int tiles_n,
     bn = t - bm * tiles_n;
 }
 
-// LDS plan of one workgroup: S stages of [activation tile BM x 128 B][weight tiles], a 1 KB sink for padding
-// loads, the per-channel epilogue constants.  The epilogue staging reuses the stages.
-template <bool I8, int BITS, int WGM, int WGN, int TM, int TN, int S>
+// LDS plan of one workgroup: S stages, each KS sub-stages of [activation tile BM x 128 B][weight tiles]; a 1 KB sink
+// for padding loads; the per-channel epilogue constants.  The accumulator exchange (KS == 2) and the epilogue staging
+// reuse the stages.
+//
+// KS == 2 splits the reduction inside the workgroup: a second group of WGM x WGN waves works on the same output
+// tile and takes every other 128-byte k step.  It is for problems with few tiles: a compute unit then still has two
+// waves per SIMD to alternate between while fragments travel from LDS, without any extra global traffic; the two
+// accumulator sets meet once, through LDS, before the epilogue.
+template <bool I8, int BITS, int WGM, int WGN, int TM, int TN, int S, int KS>
 struct GemmPlan {
-    static constexpr int NW = WGM * WGN, NT = NW * 64;
+    static constexpr int NWG = WGM * WGN;                     // waves of one group
+    static constexpr int NW = NWG * KS, NT = NW * 64;
     static constexpr int BM = WGM * TM * 32, BN = WGN * TN * 32;
-    static constexpr int CH = I8 ? 2 : 1;                     // 64-k weight tiles per stage
+    static constexpr int CH = I8 ? 2 : 1;                     // 64-k weight tiles per 128-byte k step
     static constexpr int A_BYTES = BM * 128;
     static constexpr int BSLOT = BITS == 8 ? 2048 : 1024;     // LDS slot of one weight tile
-    static constexpr int NBT = (BN / 32) * CH;                // weight tiles per stage
+    static constexpr int NBT = (BN / 32) * CH;                // weight tiles per sub-stage
     static constexpr int B_BYTES = NBT * BSLOT;
-    static constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
-    static constexpr int DMA_A = BM / (8 * NW);               // LDS-writing loads per wave per stage, activations
-    static constexpr int NBI = NBT * (BITS == 8 ? 2 : 1);     // LDS-writing loads per stage, weights
+    static constexpr int SUB_BYTES = A_BYTES + B_BYTES;
+    static constexpr int STAGE_BYTES = KS * SUB_BYTES;
+    static constexpr int NAI = KS * (BM / 8);                 // LDS-writing loads per stage, activations
+    static constexpr int DMA_A = NAI / NW;                    // ... per wave
+    static constexpr int NBI1 = NBT * (BITS == 8 ? 2 : 1);    // LDS-writing loads per sub-stage, weights
+    static constexpr int NBI = KS * NBI1;
     static constexpr int DMA_B = (NBI + NW - 1) / NW;         // per wave (padded with loads into the sink)
     static constexpr int OPS = DMA_A + DMA_B;                 // vector-memory operations per wave per stage
     static constexpr int SINK = S * STAGE_BYTES;
     static constexpr int CONSTS = SINK + 1024;
     static constexpr int LDS_BYTES = CONSTS + BN * 16;
-    static_assert(BM % (8 * NW) == 0, "tile rows must split over the waves");
+    static_assert(NAI % NW == 0, "tile rows must split over the waves");
+    static_assert(KS == 1 || NWG * TM * TN * 1024 <= S * STAGE_BYTES, "accumulator exchange must fit the stages");
 };
 
-template <bool I8, int BITS, int WGM, int WGN, int TM, int TN, int S>
-__global__ __launch_bounds__(WGM* WGN * 64, (TM * TN <= 8 ? 2 : 1)) void gemm_kernel(const GemmArgs g) {
-    using P = GemmPlan<I8, BITS, WGM, WGN, TM, TN, S>;
+template <bool I8, int BITS, int WGM, int WGN, int TM, int TN, int S, int KS>
+__global__ __launch_bounds__(WGM* WGN* KS * 64, (TM * TN <= 8 ? 2 : 1)) void gemm_kernel(const GemmArgs g) {
+    using P = GemmPlan<I8, BITS, WGM, WGN, TM, TN, S, KS>;
     constexpr int NW = P::NW, NT = P::NT, BM = P::BM, BN = P::BN, CH = P::CH;
     constexpr int STAGE_BYTES = P::STAGE_BYTES;
     using acc_t = typename std::conditional<I8, int16v, float16v>::type;
@@ -304,7 +315,8 @@ __global__ __launch_bounds__(WGM* WGN * 64, (TM * TN <= 8 ? 2 : 1)) void gemm_ke
 
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
     const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
-    const int wm = wv / WGN, wn = wv % WGN;
+    const int grp = wv / P::NWG, wvg = wv % P::NWG;  // k-split group, wave inside the group
+    const int wm = wvg / WGN, wn = wvg % WGN;
     int bm, bn;
     tile_of_block(blockIdx.x, g.tiles_m, g.tiles_n, bm, bn);
     const int m0 = bm * BM, n0 = bn * BN;
@@ -325,13 +337,15 @@ __global__ __launch_bounds__(WGM* WGN * 64, (TM * TN <= 8 ? 2 : 1)) void gemm_ke
     uint32_t a_lds[P::DMA_A];
 #pragma unroll
     for (int i = 0; i < P::DMA_A; ++i) {
-        const int row0 = (i * NW + wv) * 8;
+        const int j = i * NW + wv;
+        const int sub = j / (BM / 8), row0 = (j % (BM / 8)) * 8;
         const int row = row0 + (lane >> 3);
         const int piece = (lane & 7) ^ swz(row);
-        a_voff[i] = m0 + row < g.M ? (int)((long)(m0 + row) * g.a_row_bytes + piece * 16) : OOB;
-        a_lds[i] = (uint32_t)(row0 * 128);
+        a_voff[i] = m0 + row < g.M ? (int)((long)(m0 + row) * g.a_row_bytes + sub * 128 + piece * 16) : OOB;
+        a_lds[i] = (uint32_t)(sub * P::SUB_BYTES + row0 * 128);
     }
-    // weight loads: instruction j of a stage copies piece j % PCS of weight tile j / PCS (tile = channel group, chunk)
+    // weight loads: instruction jj of a sub-stage copies piece jj % PCS of weight tile jj / PCS (tile = channel group,
+    // chunk)
     constexpr int PCS = BITS == 8 ? 2 : 1;
     constexpr int VALID_LANES = BITS == 8 ? 64 : 16 * BITS;  // lanes of a 16-byte-per-lane copy that hold tile data
     int b_voff[P::DMA_B];
@@ -339,13 +353,15 @@ __global__ __launch_bounds__(WGM* WGN * 64, (TM * TN <= 8 ? 2 : 1)) void gemm_ke
 #pragma unroll
     for (int i = 0; i < P::DMA_B; ++i) {
         const int j = i * NW + wv;
-        const int t = j / PCS, piece = j % PCS;
+        const int sub = j / P::NBI1, jj = j % P::NBI1;
+        const int t = jj / PCS, piece = jj % PCS;
         const int gt = t / CH, cc = t % CH;
         int gi = (n0 >> 5) + gt;
         gi = gi < G ? gi : G - 1;
         const bool on = j < P::NBI && lane < VALID_LANES;
-        b_voff[i] = on ? (gi * KC + cc) * TILE_B + piece * 1024 + lane * 16 : OOB;
-        b_lds[i] = j < P::NBI ? (uint32_t)(P::A_BYTES + t * P::BSLOT + piece * 1024) : (uint32_t)0xFFFFFFFFu;
+        b_voff[i] = on ? (gi * KC + sub * CH + cc) * TILE_B + piece * 1024 + lane * 16 : OOB;
+        b_lds[i] = j < P::NBI ? (uint32_t)(sub * P::SUB_BYTES + P::A_BYTES + t * P::BSLOT + piece * 1024)
+                              : (uint32_t)0xFFFFFFFFu;
     }
 
     int zc[TN];
@@ -368,8 +384,8 @@ __global__ __launch_bounds__(WGM* WGN * 64, (TM * TN <= 8 ? 2 : 1)) void gemm_ke
     // Every wave issues exactly OPS loads per stage (padding loads go to the sink), so that "at most
     // (S-2)*OPS loads outstanding" means "the oldest stage in flight has landed" for every wave alike.
     auto issue = [&](int stage, int buf) {
-        const int soff_a = __builtin_amdgcn_readfirstlane(stage * 128);
-        const int soff_b = __builtin_amdgcn_readfirstlane(stage * CH * TILE_B);
+        const int soff_a = __builtin_amdgcn_readfirstlane(stage * KS * 128);
+        const int soff_b = __builtin_amdgcn_readfirstlane(stage * KS * CH * TILE_B);
         const uint32_t sb = lds_base + buf * STAGE_BYTES;
 #pragma unroll
         for (int i = 0; i < P::DMA_A; ++i)
@@ -392,7 +408,8 @@ __global__ __launch_bounds__(WGM* WGN * 64, (TM * TN <= 8 ? 2 : 1)) void gemm_ke
 
     long long t0 = 0, t1 = 0, t2 = 0;
     if (g.phase_clk) t0 = clock64();
-    const int KT = g.k_stages;
+    const int KSTEPS = g.k_stages;                // 128-byte k steps
+    const int KT = (KSTEPS + KS - 1) / KS;        // pipeline stages
 #pragma unroll
     for (int s = 0; s < S - 1; ++s)
         if (s < KT) issue(s, s);
@@ -414,7 +431,11 @@ __global__ __launch_bounds__(WGM* WGN * 64, (TM * TN <= 8 ? 2 : 1)) void gemm_ke
         // Multiply the stage.  On this hardware an LDS read into registers, a vector ALU instruction and an MFMA
         // all take turns on the SIMD, so the only latency worth hiding is that of the LDS reads: the fragments of
         // step s+1 are requested before the MFMAs of step s are issued (two register sets for the activations).
-        const uint8_t* abuf = lds + buf * STAGE_BYTES;
+        const uint8_t* abuf = lds + buf * STAGE_BYTES + grp * P::SUB_BYTES;
+        if (KS > 1 && kt * KS + grp >= KSTEPS) {  // odd tail: this group's k step does not exist
+            buf = buf + 1 == S ? 0 : buf + 1;
+            continue;
+        }
         WChunk<BITS> wq[TN][CH];
         frag_t xf[2][TM];
 #pragma unroll
@@ -460,7 +481,41 @@ __global__ __launch_bounds__(WGM* WGN * 64, (TM * TN <= 8 ? 2 : 1)) void gemm_ke
         }
         buf = buf + 1 == S ? 0 : buf + 1;
     }
-    __syncthreads();  // every wave is done reading the stages: the epilogue may overwrite them
+    __syncthreads();  // every wave is done reading the stages: what follows may overwrite them
+
+    if constexpr (KS == 2) {
+        // group 1 hands its accumulators to group 0 through LDS ([register quad][lane], 16 bytes per lane)
+        uint8_t* xch = lds + wvg * (TM * TN * 4 * 1024) + lane * 16;
+        if (grp == 1) {
+#pragma unroll
+            for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+                for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        using quad_t = typename std::conditional<I8, int4v, float4v>::type;
+                        quad_t v;
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) v[r] = acc[tm][tn][4 * q + r];
+                        *(quad_t*)(xch + ((tm * TN + tn) * 4 + q) * 1024) = v;
+                    }
+        }
+        __syncthreads();
+        if (grp == 0) {
+#pragma unroll
+            for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+                for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        using quad_t = typename std::conditional<I8, int4v, float4v>::type;
+                        const quad_t v = *(const quad_t*)(xch + ((tm * TN + tn) * 4 + q) * 1024);
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) acc[tm][tn][4 * q + r] += v[r];
+                    }
+        }
+        __syncthreads();
+    }
 
     if (g.phase_clk) t2 = clock64();
     // ---------------------------------------------------------------- epilogue
@@ -474,8 +529,8 @@ __global__ __launch_bounds__(WGM* WGN * 64, (TM * TN <= 8 ? 2 : 1)) void gemm_ke
     constexpr int ROWS_PER_PASS = 64 / CPR;     // rows one store instruction covers
     static_assert(64 % CPR == 0, "TN must be 1, 2 or 4");
     constexpr int EP_BYTES = 32 * CPR * 16;     // staging bytes per wave
-    static_assert(NW * EP_BYTES <= S * STAGE_BYTES, "epilogue staging must fit the LDS stages");
-    uint8_t* ep = lds + wv * EP_BYTES;
+    static_assert(P::NWG * EP_BYTES <= S * STAGE_BYTES, "epilogue staging must fit the LDS stages");
+    uint8_t* ep = lds + wvg * EP_BYTES;
 
     // Per-channel epilogue constants of the workgroup's BN channels, computed once by BN threads and parked in
     // LDS behind the stages: multiplier, additive term and (int8) the two zero-point corrections.
@@ -507,6 +562,7 @@ __global__ __launch_bounds__(WGM* WGN * 64, (TM * TN <= 8 ? 2 : 1)) void gemm_ke
     const int nw0 = n0 + wn * TN * 32;  // first channel of this wave
 #pragma unroll
     for (int tm = 0; tm < TM; ++tm) {
+        if (KS > 1 && grp != 0) break;  // the finished sums live in group 0
         const int mt0 = m0 + (wm * TM + tm) * 32;  // first row of this 32-row slab
         int rsum = 0;
         if constexpr (I8) {
@@ -569,6 +625,7 @@ __global__ __launch_bounds__(WGM* WGN * 64, (TM * TN <= 8 ? 2 : 1)) void gemm_ke
 // ---------------------------------------------------------------------------------------------
 // Tile table.  index -> workgroup tile (rows x channels), waves, wave tile:
 //   0: 128x256, 4 waves (1x4) of 128x64     1: 128x128, 4 waves (2x2) of 64x64     2: 64x64, 4 waves of 32x32
+//   3: as 1 and 4: as 2, with a second wave group splitting k inside the workgroup (8 waves)
 // A tall wave tile pays: every widened weight fragment then feeds 4 MFMAs (measured: LDS reads into registers,
 // vector ALU instructions and MFMAs take turns on a SIMD, they do not overlap).  256x256 tiles with one wave per
 // SIMD and 128x128 tiles with two-wave workgroups were measured slower on every configured shape.
@@ -583,39 +640,41 @@ void set_phase_buffer(long long* p, long workgroups) {
 }
 void set_force_tile(int t) { g_force_tile = t; }
 
-static int pick_tile(int M, int N) {
-    if (g_force_tile >= 0 && g_force_tile <= 2) return g_force_tile;
+// Measured on the SDXL shapes: the large tile wins once it yields two or more workgroups per compute unit; the
+// k-split variants only pay where tiles are few and k is long (FF-out at the 640 level, the K/V projections).
+static int pick_tile(int M, int N, int K) {
+    if (g_force_tile >= 0 && g_force_tile <= 4) return g_force_tile;
     const long t0 = (long)((M + 127) / 128) * ((N + 255) / 256);
     if (t0 >= 512) return 0;
     const long t1 = (long)((M + 127) / 128) * ((N + 127) / 128);
-    if (t1 >= 128) return 1;
-    return 2;
+    if (t1 >= 128) return (t1 < 256 && K >= 2048) ? 3 : 1;
+    return K >= 1024 ? 4 : 2;
 }
 
-template <bool I8, int BITS, int WGM, int WGN, int TM, int TN, int S>
+template <bool I8, int BITS, int WGM, int WGN, int TM, int TN, int S, int KS>
 constexpr bool stages_fit(int budget) {
-    using P = GemmPlan<I8, BITS, WGM, WGN, TM, TN, S>;
+    using P = GemmPlan<I8, BITS, WGM, WGN, TM, TN, S, KS>;
     return P::LDS_BYTES <= budget && (S - 2) * P::OPS <= 63;
 }
 
-template <bool I8, int BITS, int WGM, int WGN, int TM, int TN>
+template <bool I8, int BITS, int WGM, int WGN, int TM, int TN, int KS>
 constexpr int pick_stages(int budget, int max_stages) {
-    if (max_stages >= 8 && stages_fit<I8, BITS, WGM, WGN, TM, TN, 8>(budget)) return 8;
-    if (max_stages >= 6 && stages_fit<I8, BITS, WGM, WGN, TM, TN, 6>(budget)) return 6;
-    if (max_stages >= 4 && stages_fit<I8, BITS, WGM, WGN, TM, TN, 4>(budget)) return 4;
-    if (stages_fit<I8, BITS, WGM, WGN, TM, TN, 3>(budget)) return 3;
+    if (max_stages >= 8 && stages_fit<I8, BITS, WGM, WGN, TM, TN, 8, KS>(budget)) return 8;
+    if (max_stages >= 6 && stages_fit<I8, BITS, WGM, WGN, TM, TN, 6, KS>(budget)) return 6;
+    if (max_stages >= 4 && stages_fit<I8, BITS, WGM, WGN, TM, TN, 4, KS>(budget)) return 4;
+    if (stages_fit<I8, BITS, WGM, WGN, TM, TN, 3, KS>(budget)) return 3;
     return 2;
 }
 
-template <bool I8, int BITS, int WGM, int WGN, int TM, int TN, int BUDGET, int MAXS>
+template <bool I8, int BITS, int WGM, int WGN, int TM, int TN, int KS, int BUDGET, int MAXS>
 static int run_gemm(GemmArgs& g, int tile_index, hipStream_t st) {
-    constexpr int S = pick_stages<I8, BITS, WGM, WGN, TM, TN>(BUDGET, MAXS);
-    using P = GemmPlan<I8, BITS, WGM, WGN, TM, TN, S>;
+    constexpr int S = pick_stages<I8, BITS, WGM, WGN, TM, TN, KS>(BUDGET, MAXS);
+    using P = GemmPlan<I8, BITS, WGM, WGN, TM, TN, S, KS>;
     static_assert(P::LDS_BYTES <= 160 * 1024, "LDS plan exceeds the compute unit");
     g.tiles_m = (g.M + P::BM - 1) / P::BM;
     g.tiles_n = (g.N + P::BN - 1) / P::BN;
     g.phase_clk = ((long)g.tiles_m * g.tiles_n <= g_phase_cap) ? g_phase_clk : nullptr;
-    auto kern = gemm_kernel<I8, BITS, WGM, WGN, TM, TN, S>;
+    auto kern = gemm_kernel<I8, BITS, WGM, WGN, TM, TN, S, KS>;
     static bool prepared = false;  // once per instantiation: allow more than 64 KB of dynamic LDS, name the slot
     const int slot = prof_gemm_slot(I8 ? 1 : 0, BITS, tile_index);
     if (!prepared) {
@@ -625,8 +684,8 @@ static int run_gemm(GemmArgs& g, int tile_index, hipStream_t st) {
             return MQ_ERR_HIP;
         }
         char name[96];
-        snprintf(name, sizeof name, "mq::gemm_kernel<%s, %d, %d, %d, %d, %d, %d>", I8 ? "true" : "false", BITS, WGM,
-                 WGN, TM, TN, S);
+        snprintf(name, sizeof name, "mq::gemm_kernel<%s, %d, %d, %d, %d, %d, %d, %d>", I8 ? "true" : "false", BITS,
+                 WGM, WGN, TM, TN, S, KS);
         prof_name_slot(slot, name);
         prepared = true;
     }
@@ -640,10 +699,12 @@ static int run_gemm(GemmArgs& g, int tile_index, hipStream_t st) {
 
 template <bool I8, int BITS>
 static int dispatch_gemm(GemmArgs& g, hipStream_t st) {
-    switch (pick_tile(g.M, g.N)) {
-        case 0: return run_gemm<I8, BITS, 1, 4, 4, 2, 80 * 1024, 4>(g, 0, st);
-        case 1: return run_gemm<I8, BITS, 2, 2, 2, 2, 80 * 1024, 4>(g, 1, st);
-        default: return run_gemm<I8, BITS, 2, 2, 1, 1, 80 * 1024, 8>(g, 2, st);
+    switch (pick_tile(g.M, g.N, g.K)) {
+        case 0: return run_gemm<I8, BITS, 1, 4, 4, 2, 1, 80 * 1024, 4>(g, 0, st);
+        case 1: return run_gemm<I8, BITS, 2, 2, 2, 2, 1, 80 * 1024, 4>(g, 1, st);
+        case 2: return run_gemm<I8, BITS, 2, 2, 1, 1, 1, 80 * 1024, 8>(g, 2, st);
+        case 3: return run_gemm<I8, BITS, 2, 2, 2, 2, 2, 160 * 1024, 4>(g, 3, st);
+        default: return run_gemm<I8, BITS, 2, 2, 1, 1, 2, 80 * 1024, 8>(g, 4, st);
     }
 }
 

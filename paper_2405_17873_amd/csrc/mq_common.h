@@ -90,10 +90,12 @@ void set_force_tile(int t);
 void set_phase_buffer(long long* p, long workgroups);
 
 // ---- optional per-kernel event timing (prof.hip) ----
-enum { PROF_ACT_MINMAX = 24, PROF_ACT_QUANTIZE = 25, PROF_BOS_ROWS = 26 };
+enum { PROF_ACT_MINMAX = 40, PROF_ACT_QUANTIZE = 41, PROF_BOS_ROWS = 42 };
 int prof_num_slots();
 int prof_gemm_slot(int family /*0 weight-only, 1 int8*/, int bits, int tile);
 bool prof_enabled();
+bool prof_wants(int slot);
+int prof_filter(int slot, int stride);
 void prof_name_slot(int slot, const char* name);
 int prof_enable(int on);
 bool prof_begin(hipStream_t st, hipEvent_t* a, hipEvent_t* b);
@@ -108,7 +110,7 @@ struct ProfScope {
     hipStream_t st;
     double ops, bytes;
     ProfScope(hipStream_t s, int slot_, double ops_, double bytes_) : slot(slot_), st(s), ops(ops_), bytes(bytes_) {
-        if (prof_enabled()) open = prof_begin(st, &a, &b);
+        if (prof_enabled() && prof_wants(slot)) open = prof_begin(st, &a, &b);
     }
     ~ProfScope() {
         if (open) prof_end(a, b, st, slot, ops, bytes);

@@ -21,6 +21,9 @@ struct Slot {
 };
 std::mutex g_mu;
 bool g_on = false;
+int g_filter_slot = -1;   // -1: every kernel; else only launches of this slot ...
+int g_filter_stride = 1;  // ... and of those only every stride-th
+long g_filter_count = 0;
 std::vector<Slot> g_slots;
 std::vector<Pair> g_free;
 
@@ -33,14 +36,31 @@ void init_slots() {
 }
 }  // namespace
 
-int prof_num_slots() { return 27; }
+int prof_num_slots() { return 43; }
 
 int prof_gemm_slot(int family, int bits, int tile) {
     const int b = bits == 2 ? 0 : bits == 3 ? 1 : bits == 4 ? 2 : 3;
-    return (family * 4 + b) * 3 + tile;
+    return (family * 4 + b) * 5 + tile;
 }
 
 bool prof_enabled() { return g_on; }
+
+bool prof_wants(int slot) {
+    if (g_filter_slot < 0) return true;
+    if (slot != g_filter_slot) return false;
+    std::lock_guard<std::mutex> lk(g_mu);
+    return (g_filter_count++ % g_filter_stride) == 0;
+}
+
+int prof_filter(int slot, int stride) {
+    std::lock_guard<std::mutex> lk(g_mu);
+    init_slots();
+    if (slot >= (int)g_slots.size() || stride < 1) return MQ_ERR_BAD_ARG;
+    g_filter_slot = slot;
+    g_filter_stride = stride;
+    g_filter_count = 0;
+    return MQ_OK;
+}
 
 void prof_name_slot(int slot, const char* name) {
     std::lock_guard<std::mutex> lk(g_mu);

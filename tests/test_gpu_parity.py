@@ -128,7 +128,7 @@ W_ONLY_SHAPES = [
 
 
 @pytest.mark.parametrize("bits", ALL_BITS)
-@pytest.mark.parametrize("tile", (-1, 0, 1, 2))
+@pytest.mark.parametrize("tile", (-1, 0, 1, 2, 3, 4))
 def test_w_only_small_shapes(mq, orc, bits, tile):
     mq.tune_force_tile(tile)
     for (M, K, N) in W_ONLY_SHAPES:
@@ -199,7 +199,7 @@ A8_SHAPES = [(256, 320, 320), (1, 64, 32), (77, 128, 40), (608, 2048, 640), (300
 
 
 @pytest.mark.parametrize("mode", ("w8s", "w8a", "w4"))
-@pytest.mark.parametrize("tile", (-1, 0, 1, 2))
+@pytest.mark.parametrize("tile", (-1, 0, 1, 2, 3, 4))
 def test_a8_small_shapes(mq, orc, mode, tile):
     mq.tune_force_tile(tile)
     bits, sym = {"w8s": (8, True), "w8a": (8, False), "w4": (4, False)}[mode]
