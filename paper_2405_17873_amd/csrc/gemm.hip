@@ -413,6 +413,29 @@ __global__ __launch_bounds__(WGM* WGN* KS * 64, (TM * TN <= 8 ? 2 : 1)) void gem
 #pragma unroll
     for (int s = 0; s < S - 1; ++s)
         if (s < KT) issue(s, s);
+    // Per-channel epilogue inputs of the workgroup's BN channels: thread t fetches those of channel n0 + t now, while
+    // the first stages are in flight, and keeps them in registers; they are combined and parked in LDS after the loop.
+    static_assert(BN <= NT, "one thread per channel");
+    float c_scale = 0.0f, c_bias = 0.0f, c_sx = 1.0f;
+    int c_zp = 0, c_colsum = 0, c_zx = 0;
+    if (threadIdx.x < BN) {
+        int n = n0 + threadIdx.x;
+        n = n < g.N ? n : g.N - 1;
+        c_scale = g.w_scale[n];
+        if (g.bias) c_bias = (float)g.bias[n];
+        if constexpr (I8) {
+            c_zp = g.w_zp[n];
+            c_colsum = g.w_colsum[n];
+            c_sx = g.params->scale;
+            c_zx = g.params->zp;
+        }
+    }
+    int rsum[TM];
+#pragma unroll
+    for (int tm = 0; tm < TM; ++tm) {
+        const int m = m0 + (wm * TM + tm) * 32 + l31;
+        rsum[tm] = I8 ? g.rowsum[m < g.M ? m : g.M - 1] : 0;
+    }
     if (g.phase_clk) t1 = clock64();
     int buf = 0;
     for (int kt = 0; kt < KT; ++kt) {
@@ -483,6 +506,28 @@ __global__ __launch_bounds__(WGM* WGN* KS * 64, (TM * TN <= 8 ? 2 : 1)) void gem
     }
     __syncthreads();  // every wave is done reading the stages: what follows may overwrite them
 
+    // Park the per-channel constants in LDS behind the stages: multiplier, additive term and (int8) the two
+    // zero-point corrections.
+    //   weight-only: y = acc * s_w[n] + bias[n]
+    //   int8: stored operands are a' = qx - 128 and b' = qw - w_off; with dx = 128 - z_x, dw = w_off - z_w[n]:
+    //         ACC = raw + dw * rowsum_a'[m] + dx * (colsum_b'[n] + K * dw),  colsum_b' = colsum - K * w_off,
+    //         y = ACC * (s_x * s_w[n]) + bias[n].  Wrap-around int32 arithmetic is exact because ACC itself fits.
+    float* ch_mul = (float*)(lds + P::CONSTS);
+    float* ch_add = ch_mul + BN;
+    int* ch_dw = (int*)(ch_add + BN);
+    int* ch_cn = ch_dw + BN;
+    if (threadIdx.x < BN) {
+        const int t = threadIdx.x;
+        if constexpr (I8) {
+            const int dx = 128 - c_zx;
+            const int dw = g.w_off - c_zp;
+            ch_dw[t] = dw;
+            ch_cn[t] = dx * (c_colsum - g.K * g.w_off + g.K * dw);
+        }
+        ch_mul[t] = c_scale * c_sx;
+        ch_add[t] = c_bias;
+    }
+
     if constexpr (KS == 2) {
         // group 1 hands its accumulators to group 0 through LDS ([register quad][lane], 16 bytes per lane)
         uint8_t* xch = lds + wvg * (TM * TN * 4 * 1024) + lane * 16;
@@ -517,6 +562,7 @@ __global__ __launch_bounds__(WGM* WGN* KS * 64, (TM * TN <= 8 ? 2 : 1)) void gem
         __syncthreads();
     }
 
+    if constexpr (KS == 1) __syncthreads();  // constants visible (the k-split exchange above has its own barriers)
     if (g.phase_clk) t2 = clock64();
     // ---------------------------------------------------------------- epilogue
     // Result element v of a lane is channel 8*(v/4) + 4*kb + v%4 of its 32-channel tile, activation row l31:
@@ -532,43 +578,11 @@ __global__ __launch_bounds__(WGM* WGN* KS * 64, (TM * TN <= 8 ? 2 : 1)) void gem
     static_assert(P::NWG * EP_BYTES <= S * STAGE_BYTES, "epilogue staging must fit the LDS stages");
     uint8_t* ep = lds + wvg * EP_BYTES;
 
-    // Per-channel epilogue constants of the workgroup's BN channels, computed once by BN threads and parked in
-    // LDS behind the stages: multiplier, additive term and (int8) the two zero-point corrections.
-    //   weight-only: y = acc * s_w[n] + bias[n]
-    //   int8: stored operands are a' = qx - 128 and b' = qw - w_off; with dx = 128 - z_x, dw = w_off - z_w[n]:
-    //         ACC = raw + dw * rowsum_a'[m] + dx * (colsum_b'[n] + K * dw),  colsum_b' = colsum - K * w_off,
-    //         y = ACC * (s_x * s_w[n]) + bias[n].  Wrap-around int32 arithmetic is exact because ACC itself fits.
-    float* ch_mul = (float*)(lds + P::CONSTS);
-    float* ch_add = ch_mul + BN;
-    int* ch_dw = (int*)(ch_add + BN);
-    int* ch_cn = ch_dw + BN;
-    for (int t = threadIdx.x; t < BN; t += NT) {
-        int n = n0 + t;
-        n = n < g.N ? n : g.N - 1;
-        float mul = g.w_scale[n];
-        if constexpr (I8) {
-            const float sx = g.params->scale;
-            const int dx = 128 - g.params->zp;
-            const int dw = g.w_off - g.w_zp[n];
-            ch_dw[t] = dw;
-            ch_cn[t] = dx * (g.w_colsum[n] - g.K * g.w_off + g.K * dw);
-            mul *= sx;
-        }
-        ch_mul[t] = mul;
-        ch_add[t] = g.bias ? (float)g.bias[n] : 0.0f;
-    }
-    __syncthreads();
-
     const int nw0 = n0 + wn * TN * 32;  // first channel of this wave
 #pragma unroll
     for (int tm = 0; tm < TM; ++tm) {
         if (KS > 1 && grp != 0) break;  // the finished sums live in group 0
         const int mt0 = m0 + (wm * TM + tm) * 32;  // first row of this 32-row slab
-        int rsum = 0;
-        if constexpr (I8) {
-            const int m = mt0 + l31;
-            rsum = g.rowsum[m < g.M ? m : g.M - 1];
-        }
 #pragma unroll
         for (int tn = 0; tn < TN; ++tn)
 #pragma unroll
@@ -583,7 +597,8 @@ __global__ __launch_bounds__(WGM* WGN* KS * 64, (TM * TN <= 8 ? 2 : 1)) void gem
                     int4v a;
 #pragma unroll
                     for (int r = 0; r < 4; ++r) {
-                        a[r] = acc[tm][tn][4 * q + r] + dw[r] * rsum + cn[r];
+                        // |dw| <= 255 and |rowsum| <= 128 * K < 2^23: a 24-bit multiply (full rate) is exact
+                        a[r] = acc[tm][tn][4 * q + r] + __mul24(dw[r], rsum[tm]) + cn[r];
                         o[r] = (_Float16)((float)a[r] * mul[r] + add[r]);
                     }
                     if (g.acc_debug) {
