@@ -36,6 +36,7 @@ typedef int int4v __attribute__((ext_vector_type(4)));
 typedef uint32_t uint4v __attribute__((ext_vector_type(4)));
 typedef uint32_t uint2v __attribute__((ext_vector_type(2)));
 typedef uint32_t uint3v __attribute__((ext_vector_type(3)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
 // Swizzle of the 16-byte piece index inside a 128-byte LDS row.  Distinct over any 8 consecutive rows and,
 // together with the row parity, over any 16 consecutive rows.
@@ -151,6 +152,22 @@ __device__ __forceinline__ half8 dequant_step<8>(const WChunk<8>& c, int s, int 
     return half8{p0[0], p0[1], p1[0], p1[1], p2[0], p2[1], p3[0], p3[1]};
 }
 
+// bfloat16 variant: the widened weights are small integers (|q - z| <= 255), exact in fp16 and in bf16 alike, so
+// the fp16 fragment is converted pair by pair: two fp16 -> fp32 conversions and one byte permute that keeps the
+// upper halves (which for these values is the exact bf16).
+__device__ __forceinline__ bf16x8 half8_to_bf16x8(half8 h) {
+    uint4v o;
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+        const uint32_t f0 = __float_as_uint((float)h[2 * p]), f1 = __float_as_uint((float)h[2 * p + 1]);
+        o[p] = __builtin_amdgcn_perm(f1, f0, 0x07060302u);
+    }
+    return __builtin_bit_cast(bf16x8, o);
+}
+
+__device__ __forceinline__ float bf16_bits_to_float(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
+__device__ __forceinline__ uint16_t float_to_bf16_bits(float f) { return __builtin_bit_cast(uint16_t, (__bf16)f); }
+
 // ---------------------------------------------------------------------------------------------
 // Buffer addressing.  Both operands are read through buffer resources: a lane's offset is a 32-bit
 // register computed once, the k advance is a scalar offset, and anything past the end of the buffer reads
@@ -247,8 +264,8 @@ struct GemmArgs {
     int k_stages;         // number of 128-byte stages
     const float* w_scale;
     const int32_t* w_zp;
-    const _Float16* bias;
-    _Float16* y;
+    const uint16_t* bias;  // fp16 or bf16 bits
+    uint16_t* y;
     long ldy;
     int tiles_m, tiles_n;
     // int8 only
@@ -305,8 +322,9 @@ struct GemmPlan {
     static_assert(KS == 1 || NWG * TM * TN * 1024 <= S * STAGE_BYTES, "accumulator exchange must fit the stages");
 };
 
-template <bool I8, int BITS, int WGM, int WGN, int TM, int TN, int S, int KS>
+template <bool I8, int BITS, int WGM, int WGN, int TM, int TN, int S, int KS, bool BF = false>
 __global__ __launch_bounds__(WGM* WGN* KS * 64, (TM * TN <= 8 ? 2 : 1)) void gemm_kernel(const GemmArgs g) {
+    static_assert(!(I8 && BF), "the int8 path writes fp16");
     using P = GemmPlan<I8, BITS, WGM, WGN, TM, TN, S, KS>;
     constexpr int NW = P::NW, NT = P::NT, BM = P::BM, BN = P::BN, CH = P::CH;
     constexpr int STAGE_BYTES = P::STAGE_BYTES;
@@ -422,7 +440,7 @@ __global__ __launch_bounds__(WGM* WGN* KS * 64, (TM * TN <= 8 ? 2 : 1)) void gem
         int n = n0 + threadIdx.x;
         n = n < g.N ? n : g.N - 1;
         c_scale = g.w_scale[n];
-        if (g.bias) c_bias = (float)g.bias[n];
+        if (g.bias) c_bias = BF ? bf16_bits_to_float(g.bias[n]) : (float)__builtin_bit_cast(_Float16, g.bias[n]);
         if constexpr (I8) {
             c_zp = g.w_zp[n];
             c_colsum = g.w_colsum[n];
@@ -488,6 +506,7 @@ __global__ __launch_bounds__(WGM* WGN* KS * 64, (TM * TN <= 8 ? 2 : 1)) void gem
                     wf[tn] = widen_step<BITS>(wq[tn][s >> 1], s & 1, xflip);
                 else
                     wf[tn] = dequant_step<BITS>(wq[tn][0], s, zc[tn]);
+                if constexpr (BF) wf[tn] = __builtin_bit_cast(half8, half8_to_bf16x8(wf[tn]));  // bf16 bits from here on
             }
 #pragma unroll
             for (int tm = 0; tm < TM; ++tm)
@@ -496,6 +515,9 @@ __global__ __launch_bounds__(WGM* WGN* KS * 64, (TM * TN <= 8 ? 2 : 1)) void gem
                     if constexpr (I8)
                         acc[tm][tn] =
                             __builtin_amdgcn_mfma_i32_32x32x32_i8(wf[tn], xf[s & 1][tm], acc[tm][tn], 0, 0, 0);
+                    else if constexpr (BF)
+                        acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                            __builtin_bit_cast(bf16x8, wf[tn]), __builtin_bit_cast(bf16x8, xf[s & 1][tm]), acc[tm][tn], 0, 0, 0);
                     else
                         acc[tm][tn] =
                             __builtin_amdgcn_mfma_f32_32x32x16_f16(wf[tn], xf[s & 1][tm], acc[tm][tn], 0, 0, 0);
@@ -607,7 +629,13 @@ __global__ __launch_bounds__(WGM* WGN* KS * 64, (TM * TN <= 8 ? 2 : 1)) void gem
                     }
                 } else {
 #pragma unroll
-                    for (int r = 0; r < 4; ++r) o[r] = (_Float16)(acc[tm][tn][4 * q + r] * mul[r] + add[r]);
+                    for (int r = 0; r < 4; ++r) {
+                        const float v = acc[tm][tn][4 * q + r] * mul[r] + add[r];
+                        if constexpr (BF)
+                            o[r] = __builtin_bit_cast(_Float16, float_to_bf16_bits(v));  // bits only
+                        else
+                            o[r] = (_Float16)v;
+                    }
                 }
                 const int chunk = tn * 4 + q;
                 *(half4*)(ep + l31 * (CPR * 16) + (((chunk ^ l31) & (CPR - 1)) << 4) + kb * 8) = o;
@@ -681,7 +709,7 @@ constexpr int pick_stages(int budget, int max_stages) {
     return 2;
 }
 
-template <bool I8, int BITS, int WGM, int WGN, int TM, int TN, int KS, int BUDGET, int MAXS>
+template <bool I8, int BITS, int WGM, int WGN, int TM, int TN, int KS, int BUDGET, int MAXS, bool BF = false>
 static int run_gemm(GemmArgs& g, int tile_index, hipStream_t st) {
     constexpr int S = pick_stages<I8, BITS, WGM, WGN, TM, TN, KS>(BUDGET, MAXS);
     using P = GemmPlan<I8, BITS, WGM, WGN, TM, TN, S, KS>;
@@ -689,9 +717,9 @@ static int run_gemm(GemmArgs& g, int tile_index, hipStream_t st) {
     g.tiles_m = (g.M + P::BM - 1) / P::BM;
     g.tiles_n = (g.N + P::BN - 1) / P::BN;
     g.phase_clk = ((long)g.tiles_m * g.tiles_n <= g_phase_cap) ? g_phase_clk : nullptr;
-    auto kern = gemm_kernel<I8, BITS, WGM, WGN, TM, TN, S, KS>;
+    auto kern = gemm_kernel<I8, BITS, WGM, WGN, TM, TN, S, KS, BF>;
     static bool prepared = false;  // once per instantiation: allow more than 64 KB of dynamic LDS, name the slot
-    const int slot = prof_gemm_slot(I8 ? 1 : 0, BITS, tile_index);
+    const int slot = prof_gemm_slot(I8 ? 1 : (BF ? 2 : 0), BITS, tile_index);
     if (!prepared) {
         if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, P::LDS_BYTES) !=
             hipSuccess) {
@@ -699,8 +727,8 @@ static int run_gemm(GemmArgs& g, int tile_index, hipStream_t st) {
             return MQ_ERR_HIP;
         }
         char name[96];
-        snprintf(name, sizeof name, "mq::gemm_kernel<%s, %d, %d, %d, %d, %d, %d, %d>", I8 ? "true" : "false", BITS,
-                 WGM, WGN, TM, TN, S, KS);
+        snprintf(name, sizeof name, "mq::gemm_kernel<%s, %d, %d, %d, %d, %d, %d, %d, %s>", I8 ? "true" : "false", BITS,
+                 WGM, WGN, TM, TN, S, KS, BF ? "true" : "false");
         prof_name_slot(slot, name);
         prepared = true;
     }
@@ -723,10 +751,20 @@ static int dispatch_gemm(GemmArgs& g, hipStream_t st) {
     }
 }
 
+// bfloat16 activations: the three plain tiles (the k-split variants fall back to their plain counterparts).
+template <int BITS>
+static int dispatch_gemm_bf16(GemmArgs& g, hipStream_t st) {
+    const int t = pick_tile(g.M, g.N, g.K);
+    switch (t >= 3 ? t - 2 : t) {
+        case 0: return run_gemm<false, BITS, 1, 4, 4, 2, 1, 80 * 1024, 4, true>(g, 0, st);
+        case 1: return run_gemm<false, BITS, 2, 2, 2, 2, 1, 80 * 1024, 4, true>(g, 1, st);
+        default: return run_gemm<false, BITS, 2, 2, 1, 1, 1, 80 * 1024, 8, true>(g, 2, st);
+    }
+}
+
 int launch_gemm_w_only(const void* x, int M, int K, int ldx, const void* packed, int N, int bits,
                        const float* w_scale, const int32_t* w_zp, const void* bias, void* y, int ldy, int dtype,
                        hipStream_t st) {
-    (void)dtype;
     GemmArgs g{};
     g.a = x;
     g.a_row_bytes = (long)ldx * 2;
@@ -735,8 +773,17 @@ int launch_gemm_w_only(const void* x, int M, int K, int ldx, const void* packed,
     g.packed_bytes = (uint32_t)((long)((N + 31) / 32) * (K / 64) * 256 * bits);
     g.M = M; g.N = N; g.K = K;
     g.k_stages = K / 64;
-    g.w_scale = w_scale; g.w_zp = w_zp; g.bias = (const _Float16*)bias;
-    g.y = (_Float16*)y; g.ldy = ldy;
+    g.w_scale = w_scale; g.w_zp = w_zp; g.bias = (const uint16_t*)bias;
+    g.y = (uint16_t*)y; g.ldy = ldy;
+    if (dtype == MQ_BF16) {
+        switch (bits) {
+            case 2: return dispatch_gemm_bf16<2>(g, st);
+            case 3: return dispatch_gemm_bf16<3>(g, st);
+            case 4: return dispatch_gemm_bf16<4>(g, st);
+            case 8: return dispatch_gemm_bf16<8>(g, st);
+        }
+        return MQ_ERR_UNSUPPORTED_BITS;
+    }
     switch (bits) {
         case 2: return dispatch_gemm<false, 2>(g, st);
         case 3: return dispatch_gemm<false, 3>(g, st);
@@ -759,8 +806,8 @@ int launch_gemm_a8(const int8_t* a8, const int32_t* rowsum, const ActParams* par
     g.packed_bytes = (uint32_t)((long)((N + 31) / 32) * (K / 64) * 256 * w_bits);
     g.M = M; g.N = N; g.K = K;
     g.k_stages = Kp / 128;
-    g.w_scale = w_scale; g.w_zp = w_zp; g.bias = (const _Float16*)bias;
-    g.y = (_Float16*)y; g.ldy = ldy;
+    g.w_scale = w_scale; g.w_zp = w_zp; g.bias = (const uint16_t*)bias;
+    g.y = (uint16_t*)y; g.ldy = ldy;
     g.rowsum = rowsum; g.params = params; g.w_colsum = w_colsum;
     g.out_map = out_map; g.acc_debug = acc_debug;
     if (w_bits == 4) {

@@ -90,9 +90,9 @@ void set_force_tile(int t);
 void set_phase_buffer(long long* p, long workgroups);
 
 // ---- optional per-kernel event timing (prof.hip) ----
-enum { PROF_ACT_MINMAX = 40, PROF_ACT_QUANTIZE = 41, PROF_BOS_ROWS = 42 };
+enum { PROF_ACT_MINMAX = 60, PROF_ACT_QUANTIZE = 61, PROF_BOS_ROWS = 62 };
 int prof_num_slots();
-int prof_gemm_slot(int family /*0 weight-only, 1 int8*/, int bits, int tile);
+int prof_gemm_slot(int family /*0 weight-only fp16, 1 int8, 2 weight-only bf16*/, int bits, int tile);
 bool prof_enabled();
 bool prof_wants(int slot);
 int prof_filter(int slot, int stride);

@@ -36,7 +36,7 @@ void init_slots() {
 }
 }  // namespace
 
-int prof_num_slots() { return 43; }
+int prof_num_slots() { return 63; }
 
 int prof_gemm_slot(int family, int bits, int tile) {
     const int b = bits == 2 ? 0 : bits == 3 ? 1 : bits == 4 ? 2 : 3;

@@ -160,6 +160,31 @@ def test_w_only_exact_integer_case(mq, orc):
         assert np.array_equal(y.astype(np.float64), ref.astype(np.float16).astype(np.float64)), bits
 
 
+def test_w_only_bf16(mq, orc):
+    """bfloat16 activations, bias and output (fp32 accumulate); weights quantised from bf16 as well."""
+    for (M, K, N, tile) in ((256, 320, 320, -1), (300, 640, 640, 1), (77, 128, 40, 2), (513, 2048, 264, 0)):
+        mq.tune_force_tile(tile)
+        xb = torch.from_numpy(si.normal(21, f"bf/x{M}", (M, K)).astype(np.float32)).to(torch.bfloat16)
+        wb = torch.from_numpy(si.normal(21, f"bf/w{N}", (N, K), 0.02).astype(np.float32)).to(torch.bfloat16)
+        bb = torch.from_numpy(si.normal(21, f"bf/b{N}", (N,), 0.01).astype(np.float32)).to(torch.bfloat16)
+        bits16 = lambda t: t.view(torch.int16).numpy().view(np.uint16)
+        for bits in ALL_BITS:
+            c, s, z = mq.quantize_weights(wb.cuda(), bits)
+            oc, os_, oz = orc.quantize_weights(bits16(wb), bits, dtype=orc.BF16)
+            assert np.array_equal(host(c), oc) and np.array_equal(host(s), os_) and np.array_equal(host(z), oz)
+            packed, cs = mq.pack_weights(c, bits, mq.LAYOUT_KERNEL)
+            pw = mq.PackedWeight(packed, s, z, cs, N, K, bits, mq.LAYOUT_KERNEL, False)
+            y = mq.qlinear_w_only(xb.cuda(), pw, bb.cuda())
+            assert y.dtype == torch.bfloat16
+            ref = orc.linear_w_only(bits16(xb), oc, os_, oz, bits16(bb), dtype=orc.BF16)
+            got = host(y.float()).astype(np.float64)
+            want = torch.from_numpy(ref.view(np.int16)).view(torch.bfloat16).float().numpy().astype(np.float64)
+            fro = np.linalg.norm(got - want) / np.linalg.norm(want)
+            elt = np.abs(got - want).max() / np.abs(want).max()
+            assert fro <= FRO_TOL and elt <= ELT_TOL, f"bf16 b{bits} {M}x{K}x{N}: fro={fro:.3e} elt={elt:.3e}"
+    mq.tune_force_tile(-1)
+
+
 def test_w_only_strided_views(mq, orc):
     M, K, N = 130, 128, 64
     xbig = si.activations_f16(12, "wo/xs", M, K + 64)
