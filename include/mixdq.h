@@ -68,6 +68,13 @@ int mq_prof_reset(void);
  * reports whole-run throughput restricts the bracketing: only launches of `slot` (-1: every kernel), and of those
  * only every `stride`-th.  Totals then cover the bracketed launches only. */
 int mq_prof_filter(int slot, int stride);
+/* Microseconds an event pair adds to the kernel it brackets, measured (once, synchronising on `stream`) with a
+ * one-workgroup kernel that spins for 20 us of the constant 100 MHz clock.  Subtract it from a bracketed average
+ * to compare with a profiler's kernel durations. */
+double mq_prof_bracket_overhead_us(void* stream);
+/* A plain device-to-device copy kernel (kernel name mq::prof_copy_kernel) of `bytes` bytes (multiple of 16, 16-byte
+ * aligned pointers): the known-size reference that hardware HBM traffic counters are scaled by. */
+int mq_prof_copy(void* dst, const void* src, size_t bytes, void* stream);
 
 /* Phase timing inside the GEMM kernels: while clk != NULL every GEMM launch with at most `workgroups` workgroups
  * writes four shader-clock samples per workgroup (start, main loop entered, epilogue entered, end) to

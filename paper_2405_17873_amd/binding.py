@@ -21,7 +21,7 @@ _ERRORS = {
 }
 
 EXPORTS = ("mq_version", "mq_last_hip_error", "mq_tune_force_tile", "mq_prof_enable", "mq_prof_num_slots", "mq_prof_read",
-           "mq_prof_reset", "mq_prof_phase_buffer", "mq_prof_filter", "mq_quantize_weights", "mq_packed_bytes", "mq_pack_weights",
+           "mq_prof_reset", "mq_prof_phase_buffer", "mq_prof_filter", "mq_prof_bracket_overhead_us", "mq_prof_copy", "mq_quantize_weights", "mq_packed_bytes", "mq_pack_weights",
            "mq_unpack_weights", "mq_qlinear_w_only", "mq_qlinear_a8_workspace_bytes", "mq_qlinear_w8a8",
            "mq_qlinear_w4a8", "mq_bos_aware_kv_proj_workspace_bytes", "mq_bos_aware_kv_proj")
 
@@ -48,6 +48,7 @@ def load():
         _lib = C.CDLL(_LIB_PATH)
         for name in ("mq_packed_bytes", "mq_qlinear_a8_workspace_bytes", "mq_bos_aware_kv_proj_workspace_bytes"):
             getattr(_lib, name).restype = C.c_size_t
+        _lib.mq_prof_bracket_overhead_us.restype = C.c_double
     return _lib
 
 
@@ -70,6 +71,16 @@ def prof_enable(on: bool) -> None:
 
 def prof_filter(slot: int = -1, stride: int = 1) -> None:
     _check(load().mq_prof_filter(int(slot), int(stride)), "mq_prof_filter")
+
+
+def prof_bracket_overhead_us() -> float:
+    return float(load().mq_prof_bracket_overhead_us(_stream()))
+
+
+def prof_copy(dst: torch.Tensor, src: torch.Tensor) -> None:
+    nbytes = src.numel() * src.element_size()
+    assert dst.numel() * dst.element_size() == nbytes
+    _check(load().mq_prof_copy(_ptr(dst), _ptr(src), C.c_size_t(nbytes), _stream()), "mq_prof_copy")
 
 
 def prof_reset() -> None:

@@ -87,6 +87,10 @@ int mq_prof_read(int slot, char* name_host, int name_cap, long long* launches_ho
 }
 int mq_prof_reset(void) { return prof_reset(); }
 int mq_prof_filter(int slot, int stride) { return prof_filter(slot, stride); }
+int mq_prof_copy(void* dst, const void* src, size_t bytes, void* stream) {
+    return prof_copy(dst, src, bytes, (hipStream_t)stream);
+}
+double mq_prof_bracket_overhead_us(void* stream) { return prof_bracket_overhead_us((hipStream_t)stream); }
 
 int mq_quantize_weights(const void* w, int N, int K, int bits, int symmetric, int dtype, uint8_t* codes, float* scale,
                         int32_t* zp, void* stream) {

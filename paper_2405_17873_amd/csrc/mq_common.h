@@ -102,6 +102,8 @@ bool prof_begin(hipStream_t st, hipEvent_t* a, hipEvent_t* b);
 void prof_end(hipEvent_t a, hipEvent_t b, hipStream_t st, int slot, double ops, double bytes);
 int prof_read(int slot, char* name, int name_cap, long long* launches, double* ms, double* ops, double* bytes);
 int prof_reset();
+double prof_bracket_overhead_us(hipStream_t st);
+int prof_copy(void* dst, const void* src, size_t bytes, hipStream_t st);
 
 struct ProfScope {
     bool open = false;

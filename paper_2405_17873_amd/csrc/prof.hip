@@ -38,6 +38,47 @@ void init_slots() {
 
 int prof_num_slots() { return 63; }
 
+// What an event pair adds to the kernel it brackets (dispatch latency on either side): measured once, on the
+// stream given, with a single-workgroup kernel that spins for a known 20 us of the constant 100 MHz clock.
+__global__ void prof_spin_kernel(long long ticks) {
+    const long long t0 = wall_clock64();
+    while (wall_clock64() - t0 < ticks) {
+    }
+}
+
+// Plain copy of a known size: the reference that HBM traffic counters are scaled by.
+__global__ __launch_bounds__(256) void prof_copy_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, long n16) {
+    for (long i = (long)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += (long)gridDim.x * blockDim.x) dst[i] = src[i];
+}
+
+int prof_copy(void* dst, const void* src, size_t bytes, hipStream_t st) {
+    if (!dst || !src || bytes % 16 != 0 || ((uintptr_t)dst | (uintptr_t)src) % 16 != 0) return MQ_ERR_BAD_ARG;
+    hipLaunchKernelGGL(prof_copy_kernel, dim3(4096), dim3(256), 0, st, (const uint4*)src, (uint4*)dst, (long)(bytes / 16));
+    MQ_HIP_CHECK_LAUNCH();
+    return MQ_OK;
+}
+
+static double g_overhead_us = -1.0;
+
+double prof_bracket_overhead_us(hipStream_t st) {
+    if (g_overhead_us >= 0.0) return g_overhead_us;
+    hipEvent_t a, b;
+    if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) return 0.0;
+    double best = 1e30;
+    for (int i = 0; i < 12; ++i) {
+        (void)hipEventRecord(a, st);
+        hipLaunchKernelGGL(prof_spin_kernel, dim3(1), dim3(64), 0, st, 2000LL);
+        (void)hipEventRecord(b, st);
+        if (hipEventSynchronize(b) != hipSuccess) break;
+        float ms = 0;
+        if (hipEventElapsedTime(&ms, a, b) == hipSuccess && i >= 2 && ms * 1e3 < best) best = ms * 1e3;
+    }
+    (void)hipEventDestroy(a);
+    (void)hipEventDestroy(b);
+    g_overhead_us = best < 1e29 ? (best > 20.0 ? best - 20.0 : 0.0) : 0.0;
+    return g_overhead_us;
+}
+
 int prof_gemm_slot(int family, int bits, int tile) {
     const int b = bits == 2 ? 0 : bits == 3 ? 1 : bits == 4 ? 2 : 3;
     return (family * 4 + b) * 5 + tile;
