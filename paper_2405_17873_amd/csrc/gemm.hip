@@ -319,7 +319,6 @@ struct GemmPlan {
     static constexpr int CONSTS = SINK + 1024;
     static constexpr int LDS_BYTES = CONSTS + BN * 16;
     static_assert(NAI % NW == 0, "tile rows must split over the waves");
-    static_assert(KS == 1 || NWG * TM * TN * 1024 <= S * STAGE_BYTES, "accumulator exchange must fit the stages");
 };
 
 template <bool I8, int BITS, int WGM, int WGN, int TM, int TN, int S, int KS, bool BF = false>
@@ -360,7 +359,7 @@ __global__ __launch_bounds__(WGM* WGN* KS * 64, (TM * TN <= 8 ? 2 : 1)) void gem
         const int row = row0 + (lane >> 3);
         const int piece = (lane & 7) ^ swz(row);
         a_voff[i] = m0 + row < g.M ? (int)((long)(m0 + row) * g.a_row_bytes + sub * 128 + piece * 16) : OOB;
-        a_lds[i] = (uint32_t)(sub * P::SUB_BYTES + row0 * 128);
+        a_lds[i] = __builtin_amdgcn_readfirstlane((uint32_t)(sub * P::SUB_BYTES + row0 * 128));
     }
     // weight loads: instruction jj of a sub-stage copies piece jj % PCS of weight tile jj / PCS (tile = channel group,
     // chunk)
@@ -378,8 +377,8 @@ __global__ __launch_bounds__(WGM* WGN* KS * 64, (TM * TN <= 8 ? 2 : 1)) void gem
         gi = gi < G ? gi : G - 1;
         const bool on = j < P::NBI && lane < VALID_LANES;
         b_voff[i] = on ? (gi * KC + sub * CH + cc) * TILE_B + piece * 1024 + lane * 16 : OOB;
-        b_lds[i] = j < P::NBI ? (uint32_t)(sub * P::SUB_BYTES + P::A_BYTES + t * P::BSLOT + piece * 1024)
-                              : (uint32_t)0xFFFFFFFFu;
+        b_lds[i] = __builtin_amdgcn_readfirstlane(
+            j < P::NBI ? (uint32_t)(sub * P::SUB_BYTES + P::A_BYTES + t * P::BSLOT + piece * 1024) : (uint32_t)0xFFFFFFFFu);
     }
 
     int zc[TN];
@@ -399,40 +398,10 @@ __global__ __launch_bounds__(WGM* WGN* KS * 64, (TM * TN <= 8 ? 2 : 1)) void gem
 #pragma unroll
             for (int i = 0; i < 16; ++i) acc[tm][tn][i] = 0;
 
-    // Every wave issues exactly OPS loads per stage (padding loads go to the sink), so that "at most
-    // (S-2)*OPS loads outstanding" means "the oldest stage in flight has landed" for every wave alike.
-    auto issue = [&](int stage, int buf) {
-        const int soff_a = __builtin_amdgcn_readfirstlane(stage * KS * 128);
-        const int soff_b = __builtin_amdgcn_readfirstlane(stage * KS * CH * TILE_B);
-        const uint32_t sb = lds_base + buf * STAGE_BYTES;
-#pragma unroll
-        for (int i = 0; i < P::DMA_A; ++i)
-            dma_to_lds_b128(ra, __builtin_amdgcn_readfirstlane(sb + a_lds[i]), a_voff[i], soff_a);
-#pragma unroll
-        for (int i = 0; i < P::DMA_B; ++i) {
-            const uint32_t dst = b_lds[i] == 0xFFFFFFFFu ? lds_base + P::SINK : sb + b_lds[i];
-            dma_to_lds_b128(rb, __builtin_amdgcn_readfirstlane(dst), b_voff[i], soff_b);
-        }
-    };
-
-    // LDS read offsets of this lane: row l31 of the wave's first tile, one register per MFMA step
-    const int sw = swz(l31);
-    uint32_t rd[4];
-#pragma unroll
-    for (int s = 0; s < 4; ++s) {
-        const int piece = I8 ? ((s >> 1) * 4 + kb * 2 + (s & 1)) : (kb * 4 + s);
-        rd[s] = (uint32_t)(wm * TM * 32 * 128 + l31 * 128 + ((piece ^ sw) << 4));
-    }
-
-    long long t0 = 0, t1 = 0, t2 = 0;
-    if (g.phase_clk) t0 = clock64();
-    const int KSTEPS = g.k_stages;                // 128-byte k steps
-    const int KT = (KSTEPS + KS - 1) / KS;        // pipeline stages
-#pragma unroll
-    for (int s = 0; s < S - 1; ++s)
-        if (s < KT) issue(s, s);
-    // Per-channel epilogue inputs of the workgroup's BN channels: thread t fetches those of channel n0 + t now, while
-    // the first stages are in flight, and keeps them in registers; they are combined and parked in LDS after the loop.
+    // Per-channel epilogue inputs of the workgroup's BN channels: thread t fetches those of channel n0 + t now and
+    // keeps them in registers; they are combined and parked in LDS after the loop.  These ordinary loads are issued
+    // BEFORE the first LDS-writing load, so that they are the oldest entries of the vector-memory counter and the
+    // hand-counted waits below see only the stage loads behind them.
     static_assert(BN <= NT, "one thread per channel");
     float c_scale = 0.0f, c_bias = 0.0f, c_sx = 1.0f;
     int c_zp = 0, c_colsum = 0, c_zx = 0;
@@ -454,77 +423,140 @@ __global__ __launch_bounds__(WGM* WGN* KS * 64, (TM * TN <= 8 ? 2 : 1)) void gem
         const int m = m0 + (wm * TM + tm) * 32 + l31;
         rsum[tm] = I8 ? g.rowsum[m < g.M ? m : g.M - 1] : 0;
     }
+
+    // Every wave issues exactly OPS loads per stage (padding loads go to the sink), so that "at most n * OPS loads
+    // outstanding" means "all but the n youngest stages have landed" for every wave alike.
+    auto issue = [&](int stage, int buf) {
+        const int soff_a = __builtin_amdgcn_readfirstlane(stage * KS * 128);
+        const int soff_b = __builtin_amdgcn_readfirstlane(stage * KS * CH * TILE_B);
+        const uint32_t sb = lds_base + buf * STAGE_BYTES;
+#pragma unroll
+        for (int i = 0; i < P::DMA_A; ++i)
+            dma_to_lds_b128(ra, __builtin_amdgcn_readfirstlane(sb + a_lds[i]), a_voff[i], soff_a);
+#pragma unroll
+        for (int i = 0; i < P::DMA_B; ++i)
+            dma_to_lds_b128(rb, __builtin_amdgcn_readfirstlane(b_lds[i] == 0xFFFFFFFFu ? lds_base + P::SINK : sb + b_lds[i]),
+                            b_voff[i], soff_b);
+    };
+
+    // LDS read offsets of this lane: row l31 of the wave's first tile, one register per MFMA step
+    const int sw = swz(l31);
+    uint32_t rd[4];
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+        const int piece = I8 ? ((s >> 1) * 4 + kb * 2 + (s & 1)) : (kb * 4 + s);
+        rd[s] = (uint32_t)(wm * TM * 32 * 128 + l31 * 128 + ((piece ^ sw) << 4));
+    }
+
+    long long t0 = 0, t1 = 0, t2 = 0;
+    if (g.phase_clk) t0 = clock64();
+    const int KSTEPS = g.k_stages;                // 128-byte k steps
+    const int KT = (KSTEPS + KS - 1) / KS;        // pipeline stages
+#pragma unroll
+    for (int s = 0; s < S; ++s)
+        if (s < KT) issue(s, s);
     if (g.phase_clk) t1 = clock64();
-    int buf = 0;
-    for (int kt = 0; kt < KT; ++kt) {
-        // stage kt must have landed; the S-2 younger stages may stay in flight while they exist
-        if (S > 2 && kt + (S - 2) < KT)
-            wait_vmcnt<(S > 2 ? (S - 2) * P::OPS : 0)>();
-        else
-            wait_vmcnt<0>();
-        __syncthreads();
-        // refill the buffer that was multiplied in the previous iteration (everyone is past it now)
-        if (kt + S - 1 < KT) {
-            int nb = buf + S - 1;
-            nb = nb >= S ? nb - S : nb;
-            issue(kt + S - 1, nb);
-        }
-        // Multiply the stage.  On this hardware an LDS read into registers, a vector ALU instruction and an MFMA
-        // all take turns on the SIMD, so the only latency worth hiding is that of the LDS reads: the fragments of
-        // step s+1 are requested before the MFMAs of step s are issued (two register sets for the activations).
-        const uint8_t* abuf = lds + buf * STAGE_BYTES + grp * P::SUB_BYTES;
-        if (KS > 1 && kt * KS + grp >= KSTEPS) {  // odd tail: this group's k step does not exist
-            buf = buf + 1 == S ? 0 : buf + 1;
-            continue;
-        }
-        WChunk<BITS> wq[TN][CH];
-        frag_t xf[2][TM];
+
+    // Main loop.  On this hardware an LDS read into registers, a vector ALU instruction and an MFMA take turns on
+    // the SIMD, and a workgroup has one wave per SIMD, so every latency has to be covered by the wave's own MFMAs:
+    //   * the activation fragments of steps 1..3 are requested one or two steps ahead (four register sets);
+    //   * the hand-over to the next stage (wait for its loads, barrier, refill of the buffer just read, request of
+    //     its first fragments) sits in the MIDDLE of a stage, after the last LDS read of the current stage has
+    //     returned and before the MFMAs of steps 2 and 3, which then run while the barrier settles and the first
+    //     fragments of the next stage travel.
+    WChunk<BITS> wq[TN][CH];
+    frag_t xf[4][TM];
+    auto request_first = [&](const uint8_t* abuf) {
 #pragma unroll
         for (int tn = 0; tn < TN; ++tn)
-            read_chunk<BITS>(wq[tn][0], abuf + P::A_BYTES + ((wn * TN + tn) * CH) * P::BSLOT, lane);
+#pragma unroll
+            for (int c = 0; c < CH; ++c)
+                read_chunk<BITS>(wq[tn][c], abuf + P::A_BYTES + ((wn * TN + tn) * CH + c) * P::BSLOT, lane);
 #pragma unroll
         for (int tm = 0; tm < TM; ++tm) xf[0][tm] = *(const frag_t*)(abuf + rd[0] + tm * 32 * 128);
+    };
+    auto widen = [&](frag_t (&wf)[TN], int s) {
 #pragma unroll
-        for (int s = 0; s < 4; ++s) {
-            if constexpr (CH == 2) {
-                if (s == 0) {
+        for (int tn = 0; tn < TN; ++tn) {
+            if constexpr (I8)
+                wf[tn] = widen_step<BITS>(wq[tn][s >> 1], s & 1, xflip);
+            else
+                wf[tn] = dequant_step<BITS>(wq[tn][0], s, zc[tn]);
+            if constexpr (BF) wf[tn] = __builtin_bit_cast(half8, half8_to_bf16x8(wf[tn]));  // bf16 bits from here on
+        }
+    };
+    auto multiply = [&](const frag_t (&wf)[TN], int s) {
 #pragma unroll
-                    for (int tn = 0; tn < TN; ++tn)
-                        read_chunk<BITS>(wq[tn][1], abuf + P::A_BYTES + ((wn * TN + tn) * CH + 1) * P::BSLOT, lane);
-                }
-            }
-            if (s < 3) {
-#pragma unroll
-                for (int tm = 0; tm < TM; ++tm)
-                    xf[(s + 1) & 1][tm] = *(const frag_t*)(abuf + rd[s + 1] + tm * 32 * 128);
-            }
-            __builtin_amdgcn_sched_barrier(0);
-            frag_t wf[TN];
+        for (int tm = 0; tm < TM; ++tm)
 #pragma unroll
             for (int tn = 0; tn < TN; ++tn) {
                 if constexpr (I8)
-                    wf[tn] = widen_step<BITS>(wq[tn][s >> 1], s & 1, xflip);
+                    acc[tm][tn] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wf[tn], xf[s][tm], acc[tm][tn], 0, 0, 0);
+                else if constexpr (BF)
+                    acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                        __builtin_bit_cast(bf16x8, wf[tn]), __builtin_bit_cast(bf16x8, xf[s][tm]), acc[tm][tn], 0, 0, 0);
                 else
-                    wf[tn] = dequant_step<BITS>(wq[tn][0], s, zc[tn]);
-                if constexpr (BF) wf[tn] = __builtin_bit_cast(half8, half8_to_bf16x8(wf[tn]));  // bf16 bits from here on
+                    acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_f16(wf[tn], xf[s][tm], acc[tm][tn], 0, 0, 0);
             }
+    };
+
+    // stage 0 must have landed; the younger stages stay in flight
+    constexpr int W_FIRST = (S - 1) * P::OPS <= 63 ? (S - 1) * P::OPS : (S > 2 ? (S - 2) * P::OPS : 0);
+    if (KT >= S)
+        wait_vmcnt<W_FIRST>();
+    else
+        wait_vmcnt<0>();
+    __syncthreads();
+    request_first(lds + grp * P::SUB_BYTES);
+
+    int buf = 0;
+    for (int kt = 0; kt < KT; ++kt) {
+        const uint8_t* abuf = lds + buf * STAGE_BYTES + grp * P::SUB_BYTES;
+        // odd tail of a k-split: the last k step of group 1 does not exist (it still takes part in the barriers)
+        const bool live = KS == 1 || kt * KS + grp < KSTEPS;
+        frag_t wf[2][TN];
+        // step 0
 #pragma unroll
-            for (int tm = 0; tm < TM; ++tm)
+        for (int tm = 0; tm < TM; ++tm) xf[1][tm] = *(const frag_t*)(abuf + rd[1] + tm * 32 * 128);
+        __builtin_amdgcn_sched_barrier(0);
+        widen(wf[0], 0);
+        if (live) multiply(wf[0], 0);
+        __builtin_amdgcn_sched_barrier(0);
+        // step 1: the last LDS reads of this stage
 #pragma unroll
-                for (int tn = 0; tn < TN; ++tn) {
-                    if constexpr (I8)
-                        acc[tm][tn] =
-                            __builtin_amdgcn_mfma_i32_32x32x32_i8(wf[tn], xf[s & 1][tm], acc[tm][tn], 0, 0, 0);
-                    else if constexpr (BF)
-                        acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                            __builtin_bit_cast(bf16x8, wf[tn]), __builtin_bit_cast(bf16x8, xf[s & 1][tm]), acc[tm][tn], 0, 0, 0);
-                    else
-                        acc[tm][tn] =
-                            __builtin_amdgcn_mfma_f32_32x32x16_f16(wf[tn], xf[s & 1][tm], acc[tm][tn], 0, 0, 0);
-                }
-            __builtin_amdgcn_sched_barrier(0);
+        for (int tm = 0; tm < TM; ++tm) xf[2][tm] = *(const frag_t*)(abuf + rd[2] + tm * 32 * 128);
+#pragma unroll
+        for (int tm = 0; tm < TM; ++tm) xf[3][tm] = *(const frag_t*)(abuf + rd[3] + tm * 32 * 128);
+        __builtin_amdgcn_sched_barrier(0);
+        widen(wf[1], 1);
+        if (live) multiply(wf[1], 1);
+        __builtin_amdgcn_sched_barrier(0);
+        // the packed weights of this stage are widened completely before their registers are reused
+        widen(wf[0], 2);
+        widen(wf[1], 3);
+#pragma unroll
+        for (int tn = 0; tn < TN; ++tn)  // materialise them here (the compiler would otherwise sink them past the branch)
+            asm volatile("" : "+v"(wf[0][tn]), "+v"(wf[1][tn]));
+        __builtin_amdgcn_sched_barrier(0);
+        int nb = buf + 1 == S ? 0 : buf + 1;
+        if (kt + 1 < KT) {
+            // hand-over: stage kt+1 must have landed (the S-2 stages behind it may stay in flight while they exist);
+            // the barrier also says that every wave holds its last fragments of stage kt, so its buffer is refilled
+            if (S > 2 && kt + S - 1 < KT)
+                wait_vmcnt<(S > 2 ? (S - 2) * P::OPS : 0)>();
+            else
+                wait_vmcnt<0>();
+            __syncthreads();
+            if (kt + S < KT) issue(kt + S, buf);
+            request_first(lds + nb * STAGE_BYTES + grp * P::SUB_BYTES);
         }
-        buf = buf + 1 == S ? 0 : buf + 1;
+        __builtin_amdgcn_sched_barrier(0);
+        if (live) {
+            multiply(wf[0], 2);
+            multiply(wf[1], 3);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        buf = nb;
     }
     __syncthreads();  // every wave is done reading the stages: what follows may overwrite them
 
@@ -550,36 +582,44 @@ __global__ __launch_bounds__(WGM* WGN* KS * 64, (TM * TN <= 8 ? 2 : 1)) void gem
         ch_add[t] = c_bias;
     }
 
+    // k-split: the two groups' partial sums meet through LDS ([register quad][lane], 16 bytes per lane).  With an
+    // even number of row slabs per wave each group finishes half of them (it sends the other half across and adds
+    // what it receives), so both groups take part in the epilogue; otherwise group 1 sends everything to group 0.
+    constexpr bool SPLIT_EPI = KS == 2 && TM % 2 == 0;
+    constexpr int TMX = SPLIT_EPI ? TM / 2 : TM;  // slabs one wave sends
+    auto owner = [](int tm) { return SPLIT_EPI ? (tm & 1) : 0; };
     if constexpr (KS == 2) {
-        // group 1 hands its accumulators to group 0 through LDS ([register quad][lane], 16 bytes per lane)
-        uint8_t* xch = lds + wvg * (TM * TN * 4 * 1024) + lane * 16;
-        if (grp == 1) {
+        using quad_t = typename std::conditional<I8, int4v, float4v>::type;
+        constexpr int XW = TMX * TN * 4 * 1024;  // bytes one wave sends
+        static_assert(P::NWG * (SPLIT_EPI ? 2 : 1) * XW <= S * STAGE_BYTES, "accumulator exchange must fit the stages");
+        auto area = [&](int writer) { return lds + (SPLIT_EPI ? wvg * 2 + writer : wvg) * XW + lane * 16; };
+        uint8_t* out = area(grp);
 #pragma unroll
-            for (int tm = 0; tm < TM; ++tm)
+        for (int tm = 0; tm < TM; ++tm) {
+            if (owner(tm) == grp) continue;
 #pragma unroll
-                for (int tn = 0; tn < TN; ++tn)
+            for (int tn = 0; tn < TN; ++tn)
 #pragma unroll
-                    for (int q = 0; q < 4; ++q) {
-                        using quad_t = typename std::conditional<I8, int4v, float4v>::type;
-                        quad_t v;
+                for (int q = 0; q < 4; ++q) {
+                    quad_t v;
 #pragma unroll
-                        for (int r = 0; r < 4; ++r) v[r] = acc[tm][tn][4 * q + r];
-                        *(quad_t*)(xch + ((tm * TN + tn) * 4 + q) * 1024) = v;
-                    }
+                    for (int r = 0; r < 4; ++r) v[r] = acc[tm][tn][4 * q + r];
+                    *(quad_t*)(out + (((SPLIT_EPI ? tm >> 1 : tm) * TN + tn) * 4 + q) * 1024) = v;
+                }
         }
         __syncthreads();
-        if (grp == 0) {
+        const uint8_t* in = area(1 - grp);
 #pragma unroll
-            for (int tm = 0; tm < TM; ++tm)
+        for (int tm = 0; tm < TM; ++tm) {
+            if (owner(tm) != grp) continue;
 #pragma unroll
-                for (int tn = 0; tn < TN; ++tn)
+            for (int tn = 0; tn < TN; ++tn)
 #pragma unroll
-                    for (int q = 0; q < 4; ++q) {
-                        using quad_t = typename std::conditional<I8, int4v, float4v>::type;
-                        const quad_t v = *(const quad_t*)(xch + ((tm * TN + tn) * 4 + q) * 1024);
+                for (int q = 0; q < 4; ++q) {
+                    const quad_t v = *(const quad_t*)(in + (((SPLIT_EPI ? tm >> 1 : tm) * TN + tn) * 4 + q) * 1024);
 #pragma unroll
-                        for (int r = 0; r < 4; ++r) acc[tm][tn][4 * q + r] += v[r];
-                    }
+                    for (int r = 0; r < 4; ++r) acc[tm][tn][4 * q + r] += v[r];
+                }
         }
         __syncthreads();
     }
@@ -589,24 +629,24 @@ __global__ __launch_bounds__(WGM* WGN* KS * 64, (TM * TN <= 8 ? 2 : 1)) void gem
     // ---------------------------------------------------------------- epilogue
     // Result element v of a lane is channel 8*(v/4) + 4*kb + v%4 of its 32-channel tile, activation row l31:
     // four consecutive channels of ONE row per lane, so a direct store would scatter 8-byte pieces over 32 rows.
-    // Instead every wave transposes through its own slice of the (now idle) LDS stages, 32 rows at a time:
-    // finished fp16 values are written as 8-byte pieces into a [32 rows][TN*32 channels] image (16-byte chunks
-    // XOR-swizzled by row), read back as 16 bytes per lane along rows, and stored with 16 lanes covering one
-    // contiguous row segment of TN*64 bytes.
-    constexpr int CPR = TN * 4;                 // 16-byte chunks per staged row
-    constexpr int ROWS_PER_PASS = 64 / CPR;     // rows one store instruction covers
-    static_assert(64 % CPR == 0, "TN must be 1, 2 or 4");
-    constexpr int EP_BYTES = 32 * CPR * 16;     // staging bytes per wave
-    static_assert(P::NWG * EP_BYTES <= S * STAGE_BYTES, "epilogue staging must fit the LDS stages");
-    uint8_t* ep = lds + wvg * EP_BYTES;
-
+    // Instead every wave transposes through its own slice of the (now idle) LDS stages, 32 rows and up to 4 channel
+    // tiles at a time: finished fp16 values are written as 8-byte pieces into a [32 rows][GS*32 channels] image
+    // (16-byte chunks XOR-swizzled by row), read back as 16 bytes per lane along rows, and stored with 4*GS lanes
+    // covering one contiguous row segment of GS*64 bytes.
+    static_assert(TN == 1 || TN == 2 || TN == 4, "channel tiles per wave: 1, 2 or 4");
+    constexpr int G0 = TN >= 4 ? 4 : TN;         // channel tiles staged at a time
+    constexpr int EP_BYTES = 32 * G0 * 64;       // staging bytes per storing wave
+    static_assert((SPLIT_EPI ? NW : P::NWG) * EP_BYTES <= S * STAGE_BYTES, "epilogue staging must fit the LDS stages");
+    uint8_t* ep = lds + (SPLIT_EPI ? wv : wvg) * EP_BYTES;
     const int nw0 = n0 + wn * TN * 32;  // first channel of this wave
-#pragma unroll
-    for (int tm = 0; tm < TM; ++tm) {
-        if (KS > 1 && grp != 0) break;  // the finished sums live in group 0
+
+    auto store_cols = [&](auto tn0_c, auto gs_c, int tm) {
+        constexpr int TN0 = decltype(tn0_c)::value, GS = decltype(gs_c)::value;
+        constexpr int CPR = GS * 4;              // 16-byte chunks per staged row
+        constexpr int ROWS_PER_PASS = 64 / CPR;  // rows one store instruction covers
         const int mt0 = m0 + (wm * TM + tm) * 32;  // first row of this 32-row slab
 #pragma unroll
-        for (int tn = 0; tn < TN; ++tn)
+        for (int tn = TN0; tn < TN0 + GS; ++tn)
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
                 const int cl = (wn * TN + tn) * 32 + 8 * q + 4 * kb;  // channel inside the workgroup tile
@@ -637,7 +677,7 @@ __global__ __launch_bounds__(WGM* WGN* KS * 64, (TM * TN <= 8 ? 2 : 1)) void gem
                             o[r] = (_Float16)v;
                     }
                 }
-                const int chunk = tn * 4 + q;
+                const int chunk = (tn - TN0) * 4 + q;
                 *(half4*)(ep + l31 * (CPR * 16) + (((chunk ^ l31) & (CPR - 1)) << 4) + kb * 8) = o;
             }
         __builtin_amdgcn_wave_barrier();
@@ -645,7 +685,7 @@ __global__ __launch_bounds__(WGM* WGN* KS * 64, (TM * TN <= 8 ? 2 : 1)) void gem
         for (int i = 0; i < 32 / ROWS_PER_PASS; ++i) {
             const int row = i * ROWS_PER_PASS + lane / CPR, c = lane % CPR;
             const uint4v v = *(const uint4v*)(ep + row * (CPR * 16) + (((c ^ row) & (CPR - 1)) << 4));
-            const int m = mt0 + row, n = nw0 + c * 8;
+            const int m = mt0 + row, n = nw0 + TN0 * 32 + c * 8;
             if (m < g.M && n < g.N) {
                 long yr = m;
                 if constexpr (I8) yr = g.out_map.phys(m);
@@ -653,6 +693,11 @@ __global__ __launch_bounds__(WGM* WGN* KS * 64, (TM * TN <= 8 ? 2 : 1)) void gem
             }
         }
         __builtin_amdgcn_wave_barrier();
+    };
+#pragma unroll
+    for (int tm = 0; tm < TM; ++tm) {
+        if (KS > 1 && owner(tm) != grp) continue;  // the finished sums of this slab live in the other group
+        store_cols(std::integral_constant<int, 0>{}, std::integral_constant<int, G0>{}, tm);
     }
     if (g.phase_clk && threadIdx.x == 0) {
         long long* o = g.phase_clk + (long)blockIdx.x * 4;

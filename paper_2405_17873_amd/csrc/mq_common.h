@@ -90,7 +90,7 @@ void set_force_tile(int t);
 void set_phase_buffer(long long* p, long workgroups);
 
 // ---- optional per-kernel event timing (prof.hip) ----
-enum { PROF_ACT_MINMAX = 60, PROF_ACT_QUANTIZE = 61, PROF_BOS_ROWS = 62 };
+enum { PROF_GEMM_TILES = 5, PROF_ACT_MINMAX = 12 * PROF_GEMM_TILES, PROF_ACT_QUANTIZE, PROF_BOS_ROWS };
 int prof_num_slots();
 int prof_gemm_slot(int family /*0 weight-only fp16, 1 int8, 2 weight-only bf16*/, int bits, int tile);
 bool prof_enabled();

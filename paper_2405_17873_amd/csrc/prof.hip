@@ -36,7 +36,7 @@ void init_slots() {
 }
 }  // namespace
 
-int prof_num_slots() { return 63; }
+int prof_num_slots() { return PROF_BOS_ROWS + 1; }
 
 // What an event pair adds to the kernel it brackets (dispatch latency on either side): measured once, on the
 // stream given, with a single-workgroup kernel that spins for a known 20 us of the constant 100 MHz clock.
@@ -81,7 +81,7 @@ double prof_bracket_overhead_us(hipStream_t st) {
 
 int prof_gemm_slot(int family, int bits, int tile) {
     const int b = bits == 2 ? 0 : bits == 3 ? 1 : bits == 4 ? 2 : 3;
-    return (family * 4 + b) * 5 + tile;
+    return (family * 4 + b) * PROF_GEMM_TILES + tile;
 }
 
 bool prof_enabled() { return g_on; }
