@@ -1,0 +1,147 @@
+#!/usr/bin/env python3
+"""Per-shape report of the quantized-linear hot path on one MI355X (a table, not the one-line benchmark).
+
+For every configured layer shape and mode it prints the time per call, the achieved op rate and algorithmic byte rate,
+the two roofline times (HBM at 8 TB/s, dense MFMA at 2.5 PFLOP/s fp16 / 5.0 POP/s int8), which of them binds, and
+the fraction  max(t_HBM, t_MFMA) / t_measured.
+
+Timing: calls are issued back to back on one stream and timed as a whole with one event pair (N calls / elapsed), so
+the figure is the throughput a pipeline of such layers sees, launch cost included.  Every call of the loop uses its
+own set of buffers (activations, packed weights, outputs), and the sets together exceed the 256 MB last-level cache, so
+no call finds its operands cached by the previous one.  The A8 rows include the activation min/max and quantise
+kernels ("dyn") or the quantise kernel only ("static"); the "kernel" column is the library's own event timing of the
+GEMM kernel alone (bracket cost subtracted).
+
+Algorithmic bytes per call: X once (2 M K) + packed weights (N K bits / 8) + 10 N (scale, zero point, bias) + Y once
+(2 M N); ops = 2 M N K.
+"""
+from __future__ import annotations
+
+import argparse
+import os
+import sys
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM = 8000e9
+PEAK = {"w": 2500e12, "a": 5000e12}
+LLC_BYTES = 320 << 20
+
+
+def shapes():
+    S = []
+    # (label, M, K, N, modes)   modes: w<bits> weight-only, a4/a8 dynamic, s4/s8 static activation parameters
+    S.append(("c1", 256, 320, 320, ("w4", "a8sym")))
+    for (K, N) in ((640, 640), (640, 5120), (2560, 640)):
+        S.append(("c2", 4096, K, N, ("w8", "w4", "w3", "w2")))
+    for (K, N) in ((1280, 1280), (1280, 10240), (5120, 1280)):
+        S.append(("c3", 4096, K, N, ("a4", "a8sym", "s4", "w4")))
+    for N in (640, 1280):
+        S.append(("c4", 8 * 77, 2048, N, ("bos8", "bos4")))
+    for (K, N) in ((640, 640), (640, 5120), (2560, 640)):
+        S.append(("c5", 16384, K, N, ("w4", "w2", "a4")))
+    S.append(("c5", 4 * 77, 2048, 1280, ("w4", "bos4")))
+    for M in (1, 4, 16, 64, 77):
+        for (K, N) in ((1280, 1280), (1280, 10240), (5120, 1280), (2048, 1280)):
+            S.append(("small-M", M, K, N, ("w8", "w4", "w2")))
+    return S
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--iters", type=int, default=200)
+    ap.add_argument("--only", default="", help="comma-separated labels (c1,c2,c3,c4,c5,small-M)")
+    args = ap.parse_args()
+
+    import torch
+
+    import paper_2405_17873_amd as mq
+    mq.load()
+    dev = torch.device("cuda:0")
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(0)
+    overhead_us = mq.prof_bracket_overhead_us()
+    only = set(filter(None, args.only.split(",")))
+
+    print(f"# per-shape report, {torch.cuda.get_device_name(0)}; iters per row {args.iters}; "
+          f"event-bracket cost subtracted from the kernel column: {overhead_us:.2f} us")
+    print(f"{'cfg':8s}{'M':>6s}{'K':>6s}{'N':>6s} {'mode':7s}{'us/call':>9s}{'kernel us':>10s}{'T(FL)OP/s':>10s}"
+          f"{'GB/s':>8s}{'t_HBM us':>9s}{'t_MFMA us':>10s} {'binds':5s}{'frac':>6s}{'k.frac':>7s}")
+
+    for (cfg, M, K, N, modes) in shapes():
+        if only and cfg not in only:
+            continue
+        for mode in modes:
+            bos = mode.startswith("bos")
+            sym = mode.endswith("sym")
+            kind = "w" if mode[0] == "w" else "a"
+            bits = int(mode.replace("sym", "").replace("bos", "")[-1]) if not bos else int(mode[3:])
+            xbytes = 2 * M * K
+            wbytes = N * K * bits // 8
+            alg_bytes = xbytes + wbytes + 10 * N + 2 * M * N
+            ops = 2.0 * M * N * K
+            nsets = max(2, min(args.iters, -(-LLC_BYTES // (alg_bytes + (M * K if kind == "a" else 0)))))
+            sets = []
+            ws = None
+            for _ in range(nsets):
+                w = (torch.randn(N, K, generator=gen, device=dev) * 0.02).half()
+                c, s, z = mq.quantize_weights(w, bits, sym)
+                p, cs = mq.pack_weights(c, bits, mq.LAYOUT_KERNEL, codes_signed=sym)
+                pw = mq.PackedWeight(p, s, z, cs, N, K, bits, mq.LAYOUT_KERNEL, sym)
+                bias = (torch.randn(N, generator=gen, device=dev) * 0.01).half()
+                if bos:
+                    B, T = M // 77, 77
+                    x = torch.randn(B, T, K, generator=gen, device=dev)
+                    x[:, 0, :16] *= 60.0
+                    x = x.half()
+                    y = torch.empty(B, T, N, dtype=torch.float16, device=dev)
+                    ws = ws if ws is not None else torch.empty(mq.bos_aware_kv_proj_workspace_bytes(B, T, K),
+                                                                dtype=torch.uint8, device=dev)
+                    sets.append(mq.plan_bos_aware_kv_proj(x, pw, y, ws, w_f16=w, bias=bias))
+                    continue
+                del w
+                x = torch.randn(M, K, generator=gen, device=dev).half()
+                y = torch.empty(M, N, dtype=torch.float16, device=dev)
+                if kind == "w":
+                    sets.append(mq.plan_qlinear_w_only(x, pw, bias, y))
+                else:
+                    ws = ws if ws is not None else torch.empty(mq.qlinear_a8_workspace_bytes(M, K), dtype=torch.uint8,
+                                                                device=dev)
+                    act = None
+                    if mode[0] == "s":
+                        act = (torch.tensor([8.0 / 255], device=dev), torch.tensor([128], dtype=torch.int32, device=dev))
+                    sets.append(mq.plan_qlinear_a8(x, pw, bias, y, ws, act=act))
+            for i in range(min(nsets, 8)):
+                sets[i]()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for i in range(args.iters):
+                sets[i % nsets]()
+            e1.record()
+            torch.cuda.synchronize()
+            us = e0.elapsed_time(e1) * 1e3 / args.iters
+            # the GEMM kernel alone, from the library's event brackets
+            mq.prof_reset()
+            mq.prof_filter(-1, 1)
+            mq.prof_enable(True)
+            for i in range(min(args.iters, 50)):
+                sets[i % nsets]()
+            torch.cuda.synchronize()
+            mq.prof_enable(False)
+            ker = [k for k in mq.prof_read() if "gemm_kernel" in k["kernel"]]
+            k_us = sum(k["ms"] for k in ker) * 1e3 / max(1, sum(k["launches"] for k in ker)) - overhead_us if ker else 0.0
+            k_us = max(k_us, 0.05)
+            t_hbm = alg_bytes / HBM * 1e6
+            t_mfma = ops / PEAK[kind] * 1e6
+            bind = "HBM" if t_hbm >= t_mfma else "MFMA"
+            print(f"{cfg:8s}{M:6d}{K:6d}{N:6d} {mode:7s}{us:9.2f}{k_us:10.2f}{ops / us / 1e6:10.1f}"
+                  f"{alg_bytes / us / 1e3:8.0f}{t_hbm:9.2f}{t_mfma:10.2f} {bind:5s}{max(t_hbm, t_mfma) / us:6.3f}"
+                  f"{max(t_hbm, t_mfma) / k_us:7.3f}", flush=True)
+            del sets
+            torch.cuda.empty_cache()
+
+
+if __name__ == "__main__":
+    main()
