@@ -15,7 +15,7 @@ namespace mq {
 
 typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 
-static constexpr int kPartialSlots = 1024;  // upper bound of pass-1 workgroups
+static constexpr int kPartialSlots = 512;  // upper bound of pass-1 workgroups
 int act_quant_partial_slots() { return kPartialSlots; }
 
 template <typename T, typename Op>
@@ -25,34 +25,39 @@ __device__ inline T wave_reduce(T v, Op op) {
     return v;
 }
 
-// A wave walks RPW rows at a time with 16-byte loads, so that every lane keeps RPW (or more) loads in flight.
-static constexpr int RPW = 4;
+// Both passes are bound by memory latency at the sizes of this path (5 to 80 MB per tensor): what counts is the
+// number of bytes requested before the first one arrives.  The tensor is therefore walked as a flat list of 16-byte
+// vectors (8 values; vector i is piece i % (K/8) of row i / (K/8)), every lane requests several vectors before it
+// touches one, and the grids are sized so that every compute unit holds a few workgroups.
+static constexpr int MM_U = 8;  // vectors per lane per round, pass 1
+static constexpr int Q_U = 4;   // vectors per lane per round, pass 2
 
-__global__ __launch_bounds__(256) void act_minmax_kernel(const _Float16* __restrict__ x, int M, int K, long ldx,
-                                                         RowMap map, float* __restrict__ partials) {
+__global__ __launch_bounds__(256) void act_minmax_kernel(const _Float16* __restrict__ x, uint32_t nv, uint32_t K8,
+                                                         long ldx, RowMap map, int flat,
+                                                         float* __restrict__ partials) {
     const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
-    const int K8 = K >> 3;
     float mn = INFINITY, mx = -INFINITY;
-    for (long r0 = ((long)blockIdx.x * 4 + wv) * RPW; r0 < M; r0 += (long)gridDim.x * 4 * RPW) {
-        const half8* row[RPW];
+    for (uint32_t base = blockIdx.x * (256u * MM_U); base < nv; base += gridDim.x * (256u * MM_U)) {
+        half8 v[MM_U];
 #pragma unroll
-        for (int j = 0; j < RPW; ++j) {
-            const long r = r0 + j < M ? r0 + j : M - 1;  // a repeated row does not change a min or a max
-            row[j] = (const half8*)(x + map.phys(r) * ldx);
+        for (int u = 0; u < MM_U; ++u) {
+            uint32_t i = base + u * 256u + threadIdx.x;
+            i = i < nv ? i : nv - 1;  // a repeated vector does not change a min or a max
+            if (flat) {
+                v[u] = ((const half8*)x)[i];
+            } else {
+                const uint32_t row = i / K8, p = i - row * K8;
+                v[u] = ((const half8*)(x + map.phys(row) * ldx))[p];
+            }
         }
-        for (int p = lane; p < K8; p += 64) {
-            half8 v[RPW];
 #pragma unroll
-            for (int j = 0; j < RPW; ++j) v[j] = row[j][p];
+        for (int u = 0; u < MM_U; ++u)
 #pragma unroll
-            for (int j = 0; j < RPW; ++j)
-#pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    const float f = (float)v[j][e];
-                    mn = fminf(mn, f);
-                    mx = fmaxf(mx, f);
-                }
-        }
+            for (int e = 0; e < 8; ++e) {
+                const float f = (float)v[u][e];
+                mn = fminf(mn, f);
+                mx = fmaxf(mx, f);
+            }
     }
     mn = wave_reduce(mn, [](float a, float b) { return fminf(a, b); });
     mx = wave_reduce(mx, [](float a, float b) { return fmaxf(a, b); });
@@ -68,8 +73,11 @@ __global__ __launch_bounds__(256) void act_minmax_kernel(const _Float16* __restr
     }
 }
 
+static constexpr int Q_MAX_ROWS = 128;  // rows per workgroup, pass 2 (1024 output vectors of at least 8 per row)
+
+// A workgroup converts R whole rows (so that it owns their row sums): R * Kp/8 output vectors, 1024 per round.
 __global__ __launch_bounds__(256) void act_quantize_kernel(const _Float16* __restrict__ x, int M, int K, long ldx,
-                                                           RowMap map, const float* __restrict__ partials,
+                                                           RowMap map, int R, const float* __restrict__ partials,
                                                            int n_partials, const float* __restrict__ act_scale,
                                                            const int32_t* __restrict__ act_zp,
                                                            int8_t* __restrict__ a8, int32_t* __restrict__ rowsum,
@@ -77,6 +85,11 @@ __global__ __launch_bounds__(256) void act_quantize_kernel(const _Float16* __res
                                                            float* __restrict__ act_scale_out,
                                                            int32_t* __restrict__ act_zp_out) {
     const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    __shared__ float smn[4], smx[4];
+    __shared__ int lsum[Q_MAX_ROWS];
+    const int r0 = blockIdx.x * R;
+    const int Rr = M - r0 < R ? M - r0 : R;
+    if (threadIdx.x < Q_MAX_ROWS) lsum[threadIdx.x] = 0;
     float s, zf;
     if (partials) {
         float mn = INFINITY, mx = -INFINITY;
@@ -86,7 +99,6 @@ __global__ __launch_bounds__(256) void act_quantize_kernel(const _Float16* __res
         }
         mn = wave_reduce(mn, [](float a, float b) { return fminf(a, b); });
         mx = wave_reduce(mx, [](float a, float b) { return fmaxf(a, b); });
-        __shared__ float smn[4], smx[4];
         if (lane == 0) {
             smn[wv] = mn;
             smx[wv] = mx;
@@ -106,6 +118,7 @@ __global__ __launch_bounds__(256) void act_quantize_kernel(const _Float16* __res
     } else {
         s = *act_scale;
         zf = (float)*act_zp;
+        __syncthreads();
     }
     const float inv = 1.0f / s;
     if (blockIdx.x == 0 && threadIdx.x == 0) {
@@ -114,69 +127,74 @@ __global__ __launch_bounds__(256) void act_quantize_kernel(const _Float16* __res
         if (act_scale_out) *act_scale_out = s;
         if (act_zp_out) *act_zp_out = (int)zf;
     }
-    const int K8 = K >> 3;
-    const int Kp = (K + 127) / 128 * 128;  // row stride of the int8 copy; the padding is zero
-    for (long r0 = ((long)blockIdx.x * 4 + wv) * RPW; r0 < M; r0 += (long)gridDim.x * 4 * RPW) {
-        const half8* row[RPW];
-        int sum[RPW];
+    const uint32_t K8 = K >> 3;
+    const uint32_t Kp = (K + 127) / 128 * 128;  // row stride of the int8 copy; the padding is zero
+    const uint32_t Kp8 = Kp >> 3;               // a multiple of 16: an aligned group of 8 lanes never straddles rows
+    const uint32_t nvo = (uint32_t)Rr * Kp8;
+    for (uint32_t base = 0; base < nvo; base += 256u * Q_U) {
+        half8 v[Q_U];
+        uint32_t lr[Q_U], pp[Q_U];
 #pragma unroll
-        for (int j = 0; j < RPW; ++j) {
-            const long r = r0 + j < M ? r0 + j : M - 1;
-            row[j] = (const half8*)(x + map.phys(r) * ldx);
-            sum[j] = 0;
+        for (int u = 0; u < Q_U; ++u) {
+            const uint32_t i = base + u * 256u + threadIdx.x;
+            lr[u] = i / Kp8;
+            pp[u] = i - lr[u] * Kp8;
+            if (i < nvo && pp[u] < K8) v[u] = ((const half8*)(x + map.phys(r0 + lr[u]) * ldx))[pp[u]];
         }
-        for (int p = lane; p < (Kp >> 3); p += 64) {
-            half8 v[RPW];
-            if (p < K8) {
 #pragma unroll
-                for (int j = 0; j < RPW; ++j) v[j] = row[j][p];
-            }
+        for (int u = 0; u < Q_U; ++u) {
+            const uint32_t i = base + u * 256u + threadIdx.x;
+            const bool valid = i < nvo;
+            uint32_t w0 = 0, w1 = 0;
+            int sum = 0;
+            if (valid && pp[u] < K8) {
+                int q[8];
 #pragma unroll
-            for (int j = 0; j < RPW; ++j) {
-                uint32_t w0 = 0, w1 = 0;
-                if (p < K8) {
-                    int q[8];
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) {
-                        float t = rintf((float)v[j][e] * inv) + zf;
-                        t = fminf(fmaxf(t, 0.0f), 255.0f);
-                        q[e] = (int)t - 128;
-                        sum[j] += q[e];
-                    }
-#pragma unroll
-                    for (int b = 0; b < 4; ++b) {
-                        w0 |= ((uint32_t)(q[k8_perm(b)] & 255)) << (8 * b);
-                        w1 |= ((uint32_t)(q[k8_perm(4 + b)] & 255)) << (8 * b);
-                    }
+                for (int e = 0; e < 8; ++e) {
+                    float t = rintf((float)v[u][e] * inv) + zf;
+                    t = fminf(fmaxf(t, 0.0f), 255.0f);
+                    q[e] = (int)t - 128;
+                    sum += q[e];
                 }
-                if (r0 + j < M) ((uint2*)(a8 + (r0 + j) * (long)Kp))[p] = make_uint2(w0, w1);
-            }
-        }
 #pragma unroll
-        for (int j = 0; j < RPW; ++j) {
-            const int t = wave_reduce(sum[j], [](int a, int b) { return a + b; });
-            if (lane == 0 && r0 + j < M) rowsum[r0 + j] = t;
+                for (int b = 0; b < 4; ++b) {
+                    w0 |= ((uint32_t)(q[k8_perm(b)] & 255)) << (8 * b);
+                    w1 |= ((uint32_t)(q[k8_perm(4 + b)] & 255)) << (8 * b);
+                }
+            }
+            if (valid) ((uint2*)(a8 + (long)(r0 + lr[u]) * Kp))[pp[u]] = make_uint2(w0, w1);
+            sum += __shfl_xor(sum, 1, 64);
+            sum += __shfl_xor(sum, 2, 64);
+            sum += __shfl_xor(sum, 4, 64);
+            if (valid && (lane & 7) == 0) atomicAdd(&lsum[lr[u]], sum);
         }
     }
+    __syncthreads();
+    if ((int)threadIdx.x < Rr) rowsum[r0 + threadIdx.x] = lsum[threadIdx.x];
 }
 
 int launch_act_quant(const void* x, int M, int K, int ldx, RowMap in_map, const float* act_scale,
                      const int32_t* act_zp, int8_t* a8, int32_t* rowsum, ActParams* params, float* partials,
                      float* act_scale_out, int32_t* act_zp_out, hipStream_t st) {
-    int grid = (M + 4 * RPW - 1) / (4 * RPW);
-    if (grid > kPartialSlots) grid = kPartialSlots;
+    const uint32_t K8 = (uint32_t)K >> 3;
+    const uint32_t nv = (uint32_t)M * K8;  // M * ldx * 2 < 2^31 has been checked: this fits easily
+    long g1 = ((long)nv + 256 * MM_U - 1) / (256 * MM_U);
+    const int grid = (int)(g1 > kPartialSlots ? kPartialSlots : g1);
     const bool dynamic = act_scale == nullptr;
     if (dynamic) {
+        const int flat = in_map.rows_per_group <= 0 && ldx == K;
         ProfScope prof(st, PROF_ACT_MINMAX, 0.0, 2.0 * M * K);
-        hipLaunchKernelGGL(act_minmax_kernel, dim3(grid), dim3(256), 0, st, (const _Float16*)x, M, K, (long)ldx, in_map,
-                           partials);
+        hipLaunchKernelGGL(act_minmax_kernel, dim3(grid), dim3(256), 0, st, (const _Float16*)x, nv, K8, (long)ldx,
+                           in_map, flat, partials);
         MQ_HIP_CHECK_LAUNCH();
     }
-    int qgrid = (M + 4 * RPW - 1) / (4 * RPW);
-    if (qgrid > 4096) qgrid = 4096;
+    const int Kp8 = (K + 127) / 128 * 16;
+    int R = 256 * Q_U / Kp8;
+    R = R < 1 ? 1 : (R > Q_MAX_ROWS ? Q_MAX_ROWS : R);
+    const int qgrid = (M + R - 1) / R;
     ProfScope prof(st, PROF_ACT_QUANTIZE, 0.0, 3.0 * M * K + 4.0 * M);
     hipLaunchKernelGGL(act_quantize_kernel, dim3(qgrid), dim3(256), 0, st, (const _Float16*)x, M, K, (long)ldx, in_map,
-                       dynamic ? partials : (const float*)nullptr, grid, act_scale, act_zp, a8, rowsum, params,
+                       R, dynamic ? partials : (const float*)nullptr, grid, act_scale, act_zp, a8, rowsum, params,
                        act_scale_out, act_zp_out);
     MQ_HIP_CHECK_LAUNCH();
     return MQ_OK;

@@ -7,11 +7,14 @@ namespace mq {
 
 typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 
-// One wave per output channel n; the wave walks K in 16-byte pieces and keeps one accumulator per prompt.
+// One wave per output channel n.  The wave walks K in rounds of 4 x 64 sixteen-byte pieces: it requests the four
+// weight pieces and the matching pieces of every prompt's BOS row before it multiplies any, so that one round trip
+// to memory covers 512 k (the kernel is latency bound: a few MB of weights, a few KB of activations).
 template <int BCHUNK>
 __global__ __launch_bounds__(256) void bos_rows_kernel(const _Float16* __restrict__ ctx, int B, int T, int K,
                                                        const _Float16* __restrict__ w, const _Float16* __restrict__ bias,
                                                        _Float16* __restrict__ y, int N) {
+    constexpr int U = 4;
     const int lane = threadIdx.x & 63;
     const int n = blockIdx.x * 4 + (threadIdx.x >> 6);
     if (n >= N) return;
@@ -21,15 +24,26 @@ __global__ __launch_bounds__(256) void bos_rows_kernel(const _Float16* __restric
         float acc[BCHUNK];
 #pragma unroll
         for (int i = 0; i < BCHUNK; ++i) acc[i] = 0.0f;
-        for (int p = lane; p < K8; p += 64) {
-            const half8 wv = wr[p];
+        for (int p0 = 0; p0 < K8; p0 += 64 * U) {
+            half8 wv[U], xv[BCHUNK][U];
 #pragma unroll
-            for (int i = 0; i < BCHUNK; ++i) {
-                if (b0 + i < B) {
-                    const half8 xv = ((const half8*)(ctx + (size_t)(b0 + i) * T * K))[p];
+            for (int u = 0; u < U; ++u) {
+                const int p = p0 + u * 64 + lane;
+                const int pc = p < K8 ? p : K8 - 1;  // clamped piece: its products are dropped below
+                wv[u] = wr[pc];
 #pragma unroll
-                    for (int e = 0; e < 8; ++e) acc[i] += (float)xv[e] * (float)wv[e];
+                for (int i = 0; i < BCHUNK; ++i) {
+                    const int b = b0 + i < B ? b0 + i : B - 1;
+                    xv[i][u] = ((const half8*)(ctx + (size_t)b * T * K))[pc];
                 }
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                if (p0 + u * 64 + lane >= K8) continue;
+#pragma unroll
+                for (int i = 0; i < BCHUNK; ++i)
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) acc[i] += (float)xv[i][u][e] * (float)wv[u][e];
             }
         }
 #pragma unroll

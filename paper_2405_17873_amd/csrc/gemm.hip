@@ -322,7 +322,9 @@ struct GemmPlan {
 };
 
 template <bool I8, int BITS, int WGM, int WGN, int TM, int TN, int S, int KS, bool BF = false>
-__global__ __launch_bounds__(WGM* WGN* KS * 64, (TM * TN <= 8 ? 2 : 1)) void gemm_kernel(const GemmArgs g) {
+__global__ __launch_bounds__(WGM* WGN* KS * 64,
+                             (TM * TN <= 8 && GemmPlan<I8, BITS, WGM, WGN, TM, TN, S, KS>::LDS_BYTES <= 80 * 1024) ? 2 : 1)
+void gemm_kernel(const GemmArgs g) {
     static_assert(!(I8 && BF), "the int8 path writes fp16");
     using P = GemmPlan<I8, BITS, WGM, WGN, TM, TN, S, KS>;
     constexpr int NW = P::NW, NT = P::NT, BM = P::BM, BN = P::BN, CH = P::CH;
@@ -730,10 +732,12 @@ void set_force_tile(int t) { g_force_tile = t; }
 
 // Measured on the SDXL shapes: the large tile wins once it yields two or more workgroups per compute unit; the
 // k-split variants only pay where tiles are few and k is long (FF-out at the 640 level, the K/V projections).
-static int pick_tile(int M, int N, int K) {
+static int pick_tile(int M, int N, int K, bool wide_weights = false) {
     if (g_force_tile >= 0 && g_force_tile <= 4) return g_force_tile;
     const long t0 = (long)((M + 127) / 128) * ((N + 255) / 256);
-    if (t0 >= 512) return 0;
+    // (8-bit weights of the int8 path: the large tile leaves LDS for one workgroup per compute unit only, and two
+    // co-resident 128x128 workgroups were measured faster on every configured shape)
+    if (t0 >= 512 && !wide_weights) return 0;
     const long t1 = (long)((M + 127) / 128) * ((N + 127) / 128);
     if (t1 >= 128) return (t1 < 256 && K >= 2048) ? 3 : 1;
     return K >= 1024 ? 4 : 2;
@@ -787,8 +791,11 @@ static int run_gemm(GemmArgs& g, int tile_index, hipStream_t st) {
 
 template <bool I8, int BITS>
 static int dispatch_gemm(GemmArgs& g, hipStream_t st) {
-    switch (pick_tile(g.M, g.N, g.K)) {
-        case 0: return run_gemm<I8, BITS, 1, 4, 4, 2, 1, 80 * 1024, 4>(g, 0, st);
+    // 8-bit weights of the int8 path take 2 KB of LDS per 32x64 tile: two workgroups per compute unit would leave
+    // room for two stages only, so these run one workgroup per compute unit with a deeper pipeline instead
+    constexpr bool WIDE = I8 && BITS == 8;
+    switch (pick_tile(g.M, g.N, g.K, WIDE)) {
+        case 0: return run_gemm<I8, BITS, 1, 4, 4, 2, 1, WIDE ? 160 * 1024 : 80 * 1024, 4>(g, 0, st);
         case 1: return run_gemm<I8, BITS, 2, 2, 2, 2, 1, 80 * 1024, 4>(g, 1, st);
         case 2: return run_gemm<I8, BITS, 2, 2, 1, 1, 1, 80 * 1024, 8>(g, 2, st);
         case 3: return run_gemm<I8, BITS, 2, 2, 2, 2, 2, 160 * 1024, 4>(g, 3, st);
