@@ -53,6 +53,15 @@ int mq_last_hip_error(void);
  * from the problem shape).  Process-wide, not thread safe; results do not depend on the tile. */
 void mq_tune_force_tile(int tile);
 
+/* Tuning and test hook: split of a GEMM's reduction over several workgroups per output tile (0: automatic, for
+ * problems with few tiles and a long reduction; 1: never; n > 1: n parts wherever the reduction has that many
+ * pipeline stages).  The partial sums pass through 32 MB of device memory that the library owns (a ring, one
+ * stretch per launch).  Launches on one stream never share live scratch; launches running at the same time on
+ * different streams are safe while their combined need fits the ring.  A split result is deterministic (the parts
+ * are added in a fixed order) but may differ from the unsplit one in the last bit of a 16-bit output.
+ * Process-wide, not thread safe. */
+void mq_tune_force_splits(int parts);
+
 /* Per-kernel timing for benchmarks.  While enabled, every kernel launch of the library is bracketed by two HIP
  * events recorded on the stream it is launched on.  mq_prof_read waits for the pending events of one slot and
  * returns, accumulated since the last reset: the kernel's name (host buffer), number of launches, elapsed

@@ -20,7 +20,7 @@ _ERRORS = {
     -5: "MQ_ERR_HIP", -6: "MQ_ERR_UNSUPPORTED_LAYOUT", -7: "MQ_ERR_OVERFLOW_RISK",
 }
 
-EXPORTS = ("mq_version", "mq_last_hip_error", "mq_tune_force_tile", "mq_prof_enable", "mq_prof_num_slots", "mq_prof_read",
+EXPORTS = ("mq_version", "mq_last_hip_error", "mq_tune_force_tile", "mq_tune_force_splits", "mq_prof_enable", "mq_prof_num_slots", "mq_prof_read",
            "mq_prof_reset", "mq_prof_phase_buffer", "mq_prof_filter", "mq_prof_bracket_overhead_us", "mq_prof_copy", "mq_quantize_weights", "mq_packed_bytes", "mq_pack_weights",
            "mq_unpack_weights", "mq_qlinear_w_only", "mq_qlinear_a8_workspace_bytes", "mq_qlinear_w8a8",
            "mq_qlinear_w4a8", "mq_bos_aware_kv_proj_workspace_bytes", "mq_bos_aware_kv_proj")
@@ -58,6 +58,10 @@ def version() -> int:
 
 def tune_force_tile(tile: int) -> None:
     load().mq_tune_force_tile(int(tile))
+
+
+def tune_force_splits(parts: int) -> None:
+    load().mq_tune_force_splits(int(parts))
 
 
 def prof_phase_buffer(buf: Optional[torch.Tensor]) -> None:

@@ -20,6 +20,7 @@
 //     that every lane's global and LDS accesses are 16 bytes wide.
 #include <stdio.h>
 
+#include <mutex>
 #include <type_traits>
 
 #include "mq_common.h"
@@ -276,6 +277,11 @@ struct GemmArgs {
     long long* phase_clk;  // optional: 4 shader-clock samples per workgroup (start, loop, epilogue, end)
     RowMap out_map;
     int32_t* acc_debug;
+    // split of the reduction over `splits` workgroups per tile (1 = none): partial accumulators in `partial`
+    // ([tile][split][BM * BN] 4-byte values, register order), one arrival counter per tile (zero between launches)
+    int splits;
+    uint32_t* partial;
+    uint32_t* counters;
 };
 
 // Workgroup id -> tile.  Consecutive workgroup ids land on different XCDs (8 of them, each with its own L2),
@@ -337,7 +343,13 @@ void gemm_kernel(const GemmArgs g) {
     const int grp = wv / P::NWG, wvg = wv % P::NWG;  // k-split group, wave inside the group
     const int wm = wvg / WGN, wn = wvg % WGN;
     int bm, bn;
-    tile_of_block(blockIdx.x, g.tiles_m, g.tiles_n, bm, bn);
+    // (the large wave tile has no registers to spare for the split of the reduction over workgroups, and no use
+    // for it: its problems have hundreds of tiles)
+    constexpr bool CAN_SPLIT = TM * TN <= 4;
+    const int splits = CAN_SPLIT ? g.splits : 1;
+    const int tile_id = splits > 1 ? (int)blockIdx.x / splits : (int)blockIdx.x;
+    const int sp = (int)blockIdx.x - tile_id * splits;  // which part of the reduction this workgroup takes
+    tile_of_block(tile_id, g.tiles_m, g.tiles_n, bm, bn);
     const int m0 = bm * BM, n0 = bn * BN;
     const int KC = g.K >> 6;
     const int G = (g.N + 31) >> 5;
@@ -428,9 +440,13 @@ void gemm_kernel(const GemmArgs g) {
 
     // Every wave issues exactly OPS loads per stage (padding loads go to the sink), so that "at most n * OPS loads
     // outstanding" means "all but the n youngest stages have landed" for every wave alike.
+    const int KSTEPS = g.k_stages;                // 128-byte k steps
+    const int KT_ALL = (KSTEPS + KS - 1) / KS;    // pipeline stages of the whole reduction
+    const int kt0 = splits > 1 ? (int)((long)sp * KT_ALL / splits) : 0;
+    const int KT = (splits > 1 ? (int)((long)(sp + 1) * KT_ALL / splits) : KT_ALL) - kt0;  // ... of this workgroup
     auto issue = [&](int stage, int buf) {
-        const int soff_a = __builtin_amdgcn_readfirstlane(stage * KS * 128);
-        const int soff_b = __builtin_amdgcn_readfirstlane(stage * KS * CH * TILE_B);
+        const int soff_a = __builtin_amdgcn_readfirstlane((kt0 + stage) * KS * 128);
+        const int soff_b = __builtin_amdgcn_readfirstlane((kt0 + stage) * KS * CH * TILE_B);
         const uint32_t sb = lds_base + buf * STAGE_BYTES;
 #pragma unroll
         for (int i = 0; i < P::DMA_A; ++i)
@@ -452,8 +468,6 @@ void gemm_kernel(const GemmArgs g) {
 
     long long t0 = 0, t1 = 0, t2 = 0;
     if (g.phase_clk) t0 = clock64();
-    const int KSTEPS = g.k_stages;                // 128-byte k steps
-    const int KT = (KSTEPS + KS - 1) / KS;        // pipeline stages
 #pragma unroll
     for (int s = 0; s < S; ++s)
         if (s < KT) issue(s, s);
@@ -515,7 +529,7 @@ void gemm_kernel(const GemmArgs g) {
     for (int kt = 0; kt < KT; ++kt) {
         const uint8_t* abuf = lds + buf * STAGE_BYTES + grp * P::SUB_BYTES;
         // odd tail of a k-split: the last k step of group 1 does not exist (it still takes part in the barriers)
-        const bool live = KS == 1 || kt * KS + grp < KSTEPS;
+        const bool live = KS == 1 || (kt0 + kt) * KS + grp < KSTEPS;
         frag_t wf[2][TN];
         // step 0
 #pragma unroll
@@ -627,6 +641,79 @@ void gemm_kernel(const GemmArgs g) {
     }
 
     if constexpr (KS == 1) __syncthreads();  // constants visible (the k-split exchange above has its own barriers)
+
+    // Reduction split over workgroups: every workgroup stores its partial sums (register order, one 4-byte value per
+    // lane per store: fully coalesced; rows past M skipped), then takes a ticket; the one that draws the last ticket
+    // adds the partial sums of all parts, its own included, in part order (so the result does not depend on which
+    // workgroup came last) and goes on to the epilogue; the others are done.  Nobody waits for anybody.
+    // The partial sums are written and read with device-scope atomic accesses (write-through stores, loads that
+    // bypass the L2 of the reader's XCD), so no cache has to be flushed: the wait for the stores' completion before
+    // the ticket is all the ordering that is needed.
+    if (CAN_SPLIT && splits > 1) {
+        using elem_t = typename std::conditional<I8, int, float>::type;
+        const size_t tile_elems = (size_t)BM * BN;
+        elem_t* mine = (elem_t*)(g.partial + ((size_t)tile_id * splits + sp) * tile_elems);
+#pragma unroll
+        for (int tm = 0; tm < TM; ++tm) {
+            if (KS > 1 && owner(tm) != grp) continue;
+            if (m0 + (wm * TM + tm) * 32 + l31 >= g.M) continue;
+#pragma unroll
+            for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+                for (int i = 0; i < 16; ++i)
+                    __hip_atomic_store(mine + (((wvg * TM + tm) * TN + tn) * 16 + i) * 64 + lane, (elem_t)acc[tm][tn][i],
+                                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        wait_vmcnt<0>();  // this wave's stores have completed (reached the level all compute units see)
+        __syncthreads();
+        uint32_t* ticket = (uint32_t*)(lds + P::SINK);  // the sink of padding loads is idle by now
+        if (threadIdx.x == 0)
+            *ticket = __hip_atomic_fetch_add(g.counters + tile_id, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __syncthreads();
+        if (*ticket != (uint32_t)(splits - 1)) return;
+        if (threadIdx.x == 0) g.counters[tile_id] = 0;  // ready for the next launch that is handed this counter
+#pragma unroll
+        for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+            for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) acc[tm][tn][i] = 0;
+        // (the loads of PU parts are requested together where the registers allow; the additions keep part order)
+        constexpr int PU = TM * TN == 1 ? 4 : 1;
+        for (int part0 = 0; part0 < splits; part0 += PU) {
+            elem_t v[PU][TM][TN][16];
+#pragma unroll
+            for (int u = 0; u < PU; ++u) {
+                const int part = part0 + u < splits ? part0 + u : splits - 1;
+                const elem_t* theirs = (const elem_t*)(g.partial + ((size_t)tile_id * splits + part) * tile_elems);
+#pragma unroll
+                for (int tm = 0; tm < TM; ++tm) {
+                    if (KS > 1 && owner(tm) != grp) continue;
+                    if (m0 + (wm * TM + tm) * 32 + l31 >= g.M) continue;
+#pragma unroll
+                    for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+                        for (int i = 0; i < 16; ++i)
+                            v[u][tm][tn][i] =
+                                __hip_atomic_load(theirs + (((wvg * TM + tm) * TN + tn) * 16 + i) * 64 + lane,
+                                                  __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < PU; ++u) {
+                if (part0 + u >= splits) break;
+#pragma unroll
+                for (int tm = 0; tm < TM; ++tm) {
+                    if (KS > 1 && owner(tm) != grp) continue;
+                    if (m0 + (wm * TM + tm) * 32 + l31 >= g.M) continue;
+#pragma unroll
+                    for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+                        for (int i = 0; i < 16; ++i) acc[tm][tn][i] += v[u][tm][tn][i];
+                }
+            }
+        }
+    }
     if (g.phase_clk) t2 = clock64();
     // ---------------------------------------------------------------- epilogue
     // Result element v of a lane is channel 8*(v/4) + 4*kb + v%4 of its 32-channel tile, activation row l31:
@@ -730,6 +817,56 @@ void set_phase_buffer(long long* p, long workgroups) {
 }
 void set_force_tile(int t) { g_force_tile = t; }
 
+// ---- reduction split over workgroups: scratch of the library --------------------------------------------------
+// Problems with few tiles and a long reduction (K/V projections, a handful of activation rows) are bound by memory
+// latency: the only remedy is to have more workgroups request the operands at once.  Their partial sums go through
+// a ring of device memory that belongs to the library, with one arrival counter per tile.  A launch is handed the
+// next stretch of both rings; counters are zero when handed out and the kernel leaves them zero.  Launches on one
+// stream run one after the other, so they never share live scratch; launches that run at the same time on several
+// streams are safe as long as what they need together fits the ring (a stretch is reused one full turn later).
+static constexpr size_t kSplitRingBytes = 32u << 20;
+static constexpr int kSplitCounters = 16384;
+static __device__ __attribute__((aligned(256))) uint32_t g_split_ring[kSplitRingBytes / 4];
+static __device__ __attribute__((aligned(256))) uint32_t g_split_counters[kSplitCounters];
+static int g_force_splits = 0;  // 0: automatic, 1: never, n > 1: n parts wherever the reduction is long enough
+void set_force_splits(int n) { g_force_splits = n < 0 ? 0 : n; }
+
+namespace {
+struct SplitScratch {
+    uint32_t* ring = nullptr;
+    uint32_t* counters = nullptr;
+    size_t ring_cursor = 0;  // bytes
+    int counter_cursor = 0;
+};
+std::mutex g_split_mutex;
+SplitScratch g_split_dev[16];
+
+// Hands out `bytes` of the ring and `tiles` counters of the current device; false if the request cannot be served.
+bool take_split_scratch(size_t bytes, int tiles, uint32_t** partial, uint32_t** counters) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 16) return false;
+    if (bytes > kSplitRingBytes / 2 || tiles > kSplitCounters / 2) return false;
+    std::lock_guard<std::mutex> lock(g_split_mutex);
+    SplitScratch& sc = g_split_dev[dev];
+    if (!sc.ring) {
+        void *r = nullptr, *c = nullptr;
+        if (hipGetSymbolAddress(&r, HIP_SYMBOL(g_split_ring)) != hipSuccess ||
+            hipGetSymbolAddress(&c, HIP_SYMBOL(g_split_counters)) != hipSuccess)
+            return false;
+        sc.ring = (uint32_t*)r;
+        sc.counters = (uint32_t*)c;
+    }
+    bytes = (bytes + 255) & ~(size_t)255;
+    if (sc.ring_cursor + bytes > kSplitRingBytes) sc.ring_cursor = 0;
+    if (sc.counter_cursor + tiles > kSplitCounters) sc.counter_cursor = 0;
+    *partial = sc.ring + sc.ring_cursor / 4;
+    *counters = sc.counters + sc.counter_cursor;
+    sc.ring_cursor += bytes;
+    sc.counter_cursor += tiles;
+    return true;
+}
+}  // namespace
+
 // Measured on the SDXL shapes: the large tile wins once it yields two or more workgroups per compute unit; the
 // k-split variants only pay where tiles are few and k is long (FF-out at the 640 level, the K/V projections).
 static int pick_tile(int M, int N, int K, bool wide_weights = false) {
@@ -765,7 +902,23 @@ static int run_gemm(GemmArgs& g, int tile_index, hipStream_t st) {
     static_assert(P::LDS_BYTES <= 160 * 1024, "LDS plan exceeds the compute unit");
     g.tiles_m = (g.M + P::BM - 1) / P::BM;
     g.tiles_n = (g.N + P::BN - 1) / P::BN;
-    g.phase_clk = ((long)g.tiles_m * g.tiles_n <= g_phase_cap) ? g_phase_clk : nullptr;
+    // Split the reduction over workgroups where the tiles alone would leave most compute units idle and the reduction
+    // is long: as many parts as fill about two workgroups per compute unit, each at least four pipeline stages long.
+    const long tiles = (long)g.tiles_m * g.tiles_n;
+    const int KT = (g.k_stages + KS - 1) / KS;
+    int splits = 1;
+    if (g_force_splits > 1) {
+        splits = g_force_splits < KT ? g_force_splits : KT;
+    } else if (g_force_splits == 0 && tiles <= 64 && KT >= 16) {
+        // (measured: handing the sums over costs about as much as eight pipeline stages)
+        splits = (int)(512 / tiles);
+        if (splits > KT / 4) splits = KT / 4;
+        if (splits > 16) splits = 16;
+    }
+    g.splits = 1;
+    if (TM * TN <= 4 && splits > 1 && take_split_scratch((size_t)tiles * splits * P::BM * P::BN * 4, (int)tiles, &g.partial, &g.counters))
+        g.splits = splits;
+    g.phase_clk = (tiles * g.splits <= g_phase_cap) ? g_phase_clk : nullptr;
     auto kern = gemm_kernel<I8, BITS, WGM, WGN, TM, TN, S, KS, BF>;
     static bool prepared = false;  // once per instantiation: allow more than 64 KB of dynamic LDS, name the slot
     const int slot = prof_gemm_slot(I8 ? 1 : (BF ? 2 : 0), BITS, tile_index);
@@ -784,7 +937,7 @@ static int run_gemm(GemmArgs& g, int tile_index, hipStream_t st) {
     const double abytes = I8 ? 1.0 * g.M * g.K + 4.0 * g.M : 2.0 * g.M * g.K;
     ProfScope prof(st, slot, 2.0 * g.M * g.N * g.K,
                    abytes + (double)g.N * g.K * BITS / 8 + (I8 ? 14.0 : 10.0) * g.N + 2.0 * g.M * g.N);
-    hipLaunchKernelGGL(kern, dim3(g.tiles_m * g.tiles_n), dim3(P::NT), P::LDS_BYTES, st, g);
+    hipLaunchKernelGGL(kern, dim3(g.tiles_m * g.tiles_n * g.splits), dim3(P::NT), P::LDS_BYTES, st, g);
     MQ_HIP_CHECK_LAUNCH();
     return MQ_OK;
 }

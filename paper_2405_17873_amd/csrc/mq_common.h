@@ -87,6 +87,7 @@ int launch_gemm_a8(const int8_t* a8, const int32_t* rowsum, const ActParams* par
                    hipStream_t st);
 
 void set_force_tile(int t);
+void set_force_splits(int n);
 void set_phase_buffer(long long* p, long workgroups);
 
 // ---- optional per-kernel event timing (prof.hip) ----

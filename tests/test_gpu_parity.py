@@ -218,6 +218,51 @@ def test_w_only_transformer_block_shapes_sampled_rows(mq, orc, M, K, N):
             ref.view(np.float16).astype(np.float64)).max() + 1
 
 
+# ----------------------------------------------------------------------------------------------- reduction split over workgroups
+
+SPLIT_SHAPES = [(1, 5120, 1280), (16, 1280, 320), (77, 2048, 1280), (308, 2048, 640), (130, 640, 96), (33, 256, 40)]
+
+
+@pytest.mark.parametrize("tile", (-1, 1, 2, 3, 4))
+@pytest.mark.parametrize("parts", (0, 2, 3, 7))
+def test_split_reduction_matches_oracle(mq, orc, tile, parts):
+    """Few tiles, long reduction: several workgroups per tile, partial sums through the library's scratch ring.
+    parts = 0 is the automatic choice; forced part counts also cover uneven splits and the k-split tiles."""
+    mq.tune_force_tile(tile)
+    mq.tune_force_splits(parts)
+    try:
+        for (M, K, N) in SPLIT_SHAPES:
+            x = si.activations_f16(31, f"sp/x{M}x{K}", M, K, outlier_prob=0.01)
+            w = si.weights_f16(31, f"sp/w{N}x{K}", N, K)
+            b = si.bias_f16(31, f"sp/b{N}", N)
+            for bits in (4, 3):
+                pw, oc, os_, oz = make_weight(mq, orc, w, bits)
+                y = mq.qlinear_w_only(dev(x), pw, dev(b))
+                assert_close16(host(y), orc.linear_w_only(x, oc, os_, oz, b), f"split w{bits} {M}x{K}x{N} parts{parts}")
+            pw, oc, os_, oz = make_weight(mq, orc, w, 4)
+            y, acc, _ = mq.qlinear_w4a8(dev(x), pw, bias=dev(b), want_acc=True)
+            ry, racc, _ = orc.linear_a8(x, oc, os_, oz, bias=b)
+            assert np.array_equal(host(acc), racc), f"split acc {M}x{K}x{N} parts{parts}"
+            assert_close16(host(y), ry, f"split a4 {M}x{K}x{N} parts{parts}")
+    finally:
+        mq.tune_force_splits(0)
+        mq.tune_force_tile(-1)
+
+
+def test_split_reduction_is_deterministic_and_reuses_its_scratch(mq, orc):
+    """Many launches in a row walk the scratch ring several times round; every result is bit-identical."""
+    M, K, N = 64, 5120, 1280
+    x = dev(si.activations_f16(32, "sp/det", M, K))
+    pw, *_ = make_weight(mq, orc, si.weights_f16(32, "sp/detw", N, K), 4)
+    mq.tune_force_splits(16)  # 20 tiles x 16 parts x 16 KB = 5 MB per launch: the 32 MB ring wraps every 6 launches
+    try:
+        y0 = mq.qlinear_w_only(x, pw).clone()
+        for _ in range(40):
+            assert torch.equal(mq.qlinear_w_only(x, pw), y0)
+    finally:
+        mq.tune_force_splits(0)
+
+
 # ----------------------------------------------------------------------------------------------- 8-bit activations
 
 A8_SHAPES = [(256, 320, 320), (1, 64, 32), (77, 128, 40), (608, 2048, 640), (300, 1280, 264), (130, 192, 64)]
