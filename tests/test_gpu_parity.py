@@ -324,6 +324,67 @@ def test_a8_transformer_block_shapes_sampled_rows(mq, orc, K, N):
         assert_close16(host(y)[rows], ry, f"c3 W{bits}A8 {K}->{N}")
 
 
+def test_a8_longest_reduction_and_extreme_codes(mq, orc):
+    """K = 33024 is the longest reduction the int32 accumulator is guaranteed to hold (255 * 255 * K < 2^31).  All
+    activation codes and all weight codes are 0 or 255 with zero points 0; row 0 against channel 0 is 255 * 255 in
+    every term, which puts that accumulator within 1e-4 of the int32 limit."""
+    M, K, N = 40, 33024, 72
+    rng = np.random.default_rng(33024)
+    x = np.where(rng.random((M, K)) < 0.5, 0.0, 1.0)
+    x[0] = 1.0
+    w = np.where(rng.random((N, K)) < 0.5, 0.0, 0.02)
+    w[0] = 0.02
+    x, w = x.astype(np.float16), w.astype(np.float16)
+    pw, oc, os_, oz = make_weight(mq, orc, w, 8)
+    y, acc, _ = mq.qlinear_w8a8(dev(x), pw, want_acc=True)
+    ry, racc, _ = orc.linear_a8(x, oc, os_, oz)
+    assert int(racc[0, 0]) == 255 * 255 * K and 255 * 255 * K > 0.9999 * 2 ** 31
+    assert np.array_equal(host(acc), racc)
+    assert_close16(host(y), ry, "longest reduction")
+
+
+def test_many_rows_and_smallest_problem(mq, orc):
+    """70001 activation rows (a ragged multiple of every tile height) against the smallest weight the layout allows,
+    and a 1 x 64 -> 8 problem."""
+    for (M, K, N, bits) in ((70001, 64, 32, 2), (1, 64, 8, 3), (3, 64, 8, 8)):
+        x = si.activations_f16(41, f"edge/x{M}", M, K)
+        w = si.weights_f16(41, f"edge/w{N}", N, K)
+        pw, oc, os_, oz = make_weight(mq, orc, w, bits)
+        assert_close16(host(mq.qlinear_w_only(dev(x), pw)), orc.linear_w_only(x, oc, os_, oz), f"edge w{bits} M={M}")
+        if bits == 8:
+            y, acc, _ = mq.qlinear_w8a8(dev(x), pw, want_acc=True)
+            ry, racc, _ = orc.linear_a8(x, oc, os_, oz)
+            assert np.array_equal(host(acc), racc)
+            assert_close16(host(y), ry, "edge a8")
+
+
+def test_degenerate_tensors(mq, orc):
+    """Constant activations (all zero: scale 1, zero point 0; all equal and positive: the range is [0, v]) and weight
+    rows that are constant or zero."""
+    M, K, N = 96, 128, 64
+    w = si.weights_f16(42, "deg/w", N, K)
+    w[0] = 0
+    w[1] = np.float16(0.015)
+    w[2] = np.float16(-0.015)
+    b = si.bias_f16(42, "deg/b", N)
+    for bits, fn in ((4, mq.qlinear_w4a8), (8, mq.qlinear_w8a8)):
+        pw, oc, os_, oz = make_weight(mq, orc, w, bits)
+        for fill in (0.0, 0.75, -2.0):
+            x = np.full((M, K), fill, np.float16)
+            y, acc, (s_out, z_out) = fn(dev(x), pw, bias=dev(b), want_acc=True, want_act=True)
+            ry, racc, (rs, rz) = orc.linear_a8(x, oc, os_, oz, bias=b)
+            assert host(s_out)[0] == rs and host(z_out)[0] == rz
+            assert np.array_equal(host(acc), racc)
+            assert_close16(host(y), ry, f"degenerate a8 fill {fill}")
+            assert_close16(host(mq.qlinear_w_only(dev(x), pw, dev(b))), orc.linear_w_only(x, oc, os_, oz, b),
+                           f"degenerate w_only fill {fill}")
+    x = np.zeros((M, K), np.float16)
+    pw, *_ = make_weight(mq, orc, w, 4)
+    y, _, (s_out, z_out) = mq.qlinear_w4a8(dev(x), pw, bias=dev(b), want_act=True)
+    assert host(s_out)[0] == 1.0 and host(z_out)[0] == 0
+    assert np.array_equal(host(y), np.broadcast_to(b.view(np.float16), (M, N)))  # zero input: the output is the bias
+
+
 # ----------------------------------------------------------------------------------------------- BOS-aware K/V
 
 @pytest.mark.parametrize("N", (640, 1280))
