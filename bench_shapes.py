@@ -31,12 +31,13 @@ LLC_BYTES = 320 << 20
 
 def shapes():
     S = []
-    # (label, M, K, N, modes)   modes: w<bits> weight-only, a4/a8 dynamic, s4/s8 static activation parameters
+    # (label, M, K, N, modes)   modes: w<bits> weight-only (w16: the layer kept at fp16), a4/a8 dynamic, s4/s8 static
+    # activation parameters, bos<bits> the BOS-aware K/V projection
     S.append(("c1", 256, 320, 320, ("w4", "a8sym")))
     for (K, N) in ((640, 640), (640, 5120), (2560, 640)):
-        S.append(("c2", 4096, K, N, ("w8", "w4", "w3", "w2")))
+        S.append(("c2", 4096, K, N, ("w16", "w8", "w4", "w3", "w2")))
     for (K, N) in ((1280, 1280), (1280, 10240), (5120, 1280)):
-        S.append(("c3", 4096, K, N, ("a4", "a8sym", "s4", "w4")))
+        S.append(("c3", 4096, K, N, ("a4", "a8sym", "s4", "w4", "w16")))
     for N in (640, 1280):
         S.append(("c4", 8 * 77, 2048, N, ("bos8", "bos4")))
     for (K, N) in ((640, 640), (640, 5120), (2560, 640)):
@@ -76,7 +77,7 @@ def main():
             bos = mode.startswith("bos")
             sym = mode.endswith("sym")
             kind = "w" if mode[0] == "w" else "a"
-            bits = int(mode.replace("sym", "").replace("bos", "")[-1]) if not bos else int(mode[3:])
+            bits = int(mode[3:]) if bos else (16 if mode == "w16" else int(mode.replace("sym", "")[-1]))
             xbytes = 2 * M * K
             wbytes = N * K * bits // 8
             alg_bytes = xbytes + wbytes + 10 * N + 2 * M * N
@@ -86,9 +87,12 @@ def main():
             ws = None
             for _ in range(nsets):
                 w = (torch.randn(N, K, generator=gen, device=dev) * 0.02).half()
-                c, s, z = mq.quantize_weights(w, bits, sym)
-                p, cs = mq.pack_weights(c, bits, mq.LAYOUT_KERNEL, codes_signed=sym)
-                pw = mq.PackedWeight(p, s, z, cs, N, K, bits, mq.LAYOUT_KERNEL, sym)
+                if bits == 16:
+                    pw = mq.keep_weights_16bit(w)
+                else:
+                    c, s, z = mq.quantize_weights(w, bits, sym)
+                    p, cs = mq.pack_weights(c, bits, mq.LAYOUT_KERNEL, codes_signed=sym)
+                    pw = mq.PackedWeight(p, s, z, cs, N, K, bits, mq.LAYOUT_KERNEL, sym)
                 bias = (torch.randn(N, generator=gen, device=dev) * 0.01).half()
                 if bos:
                     B, T = M // 77, 77

@@ -111,6 +111,8 @@ int mq_quantize_weights(const void* w, int N, int K, int bits, int symmetric, in
 
 /* Size in bytes of the packed form of an N x K code matrix.  Canonical: N*K*bits/8 (needs K*bits % 8 == 0).
  * Kernel layout: ceil(N/32)*32 rows are stored (padding rows hold code 0), K % 64 == 0 is required.
+ * bits = 16 stands for unquantised 16-bit weights (paper Sec. 4.2 and App. C item 1: about 1 % of the layers,
+ * the most sensitive ones, stay at FP16): they take the same tile order, 2 bytes per weight.
  * Returns 0 for an unsupported combination. */
 size_t mq_packed_bytes(int N, int K, int bits, int layout);
 
@@ -119,11 +121,14 @@ size_t mq_packed_bytes(int N, int K, int bits, int layout);
  *   packed  mq_packed_bytes(...) bytes out.
  *   colsum  nullable [N] int32 out: sum over k of the code, read as two's complement int8 when
  *           codes_signed != 0 (8-bit symmetric weights), else as unsigned.  The integer GEMMs need it.
+ *   bits = 16: `codes` points to [N,K] 16-bit values (fp16 or bf16 bit patterns; the packer only moves them),
+ *           canonical is the matrix itself, colsum must be null.
  * Errors: as above plus MQ_ERR_BAD_SHAPE when K is not a multiple of the layout's group. */
 int mq_pack_weights(const uint8_t* codes, int N, int K, int bits, int layout, int codes_signed, void* packed,
                     int32_t* colsum, void* stream);
 
-/* Inverse of mq_pack_weights for either layout (a test aid; also converts between layouts). */
+/* Inverse of mq_pack_weights for either layout (a test aid; also converts between layouts).  bits = 16: `codes`
+ * receives [N,K] 16-bit values. */
 int mq_unpack_weights(const void* packed, int N, int K, int bits, int layout, uint8_t* codes, void* stream);
 
 /* ------------------------------------------------------------------------------------------------
@@ -134,7 +139,9 @@ int mq_unpack_weights(const void* packed, int N, int K, int bits, int layout, ui
  *     Y[m,n] = round16( sum_k X[m,k] * scale[n] * (code[n,k] - zp[n]) + bias[n] ),  fp32 accumulation.
  *   x      [M,K] row stride ldx, 16-byte aligned, ldx % 8 == 0.     y [M,N] row stride ldy, 16-byte aligned, ldy % 8 == 0.
  *   packed MQ_LAYOUT_KERNEL, unsigned codes.   bias nullable [N] (same 16-bit dtype as x and y).
- *   K % 64 == 0, N % 8 == 0, M*ldx*2 < 2^31 bytes.  No workspace is needed. */
+ *   K % 64 == 0, N % 8 == 0, M*ldx*2 < 2^31 bytes.  No workspace is needed.
+ *   bits = 16: the layer is kept at 16 bits; packed holds the weights themselves (same dtype as x) in
+ *   MQ_LAYOUT_KERNEL, w_scale and w_zp are ignored (may be null):  Y = round16( sum_k X[m,k] * W[n,k] + bias[n] ). */
 int mq_qlinear_w_only(const void* x, int M, int K, int ldx, const void* packed, int N, int bits, int layout,
                       const float* w_scale, const int32_t* w_zp, const void* bias, void* y, int ldy, int dtype,
                       void* stream);

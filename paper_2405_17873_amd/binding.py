@@ -131,14 +131,20 @@ def _dtype_code(t: torch.Tensor) -> int:
 class PackedWeight:
     """A quantised, packed weight matrix resident on the GPU (what the offline step hands to the hot path)."""
     packed: torch.Tensor      # uint8 bytes
-    scale: torch.Tensor       # float32 [N]
-    zp: torch.Tensor          # int32 [N]
+    scale: Optional[torch.Tensor]   # float32 [N] (None for unquantised 16-bit weights)
+    zp: Optional[torch.Tensor]      # int32 [N]
     colsum: Optional[torch.Tensor]  # int32 [N]
     N: int
     K: int
     bits: int
     layout: int
     signed: bool
+
+
+def keep_weights_16bit(w: torch.Tensor) -> PackedWeight:
+    """An unquantised fp16/bf16 weight matrix in the layout the GEMM reads (a layer kept at 16 bits)."""
+    packed, _ = pack_weights(w, 16, LAYOUT_KERNEL)
+    return PackedWeight(packed, None, None, None, w.shape[0], w.shape[1], 16, LAYOUT_KERNEL, False)
 
 
 def quantize_weights(w: torch.Tensor, bits: int, symmetric: bool = False):
@@ -159,19 +165,22 @@ def packed_bytes(N: int, K: int, bits: int, layout: int) -> int:
 
 def pack_weights(codes: torch.Tensor, bits: int, layout: int = LAYOUT_KERNEL, codes_signed: bool = False,
                  want_colsum: bool = True):
-    """codes uint8 [N,K] -> (packed uint8 [bytes], colsum int32 [N] or None)."""
-    assert codes.is_cuda and codes.dtype == torch.uint8 and codes.is_contiguous()
+    """codes uint8 [N,K] -> (packed uint8 [bytes], colsum int32 [N] or None).  bits = 16: `codes` is the fp16/bf16
+    weight matrix itself and there is no colsum."""
+    assert codes.is_cuda and codes.dim() == 2 and codes.is_contiguous()
+    assert codes.dtype == torch.uint8 if bits != 16 else codes.dtype in (torch.float16, torch.bfloat16)
     N, K = codes.shape
     nbytes = packed_bytes(N, K, bits, layout)
     packed = torch.empty(max(nbytes, 1), dtype=torch.uint8, device=codes.device)
-    colsum = torch.empty(N, dtype=torch.int32, device=codes.device) if want_colsum else None
+    colsum = torch.empty(N, dtype=torch.int32, device=codes.device) if (want_colsum and bits != 16) else None
     _check(load().mq_pack_weights(_ptr(codes), N, K, bits, layout, int(codes_signed), _ptr(packed), _ptr(colsum),
                                   _stream()), "mq_pack_weights")
     return packed, colsum
 
 
-def unpack_weights(packed: torch.Tensor, N: int, K: int, bits: int, layout: int) -> torch.Tensor:
-    codes = torch.empty((N, K), dtype=torch.uint8, device=packed.device)
+def unpack_weights(packed: torch.Tensor, N: int, K: int, bits: int, layout: int, dtype=torch.float16) -> torch.Tensor:
+    """Codes uint8 [N,K]; for bits = 16 the weight matrix in `dtype`."""
+    codes = torch.empty((N, K), dtype=torch.uint8 if bits != 16 else dtype, device=packed.device)
     _check(load().mq_unpack_weights(_ptr(packed), N, K, bits, layout, _ptr(codes), _stream()), "mq_unpack_weights")
     return codes
 

@@ -11,6 +11,8 @@ void set_hip_error(int e) { g_last_hip_error.store(e); }
 static inline bool aligned(const void* p, size_t a) { return ((uintptr_t)p % a) == 0; }
 static inline size_t up256(size_t v) { return (v + 255) / 256 * 256; }
 static inline bool bits_ok(int b) { return b == 2 || b == 3 || b == 4 || b == 8; }
+// 16: unquantised 16-bit weights, accepted by the packers and by the weight-only linear
+static inline bool bits_ok16(int b) { return bits_ok(b) || b == 16; }
 
 // Workspace of the 8-bit-activation path.
 struct A8Workspace {
@@ -37,15 +39,17 @@ struct A8Workspace {
 };
 
 static int check_linear_common(const void* x, int M, int K, int ldx, const void* packed, int N, int layout,
-                               const float* w_scale, const int32_t* w_zp, const void* bias, const void* y, int ldy) {
-    if (!x || !packed || !w_scale || !w_zp || !y) return MQ_ERR_BAD_ARG;
+                               const float* w_scale, const int32_t* w_zp, const void* bias, const void* y, int ldy,
+                               bool need_params = true) {
+    if (!x || !packed || !y) return MQ_ERR_BAD_ARG;
+    if (need_params && (!w_scale || !w_zp)) return MQ_ERR_BAD_ARG;
     if (M <= 0 || K <= 0 || N <= 0 || ldx < K || ldy < N) return MQ_ERR_BAD_SHAPE;
     if (layout != MQ_LAYOUT_KERNEL) return MQ_ERR_UNSUPPORTED_LAYOUT;
     if (K % 64 != 0 || N % 8 != 0 || ldx % 8 != 0 || ldy % 8 != 0) return MQ_ERR_BAD_SHAPE;
     // lane offsets into X and into the packed weights are 32-bit
     if ((long)M * ldx * 2 >= (1L << 31) || (long)(N + 31) * K >= (1L << 31)) return MQ_ERR_BAD_SHAPE;
-    if (!aligned(x, 16) || !aligned(packed, 16) || !aligned(w_scale, 16) || !aligned(w_zp, 16) || !aligned(y, 16) ||
-        (bias && !aligned(bias, 8)))
+    if (!aligned(x, 16) || !aligned(packed, 16) || (w_scale && !aligned(w_scale, 16)) ||
+        (w_zp && !aligned(w_zp, 16)) || !aligned(y, 16) || (bias && !aligned(bias, 8)))
         return MQ_ERR_BAD_ARG;
     return MQ_OK;
 }
@@ -103,7 +107,7 @@ int mq_quantize_weights(const void* w, int N, int K, int bits, int symmetric, in
 }
 
 size_t mq_packed_bytes(int N, int K, int bits, int layout) {
-    if (N <= 0 || K <= 0 || !bits_ok(bits)) return 0;
+    if (N <= 0 || K <= 0 || !bits_ok16(bits)) return 0;
     if (layout == MQ_LAYOUT_CANONICAL) {
         if (((long)K * bits) % 8 != 0) return 0;
         return (size_t)N * ((size_t)K * bits / 8);
@@ -119,9 +123,10 @@ int mq_pack_weights(const uint8_t* codes, int N, int K, int bits, int layout, in
                     int32_t* colsum, void* stream) {
     if (!codes || !packed) return MQ_ERR_BAD_ARG;
     if (N <= 0 || K <= 0) return MQ_ERR_BAD_SHAPE;
-    if (!bits_ok(bits)) return MQ_ERR_UNSUPPORTED_BITS;
+    if (!bits_ok16(bits)) return MQ_ERR_UNSUPPORTED_BITS;
     if (layout != MQ_LAYOUT_CANONICAL && layout != MQ_LAYOUT_KERNEL) return MQ_ERR_UNSUPPORTED_LAYOUT;
     if (codes_signed && bits != 8) return MQ_ERR_BAD_ARG;
+    if (bits == 16 && colsum) return MQ_ERR_BAD_ARG;  // no code sums of unquantised weights
     if (mq_packed_bytes(N, K, bits, layout) == 0) return MQ_ERR_BAD_SHAPE;
     if (layout == MQ_LAYOUT_KERNEL && !aligned(packed, 16)) return MQ_ERR_BAD_ARG;
     return launch_pack(codes, N, K, bits, layout, codes_signed ? 1 : 0, packed, colsum, (hipStream_t)stream);
@@ -130,7 +135,7 @@ int mq_pack_weights(const uint8_t* codes, int N, int K, int bits, int layout, in
 int mq_unpack_weights(const void* packed, int N, int K, int bits, int layout, uint8_t* codes, void* stream) {
     if (!codes || !packed) return MQ_ERR_BAD_ARG;
     if (N <= 0 || K <= 0) return MQ_ERR_BAD_SHAPE;
-    if (!bits_ok(bits)) return MQ_ERR_UNSUPPORTED_BITS;
+    if (!bits_ok16(bits)) return MQ_ERR_UNSUPPORTED_BITS;
     if (layout != MQ_LAYOUT_CANONICAL && layout != MQ_LAYOUT_KERNEL) return MQ_ERR_UNSUPPORTED_LAYOUT;
     if (mq_packed_bytes(N, K, bits, layout) == 0) return MQ_ERR_BAD_SHAPE;
     if (layout == MQ_LAYOUT_KERNEL && !aligned(packed, 16)) return MQ_ERR_BAD_ARG;
@@ -140,10 +145,11 @@ int mq_unpack_weights(const void* packed, int N, int K, int bits, int layout, ui
 int mq_qlinear_w_only(const void* x, int M, int K, int ldx, const void* packed, int N, int bits, int layout,
                       const float* w_scale, const int32_t* w_zp, const void* bias, void* y, int ldy, int dtype,
                       void* stream) {
-    if (!bits_ok(bits)) return MQ_ERR_UNSUPPORTED_BITS;
+    if (!bits_ok16(bits)) return MQ_ERR_UNSUPPORTED_BITS;
     if (dtype != MQ_F16 && dtype != MQ_BF16) return MQ_ERR_BAD_ARG;
-    int rc = check_linear_common(x, M, K, ldx, packed, N, layout, w_scale, w_zp, bias, y, ldy);
+    int rc = check_linear_common(x, M, K, ldx, packed, N, layout, w_scale, w_zp, bias, y, ldy, bits != 16);
     if (rc) return rc;
+    if (bits == 16) w_scale = nullptr, w_zp = nullptr;  // 16-bit weights are used as they are
     return launch_gemm_w_only(x, M, K, ldx, packed, N, bits, w_scale, w_zp, bias, y, ldy, dtype, (hipStream_t)stream);
 }
 

@@ -59,7 +59,7 @@ __device__ __forceinline__ half2v splat(float v) {
 // ---------------------------------------------------------------------------------------------
 template <int BITS>
 struct WChunk {
-    static constexpr int WORDS = BITS == 8 ? 8 : BITS;  // 32-bit words per lane per 64-k tile
+    static constexpr int WORDS = BITS == 8 ? 8 : BITS;  // 32-bit words per lane per 64-k tile (16: unquantised)
     uint32_t w[WORDS];
 };
 
@@ -153,6 +153,13 @@ __device__ __forceinline__ half8 dequant_step<8>(const WChunk<8>& c, int s, int 
     return half8{p0[0], p0[1], p1[0], p1[1], p2[0], p2[1], p3[0], p3[1]};
 }
 
+// 16 bit: the weights are unquantised fp16 (or bf16) values, piece s is the operand of step s as it stands.
+template <>
+__device__ __forceinline__ half8 dequant_step<16>(const WChunk<16>& c, int s, int) {
+    const uint4v v = {c.w[4 * s], c.w[4 * s + 1], c.w[4 * s + 2], c.w[4 * s + 3]};
+    return __builtin_bit_cast(half8, v);
+}
+
 // bfloat16 variant: the widened weights are small integers (|q - z| <= 255), exact in fp16 and in bf16 alike, so
 // the fp16 fragment is converted pair by pair: two fp16 -> fp32 conversions and one byte permute that keeps the
 // upper halves (which for these values is the exact bf16).
@@ -224,6 +231,12 @@ __device__ __forceinline__ void read_chunk(WChunk<BITS>& c, const uint8_t* tile,
     } else if constexpr (BITS == 3) {
         const uint32_t* p = (const uint32_t*)(tile + lane * 12);
         c.w[0] = p[0]; c.w[1] = p[1]; c.w[2] = p[2];
+    } else if constexpr (BITS == 16) {
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            const uint4v v = *(const uint4v*)(tile + s * 1024 + lane * 16);
+            c.w[4 * s] = v[0]; c.w[4 * s + 1] = v[1]; c.w[4 * s + 2] = v[2]; c.w[4 * s + 3] = v[3];
+        }
     } else {
         const uint4v v0 = *(const uint4v*)(tile + lane * 16);
         const uint4v v1 = *(const uint4v*)(tile + 1024 + lane * 16);
@@ -310,14 +323,15 @@ struct GemmPlan {
     static constexpr int BM = WGM * TM * 32, BN = WGN * TN * 32;
     static constexpr int CH = I8 ? 2 : 1;                     // 64-k weight tiles per 128-byte k step
     static constexpr int A_BYTES = BM * 128;
-    static constexpr int BSLOT = BITS == 8 ? 2048 : 1024;     // LDS slot of one weight tile
+    static constexpr int BSLOT = BITS == 16 ? 4096 : BITS == 8 ? 2048 : 1024;  // LDS slot of one weight tile
+    static constexpr int PIECES = BITS == 16 ? 4 : BITS == 8 ? 2 : 1;           // 1 KB wave loads per weight tile
     static constexpr int NBT = (BN / 32) * CH;                // weight tiles per sub-stage
     static constexpr int B_BYTES = NBT * BSLOT;
     static constexpr int SUB_BYTES = A_BYTES + B_BYTES;
     static constexpr int STAGE_BYTES = KS * SUB_BYTES;
     static constexpr int NAI = KS * (BM / 8);                 // LDS-writing loads per stage, activations
     static constexpr int DMA_A = NAI / NW;                    // ... per wave
-    static constexpr int NBI1 = NBT * (BITS == 8 ? 2 : 1);    // LDS-writing loads per sub-stage, weights
+    static constexpr int NBI1 = NBT * PIECES;                 // LDS-writing loads per sub-stage, weights
     static constexpr int NBI = KS * NBI1;
     static constexpr int DMA_B = (NBI + NW - 1) / NW;         // per wave (padded with loads into the sink)
     static constexpr int OPS = DMA_A + DMA_B;                 // vector-memory operations per wave per stage
@@ -377,8 +391,8 @@ void gemm_kernel(const GemmArgs g) {
     }
     // weight loads: instruction jj of a sub-stage copies piece jj % PCS of weight tile jj / PCS (tile = channel group,
     // chunk)
-    constexpr int PCS = BITS == 8 ? 2 : 1;
-    constexpr int VALID_LANES = BITS == 8 ? 64 : 16 * BITS;  // lanes of a 16-byte-per-lane copy that hold tile data
+    constexpr int PCS = P::PIECES;
+    constexpr int VALID_LANES = BITS >= 8 ? 64 : 16 * BITS;  // lanes of a 16-byte-per-lane copy that hold tile data
     int b_voff[P::DMA_B];
     uint32_t b_lds[P::DMA_B];
 #pragma unroll
@@ -401,7 +415,7 @@ void gemm_kernel(const GemmArgs g) {
         int gi = (n0 >> 5) + wn * TN + tn;
         gi = gi < G ? gi : G - 1;
         const int n = gi * 32 + l31;
-        zc[tn] = I8 ? 0 : g.w_zp[n < g.N ? n : g.N - 1];
+        zc[tn] = (I8 || BITS == 16) ? 0 : g.w_zp[n < g.N ? n : g.N - 1];
     }
 
     acc_t acc[TM][TN];
@@ -422,7 +436,7 @@ void gemm_kernel(const GemmArgs g) {
     if (threadIdx.x < BN) {
         int n = n0 + threadIdx.x;
         n = n < g.N ? n : g.N - 1;
-        c_scale = g.w_scale[n];
+        c_scale = BITS == 16 ? 1.0f : g.w_scale[n];
         if (g.bias) c_bias = BF ? bf16_bits_to_float(g.bias[n]) : (float)__builtin_bit_cast(_Float16, g.bias[n]);
         if constexpr (I8) {
             c_zp = g.w_zp[n];
@@ -498,7 +512,7 @@ void gemm_kernel(const GemmArgs g) {
                 wf[tn] = widen_step<BITS>(wq[tn][s >> 1], s & 1, xflip);
             else
                 wf[tn] = dequant_step<BITS>(wq[tn][0], s, zc[tn]);
-            if constexpr (BF) wf[tn] = __builtin_bit_cast(half8, half8_to_bf16x8(wf[tn]));  // bf16 bits from here on
+            if constexpr (BF && BITS != 16) wf[tn] = __builtin_bit_cast(half8, half8_to_bf16x8(wf[tn]));  // bf16 bits now
         }
     };
     auto multiply = [&](const frag_t (&wf)[TN], int s) {
@@ -944,9 +958,10 @@ static int run_gemm(GemmArgs& g, int tile_index, hipStream_t st) {
 
 template <bool I8, int BITS>
 static int dispatch_gemm(GemmArgs& g, hipStream_t st) {
-    // 8-bit weights of the int8 path take 2 KB of LDS per 32x64 tile: two workgroups per compute unit would leave
-    // room for two stages only, so these run one workgroup per compute unit with a deeper pipeline instead
-    constexpr bool WIDE = I8 && BITS == 8;
+    // 8-bit weights of the int8 path take 2 KB of LDS per 32x64 tile and unquantised 16-bit weights 4 KB: with the
+    // large tile two workgroups per compute unit would not fit, so it runs one per compute unit with a deeper
+    // pipeline (and is not chosen automatically)
+    constexpr bool WIDE = (I8 && BITS == 8) || BITS == 16;
     switch (pick_tile(g.M, g.N, g.K, WIDE)) {
         case 0: return run_gemm<I8, BITS, 1, 4, 4, 2, 1, WIDE ? 160 * 1024 : 80 * 1024, 4>(g, 0, st);
         case 1: return run_gemm<I8, BITS, 2, 2, 2, 2, 1, 80 * 1024, 4>(g, 1, st);
@@ -959,9 +974,10 @@ static int dispatch_gemm(GemmArgs& g, hipStream_t st) {
 // bfloat16 activations: the three plain tiles (the k-split variants fall back to their plain counterparts).
 template <int BITS>
 static int dispatch_gemm_bf16(GemmArgs& g, hipStream_t st) {
-    const int t = pick_tile(g.M, g.N, g.K);
+    constexpr bool WIDE = BITS == 16;
+    const int t = pick_tile(g.M, g.N, g.K, WIDE);
     switch (t >= 3 ? t - 2 : t) {
-        case 0: return run_gemm<false, BITS, 1, 4, 4, 2, 1, 80 * 1024, 4, true>(g, 0, st);
+        case 0: return run_gemm<false, BITS, 1, 4, 4, 2, 1, WIDE ? 160 * 1024 : 80 * 1024, 4, true>(g, 0, st);
         case 1: return run_gemm<false, BITS, 2, 2, 2, 2, 1, 80 * 1024, 4, true>(g, 1, st);
         default: return run_gemm<false, BITS, 2, 2, 1, 1, 1, 80 * 1024, 8, true>(g, 2, st);
     }
@@ -986,6 +1002,7 @@ int launch_gemm_w_only(const void* x, int M, int K, int ldx, const void* packed,
             case 3: return dispatch_gemm_bf16<3>(g, st);
             case 4: return dispatch_gemm_bf16<4>(g, st);
             case 8: return dispatch_gemm_bf16<8>(g, st);
+            case 16: return dispatch_gemm_bf16<16>(g, st);
         }
         return MQ_ERR_UNSUPPORTED_BITS;
     }
@@ -994,6 +1011,7 @@ int launch_gemm_w_only(const void* x, int M, int K, int ldx, const void* packed,
         case 3: return dispatch_gemm<false, 3>(g, st);
         case 4: return dispatch_gemm<false, 4>(g, st);
         case 8: return dispatch_gemm<false, 8>(g, st);
+        case 16: return dispatch_gemm<false, 16>(g, st);
     }
     return MQ_ERR_UNSUPPORTED_BITS;
 }

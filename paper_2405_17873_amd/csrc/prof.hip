@@ -80,8 +80,8 @@ double prof_bracket_overhead_us(hipStream_t st) {
 }
 
 int prof_gemm_slot(int family, int bits, int tile) {
-    const int b = bits == 2 ? 0 : bits == 3 ? 1 : bits == 4 ? 2 : 3;
-    return (family * 4 + b) * PROF_GEMM_TILES + tile;
+    const int b = bits == 2 ? 0 : bits == 3 ? 1 : bits == 4 ? 2 : bits == 8 ? 3 : 4;
+    return (family * PROF_GEMM_BITS + b) * PROF_GEMM_TILES + tile;
 }
 
 bool prof_enabled() { return g_on; }

@@ -246,6 +246,32 @@ __global__ void unpack_kernel_layout_kernel(const uint8_t* __restrict__ packed, 
     for (int e = 0; e < 32; ++e) codes[(size_t)n * K + c * 64 + kb * 32 + e] = (uint8_t)cd[e];
 }
 
+// 16-bit weights (the layers a bit-width configuration leaves unquantised): the same 32-channel x 64-k tiles, 4 KB each.
+// Lane L = kb * 32 + j owns the 32 values k' = 0..31 of channel j in k-half kb; they are stored as four 16-byte pieces,
+// piece s (values 8s .. 8s+7: the lane's MFMA operand of step s) at s * 1024 + L * 16.  One thread per piece.
+__global__ void pack16_kernel_layout_kernel(const uint16_t* __restrict__ w, int N, int K, int to_kernel,
+                                            uint16_t* __restrict__ out) {
+    const int KC = K / 64;
+    const int Np = (N + 31) / 32 * 32;
+    const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= (long)Np * KC * 8) return;
+    const int L = idx % 64;
+    const int s = (idx / 64) % 4;
+    const int c = (idx / 256) % KC;
+    const int g = idx / (256L * KC);
+    const int j = L % 32, kb = L / 32;
+    const int n = g * 32 + j;
+    const size_t tile = ((size_t)g * KC + c) * 2048 + (size_t)s * 512 + (size_t)L * 8;  // in 16-bit units
+    const size_t src = (size_t)n * K + c * 64 + kb * 32 + s * 8;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        if (to_kernel)
+            out[tile + e] = n < N ? w[src + e] : (uint16_t)0;
+        else if (n < N)
+            out[src + e] = w[tile + e];
+    }
+}
+
 // One wave per channel.
 __global__ __launch_bounds__(256) void code_colsum_kernel(const uint8_t* __restrict__ codes, int N, int K, int bits,
                                                           int codes_signed, int32_t* __restrict__ colsum) {
@@ -271,6 +297,20 @@ int launch_quantize_weights(const void* w, int N, int K, int bits, int symmetric
 
 int launch_pack(const uint8_t* codes, int N, int K, int bits, int layout, int codes_signed, void* packed,
                 int32_t* colsum, hipStream_t st) {
+    if (bits == 16) {  // 16-bit values, not codes: canonical is the matrix itself
+        if (layout == MQ_LAYOUT_CANONICAL) {
+            if (hipMemcpyAsync(packed, codes, (size_t)N * K * 2, hipMemcpyDeviceToDevice, st) != hipSuccess) {
+                set_hip_error((int)hipGetLastError());
+                return MQ_ERR_HIP;
+            }
+            return MQ_OK;
+        }
+        const long total = (long)((N + 31) / 32 * 32) * (K / 64) * 8;
+        hipLaunchKernelGGL(pack16_kernel_layout_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
+                           (const uint16_t*)codes, N, K, 1, (uint16_t*)packed);
+        MQ_HIP_CHECK_LAUNCH();
+        return MQ_OK;
+    }
     if (layout == MQ_LAYOUT_CANONICAL) {
         const long total = (long)N * ((long)K * bits / 8);
         hipLaunchKernelGGL(pack_canonical_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, codes, N, K,
@@ -290,6 +330,20 @@ int launch_pack(const uint8_t* codes, int N, int K, int bits, int layout, int co
 }
 
 int launch_unpack(const void* packed, int N, int K, int bits, int layout, uint8_t* codes, hipStream_t st) {
+    if (bits == 16) {
+        if (layout == MQ_LAYOUT_CANONICAL) {
+            if (hipMemcpyAsync(codes, packed, (size_t)N * K * 2, hipMemcpyDeviceToDevice, st) != hipSuccess) {
+                set_hip_error((int)hipGetLastError());
+                return MQ_ERR_HIP;
+            }
+            return MQ_OK;
+        }
+        const long total = (long)((N + 31) / 32 * 32) * (K / 64) * 8;
+        hipLaunchKernelGGL(pack16_kernel_layout_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
+                           (const uint16_t*)packed, N, K, 0, (uint16_t*)codes);
+        MQ_HIP_CHECK_LAUNCH();
+        return MQ_OK;
+    }
     if (layout == MQ_LAYOUT_CANONICAL) {
         const long total = (long)N * K;
         hipLaunchKernelGGL(unpack_canonical_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,

@@ -36,6 +36,8 @@ def test_every_declared_symbol_is_exported(lib):
 def test_size_queries(lib):
     import paper_2405_17873_amd as mq
     assert mq.packed_bytes(320, 320, 4, mq.LAYOUT_CANONICAL) == 320 * 160
+    assert mq.packed_bytes(40, 128, 16, mq.LAYOUT_KERNEL) == 64 * 128 * 2  # unquantised 16-bit weights, 32-row tiles
+    assert mq.packed_bytes(40, 128, 16, mq.LAYOUT_CANONICAL) == 40 * 128 * 2
     assert mq.packed_bytes(320, 320, 3, mq.LAYOUT_CANONICAL) == 320 * 120
     assert mq.packed_bytes(320, 320, 2, mq.LAYOUT_KERNEL) == 320 * 80
     assert mq.packed_bytes(33, 64, 8, mq.LAYOUT_KERNEL) == 64 * 64  # padded to 64 channels
@@ -63,6 +65,8 @@ def test_error_codes_without_a_gpu(lib):
     assert lib.mq_pack_weights(p, 4, 96, 4, 1, 0, p, null, st) == -2
     assert lib.mq_pack_weights(p, 4, 64, 4, 9, 0, p, null, st) == -6
     assert lib.mq_pack_weights(p, 4, 64, 4, 1, 1, p, null, st) == -1  # signed codes only at 8 bit
+    assert lib.mq_pack_weights(p, 4, 64, 16, 1, 0, p, p, st) == -1  # no code sums of unquantised weights
+    assert lib.mq_quantize_weights(p, 4, 64, 16, 0, 0, p, p, p, st) == -3
     assert lib.mq_unpack_weights(p, 4, 64, 6, 1, p, st) == -3
     # w_only
     args = lambda **o: [o.get("x", p), o.get("M", 8), o.get("K", 64), o.get("ldx", 64), p, o.get("N", 32),

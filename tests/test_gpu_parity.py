@@ -218,6 +218,50 @@ def test_w_only_transformer_block_shapes_sampled_rows(mq, orc, M, K, N):
             ref.view(np.float16).astype(np.float64)).max() + 1
 
 
+# ----------------------------------------------------------------------------------------------- layers kept at 16 bits
+
+@pytest.mark.parametrize("tile", (-1, 0, 1, 2, 3, 4))
+def test_unquantised_16bit_layer(mq, orc, tile):
+    """bits = 16: the weights go through the same tile order and GEMM skeleton unquantised (fp16 and bf16)."""
+    mq.tune_force_tile(tile)
+    try:
+        for (M, K, N) in ((256, 320, 320), (77, 128, 40), (300, 640, 264), (513, 2048, 640)):
+            if tile == 0 and M * N > 400000:
+                continue
+            x = si.activations_f16(51, f"w16/x{M}x{K}", M, K)
+            w = si.weights_f16(51, f"w16/w{N}x{K}", N, K)
+            b = si.bias_f16(51, f"w16/b{N}", N)
+            wd = dev(w)
+            pw = mq.keep_weights_16bit(wd)
+            assert pw.packed.numel() == (N + 31) // 32 * 32 * K * 2
+            assert torch.equal(mq.unpack_weights(pw.packed, N, K, 16, mq.LAYOUT_KERNEL), wd)
+            for bias in (b, None):
+                y = mq.qlinear_w_only(dev(x), pw, None if bias is None else dev(bias))
+                assert_close16(host(y), orc.linear_fp(x, w, bias), f"w16 tile{tile} {M}x{K}x{N}")
+        # bf16
+        M, K, N = 130, 192, 72
+        xb = torch.from_numpy(si.normal(52, "w16/xb", (M, K)).astype(np.float32)).to(torch.bfloat16)
+        wb = torch.from_numpy(si.normal(52, "w16/wb", (N, K), 0.02).astype(np.float32)).to(torch.bfloat16)
+        pw = mq.keep_weights_16bit(wb.cuda())
+        y = mq.qlinear_w_only(xb.cuda(), pw)
+        assert y.dtype == torch.bfloat16
+        ref = orc.linear_fp(xb.view(torch.int16).numpy().view(np.uint16), wb.view(torch.int16).numpy().view(np.uint16),
+                            dtype=orc.BF16)
+        got = host(y.view(torch.int16)).view(np.uint16)
+        a = orc.f16_to_f64(got, orc.BF16)
+        r = orc.f16_to_f64(ref, orc.BF16)
+        assert np.linalg.norm(a - r) <= FRO_TOL * np.linalg.norm(r) and np.abs(a - r).max() <= ELT_TOL * np.abs(r).max()
+    finally:
+        mq.tune_force_tile(-1)
+
+
+def test_16bit_canonical_pack_is_the_matrix(mq):
+    w = dev(si.weights_f16(53, "w16/c", 40, 128))
+    p, cs = mq.pack_weights(w, 16, mq.LAYOUT_CANONICAL)
+    assert cs is None and torch.equal(p.view(torch.float16).view(40, 128), w)
+    assert torch.equal(mq.unpack_weights(p, 40, 128, 16, mq.LAYOUT_CANONICAL), w)
+
+
 # ----------------------------------------------------------------------------------------------- reduction split over workgroups
 
 SPLIT_SHAPES = [(1, 5120, 1280), (16, 1280, 320), (77, 2048, 1280), (308, 2048, 640), (130, 640, 96), (33, 256, 40)]

@@ -318,6 +318,30 @@ def test_w_only_transposed_operand_would_fail(orc):
     assert np.allclose(y, x.astype(np.float64) @ what.T, rtol=2e-3, atol=1e-3)
 
 
+def test_fp_linear_exact_rationals_and_integer_case(orc):
+    """The unquantised 16-bit linear (layers kept at FP16; also the BOS row): brute force in exact rationals on a tiny
+    case (N != K, so a transposed weight index cannot pass), an integer case that is exact, and a float64 matmul."""
+    rng = np.random.default_rng(6)
+    M, K, N = 3, 8, 5
+    x = rng.normal(0, 1, (M, K)).astype(np.float16)
+    w = rng.normal(0, 0.5, (N, K)).astype(np.float16)
+    b = rng.normal(0, 0.1, N).astype(np.float16)
+    y = orc.linear_fp(x, w, b).view(np.float16)
+    for m in range(M):
+        for n in range(N):
+            acc = sum((Fraction(float(x[m, k])) * Fraction(float(w[n, k])) for k in range(K)), Fraction(float(b[n])))
+            assert y[m, n] == np.float16(float(acc)), (m, n)
+    xi = rng.integers(-8, 9, (16, 64)).astype(np.float16)
+    wi = rng.integers(-15, 16, (24, 64)).astype(np.float16)
+    assert np.array_equal(orc.linear_fp(xi, wi).view(np.float16), (xi.astype(np.int64) @ wi.astype(np.int64).T).astype(np.float16))
+    x = rng.normal(0, 1, (33, 128)).astype(np.float16)
+    w = rng.normal(0, 0.02, (48, 128)).astype(np.float16)
+    y = orc.linear_fp(x, w).view(np.float16)
+    ref16 = (x.astype(np.float64) @ w.astype(np.float64).T).astype(np.float16)
+    ulp = np.abs(y.astype(np.float64) - ref16.astype(np.float64)) / np.spacing(np.abs(ref16)).astype(np.float64)
+    assert ulp.max() <= 1.0 and (ulp > 0).mean() < 0.01
+
+
 def test_w_only_bf16(orc):
     import torch
     rng = np.random.default_rng(5)
