@@ -217,3 +217,52 @@ def bos_aware_kv_proj(ctx, wcodes, w_scale, w_zp, w_signed=False, w_f16=None, bo
                                        int(act is None), C.byref(s), C.byref(z), _p(_u16(bias)), _p(y),
                                        int(naive_all_rows)), "bos_aware_kv_proj")
     return y, (np.float32(s.value), int(z.value))
+
+
+def gelu32(g):
+    """The fp32 GELU of the fused feed-forward epilogue, element by element."""
+    g = np.ascontiguousarray(g, np.float32)
+    out = np.empty_like(g)
+    _check(lib().orc_gelu32(_p(g), C.c_long(g.size), _p(out)), "gelu32")
+    return out
+
+
+def linear_a8_geglu(x, wcodes, w_scale, w_zp, out_act, w_signed=False, act=None, bias=None, rows=None, want_h16=True):
+    """GEGLU projection, 8-bit activations in and out.  wcodes [2H,K]; out_act = (scale, zp) of the gated product.
+    Returns (codes uint8 [R,H], h16 uint16 [R,H] or None, (act_scale, act_zp))."""
+    x = _u16(x)
+    bias = _u16(bias)
+    wcodes = np.ascontiguousarray(wcodes, np.uint8)
+    M, K = x.shape
+    H = wcodes.shape[0] // 2
+    assert wcodes.shape == (2 * H, K)
+    rows, nr = _rows(rows)
+    R = nr if rows is not None else M
+    codes = np.empty((R, H), np.uint8)
+    h16 = np.empty((R, H), np.uint16) if want_h16 else None
+    s = C.c_float(0.0 if act is None else act[0])
+    z = C.c_int32(0 if act is None else act[1])
+    _check(lib().orc_linear_a8_geglu(_p(x), C.c_long(M), K, C.c_long(K), _p(wcodes), H, int(w_signed),
+                                     _p(np.ascontiguousarray(w_scale, np.float32)),
+                                     _p(np.ascontiguousarray(w_zp, np.int32)), int(act is None), C.byref(s),
+                                     C.byref(z), _p(bias), C.c_float(out_act[0]), C.c_int32(out_act[1]), _p(codes),
+                                     _p(h16), _p(rows), C.c_long(nr)), "linear_a8_geglu")
+    return codes, h16, (np.float32(s.value), int(z.value))
+
+
+def linear_a8_codes(qx, act, wcodes, w_scale, w_zp, w_signed=False, bias=None, want_acc=True):
+    """A8 linear on activations that arrive as unsigned 8-bit codes with act = (scale, zp).
+    Returns (y uint16 [M,N], acc int32 or None)."""
+    qx = np.ascontiguousarray(qx, np.uint8)
+    bias = _u16(bias)
+    wcodes = np.ascontiguousarray(wcodes, np.uint8)
+    M, K = qx.shape
+    N = wcodes.shape[0]
+    assert wcodes.shape[1] == K
+    y = np.empty((M, N), np.uint16)
+    acc = np.empty((M, N), np.int32) if want_acc else None
+    _check(lib().orc_linear_a8_codes(_p(qx), C.c_long(M), K, C.c_float(act[0]), C.c_int32(act[1]), _p(wcodes), N,
+                                     int(w_signed), _p(np.ascontiguousarray(w_scale, np.float32)),
+                                     _p(np.ascontiguousarray(w_zp, np.int32)), _p(bias), _p(y), C.c_long(N), _p(acc)),
+           "linear_a8_codes")
+    return y, acc

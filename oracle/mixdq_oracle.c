@@ -440,3 +440,137 @@ int orc_bos_aware_kv_proj(const uint16_t* ctx, int B, int T, int K, const uint8_
     }
     return ORC_OK;
 }
+
+/* ------------------------------------------------------------------------- */
+/* Feed-forward pair with the activation kept in 8 bits between the two      */
+/* linears (an extension; the paper's Sec. 4.3 names the separate FP16->INT8 */
+/* conversion layers as the overhead of the W8A8 path, this removes the one  */
+/* between the GEGLU projection and the output linear of a transformer       */
+/* block's feed-forward).                                                     */
+/*                                                                           */
+/*   lin[m,n] = fma((float)ACC[m,n], s_x * s_w[n], bias[n])     n in [0, 2H)  */
+/*   h[m,j]   = lin[m,j] * gelu(lin[m,H+j])                     j in [0, H)   */
+/*   code     = clamp(rne(h * (1/s_o)) + z_o, 0, 255)                         */
+/*                                                                           */
+/* (first half of the projection = value, second half = gate).  A code is an */
+/* integer decided by floating point, so every operation is spelt out: all   */
+/* are single IEEE fp32 operations, and the error function is the five-term  */
+/* rational approximation of Abramowitz & Stegun 7.1.26 (|error| < 1.5e-7)   */
+/* over an exponential computed by range reduction and a degree-6 polynomial.*/
+/* ------------------------------------------------------------------------- */
+
+/* exp(y) for y <= 0 in fp32: y = n ln2 + r, |r| <= ln2/2; e^r by Horner; scaled by 2^n. */
+static float exp32_nonpos(float y) {
+    if (y < -87.0f) return 0.0f;
+    float n = rintf(y * 1.44269504f);
+    float r = fmaf(n, -0.693145752f, y);
+    r = fmaf(n, -1.42860677e-6f, r);
+    float p = 1.0f / 720.0f;
+    p = fmaf(p, r, 1.0f / 120.0f);
+    p = fmaf(p, r, 1.0f / 24.0f);
+    p = fmaf(p, r, 1.0f / 6.0f);
+    p = fmaf(p, r, 0.5f);
+    p = fmaf(p, r, 1.0f);
+    p = fmaf(p, r, 1.0f);
+    return ldexpf(p, (int)n);
+}
+
+static float gelu32(float g) {
+    float x = fabsf(g) * 0.70710678f;
+    float t = 1.0f / fmaf(0.3275911f, x, 1.0f);
+    float p = 1.061405429f;
+    p = fmaf(p, t, -1.453152027f);
+    p = fmaf(p, t, 1.421413741f);
+    p = fmaf(p, t, -0.284496736f);
+    p = fmaf(p, t, 0.254829592f);
+    p = p * t;
+    float e = exp32_nonpos(-(x * x));
+    float erf_abs = fmaf(-p, e, 1.0f);
+    float erf_g = copysignf(erf_abs, g);
+    return (0.5f * g) * (1.0f + erf_g);
+}
+
+int orc_gelu32(const float* g, long n, float* out) {
+    if (!g || !out || n <= 0) return ORC_BAD_ARG;
+    for (long i = 0; i < n; ++i) out[i] = gelu32(g[i]);
+    return ORC_OK;
+}
+
+/* GEGLU projection with 8-bit activations in and out.  wcodes [2H,K]; codes_out [R,H] unsigned codes of the
+ * gated product under the given static output parameters; h16_out nullable [R,H]: the same product rounded to fp16. */
+int orc_linear_a8_geglu(const uint16_t* x, long M, int K, long ldx, const uint8_t* wcodes, int H, int w_signed,
+                        const float* w_scale, const int32_t* w_zp, int dynamic, float* act_scale, int32_t* act_zp,
+                        const uint16_t* bias, float out_scale, int32_t out_zp, uint8_t* codes_out, uint16_t* h16_out,
+                        const int64_t* rows, long nrows) {
+    if (!x || !wcodes || !w_scale || !w_zp || !act_scale || !act_zp || !codes_out || M <= 0 || K <= 0 || H <= 0 ||
+        ldx < K || !(out_scale > 0.0f) || out_zp < 0 || out_zp > 255)
+        return ORC_BAD_ARG;
+    long R = rows ? nrows : M;
+    if (R <= 0) return ORC_BAD_ARG;
+    if (dynamic) {
+        int rc = orc_act_params(x, M, K, ldx, ORC_F16, act_scale, act_zp);
+        if (rc) return rc;
+    }
+    float sx = *act_scale;
+    int32_t zx = *act_zp;
+    if (!(sx > 0.0f) || zx < 0 || zx > 255) return ORC_BAD_ARG;
+    float inv = 1.0f / sx;
+    float inv_o = 1.0f / out_scale;
+    float zf_o = (float)out_zp;
+    int N = 2 * H;
+    int overflow = 0;
+#pragma omp parallel for schedule(static) reduction(| : overflow)
+    for (long r = 0; r < R; ++r) {
+        long m = rows ? rows[r] : r;
+        int* xd = (int*)malloc((size_t)K * sizeof(int));
+        float* lin = (float*)malloc((size_t)N * sizeof(float));
+        for (int k = 0; k < K; ++k) xd[k] = asym_code((float)half_to_double(x[m * ldx + k]), inv, zx, 255) - zx;
+        for (int n = 0; n < N; ++n) {
+            int64_t acc = 0;
+            for (int k = 0; k < K; ++k) {
+                int q = w_signed ? (int)(int8_t)wcodes[(size_t)n * K + k] : (int)wcodes[(size_t)n * K + k];
+                acc += (int64_t)xd[k] * (q - w_zp[n]);
+            }
+            if (acc > INT32_MAX || acc < INT32_MIN) overflow |= 1;
+            float mul = sx * w_scale[n];
+            float add = bias ? (float)half_to_double(bias[n]) : 0.0f;
+            lin[n] = fmaf((float)(int32_t)acc, mul, add);
+        }
+        for (int j = 0; j < H; ++j) {
+            float h = lin[j] * gelu32(lin[H + j]);
+            float t = rintf(h * inv_o) + zf_o;
+            t = t < 0.0f ? 0.0f : (t > 255.0f ? 255.0f : t);
+            codes_out[r * (long)H + j] = (uint8_t)(int)t;
+            if (h16_out) h16_out[r * (long)H + j] = double_to_half((double)h);
+        }
+        free(xd);
+        free(lin);
+    }
+    return overflow ? ORC_OVERFLOW : ORC_OK;
+}
+
+/* A8 linear whose activations arrive as unsigned 8-bit codes with their parameters (the consumer of the above). */
+int orc_linear_a8_codes(const uint8_t* qx, long M, int K, float act_scale, int32_t act_zp, const uint8_t* wcodes, int N,
+                        int w_signed, const float* w_scale, const int32_t* w_zp, const uint16_t* bias, uint16_t* y,
+                        long ldy, int32_t* acc_out) {
+    if (!qx || !wcodes || !w_scale || !w_zp || !y || M <= 0 || K <= 0 || N <= 0 || ldy < N || !(act_scale > 0.0f) ||
+        act_zp < 0 || act_zp > 255)
+        return ORC_BAD_ARG;
+    int overflow = 0;
+#pragma omp parallel for schedule(static) reduction(| : overflow)
+    for (long m = 0; m < M; ++m) {
+        for (int n = 0; n < N; ++n) {
+            int64_t acc = 0;
+            for (int k = 0; k < K; ++k) {
+                int q = w_signed ? (int)(int8_t)wcodes[(size_t)n * K + k] : (int)wcodes[(size_t)n * K + k];
+                acc += (int64_t)((int)qx[m * (long)K + k] - act_zp) * (q - w_zp[n]);
+            }
+            if (acc > INT32_MAX || acc < INT32_MIN) overflow |= 1;
+            if (acc_out) acc_out[m * (long)N + n] = (int32_t)acc;
+            double v = (double)acc * ((double)act_scale * (double)w_scale[n]);
+            if (bias) v += half_to_double(bias[n]);
+            y[m * ldy + n] = double_to_half(v);
+        }
+    }
+    return overflow ? ORC_OVERFLOW : ORC_OK;
+}

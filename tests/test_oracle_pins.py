@@ -492,3 +492,65 @@ def test_generators_are_deterministic_and_have_the_stated_moments():
     ctx = si.bos_context_f16(0, "t/ctx", 8, 77, 2048).astype(np.float64)
     assert np.array_equal(ctx[0, 0], ctx[7, 0])
     assert np.abs(ctx[:, 0]).max() > 5 * np.abs(ctx[:, 1:]).max() / 2
+
+
+# ----------------------------------------------------------------------------------------------- fused feed-forward pair
+
+def test_gelu32_against_the_error_function(orc):
+    import math
+    g = np.concatenate([np.linspace(-9, 9, 40001), [0.0, -0.0, 1e-8, -1e-8, 50.0, -50.0]]).astype(np.float32)
+    out = orc.gelu32(g).astype(np.float64)
+    ref = np.array([0.5 * float(v) * (1.0 + math.erf(float(v) / math.sqrt(2.0))) for v in g])
+    assert np.abs(out - ref).max() < 1e-6          # the rational approximation is good to 1.5e-7 in erf
+    assert (out[g == 0] == 0).all() and orc.gelu32(np.float32([50.0]))[0] == 50.0
+    assert orc.gelu32(np.float32([-50.0]))[0] == 0.0
+    pos = np.sort(g[g > 0.1])
+    assert (np.diff(orc.gelu32(pos)) >= 0).all()   # increasing right of its minimum
+
+
+def test_a8_from_codes_is_the_a8_linear_after_its_quantiser(orc):
+    x, w, b, c, s, z = _random_quantised_layer(orc, 71, 19, 128, 24, 4)
+    act = (np.float32(0.031), 121)
+    qx = orc.act_quantize(x, *act)
+    y0, acc0, _ = orc.linear_a8(x, c, s, z, act=act, bias=b)
+    y1, acc1 = orc.linear_a8_codes(qx, act, c, s, z, bias=b)
+    assert np.array_equal(acc0, acc1) and np.array_equal(y0, y1)
+
+
+def test_geglu_order_bias_and_output_quantiser_by_hand(orc):
+    """Zero weights leave lin = bias: the product is value * gelu(gate) with the FIRST half of the projection as
+    value, and its code follows the affine quantiser with the given output parameters."""
+    import math
+    H, K = 4, 64
+    codes = np.zeros((2 * H, K), np.uint8)
+    s, z = np.ones(2 * H, np.float32), np.zeros(2 * H, np.int32)
+    bias = np.array([1.0, -2.0, 0.5, 3.0, 0.0, 1.0, -1.0, 2.0], np.float16)   # values | gates
+    x = np.ones((2, K), np.float16)
+    out_act = (np.float32(0.05), 40)
+    q, h16, _ = orc.linear_a8_geglu(x, codes, s, z, out_act, act=(np.float32(1.0), 0), bias=bias)
+    gelu = lambda g: 0.5 * g * (1.0 + math.erf(g / math.sqrt(2.0)))
+    want = [1.0 * gelu(0.0), -2.0 * gelu(1.0), 0.5 * gelu(-1.0), 3.0 * gelu(2.0)]
+    assert np.allclose(h16.view(np.float16)[0].astype(np.float64), want, atol=2e-3)
+    assert q[0].tolist() == [min(255, max(0, round(v / 0.05) + 40)) for v in want] and np.array_equal(q[0], q[1])
+
+
+@pytest.mark.parametrize("bits,symmetric", [(4, False), (8, True)])
+def test_geglu_requant_against_float64_rederivation(orc, bits, symmetric):
+    import math
+    M, K, H = 21, 128, 40
+    x, w, b, c, s, z = _random_quantised_layer(orc, 72 + bits, M, K, 2 * H, bits, symmetric)
+    out_act = (np.float32(0.004), 30)
+    q, h16, act = orc.linear_a8_geglu(x, c, s, z, out_act, w_signed=symmetric, bias=b)
+    _, acc, act2 = orc.linear_a8(x, c, s, z, w_signed=symmetric, bias=b)
+    assert act == act2
+    lin = acc.astype(np.float64) * (np.float64(act[0]) * s.astype(np.float64))[None, :] + b.astype(np.float64)[None, :]
+    erf = np.vectorize(math.erf)
+    h = lin[:, :H] * 0.5 * lin[:, H:] * (1.0 + erf(lin[:, H:] / math.sqrt(2.0)))
+    want = np.clip(np.rint(h / np.float64(out_act[0])) + out_act[1], 0, 255)
+    d = q.astype(np.int64) - want.astype(np.int64)
+    assert np.abs(d).max() <= 1 and (d != 0).mean() < 0.02     # fp32 versus fp64 only moves borderline roundings
+    assert len(np.unique(q)) > 20                               # the codes are spread, not saturated
+    assert np.allclose(h16.view(np.float16).astype(np.float64), h, rtol=2e-3, atol=2e-4)
+    rows = [0, 5, 20]
+    q2, _, _ = orc.linear_a8_geglu(x, c, s, z, out_act, w_signed=symmetric, bias=b, rows=rows, act=act)
+    assert np.array_equal(q2, q[rows])
