@@ -176,6 +176,46 @@ int mq_qlinear_w4a8(const void* x, int M, int K, int ldx, const void* packed, in
                     const int32_t* act_zp, const void* bias, void* y, int ldy, int32_t* acc_debug,
                     float* act_scale_out, int32_t* act_zp_out, void* ws, size_t ws_bytes, void* stream);
 
+/* ------------------------------------------------------------------------------------------------
+ * Feed-forward pair with the activation kept in 8 bits between its two linears (an extension: paper Sec. 4.3
+ * names the separate FP16->INT8 conversion layers as the overhead of the W8A8 path; this removes the one between
+ * the gated projection and the output linear of a transformer block's feed-forward, and the 8C-wide fp16
+ * tensor between them never reaches memory).
+ *
+ * The int8 activation layout ("A8 layout") that links the two calls: row stride mq_a8_row_bytes(K) = K rounded
+ * up to 128 (or more, a multiple of 128), byte value a' = code - 128 (two's complement), inside every group of 8
+ * consecutive k the bytes are stored in the order 0,4,1,5,2,6,3,7, and the bytes from K to the stride are zero.
+ * ---------------------------------------------------------------------------------------------- */
+size_t mq_a8_row_bytes(int K);
+
+/* Gated projection (GEGLU) with 8-bit input and output.  The weight matrix has 2H rows: rows [0,H) produce the
+ * value, rows [H,2H) the gate.
+ *     lin[m,n]  = fma( (float)ACC[m,n], s_x * s_w[n], bias[n] )            ACC as in mq_qlinear_w8a8
+ *     h[m,j]    = lin[m,j] * gelu( lin[m,H+j] )                            j in [0,H)
+ *     code[m,j] = clamp( rne(h / s_o) + z_o, 0, 255 )                      h / s_o as a multiply by the fp32 1/s_o
+ * gelu(g) = 0.5 g (1 + erf(g / sqrt 2)); every step is one IEEE fp32 operation and erf is the five-term rational
+ * approximation of Abramowitz & Stegun 7.1.26 over an exponential by range reduction and a degree-6 polynomial, so
+ * that the codes are reproducible bit for bit.
+ *   x [M,K] fp16 (as in mq_qlinear_w8a8, dynamic or static activation parameters), packed: w_bits = 4 or 8,
+ *   MQ_LAYOUT_KERNEL, 2H rows; w_scale, w_zp, w_colsum, bias [2H].  H % 32 == 0.
+ *   out_scale, out_zp: device pointers to the static parameters (s_o, z_o) of the gated product.
+ *   a8_out  [M, mq_a8_row_bytes(H)] int8 out, A8 layout, 16-byte aligned.
+ *   h16_out nullable [M,H] fp16 out (row stride ldh, ldh % 8 == 0): the gated product itself.
+ *   ws: mq_qlinear_a8_workspace_bytes(M, K). */
+int mq_qlinear_a8_geglu(const void* x, int M, int K, int ldx, const void* packed, int H, int w_bits, int layout,
+                        int w_signed, const float* w_scale, const int32_t* w_zp, const int32_t* w_colsum,
+                        const float* act_scale, const int32_t* act_zp, const void* bias, const float* out_scale,
+                        const int32_t* out_zp, int8_t* a8_out, void* h16_out, int ldh, float* act_scale_out,
+                        int32_t* act_zp_out, void* ws, size_t ws_bytes, void* stream);
+
+/* W8A8 / W4A8 linear on activations that arrive as codes in the A8 layout (row stride lda bytes) together with
+ * their parameters (device pointers act_scale, act_zp): ACC and Y as in mq_qlinear_w8a8.  The row sums of the
+ * codes, which the zero-point correction needs, are taken inside the GEMM; no workspace. */
+int mq_qlinear_a8_codes(const int8_t* a8, int M, int K, int lda, const float* act_scale, const int32_t* act_zp,
+                        const void* packed, int N, int w_bits, int layout, int w_signed, const float* w_scale,
+                        const int32_t* w_zp, const int32_t* w_colsum, const void* bias, void* y, int ldy,
+                        int32_t* acc_debug, void* stream);
+
 size_t mq_bos_aware_kv_proj_workspace_bytes(int B, int T, int K);
 
 /* BOS-aware cross-attention K/V projection (paper Sec. 3.1).  ctx is the text embedding [B,T,K] fp16,

@@ -23,7 +23,8 @@ _ERRORS = {
 EXPORTS = ("mq_version", "mq_last_hip_error", "mq_tune_force_tile", "mq_tune_force_splits", "mq_prof_enable", "mq_prof_num_slots", "mq_prof_read",
            "mq_prof_reset", "mq_prof_phase_buffer", "mq_prof_filter", "mq_prof_bracket_overhead_us", "mq_prof_copy", "mq_quantize_weights", "mq_packed_bytes", "mq_pack_weights",
            "mq_unpack_weights", "mq_qlinear_w_only", "mq_qlinear_a8_workspace_bytes", "mq_qlinear_w8a8",
-           "mq_qlinear_w4a8", "mq_bos_aware_kv_proj_workspace_bytes", "mq_bos_aware_kv_proj")
+           "mq_qlinear_w4a8", "mq_a8_row_bytes", "mq_qlinear_a8_geglu", "mq_qlinear_a8_codes",
+           "mq_bos_aware_kv_proj_workspace_bytes", "mq_bos_aware_kv_proj")
 
 
 class MixdqError(RuntimeError):
@@ -46,7 +47,7 @@ def load():
         if not os.path.exists(_LIB_PATH):
             raise RuntimeError(f"{_LIB_PATH} is missing: run `python -c 'import __graft_entry__ as g; g.build()'`")
         _lib = C.CDLL(_LIB_PATH)
-        for name in ("mq_packed_bytes", "mq_qlinear_a8_workspace_bytes", "mq_bos_aware_kv_proj_workspace_bytes"):
+        for name in ("mq_a8_row_bytes", "mq_packed_bytes", "mq_qlinear_a8_workspace_bytes", "mq_bos_aware_kv_proj_workspace_bytes"):
             getattr(_lib, name).restype = C.c_size_t
         _lib.mq_prof_bracket_overhead_us.restype = C.c_double
     return _lib
@@ -242,6 +243,61 @@ def qlinear_w8a8(x, w: PackedWeight, act=None, bias=None, out=None, ws=None, wan
 def qlinear_w4a8(x, w: PackedWeight, act=None, bias=None, out=None, ws=None, want_acc=False, want_act=False):
     assert w.bits == 4 and not w.signed
     return _qlinear_a8("mq_qlinear_w4a8", x, w, act, bias, out, ws, want_acc, want_act)
+
+
+def a8_row_bytes(K: int) -> int:
+    return int(load().mq_a8_row_bytes(K))
+
+
+def qlinear_a8_geglu(x, w: PackedWeight, out_act, act=None, bias=None, ws=None, want_h16=False, want_act=False):
+    """Gated projection with 8-bit output.  w has 2H rows; out_act = (scale, zp) one-element device tensors.
+    Returns (a8 int8 [M, a8_row_bytes(H)], h16 fp16 [M,H] or None, (act_scale, act_zp) or None)."""
+    assert x.is_cuda and x.dim() == 2 and x.stride(1) == 1 and x.dtype == torch.float16
+    M, K = x.shape
+    H = w.N // 2
+    a8 = torch.empty((M, a8_row_bytes(H)), dtype=torch.int8, device=x.device)
+    h16 = torch.empty((M, H), dtype=torch.float16, device=x.device) if want_h16 else None
+    ws = _workspace(qlinear_a8_workspace_bytes(M, K), x.device, ws)
+    a_s, a_z = (None, None) if act is None else act
+    so = torch.empty(1, dtype=torch.float32, device=x.device) if want_act else None
+    zo = torch.empty(1, dtype=torch.int32, device=x.device) if want_act else None
+    _check(load().mq_qlinear_a8_geglu(_ptr(x), M, K, x.stride(0), _ptr(w.packed), H, w.bits, w.layout, int(w.signed),
+                                      _ptr(w.scale), _ptr(w.zp), _ptr(w.colsum), _ptr(a_s), _ptr(a_z), _ptr(bias),
+                                      _ptr(out_act[0]), _ptr(out_act[1]), _ptr(a8), _ptr(h16), H, _ptr(so), _ptr(zo),
+                                      _ptr(ws), C.c_size_t(ws.numel()), _stream()), "mq_qlinear_a8_geglu")
+    return a8, h16, ((so, zo) if want_act else None)
+
+
+def qlinear_a8_codes(a8, K: int, act, w: PackedWeight, bias=None, out=None, want_acc=False):
+    """A8 linear on activations in the A8 layout (a8 int8 [M, stride]); act = (scale, zp) one-element device tensors."""
+    assert a8.is_cuda and a8.dim() == 2 and a8.stride(1) == 1 and a8.dtype == torch.int8 and K == w.K
+    M = a8.shape[0]
+    y = out if out is not None else torch.empty((M, w.N), dtype=torch.float16, device=a8.device)
+    acc = torch.empty((M, w.N), dtype=torch.int32, device=a8.device) if want_acc else None
+    _check(load().mq_qlinear_a8_codes(_ptr(a8), M, K, a8.stride(0), _ptr(act[0]), _ptr(act[1]), _ptr(w.packed), w.N,
+                                      w.bits, w.layout, int(w.signed), _ptr(w.scale), _ptr(w.zp), _ptr(w.colsum),
+                                      _ptr(bias), _ptr(y), y.stride(0), _ptr(acc), _stream()), "mq_qlinear_a8_codes")
+    return y, acc
+
+
+def plan_qlinear_a8_geglu(x, w: PackedWeight, out_act, bias, a8_out, ws, act=None):
+    M, K = x.shape
+    H = w.N // 2
+    a_s, a_z = (None, None) if act is None else act
+    null = C.c_void_p(0)
+    args = (_ptr(x), M, K, x.stride(0), _ptr(w.packed), H, w.bits, w.layout, int(w.signed), _ptr(w.scale), _ptr(w.zp),
+            _ptr(w.colsum), _ptr(a_s), _ptr(a_z), _ptr(bias), _ptr(out_act[0]), _ptr(out_act[1]), _ptr(a8_out), null, H,
+            null, null, _ptr(ws), C.c_size_t(ws.numel()), _stream())
+    return _planned(load().mq_qlinear_a8_geglu, "mq_qlinear_a8_geglu", args, (x, w, out_act, bias, a8_out, ws, act))
+
+
+def plan_qlinear_a8_codes(a8, K, act, w: PackedWeight, bias, out):
+    M = a8.shape[0]
+    null = C.c_void_p(0)
+    args = (_ptr(a8), M, K, a8.stride(0), _ptr(act[0]), _ptr(act[1]), _ptr(w.packed), w.N, w.bits, w.layout,
+            int(w.signed), _ptr(w.scale), _ptr(w.zp), _ptr(w.colsum), _ptr(bias), _ptr(out), out.stride(0), null,
+            _stream())
+    return _planned(load().mq_qlinear_a8_codes, "mq_qlinear_a8_codes", args, (a8, act, w, bias, out))
 
 
 def bos_aware_kv_proj_workspace_bytes(B: int, T: int, K: int) -> int:

@@ -153,6 +153,54 @@ int mq_qlinear_w_only(const void* x, int M, int K, int ldx, const void* packed, 
     return launch_gemm_w_only(x, M, K, ldx, packed, N, bits, w_scale, w_zp, bias, y, ldy, dtype, (hipStream_t)stream);
 }
 
+size_t mq_a8_row_bytes(int K) { return K > 0 ? ((size_t)K + 127) / 128 * 128 : 0; }
+
+int mq_qlinear_a8_geglu(const void* x, int M, int K, int ldx, const void* packed, int H, int w_bits, int layout,
+                        int w_signed, const float* w_scale, const int32_t* w_zp, const int32_t* w_colsum,
+                        const float* act_scale, const int32_t* act_zp, const void* bias, const float* out_scale,
+                        const int32_t* out_zp, int8_t* a8_out, void* h16_out, int ldh, float* act_scale_out,
+                        int32_t* act_zp_out, void* ws, size_t ws_bytes, void* stream) {
+    if (w_bits != 4 && w_bits != 8) return MQ_ERR_UNSUPPORTED_BITS;
+    if (H <= 0 || H % 32 != 0 || H > (1 << 29)) return MQ_ERR_BAD_SHAPE;
+    // x, weights of 2H rows; the fp16 product (if asked for) stands in for y in the common checks
+    int rc = check_linear_common(x, M, K, ldx, packed, 2 * H, layout, w_scale, w_zp, bias, a8_out, 2 * H);
+    if (rc) return rc;
+    if (!w_colsum || !ws || !out_scale || !out_zp) return MQ_ERR_BAD_ARG;
+    if ((act_scale == nullptr) != (act_zp == nullptr)) return MQ_ERR_BAD_ARG;
+    if (!aligned(w_colsum, 16) || !aligned(ws, 256)) return MQ_ERR_BAD_ARG;
+    if (h16_out && (!aligned(h16_out, 16) || ldh < H || ldh % 8 != 0)) return MQ_ERR_BAD_ARG;
+    if ((long)M * (long)mq_a8_row_bytes(H) >= (1L << 31)) return MQ_ERR_BAD_SHAPE;
+    if ((long)255 * 255 * K >= (1L << 31)) return MQ_ERR_OVERFLOW_RISK;
+    if (ws_bytes < A8Workspace::bytes(M, K)) return MQ_ERR_WORKSPACE_TOO_SMALL;
+    hipStream_t st = (hipStream_t)stream;
+    A8Workspace w(ws, M, K);
+    rc = launch_act_quant(x, M, K, ldx, RowMap{0, 0, 0}, act_scale, act_zp, w.a8, w.rowsum, w.params, w.partials,
+                          act_scale_out, act_zp_out, st);
+    if (rc) return rc;
+    return launch_gemm_a8_geglu(w.a8, w.rowsum, w.params, M, K, packed, H, w_bits, w_signed ? 1 : 0, w_scale, w_zp,
+                                w_colsum, bias, out_scale, out_zp, a8_out, h16_out, ldh, st);
+}
+
+int mq_qlinear_a8_codes(const int8_t* a8, int M, int K, int lda, const float* act_scale, const int32_t* act_zp,
+                        const void* packed, int N, int w_bits, int layout, int w_signed, const float* w_scale,
+                        const int32_t* w_zp, const int32_t* w_colsum, const void* bias, void* y, int ldy,
+                        int32_t* acc_debug, void* stream) {
+    if (w_bits != 4 && w_bits != 8) return MQ_ERR_UNSUPPORTED_BITS;
+    if (!a8 || !act_scale || !act_zp || !packed || !w_scale || !w_zp || !w_colsum || !y) return MQ_ERR_BAD_ARG;
+    if (M <= 0 || K <= 0 || N <= 0 || ldy < N) return MQ_ERR_BAD_SHAPE;
+    if (layout != MQ_LAYOUT_KERNEL) return MQ_ERR_UNSUPPORTED_LAYOUT;
+    if (K % 64 != 0 || N % 8 != 0 || ldy % 8 != 0) return MQ_ERR_BAD_SHAPE;
+    if (lda % 128 != 0 || (size_t)lda < mq_a8_row_bytes(K)) return MQ_ERR_BAD_SHAPE;
+    if ((long)M * lda >= (1L << 31) || (long)(N + 31) * K >= (1L << 31)) return MQ_ERR_BAD_SHAPE;
+    if (!aligned(a8, 16) || !aligned(packed, 16) || !aligned(w_scale, 16) || !aligned(w_zp, 16) ||
+        !aligned(w_colsum, 16) || !aligned(y, 16) || (bias && !aligned(bias, 8)) ||
+        (acc_debug && !aligned(acc_debug, 16)))
+        return MQ_ERR_BAD_ARG;
+    if ((long)255 * 255 * K >= (1L << 31)) return MQ_ERR_OVERFLOW_RISK;
+    return launch_gemm_a8_codes(a8, lda, act_scale, act_zp, M, K, packed, N, w_bits, w_signed ? 1 : 0, w_scale, w_zp,
+                                w_colsum, bias, y, ldy, acc_debug, (hipStream_t)stream);
+}
+
 size_t mq_qlinear_a8_workspace_bytes(int M, int K) {
     if (M <= 0 || K <= 0) return 0;
     return A8Workspace::bytes(M, K);

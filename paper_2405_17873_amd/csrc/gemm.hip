@@ -260,6 +260,41 @@ __device__ __forceinline__ int4v widen_step(const WChunk<WBITS>& c, int s /*0..1
 }
 
 // ---------------------------------------------------------------------------------------------
+// GELU of the gated feed-forward epilogue.  Its result decides an integer code, so it is a fixed sequence of single
+// IEEE fp32 operations (no contraction, no library call): erf by the five-term rational approximation of Abramowitz
+// & Stegun 7.1.26 (|error| < 1.5e-7), exp by range reduction and a degree-6 polynomial.
+// ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ float exp32_nonpos(float y) {
+    if (y < -87.0f) return 0.0f;
+    const float n = rintf(__fmul_rn(y, 1.44269504f));
+    float r = __fmaf_rn(n, -0.693145752f, y);
+    r = __fmaf_rn(n, -1.42860677e-6f, r);
+    float p = 1.0f / 720.0f;
+    p = __fmaf_rn(p, r, 1.0f / 120.0f);
+    p = __fmaf_rn(p, r, 1.0f / 24.0f);
+    p = __fmaf_rn(p, r, 1.0f / 6.0f);
+    p = __fmaf_rn(p, r, 0.5f);
+    p = __fmaf_rn(p, r, 1.0f);
+    p = __fmaf_rn(p, r, 1.0f);
+    return ldexpf(p, (int)n);
+}
+
+__device__ __forceinline__ float gelu32(float g) {
+    const float x = __fmul_rn(fabsf(g), 0.70710678f);
+    const float t = __fdiv_rn(1.0f, __fmaf_rn(0.3275911f, x, 1.0f));
+    float p = 1.061405429f;
+    p = __fmaf_rn(p, t, -1.453152027f);
+    p = __fmaf_rn(p, t, 1.421413741f);
+    p = __fmaf_rn(p, t, -0.284496736f);
+    p = __fmaf_rn(p, t, 0.254829592f);
+    p = __fmul_rn(p, t);
+    const float e = exp32_nonpos(-__fmul_rn(x, x));
+    const float erf_abs = __fmaf_rn(-p, e, 1.0f);
+    const float erf_g = copysignf(erf_abs, g);
+    return __fmul_rn(__fmul_rn(0.5f, g), __fadd_rn(1.0f, erf_g));
+}
+
+// ---------------------------------------------------------------------------------------------
 // The GEMM kernel.  I8 == false: weight-only, fp16 activations straight from X, 64 k per stage.
 //                   I8 == true : int8 activation copy (row stride Kp = K rounded up to 128, padding zero),
 //                                128 k per stage = two 64-k weight tiles.
@@ -295,6 +330,15 @@ struct GemmArgs {
     int splits;
     uint32_t* partial;
     uint32_t* counters;
+    // MODE 1 (gated feed-forward projection, 8-bit output): N = 2H weight rows; codes of the gated product go to
+    // a8_out (row stride ld8 bytes, the int8 activation layout), optionally the product itself as fp16 to y
+    const float* out_scale_p;
+    const int32_t* out_zp_p;
+    int8_t* a8_out;
+    long ld8;
+    // MODE 2 (activations arrive as int8 codes): their parameters; row sums are taken inside the main loop
+    const float* act_scale_p;
+    const int32_t* act_zp_p;
 };
 
 // Workgroup id -> tile.  Consecutive workgroup ids land on different XCDs (8 of them, each with its own L2),
@@ -341,11 +385,18 @@ struct GemmPlan {
     static_assert(NAI % NW == 0, "tile rows must split over the waves");
 };
 
-template <bool I8, int BITS, int WGM, int WGN, int TM, int TN, int S, int KS, bool BF = false>
+// MODE 0: Y = linear(X).  MODE 1 (int8, two channel tiles per wave): gated feed-forward projection; the wave's first
+// channel tile is a value tile, its second the gate tile of the same 32 columns, and the epilogue emits
+// value * gelu(gate) as 8-bit codes for the next integer GEMM.  MODE 2 (int8): the activations arrive as codes with
+// their parameters; the row sums the epilogue needs are accumulated in the main loop.
+template <bool I8, int BITS, int WGM, int WGN, int TM, int TN, int S, int KS, bool BF = false, int MODE = 0>
 __global__ __launch_bounds__(WGM* WGN* KS * 64,
                              (TM * TN <= 8 && GemmPlan<I8, BITS, WGM, WGN, TM, TN, S, KS>::LDS_BYTES <= 80 * 1024) ? 2 : 1)
 void gemm_kernel(const GemmArgs g) {
     static_assert(!(I8 && BF), "the int8 path writes fp16");
+    constexpr bool GEGLU = MODE == 1, RS_INLINE = MODE == 2;
+    static_assert(MODE == 0 || (I8 && KS == 1), "the feed-forward pair is an int8 path without in-workgroup k split");
+    static_assert(!GEGLU || TN == 2, "value tile and gate tile per wave");
     using P = GemmPlan<I8, BITS, WGM, WGN, TM, TN, S, KS>;
     constexpr int NW = P::NW, NT = P::NT, BM = P::BM, BN = P::BN, CH = P::CH;
     constexpr int STAGE_BYTES = P::STAGE_BYTES;
@@ -359,14 +410,21 @@ void gemm_kernel(const GemmArgs g) {
     int bm, bn;
     // (the large wave tile has no registers to spare for the split of the reduction over workgroups, and no use
     // for it: its problems have hundreds of tiles)
-    constexpr bool CAN_SPLIT = TM * TN <= 4;
+    constexpr bool CAN_SPLIT = TM * TN <= 4 && MODE == 0;
     const int splits = CAN_SPLIT ? g.splits : 1;
     const int tile_id = splits > 1 ? (int)blockIdx.x / splits : (int)blockIdx.x;
     const int sp = (int)blockIdx.x - tile_id * splits;  // which part of the reduction this workgroup takes
     tile_of_block(tile_id, g.tiles_m, g.tiles_n, bm, bn);
-    const int m0 = bm * BM, n0 = bn * BN;
+    // n0: first output column of the workgroup (MODE 1: first gated column; it covers BN / 2 of them)
+    const int m0 = bm * BM, n0 = GEGLU ? bn * (BN / 2) : bn * BN;
     const int KC = g.K >> 6;
     const int G = (g.N + 31) >> 5;
+    const int H = g.N >> 1;  // MODE 1: gated columns
+    // local 32-channel group (wave column * TN + channel tile) -> group of weight rows, clamped to an existing one
+    auto group_of = [&](int gt) {
+        int gi = GEGLU ? ((gt % TN) ? (H >> 5) : 0) + (n0 >> 5) + gt / TN : (n0 >> 5) + gt;
+        return gi < G ? gi : G - 1;
+    };
     const int l31 = lane & 31, kb = lane >> 5;
     const uint32_t xflip = (I8 && g.w_off) ? 0x80808080u : 0u;
     constexpr int TILE_B = 256 * BITS;
@@ -401,8 +459,7 @@ void gemm_kernel(const GemmArgs g) {
         const int sub = j / P::NBI1, jj = j % P::NBI1;
         const int t = jj / PCS, piece = jj % PCS;
         const int gt = t / CH, cc = t % CH;
-        int gi = (n0 >> 5) + gt;
-        gi = gi < G ? gi : G - 1;
+        const int gi = group_of(gt);
         const bool on = j < P::NBI && lane < VALID_LANES;
         b_voff[i] = on ? (gi * KC + sub * CH + cc) * TILE_B + piece * 1024 + lane * 16 : OOB;
         b_lds[i] = __builtin_amdgcn_readfirstlane(
@@ -412,9 +469,7 @@ void gemm_kernel(const GemmArgs g) {
     int zc[TN];
 #pragma unroll
     for (int tn = 0; tn < TN; ++tn) {
-        int gi = (n0 >> 5) + wn * TN + tn;
-        gi = gi < G ? gi : G - 1;
-        const int n = gi * 32 + l31;
+        const int n = group_of(wn * TN + tn) * 32 + l31;
         zc[tn] = (I8 || BITS == 16) ? 0 : g.w_zp[n < g.N ? n : g.N - 1];
     }
 
@@ -434,22 +489,22 @@ void gemm_kernel(const GemmArgs g) {
     float c_scale = 0.0f, c_bias = 0.0f, c_sx = 1.0f;
     int c_zp = 0, c_colsum = 0, c_zx = 0;
     if (threadIdx.x < BN) {
-        int n = n0 + threadIdx.x;
+        int n = group_of((int)threadIdx.x >> 5) * 32 + ((int)threadIdx.x & 31);
         n = n < g.N ? n : g.N - 1;
         c_scale = BITS == 16 ? 1.0f : g.w_scale[n];
         if (g.bias) c_bias = BF ? bf16_bits_to_float(g.bias[n]) : (float)__builtin_bit_cast(_Float16, g.bias[n]);
         if constexpr (I8) {
             c_zp = g.w_zp[n];
             c_colsum = g.w_colsum[n];
-            c_sx = g.params->scale;
-            c_zx = g.params->zp;
+            c_sx = RS_INLINE ? *g.act_scale_p : g.params->scale;
+            c_zx = RS_INLINE ? *g.act_zp_p : g.params->zp;
         }
     }
     int rsum[TM];
 #pragma unroll
     for (int tm = 0; tm < TM; ++tm) {
         const int m = m0 + (wm * TM + tm) * 32 + l31;
-        rsum[tm] = I8 ? g.rowsum[m < g.M ? m : g.M - 1] : 0;
+        rsum[tm] = (I8 && !RS_INLINE) ? g.rowsum[m < g.M ? m : g.M - 1] : 0;
     }
 
     // Every wave issues exactly OPS loads per stage (padding loads go to the sink), so that "at most n * OPS loads
@@ -528,6 +583,14 @@ void gemm_kernel(const GemmArgs g) {
                 else
                     acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_f16(wf[tn], xf[s][tm], acc[tm][tn], 0, 0, 0);
             }
+        if constexpr (RS_INLINE) {  // this lane's share of the row sums of the stored activations (bytes a' = code - 128)
+#pragma unroll
+            for (int tm = 0; tm < TM; ++tm) {
+                const int4v a = __builtin_bit_cast(int4v, xf[s][tm]);
+#pragma unroll
+                for (int i = 0; i < 4; ++i) rsum[tm] = __builtin_amdgcn_sdot4(a[i], 0x01010101, rsum[tm], false);
+            }
+        }
     };
 
     // stage 0 must have landed; the younger stages stay in flight
@@ -589,6 +652,11 @@ void gemm_kernel(const GemmArgs g) {
         buf = nb;
     }
     __syncthreads();  // every wave is done reading the stages: what follows may overwrite them
+
+    if constexpr (RS_INLINE) {  // lanes l and l + 32 hold the two k-halves of row l's sum
+#pragma unroll
+        for (int tm = 0; tm < TM; ++tm) rsum[tm] += __shfl_xor(rsum[tm], 32, 64);
+    }
 
     // Park the per-channel constants in LDS behind the stages: multiplier, additive term and (int8) the two
     // zero-point corrections.
@@ -736,6 +804,69 @@ void gemm_kernel(const GemmArgs g) {
     // tiles at a time: finished fp16 values are written as 8-byte pieces into a [32 rows][GS*32 channels] image
     // (16-byte chunks XOR-swizzled by row), read back as 16 bytes per lane along rows, and stored with 4*GS lanes
     // covering one contiguous row segment of GS*64 bytes.
+    if constexpr (GEGLU) {
+        // value * gelu(gate) -> 8-bit codes in the int8 activation layout (a' = code - 128, groups of 8 columns in
+        // the order 0,4,1,5,2,6,3,7, columns from H to the row stride zero), optionally the product itself as fp16.
+        // A lane holds four consecutive columns of one row; the lane 32 further on holds the other four of the same
+        // group of 8, so the two swap their packed words and each keeps one of the group's two output words.
+        // Rows are staged through LDS (32 rows x 32 bytes per wave) and leave as 16-byte pieces.
+        const float inv_o = __fdiv_rn(1.0f, *g.out_scale_p);
+        const float zf_o = (float)*g.out_zp_p;
+        static_assert(P::NWG * 3072 <= S * STAGE_BYTES, "epilogue staging must fit the LDS stages");
+        uint8_t* ep8 = lds + wvg * 3072;
+        uint8_t* ep16 = ep8 + 1024;
+        const int col0 = n0 + wn * 32;  // first gated column of this wave
+#pragma unroll
+        for (int tm = 0; tm < TM; ++tm) {
+            const int mt0 = m0 + (wm * TM + tm) * 32;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int cl_v = (wn * TN) * 32 + 8 * q + 4 * kb, cl_g = cl_v + 32;
+                const float4v mul_v = *(const float4v*)(ch_mul + cl_v), add_v = *(const float4v*)(ch_add + cl_v);
+                const float4v mul_g = *(const float4v*)(ch_mul + cl_g), add_g = *(const float4v*)(ch_add + cl_g);
+                const int4v dw_v = *(const int4v*)(ch_dw + cl_v), cn_v = *(const int4v*)(ch_cn + cl_v);
+                const int4v dw_g = *(const int4v*)(ch_dw + cl_g), cn_g = *(const int4v*)(ch_cn + cl_g);
+                uint32_t word = 0;
+                half4 hh;
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const int av = acc[tm][0][4 * q + r] + __mul24(dw_v[r], rsum[tm]) + cn_v[r];
+                    const int ag = acc[tm][1][4 * q + r] + __mul24(dw_g[r], rsum[tm]) + cn_g[r];
+                    const float lv = __fmaf_rn((float)av, mul_v[r], add_v[r]);
+                    const float lg = __fmaf_rn((float)ag, mul_g[r], add_g[r]);
+                    const float h = __fmul_rn(lv, gelu32(lg));
+                    float t = __fadd_rn(rintf(__fmul_rn(h, inv_o)), zf_o);
+                    t = fminf(fmaxf(t, 0.0f), 255.0f);
+                    const int code = col0 + 8 * q + 4 * kb + r < H ? (int)t - 128 : 0;
+                    word |= ((uint32_t)code & 255u) << (8 * r);
+                    hh[r] = (_Float16)h;
+                }
+                const uint32_t other = (uint32_t)__shfl_xor((int)word, 32, 64);
+                const uint32_t lo = kb ? other : word, hi = kb ? word : other;  // columns 0..3 and 4..7 of the group
+                // v_perm_b32: selector bytes 0..3 pick bytes of the second source, 4..7 of the first
+                const uint32_t out = kb ? __builtin_amdgcn_perm(hi, lo, 0x07030602u) : __builtin_amdgcn_perm(hi, lo, 0x05010400u);
+                *(uint32_t*)(ep8 + l31 * 32 + q * 8 + kb * 4) = out;
+                if (g.y) *(half4*)(ep16 + l31 * 64 + q * 16 + kb * 8) = hh;
+            }
+            __builtin_amdgcn_wave_barrier();
+            {
+                const int row = lane >> 1, half = lane & 1;
+                const uint4v v = *(const uint4v*)(ep8 + row * 32 + half * 16);
+                const int m = mt0 + row, col = col0 + half * 16;
+                if (m < g.M && col < g.ld8) *(uint4v*)(g.a8_out + (long)m * g.ld8 + col) = v;
+            }
+            if (g.y) {
+#pragma unroll
+                for (int i = 0; i < 2; ++i) {
+                    const int idx = i * 64 + lane, row = idx >> 2, c = idx & 3;
+                    const uint4v v = *(const uint4v*)(ep16 + row * 64 + c * 16);
+                    const int m = mt0 + row, col = col0 + c * 8;
+                    if (m < g.M && col < H) *(uint4v*)(g.y + (long)m * g.ldy + col) = v;
+                }
+            }
+            __builtin_amdgcn_wave_barrier();
+        }
+    } else {
     static_assert(TN == 1 || TN == 2 || TN == 4, "channel tiles per wave: 1, 2 or 4");
     constexpr int G0 = TN >= 4 ? 4 : TN;         // channel tiles staged at a time
     constexpr int EP_BYTES = 32 * G0 * 64;       // staging bytes per storing wave
@@ -801,6 +932,7 @@ void gemm_kernel(const GemmArgs g) {
     for (int tm = 0; tm < TM; ++tm) {
         if (KS > 1 && owner(tm) != grp) continue;  // the finished sums of this slab live in the other group
         store_cols(std::integral_constant<int, 0>{}, std::integral_constant<int, G0>{}, tm);
+    }
     }
     if (g.phase_clk && threadIdx.x == 0) {
         long long* o = g.phase_clk + (long)blockIdx.x * 4;
@@ -909,13 +1041,14 @@ constexpr int pick_stages(int budget, int max_stages) {
     return 2;
 }
 
-template <bool I8, int BITS, int WGM, int WGN, int TM, int TN, int KS, int BUDGET, int MAXS, bool BF = false>
+template <bool I8, int BITS, int WGM, int WGN, int TM, int TN, int KS, int BUDGET, int MAXS, bool BF = false, int MODE = 0>
 static int run_gemm(GemmArgs& g, int tile_index, hipStream_t st) {
     constexpr int S = pick_stages<I8, BITS, WGM, WGN, TM, TN, KS>(BUDGET, MAXS);
     using P = GemmPlan<I8, BITS, WGM, WGN, TM, TN, S, KS>;
     static_assert(P::LDS_BYTES <= 160 * 1024, "LDS plan exceeds the compute unit");
     g.tiles_m = (g.M + P::BM - 1) / P::BM;
     g.tiles_n = (g.N + P::BN - 1) / P::BN;
+    if (MODE == 1) g.tiles_n = (int)((g.ld8 + P::BN / 2 - 1) / (P::BN / 2));  // gated columns up to the padded row end
     // Split the reduction over workgroups where the tiles alone would leave most compute units idle and the reduction
     // is long: as many parts as fill about two workgroups per compute unit, each at least four pipeline stages long.
     const long tiles = (long)g.tiles_m * g.tiles_n;
@@ -930,12 +1063,12 @@ static int run_gemm(GemmArgs& g, int tile_index, hipStream_t st) {
         if (splits > 16) splits = 16;
     }
     g.splits = 1;
-    if (TM * TN <= 4 && splits > 1 && take_split_scratch((size_t)tiles * splits * P::BM * P::BN * 4, (int)tiles, &g.partial, &g.counters))
+    if (MODE == 0 && TM * TN <= 4 && splits > 1 && take_split_scratch((size_t)tiles * splits * P::BM * P::BN * 4, (int)tiles, &g.partial, &g.counters))
         g.splits = splits;
     g.phase_clk = (tiles * g.splits <= g_phase_cap) ? g_phase_clk : nullptr;
-    auto kern = gemm_kernel<I8, BITS, WGM, WGN, TM, TN, S, KS, BF>;
+    auto kern = gemm_kernel<I8, BITS, WGM, WGN, TM, TN, S, KS, BF, MODE>;
     static bool prepared = false;  // once per instantiation: allow more than 64 KB of dynamic LDS, name the slot
-    const int slot = prof_gemm_slot(I8 ? 1 : (BF ? 2 : 0), BITS, tile_index);
+    const int slot = prof_gemm_slot(MODE ? 2 + MODE : (I8 ? 1 : (BF ? 2 : 0)), BITS, tile_index);
     if (!prepared) {
         if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, P::LDS_BYTES) !=
             hipSuccess) {
@@ -943,14 +1076,19 @@ static int run_gemm(GemmArgs& g, int tile_index, hipStream_t st) {
             return MQ_ERR_HIP;
         }
         char name[96];
-        snprintf(name, sizeof name, "mq::gemm_kernel<%s, %d, %d, %d, %d, %d, %d, %d, %s>", I8 ? "true" : "false", BITS,
-                 WGM, WGN, TM, TN, S, KS, BF ? "true" : "false");
+        if (MODE)
+            snprintf(name, sizeof name, "mq::gemm_kernel<%s, %d, %d, %d, %d, %d, %d, %d, %s, %d>", I8 ? "true" : "false",
+                     BITS, WGM, WGN, TM, TN, S, KS, BF ? "true" : "false", MODE);
+        else
+            snprintf(name, sizeof name, "mq::gemm_kernel<%s, %d, %d, %d, %d, %d, %d, %d, %s>", I8 ? "true" : "false",
+                     BITS, WGM, WGN, TM, TN, S, KS, BF ? "true" : "false");
         prof_name_slot(slot, name);
         prepared = true;
     }
     const double abytes = I8 ? 1.0 * g.M * g.K + 4.0 * g.M : 2.0 * g.M * g.K;
+    const double ybytes = MODE == 1 ? 1.0 * g.M * g.ld8 + (g.y ? 1.0 * g.M * g.N : 0.0) : 2.0 * g.M * g.N;
     ProfScope prof(st, slot, 2.0 * g.M * g.N * g.K,
-                   abytes + (double)g.N * g.K * BITS / 8 + (I8 ? 14.0 : 10.0) * g.N + 2.0 * g.M * g.N);
+                   abytes + (double)g.N * g.K * BITS / 8 + (I8 ? 14.0 : 10.0) * g.N + ybytes);
     hipLaunchKernelGGL(kern, dim3(g.tiles_m * g.tiles_n * g.splits), dim3(P::NT), P::LDS_BYTES, st, g);
     MQ_HIP_CHECK_LAUNCH();
     return MQ_OK;
@@ -1042,6 +1180,83 @@ int launch_gemm_a8(const int8_t* a8, const int32_t* rowsum, const ActParams* par
         // which reads them as q - 128 (w_off = 128); signed (symmetric) codes are used as they are.
         g.w_off = w_signed ? 0 : 128;
         return dispatch_gemm<true, 8>(g, st);
+    }
+    return MQ_ERR_UNSUPPORTED_BITS;
+}
+
+
+// Gated feed-forward projection with 8-bit output (MODE 1).  N = 2H weight rows.
+int launch_gemm_a8_geglu(const int8_t* a8, const int32_t* rowsum, const ActParams* params, int M, int K,
+                         const void* packed, int H, int w_bits, int w_signed, const float* w_scale, const int32_t* w_zp,
+                         const int32_t* w_colsum, const void* bias, const float* out_scale, const int32_t* out_zp,
+                         int8_t* a8_out, void* h16, int ldh, hipStream_t st) {
+    const int Kp = (K + 127) / 128 * 128;
+    GemmArgs g{};
+    g.a = a8;
+    g.a_row_bytes = Kp;
+    g.a_bytes = (uint32_t)((long)M * Kp);
+    g.packed = (const uint8_t*)packed;
+    g.packed_bytes = (uint32_t)((long)((2 * H + 31) / 32) * (K / 64) * 256 * w_bits);
+    g.M = M; g.N = 2 * H; g.K = K;
+    g.k_stages = Kp / 128;
+    g.w_scale = w_scale; g.w_zp = w_zp; g.bias = (const uint16_t*)bias;
+    g.y = (uint16_t*)h16; g.ldy = ldh;
+    g.rowsum = rowsum; g.params = params; g.w_colsum = w_colsum;
+    g.out_scale_p = out_scale; g.out_zp_p = out_zp;
+    g.a8_out = a8_out; g.ld8 = (H + 127) / 128 * 128;
+    // the large tile (128 gated columns per workgroup) once it yields two workgroups per compute unit
+    const bool big = g_force_tile == 0 || (g_force_tile < 0 && (long)((M + 127) / 128) * ((H + 127) / 128) >= 512);
+    if (w_bits == 4) {
+        g.w_off = 0;
+        if (big) return run_gemm<true, 4, 1, 4, 4, 2, 1, 80 * 1024, 4, false, 1>(g, 0, st);
+        return run_gemm<true, 4, 2, 2, 2, 2, 1, 80 * 1024, 4, false, 1>(g, 1, st);
+    }
+    if (w_bits == 8) {
+        g.w_off = w_signed ? 0 : 128;
+        if (g_force_tile == 0) return run_gemm<true, 8, 1, 4, 4, 2, 1, 160 * 1024, 4, false, 1>(g, 0, st);
+        return run_gemm<true, 8, 2, 2, 2, 2, 1, 80 * 1024, 4, false, 1>(g, 1, st);
+    }
+    return MQ_ERR_UNSUPPORTED_BITS;
+}
+
+// Integer GEMM on activations that arrive as codes in the int8 activation layout (MODE 2).
+int launch_gemm_a8_codes(const int8_t* a8, long lda, const float* act_scale, const int32_t* act_zp, int M, int K,
+                         const void* packed, int N, int w_bits, int w_signed, const float* w_scale, const int32_t* w_zp,
+                         const int32_t* w_colsum, const void* bias, void* y, int ldy, int32_t* acc_debug,
+                         hipStream_t st) {
+    const int Kp = (K + 127) / 128 * 128;
+    GemmArgs g{};
+    g.a = a8;
+    g.a_row_bytes = lda;
+    g.a_bytes = (uint32_t)((long)(M - 1) * lda + Kp);
+    g.packed = (const uint8_t*)packed;
+    g.packed_bytes = (uint32_t)((long)((N + 31) / 32) * (K / 64) * 256 * w_bits);
+    g.M = M; g.N = N; g.K = K;
+    g.k_stages = Kp / 128;
+    g.w_scale = w_scale; g.w_zp = w_zp; g.bias = (const uint16_t*)bias;
+    g.y = (uint16_t*)y; g.ldy = ldy;
+    g.w_colsum = w_colsum;
+    g.act_scale_p = act_scale; g.act_zp_p = act_zp;
+    g.acc_debug = acc_debug;
+    // no in-workgroup k split here, and not the large tile (no registers to spare for the row sums; the layers this
+    // serves, the output linears of feed-forward blocks, are narrow)
+    int t = pick_tile(M, N, K, true);
+    t = t >= 3 ? t - 2 : t;
+    if (w_bits == 4) {
+        g.w_off = 0;
+        switch (t) {
+            case 0:
+            case 1: return run_gemm<true, 4, 2, 2, 2, 2, 1, 80 * 1024, 4, false, 2>(g, 1, st);
+            default: return run_gemm<true, 4, 2, 2, 1, 1, 1, 80 * 1024, 8, false, 2>(g, 2, st);
+        }
+    }
+    if (w_bits == 8) {
+        g.w_off = w_signed ? 0 : 128;
+        switch (t) {
+            case 0:
+            case 1: return run_gemm<true, 8, 2, 2, 2, 2, 1, 80 * 1024, 4, false, 2>(g, 1, st);
+            default: return run_gemm<true, 8, 2, 2, 1, 1, 1, 80 * 1024, 8, false, 2>(g, 2, st);
+        }
     }
     return MQ_ERR_UNSUPPORTED_BITS;
 }

@@ -86,14 +86,24 @@ int launch_gemm_a8(const int8_t* a8, const int32_t* rowsum, const ActParams* par
                    const int32_t* w_colsum, const void* bias, void* y, int ldy, RowMap out_map, int32_t* acc_debug,
                    hipStream_t st);
 
+int launch_gemm_a8_geglu(const int8_t* a8, const int32_t* rowsum, const ActParams* params, int M, int K,
+                         const void* packed, int H, int w_bits, int w_signed, const float* w_scale, const int32_t* w_zp,
+                         const int32_t* w_colsum, const void* bias, const float* out_scale, const int32_t* out_zp,
+                         int8_t* a8_out, void* h16, int ldh, hipStream_t st);
+int launch_gemm_a8_codes(const int8_t* a8, long lda, const float* act_scale, const int32_t* act_zp, int M, int K,
+                         const void* packed, int N, int w_bits, int w_signed, const float* w_scale, const int32_t* w_zp,
+                         const int32_t* w_colsum, const void* bias, void* y, int ldy, int32_t* acc_debug,
+                         hipStream_t st);
+
 void set_force_tile(int t);
 void set_force_splits(int n);
 void set_phase_buffer(long long* p, long workgroups);
 
 // ---- optional per-kernel event timing (prof.hip) ----
-enum { PROF_GEMM_TILES = 5, PROF_GEMM_BITS = 5, PROF_ACT_MINMAX = 3 * PROF_GEMM_BITS * PROF_GEMM_TILES, PROF_ACT_QUANTIZE, PROF_BOS_ROWS };
+enum { PROF_GEMM_TILES = 5, PROF_GEMM_BITS = 5, PROF_GEMM_FAMILIES = 5, PROF_ACT_MINMAX = PROF_GEMM_FAMILIES * PROF_GEMM_BITS * PROF_GEMM_TILES, PROF_ACT_QUANTIZE, PROF_BOS_ROWS };
 int prof_num_slots();
-int prof_gemm_slot(int family /*0 weight-only fp16, 1 int8, 2 weight-only bf16*/, int bits, int tile);
+int prof_gemm_slot(int family /*0 weight-only fp16, 1 int8, 2 weight-only bf16, 3 int8 gated projection, 4 int8 on codes*/,
+                   int bits, int tile);
 bool prof_enabled();
 bool prof_wants(int slot);
 int prof_filter(int slot, int stride);

@@ -429,6 +429,96 @@ def test_degenerate_tensors(mq, orc):
     assert np.array_equal(host(y), np.broadcast_to(b.view(np.float16), (M, N)))  # zero input: the output is the bias
 
 
+# ----------------------------------------------------------------------------------------------- feed-forward pair, 8 bits in between
+
+def a8_layout(codes):
+    """Unsigned codes [M,K] -> the int8 activation layout the GEMM reads (test-side marshalling only)."""
+    M, K = codes.shape
+    Kp = (K + 127) // 128 * 128
+    a = np.zeros((M, Kp), np.int8)
+    a[:, :K] = (codes.astype(np.int16) - 128).astype(np.int8)
+    perm = np.array([0, 4, 1, 5, 2, 6, 3, 7])
+    return a.reshape(M, Kp // 8, 8)[:, :, perm].reshape(M, Kp)
+
+
+def a8_unlayout(a8, K):
+    """The inverse: int8 layout [M,Kp] -> unsigned codes [M,K] and the padding bytes."""
+    M, Kp = a8.shape
+    inv = np.argsort(np.array([0, 4, 1, 5, 2, 6, 3, 7]))
+    lin = a8.reshape(M, Kp // 8, 8)[:, :, inv].reshape(M, Kp)
+    return (lin[:, :K].astype(np.int16) + 128).astype(np.uint8), lin[:, K:]
+
+
+@pytest.mark.parametrize("bits,sym", [(4, False), (8, True), (8, False)])
+@pytest.mark.parametrize("tile", (-1, 0, 1))
+def test_geglu_projection_emits_the_oracles_codes(mq, orc, bits, sym, tile):
+    """value * gelu(gate) -> 8-bit codes: bit-exact (exact int32 accumulators, then the same fp32 operations)."""
+    mq.tune_force_tile(tile)
+    try:
+        for (M, K, H) in ((256, 320, 320), (77, 128, 32), (300, 640, 96), (130, 1280, 160)):
+            x = si.activations_f16(61, f"ff/x{M}x{K}", M, K, outlier_prob=0.01)
+            w = si.weights_f16(61, f"ff/w{H}x{K}", 2 * H, K)
+            b = si.bias_f16(61, f"ff/b{H}", 2 * H)
+            pw, oc, os_, oz = make_weight(mq, orc, w, bits, sym)
+            out_act = (np.float32(0.006), 28)
+            d_out = (dev(np.array([out_act[0]], np.float32)), dev(np.array([out_act[1]], np.int32)))
+            for act in (None, (np.float32(0.03), 117)):
+                d_act = None if act is None else (dev(np.array([act[0]], np.float32)), dev(np.array([act[1]], np.int32)))
+                a8, h16, got_act = mq.qlinear_a8_geglu(dev(x), pw, d_out, act=d_act, bias=dev(b), want_h16=True,
+                                                       want_act=True)
+                rq, rh, ract = orc.linear_a8_geglu(x, oc, os_, oz, out_act, w_signed=sym, act=act, bias=b)
+                assert host(got_act[0])[0] == ract[0] and host(got_act[1])[0] == ract[1]
+                codes, pad = a8_unlayout(host(a8), H)
+                assert a8.shape[1] == (H + 127) // 128 * 128 and not pad.any()
+                assert np.array_equal(codes, rq), f"geglu codes b{bits} tile{tile} {M}x{K}x{H}"
+                assert np.array_equal(host(h16).view(np.uint16), rh), "gated product in fp16"
+    finally:
+        mq.tune_force_tile(-1)
+
+
+@pytest.mark.parametrize("bits,sym", [(4, False), (8, True), (8, False)])
+@pytest.mark.parametrize("tile", (-1, 1, 2))
+def test_a8_linear_on_codes(mq, orc, bits, sym, tile):
+    mq.tune_force_tile(tile)
+    try:
+        rng = np.random.default_rng(62)
+        for (M, K, N) in ((256, 320, 320), (77, 128, 40), (300, 2560, 264), (1, 64, 8)):
+            qx = rng.integers(0, 256, (M, K)).astype(np.uint8)
+            qx[0] = 255
+            qx[-1] = 0
+            act = (np.float32(0.0123), 97)
+            w = si.weights_f16(62, f"cd/w{N}x{K}", N, K)
+            b = si.bias_f16(62, f"cd/b{N}", N)
+            pw, oc, os_, oz = make_weight(mq, orc, w, bits, sym)
+            d_act = (dev(np.array([act[0]], np.float32)), dev(np.array([act[1]], np.int32)))
+            y, acc = mq.qlinear_a8_codes(dev(a8_layout(qx)), K, d_act, pw, bias=dev(b), want_acc=True)
+            ry, racc = orc.linear_a8_codes(qx, act, oc, os_, oz, w_signed=sym, bias=b)
+            assert np.array_equal(host(acc), racc), f"codes acc b{bits} tile{tile} {M}x{K}x{N}"
+            assert_close16(host(y), ry, f"codes b{bits} tile{tile} {M}x{K}x{N}")
+    finally:
+        mq.tune_force_tile(-1)
+
+
+def test_feed_forward_pair_end_to_end(mq, orc):
+    """Gated projection (C -> 8C) into the output linear (4C -> C) with the activation kept in 8 bits in between: the
+    second call consumes exactly what the first wrote; against the oracle run the same way."""
+    M, C_ = 200, 320
+    x = si.activations_f16(63, "ffp/x", M, C_)
+    w1 = si.weights_f16(63, "ffp/w1", 8 * C_, C_)
+    w2 = si.weights_f16(63, "ffp/w2", C_, 4 * C_)
+    b1, b2 = si.bias_f16(63, "ffp/b1", 8 * C_), si.bias_f16(63, "ffp/b2", C_)
+    p1, c1, s1, z1 = make_weight(mq, orc, w1, 4)
+    p2, c2, s2, z2 = make_weight(mq, orc, w2, 4)
+    mid = (np.float32(0.004), 42)
+    d_mid = (dev(np.array([mid[0]], np.float32)), dev(np.array([mid[1]], np.int32)))
+    a8, _, _ = mq.qlinear_a8_geglu(dev(x), p1, d_mid, bias=dev(b1))
+    y, acc = mq.qlinear_a8_codes(a8, 4 * C_, d_mid, p2, bias=dev(b2), want_acc=True)
+    rq, _, _ = orc.linear_a8_geglu(x, c1, s1, z1, mid, bias=b1, want_h16=False)
+    ry, racc = orc.linear_a8_codes(rq, mid, c2, s2, z2, bias=b2)
+    assert np.array_equal(host(acc), racc)
+    assert_close16(host(y), ry, "feed-forward pair")
+
+
 # ----------------------------------------------------------------------------------------------- BOS-aware K/V
 
 @pytest.mark.parametrize("N", (640, 1280))
