@@ -52,7 +52,7 @@ def shapes():
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--iters", type=int, default=200)
-    ap.add_argument("--only", default="", help="comma-separated labels (c1,c2,c3,c4,c5,small-M)")
+    ap.add_argument("--only", default="", help="comma-separated labels (c1,c2,c3,c4,c5,small-M,ff)")
     args = ap.parse_args()
 
     import torch
@@ -145,6 +145,65 @@ def main():
                   f"{max(t_hbm, t_mfma) / k_us:7.3f}", flush=True)
             del sets
             torch.cuda.empty_cache()
+    if not only or "ff" in only:
+        ff_pairs(mq, torch, min(args.iters, 100), overhead_us)
+
+
+def ff_pairs(mq, torch, iters, overhead_us):
+    """Feed-forward block of a transformer layer, C -> 8C -> (GEGLU) -> 4C -> C, W4A8 with static activation
+    parameters: the fused pair (gated projection that emits 8-bit codes + output linear on codes: 3 kernels) against
+    the same two linears through the ordinary entry points (fp16 8C-wide tensor out, fp16 4C-wide tensor in, both
+    with static parameters: 4 kernels; the GEGLU kernel that a framework would run between them is NOT included)."""
+    dev = torch.device("cuda:0")
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(1)
+    print("\n# feed-forward pair, W4A8, static activation parameters: us per block (both linears), cold operands")
+    print(f"{'M':>6s}{'C':>6s} {'fused us':>9s}{'separate us':>12s}{'T OP/s fused':>13s}{'t_MFMA us':>10s}{'frac':>6s}")
+    for (M, Cc) in ((4096, 1280), (16384, 640)):
+        ops = 2.0 * M * Cc * 8 * Cc + 2.0 * M * 4 * Cc * Cc
+        per_set = 2 * M * Cc + 4 * Cc * Cc + M * 4 * Cc * 2 + 2 * Cc * Cc + 2 * M * Cc
+        nsets = max(2, min(iters, -(-LLC_BYTES // per_set)))
+        fused, sep = [], []
+        sc = lambda v: torch.tensor([v], dtype=torch.float32, device=dev)
+        zi = lambda v: torch.tensor([v], dtype=torch.int32, device=dev)
+        act_in, act_mid = (sc(8.0 / 255), zi(128)), (sc(0.01), zi(20))
+        ws = torch.empty(max(mq.qlinear_a8_workspace_bytes(M, Cc), mq.qlinear_a8_workspace_bytes(M, 4 * Cc)),
+                         dtype=torch.uint8, device=dev)
+        for _ in range(nsets):
+            packs = []
+            for (N, K) in ((8 * Cc, Cc), (Cc, 4 * Cc)):
+                w = (torch.randn(N, K, generator=gen, device=dev) * 0.02).half()
+                c, s_, z = mq.quantize_weights(w, 4)
+                p, cs = mq.pack_weights(c, 4, mq.LAYOUT_KERNEL)
+                packs.append(mq.PackedWeight(p, s_, z, cs, N, K, 4, mq.LAYOUT_KERNEL, False))
+                del w, c
+            x = torch.randn(M, Cc, generator=gen, device=dev).half()
+            a8 = torch.empty((M, mq.a8_row_bytes(4 * Cc)), dtype=torch.int8, device=dev)
+            y = torch.empty(M, Cc, dtype=torch.float16, device=dev)
+            f1 = mq.plan_qlinear_a8_geglu(x, packs[0], act_mid, None, a8, ws, act=act_in)
+            f2 = mq.plan_qlinear_a8_codes(a8, 4 * Cc, act_mid, packs[1], None, y)
+            fused.append((f1, f2))
+            y8 = torch.empty(M, 8 * Cc, dtype=torch.float16, device=dev)
+            s1 = mq.plan_qlinear_a8(x, packs[0], None, y8, ws, act=act_in)
+            s2 = mq.plan_qlinear_a8(y8[:, :4 * Cc], packs[1], None, y, ws, act=act_mid)
+            sep.append((s1, s2))
+        res = []
+        for calls in (fused, sep):
+            for i in range(min(nsets, 4)):
+                calls[i][0](), calls[i][1]()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for i in range(iters):
+                calls[i % nsets][0](), calls[i % nsets][1]()
+            e1.record()
+            torch.cuda.synchronize()
+            res.append(e0.elapsed_time(e1) * 1e3 / iters)
+        t_mfma = ops / PEAK["a"] * 1e6
+        print(f"{M:6d}{Cc:6d} {res[0]:9.2f}{res[1]:12.2f}{ops / res[0] / 1e6:13.1f}{t_mfma:10.2f}{t_mfma / res[0]:6.3f}",
+              flush=True)
+        del fused, sep
+        torch.cuda.empty_cache()
 
 
 if __name__ == "__main__":

@@ -454,14 +454,13 @@ int orc_bos_aware_kv_proj(const uint16_t* ctx, int B, int T, int K, const uint8_
 /*                                                                           */
 /* (first half of the projection = value, second half = gate).  A code is an */
 /* integer decided by floating point, so every operation is spelt out: all   */
-/* are single IEEE fp32 operations, and the error function is the five-term  */
-/* rational approximation of Abramowitz & Stegun 7.1.26 (|error| < 1.5e-7)   */
-/* over an exponential computed by range reduction and a degree-6 polynomial.*/
+/* are single IEEE fp32 operations; the error function is 1 - exp(-x P(x))   */
+/* with a fitted degree-6 P (|error| < 2e-7, no division) over an exponential*/
+/* computed by range reduction and a degree-6 polynomial.                    */
 /* ------------------------------------------------------------------------- */
 
-/* exp(y) for y <= 0 in fp32: y = n ln2 + r, |r| <= ln2/2; e^r by Horner; scaled by 2^n. */
+/* exp(y) for -64 < y <= 0 in fp32: y = n ln2 + r, |r| <= ln2/2; e^r by Horner; scaled by 2^n. */
 static float exp32_nonpos(float y) {
-    if (y < -87.0f) return 0.0f;
     float n = rintf(y * 1.44269504f);
     float r = fmaf(n, -0.693145752f, y);
     r = fmaf(n, -1.42860677e-6f, r);
@@ -475,18 +474,20 @@ static float exp32_nonpos(float y) {
     return ldexpf(p, (int)n);
 }
 
+/* gelu(g) = 0.5 g (1 + erf(g / sqrt 2)) with erf(x) = 1 - exp(-x P(x)) for 0 <= x <= 4.3 (beyond, x is held at 4.3,
+ * where erf is 1 to 1e-9) and odd symmetry; P is a degree-6 polynomial fitted to -ln(erfc(x)) / x, which keeps the
+ * absolute error of erf below 2e-7 without any division. */
 static float gelu32(float g) {
-    float x = fabsf(g) * 0.70710678f;
-    float t = 1.0f / fmaf(0.3275911f, x, 1.0f);
-    float p = 1.061405429f;
-    p = fmaf(p, t, -1.453152027f);
-    p = fmaf(p, t, 1.421413741f);
-    p = fmaf(p, t, -0.284496736f);
-    p = fmaf(p, t, 0.254829592f);
-    p = p * t;
-    float e = exp32_nonpos(-(x * x));
-    float erf_abs = fmaf(-p, e, 1.0f);
-    float erf_g = copysignf(erf_abs, g);
+    float x = fminf(fabsf(g) * 0.70710678f, 4.3f);
+    float p = -5.95750535e-05f;
+    p = fmaf(p, x, 0.000253331062f);
+    p = fmaf(p, x, 0.00176583871f);
+    p = fmaf(p, x, -0.0206223261f);
+    p = fmaf(p, x, 0.103378408f);
+    p = fmaf(p, x, 0.636503041f);
+    p = fmaf(p, x, 1.12838686f);
+    float e = exp32_nonpos(-(p * x));
+    float erf_g = copysignf(1.0f - e, g);
     return (0.5f * g) * (1.0f + erf_g);
 }
 

@@ -261,11 +261,11 @@ __device__ __forceinline__ int4v widen_step(const WChunk<WBITS>& c, int s /*0..1
 
 // ---------------------------------------------------------------------------------------------
 // GELU of the gated feed-forward epilogue.  Its result decides an integer code, so it is a fixed sequence of single
-// IEEE fp32 operations (no contraction, no library call): erf by the five-term rational approximation of Abramowitz
-// & Stegun 7.1.26 (|error| < 1.5e-7), exp by range reduction and a degree-6 polynomial.
+// IEEE fp32 operations (no contraction, no library call, no division): gelu(g) = 0.5 g (1 + erf(g / sqrt 2)) with
+// erf(x) = 1 - exp(-x P(x)) on [0, 4.3] (x is held at 4.3 beyond), P a degree-6 polynomial fitted to
+// -ln(erfc(x)) / x (|error of erf| < 2e-7), and exp by range reduction and a degree-6 polynomial.
 // ---------------------------------------------------------------------------------------------
-__device__ __forceinline__ float exp32_nonpos(float y) {
-    if (y < -87.0f) return 0.0f;
+__device__ __forceinline__ float exp32_nonpos(float y) {  // -64 < y <= 0
     const float n = rintf(__fmul_rn(y, 1.44269504f));
     float r = __fmaf_rn(n, -0.693145752f, y);
     r = __fmaf_rn(n, -1.42860677e-6f, r);
@@ -280,17 +280,16 @@ __device__ __forceinline__ float exp32_nonpos(float y) {
 }
 
 __device__ __forceinline__ float gelu32(float g) {
-    const float x = __fmul_rn(fabsf(g), 0.70710678f);
-    const float t = __fdiv_rn(1.0f, __fmaf_rn(0.3275911f, x, 1.0f));
-    float p = 1.061405429f;
-    p = __fmaf_rn(p, t, -1.453152027f);
-    p = __fmaf_rn(p, t, 1.421413741f);
-    p = __fmaf_rn(p, t, -0.284496736f);
-    p = __fmaf_rn(p, t, 0.254829592f);
-    p = __fmul_rn(p, t);
-    const float e = exp32_nonpos(-__fmul_rn(x, x));
-    const float erf_abs = __fmaf_rn(-p, e, 1.0f);
-    const float erf_g = copysignf(erf_abs, g);
+    const float x = fminf(__fmul_rn(fabsf(g), 0.70710678f), 4.3f);
+    float p = -5.95750535e-05f;
+    p = __fmaf_rn(p, x, 0.000253331062f);
+    p = __fmaf_rn(p, x, 0.00176583871f);
+    p = __fmaf_rn(p, x, -0.0206223261f);
+    p = __fmaf_rn(p, x, 0.103378408f);
+    p = __fmaf_rn(p, x, 0.636503041f);
+    p = __fmaf_rn(p, x, 1.12838686f);
+    const float e = exp32_nonpos(-__fmul_rn(p, x));
+    const float erf_g = copysignf(__fsub_rn(1.0f, e), g);
     return __fmul_rn(__fmul_rn(0.5f, g), __fadd_rn(1.0f, erf_g));
 }
 
@@ -1076,12 +1075,8 @@ static int run_gemm(GemmArgs& g, int tile_index, hipStream_t st) {
             return MQ_ERR_HIP;
         }
         char name[96];
-        if (MODE)
-            snprintf(name, sizeof name, "mq::gemm_kernel<%s, %d, %d, %d, %d, %d, %d, %d, %s, %d>", I8 ? "true" : "false",
-                     BITS, WGM, WGN, TM, TN, S, KS, BF ? "true" : "false", MODE);
-        else
-            snprintf(name, sizeof name, "mq::gemm_kernel<%s, %d, %d, %d, %d, %d, %d, %d, %s>", I8 ? "true" : "false",
-                     BITS, WGM, WGN, TM, TN, S, KS, BF ? "true" : "false");
+        snprintf(name, sizeof name, "mq::gemm_kernel<%s, %d, %d, %d, %d, %d, %d, %d, %s, %d>", I8 ? "true" : "false",
+                 BITS, WGM, WGN, TM, TN, S, KS, BF ? "true" : "false", MODE);
         prof_name_slot(slot, name);
         prepared = true;
     }
