@@ -266,3 +266,41 @@ def linear_a8_codes(qx, act, wcodes, w_scale, w_zp, w_signed=False, bias=None, w
                                      _p(np.ascontiguousarray(w_zp, np.int32)), _p(bias), _p(y), C.c_long(N), _p(acc)),
            "linear_a8_codes")
     return y, acc
+
+
+def conv3x3_w_only(x, codes, w_scale, w_zp, bias=None, dtype=F16, pix=None):
+    """x [B,H,W,Cin] 16-bit; codes [N, 9*Cin] with k = (r*3+s)*Cin + c.  Returns y uint16 [B*H*W or len(pix), N]."""
+    x = _u16(x)
+    bias = _u16(bias)
+    codes = np.ascontiguousarray(codes, np.uint8)
+    B, H, W, Cin = x.shape
+    N = codes.shape[0]
+    assert codes.shape[1] == 9 * Cin
+    pix, npx = _rows(pix)
+    R = npx if pix is not None else B * H * W
+    y = np.empty((R, N), np.uint16)
+    _check(lib().orc_conv3x3_w_only(_p(x), B, H, W, Cin, _p(codes), N, _p(np.ascontiguousarray(w_scale, np.float32)),
+                                    _p(np.ascontiguousarray(w_zp, np.int32)), _p(bias), dtype, _p(y), _p(pix),
+                                    C.c_long(npx)), "conv3x3_w_only")
+    return y
+
+
+def conv3x3_a8(x, wcodes, w_scale, w_zp, w_signed=False, act=None, bias=None, pix=None, want_acc=True):
+    """Returns (y uint16, acc int32 or None, (act_scale, act_zp))."""
+    x = _u16(x)
+    bias = _u16(bias)
+    wcodes = np.ascontiguousarray(wcodes, np.uint8)
+    B, H, W, Cin = x.shape
+    N = wcodes.shape[0]
+    assert wcodes.shape[1] == 9 * Cin
+    pix, npx = _rows(pix)
+    R = npx if pix is not None else B * H * W
+    y = np.empty((R, N), np.uint16)
+    acc = np.empty((R, N), np.int32) if want_acc else None
+    s = C.c_float(0.0 if act is None else act[0])
+    z = C.c_int32(0 if act is None else act[1])
+    _check(lib().orc_conv3x3_a8(_p(x), B, H, W, Cin, _p(wcodes), N, int(w_signed),
+                                _p(np.ascontiguousarray(w_scale, np.float32)), _p(np.ascontiguousarray(w_zp, np.int32)),
+                                int(act is None), C.byref(s), C.byref(z), _p(bias), _p(y), _p(acc), _p(pix),
+                                C.c_long(npx)), "conv3x3_a8")
+    return y, acc, (np.float32(s.value), int(z.value))

@@ -575,3 +575,104 @@ int orc_linear_a8_codes(const uint8_t* qx, long M, int K, float act_scale, int32
     }
     return overflow ? ORC_OVERFLOW : ORC_OK;
 }
+
+/* ------------------------------------------------------------------------- */
+/* 3x3 convolution, stride 1, zero padding 1 (the paper quantises "all the   */
+/* linear and convolution layers", Sec. 4.1 "Quantization Scheme": weights   */
+/* per output channel -- here over the whole 3x3xCin filter --, activations  */
+/* per tensor).  Layouts: x [B,H,W,Cin] and y [B,H,W,N] channels-last; the   */
+/* weight codes [N, 9*Cin] with k = (r*3 + s)*Cin + c for filter row r,      */
+/* filter column s, input channel c.                                         */
+/*     y[b,i,j,n] = sum_{r,s,c} x[b,i+r-1,j+s-1,c] * w[n,r,s,c] + bias[n]    */
+/* with x = 0 outside the image.  `pix` selects output pixels (flat index    */
+/* (b*H + i)*W + j), NULL = all.                                             */
+/* ------------------------------------------------------------------------- */
+int orc_conv3x3_w_only(const uint16_t* x, int B, int H, int W, int Cin, const uint8_t* codes, int N,
+                       const float* w_scale, const int32_t* w_zp, const uint16_t* bias, int dtype, uint16_t* y,
+                       const int64_t* pix, long npix) {
+    if (!x || !codes || !w_scale || !w_zp || !y || B <= 0 || H <= 0 || W <= 0 || Cin <= 0 || N <= 0) return ORC_BAD_ARG;
+    long M = (long)B * H * W;
+    long R = pix ? npix : M;
+    if (R <= 0) return ORC_BAD_ARG;
+    int K = 9 * Cin;
+    double* what = (double*)malloc((size_t)N * K * sizeof(double));
+    if (!what) return ORC_BAD_ARG;
+    for (int n = 0; n < N; ++n)
+        for (int k = 0; k < K; ++k)
+            what[(size_t)n * K + k] = (double)w_scale[n] * (double)((int)codes[(size_t)n * K + k] - w_zp[n]);
+#pragma omp parallel for schedule(static)
+    for (long rr = 0; rr < R; ++rr) {
+        long m = pix ? pix[rr] : rr;
+        int j = (int)(m % W), i = (int)((m / W) % H), b = (int)(m / ((long)W * H));
+        double* col = (double*)calloc((size_t)K, sizeof(double));
+        for (int r = 0; r < 3; ++r)
+            for (int s = 0; s < 3; ++s) {
+                int ii = i + r - 1, jj = j + s - 1;
+                if (ii < 0 || ii >= H || jj < 0 || jj >= W) continue;
+                const uint16_t* px = x + (((long)b * H + ii) * W + jj) * Cin;
+                for (int c = 0; c < Cin; ++c) col[(r * 3 + s) * Cin + c] = in16(px[c], dtype);
+            }
+        for (int n = 0; n < N; ++n) {
+            const double* wr = what + (size_t)n * K;
+            double acc = 0.0;
+            for (int k = 0; k < K; ++k) acc += col[k] * wr[k];
+            if (bias) acc += in16(bias[n], dtype);
+            y[rr * (long)N + n] = out16(acc, dtype);
+        }
+        free(col);
+    }
+    free(what);
+    return ORC_OK;
+}
+
+/* The same convolution on 8-bit activations: one (scale, zero point) for the whole input tensor, dynamic (min-max
+ * over all of x) or given; a padded position holds the value 0, whose code is the zero point, so it adds nothing:
+ *     ACC[m,n] = sum over in-image (r,s), c of (qx - z_x)(qw - z_w[n]);  y = fp16(ACC * s_x * s_w[n] + bias[n]). */
+int orc_conv3x3_a8(const uint16_t* x, int B, int H, int W, int Cin, const uint8_t* wcodes, int N, int w_signed,
+                   const float* w_scale, const int32_t* w_zp, int dynamic, float* act_scale, int32_t* act_zp,
+                   const uint16_t* bias, uint16_t* y, int32_t* acc_out, const int64_t* pix, long npix) {
+    if (!x || !wcodes || !w_scale || !w_zp || !act_scale || !act_zp || !y || B <= 0 || H <= 0 || W <= 0 || Cin <= 0 ||
+        N <= 0)
+        return ORC_BAD_ARG;
+    long M = (long)B * H * W;
+    long R = pix ? npix : M;
+    if (R <= 0) return ORC_BAD_ARG;
+    if (dynamic) {
+        int rc = orc_act_params(x, M, Cin, Cin, ORC_F16, act_scale, act_zp);
+        if (rc) return rc;
+    }
+    float sx = *act_scale;
+    int32_t zx = *act_zp;
+    if (!(sx > 0.0f) || zx < 0 || zx > 255) return ORC_BAD_ARG;
+    float inv = 1.0f / sx;
+    int K = 9 * Cin;
+    int overflow = 0;
+#pragma omp parallel for schedule(static) reduction(| : overflow)
+    for (long rr = 0; rr < R; ++rr) {
+        long m = pix ? pix[rr] : rr;
+        int j = (int)(m % W), i = (int)((m / W) % H), b = (int)(m / ((long)W * H));
+        int* col = (int*)calloc((size_t)K, sizeof(int));
+        for (int r = 0; r < 3; ++r)
+            for (int s = 0; s < 3; ++s) {
+                int ii = i + r - 1, jj = j + s - 1;
+                if (ii < 0 || ii >= H || jj < 0 || jj >= W) continue;
+                const uint16_t* px = x + (((long)b * H + ii) * W + jj) * Cin;
+                for (int c = 0; c < Cin; ++c)
+                    col[(r * 3 + s) * Cin + c] = asym_code((float)half_to_double(px[c]), inv, zx, 255) - zx;
+            }
+        for (int n = 0; n < N; ++n) {
+            int64_t acc = 0;
+            for (int k = 0; k < K; ++k) {
+                int q = w_signed ? (int)(int8_t)wcodes[(size_t)n * K + k] : (int)wcodes[(size_t)n * K + k];
+                acc += (int64_t)col[k] * (q - w_zp[n]);
+            }
+            if (acc > INT32_MAX || acc < INT32_MIN) overflow |= 1;
+            if (acc_out) acc_out[rr * (long)N + n] = (int32_t)acc;
+            double v = (double)acc * ((double)sx * (double)w_scale[n]);
+            if (bias) v += half_to_double(bias[n]);
+            y[rr * (long)N + n] = double_to_half(v);
+        }
+        free(col);
+    }
+    return overflow ? ORC_OVERFLOW : ORC_OK;
+}

@@ -554,3 +554,62 @@ def test_geglu_requant_against_float64_rederivation(orc, bits, symmetric):
     rows = [0, 5, 20]
     q2, _, _ = orc.linear_a8_geglu(x, c, s, z, out_act, w_signed=symmetric, bias=b, rows=rows, act=act)
     assert np.array_equal(q2, q[rows])
+
+
+# ----------------------------------------------------------------------------------------------- 3x3 convolution
+
+def _conv_case(orc, seed, B, H, W, Cin, N, bits, symmetric=False):
+    rng = np.random.default_rng(seed)
+    x = rng.normal(0, 1, (B, H, W, Cin)).astype(np.float16)
+    w = rng.normal(0, 0.05, (N, 3, 3, Cin)).astype(np.float16)      # [N, r, s, c]
+    b = rng.normal(0, 0.1, N).astype(np.float16)
+    c, s, z = orc.quantize_weights(w.reshape(N, 9 * Cin), bits, symmetric=symmetric)
+    return x, w, b, c, s, z
+
+
+@pytest.mark.parametrize("bits", (4, 8))
+def test_conv_w_only_equals_a_library_convolution_on_dequantised_weights(orc, bits):
+    import torch
+    B, H, W, Cin, N = 2, 5, 7, 8, 6
+    x, w, b, c, s, z = _conv_case(orc, 80 + bits, B, H, W, Cin, N, bits)
+    y = orc.conv3x3_w_only(x, c, s, z, b).view(np.float16).reshape(B, H, W, N)
+    what = (s.astype(np.float64)[:, None] * (c.astype(np.float64) - z[:, None])).reshape(N, 3, 3, Cin)
+    ref = torch.nn.functional.conv2d(torch.from_numpy(x.astype(np.float64)).permute(0, 3, 1, 2),
+                                     torch.from_numpy(what).permute(0, 3, 1, 2), torch.from_numpy(b.astype(np.float64)),
+                                     padding=1).permute(0, 2, 3, 1).numpy()
+    ref16 = ref.astype(np.float16)
+    ulp = np.abs(y.astype(np.float64) - ref16.astype(np.float64)) / np.spacing(np.abs(ref16)).astype(np.float64)
+    assert ulp.max() <= 1.0 and (ulp > 0).mean() < 0.01
+    pix = [0, 6, 17, B * H * W - 1]
+    assert np.array_equal(orc.conv3x3_w_only(x, c, s, z, b, pix=pix).view(np.float16), y.reshape(-1, N)[pix])
+
+
+def test_conv_on_a_single_pixel_is_the_linear_of_the_centre_tap(orc):
+    x, w, b, c, s, z = _conv_case(orc, 83, 3, 1, 1, 64, 10, 4)
+    y = orc.conv3x3_w_only(x, c, s, z, b)
+    centre = c.reshape(10, 9, 64)[:, 4, :]
+    assert np.array_equal(y, orc.linear_w_only(x.reshape(3, 64), centre, s, z, b))
+    ya, acca, act = orc.conv3x3_a8(x, c, s, z, bias=b)
+    yl, accl, actl = orc.linear_a8(x.reshape(3, 64), centre, s, z, bias=b)
+    assert act == actl and np.array_equal(acca, accl) and np.array_equal(ya, yl)
+
+
+@pytest.mark.parametrize("bits,symmetric", [(4, False), (8, True)])
+def test_conv_a8_integer_accumulators_by_library_convolution(orc, bits, symmetric):
+    """ACC equals an integer convolution of (codes - zero point) with zero padding: padding adds nothing because the
+    value 0 has the zero point as its code."""
+    import torch
+    B, H, W, Cin, N = 2, 4, 6, 16, 5
+    x, w, b, c, s, z = _conv_case(orc, 84 + bits, B, H, W, Cin, N, bits, symmetric)
+    y, acc, act = orc.conv3x3_a8(x, c, s, z, w_signed=symmetric, bias=b)
+    qx = orc.act_quantize(x.reshape(-1, Cin), *act).reshape(B, H, W, Cin).astype(np.int64) - act[1]
+    qw = (c.view(np.int8).astype(np.int64) if symmetric else c.astype(np.int64)) - z[:, None]
+    ref = torch.nn.functional.conv2d(torch.from_numpy(qx).permute(0, 3, 1, 2).double(),
+                                     torch.from_numpy(qw.reshape(N, 3, 3, Cin)).permute(0, 3, 1, 2).double(),
+                                     padding=1).permute(0, 2, 3, 1).numpy().reshape(-1, N)
+    assert np.array_equal(acc.astype(np.int64), np.rint(ref).astype(np.int64))
+    assert act == orc.act_params(x.reshape(-1, Cin))
+    yf = acc.astype(np.float64) * (np.float64(act[0]) * s.astype(np.float64))[None, :] + b.astype(np.float64)[None, :]
+    assert np.array_equal(y.view(np.float16), yf.astype(np.float16))
+    # a shifted filter index or a transposed tap order would break this: the input is not symmetric under either
+    assert not np.array_equal(acc, orc.conv3x3_a8(x[:, :, ::-1].copy(), c, s, z, w_signed=symmetric, act=act)[1])
