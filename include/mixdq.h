@@ -216,6 +216,35 @@ int mq_qlinear_a8_codes(const int8_t* a8, int M, int K, int lda, const float* ac
                         const int32_t* w_zp, const int32_t* w_colsum, const void* bias, void* y, int ldy,
                         int32_t* acc_debug, void* stream);
 
+/* ------------------------------------------------------------------------------------------------
+ * 3x3 convolution, stride 1, zero padding 1 (paper Sec. 4.1 "Quantization Scheme": the convolution layers are
+ * quantised like the linear ones, weights per output channel over the whole 3x3xCin filter, activations per tensor).
+ * Channels-last tensors: x [B,H,W,Cin], y [B,H,W,N] (contiguous).  The weight matrix handed to mq_quantize_weights /
+ * mq_pack_weights is [N, 9*Cin] with k = (r*3 + s)*Cin + c (filter row r, filter column s, input channel c), in
+ * MQ_LAYOUT_KERNEL.  No im2col copy is made: the GEMM's activation loads address the taps themselves, and taps
+ * outside the image read as zero.  Cin % 64 == 0, N % 8 == 0, B*H*W*Cin*2 < 2^31.
+ * ---------------------------------------------------------------------------------------------- */
+
+/* Weight-only convolution, W{2,3,4,8}A16:  y = fp16( sum_{r,s,c} x[b,i+r-1,j+s-1,c] * scale[n]*(code - zp[n]) + bias[n] ). */
+int mq_conv3x3_w_only(const void* x, int B, int H, int W, int Cin, const void* packed, int N, int bits, int layout,
+                      const float* w_scale, const int32_t* w_zp, const void* bias, void* y, void* stream);
+
+/* Sums of the weight codes per filter tap, [9][N] int32 (tap = r*3 + s): needed by mq_conv3x3_a8 for the output
+ * pixels whose filter reaches outside the image.  codes [N, 9*Cin] as handed to mq_pack_weights. */
+int mq_conv_tap_sums(const uint8_t* codes, int N, int Cin, int bits, int codes_signed, int32_t* tapsum, void* stream);
+
+size_t mq_conv3x3_a8_workspace_bytes(int B, int H, int W, int Cin);
+
+/* W8A8 / W4A8 convolution: activations quantised per tensor (dynamic min/max over x, or the given static
+ * parameters) as in mq_qlinear_w8a8; a padded position holds the value 0, whose code is the zero point:
+ *     ACC[m,n] = sum over in-image (r,s), c of (qx - z_x)(qw - z_w[n]),   y = fp16(ACC * s_x * s_w[n] + bias[n]).
+ * acc_debug nullable [B*H*W, N] int32. */
+int mq_conv3x3_a8(const void* x, int B, int H, int W, int Cin, const void* packed, int N, int w_bits, int layout,
+                  int w_signed, const float* w_scale, const int32_t* w_zp, const int32_t* w_colsum,
+                  const int32_t* w_tapsum, const float* act_scale, const int32_t* act_zp, const void* bias, void* y,
+                  int32_t* acc_debug, float* act_scale_out, int32_t* act_zp_out, void* ws, size_t ws_bytes,
+                  void* stream);
+
 size_t mq_bos_aware_kv_proj_workspace_bytes(int B, int T, int K);
 
 /* BOS-aware cross-attention K/V projection (paper Sec. 3.1).  ctx is the text embedding [B,T,K] fp16,

@@ -23,7 +23,8 @@ _ERRORS = {
 EXPORTS = ("mq_version", "mq_last_hip_error", "mq_tune_force_tile", "mq_tune_force_splits", "mq_prof_enable", "mq_prof_num_slots", "mq_prof_read",
            "mq_prof_reset", "mq_prof_phase_buffer", "mq_prof_filter", "mq_prof_bracket_overhead_us", "mq_prof_copy", "mq_quantize_weights", "mq_packed_bytes", "mq_pack_weights",
            "mq_unpack_weights", "mq_qlinear_w_only", "mq_qlinear_a8_workspace_bytes", "mq_qlinear_w8a8",
-           "mq_qlinear_w4a8", "mq_a8_row_bytes", "mq_qlinear_a8_geglu", "mq_qlinear_a8_codes",
+           "mq_qlinear_w4a8", "mq_a8_row_bytes", "mq_qlinear_a8_geglu", "mq_qlinear_a8_codes", "mq_conv3x3_w_only",
+           "mq_conv_tap_sums", "mq_conv3x3_a8_workspace_bytes", "mq_conv3x3_a8",
            "mq_bos_aware_kv_proj_workspace_bytes", "mq_bos_aware_kv_proj")
 
 
@@ -47,7 +48,7 @@ def load():
         if not os.path.exists(_LIB_PATH):
             raise RuntimeError(f"{_LIB_PATH} is missing: run `python -c 'import __graft_entry__ as g; g.build()'`")
         _lib = C.CDLL(_LIB_PATH)
-        for name in ("mq_a8_row_bytes", "mq_packed_bytes", "mq_qlinear_a8_workspace_bytes", "mq_bos_aware_kv_proj_workspace_bytes"):
+        for name in ("mq_a8_row_bytes", "mq_conv3x3_a8_workspace_bytes", "mq_packed_bytes", "mq_qlinear_a8_workspace_bytes", "mq_bos_aware_kv_proj_workspace_bytes"):
             getattr(_lib, name).restype = C.c_size_t
         _lib.mq_prof_bracket_overhead_us.restype = C.c_double
     return _lib
@@ -298,6 +299,48 @@ def plan_qlinear_a8_codes(a8, K, act, w: PackedWeight, bias, out):
             int(w.signed), _ptr(w.scale), _ptr(w.zp), _ptr(w.colsum), _ptr(bias), _ptr(out), out.stride(0), null,
             _stream())
     return _planned(load().mq_qlinear_a8_codes, "mq_qlinear_a8_codes", args, (a8, act, w, bias, out))
+
+
+def conv_tap_sums(codes: torch.Tensor, Cin: int, bits: int, codes_signed: bool = False) -> torch.Tensor:
+    """codes uint8 [N, 9*Cin] -> int32 [9, N]."""
+    N = codes.shape[0]
+    assert codes.is_cuda and codes.dtype == torch.uint8 and codes.is_contiguous() and codes.shape[1] == 9 * Cin
+    out = torch.empty((9, N), dtype=torch.int32, device=codes.device)
+    _check(load().mq_conv_tap_sums(_ptr(codes), N, Cin, bits, int(codes_signed), _ptr(out), _stream()), "mq_conv_tap_sums")
+    return out
+
+
+def conv3x3_w_only(x: torch.Tensor, w: PackedWeight, bias=None, out=None) -> torch.Tensor:
+    """x [B,H,W,Cin] fp16 channels-last contiguous; w packed from the [N, 9*Cin] matrix.  Returns y [B,H,W,N]."""
+    assert x.is_cuda and x.dim() == 4 and x.is_contiguous() and x.dtype == torch.float16
+    B, H, W, Cin = x.shape
+    assert w.K == 9 * Cin
+    y = out if out is not None else torch.empty((B, H, W, w.N), dtype=torch.float16, device=x.device)
+    _check(load().mq_conv3x3_w_only(_ptr(x), B, H, W, Cin, _ptr(w.packed), w.N, w.bits, w.layout, _ptr(w.scale),
+                                    _ptr(w.zp), _ptr(bias), _ptr(y), _stream()), "mq_conv3x3_w_only")
+    return y
+
+
+def conv3x3_a8_workspace_bytes(B: int, H: int, W: int, Cin: int) -> int:
+    return int(load().mq_conv3x3_a8_workspace_bytes(B, H, W, Cin))
+
+
+def conv3x3_a8(x, w: PackedWeight, tapsum, act=None, bias=None, out=None, ws=None, want_acc=False, want_act=False):
+    """Returns (y [B,H,W,N], acc int32 [B*H*W,N] or None, (act_scale, act_zp) or None)."""
+    assert x.is_cuda and x.dim() == 4 and x.is_contiguous() and x.dtype == torch.float16
+    B, H, W, Cin = x.shape
+    assert w.K == 9 * Cin
+    y = out if out is not None else torch.empty((B, H, W, w.N), dtype=torch.float16, device=x.device)
+    acc = torch.empty((B * H * W, w.N), dtype=torch.int32, device=x.device) if want_acc else None
+    ws = _workspace(conv3x3_a8_workspace_bytes(B, H, W, Cin), x.device, ws)
+    a_s, a_z = (None, None) if act is None else act
+    so = torch.empty(1, dtype=torch.float32, device=x.device) if want_act else None
+    zo = torch.empty(1, dtype=torch.int32, device=x.device) if want_act else None
+    _check(load().mq_conv3x3_a8(_ptr(x), B, H, W, Cin, _ptr(w.packed), w.N, w.bits, w.layout, int(w.signed),
+                                _ptr(w.scale), _ptr(w.zp), _ptr(w.colsum), _ptr(tapsum), _ptr(a_s), _ptr(a_z), _ptr(bias),
+                                _ptr(y), _ptr(acc), _ptr(so), _ptr(zo), _ptr(ws), C.c_size_t(ws.numel()), _stream()),
+           "mq_conv3x3_a8")
+    return y, acc, ((so, zo) if want_act else None)
 
 
 def bos_aware_kv_proj_workspace_bytes(B: int, T: int, K: int) -> int:

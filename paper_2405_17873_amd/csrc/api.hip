@@ -201,6 +201,67 @@ int mq_qlinear_a8_codes(const int8_t* a8, int M, int K, int lda, const float* ac
                                 w_colsum, bias, y, ldy, acc_debug, (hipStream_t)stream);
 }
 
+static int check_conv_common(const void* x, int B, int H, int W, int Cin, const void* packed, int N, int layout,
+                             const float* w_scale, const int32_t* w_zp, const void* bias, const void* y) {
+    if (!x || !packed || !w_scale || !w_zp || !y) return MQ_ERR_BAD_ARG;
+    if (B <= 0 || H <= 0 || W <= 0 || Cin <= 0 || N <= 0) return MQ_ERR_BAD_SHAPE;
+    if (layout != MQ_LAYOUT_KERNEL) return MQ_ERR_UNSUPPORTED_LAYOUT;
+    if (Cin % 64 != 0 || N % 8 != 0) return MQ_ERR_BAD_SHAPE;
+    const long M = (long)B * H * W;
+    // lane offsets into X, Y rows and the packed weights are 32-bit
+    if (M * Cin * 2 >= (1L << 31) || M >= (1L << 31) / 4 || (long)(N + 31) * 9 * Cin >= (1L << 31)) return MQ_ERR_BAD_SHAPE;
+    if (!aligned(x, 16) || !aligned(packed, 16) || !aligned(w_scale, 16) || !aligned(w_zp, 16) || !aligned(y, 16) ||
+        (bias && !aligned(bias, 8)))
+        return MQ_ERR_BAD_ARG;
+    return MQ_OK;
+}
+
+int mq_conv3x3_w_only(const void* x, int B, int H, int W, int Cin, const void* packed, int N, int bits, int layout,
+                      const float* w_scale, const int32_t* w_zp, const void* bias, void* y, void* stream) {
+    if (!bits_ok(bits)) return MQ_ERR_UNSUPPORTED_BITS;
+    int rc = check_conv_common(x, B, H, W, Cin, packed, N, layout, w_scale, w_zp, bias, y);
+    if (rc) return rc;
+    return launch_conv3x3_w_only(x, B, H, W, Cin, packed, N, bits, w_scale, w_zp, bias, y, (hipStream_t)stream);
+}
+
+int mq_conv_tap_sums(const uint8_t* codes, int N, int Cin, int bits, int codes_signed, int32_t* tapsum, void* stream) {
+    if (!codes || !tapsum) return MQ_ERR_BAD_ARG;
+    if (N <= 0 || Cin <= 0) return MQ_ERR_BAD_SHAPE;
+    if (!bits_ok(bits)) return MQ_ERR_UNSUPPORTED_BITS;
+    if (codes_signed && bits != 8) return MQ_ERR_BAD_ARG;
+    return launch_tap_sums(codes, N, Cin, bits, codes_signed ? 1 : 0, tapsum, (hipStream_t)stream);
+}
+
+size_t mq_conv3x3_a8_workspace_bytes(int B, int H, int W, int Cin) {
+    if (B <= 0 || H <= 0 || W <= 0 || Cin <= 0) return 0;
+    return A8Workspace::bytes((long)B * H * W, Cin);
+}
+
+int mq_conv3x3_a8(const void* x, int B, int H, int W, int Cin, const void* packed, int N, int w_bits, int layout,
+                  int w_signed, const float* w_scale, const int32_t* w_zp, const int32_t* w_colsum,
+                  const int32_t* w_tapsum, const float* act_scale, const int32_t* act_zp, const void* bias, void* y,
+                  int32_t* acc_debug, float* act_scale_out, int32_t* act_zp_out, void* ws, size_t ws_bytes,
+                  void* stream) {
+    if (w_bits != 4 && w_bits != 8) return MQ_ERR_UNSUPPORTED_BITS;
+    int rc = check_conv_common(x, B, H, W, Cin, packed, N, layout, w_scale, w_zp, bias, y);
+    if (rc) return rc;
+    if (!w_colsum || !w_tapsum || !ws) return MQ_ERR_BAD_ARG;
+    if ((act_scale == nullptr) != (act_zp == nullptr)) return MQ_ERR_BAD_ARG;
+    if (!aligned(w_colsum, 16) || !aligned(w_tapsum, 4) || !aligned(ws, 256) || (acc_debug && !aligned(acc_debug, 16)))
+        return MQ_ERR_BAD_ARG;
+    if ((long)255 * 255 * 9 * Cin >= (1L << 31)) return MQ_ERR_OVERFLOW_RISK;
+    const long M = (long)B * H * W;
+    if (M >= (1L << 31) / 8) return MQ_ERR_BAD_SHAPE;
+    if (ws_bytes < A8Workspace::bytes(M, Cin)) return MQ_ERR_WORKSPACE_TOO_SMALL;
+    hipStream_t st = (hipStream_t)stream;
+    A8Workspace w(ws, M, Cin);
+    rc = launch_act_quant(x, (int)M, Cin, Cin, RowMap{0, 0, 0}, act_scale, act_zp, w.a8, w.rowsum, w.params, w.partials,
+                          act_scale_out, act_zp_out, st);
+    if (rc) return rc;
+    return launch_conv3x3_a8(w.a8, w.params, B, H, W, Cin, packed, N, w_bits, w_signed ? 1 : 0, w_scale, w_zp, w_colsum,
+                             w_tapsum, bias, y, acc_debug, st);
+}
+
 size_t mq_qlinear_a8_workspace_bytes(int M, int K) {
     if (M <= 0 || K <= 0) return 0;
     return A8Workspace::bytes(M, K);

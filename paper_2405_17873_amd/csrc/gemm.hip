@@ -338,6 +338,12 @@ struct GemmArgs {
     // MODE 2 (activations arrive as int8 codes): their parameters; row sums are taken inside the main loop
     const float* act_scale_p;
     const int32_t* act_zp_p;
+    // MODE 3 / 4 (3x3 convolution, stride 1, zero padding 1, channels-last): a is the [B*H*W, Cin] activation tensor
+    // (a_row_bytes per pixel), K = 9 * Cin, row m is output pixel m; the k order is (filter row, filter column, c)
+    int conv_h, conv_w;
+    int conv_cpt;            // 64-channel chunks per filter tap (Cin / 64)
+    uint32_t conv_cpt_inv;   // ceil(2^32 / conv_cpt) for conv_cpt > 1
+    const int32_t* w_tapsum; // MODE 4: [9][N] sums of the weight codes per filter tap
 };
 
 // Workgroup id -> tile.  Consecutive workgroup ids land on different XCDs (8 of them, each with its own L2),
@@ -393,8 +399,10 @@ __global__ __launch_bounds__(WGM* WGN* KS * 64,
                              (TM * TN <= 8 && GemmPlan<I8, BITS, WGM, WGN, TM, TN, S, KS>::LDS_BYTES <= 80 * 1024) ? 2 : 1)
 void gemm_kernel(const GemmArgs g) {
     static_assert(!(I8 && BF), "the int8 path writes fp16");
-    constexpr bool GEGLU = MODE == 1, RS_INLINE = MODE == 2;
-    static_assert(MODE == 0 || (I8 && KS == 1), "the feed-forward pair is an int8 path without in-workgroup k split");
+    constexpr bool GEGLU = MODE == 1, RS_INLINE = MODE == 2 || MODE == 4, CONV = MODE == 3 || MODE == 4;
+    static_assert(MODE == 0 || KS == 1, "the special modes have no in-workgroup k split");
+    static_assert((MODE != 1 && MODE != 2 && MODE != 4) || I8, "int8 modes");
+    static_assert(MODE != 3 || !I8, "MODE 3 is the weight-only convolution");
     static_assert(!GEGLU || TN == 2, "value tile and gate tile per wave");
     using P = GemmPlan<I8, BITS, WGM, WGN, TM, TN, S, KS>;
     constexpr int NW = P::NW, NT = P::NT, BM = P::BM, BN = P::BN, CH = P::CH;
@@ -437,6 +445,20 @@ void gemm_kernel(const GemmArgs g) {
     // Rows past M get an offset past the end of the buffer and therefore read as zero.
     int a_voff[P::DMA_A];
     uint32_t a_lds[P::DMA_A];
+    int a_half[CONV ? P::DMA_A : 1];
+    uint32_t a_taps[CONV ? P::DMA_A : 1];
+    // convolution: which of the 9 filter taps (bit r * 3 + s) of output pixel m read inside the image
+    auto tap_mask = [&](int m) -> uint32_t {
+        if (m >= g.M) return 0u;
+        const int j = m % g.conv_w, i = (m / g.conv_w) % g.conv_h;
+        const uint32_t rows = (i > 0 ? 1u : 0u) | 2u | (i + 1 < g.conv_h ? 4u : 0u);
+        const uint32_t cols = (j > 0 ? 1u : 0u) | 2u | (j + 1 < g.conv_w ? 4u : 0u);
+        uint32_t mk = 0;
+#pragma unroll
+        for (int r = 0; r < 3; ++r)
+            if (rows >> r & 1u) mk |= cols << (3 * r);
+        return mk;
+    };
 #pragma unroll
     for (int i = 0; i < P::DMA_A; ++i) {
         const int j = i * NW + wv;
@@ -445,6 +467,14 @@ void gemm_kernel(const GemmArgs g) {
         const int piece = (lane & 7) ^ swz(row);
         a_voff[i] = m0 + row < g.M ? (int)((long)(m0 + row) * g.a_row_bytes + sub * 128 + piece * 16) : OOB;
         a_lds[i] = __builtin_amdgcn_readfirstlane((uint32_t)(sub * P::SUB_BYTES + row0 * 128));
+        if constexpr (CONV) {
+            // row = output pixel; the lane's 16 bytes of a stage lie in one 64-channel chunk (int8: piece / 4 says
+            // which of the stage's two), i.e. in one filter tap: per stage it adds that tap's pixel offset, or
+            // reads nothing (zero) where the tap falls outside the image
+            a_voff[i] = (int)((long)(m0 + row) * g.a_row_bytes) + (I8 ? (piece & 3) : piece) * 16;
+            a_half[i] = I8 ? piece >> 2 : 0;
+            a_taps[i] = tap_mask(m0 + row);
+        }
     }
     // weight loads: instruction jj of a sub-stage copies piece jj % PCS of weight tile jj / PCS (tile = channel group,
     // chunk)
@@ -516,9 +546,29 @@ void gemm_kernel(const GemmArgs g) {
         const int soff_a = __builtin_amdgcn_readfirstlane((kt0 + stage) * KS * 128);
         const int soff_b = __builtin_amdgcn_readfirstlane((kt0 + stage) * KS * CH * TILE_B);
         const uint32_t sb = lds_base + buf * STAGE_BYTES;
+        if constexpr (CONV) {
+            // the stage's 64-channel chunks -> (filter tap, chunk inside the tap) -> byte offset from the output pixel
+            int tap[CH], delta[CH];
 #pragma unroll
-        for (int i = 0; i < P::DMA_A; ++i)
-            dma_to_lds_b128(ra, __builtin_amdgcn_readfirstlane(sb + a_lds[i]), a_voff[i], soff_a);
+            for (int h = 0; h < CH; ++h) {
+                const uint32_t ci = (uint32_t)(kt0 + stage) * CH + h;
+                const uint32_t t = g.conv_cpt > 1 ? __umulhi(ci, g.conv_cpt_inv) : ci;
+                const int cc = (int)(ci - t * g.conv_cpt);
+                tap[h] = ci < (uint32_t)KC ? (int)t : 31;  // past the end of K (int8 padding of the last stage): no tap
+                delta[h] = (((int)t / 3 - 1) * g.conv_w + ((int)t % 3 - 1)) * (int)g.a_row_bytes + cc * (I8 ? 64 : 128);
+            }
+#pragma unroll
+            for (int i = 0; i < P::DMA_A; ++i) {
+                const int t = CH == 2 && a_half[i] ? tap[CH - 1] : tap[0];
+                const int d = CH == 2 && a_half[i] ? delta[CH - 1] : delta[0];
+                const int voff = (a_taps[i] >> t) & 1u ? a_voff[i] + d : OOB;
+                dma_to_lds_b128(ra, __builtin_amdgcn_readfirstlane(sb + a_lds[i]), voff, 0);
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < P::DMA_A; ++i)
+                dma_to_lds_b128(ra, __builtin_amdgcn_readfirstlane(sb + a_lds[i]), a_voff[i], soff_a);
+        }
 #pragma unroll
         for (int i = 0; i < P::DMA_B; ++i)
             dma_to_lds_b128(rb, __builtin_amdgcn_readfirstlane(b_lds[i] == 0xFFFFFFFFu ? lds_base + P::SINK : sb + b_lds[i]),
@@ -890,10 +940,30 @@ void gemm_kernel(const GemmArgs g) {
                     const int4v dw = *(const int4v*)(ch_dw + cl);
                     const int4v cn = *(const int4v*)(ch_cn + cl);
                     int4v a;
+                    int4v border = {0, 0, 0, 0};
+                    if constexpr (MODE == 4) {
+                        // Convolution: a filter tap outside the image reads zero bytes, which stand for the code
+                        // 128, not for the value 0 (code z_x).  The constant term cn counts every tap; take back
+                        // dx * sum_c (q_w - z_w) of the taps this pixel does not have.
+                        const uint32_t have = tap_mask(mt0 + l31);
+                        if (have != 0x1FFu) {
+                            const int n_real = n0 + cl;
+                            const int dxv = 128 - *g.act_zp_p;
+                            const int cin = g.conv_cpt * 64;
+                            for (int t = 0; t < 9; ++t) {
+                                if (have >> t & 1u) continue;
+#pragma unroll
+                                for (int r = 0; r < 4; ++r) {
+                                    const int n = n_real + r < g.N ? n_real + r : g.N - 1;
+                                    border[r] += dxv * (g.w_tapsum[t * g.N + n] - cin * (g.w_off - dw[r]));
+                                }
+                            }
+                        }
+                    }
 #pragma unroll
                     for (int r = 0; r < 4; ++r) {
                         // |dw| <= 255 and |rowsum| <= 128 * K < 2^23: a 24-bit multiply (full rate) is exact
-                        a[r] = acc[tm][tn][4 * q + r] + __mul24(dw[r], rsum[tm]) + cn[r];
+                        a[r] = acc[tm][tn][4 * q + r] + __mul24(dw[r], rsum[tm]) + cn[r] - border[r];
                         o[r] = (_Float16)((float)a[r] * mul[r] + add[r]);
                     }
                     if (g.acc_debug) {
@@ -1080,7 +1150,8 @@ static int run_gemm(GemmArgs& g, int tile_index, hipStream_t st) {
         prof_name_slot(slot, name);
         prepared = true;
     }
-    const double abytes = I8 ? 1.0 * g.M * g.K + 4.0 * g.M : 2.0 * g.M * g.K;
+    const double kin = MODE >= 3 ? g.K / 9.0 : (double)g.K;  // a convolution reads each activation once, not nine times
+    const double abytes = I8 ? 1.0 * g.M * kin + (MODE == 0 ? 4.0 * g.M : 0.0) : 2.0 * g.M * kin;
     const double ybytes = MODE == 1 ? 1.0 * g.M * g.ld8 + (g.y ? 1.0 * g.M * g.N : 0.0) : 2.0 * g.M * g.N;
     ProfScope prof(st, slot, 2.0 * g.M * g.N * g.K,
                    abytes + (double)g.N * g.K * BITS / 8 + (I8 ? 14.0 : 10.0) * g.N + ybytes);
@@ -1252,6 +1323,82 @@ int launch_gemm_a8_codes(const int8_t* a8, long lda, const float* act_scale, con
             case 1: return run_gemm<true, 8, 2, 2, 2, 2, 1, 80 * 1024, 4, false, 2>(g, 1, st);
             default: return run_gemm<true, 8, 2, 2, 1, 1, 1, 80 * 1024, 8, false, 2>(g, 2, st);
         }
+    }
+    return MQ_ERR_UNSUPPORTED_BITS;
+}
+
+
+// 3x3 convolution, stride 1, zero padding 1, channels-last (MODE 3 weight-only, MODE 4 int8 activations).
+static void conv_args(GemmArgs& g, int B, int H, int W, int Cin, long pix_bytes) {
+    g.a_row_bytes = pix_bytes;
+    g.a_bytes = (uint32_t)((long)B * H * W * pix_bytes);
+    g.M = B * H * W;
+    g.K = 9 * Cin;
+    g.conv_h = H;
+    g.conv_w = W;
+    g.conv_cpt = Cin / 64;
+    g.conv_cpt_inv = g.conv_cpt > 1 ? (uint32_t)(((1ull << 32) + g.conv_cpt - 1) / g.conv_cpt) : 0u;
+}
+
+template <int BITS>
+static int dispatch_conv_w_only(GemmArgs& g, hipStream_t st) {
+    constexpr bool WIDE = BITS == 16;
+    int t = pick_tile(g.M, g.N, g.K, WIDE);
+    t = t >= 3 ? t - 2 : t;
+    switch (t) {
+        case 0: return run_gemm<false, BITS, 1, 4, 4, 2, 1, 80 * 1024, 4, false, 3>(g, 0, st);
+        case 1: return run_gemm<false, BITS, 2, 2, 2, 2, 1, 80 * 1024, 4, false, 3>(g, 1, st);
+        default: return run_gemm<false, BITS, 2, 2, 1, 1, 1, 80 * 1024, 8, false, 3>(g, 2, st);
+    }
+}
+
+int launch_conv3x3_w_only(const void* x, int B, int H, int W, int Cin, const void* packed, int N, int bits,
+                          const float* w_scale, const int32_t* w_zp, const void* bias, void* y, hipStream_t st) {
+    GemmArgs g{};
+    g.a = x;
+    conv_args(g, B, H, W, Cin, (long)Cin * 2);
+    g.packed = (const uint8_t*)packed;
+    g.packed_bytes = (uint32_t)((long)((N + 31) / 32) * (g.K / 64) * 256 * bits);
+    g.N = N;
+    g.k_stages = g.K / 64;
+    g.w_scale = w_scale; g.w_zp = w_zp; g.bias = (const uint16_t*)bias;
+    g.y = (uint16_t*)y; g.ldy = N;
+    switch (bits) {
+        case 2: return dispatch_conv_w_only<2>(g, st);
+        case 3: return dispatch_conv_w_only<3>(g, st);
+        case 4: return dispatch_conv_w_only<4>(g, st);
+        case 8: return dispatch_conv_w_only<8>(g, st);
+    }
+    return MQ_ERR_UNSUPPORTED_BITS;
+}
+
+int launch_conv3x3_a8(const int8_t* a8, const ActParams* params, int B, int H, int W, int Cin, const void* packed, int N,
+                      int w_bits, int w_signed, const float* w_scale, const int32_t* w_zp, const int32_t* w_colsum,
+                      const int32_t* w_tapsum, const void* bias, void* y, int32_t* acc_debug, hipStream_t st) {
+    GemmArgs g{};
+    g.a = a8;
+    conv_args(g, B, H, W, Cin, (long)(Cin + 127) / 128 * 128);
+    g.packed = (const uint8_t*)packed;
+    g.packed_bytes = (uint32_t)((long)((N + 31) / 32) * (g.K / 64) * 256 * w_bits);
+    g.N = N;
+    g.k_stages = (g.K + 127) / 128;
+    g.w_scale = w_scale; g.w_zp = w_zp; g.bias = (const uint16_t*)bias;
+    g.y = (uint16_t*)y; g.ldy = N;
+    g.w_colsum = w_colsum; g.w_tapsum = w_tapsum;
+    g.act_scale_p = &params->scale; g.act_zp_p = &params->zp;
+    g.acc_debug = acc_debug;
+    // (not the large tile: no registers to spare for the row sums and the tap masks)
+    int t = pick_tile(g.M, N, g.K, true);
+    t = t >= 3 ? t - 2 : t;
+    if (w_bits == 4) {
+        g.w_off = 0;
+        if (t <= 1) return run_gemm<true, 4, 2, 2, 2, 2, 1, 80 * 1024, 4, false, 4>(g, 1, st);
+        return run_gemm<true, 4, 2, 2, 1, 1, 1, 80 * 1024, 8, false, 4>(g, 2, st);
+    }
+    if (w_bits == 8) {
+        g.w_off = w_signed ? 0 : 128;
+        if (t <= 1) return run_gemm<true, 8, 2, 2, 2, 2, 1, 80 * 1024, 4, false, 4>(g, 1, st);
+        return run_gemm<true, 8, 2, 2, 1, 1, 1, 80 * 1024, 8, false, 4>(g, 2, st);
     }
     return MQ_ERR_UNSUPPORTED_BITS;
 }

@@ -95,14 +95,21 @@ int launch_gemm_a8_codes(const int8_t* a8, long lda, const float* act_scale, con
                          const int32_t* w_colsum, const void* bias, void* y, int ldy, int32_t* acc_debug,
                          hipStream_t st);
 
+int launch_conv3x3_w_only(const void* x, int B, int H, int W, int Cin, const void* packed, int N, int bits,
+                          const float* w_scale, const int32_t* w_zp, const void* bias, void* y, hipStream_t st);
+int launch_conv3x3_a8(const int8_t* a8, const ActParams* params, int B, int H, int W, int Cin, const void* packed, int N,
+                      int w_bits, int w_signed, const float* w_scale, const int32_t* w_zp, const int32_t* w_colsum,
+                      const int32_t* w_tapsum, const void* bias, void* y, int32_t* acc_debug, hipStream_t st);
+int launch_tap_sums(const uint8_t* codes, int N, int Cin, int bits, int codes_signed, int32_t* tapsum, hipStream_t st);
+
 void set_force_tile(int t);
 void set_force_splits(int n);
 void set_phase_buffer(long long* p, long workgroups);
 
 // ---- optional per-kernel event timing (prof.hip) ----
-enum { PROF_GEMM_TILES = 5, PROF_GEMM_BITS = 5, PROF_GEMM_FAMILIES = 5, PROF_ACT_MINMAX = PROF_GEMM_FAMILIES * PROF_GEMM_BITS * PROF_GEMM_TILES, PROF_ACT_QUANTIZE, PROF_BOS_ROWS };
+enum { PROF_GEMM_TILES = 5, PROF_GEMM_BITS = 5, PROF_GEMM_FAMILIES = 7, PROF_ACT_MINMAX = PROF_GEMM_FAMILIES * PROF_GEMM_BITS * PROF_GEMM_TILES, PROF_ACT_QUANTIZE, PROF_BOS_ROWS };
 int prof_num_slots();
-int prof_gemm_slot(int family /*0 weight-only fp16, 1 int8, 2 weight-only bf16, 3 int8 gated projection, 4 int8 on codes*/,
+int prof_gemm_slot(int family /*0 weight-only fp16, 1 int8, 2 weight-only bf16, 3 int8 gated projection, 4 int8 on codes, 5 weight-only convolution, 6 int8 convolution*/,
                    int bits, int tile);
 bool prof_enabled();
 bool prof_wants(int slot);

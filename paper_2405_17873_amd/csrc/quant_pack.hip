@@ -287,6 +287,30 @@ __global__ __launch_bounds__(256) void code_colsum_kernel(const uint8_t* __restr
     if ((threadIdx.x & 63) == 0) colsum[n] = s;
 }
 
+// Sums of the weight codes per filter tap of a 3x3 convolution (codes [N, 9 * Cin], k = tap * Cin + c): one wave per
+// (channel, tap).  The int8 convolution needs them for output pixels whose filter reaches outside the image.
+__global__ __launch_bounds__(256) void tap_sums_kernel(const uint8_t* __restrict__ codes, int N, int Cin, int bits,
+                                                       int codes_signed, int32_t* __restrict__ tapsum) {
+    const int idx = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (idx >= N * 9) return;
+    const int n = idx / 9, t = idx % 9;
+    const unsigned mask = (1u << bits) - 1u;
+    int s = 0;
+    for (int c = threadIdx.x & 63; c < Cin; c += 64) {
+        const uint8_t q = codes[(size_t)n * 9 * Cin + (size_t)t * Cin + c];
+        s += codes_signed ? (int)(int8_t)q : (int)(q & mask);
+    }
+    s = wave_reduce(s, [](int a, int b) { return a + b; });
+    if ((threadIdx.x & 63) == 0) tapsum[(size_t)t * N + n] = s;
+}
+
+int launch_tap_sums(const uint8_t* codes, int N, int Cin, int bits, int codes_signed, int32_t* tapsum, hipStream_t st) {
+    hipLaunchKernelGGL(tap_sums_kernel, dim3((N * 9 + 3) / 4), dim3(256), 0, st, codes, N, Cin, bits, codes_signed,
+                       tapsum);
+    MQ_HIP_CHECK_LAUNCH();
+    return MQ_OK;
+}
+
 int launch_quantize_weights(const void* w, int N, int K, int bits, int symmetric, int dtype, uint8_t* codes,
                             float* scale, int32_t* zp, hipStream_t st) {
     hipLaunchKernelGGL(quantize_weights_kernel, dim3(N), dim3(256), 0, st, (const uint16_t*)w, N, K, bits, symmetric,

@@ -519,6 +519,69 @@ def test_feed_forward_pair_end_to_end(mq, orc):
     assert_close16(host(y), ry, "feed-forward pair")
 
 
+# ----------------------------------------------------------------------------------------------- 3x3 convolution
+
+CONV_SHAPES = [  # B, H, W, Cin, N
+    (2, 8, 8, 64, 32),
+    (1, 16, 16, 128, 64),
+    (2, 5, 7, 64, 40),      # ragged rows, N not a multiple of the tile
+    (1, 32, 32, 320, 320),  # five 64-channel chunks per tap: an int8 stage straddles two taps, the last one is half padding
+    (3, 1, 1, 64, 8),       # a single pixel: only the centre tap is inside
+    (1, 1, 9, 192, 24),
+    (1, 9, 1, 64, 16),
+]
+
+
+def conv_weight(mq, orc, seed, N, Cin, bits, sym=False):
+    w = si.weights_f16(seed, f"cv/w{N}x{Cin}", N, 9 * Cin, 0.05)   # [N, (r, s, c)]
+    pw, oc, os_, oz = make_weight(mq, orc, w, bits, sym)
+    c, _, _ = mq.quantize_weights(dev(w), bits, sym)
+    tapsum = mq.conv_tap_sums(c, Cin, bits, sym)
+    q = oc.view(np.int8).astype(np.int64) if sym else oc.astype(np.int64)
+    assert np.array_equal(host(tapsum), q.reshape(N, 9, Cin).sum(2).T)
+    return pw, oc, os_, oz, tapsum
+
+
+@pytest.mark.parametrize("bits", ALL_BITS)
+@pytest.mark.parametrize("tile", (-1, 0, 1, 2))
+def test_conv_w_only(mq, orc, bits, tile):
+    mq.tune_force_tile(tile)
+    try:
+        for (B, H, W, Cin, N) in CONV_SHAPES:
+            if tile == 0 and B * H * W * N > 200000:
+                continue
+            x = si.activations_f16(71, f"cv/x{B}x{H}x{W}x{Cin}", B * H * W, Cin).reshape(B, H, W, Cin)
+            b = si.bias_f16(71, f"cv/b{N}", N)
+            pw, oc, os_, oz, _ = conv_weight(mq, orc, 71, N, Cin, bits)
+            y = mq.conv3x3_w_only(dev(x), pw, dev(b))
+            assert_close16(host(y).reshape(-1, N), orc.conv3x3_w_only(x, oc, os_, oz, b),
+                           f"conv w{bits} tile{tile} {B}x{H}x{W}x{Cin}->{N}")
+    finally:
+        mq.tune_force_tile(-1)
+
+
+@pytest.mark.parametrize("bits,sym", [(4, False), (8, True), (8, False)])
+@pytest.mark.parametrize("tile", (-1, 1, 2))
+def test_conv_a8(mq, orc, bits, sym, tile):
+    """Integer accumulators bit-exact, also on the border pixels (taps outside the image) and with a zero point far
+    from 128 (static parameters)."""
+    mq.tune_force_tile(tile)
+    try:
+        for (B, H, W, Cin, N) in CONV_SHAPES:
+            x = si.activations_f16(72, f"cv8/x{B}x{H}x{W}x{Cin}", B * H * W, Cin, outlier_prob=0.01).reshape(B, H, W, Cin)
+            b = si.bias_f16(72, f"cv8/b{N}", N)
+            pw, oc, os_, oz, tapsum = conv_weight(mq, orc, 72, N, Cin, bits, sym)
+            for act in (None, (np.float32(0.05), 31)):
+                d_act = None if act is None else (dev(np.array([act[0]], np.float32)), dev(np.array([act[1]], np.int32)))
+                y, acc, got = mq.conv3x3_a8(dev(x), pw, tapsum, act=d_act, bias=dev(b), want_acc=True, want_act=True)
+                ry, racc, ract = orc.conv3x3_a8(x, oc, os_, oz, w_signed=sym, act=act, bias=b)
+                assert host(got[0])[0] == ract[0] and host(got[1])[0] == ract[1]
+                assert np.array_equal(host(acc), racc), f"conv acc b{bits} tile{tile} {B}x{H}x{W}x{Cin}->{N}"
+                assert_close16(host(y).reshape(-1, N), ry, f"conv a8 b{bits} tile{tile}")
+    finally:
+        mq.tune_force_tile(-1)
+
+
 # ----------------------------------------------------------------------------------------------- BOS-aware K/V
 
 @pytest.mark.parametrize("N", (640, 1280))
