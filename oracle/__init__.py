@@ -304,3 +304,21 @@ def conv3x3_a8(x, wcodes, w_scale, w_zp, w_signed=False, act=None, bias=None, pi
                                 int(act is None), C.byref(s), C.byref(z), _p(bias), _p(y), _p(acc), _p(pix),
                                 C.c_long(npx)), "conv3x3_a8")
     return y, acc, (np.float32(s.value), int(z.value))
+
+
+def linear_w_only_geglu(x, codes, w_scale, w_zp, bias=None, dtype=F16, rows=None):
+    """Weight-only gated projection; codes [2H,K].  Returns h uint16 [R,H]."""
+    x = _u16(x)
+    bias = _u16(bias)
+    codes = np.ascontiguousarray(codes, np.uint8)
+    M, K = x.shape
+    H = codes.shape[0] // 2
+    assert codes.shape == (2 * H, K)
+    rows, nr = _rows(rows)
+    R = nr if rows is not None else M
+    h = np.empty((R, H), np.uint16)
+    _check(lib().orc_linear_w_only_geglu(_p(x), C.c_long(M), K, C.c_long(K), _p(codes), H,
+                                         _p(np.ascontiguousarray(w_scale, np.float32)),
+                                         _p(np.ascontiguousarray(w_zp, np.int32)), _p(bias), dtype, _p(h), _p(rows),
+                                         C.c_long(nr)), "linear_w_only_geglu")
+    return h

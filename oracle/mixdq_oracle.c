@@ -676,3 +676,33 @@ int orc_conv3x3_a8(const uint16_t* x, int B, int H, int W, int Cin, const uint8_
     }
     return overflow ? ORC_OVERFLOW : ORC_OK;
 }
+
+/* Weight-only gated projection: h[m,j] = lin[m,j] * gelu(lin[m,H+j]) with lin the weight-only linear over the 2H rows
+ * of the weight matrix (first half value, second half gate), everything in fp64 with the library erf, one rounding to
+ * the 16-bit output. */
+int orc_linear_w_only_geglu(const uint16_t* x, long M, int K, long ldx, const uint8_t* codes, int H,
+                            const float* w_scale, const int32_t* w_zp, const uint16_t* bias, int dtype, uint16_t* h16,
+                            const int64_t* rows, long nrows) {
+    if (!x || !codes || !w_scale || !w_zp || !h16 || M <= 0 || K <= 0 || H <= 0 || ldx < K) return ORC_BAD_ARG;
+    long R = rows ? nrows : M;
+    if (R <= 0) return ORC_BAD_ARG;
+    int N = 2 * H;
+#pragma omp parallel for schedule(static)
+    for (long r = 0; r < R; ++r) {
+        long m = rows ? rows[r] : r;
+        double* lin = (double*)malloc((size_t)N * sizeof(double));
+        for (int n = 0; n < N; ++n) {
+            double acc = 0.0;
+            for (int k = 0; k < K; ++k)
+                acc += in16(x[m * ldx + k], dtype) * ((double)w_scale[n] * (double)((int)codes[(size_t)n * K + k] - w_zp[n]));
+            if (bias) acc += in16(bias[n], dtype);
+            lin[n] = acc;
+        }
+        for (int j = 0; j < H; ++j) {
+            double g = lin[H + j];
+            h16[r * (long)H + j] = out16(lin[j] * (0.5 * g * (1.0 + erf(g / sqrt(2.0)))), dtype);
+        }
+        free(lin);
+    }
+    return ORC_OK;
+}

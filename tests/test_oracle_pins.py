@@ -613,3 +613,21 @@ def test_conv_a8_integer_accumulators_by_library_convolution(orc, bits, symmetri
     assert np.array_equal(y.view(np.float16), yf.astype(np.float16))
     # a shifted filter index or a transposed tap order would break this: the input is not symmetric under either
     assert not np.array_equal(acc, orc.conv3x3_a8(x[:, :, ::-1].copy(), c, s, z, w_signed=symmetric, act=act)[1])
+
+
+def test_w_only_geglu_is_value_times_gelu_of_gate(orc):
+    """From the pinned weight-only linear: first half value, second half gate, exact GELU, one rounding."""
+    import math
+    x, w, b, c, s, z = _random_quantised_layer(orc, 91, 17, 128, 48, 4)
+    H = 24
+    h = orc.linear_w_only_geglu(x, c, s, z, b).view(np.float16).astype(np.float64)
+    what = s.astype(np.float64)[:, None] * (c.astype(np.float64) - z[:, None])
+    lin = x.astype(np.float64) @ what.T + b.astype(np.float64)
+    erf = np.vectorize(math.erf)
+    ref = lin[:, :H] * 0.5 * lin[:, H:] * (1.0 + erf(lin[:, H:] / math.sqrt(2.0)))
+    ref16 = ref.astype(np.float16)
+    ulp = np.abs(h - ref16.astype(np.float64)) / np.maximum(np.spacing(np.abs(ref16)).astype(np.float64), 2.0 ** -24)
+    assert ulp.max() <= 1.0 and (ulp > 0).mean() < 0.02
+    swapped = lin[:, H:] * 0.5 * lin[:, :H] * (1.0 + erf(lin[:, :H] / math.sqrt(2.0)))
+    assert np.abs(h - swapped).max() > 0.05   # value and gate are not interchangeable
+    assert np.array_equal(orc.linear_w_only_geglu(x, c, s, z, b, rows=[3, 16]).view(np.float16).astype(np.float64), h[[3, 16]])
