@@ -208,6 +208,13 @@ int mq_qlinear_a8_geglu(const void* x, int M, int K, int ldx, const void* packed
                         const int32_t* out_zp, int8_t* a8_out, void* h16_out, int ldh, float* act_scale_out,
                         int32_t* act_zp_out, void* ws, size_t ws_bytes, void* stream);
 
+/* The gated projection on the weight-only path, W{2,3,4,8}A16, fp16 in and out:
+ *     h[m,j] = fp16( lin[m,j] * gelu(lin[m,H+j]) ),  lin = X . dequant(W)^T + bias over the 2H weight rows
+ * (fp32 accumulation, the same fp32 gelu as above).  h [M,H] row stride ldh (ldh % 8 == 0).  H % 32 == 0. */
+int mq_qlinear_w_only_geglu(const void* x, int M, int K, int ldx, const void* packed, int H, int bits, int layout,
+                            const float* w_scale, const int32_t* w_zp, const void* bias, void* h, int ldh,
+                            void* stream);
+
 /* W8A8 / W4A8 linear on activations that arrive as codes in the A8 layout (row stride lda bytes) together with
  * their parameters (device pointers act_scale, act_zp): ACC and Y as in mq_qlinear_w8a8.  The row sums of the
  * codes, which the zero-point correction needs, are taken inside the GEMM; no workspace. */

@@ -23,7 +23,7 @@ _ERRORS = {
 EXPORTS = ("mq_version", "mq_last_hip_error", "mq_tune_force_tile", "mq_tune_force_splits", "mq_prof_enable", "mq_prof_num_slots", "mq_prof_read",
            "mq_prof_reset", "mq_prof_phase_buffer", "mq_prof_filter", "mq_prof_bracket_overhead_us", "mq_prof_copy", "mq_quantize_weights", "mq_packed_bytes", "mq_pack_weights",
            "mq_unpack_weights", "mq_qlinear_w_only", "mq_qlinear_a8_workspace_bytes", "mq_qlinear_w8a8",
-           "mq_qlinear_w4a8", "mq_a8_row_bytes", "mq_qlinear_a8_geglu", "mq_qlinear_a8_codes", "mq_conv3x3_w_only",
+           "mq_qlinear_w4a8", "mq_a8_row_bytes", "mq_qlinear_a8_geglu", "mq_qlinear_w_only_geglu", "mq_qlinear_a8_codes", "mq_conv3x3_w_only",
            "mq_conv_tap_sums", "mq_conv3x3_a8_workspace_bytes", "mq_conv3x3_a8",
            "mq_bos_aware_kv_proj_workspace_bytes", "mq_bos_aware_kv_proj")
 
@@ -267,6 +267,18 @@ def qlinear_a8_geglu(x, w: PackedWeight, out_act, act=None, bias=None, ws=None, 
                                       _ptr(out_act[0]), _ptr(out_act[1]), _ptr(a8), _ptr(h16), H, _ptr(so), _ptr(zo),
                                       _ptr(ws), C.c_size_t(ws.numel()), _stream()), "mq_qlinear_a8_geglu")
     return a8, h16, ((so, zo) if want_act else None)
+
+
+def qlinear_w_only_geglu(x, w: PackedWeight, bias=None, out=None):
+    """Weight-only gated projection: w has 2H rows; returns value * gelu(gate) as fp16 [M,H]."""
+    assert x.is_cuda and x.dim() == 2 and x.stride(1) == 1 and x.dtype == torch.float16
+    M, K = x.shape
+    H = w.N // 2
+    h = out if out is not None else torch.empty((M, H), dtype=torch.float16, device=x.device)
+    _check(load().mq_qlinear_w_only_geglu(_ptr(x), M, K, x.stride(0), _ptr(w.packed), H, w.bits, w.layout, _ptr(w.scale),
+                                          _ptr(w.zp), _ptr(bias), _ptr(h), h.stride(0), _stream()),
+           "mq_qlinear_w_only_geglu")
+    return h
 
 
 def qlinear_a8_codes(a8, K: int, act, w: PackedWeight, bias=None, out=None, want_acc=False):

@@ -181,6 +181,17 @@ int mq_qlinear_a8_geglu(const void* x, int M, int K, int ldx, const void* packed
                                 w_colsum, bias, out_scale, out_zp, a8_out, h16_out, ldh, st);
 }
 
+int mq_qlinear_w_only_geglu(const void* x, int M, int K, int ldx, const void* packed, int H, int bits, int layout,
+                            const float* w_scale, const int32_t* w_zp, const void* bias, void* h, int ldh,
+                            void* stream) {
+    if (!bits_ok(bits)) return MQ_ERR_UNSUPPORTED_BITS;
+    if (H <= 0 || H % 32 != 0 || H > (1 << 29)) return MQ_ERR_BAD_SHAPE;
+    int rc = check_linear_common(x, M, K, ldx, packed, 2 * H, layout, w_scale, w_zp, bias, h, 2 * H);
+    if (rc) return rc;
+    if (ldh < H || ldh % 8 != 0) return MQ_ERR_BAD_SHAPE;
+    return launch_gemm_w_only_geglu(x, M, K, ldx, packed, H, bits, w_scale, w_zp, bias, h, ldh, (hipStream_t)stream);
+}
+
 int mq_qlinear_a8_codes(const int8_t* a8, int M, int K, int lda, const float* act_scale, const int32_t* act_zp,
                         const void* packed, int N, int w_bits, int layout, int w_signed, const float* w_scale,
                         const int32_t* w_zp, const int32_t* w_colsum, const void* bias, void* y, int ldy,

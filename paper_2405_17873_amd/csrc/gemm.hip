@@ -401,7 +401,7 @@ void gemm_kernel(const GemmArgs g) {
     static_assert(!(I8 && BF), "the int8 path writes fp16");
     constexpr bool GEGLU = MODE == 1, RS_INLINE = MODE == 2 || MODE == 4, CONV = MODE == 3 || MODE == 4;
     static_assert(MODE == 0 || KS == 1, "the special modes have no in-workgroup k split");
-    static_assert((MODE != 1 && MODE != 2 && MODE != 4) || I8, "int8 modes");
+    static_assert((MODE != 2 && MODE != 4) || I8, "int8 modes");
     static_assert(MODE != 3 || !I8, "MODE 3 is the weight-only convolution");
     static_assert(!GEGLU || TN == 2, "value tile and gate tile per wave");
     using P = GemmPlan<I8, BITS, WGM, WGN, TM, TN, S, KS>;
@@ -859,8 +859,8 @@ void gemm_kernel(const GemmArgs g) {
         // A lane holds four consecutive columns of one row; the lane 32 further on holds the other four of the same
         // group of 8, so the two swap their packed words and each keeps one of the group's two output words.
         // Rows are staged through LDS (32 rows x 32 bytes per wave) and leave as 16-byte pieces.
-        const float inv_o = __fdiv_rn(1.0f, *g.out_scale_p);
-        const float zf_o = (float)*g.out_zp_p;
+        const float inv_o = I8 ? __fdiv_rn(1.0f, *g.out_scale_p) : 0.0f;
+        const float zf_o = I8 ? (float)*g.out_zp_p : 0.0f;
         static_assert(P::NWG * 3072 <= S * STAGE_BYTES, "epilogue staging must fit the LDS stages");
         uint8_t* ep8 = lds + wvg * 3072;
         uint8_t* ep16 = ep8 + 1024;
@@ -873,32 +873,46 @@ void gemm_kernel(const GemmArgs g) {
                 const int cl_v = (wn * TN) * 32 + 8 * q + 4 * kb, cl_g = cl_v + 32;
                 const float4v mul_v = *(const float4v*)(ch_mul + cl_v), add_v = *(const float4v*)(ch_add + cl_v);
                 const float4v mul_g = *(const float4v*)(ch_mul + cl_g), add_g = *(const float4v*)(ch_add + cl_g);
-                const int4v dw_v = *(const int4v*)(ch_dw + cl_v), cn_v = *(const int4v*)(ch_cn + cl_v);
-                const int4v dw_g = *(const int4v*)(ch_dw + cl_g), cn_g = *(const int4v*)(ch_cn + cl_g);
+                int4v dw_v = {0, 0, 0, 0}, cn_v = dw_v, dw_g = dw_v, cn_g = dw_v;
+                if constexpr (I8) {
+                    dw_v = *(const int4v*)(ch_dw + cl_v), cn_v = *(const int4v*)(ch_cn + cl_v);
+                    dw_g = *(const int4v*)(ch_dw + cl_g), cn_g = *(const int4v*)(ch_cn + cl_g);
+                }
                 uint32_t word = 0;
                 half4 hh;
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
-                    const int av = acc[tm][0][4 * q + r] + __mul24(dw_v[r], rsum[tm]) + cn_v[r];
-                    const int ag = acc[tm][1][4 * q + r] + __mul24(dw_g[r], rsum[tm]) + cn_g[r];
-                    const float lv = __fmaf_rn((float)av, mul_v[r], add_v[r]);
-                    const float lg = __fmaf_rn((float)ag, mul_g[r], add_g[r]);
+                    float lv, lg;
+                    if constexpr (I8) {
+                        const int av = acc[tm][0][4 * q + r] + __mul24(dw_v[r], rsum[tm]) + cn_v[r];
+                        const int ag = acc[tm][1][4 * q + r] + __mul24(dw_g[r], rsum[tm]) + cn_g[r];
+                        lv = __fmaf_rn((float)av, mul_v[r], add_v[r]);
+                        lg = __fmaf_rn((float)ag, mul_g[r], add_g[r]);
+                    } else {
+                        lv = __fmaf_rn(acc[tm][0][4 * q + r], mul_v[r], add_v[r]);
+                        lg = __fmaf_rn(acc[tm][1][4 * q + r], mul_g[r], add_g[r]);
+                    }
                     const float h = __fmul_rn(lv, gelu32(lg));
-                    float t = __fadd_rn(rintf(__fmul_rn(h, inv_o)), zf_o);
-                    t = fminf(fmaxf(t, 0.0f), 255.0f);
-                    const int code = col0 + 8 * q + 4 * kb + r < H ? (int)t - 128 : 0;
-                    word |= ((uint32_t)code & 255u) << (8 * r);
-                    hh[r] = (_Float16)h;
+                    if constexpr (I8) {
+                        float t = __fadd_rn(rintf(__fmul_rn(h, inv_o)), zf_o);
+                        t = fminf(fmaxf(t, 0.0f), 255.0f);
+                        const int code = col0 + 8 * q + 4 * kb + r < H ? (int)t - 128 : 0;
+                        word |= ((uint32_t)code & 255u) << (8 * r);
+                    }
+                    if constexpr (BF)
+                        hh[r] = __builtin_bit_cast(_Float16, float_to_bf16_bits(h));
+                    else
+                        hh[r] = (_Float16)h;
                 }
                 const uint32_t other = (uint32_t)__shfl_xor((int)word, 32, 64);
                 const uint32_t lo = kb ? other : word, hi = kb ? word : other;  // columns 0..3 and 4..7 of the group
                 // v_perm_b32: selector bytes 0..3 pick bytes of the second source, 4..7 of the first
                 const uint32_t out = kb ? __builtin_amdgcn_perm(hi, lo, 0x07030602u) : __builtin_amdgcn_perm(hi, lo, 0x05010400u);
-                *(uint32_t*)(ep8 + l31 * 32 + q * 8 + kb * 4) = out;
+                if constexpr (I8) *(uint32_t*)(ep8 + l31 * 32 + q * 8 + kb * 4) = out;
                 if (g.y) *(half4*)(ep16 + l31 * 64 + q * 16 + kb * 8) = hh;
             }
             __builtin_amdgcn_wave_barrier();
-            {
+            if constexpr (I8) {
                 const int row = lane >> 1, half = lane & 1;
                 const uint4v v = *(const uint4v*)(ep8 + row * 32 + half * 16);
                 const int m = mt0 + row, col = col0 + half * 16;
@@ -1281,6 +1295,37 @@ int launch_gemm_a8_geglu(const int8_t* a8, const int32_t* rowsum, const ActParam
         g.w_off = w_signed ? 0 : 128;
         if (g_force_tile == 0) return run_gemm<true, 8, 1, 4, 4, 2, 1, 160 * 1024, 4, false, 1>(g, 0, st);
         return run_gemm<true, 8, 2, 2, 2, 2, 1, 80 * 1024, 4, false, 1>(g, 1, st);
+    }
+    return MQ_ERR_UNSUPPORTED_BITS;
+}
+
+template <int BITS>
+static int dispatch_w_only_geglu(GemmArgs& g, int H, hipStream_t st) {
+    const bool big = g_force_tile == 0 || (g_force_tile < 0 && (long)((g.M + 127) / 128) * ((H + 127) / 128) >= 512);
+    if (big) return run_gemm<false, BITS, 1, 4, 4, 2, 1, 80 * 1024, 4, false, 1>(g, 0, st);
+    return run_gemm<false, BITS, 2, 2, 2, 2, 1, 80 * 1024, 4, false, 1>(g, 1, st);
+}
+
+// Weight-only gated projection, fp16 out (MODE 1 on the fp16 path).
+int launch_gemm_w_only_geglu(const void* x, int M, int K, int ldx, const void* packed, int H, int bits,
+                             const float* w_scale, const int32_t* w_zp, const void* bias, void* h16, int ldh,
+                             hipStream_t st) {
+    GemmArgs g{};
+    g.a = x;
+    g.a_row_bytes = (long)ldx * 2;
+    g.a_bytes = (uint32_t)(((long)(M - 1) * ldx + K) * 2);
+    g.packed = (const uint8_t*)packed;
+    g.packed_bytes = (uint32_t)((long)((2 * H + 31) / 32) * (K / 64) * 256 * bits);
+    g.M = M; g.N = 2 * H; g.K = K;
+    g.k_stages = K / 64;
+    g.w_scale = w_scale; g.w_zp = w_zp; g.bias = (const uint16_t*)bias;
+    g.y = (uint16_t*)h16; g.ldy = ldh;
+    g.ld8 = H;  // no code output: the grid covers the H gated columns
+    switch (bits) {
+        case 2: return dispatch_w_only_geglu<2>(g, H, st);
+        case 3: return dispatch_w_only_geglu<3>(g, H, st);
+        case 4: return dispatch_w_only_geglu<4>(g, H, st);
+        case 8: return dispatch_w_only_geglu<8>(g, H, st);
     }
     return MQ_ERR_UNSUPPORTED_BITS;
 }

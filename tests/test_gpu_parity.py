@@ -499,6 +499,23 @@ def test_a8_linear_on_codes(mq, orc, bits, sym, tile):
         mq.tune_force_tile(-1)
 
 
+@pytest.mark.parametrize("bits", ALL_BITS)
+@pytest.mark.parametrize("tile", (-1, 0, 1))
+def test_w_only_geglu_projection(mq, orc, bits, tile):
+    mq.tune_force_tile(tile)
+    try:
+        for (M, K, H) in ((256, 320, 320), (77, 128, 32), (300, 640, 96)):
+            x = si.activations_f16(64, f"wg/x{M}x{K}", M, K)
+            w = si.weights_f16(64, f"wg/w{H}x{K}", 2 * H, K)
+            b = si.bias_f16(64, f"wg/b{H}", 2 * H)
+            pw, oc, os_, oz = make_weight(mq, orc, w, bits)
+            for bias in (b, None):
+                h = mq.qlinear_w_only_geglu(dev(x), pw, None if bias is None else dev(bias))
+                assert_close16(host(h), orc.linear_w_only_geglu(x, oc, os_, oz, bias), f"w_only geglu b{bits} tile{tile}")
+    finally:
+        mq.tune_force_tile(-1)
+
+
 def test_feed_forward_pair_end_to_end(mq, orc):
     """Gated projection (C -> 8C) into the output linear (4C -> C) with the activation kept in 8 bits in between: the
     second call consumes exactly what the first wrote; against the oracle run the same way."""
