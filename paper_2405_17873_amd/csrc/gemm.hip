@@ -1150,19 +1150,27 @@ static int run_gemm(GemmArgs& g, int tile_index, hipStream_t st) {
         g.splits = splits;
     g.phase_clk = (tiles * g.splits <= g_phase_cap) ? g_phase_clk : nullptr;
     auto kern = gemm_kernel<I8, BITS, WGM, WGN, TM, TN, S, KS, BF, MODE>;
-    static bool prepared = false;  // once per instantiation: allow more than 64 KB of dynamic LDS, name the slot
+    // Once per instantiation and device (callers may be on several host threads): allow more than 64 KB of dynamic
+    // LDS, name the profiling slot.
     const int slot = prof_gemm_slot(MODE ? 2 + MODE : (I8 ? 1 : (BF ? 2 : 0)), BITS, tile_index);
-    if (!prepared) {
-        if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, P::LDS_BYTES) !=
-            hipSuccess) {
-            set_hip_error((int)hipGetLastError());
-            return MQ_ERR_HIP;
+    static std::mutex prep_mutex;
+    static bool prepared[16] = {};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 16) dev = 0;
+    {
+        std::lock_guard<std::mutex> lock(prep_mutex);
+        if (!prepared[dev]) {
+            if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, P::LDS_BYTES) !=
+                hipSuccess) {
+                set_hip_error((int)hipGetLastError());
+                return MQ_ERR_HIP;
+            }
+            char name[96];
+            snprintf(name, sizeof name, "mq::gemm_kernel<%s, %d, %d, %d, %d, %d, %d, %d, %s, %d>",
+                     I8 ? "true" : "false", BITS, WGM, WGN, TM, TN, S, KS, BF ? "true" : "false", MODE);
+            prof_name_slot(slot, name);
+            prepared[dev] = true;
         }
-        char name[96];
-        snprintf(name, sizeof name, "mq::gemm_kernel<%s, %d, %d, %d, %d, %d, %d, %d, %s, %d>", I8 ? "true" : "false",
-                 BITS, WGM, WGN, TM, TN, S, KS, BF ? "true" : "false", MODE);
-        prof_name_slot(slot, name);
-        prepared = true;
     }
     const double kin = MODE >= 3 ? g.K / 9.0 : (double)g.K;  // a convolution reads each activation once, not nine times
     const double abytes = I8 ? 1.0 * g.M * kin + (MODE == 0 ? 4.0 * g.M : 0.0) : 2.0 * g.M * kin;
