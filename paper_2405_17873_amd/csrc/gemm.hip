@@ -1,23 +1,31 @@
 // MFMA GEMMs of the quantized-linear hot path for gfx950 (64-wide wavefronts, 32x32 MFMA tiles).
 //
-//   gemm_w_only : Y = X . dequant(Wq)^T      fp16 MFMA (v_mfma_f32_32x32x16_f16), fp32 accumulate
-//                 (paper App. C item 2: weight-only layers keep 16-bit floating-point compute)
-//   gemm_a8     : ACC = A8 . W8^T            int8 MFMA (v_mfma_i32_32x32x32_i8), int32 accumulate
+//   weight-only : Y = X . dequant(Wq)^T      fp16 / bf16 MFMA (v_mfma_f32_32x32x16_f16 / _bf16), fp32 accumulate
+//                 (paper App. C item 2: weight-only layers keep 16-bit floating-point compute; also the layers kept
+//                 at 16 bits, Sec. 4.2, whose weights pass unquantised)
+//   int8        : ACC = A8 . W8^T            int8 MFMA (v_mfma_i32_32x32x32_i8), int32 accumulate
 //                 (paper Sec. 4.3 / App. C item 4: integer GEMM for W8A8; 4-bit codes widened for W4A8)
+// and, on the same skeleton, selected by the kernel's MODE: the gated feed-forward projection whose epilogue emits
+// value * gelu(gate) as 8-bit codes or fp16, the int8 GEMM on activations that arrive as codes, and the 3x3
+// convolution (Sec. 4.1: convolutions are quantised like linears) by addressing the filter taps in the activation loads.
 //
 // Shared structure
-//   * One workgroup = WGM x WGN waves; each wave owns TM x TN MFMA tiles of 32x32.
+//   * One workgroup = WGM x WGN waves (x KS groups that split k); each wave owns TM x TN MFMA tiles of 32x32.
 //   * Both operands go HBM -> LDS directly (buffer loads with the LDS bit: no staging registers) through a
-//     pipeline of 2..4 LDS stages with hand-placed vmcnt waits and one barrier per stage.
+//     pipeline of 2..8 LDS stages with hand-placed vmcnt waits and one barrier per stage; the hand-over to the
+//     next stage sits in the middle of a stage, behind the MFMAs of its last two k-steps.
 //   * Activations: 128 bytes of K per row per stage, 16-byte pieces XOR-swizzled (on the global side of the
 //     copy) so that ds_read_b128 of 32 consecutive rows is conflict free.
 //   * Weights stay PACKED in LDS: the kernel layout stores, for every 32-channel x 64-k tile, the 64 lane
 //     chunks in lane order, so a tile is copied with one contiguous wave access and a lane later reads its own
 //     chunk with one conflict-free ds_read; codes are widened in registers, right before the MFMA.
 //   * The MFMA is issued with the weight fragment as the first operand: the 32x32 result then holds, per
-//     lane, 4 consecutive output channels of one activation row, i.e. an 8-byte fp16 store.
+//     lane, 4 consecutive output channels of one activation row; the epilogue transposes through LDS and stores
+//     16-byte row segments.
 //   * k-order inside a stage is permuted identically for both operands (a sum does not care), chosen so
 //     that every lane's global and LDS accesses are 16 bytes wide.
+//   * Few tiles and a long reduction: several workgroups per tile, partial sums through a scratch ring of the
+//     library, the last-arriving workgroup adds them in a fixed order (no waiting).
 #include <stdio.h>
 
 #include <mutex>
@@ -299,8 +307,8 @@ __device__ __forceinline__ float gelu32(float g) {
 //                                128 k per stage = two 64-k weight tiles.
 // A stage of the activation operand is BM rows x 128 bytes.  It is brought in by buffer loads that write LDS
 // directly (each lane 16 bytes, a wave instruction fills 8 rows), XOR-swizzled on the global side so that the
-// later ds_read_b128 of 32 consecutive rows is conflict free.  Two LDS stages; the loads of stage k+1 are in
-// flight while stage k is multiplied.
+// later ds_read_b128 of 32 consecutive rows is conflict free.  S LDS stages rotate; the loads of the next S-1 stages
+// are in flight while a stage is multiplied.
 // ---------------------------------------------------------------------------------------------
 struct GemmArgs {
     const void* a;        // X fp16 [M, lda] or int8 copy [M, Kp]
