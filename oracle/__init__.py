@@ -149,7 +149,7 @@ def _rows(rows):
     return rows, rows.size
 
 
-def linear_w_only(x, codes, w_scale, w_zp, bias=None, dtype=F16, rows=None):
+def linear_w_only(x, codes, w_scale, w_zp, bias=None, dtype=F16, rows=None, residual=None):
     """Returns y as uint16 bit patterns, [M,N] or [len(rows),N]."""
     x = _u16(x)
     bias = _u16(bias)
@@ -163,7 +163,7 @@ def linear_w_only(x, codes, w_scale, w_zp, bias=None, dtype=F16, rows=None):
     _check(lib().orc_linear_w_only(_p(x), C.c_long(M), K, C.c_long(K), _p(codes), N,
                                    _p(np.ascontiguousarray(w_scale, np.float32)),
                                    _p(np.ascontiguousarray(w_zp, np.int32)), _p(bias), dtype, _p(y), C.c_long(N),
-                                   _p(rows), C.c_long(nr)), "linear_w_only")
+                                   _p(rows), C.c_long(nr), _p(_u16(residual)), C.c_long(N)), "linear_w_only")
     return y
 
 
@@ -179,7 +179,8 @@ def linear_fp(x, w, bias=None, dtype=F16):
     return y
 
 
-def linear_a8(x, wcodes, w_scale, w_zp, w_signed=False, act=None, bias=None, rows=None, want_acc=True):
+def linear_a8(x, wcodes, w_scale, w_zp, w_signed=False, act=None, bias=None, rows=None, want_acc=True,
+              residual=None):
     """act=None: dynamic per-tensor min-max over all rows of x; else (scale, zp).
     Returns (y uint16, acc int32 or None, (act_scale, act_zp))."""
     x = _u16(x)
@@ -197,7 +198,8 @@ def linear_a8(x, wcodes, w_scale, w_zp, w_signed=False, act=None, bias=None, row
     _check(lib().orc_linear_a8(_p(x), C.c_long(M), K, C.c_long(K), _p(wcodes), N, int(w_signed),
                                _p(np.ascontiguousarray(w_scale, np.float32)),
                                _p(np.ascontiguousarray(w_zp, np.int32)), int(act is None), C.byref(s), C.byref(z),
-                               _p(bias), _p(y), C.c_long(N), _p(acc), _p(rows), C.c_long(nr)), "linear_a8")
+                               _p(bias), _p(y), C.c_long(N), _p(acc), _p(rows), C.c_long(nr), _p(_u16(residual)),
+                               C.c_long(N)), "linear_a8")
     return y, acc, (np.float32(s.value), int(z.value))
 
 
@@ -268,7 +270,7 @@ def linear_a8_codes(qx, act, wcodes, w_scale, w_zp, w_signed=False, bias=None, w
     return y, acc
 
 
-def conv3x3_w_only(x, codes, w_scale, w_zp, bias=None, dtype=F16, pix=None):
+def conv3x3_w_only(x, codes, w_scale, w_zp, bias=None, dtype=F16, pix=None, residual=None):
     """x [B,H,W,Cin] 16-bit; codes [N, 9*Cin] with k = (r*3+s)*Cin + c.  Returns y uint16 [B*H*W or len(pix), N]."""
     x = _u16(x)
     bias = _u16(bias)
@@ -281,11 +283,11 @@ def conv3x3_w_only(x, codes, w_scale, w_zp, bias=None, dtype=F16, pix=None):
     y = np.empty((R, N), np.uint16)
     _check(lib().orc_conv3x3_w_only(_p(x), B, H, W, Cin, _p(codes), N, _p(np.ascontiguousarray(w_scale, np.float32)),
                                     _p(np.ascontiguousarray(w_zp, np.int32)), _p(bias), dtype, _p(y), _p(pix),
-                                    C.c_long(npx)), "conv3x3_w_only")
+                                    C.c_long(npx), _p(_u16(residual))), "conv3x3_w_only")
     return y
 
 
-def conv3x3_a8(x, wcodes, w_scale, w_zp, w_signed=False, act=None, bias=None, pix=None, want_acc=True):
+def conv3x3_a8(x, wcodes, w_scale, w_zp, w_signed=False, act=None, bias=None, pix=None, want_acc=True, residual=None):
     """Returns (y uint16, acc int32 or None, (act_scale, act_zp))."""
     x = _u16(x)
     bias = _u16(bias)
@@ -302,7 +304,7 @@ def conv3x3_a8(x, wcodes, w_scale, w_zp, w_signed=False, act=None, bias=None, pi
     _check(lib().orc_conv3x3_a8(_p(x), B, H, W, Cin, _p(wcodes), N, int(w_signed),
                                 _p(np.ascontiguousarray(w_scale, np.float32)), _p(np.ascontiguousarray(w_zp, np.int32)),
                                 int(act is None), C.byref(s), C.byref(z), _p(bias), _p(y), _p(acc), _p(pix),
-                                C.c_long(npx)), "conv3x3_a8")
+                                C.c_long(npx), _p(_u16(residual))), "conv3x3_a8")
     return y, acc, (np.float32(s.value), int(z.value))
 
 

@@ -292,13 +292,20 @@ int orc_code_rowsum(const uint8_t* codes, int N, int K, int is_signed, int32_t* 
 /* ------------------------------------------------------------------------- */
 /* Linear layers.  rows == NULL: all M rows, y is [M, ldy].                   */
 /* rows != NULL: only the listed rows of x, y (and acc) are compact [nrows,.] */
+/* residual != NULL: a 16-bit [M, ldr] operand (indexed by the row of x, not */
+/* by the position in `rows`) added to the sum before its single rounding.   */
+/* It carries the skip connection of a block, and the first half of a layer  */
+/* whose channel-concatenated input [trunk | shortcut] is split into two     */
+/* layers with their own quantisation parameters (Sec. 4.1, "Quantization    */
+/* Scheme": the two parts have different ranges); the second call then adds  */
+/* the first call's output.                                                  */
 /* ------------------------------------------------------------------------- */
 
 /* Weight-only (App. C item 2: floating-point compute on dequantised weights):
  * w_hat[n,k] = s[n] * (q[n,k] - z[n]);  y[m,n] = round16( sum_k x[m,k] w_hat[n,k] + bias[n] ). */
 int orc_linear_w_only(const uint16_t* x, long M, int K, long ldx, const uint8_t* codes, int N,
                       const float* w_scale, const int32_t* w_zp, const uint16_t* bias, int dtype,
-                      uint16_t* y, long ldy, const int64_t* rows, long nrows) {
+                      uint16_t* y, long ldy, const int64_t* rows, long nrows, const uint16_t* residual, long ldr) {
     if (!x || !codes || !w_scale || !w_zp || !y || M <= 0 || K <= 0 || N <= 0 || ldx < K || ldy < N)
         return ORC_BAD_ARG;
     long R = rows ? nrows : M;
@@ -318,6 +325,7 @@ int orc_linear_w_only(const uint16_t* x, long M, int K, long ldx, const uint8_t*
             double acc = 0.0;
             for (int k = 0; k < K; ++k) acc += xr[k] * wr[k];
             if (bias) acc += in16(bias[n], dtype);
+            if (residual) acc += in16(residual[m * ldr + n], dtype); /* y = linear(x) + residual, one rounding */
             y[r * ldy + n] = out16(acc, dtype);
         }
         free(xr);
@@ -352,7 +360,7 @@ int orc_linear_fp(const uint16_t* x, long M, int K, long ldx, const uint16_t* w,
 int orc_linear_a8(const uint16_t* x, long M, int K, long ldx, const uint8_t* wcodes, int N, int w_signed,
                   const float* w_scale, const int32_t* w_zp, int dynamic, float* act_scale, int32_t* act_zp,
                   const uint16_t* bias, uint16_t* y, long ldy, int32_t* acc_out, const int64_t* rows,
-                  long nrows) {
+                  long nrows, const uint16_t* residual, long ldr) {
     if (!x || !wcodes || !w_scale || !w_zp || !act_scale || !act_zp || !y || M <= 0 || K <= 0 || N <= 0 ||
         ldx < K || ldy < N)
         return ORC_BAD_ARG;
@@ -389,6 +397,7 @@ int orc_linear_a8(const uint16_t* x, long M, int K, long ldx, const uint8_t* wco
             if (acc_out) acc_out[r * (long)N + n] = (int32_t)acc;
             double v = (double)acc * ((double)sx * (double)w_scale[n]);
             if (bias) v += half_to_double(bias[n]);
+            if (residual) v += half_to_double(residual[m * ldr + n]);
             y[r * ldy + n] = double_to_half(v);
         }
         free(xd);
@@ -411,7 +420,7 @@ int orc_bos_aware_kv_proj(const uint16_t* ctx, int B, int T, int K, const uint8_
     if (!ctx || !y || B <= 0 || T <= 0 || K <= 0 || N <= 0) return ORC_BAD_ARG;
     if (naive_all_rows)
         return orc_linear_a8(ctx, (long)B * T, K, K, wcodes, N, w_signed, w_scale, w_zp, dynamic, act_scale,
-                             act_zp, bias, y, N, NULL, NULL, 0);
+                             act_zp, bias, y, N, NULL, NULL, 0, NULL, 0);
     if ((w_f16 == NULL) == (bos_out == NULL)) return ORC_BAD_ARG; /* exactly one of the two */
     int rc = ORC_OK;
     if (T > 1) {
@@ -422,7 +431,7 @@ int orc_bos_aware_kv_proj(const uint16_t* ctx, int B, int T, int K, const uint8_
         for (int b = 0; b < B; ++b)
             memcpy(body + (size_t)b * (T - 1) * K, ctx + ((size_t)b * T + 1) * K, (size_t)(T - 1) * K * 2);
         rc = orc_linear_a8(body, R, K, K, wcodes, N, w_signed, w_scale, w_zp, dynamic, act_scale, act_zp, bias,
-                           ybody, N, NULL, NULL, 0);
+                           ybody, N, NULL, NULL, 0, NULL, 0);
         for (int b = 0; b < B; ++b)
             memcpy(y + ((size_t)b * T + 1) * N, ybody + (size_t)b * (T - 1) * N, (size_t)(T - 1) * N * 2);
         free(body);
@@ -585,11 +594,12 @@ int orc_linear_a8_codes(const uint8_t* qx, long M, int K, float act_scale, int32
 /* filter column s, input channel c.                                         */
 /*     y[b,i,j,n] = sum_{r,s,c} x[b,i+r-1,j+s-1,c] * w[n,r,s,c] + bias[n]    */
 /* with x = 0 outside the image.  `pix` selects output pixels (flat index    */
-/* (b*H + i)*W + j), NULL = all.                                             */
+/* (b*H + i)*W + j), NULL = all.  residual: [B,H,W,N] or NULL, as for the    */
+/* linear layers.                                                            */
 /* ------------------------------------------------------------------------- */
 int orc_conv3x3_w_only(const uint16_t* x, int B, int H, int W, int Cin, const uint8_t* codes, int N,
                        const float* w_scale, const int32_t* w_zp, const uint16_t* bias, int dtype, uint16_t* y,
-                       const int64_t* pix, long npix) {
+                       const int64_t* pix, long npix, const uint16_t* residual) {
     if (!x || !codes || !w_scale || !w_zp || !y || B <= 0 || H <= 0 || W <= 0 || Cin <= 0 || N <= 0) return ORC_BAD_ARG;
     long M = (long)B * H * W;
     long R = pix ? npix : M;
@@ -617,6 +627,7 @@ int orc_conv3x3_w_only(const uint16_t* x, int B, int H, int W, int Cin, const ui
             double acc = 0.0;
             for (int k = 0; k < K; ++k) acc += col[k] * wr[k];
             if (bias) acc += in16(bias[n], dtype);
+            if (residual) acc += in16(residual[m * (long)N + n], dtype); /* [B,H,W,N], added before the rounding */
             y[rr * (long)N + n] = out16(acc, dtype);
         }
         free(col);
@@ -630,7 +641,8 @@ int orc_conv3x3_w_only(const uint16_t* x, int B, int H, int W, int Cin, const ui
  *     ACC[m,n] = sum over in-image (r,s), c of (qx - z_x)(qw - z_w[n]);  y = fp16(ACC * s_x * s_w[n] + bias[n]). */
 int orc_conv3x3_a8(const uint16_t* x, int B, int H, int W, int Cin, const uint8_t* wcodes, int N, int w_signed,
                    const float* w_scale, const int32_t* w_zp, int dynamic, float* act_scale, int32_t* act_zp,
-                   const uint16_t* bias, uint16_t* y, int32_t* acc_out, const int64_t* pix, long npix) {
+                   const uint16_t* bias, uint16_t* y, int32_t* acc_out, const int64_t* pix, long npix,
+                   const uint16_t* residual) {
     if (!x || !wcodes || !w_scale || !w_zp || !act_scale || !act_zp || !y || B <= 0 || H <= 0 || W <= 0 || Cin <= 0 ||
         N <= 0)
         return ORC_BAD_ARG;
@@ -670,6 +682,7 @@ int orc_conv3x3_a8(const uint16_t* x, int B, int H, int W, int Cin, const uint8_
             if (acc_out) acc_out[rr * (long)N + n] = (int32_t)acc;
             double v = (double)acc * ((double)sx * (double)w_scale[n]);
             if (bias) v += half_to_double(bias[n]);
+            if (residual) v += half_to_double(residual[m * (long)N + n]);
             y[rr * (long)N + n] = double_to_half(v);
         }
         free(col);

@@ -631,3 +631,96 @@ def test_w_only_geglu_is_value_times_gelu_of_gate(orc):
     swapped = lin[:, H:] * 0.5 * lin[:, :H] * (1.0 + erf(lin[:, :H] / math.sqrt(2.0)))
     assert np.abs(h - swapped).max() > 0.05   # value and gate are not interchangeable
     assert np.array_equal(orc.linear_w_only_geglu(x, c, s, z, b, rows=[3, 16]).view(np.float16).astype(np.float64), h[[3, 16]])
+
+
+# ------------------------------------------------------------------------------- residual operand, split shortcuts
+
+def test_residual_enters_the_sum_once_before_the_single_rounding(orc):
+    """Exact rationals for the weight-only layer; for the 8-bit-activation layer the output recomputed from the
+    returned integer accumulators. A residual that were added after rounding, subtracted, or indexed by the position in
+    the row list instead of the row itself fails one of these."""
+    rng = np.random.default_rng(101)
+    M, K, N = 5, 16, 6
+    x = rng.normal(0, 1, (M, K)).astype(np.float16)
+    c = rng.integers(0, 16, (N, K)).astype(np.uint8)
+    s = rng.uniform(0.01, 0.1, N).astype(np.float32)
+    z = rng.integers(0, 16, N).astype(np.int32)
+    b = rng.normal(0, 0.1, N).astype(np.float16)
+    r = rng.normal(0, 1, (M, N)).astype(np.float16)
+    y = orc.linear_w_only(x, c, s, z, b, residual=r).view(np.float16)
+    twice = 0
+    for m in range(M):
+        for n in range(N):
+            acc = Fraction(float(b[n])) + Fraction(float(r[m, n]))
+            for k in range(K):
+                acc += Fraction(float(x[m, k])) * Fraction(float(s[n])) * (int(c[n, k]) - int(z[n]))
+            assert y[m, n] == np.float16(float(acc)), (m, n)
+            twice += y[m, n] != np.float16(np.float16(float(acc - Fraction(float(r[m, n])))) + r[m, n])
+    assert twice > 0            # rounding before the addition is a different function on this input
+    rows = [4, 1]
+    assert np.array_equal(orc.linear_w_only(x, c, s, z, b, rows=rows, residual=r).view(np.float16), y[rows])
+    assert np.array_equal(orc.linear_w_only(x, c, s, z, b, residual=np.zeros_like(r)), orc.linear_w_only(x, c, s, z, b))
+
+    ya, acc, act = orc.linear_a8(x, c, s, z, bias=b, residual=r)
+    yf = acc.astype(np.float64) * (np.float64(act[0]) * s.astype(np.float64))[None, :] + b.astype(np.float64) + \
+        r.astype(np.float64)
+    assert np.array_equal(ya.view(np.float16), yf.astype(np.float16))
+    assert np.array_equal(orc.linear_a8(x, c, s, z, bias=b, rows=rows, residual=r)[0], ya[rows])
+
+
+def test_conv_residual_is_indexed_by_pixel(orc):
+    B, H, W, Cin, N = 2, 3, 4, 8, 5
+    x, w, b, c, s, z = _conv_case(orc, 103, B, H, W, Cin, N, 4)
+    r = np.random.default_rng(104).normal(0, 1, (B, H, W, N)).astype(np.float16)
+    y0, acc, act = orc.conv3x3_a8(x, c, s, z, bias=b)
+    y, acc2, act2 = orc.conv3x3_a8(x, c, s, z, bias=b, residual=r)
+    assert act == act2 and np.array_equal(acc, acc2)
+    yf = acc.astype(np.float64) * (np.float64(act[0]) * s.astype(np.float64))[None, :] + b.astype(np.float64) + \
+        r.reshape(-1, N).astype(np.float64)
+    assert np.array_equal(y.view(np.float16), yf.astype(np.float16))
+    pix = [23, 0, 9]
+    assert np.array_equal(orc.conv3x3_a8(x, c, s, z, bias=b, pix=pix, residual=r)[0], y[pix])
+    # weight-only: against the pinned residual-free result where the sum is exact (integers below 2048)
+    xi = np.random.default_rng(105).integers(-2, 3, (B, H, W, Cin)).astype(np.float16)
+    ci = np.random.default_rng(106).integers(0, 4, (N, 9 * Cin)).astype(np.uint8)
+    ri = np.random.default_rng(107).integers(-50, 51, (B, H, W, N)).astype(np.float16)
+    one, zero = np.ones(N, np.float32), np.zeros(N, np.int32)
+    plain = orc.conv3x3_w_only(xi, ci, one, zero).view(np.float16).astype(np.float64)
+    withr = orc.conv3x3_w_only(xi, ci, one, zero, residual=ri).view(np.float16).astype(np.float64)
+    assert np.array_equal(withr, plain + ri.reshape(-1, N).astype(np.float64))
+    assert np.array_equal(orc.conv3x3_w_only(xi, ci, one, zero, pix=pix, residual=ri).view(np.float16).astype(np.float64),
+                          withr[pix])
+
+
+def test_split_shortcut_equals_the_concatenated_layer_where_sums_are_exact(orc):
+    """A layer over channel-concatenated inputs [trunk | skip] is the sum of two layers over the two parts (Sec. 4.1,
+    split of the concatenated shortcut input). With small integers every partial sum is an exact fp16 value, so two calls
+    chained through the residual operand must reproduce the one-call result bit for bit, for the linear layer and for
+    the convolution in its (r, s, c) weight order."""
+    rng = np.random.default_rng(110)
+    M, C1, C2, N = 12, 24, 8, 7
+    x1 = rng.integers(-3, 4, (M, C1)).astype(np.float16)
+    x2 = rng.integers(-3, 4, (M, C2)).astype(np.float16)
+    w1 = rng.integers(0, 8, (N, C1)).astype(np.uint8)
+    w2 = rng.integers(0, 8, (N, C2)).astype(np.uint8)
+    b = rng.integers(-4, 5, N).astype(np.float16)
+    one, zero, z3 = np.ones(N, np.float32), np.zeros(N, np.int32), np.full(N, 3, np.int32)
+    whole = orc.linear_w_only(np.concatenate([x1, x2], 1), np.concatenate([w1, w2], 1), one, z3, b)
+    first = orc.linear_w_only(x1, w1, one, z3, b)
+    assert np.array_equal(orc.linear_w_only(x2, w2, one, z3, None, residual=first), whole)
+
+    B, H, W = 2, 4, 5
+    xa = rng.integers(-2, 3, (B, H, W, C1)).astype(np.float16)
+    xb = rng.integers(-2, 3, (B, H, W, C2)).astype(np.float16)
+    wa = rng.integers(0, 4, (N, 3, 3, C1)).astype(np.uint8)
+    wb = rng.integers(0, 4, (N, 3, 3, C2)).astype(np.uint8)
+    wcat = np.concatenate([wa, wb], 3).reshape(N, -1)
+    whole = orc.conv3x3_w_only(np.concatenate([xa, xb], 3), wcat, one, zero, b)
+    first = orc.conv3x3_w_only(xa, wa.reshape(N, -1), one, zero, b)
+    assert np.array_equal(orc.conv3x3_w_only(xb, wb.reshape(N, -1), one, zero, None, residual=first), whole)
+    # 8-bit activations: each part has its own activation quantiser and its codes are not exact, so the chained result
+    # is checked to the quantiser's tolerance (the accumulators of each part are pinned above)
+    ya = orc.conv3x3_a8(xa, wa.reshape(N, -1), one, zero, bias=b)[0]
+    yb = orc.conv3x3_a8(xb, wb.reshape(N, -1), one, zero, residual=ya)[0].view(np.float16).astype(np.float64)
+    ref = whole.view(np.float16).astype(np.float64)
+    assert np.abs(yb - ref).max() <= 0.02 * np.abs(ref).max()
