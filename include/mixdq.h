@@ -141,10 +141,15 @@ int mq_unpack_weights(const void* packed, int N, int K, int bits, int layout, ui
  *   packed MQ_LAYOUT_KERNEL, unsigned codes.   bias nullable [N] (same 16-bit dtype as x and y).
  *   K % 64 == 0, N % 8 == 0, M*ldx*2 < 2^31 bytes.  No workspace is needed.
  *   bits = 16: the layer is kept at 16 bits; packed holds the weights themselves (same dtype as x) in
- *   MQ_LAYOUT_KERNEL, w_scale and w_zp are ignored (may be null):  Y = round16( sum_k X[m,k] * W[n,k] + bias[n] ). */
+ *   MQ_LAYOUT_KERNEL, w_scale and w_zp are ignored (may be null):  Y = round16( sum_k X[m,k] * W[n,k] + bias[n] ).
+ *   residual nullable [M,N] of the same 16-bit dtype, row stride ldr (ldr % 4 == 0, 8-byte aligned): added in fp32
+ *   before the rounding, Y = round16( ... + bias[n] + residual[m,n] ).  It may be y itself.  It serves a block's skip
+ *   connection, and the split of a layer over a channel-concatenated input [trunk | shortcut] into two layers with
+ *   their own quantisation parameters (paper Sec. 4.1, "Quantization Scheme"): the second call adds the first one's
+ *   output.  The same operand, with the same meaning, exists on the entry points below that take `residual`. */
 int mq_qlinear_w_only(const void* x, int M, int K, int ldx, const void* packed, int N, int bits, int layout,
                       const float* w_scale, const int32_t* w_zp, const void* bias, void* y, int ldy, int dtype,
-                      void* stream);
+                      const void* residual, int ldr, void* stream);
 
 /* Workspace for the 8-bit-activation entry points below (M rows of K activations). */
 size_t mq_qlinear_a8_workspace_bytes(int M, int K);
@@ -160,6 +165,7 @@ size_t mq_qlinear_a8_workspace_bytes(int M, int K);
  *   act_scale/act_zp  both NULL: dynamic — min/max of X is reduced on the device; otherwise static
  *            (calibrated, Sec. 4.1) parameters are read from these device scalars.
  *   acc_debug         nullable [M,N] int32 out: ACC, for bit-exact checks.
+ *   residual, ldr     nullable fp16 [M,N], as for mq_qlinear_w_only: Y = fp16( ACC * s_x * s_w[n] + bias[n] + residual ).
  *   act_scale_out/act_zp_out  nullable device scalars out: the parameters that were used.
  *   K % 64 == 0 and K <= 33024; N % 8 == 0.
  * Errors: MQ_ERR_BAD_ARG when exactly one of act_scale/act_zp is NULL; MQ_ERR_OVERFLOW_RISK;
@@ -167,14 +173,16 @@ size_t mq_qlinear_a8_workspace_bytes(int M, int K);
 int mq_qlinear_w8a8(const void* x, int M, int K, int ldx, const void* packed, int N, int layout, int w_signed,
                     const float* w_scale, const int32_t* w_zp, const int32_t* w_colsum, const float* act_scale,
                     const int32_t* act_zp, const void* bias, void* y, int ldy, int32_t* acc_debug,
-                    float* act_scale_out, int32_t* act_zp_out, void* ws, size_t ws_bytes, void* stream);
+                    const void* residual, int ldr, float* act_scale_out, int32_t* act_zp_out, void* ws,
+                    size_t ws_bytes, void* stream);
 
 /* W4A8 linear: as above with asymmetric unsigned 4-bit weight codes (the INT4 operator the paper leaves as
  * future work, App. C item 4); the codes are widened to int8 in registers ahead of the int8 MFMA. */
 int mq_qlinear_w4a8(const void* x, int M, int K, int ldx, const void* packed, int N, int layout,
                     const float* w_scale, const int32_t* w_zp, const int32_t* w_colsum, const float* act_scale,
                     const int32_t* act_zp, const void* bias, void* y, int ldy, int32_t* acc_debug,
-                    float* act_scale_out, int32_t* act_zp_out, void* ws, size_t ws_bytes, void* stream);
+                    const void* residual, int ldr, float* act_scale_out, int32_t* act_zp_out, void* ws,
+                    size_t ws_bytes, void* stream);
 
 /* ------------------------------------------------------------------------------------------------
  * Feed-forward pair with the activation kept in 8 bits between its two linears (an extension: paper Sec. 4.3
@@ -217,11 +225,12 @@ int mq_qlinear_w_only_geglu(const void* x, int M, int K, int ldx, const void* pa
 
 /* W8A8 / W4A8 linear on activations that arrive as codes in the A8 layout (row stride lda bytes) together with
  * their parameters (device pointers act_scale, act_zp): ACC and Y as in mq_qlinear_w8a8.  The row sums of the
- * codes, which the zero-point correction needs, are taken inside the GEMM; no workspace. */
+ * codes, which the zero-point correction needs, are taken inside the GEMM; no workspace.  residual: nullable fp16
+ * [M,N], row stride ldr, added before the rounding (the block's skip connection after a feed-forward). */
 int mq_qlinear_a8_codes(const int8_t* a8, int M, int K, int lda, const float* act_scale, const int32_t* act_zp,
                         const void* packed, int N, int w_bits, int layout, int w_signed, const float* w_scale,
                         const int32_t* w_zp, const int32_t* w_colsum, const void* bias, void* y, int ldy,
-                        int32_t* acc_debug, void* stream);
+                        int32_t* acc_debug, const void* residual, int ldr, void* stream);
 
 /* ------------------------------------------------------------------------------------------------
  * 3x3 convolution, stride 1, zero padding 1 (paper Sec. 4.1 "Quantization Scheme": the convolution layers are
@@ -230,11 +239,15 @@ int mq_qlinear_a8_codes(const int8_t* a8, int M, int K, int lda, const float* ac
  * mq_pack_weights is [N, 9*Cin] with k = (r*3 + s)*Cin + c (filter row r, filter column s, input channel c), in
  * MQ_LAYOUT_KERNEL.  No im2col copy is made: the GEMM's activation loads address the taps themselves, and taps
  * outside the image read as zero.  Cin % 64 == 0, N % 8 == 0, B*H*W*Cin*2 < 2^31.
+ * residual: nullable [B,H,W,N] fp16, contiguous, added before the rounding (may be y itself): the skip connection of
+ * a residual block, or the output of the convolution over the other part of a split channel-concatenated input.
  * ---------------------------------------------------------------------------------------------- */
 
-/* Weight-only convolution, W{2,3,4,8}A16:  y = fp16( sum_{r,s,c} x[b,i+r-1,j+s-1,c] * scale[n]*(code - zp[n]) + bias[n] ). */
+/* Weight-only convolution, W{2,3,4,8}A16:
+ *     y = fp16( sum_{r,s,c} x[b,i+r-1,j+s-1,c] * scale[n]*(code - zp[n]) + bias[n] + residual[b,i,j,n] ). */
 int mq_conv3x3_w_only(const void* x, int B, int H, int W, int Cin, const void* packed, int N, int bits, int layout,
-                      const float* w_scale, const int32_t* w_zp, const void* bias, void* y, void* stream);
+                      const float* w_scale, const int32_t* w_zp, const void* bias, void* y, const void* residual,
+                      void* stream);
 
 /* Sums of the weight codes per filter tap, [9][N] int32 (tap = r*3 + s): needed by mq_conv3x3_a8 for the output
  * pixels whose filter reaches outside the image.  codes [N, 9*Cin] as handed to mq_pack_weights. */
@@ -244,13 +257,14 @@ size_t mq_conv3x3_a8_workspace_bytes(int B, int H, int W, int Cin);
 
 /* W8A8 / W4A8 convolution: activations quantised per tensor (dynamic min/max over x, or the given static
  * parameters) as in mq_qlinear_w8a8; a padded position holds the value 0, whose code is the zero point:
- *     ACC[m,n] = sum over in-image (r,s), c of (qx - z_x)(qw - z_w[n]),   y = fp16(ACC * s_x * s_w[n] + bias[n]).
+ *     ACC[m,n] = sum over in-image (r,s), c of (qx - z_x)(qw - z_w[n]),
+ *     y = fp16(ACC * s_x * s_w[n] + bias[n] + residual[m,n]).
  * acc_debug nullable [B*H*W, N] int32. */
 int mq_conv3x3_a8(const void* x, int B, int H, int W, int Cin, const void* packed, int N, int w_bits, int layout,
                   int w_signed, const float* w_scale, const int32_t* w_zp, const int32_t* w_colsum,
                   const int32_t* w_tapsum, const float* act_scale, const int32_t* act_zp, const void* bias, void* y,
-                  int32_t* acc_debug, float* act_scale_out, int32_t* act_zp_out, void* ws, size_t ws_bytes,
-                  void* stream);
+                  int32_t* acc_debug, const void* residual, float* act_scale_out, int32_t* act_zp_out, void* ws,
+                  size_t ws_bytes, void* stream);
 
 size_t mq_bos_aware_kv_proj_workspace_bytes(int B, int T, int K);
 

@@ -167,15 +167,15 @@ def linear_w_only(x, codes, w_scale, w_zp, bias=None, dtype=F16, rows=None, resi
     return y
 
 
-def linear_fp(x, w, bias=None, dtype=F16):
+def linear_fp(x, w, bias=None, dtype=F16, residual=None):
     x = _u16(x)
     w = _u16(w)
     bias = _u16(bias)
     M, K = x.shape
     N = w.shape[0]
     y = np.empty((M, N), np.uint16)
-    _check(lib().orc_linear_fp(_p(x), C.c_long(M), K, C.c_long(K), _p(w), N, _p(bias), dtype, _p(y), C.c_long(N)),
-           "linear_fp")
+    _check(lib().orc_linear_fp(_p(x), C.c_long(M), K, C.c_long(K), _p(w), N, _p(bias), dtype, _p(y), C.c_long(N),
+                               _p(_u16(residual)), C.c_long(N)), "linear_fp")
     return y
 
 
@@ -252,7 +252,7 @@ def linear_a8_geglu(x, wcodes, w_scale, w_zp, out_act, w_signed=False, act=None,
     return codes, h16, (np.float32(s.value), int(z.value))
 
 
-def linear_a8_codes(qx, act, wcodes, w_scale, w_zp, w_signed=False, bias=None, want_acc=True):
+def linear_a8_codes(qx, act, wcodes, w_scale, w_zp, w_signed=False, bias=None, want_acc=True, residual=None):
     """A8 linear on activations that arrive as unsigned 8-bit codes with act = (scale, zp).
     Returns (y uint16 [M,N], acc int32 or None)."""
     qx = np.ascontiguousarray(qx, np.uint8)
@@ -265,8 +265,8 @@ def linear_a8_codes(qx, act, wcodes, w_scale, w_zp, w_signed=False, bias=None, w
     acc = np.empty((M, N), np.int32) if want_acc else None
     _check(lib().orc_linear_a8_codes(_p(qx), C.c_long(M), K, C.c_float(act[0]), C.c_int32(act[1]), _p(wcodes), N,
                                      int(w_signed), _p(np.ascontiguousarray(w_scale, np.float32)),
-                                     _p(np.ascontiguousarray(w_zp, np.int32)), _p(bias), _p(y), C.c_long(N), _p(acc)),
-           "linear_a8_codes")
+                                     _p(np.ascontiguousarray(w_zp, np.int32)), _p(bias), _p(y), C.c_long(N), _p(acc),
+                                     _p(_u16(residual)), C.c_long(N)), "linear_a8_codes")
     return y, acc
 
 

@@ -336,7 +336,7 @@ int orc_linear_w_only(const uint16_t* x, long M, int K, long ldx, const uint8_t*
 
 /* Plain 16-bit floating-point linear with unquantised weights W[N,K] (used for the BOS row). */
 int orc_linear_fp(const uint16_t* x, long M, int K, long ldx, const uint16_t* w, int N,
-                  const uint16_t* bias, int dtype, uint16_t* y, long ldy) {
+                  const uint16_t* bias, int dtype, uint16_t* y, long ldy, const uint16_t* residual, long ldr) {
     if (!x || !w || !y || M <= 0 || K <= 0 || N <= 0 || ldx < K || ldy < N) return ORC_BAD_ARG;
 #pragma omp parallel for schedule(static)
     for (long m = 0; m < M; ++m)
@@ -345,6 +345,7 @@ int orc_linear_fp(const uint16_t* x, long M, int K, long ldx, const uint16_t* w,
             for (int k = 0; k < K; ++k)
                 acc += in16(x[m * ldx + k], dtype) * in16(w[(size_t)n * K + k], dtype);
             if (bias) acc += in16(bias[n], dtype);
+            if (residual) acc += in16(residual[m * ldr + n], dtype);
             y[m * ldy + n] = out16(acc, dtype);
         }
     return ORC_OK;
@@ -443,7 +444,7 @@ int orc_bos_aware_kv_proj(const uint16_t* ctx, int B, int T, int K, const uint8_
         if (bos_out) {
             memcpy(y0, bos_out, (size_t)N * 2);
         } else {
-            rc = orc_linear_fp(ctx + (size_t)b * T * K, 1, K, K, w_f16, N, bias, ORC_F16, y0, N);
+            rc = orc_linear_fp(ctx + (size_t)b * T * K, 1, K, K, w_f16, N, bias, ORC_F16, y0, N, NULL, 0);
             if (rc) return rc;
         }
     }
@@ -562,7 +563,7 @@ int orc_linear_a8_geglu(const uint16_t* x, long M, int K, long ldx, const uint8_
 /* A8 linear whose activations arrive as unsigned 8-bit codes with their parameters (the consumer of the above). */
 int orc_linear_a8_codes(const uint8_t* qx, long M, int K, float act_scale, int32_t act_zp, const uint8_t* wcodes, int N,
                         int w_signed, const float* w_scale, const int32_t* w_zp, const uint16_t* bias, uint16_t* y,
-                        long ldy, int32_t* acc_out) {
+                        long ldy, int32_t* acc_out, const uint16_t* residual, long ldr) {
     if (!qx || !wcodes || !w_scale || !w_zp || !y || M <= 0 || K <= 0 || N <= 0 || ldy < N || !(act_scale > 0.0f) ||
         act_zp < 0 || act_zp > 255)
         return ORC_BAD_ARG;
@@ -579,6 +580,7 @@ int orc_linear_a8_codes(const uint8_t* qx, long M, int K, float act_scale, int32
             if (acc_out) acc_out[m * (long)N + n] = (int32_t)acc;
             double v = (double)acc * ((double)act_scale * (double)w_scale[n]);
             if (bias) v += half_to_double(bias[n]);
+            if (residual) v += half_to_double(residual[m * ldr + n]);
             y[m * ldy + n] = double_to_half(v);
         }
     }

@@ -187,15 +187,25 @@ def unpack_weights(packed: torch.Tensor, N: int, K: int, bits: int, layout: int,
     return codes
 
 
+def _res(residual, M, N, dtype):
+    """(pointer, row stride) of an optional [M,N] residual operand."""
+    if residual is None:
+        return C.c_void_p(0), 0
+    assert residual.is_cuda and residual.dim() == 2 and residual.shape == (M, N) and residual.stride(1) == 1
+    assert residual.dtype == dtype
+    return _ptr(residual), residual.stride(0)
+
+
 def qlinear_w_only(x: torch.Tensor, w: PackedWeight, bias: Optional[torch.Tensor] = None,
-                   out: Optional[torch.Tensor] = None) -> torch.Tensor:
-    """Y = X . dequant(W)^T + bias with 16-bit floating-point compute (weight-only quantisation)."""
+                   out: Optional[torch.Tensor] = None, residual: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Y = X . dequant(W)^T + bias (+ residual) with 16-bit floating-point compute (weight-only quantisation)."""
     assert x.is_cuda and x.dim() == 2 and x.stride(1) == 1
     M, K = x.shape
     assert K == w.K
     y = out if out is not None else torch.empty((M, w.N), dtype=x.dtype, device=x.device)
+    rp, ldr = _res(residual, M, w.N, x.dtype)
     _check(load().mq_qlinear_w_only(_ptr(x), M, K, x.stride(0), _ptr(w.packed), w.N, w.bits, w.layout, _ptr(w.scale),
-                                    _ptr(w.zp), _ptr(bias), _ptr(y), y.stride(0), _dtype_code(x), _stream()),
+                                    _ptr(w.zp), _ptr(bias), _ptr(y), y.stride(0), _dtype_code(x), rp, ldr, _stream()),
            "mq_qlinear_w_only")
     return y
 
@@ -210,7 +220,7 @@ def _workspace(nbytes: int, device, ws: Optional[torch.Tensor]):
     return ws
 
 
-def _qlinear_a8(fn_name, x, w: PackedWeight, act, bias, out, ws, want_acc, want_act):
+def _qlinear_a8(fn_name, x, w: PackedWeight, act, bias, out, ws, want_acc, want_act, residual=None):
     assert x.is_cuda and x.dim() == 2 and x.stride(1) == 1 and x.dtype == torch.float16
     M, K = x.shape
     assert K == w.K
@@ -221,29 +231,33 @@ def _qlinear_a8(fn_name, x, w: PackedWeight, act, bias, out, ws, want_acc, want_
     s_out = torch.empty(1, dtype=torch.float32, device=dev) if want_act else None
     z_out = torch.empty(1, dtype=torch.int32, device=dev) if want_act else None
     a_s, a_z = (None, None) if act is None else act
+    rp, ldr = _res(residual, M, w.N, torch.float16)
     L = load()
     if fn_name == "mq_qlinear_w8a8":
         rc = L.mq_qlinear_w8a8(_ptr(x), M, K, x.stride(0), _ptr(w.packed), w.N, w.layout, int(w.signed), _ptr(w.scale),
                                _ptr(w.zp), _ptr(w.colsum), _ptr(a_s), _ptr(a_z), _ptr(bias), _ptr(y), y.stride(0),
-                               _ptr(acc), _ptr(s_out), _ptr(z_out), _ptr(ws), C.c_size_t(ws.numel()), _stream())
+                               _ptr(acc), rp, ldr, _ptr(s_out), _ptr(z_out), _ptr(ws), C.c_size_t(ws.numel()),
+                               _stream())
     else:
         rc = L.mq_qlinear_w4a8(_ptr(x), M, K, x.stride(0), _ptr(w.packed), w.N, w.layout, _ptr(w.scale), _ptr(w.zp),
                                _ptr(w.colsum), _ptr(a_s), _ptr(a_z), _ptr(bias), _ptr(y), y.stride(0), _ptr(acc),
-                               _ptr(s_out), _ptr(z_out), _ptr(ws), C.c_size_t(ws.numel()), _stream())
+                               rp, ldr, _ptr(s_out), _ptr(z_out), _ptr(ws), C.c_size_t(ws.numel()), _stream())
     _check(rc, fn_name)
     return y, acc, (s_out, z_out)
 
 
-def qlinear_w8a8(x, w: PackedWeight, act=None, bias=None, out=None, ws=None, want_acc=False, want_act=False):
+def qlinear_w8a8(x, w: PackedWeight, act=None, bias=None, out=None, ws=None, want_acc=False, want_act=False,
+                 residual=None):
     """act=None: dynamic per-tensor min-max on the device; else (scale tensor[1] f32, zp tensor[1] i32).
     Returns (y, acc or None, (act_scale, act_zp) device scalars or (None, None))."""
     assert w.bits == 8
-    return _qlinear_a8("mq_qlinear_w8a8", x, w, act, bias, out, ws, want_acc, want_act)
+    return _qlinear_a8("mq_qlinear_w8a8", x, w, act, bias, out, ws, want_acc, want_act, residual)
 
 
-def qlinear_w4a8(x, w: PackedWeight, act=None, bias=None, out=None, ws=None, want_acc=False, want_act=False):
+def qlinear_w4a8(x, w: PackedWeight, act=None, bias=None, out=None, ws=None, want_acc=False, want_act=False,
+                 residual=None):
     assert w.bits == 4 and not w.signed
-    return _qlinear_a8("mq_qlinear_w4a8", x, w, act, bias, out, ws, want_acc, want_act)
+    return _qlinear_a8("mq_qlinear_w4a8", x, w, act, bias, out, ws, want_acc, want_act, residual)
 
 
 def a8_row_bytes(K: int) -> int:
@@ -281,15 +295,17 @@ def qlinear_w_only_geglu(x, w: PackedWeight, bias=None, out=None):
     return h
 
 
-def qlinear_a8_codes(a8, K: int, act, w: PackedWeight, bias=None, out=None, want_acc=False):
+def qlinear_a8_codes(a8, K: int, act, w: PackedWeight, bias=None, out=None, want_acc=False, residual=None):
     """A8 linear on activations in the A8 layout (a8 int8 [M, stride]); act = (scale, zp) one-element device tensors."""
     assert a8.is_cuda and a8.dim() == 2 and a8.stride(1) == 1 and a8.dtype == torch.int8 and K == w.K
     M = a8.shape[0]
     y = out if out is not None else torch.empty((M, w.N), dtype=torch.float16, device=a8.device)
     acc = torch.empty((M, w.N), dtype=torch.int32, device=a8.device) if want_acc else None
+    rp, ldr = _res(residual, M, w.N, torch.float16)
     _check(load().mq_qlinear_a8_codes(_ptr(a8), M, K, a8.stride(0), _ptr(act[0]), _ptr(act[1]), _ptr(w.packed), w.N,
                                       w.bits, w.layout, int(w.signed), _ptr(w.scale), _ptr(w.zp), _ptr(w.colsum),
-                                      _ptr(bias), _ptr(y), y.stride(0), _ptr(acc), _stream()), "mq_qlinear_a8_codes")
+                                      _ptr(bias), _ptr(y), y.stride(0), _ptr(acc), rp, ldr, _stream()),
+           "mq_qlinear_a8_codes")
     return y, acc
 
 
@@ -304,13 +320,14 @@ def plan_qlinear_a8_geglu(x, w: PackedWeight, out_act, bias, a8_out, ws, act=Non
     return _planned(load().mq_qlinear_a8_geglu, "mq_qlinear_a8_geglu", args, (x, w, out_act, bias, a8_out, ws, act))
 
 
-def plan_qlinear_a8_codes(a8, K, act, w: PackedWeight, bias, out):
+def plan_qlinear_a8_codes(a8, K, act, w: PackedWeight, bias, out, residual=None):
     M = a8.shape[0]
     null = C.c_void_p(0)
+    rp, ldr = _res(residual, M, w.N, torch.float16)
     args = (_ptr(a8), M, K, a8.stride(0), _ptr(act[0]), _ptr(act[1]), _ptr(w.packed), w.N, w.bits, w.layout,
             int(w.signed), _ptr(w.scale), _ptr(w.zp), _ptr(w.colsum), _ptr(bias), _ptr(out), out.stride(0), null,
-            _stream())
-    return _planned(load().mq_qlinear_a8_codes, "mq_qlinear_a8_codes", args, (a8, act, w, bias, out))
+            rp, ldr, _stream())
+    return _planned(load().mq_qlinear_a8_codes, "mq_qlinear_a8_codes", args, (a8, act, w, bias, out, residual))
 
 
 def conv_tap_sums(codes: torch.Tensor, Cin: int, bits: int, codes_signed: bool = False) -> torch.Tensor:
@@ -322,14 +339,24 @@ def conv_tap_sums(codes: torch.Tensor, Cin: int, bits: int, codes_signed: bool =
     return out
 
 
-def conv3x3_w_only(x: torch.Tensor, w: PackedWeight, bias=None, out=None) -> torch.Tensor:
-    """x [B,H,W,Cin] fp16 channels-last contiguous; w packed from the [N, 9*Cin] matrix.  Returns y [B,H,W,N]."""
+def _res4(residual, shape):
+    if residual is None:
+        return C.c_void_p(0)
+    assert residual.is_cuda and tuple(residual.shape) == tuple(shape) and residual.is_contiguous()
+    assert residual.dtype == torch.float16
+    return _ptr(residual)
+
+
+def conv3x3_w_only(x: torch.Tensor, w: PackedWeight, bias=None, out=None, residual=None) -> torch.Tensor:
+    """x [B,H,W,Cin] fp16 channels-last contiguous; w packed from the [N, 9*Cin] matrix.  Returns y [B,H,W,N]
+    (+ residual [B,H,W,N], added before the rounding)."""
     assert x.is_cuda and x.dim() == 4 and x.is_contiguous() and x.dtype == torch.float16
     B, H, W, Cin = x.shape
     assert w.K == 9 * Cin
     y = out if out is not None else torch.empty((B, H, W, w.N), dtype=torch.float16, device=x.device)
     _check(load().mq_conv3x3_w_only(_ptr(x), B, H, W, Cin, _ptr(w.packed), w.N, w.bits, w.layout, _ptr(w.scale),
-                                    _ptr(w.zp), _ptr(bias), _ptr(y), _stream()), "mq_conv3x3_w_only")
+                                    _ptr(w.zp), _ptr(bias), _ptr(y), _res4(residual, y.shape), _stream()),
+           "mq_conv3x3_w_only")
     return y
 
 
@@ -337,7 +364,8 @@ def conv3x3_a8_workspace_bytes(B: int, H: int, W: int, Cin: int) -> int:
     return int(load().mq_conv3x3_a8_workspace_bytes(B, H, W, Cin))
 
 
-def conv3x3_a8(x, w: PackedWeight, tapsum, act=None, bias=None, out=None, ws=None, want_acc=False, want_act=False):
+def conv3x3_a8(x, w: PackedWeight, tapsum, act=None, bias=None, out=None, ws=None, want_acc=False, want_act=False,
+               residual=None):
     """Returns (y [B,H,W,N], acc int32 [B*H*W,N] or None, (act_scale, act_zp) or None)."""
     assert x.is_cuda and x.dim() == 4 and x.is_contiguous() and x.dtype == torch.float16
     B, H, W, Cin = x.shape
@@ -350,8 +378,8 @@ def conv3x3_a8(x, w: PackedWeight, tapsum, act=None, bias=None, out=None, ws=Non
     zo = torch.empty(1, dtype=torch.int32, device=x.device) if want_act else None
     _check(load().mq_conv3x3_a8(_ptr(x), B, H, W, Cin, _ptr(w.packed), w.N, w.bits, w.layout, int(w.signed),
                                 _ptr(w.scale), _ptr(w.zp), _ptr(w.colsum), _ptr(tapsum), _ptr(a_s), _ptr(a_z), _ptr(bias),
-                                _ptr(y), _ptr(acc), _ptr(so), _ptr(zo), _ptr(ws), C.c_size_t(ws.numel()), _stream()),
-           "mq_conv3x3_a8")
+                                _ptr(y), _ptr(acc), _res4(residual, y.shape), _ptr(so), _ptr(zo), _ptr(ws),
+                                C.c_size_t(ws.numel()), _stream()), "mq_conv3x3_a8")
     return y, acc, ((so, zo) if want_act else None)
 
 
@@ -395,31 +423,33 @@ def _planned(fn, what, args, keep):
     return call
 
 
-def plan_qlinear_w_only(x, w: PackedWeight, bias, out):
+def plan_qlinear_w_only(x, w: PackedWeight, bias, out, residual=None):
     assert x.is_cuda and x.dim() == 2 and x.stride(1) == 1 and out.shape == (x.shape[0], w.N)
     M, K = x.shape
+    rp, ldr = _res(residual, M, w.N, x.dtype)
     args = (_ptr(x), M, K, x.stride(0), _ptr(w.packed), w.N, w.bits, w.layout, _ptr(w.scale), _ptr(w.zp), _ptr(bias),
-            _ptr(out), out.stride(0), _dtype_code(x), _stream())
-    return _planned(load().mq_qlinear_w_only, "mq_qlinear_w_only", args, (x, w, bias, out))
+            _ptr(out), out.stride(0), _dtype_code(x), rp, ldr, _stream())
+    return _planned(load().mq_qlinear_w_only, "mq_qlinear_w_only", args, (x, w, bias, out, residual))
 
 
-def plan_qlinear_a8(x, w: PackedWeight, bias, out, ws, act=None):
+def plan_qlinear_a8(x, w: PackedWeight, bias, out, ws, act=None, residual=None):
     """W8A8 or W4A8 by the weight's bit-width; dynamic activation parameters unless act=(scale, zp) tensors."""
     assert x.is_cuda and x.dim() == 2 and x.stride(1) == 1 and x.dtype == torch.float16
     M, K = x.shape
     a_s, a_z = (None, None) if act is None else act
     null = C.c_void_p(0)
+    rp, ldr = _res(residual, M, w.N, torch.float16)
     if w.bits == 8:
         fn, what = load().mq_qlinear_w8a8, "mq_qlinear_w8a8"
         args = (_ptr(x), M, K, x.stride(0), _ptr(w.packed), w.N, w.layout, int(w.signed), _ptr(w.scale), _ptr(w.zp),
-                _ptr(w.colsum), _ptr(a_s), _ptr(a_z), _ptr(bias), _ptr(out), out.stride(0), null, null, null, _ptr(ws),
-                C.c_size_t(ws.numel()), _stream())
+                _ptr(w.colsum), _ptr(a_s), _ptr(a_z), _ptr(bias), _ptr(out), out.stride(0), null, rp, ldr, null, null,
+                _ptr(ws), C.c_size_t(ws.numel()), _stream())
     else:
         fn, what = load().mq_qlinear_w4a8, "mq_qlinear_w4a8"
         args = (_ptr(x), M, K, x.stride(0), _ptr(w.packed), w.N, w.layout, _ptr(w.scale), _ptr(w.zp), _ptr(w.colsum),
-                _ptr(a_s), _ptr(a_z), _ptr(bias), _ptr(out), out.stride(0), null, null, null, _ptr(ws),
+                _ptr(a_s), _ptr(a_z), _ptr(bias), _ptr(out), out.stride(0), null, rp, ldr, null, null, _ptr(ws),
                 C.c_size_t(ws.numel()), _stream())
-    return _planned(fn, what, args, (x, w, bias, out, ws, act))
+    return _planned(fn, what, args, (x, w, bias, out, ws, act, residual))
 
 
 def plan_bos_aware_kv_proj(ctx, w: PackedWeight, out, ws, w_f16=None, bos_out=None, bias=None, act=None):

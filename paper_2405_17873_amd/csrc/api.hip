@@ -54,13 +54,22 @@ static int check_linear_common(const void* x, int M, int K, int ldx, const void*
     return MQ_OK;
 }
 
+// Optional residual operand: [M, ldr] 16-bit values, may be the output tensor itself.
+static int check_residual(const void* residual, long ldr, int N) {
+    if (!residual) return MQ_OK;
+    if (ldr < N || ldr % 4 != 0) return MQ_ERR_BAD_SHAPE;
+    if (!aligned(residual, 8)) return MQ_ERR_BAD_ARG;
+    return MQ_OK;
+}
+
 static int qlinear_a8(const void* x, int M, int K, int ldx, RowMap in_map, const void* packed, int N, int layout,
                       int w_bits, int w_signed, const float* w_scale, const int32_t* w_zp, const int32_t* w_colsum,
                       const float* act_scale, const int32_t* act_zp, const void* bias, void* y, int ldy, RowMap out_map,
                       int32_t* acc_debug, float* act_scale_out, int32_t* act_zp_out, void* ws, size_t ws_bytes,
-                      hipStream_t st) {
+                      const void* residual, int ldr, hipStream_t st) {
     int rc = check_linear_common(x, M, K, ldx, packed, N, layout, w_scale, w_zp, bias, y, ldy);
     if (rc) return rc;
+    if ((rc = check_residual(residual, ldr, N))) return rc;
     if (!w_colsum || !ws) return MQ_ERR_BAD_ARG;
     if ((act_scale == nullptr) != (act_zp == nullptr)) return MQ_ERR_BAD_ARG;
     if (!aligned(w_colsum, 16) || !aligned(ws, 256) || (acc_debug && !aligned(acc_debug, 16))) return MQ_ERR_BAD_ARG;
@@ -71,7 +80,7 @@ static int qlinear_a8(const void* x, int M, int K, int ldx, RowMap in_map, const
                           act_scale_out, act_zp_out, st);
     if (rc) return rc;
     return launch_gemm_a8(w.a8, w.rowsum, w.params, M, K, packed, N, w_bits, w_signed, w_scale, w_zp, w_colsum, bias,
-                          y, ldy, out_map, acc_debug, st);
+                          y, ldy, out_map, acc_debug, residual, ldr, st);
 }
 }  // namespace mq
 
@@ -144,13 +153,15 @@ int mq_unpack_weights(const void* packed, int N, int K, int bits, int layout, ui
 
 int mq_qlinear_w_only(const void* x, int M, int K, int ldx, const void* packed, int N, int bits, int layout,
                       const float* w_scale, const int32_t* w_zp, const void* bias, void* y, int ldy, int dtype,
-                      void* stream) {
+                      const void* residual, int ldr, void* stream) {
     if (!bits_ok16(bits)) return MQ_ERR_UNSUPPORTED_BITS;
     if (dtype != MQ_F16 && dtype != MQ_BF16) return MQ_ERR_BAD_ARG;
     int rc = check_linear_common(x, M, K, ldx, packed, N, layout, w_scale, w_zp, bias, y, ldy, bits != 16);
     if (rc) return rc;
+    if ((rc = check_residual(residual, ldr, N))) return rc;
     if (bits == 16) w_scale = nullptr, w_zp = nullptr;  // 16-bit weights are used as they are
-    return launch_gemm_w_only(x, M, K, ldx, packed, N, bits, w_scale, w_zp, bias, y, ldy, dtype, (hipStream_t)stream);
+    return launch_gemm_w_only(x, M, K, ldx, packed, N, bits, w_scale, w_zp, bias, y, ldy, dtype, residual, ldr,
+                              (hipStream_t)stream);
 }
 
 size_t mq_a8_row_bytes(int K) { return K > 0 ? ((size_t)K + 127) / 128 * 128 : 0; }
@@ -195,7 +206,7 @@ int mq_qlinear_w_only_geglu(const void* x, int M, int K, int ldx, const void* pa
 int mq_qlinear_a8_codes(const int8_t* a8, int M, int K, int lda, const float* act_scale, const int32_t* act_zp,
                         const void* packed, int N, int w_bits, int layout, int w_signed, const float* w_scale,
                         const int32_t* w_zp, const int32_t* w_colsum, const void* bias, void* y, int ldy,
-                        int32_t* acc_debug, void* stream) {
+                        int32_t* acc_debug, const void* residual, int ldr, void* stream) {
     if (w_bits != 4 && w_bits != 8) return MQ_ERR_UNSUPPORTED_BITS;
     if (!a8 || !act_scale || !act_zp || !packed || !w_scale || !w_zp || !w_colsum || !y) return MQ_ERR_BAD_ARG;
     if (M <= 0 || K <= 0 || N <= 0 || ldy < N) return MQ_ERR_BAD_SHAPE;
@@ -208,8 +219,9 @@ int mq_qlinear_a8_codes(const int8_t* a8, int M, int K, int lda, const float* ac
         (acc_debug && !aligned(acc_debug, 16)))
         return MQ_ERR_BAD_ARG;
     if ((long)255 * 255 * K >= (1L << 31)) return MQ_ERR_OVERFLOW_RISK;
+    if (int rc = check_residual(residual, ldr, N)) return rc;
     return launch_gemm_a8_codes(a8, lda, act_scale, act_zp, M, K, packed, N, w_bits, w_signed ? 1 : 0, w_scale, w_zp,
-                                w_colsum, bias, y, ldy, acc_debug, (hipStream_t)stream);
+                                w_colsum, bias, y, ldy, acc_debug, residual, ldr, (hipStream_t)stream);
 }
 
 static int check_conv_common(const void* x, int B, int H, int W, int Cin, const void* packed, int N, int layout,
@@ -228,11 +240,14 @@ static int check_conv_common(const void* x, int B, int H, int W, int Cin, const 
 }
 
 int mq_conv3x3_w_only(const void* x, int B, int H, int W, int Cin, const void* packed, int N, int bits, int layout,
-                      const float* w_scale, const int32_t* w_zp, const void* bias, void* y, void* stream) {
+                      const float* w_scale, const int32_t* w_zp, const void* bias, void* y, const void* residual,
+                      void* stream) {
     if (!bits_ok(bits)) return MQ_ERR_UNSUPPORTED_BITS;
     int rc = check_conv_common(x, B, H, W, Cin, packed, N, layout, w_scale, w_zp, bias, y);
     if (rc) return rc;
-    return launch_conv3x3_w_only(x, B, H, W, Cin, packed, N, bits, w_scale, w_zp, bias, y, (hipStream_t)stream);
+    if ((rc = check_residual(residual, N, N))) return rc;
+    return launch_conv3x3_w_only(x, B, H, W, Cin, packed, N, bits, w_scale, w_zp, bias, y, residual,
+                                 (hipStream_t)stream);
 }
 
 int mq_conv_tap_sums(const uint8_t* codes, int N, int Cin, int bits, int codes_signed, int32_t* tapsum, void* stream) {
@@ -251,11 +266,12 @@ size_t mq_conv3x3_a8_workspace_bytes(int B, int H, int W, int Cin) {
 int mq_conv3x3_a8(const void* x, int B, int H, int W, int Cin, const void* packed, int N, int w_bits, int layout,
                   int w_signed, const float* w_scale, const int32_t* w_zp, const int32_t* w_colsum,
                   const int32_t* w_tapsum, const float* act_scale, const int32_t* act_zp, const void* bias, void* y,
-                  int32_t* acc_debug, float* act_scale_out, int32_t* act_zp_out, void* ws, size_t ws_bytes,
-                  void* stream) {
+                  int32_t* acc_debug, const void* residual, float* act_scale_out, int32_t* act_zp_out, void* ws,
+                  size_t ws_bytes, void* stream) {
     if (w_bits != 4 && w_bits != 8) return MQ_ERR_UNSUPPORTED_BITS;
     int rc = check_conv_common(x, B, H, W, Cin, packed, N, layout, w_scale, w_zp, bias, y);
     if (rc) return rc;
+    if ((rc = check_residual(residual, N, N))) return rc;
     if (!w_colsum || !w_tapsum || !ws) return MQ_ERR_BAD_ARG;
     if ((act_scale == nullptr) != (act_zp == nullptr)) return MQ_ERR_BAD_ARG;
     if (!aligned(w_colsum, 16) || !aligned(w_tapsum, 4) || !aligned(ws, 256) || (acc_debug && !aligned(acc_debug, 16)))
@@ -270,7 +286,7 @@ int mq_conv3x3_a8(const void* x, int B, int H, int W, int Cin, const void* packe
                           act_scale_out, act_zp_out, st);
     if (rc) return rc;
     return launch_conv3x3_a8(w.a8, w.params, B, H, W, Cin, packed, N, w_bits, w_signed ? 1 : 0, w_scale, w_zp, w_colsum,
-                             w_tapsum, bias, y, acc_debug, st);
+                             w_tapsum, bias, y, acc_debug, residual, st);
 }
 
 size_t mq_qlinear_a8_workspace_bytes(int M, int K) {
@@ -280,20 +296,21 @@ size_t mq_qlinear_a8_workspace_bytes(int M, int K) {
 
 int mq_qlinear_w8a8(const void* x, int M, int K, int ldx, const void* packed, int N, int layout, int w_signed,
                     const float* w_scale, const int32_t* w_zp, const int32_t* w_colsum, const float* act_scale,
-                    const int32_t* act_zp, const void* bias, void* y, int ldy, int32_t* acc_debug, float* act_scale_out,
-                    int32_t* act_zp_out, void* ws, size_t ws_bytes, void* stream) {
+                    const int32_t* act_zp, const void* bias, void* y, int ldy, int32_t* acc_debug,
+                    const void* residual, int ldr, float* act_scale_out, int32_t* act_zp_out, void* ws, size_t ws_bytes,
+                    void* stream) {
     return qlinear_a8(x, M, K, ldx, RowMap{0, 0, 0}, packed, N, layout, 8, w_signed ? 1 : 0, w_scale, w_zp, w_colsum,
                       act_scale, act_zp, bias, y, ldy, RowMap{0, 0, 0}, acc_debug, act_scale_out, act_zp_out, ws,
-                      ws_bytes, (hipStream_t)stream);
+                      ws_bytes, residual, ldr, (hipStream_t)stream);
 }
 
 int mq_qlinear_w4a8(const void* x, int M, int K, int ldx, const void* packed, int N, int layout, const float* w_scale,
                     const int32_t* w_zp, const int32_t* w_colsum, const float* act_scale, const int32_t* act_zp,
-                    const void* bias, void* y, int ldy, int32_t* acc_debug, float* act_scale_out, int32_t* act_zp_out,
-                    void* ws, size_t ws_bytes, void* stream) {
+                    const void* bias, void* y, int ldy, int32_t* acc_debug, const void* residual, int ldr,
+                    float* act_scale_out, int32_t* act_zp_out, void* ws, size_t ws_bytes, void* stream) {
     return qlinear_a8(x, M, K, ldx, RowMap{0, 0, 0}, packed, N, layout, 4, 0, w_scale, w_zp, w_colsum, act_scale,
                       act_zp, bias, y, ldy, RowMap{0, 0, 0}, acc_debug, act_scale_out, act_zp_out, ws, ws_bytes,
-                      (hipStream_t)stream);
+                      residual, ldr, (hipStream_t)stream);
 }
 
 size_t mq_bos_aware_kv_proj_workspace_bytes(int B, int T, int K) {
@@ -313,7 +330,7 @@ int mq_bos_aware_kv_proj(const void* ctx, int B, int T, int K, const void* packe
     if (naive_all_rows)
         return qlinear_a8(ctx, B * T, K, K, RowMap{0, 0, 0}, packed, N, layout, w_bits, w_signed ? 1 : 0, w_scale, w_zp,
                           w_colsum, act_scale, act_zp, bias, y, N, RowMap{0, 0, 0}, nullptr, act_scale_out, act_zp_out,
-                          ws, ws_bytes, st);
+                          ws, ws_bytes, nullptr, 0, st);
     if ((w_f16 == nullptr) == (bos_out == nullptr)) return MQ_ERR_BAD_ARG;
     if (w_f16 && !aligned(w_f16, 16)) return MQ_ERR_BAD_ARG;
     if (ws_bytes < mq_bos_aware_kv_proj_workspace_bytes(B, T, K)) return MQ_ERR_WORKSPACE_TOO_SMALL;
@@ -321,7 +338,7 @@ int mq_bos_aware_kv_proj(const void* ctx, int B, int T, int K, const void* packe
         const RowMap body{T - 1, T, 1};  // logical row r -> token 1 + r % (T-1) of prompt r / (T-1)
         int rc = qlinear_a8(ctx, B * (T - 1), K, K, body, packed, N, layout, w_bits, w_signed ? 1 : 0, w_scale, w_zp,
                             w_colsum, act_scale, act_zp, bias, y, N, body, nullptr, act_scale_out, act_zp_out, ws,
-                            ws_bytes, st);
+                            ws_bytes, nullptr, 0, st);
         if (rc) return rc;
     } else {
         int rc = check_linear_common(ctx, B, K, K, packed, N, layout, w_scale, w_zp, bias, y, N);

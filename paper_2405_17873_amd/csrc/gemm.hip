@@ -352,6 +352,9 @@ struct GemmArgs {
     int conv_cpt;            // 64-channel chunks per filter tap (Cin / 64)
     uint32_t conv_cpt_inv;   // ceil(2^32 / conv_cpt) for conv_cpt > 1
     const int32_t* w_tapsum; // MODE 4: [9][N] sums of the weight codes per filter tap
+    // optional residual [M, ldr] (16-bit, the dtype of y; rows as the rows of y): added in fp32 before the rounding
+    const uint16_t* res;
+    long ldr;
 };
 
 // Workgroup id -> tile.  Consecutive workgroup ids land on different XCDs (8 of them, each with its own L2),
@@ -402,13 +405,15 @@ struct GemmPlan {
 // channel tile is a value tile, its second the gate tile of the same 32 columns, and the epilogue emits
 // value * gelu(gate) as 8-bit codes for the next integer GEMM.  MODE 2 (int8): the activations arrive as codes with
 // their parameters; the row sums the epilogue needs are accumulated in the main loop.
-template <bool I8, int BITS, int WGM, int WGN, int TM, int TN, int S, int KS, bool BF = false, int MODE = 0>
+template <bool I8, int BITS, int WGM, int WGN, int TM, int TN, int S, int KS, bool BF = false, int MODE = 0,
+          bool RES = false>
 __global__ __launch_bounds__(WGM* WGN* KS * 64,
                              (TM * TN <= 8 && GemmPlan<I8, BITS, WGM, WGN, TM, TN, S, KS>::LDS_BYTES <= 80 * 1024) ? 2 : 1)
 void gemm_kernel(const GemmArgs g) {
     static_assert(!(I8 && BF), "the int8 path writes fp16");
     constexpr bool GEGLU = MODE == 1, RS_INLINE = MODE == 2 || MODE == 4, CONV = MODE == 3 || MODE == 4;
     static_assert(MODE == 0 || KS == 1, "the special modes have no in-workgroup k split");
+    static_assert(!(RES && MODE == 1), "the gated projection takes no residual");
     static_assert((MODE != 2 && MODE != 4) || I8, "int8 modes");
     static_assert(MODE != 3 || !I8, "MODE 3 is the weight-only convolution");
     static_assert(!GEGLU || TN == 2, "value tile and gate tile per wave");
@@ -945,7 +950,31 @@ void gemm_kernel(const GemmArgs g) {
     uint8_t* ep = lds + (SPLIT_EPI ? wv : wvg) * EP_BYTES;
     const int nw0 = n0 + wn * TN * 32;  // first channel of this wave
 
-    auto store_cols = [&](auto tn0_c, auto gs_c, int tm) {
+    // Residual pieces arrive in the accumulator layout (8 bytes per lane: four channels of the lane's row), all of a
+    // 32-row slab at once and, where a wave stores several slabs, one slab ahead of the stores.
+    auto load_res = [&](int tm, half4 (&dst)[G0][4]) {
+        const int m = m0 + (wm * TM + tm) * 32 + l31;
+        long rr = m;
+        if constexpr (I8) rr = g.out_map.phys(m);
+#pragma unroll
+        for (int tn = 0; tn < G0; ++tn)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int n = nw0 + tn * 32 + 8 * q + 4 * kb;
+                half4 z = {0, 0, 0, 0};
+                dst[tn][q] = m < g.M && n < g.N ? *(const half4*)(g.res + rr * g.ldr + n) : z;
+            }
+    };
+    auto res_f32 = [&](_Float16 h) -> float {
+        if constexpr (BF)
+            return __builtin_bit_cast(float, (uint32_t)__builtin_bit_cast(uint16_t, h) << 16);
+        else
+            return (float)h;
+    };
+    // RES: a residual operand is present.  A kernel of its own, so that calls without one pay nothing for it.
+    constexpr bool has_res = RES;
+
+    auto store_cols = [&](auto tn0_c, auto gs_c, int tm, const half4 (&rs)[G0][4]) {
         constexpr int TN0 = decltype(tn0_c)::value, GS = decltype(gs_c)::value;
         constexpr int CPR = GS * 4;              // 16-byte chunks per staged row
         constexpr int ROWS_PER_PASS = 64 / CPR;  // rows one store instruction covers
@@ -956,7 +985,11 @@ void gemm_kernel(const GemmArgs g) {
             for (int q = 0; q < 4; ++q) {
                 const int cl = (wn * TN + tn) * 32 + 8 * q + 4 * kb;  // channel inside the workgroup tile
                 const float4v mul = *(const float4v*)(ch_mul + cl);
-                const float4v add = *(const float4v*)(ch_add + cl);
+                float4v add = *(const float4v*)(ch_add + cl);
+                if constexpr (has_res) {  // joins the bias term
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) add[r] += res_f32(rs[tn - TN0][q][r]);
+                }
                 half4 o;
                 if constexpr (I8) {
                     const int4v dw = *(const int4v*)(ch_dw + cl);
@@ -1019,10 +1052,20 @@ void gemm_kernel(const GemmArgs g) {
         }
         __builtin_amdgcn_wave_barrier();
     };
+    constexpr bool RES_AHEAD = KS == 1 && TM > 1;
+    half4 rs[2][G0][4] = {};
+    if constexpr (RES_AHEAD && has_res) load_res(0, rs[0]);
 #pragma unroll
     for (int tm = 0; tm < TM; ++tm) {
         if (KS > 1 && owner(tm) != grp) continue;  // the finished sums of this slab live in the other group
-        store_cols(std::integral_constant<int, 0>{}, std::integral_constant<int, G0>{}, tm);
+        if constexpr (has_res) {
+            if constexpr (RES_AHEAD) {
+                if (tm + 1 < TM) load_res(tm + 1, rs[(tm + 1) & 1]);
+            } else {
+                load_res(tm, rs[tm & 1]);
+            }
+        }
+        store_cols(std::integral_constant<int, 0>{}, std::integral_constant<int, G0>{}, tm, rs[tm & 1]);
     }
     }
     if (g.phase_clk && threadIdx.x == 0) {
@@ -1132,8 +1175,8 @@ constexpr int pick_stages(int budget, int max_stages) {
     return 2;
 }
 
-template <bool I8, int BITS, int WGM, int WGN, int TM, int TN, int KS, int BUDGET, int MAXS, bool BF = false, int MODE = 0>
-static int run_gemm(GemmArgs& g, int tile_index, hipStream_t st) {
+template <bool I8, int BITS, int WGM, int WGN, int TM, int TN, int KS, int BUDGET, int MAXS, bool BF, int MODE, bool RES>
+static int run_gemm_r(GemmArgs& g, int tile_index, hipStream_t st) {
     constexpr int S = pick_stages<I8, BITS, WGM, WGN, TM, TN, KS>(BUDGET, MAXS);
     using P = GemmPlan<I8, BITS, WGM, WGN, TM, TN, S, KS>;
     static_assert(P::LDS_BYTES <= 160 * 1024, "LDS plan exceeds the compute unit");
@@ -1157,7 +1200,7 @@ static int run_gemm(GemmArgs& g, int tile_index, hipStream_t st) {
     if (MODE == 0 && TM * TN <= 4 && splits > 1 && take_split_scratch((size_t)tiles * splits * P::BM * P::BN * 4, (int)tiles, &g.partial, &g.counters))
         g.splits = splits;
     g.phase_clk = (tiles * g.splits <= g_phase_cap) ? g_phase_clk : nullptr;
-    auto kern = gemm_kernel<I8, BITS, WGM, WGN, TM, TN, S, KS, BF, MODE>;
+    auto kern = gemm_kernel<I8, BITS, WGM, WGN, TM, TN, S, KS, BF, MODE, RES>;
     // Once per instantiation and device (callers may be on several host threads): allow more than 64 KB of dynamic
     // LDS, name the profiling slot.
     const int slot = prof_gemm_slot(MODE ? 2 + MODE : (I8 ? 1 : (BF ? 2 : 0)), BITS, tile_index);
@@ -1173,8 +1216,9 @@ static int run_gemm(GemmArgs& g, int tile_index, hipStream_t st) {
                 set_hip_error((int)hipGetLastError());
                 return MQ_ERR_HIP;
             }
-            char name[96];
-            snprintf(name, sizeof name, "mq::gemm_kernel<%s, %d, %d, %d, %d, %d, %d, %d, %s, %d>",
+            // (the residual variant shares the slot of the plain kernel and leaves the slot's name to it)
+            char name[112];
+            snprintf(name, sizeof name, "mq::gemm_kernel<%s, %d, %d, %d, %d, %d, %d, %d, %s, %d, false>",
                      I8 ? "true" : "false", BITS, WGM, WGN, TM, TN, S, KS, BF ? "true" : "false", MODE);
             prof_name_slot(slot, name);
             prepared[dev] = true;
@@ -1188,6 +1232,13 @@ static int run_gemm(GemmArgs& g, int tile_index, hipStream_t st) {
     hipLaunchKernelGGL(kern, dim3(g.tiles_m * g.tiles_n * g.splits), dim3(P::NT), P::LDS_BYTES, st, g);
     MQ_HIP_CHECK_LAUNCH();
     return MQ_OK;
+}
+
+template <bool I8, int BITS, int WGM, int WGN, int TM, int TN, int KS, int BUDGET, int MAXS, bool BF = false, int MODE = 0>
+static int run_gemm(GemmArgs& g, int tile_index, hipStream_t st) {
+    if constexpr (MODE != 1)
+        if (g.res) return run_gemm_r<I8, BITS, WGM, WGN, TM, TN, KS, BUDGET, MAXS, BF, MODE, true>(g, tile_index, st);
+    return run_gemm_r<I8, BITS, WGM, WGN, TM, TN, KS, BUDGET, MAXS, BF, MODE, false>(g, tile_index, st);
 }
 
 template <bool I8, int BITS>
@@ -1219,7 +1270,7 @@ static int dispatch_gemm_bf16(GemmArgs& g, hipStream_t st) {
 
 int launch_gemm_w_only(const void* x, int M, int K, int ldx, const void* packed, int N, int bits,
                        const float* w_scale, const int32_t* w_zp, const void* bias, void* y, int ldy, int dtype,
-                       hipStream_t st) {
+                       const void* res, int ldr, hipStream_t st) {
     GemmArgs g{};
     g.a = x;
     g.a_row_bytes = (long)ldx * 2;
@@ -1230,6 +1281,7 @@ int launch_gemm_w_only(const void* x, int M, int K, int ldx, const void* packed,
     g.k_stages = K / 64;
     g.w_scale = w_scale; g.w_zp = w_zp; g.bias = (const uint16_t*)bias;
     g.y = (uint16_t*)y; g.ldy = ldy;
+    g.res = (const uint16_t*)res; g.ldr = ldr;
     if (dtype == MQ_BF16) {
         switch (bits) {
             case 2: return dispatch_gemm_bf16<2>(g, st);
@@ -1253,7 +1305,7 @@ int launch_gemm_w_only(const void* x, int M, int K, int ldx, const void* packed,
 int launch_gemm_a8(const int8_t* a8, const int32_t* rowsum, const ActParams* params, int M, int K,
                    const void* packed, int N, int w_bits, int w_signed, const float* w_scale, const int32_t* w_zp,
                    const int32_t* w_colsum, const void* bias, void* y, int ldy, RowMap out_map, int32_t* acc_debug,
-                   hipStream_t st) {
+                   const void* res, int ldr, hipStream_t st) {
     const int Kp = (K + 127) / 128 * 128;
     GemmArgs g{};
     g.a = a8;
@@ -1265,6 +1317,7 @@ int launch_gemm_a8(const int8_t* a8, const int32_t* rowsum, const ActParams* par
     g.k_stages = Kp / 128;
     g.w_scale = w_scale; g.w_zp = w_zp; g.bias = (const uint16_t*)bias;
     g.y = (uint16_t*)y; g.ldy = ldy;
+    g.res = (const uint16_t*)res; g.ldr = ldr;
     g.rowsum = rowsum; g.params = params; g.w_colsum = w_colsum;
     g.out_map = out_map; g.acc_debug = acc_debug;
     if (w_bits == 4) {
@@ -1350,7 +1403,7 @@ int launch_gemm_w_only_geglu(const void* x, int M, int K, int ldx, const void* p
 int launch_gemm_a8_codes(const int8_t* a8, long lda, const float* act_scale, const int32_t* act_zp, int M, int K,
                          const void* packed, int N, int w_bits, int w_signed, const float* w_scale, const int32_t* w_zp,
                          const int32_t* w_colsum, const void* bias, void* y, int ldy, int32_t* acc_debug,
-                         hipStream_t st) {
+                         const void* res, int ldr, hipStream_t st) {
     const int Kp = (K + 127) / 128 * 128;
     GemmArgs g{};
     g.a = a8;
@@ -1362,6 +1415,7 @@ int launch_gemm_a8_codes(const int8_t* a8, long lda, const float* act_scale, con
     g.k_stages = Kp / 128;
     g.w_scale = w_scale; g.w_zp = w_zp; g.bias = (const uint16_t*)bias;
     g.y = (uint16_t*)y; g.ldy = ldy;
+    g.res = (const uint16_t*)res; g.ldr = ldr;
     g.w_colsum = w_colsum;
     g.act_scale_p = act_scale; g.act_zp_p = act_zp;
     g.acc_debug = acc_debug;
@@ -1414,7 +1468,8 @@ static int dispatch_conv_w_only(GemmArgs& g, hipStream_t st) {
 }
 
 int launch_conv3x3_w_only(const void* x, int B, int H, int W, int Cin, const void* packed, int N, int bits,
-                          const float* w_scale, const int32_t* w_zp, const void* bias, void* y, hipStream_t st) {
+                          const float* w_scale, const int32_t* w_zp, const void* bias, void* y, const void* res,
+                          hipStream_t st) {
     GemmArgs g{};
     g.a = x;
     conv_args(g, B, H, W, Cin, (long)Cin * 2);
@@ -1424,6 +1479,7 @@ int launch_conv3x3_w_only(const void* x, int B, int H, int W, int Cin, const voi
     g.k_stages = g.K / 64;
     g.w_scale = w_scale; g.w_zp = w_zp; g.bias = (const uint16_t*)bias;
     g.y = (uint16_t*)y; g.ldy = N;
+    g.res = (const uint16_t*)res; g.ldr = N;
     switch (bits) {
         case 2: return dispatch_conv_w_only<2>(g, st);
         case 3: return dispatch_conv_w_only<3>(g, st);
@@ -1435,7 +1491,8 @@ int launch_conv3x3_w_only(const void* x, int B, int H, int W, int Cin, const voi
 
 int launch_conv3x3_a8(const int8_t* a8, const ActParams* params, int B, int H, int W, int Cin, const void* packed, int N,
                       int w_bits, int w_signed, const float* w_scale, const int32_t* w_zp, const int32_t* w_colsum,
-                      const int32_t* w_tapsum, const void* bias, void* y, int32_t* acc_debug, hipStream_t st) {
+                      const int32_t* w_tapsum, const void* bias, void* y, int32_t* acc_debug, const void* res,
+                      hipStream_t st) {
     GemmArgs g{};
     g.a = a8;
     conv_args(g, B, H, W, Cin, (long)(Cin + 127) / 128 * 128);
@@ -1445,6 +1502,7 @@ int launch_conv3x3_a8(const int8_t* a8, const ActParams* params, int B, int H, i
     g.k_stages = (g.K + 127) / 128;
     g.w_scale = w_scale; g.w_zp = w_zp; g.bias = (const uint16_t*)bias;
     g.y = (uint16_t*)y; g.ldy = N;
+    g.res = (const uint16_t*)res; g.ldr = N;
     g.w_colsum = w_colsum; g.w_tapsum = w_tapsum;
     g.act_scale_p = &params->scale; g.act_zp_p = &params->zp;
     g.acc_debug = acc_debug;

@@ -79,12 +79,12 @@ int act_quant_partial_slots();
 
 int launch_gemm_w_only(const void* x, int M, int K, int ldx, const void* packed, int N, int bits,
                        const float* w_scale, const int32_t* w_zp, const void* bias, void* y, int ldy, int dtype,
-                       hipStream_t st);
+                       const void* res, int ldr, hipStream_t st);
 
 int launch_gemm_a8(const int8_t* a8, const int32_t* rowsum, const ActParams* params, int M, int K,
                    const void* packed, int N, int w_bits, int w_signed, const float* w_scale, const int32_t* w_zp,
                    const int32_t* w_colsum, const void* bias, void* y, int ldy, RowMap out_map, int32_t* acc_debug,
-                   hipStream_t st);
+                   const void* res, int ldr, hipStream_t st);
 
 int launch_gemm_a8_geglu(const int8_t* a8, const int32_t* rowsum, const ActParams* params, int M, int K,
                          const void* packed, int H, int w_bits, int w_signed, const float* w_scale, const int32_t* w_zp,
@@ -96,13 +96,15 @@ int launch_gemm_w_only_geglu(const void* x, int M, int K, int ldx, const void* p
 int launch_gemm_a8_codes(const int8_t* a8, long lda, const float* act_scale, const int32_t* act_zp, int M, int K,
                          const void* packed, int N, int w_bits, int w_signed, const float* w_scale, const int32_t* w_zp,
                          const int32_t* w_colsum, const void* bias, void* y, int ldy, int32_t* acc_debug,
-                         hipStream_t st);
+                         const void* res, int ldr, hipStream_t st);
 
 int launch_conv3x3_w_only(const void* x, int B, int H, int W, int Cin, const void* packed, int N, int bits,
-                          const float* w_scale, const int32_t* w_zp, const void* bias, void* y, hipStream_t st);
+                          const float* w_scale, const int32_t* w_zp, const void* bias, void* y, const void* res,
+                          hipStream_t st);
 int launch_conv3x3_a8(const int8_t* a8, const ActParams* params, int B, int H, int W, int Cin, const void* packed, int N,
                       int w_bits, int w_signed, const float* w_scale, const int32_t* w_zp, const int32_t* w_colsum,
-                      const int32_t* w_tapsum, const void* bias, void* y, int32_t* acc_debug, hipStream_t st);
+                      const int32_t* w_tapsum, const void* bias, void* y, int32_t* acc_debug, const void* res,
+                      hipStream_t st);
 int launch_tap_sums(const uint8_t* codes, int N, int Cin, int bits, int codes_signed, int32_t* tapsum, hipStream_t st);
 
 void set_force_tile(int t);

@@ -70,7 +70,8 @@ def test_error_codes_without_a_gpu(lib):
     assert lib.mq_unpack_weights(p, 4, 64, 6, 1, p, st) == -3
     # w_only
     args = lambda **o: [o.get("x", p), o.get("M", 8), o.get("K", 64), o.get("ldx", 64), p, o.get("N", 32),
-                        o.get("bits", 4), o.get("layout", 1), p, p, null, p, o.get("ldy", 32), 0, st]
+                        o.get("bits", 4), o.get("layout", 1), p, p, null, p, o.get("ldy", 32), 0, o.get("res", null),
+                        o.get("ldr", 0), st]
     assert lib.mq_qlinear_w_only(*args(x=null)) == -1
     assert lib.mq_qlinear_w_only(*args(bits=5)) == -3
     assert lib.mq_qlinear_w_only(*args(K=96, ldx=96)) == -2
@@ -78,15 +79,20 @@ def test_error_codes_without_a_gpu(lib):
     assert lib.mq_qlinear_w_only(*args(ldx=32)) == -2
     assert lib.mq_qlinear_w_only(*args(layout=0)) == -6
     assert lib.mq_qlinear_w_only(*args(x=C.c_void_p(p.value + 2))) == -1  # misaligned
+    assert lib.mq_qlinear_w_only(*args(res=p, ldr=16)) == -2              # residual rows shorter than N
+    assert lib.mq_qlinear_w_only(*args(res=p, ldr=34)) == -2
+    assert lib.mq_qlinear_w_only(*args(res=C.c_void_p(p.value + 4), ldr=32)) == -1
     # a8
     a8 = lambda **o: [p, 8, o.get("K", 64), o.get("K", 64), p, 32, 1, 1, p, p, o.get("colsum", p),
-                      o.get("a_s", null), o.get("a_z", null), null, p, 32, null, null, null, o.get("ws", p),
+                      o.get("a_s", null), o.get("a_z", null), null, p, 32, null, o.get("res", null), o.get("ldr", 0), null,
+                      null, o.get("ws", p),
                       C.c_size_t(o.get("wsb", 1 << 20)), st]
     assert lib.mq_qlinear_w8a8(*a8(colsum=null)) == -1
     assert lib.mq_qlinear_w8a8(*a8(a_s=p)) == -1       # scale without zero point
     assert lib.mq_qlinear_w8a8(*a8(wsb=16)) == -4
     assert lib.mq_qlinear_w8a8(*a8(K=33088)) == -7     # 255*255*K >= 2^31
     assert lib.mq_qlinear_w8a8(*a8(ws=null)) == -1
+    assert lib.mq_qlinear_w8a8(*a8(res=p, ldr=8)) == -2
     # bos
     bos = lambda **o: [p, o.get("B", 2), 5, 64, p, 32, o.get("wb", 8), 1, 1, p, p, p, o.get("wf", null),
                        o.get("bo", null), null, null, null, p, 0, null, null, p, C.c_size_t(1 << 20), st]

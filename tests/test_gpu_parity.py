@@ -599,6 +599,187 @@ def test_conv_a8(mq, orc, bits, sym, tile):
         mq.tune_force_tile(-1)
 
 
+# ----------------------------------------------------------------------------------------------- residual operand
+
+RES_SHAPES = [(256, 320, 320), (77, 128, 40), (513, 192, 264), (300, 640, 640), (1, 64, 32)]
+
+
+@pytest.mark.parametrize("tile", (-1, 0, 1, 2, 3, 4))
+def test_residual_weight_only(mq, orc, tile):
+    """y = linear(x) + residual with one rounding; the residual as its own tensor, as a strided view, and as the
+    output tensor itself (in place)."""
+    mq.tune_force_tile(tile)
+    try:
+        for bits in (4, 8):
+            for (M, K, N) in RES_SHAPES:
+                x = si.activations_f16(81, f"rs/x{M}x{K}", M, K)
+                w = si.weights_f16(81, f"rs/w{N}x{K}", N, K)
+                b = si.bias_f16(81, f"rs/b{N}", N)
+                r = si.normal(81, f"rs/r{M}x{N}", (M, N)).astype(np.float16)
+                pw, oc, os_, oz = make_weight(mq, orc, w, bits)
+                ref = orc.linear_w_only(x, oc, os_, oz, b, residual=r)
+                what = f"res w{bits} tile{tile} {M}x{K}x{N}"
+                assert_close16(host(mq.qlinear_w_only(dev(x), pw, dev(b), residual=dev(r))), ref, what)
+                wide = torch.zeros((M, N + 24), dtype=torch.float16, device="cuda")
+                wide[:, 8:8 + N] = dev(r)
+                assert_close16(host(mq.qlinear_w_only(dev(x), pw, dev(b), residual=wide[:, 8:8 + N])), ref, what + " view")
+                inplace = dev(r).clone()
+                mq.qlinear_w_only(dev(x), pw, dev(b), out=inplace, residual=inplace)
+                assert_close16(host(inplace), ref, what + " in place")
+    finally:
+        mq.tune_force_tile(-1)
+
+
+def test_residual_is_added_before_the_rounding(mq, orc):
+    """Integers: linear part up to about 2^13 (fp16 spacing 4 to 8 there), residual in [-3, 3]; rounding the linear
+    part first and adding afterwards gives other numbers, the fp32 sum rounded once is the oracle's, bit for bit."""
+    rng = np.random.default_rng(9)
+    M, K, N = 160, 256, 96
+    x = rng.integers(0, 9, (M, K)).astype(np.float16)
+    codes = rng.integers(0, 16, (N, K)).astype(np.uint8)
+    zp = np.full(N, 3, np.int32)
+    one = np.ones(N, np.float32)
+    r = rng.integers(-3, 4, (M, N)).astype(np.float16)
+    packed, cs = mq.pack_weights(dev(codes), 4, mq.LAYOUT_KERNEL)
+    pw = mq.PackedWeight(packed, dev(one), dev(zp), cs, N, K, 4, mq.LAYOUT_KERNEL, False)
+    ref = orc.linear_w_only(x, codes, one, zp, None, residual=r).view(np.float16)
+    lin = x.astype(np.int64) @ (codes.astype(np.int64) - 3).T
+    assert np.array_equal(ref, (lin + r.astype(np.int64)).astype(np.float16))
+    twice = (lin.astype(np.float16) + r).astype(np.float16)
+    assert (twice != ref).any()
+    for tile in (-1, 0, 1, 2, 3, 4):
+        mq.tune_force_tile(tile)
+        try:
+            assert np.array_equal(host(mq.qlinear_w_only(dev(x), pw, residual=dev(r))), ref), tile
+        finally:
+            mq.tune_force_tile(-1)
+
+
+def test_residual_bf16_and_unquantised_layer(mq, orc):
+    M, K, N = 200, 256, 136
+    bits16 = lambda t: t.view(torch.int16).numpy().view(np.uint16)
+    f32 = lambda name, shape, std: torch.from_numpy(si.normal(82, name, shape, std).astype(np.float32))
+    xb, wb = f32("rb/x", (M, K), 1.0).to(torch.bfloat16), f32("rb/w", (N, K), 0.03).to(torch.bfloat16)
+    rb = f32("rb/r", (M, N), 1.0).to(torch.bfloat16)
+    c, s, z = mq.quantize_weights(wb.cuda(), 4)
+    oc, os_, oz = orc.quantize_weights(bits16(wb), 4, dtype=orc.BF16)
+    packed, cs = mq.pack_weights(c, 4, mq.LAYOUT_KERNEL)
+    pw = mq.PackedWeight(packed, s, z, cs, N, K, 4, mq.LAYOUT_KERNEL, False)
+    y = mq.qlinear_w_only(xb.cuda(), pw, residual=rb.cuda())
+    ref = orc.linear_w_only(bits16(xb), oc, os_, oz, None, dtype=orc.BF16, residual=bits16(rb))
+    want = torch.from_numpy(ref.view(np.int16)).view(torch.bfloat16).float().numpy().astype(np.float64)
+    got = host(y.float()).astype(np.float64)
+    assert np.linalg.norm(got - want) / np.linalg.norm(want) <= FRO_TOL
+    assert np.abs(got - want).max() <= ELT_TOL * np.abs(want).max()
+    # a layer kept at 16 bits (fp16)
+    x = si.activations_f16(82, "rb/x16", M, K)
+    w = si.weights_f16(82, "rb/w16", N, K)
+    r = si.normal(82, "rb/r16", (M, N)).astype(np.float16)
+    pw16 = mq.keep_weights_16bit(dev(w))
+    assert_close16(host(mq.qlinear_w_only(dev(x), pw16, residual=dev(r))), orc.linear_fp(x, w, None, residual=r),
+                   "16-bit layer + residual")
+
+
+@pytest.mark.parametrize("mode", ("w8s", "w4"))
+@pytest.mark.parametrize("tile", (-1, 0, 1, 2, 3, 4))
+def test_residual_a8(mq, orc, mode, tile):
+    bits, sym = (8, True) if mode == "w8s" else (4, False)
+    mq.tune_force_tile(tile)
+    try:
+        for (M, K, N) in RES_SHAPES:
+            x = si.activations_f16(83, f"r8/x{M}x{K}", M, K, outlier_prob=0.01)
+            w = si.weights_f16(83, f"r8/w{N}x{K}", N, K)
+            b = si.bias_f16(83, f"r8/b{N}", N)
+            r = si.normal(83, f"r8/r{M}x{N}", (M, N)).astype(np.float16)
+            pw, oc, os_, oz = make_weight(mq, orc, w, bits, sym)
+            fn = mq.qlinear_w8a8 if bits == 8 else mq.qlinear_w4a8
+            y, acc, _ = fn(dev(x), pw, bias=dev(b), want_acc=True, residual=dev(r))
+            ry, racc, _ = orc.linear_a8(x, oc, os_, oz, w_signed=sym, bias=b, residual=r)
+            assert np.array_equal(host(acc), racc)
+            assert_close16(host(y), ry, f"res a8 {mode} tile{tile} {M}x{K}x{N}")
+    finally:
+        mq.tune_force_tile(-1)
+
+
+@pytest.mark.parametrize("parts", (0, 3))
+def test_residual_with_split_reduction(mq, orc, parts):
+    """The workgroup that arrives last at a split tile adds the residual once."""
+    mq.tune_force_splits(parts)
+    try:
+        for (M, K, N) in ((16, 1280, 320), (77, 2048, 1280), (130, 640, 96)):
+            x = si.activations_f16(84, f"rsp/x{M}x{K}", M, K)
+            w = si.weights_f16(84, f"rsp/w{N}x{K}", N, K)
+            r = si.normal(84, f"rsp/r{M}x{N}", (M, N)).astype(np.float16)
+            pw, oc, os_, oz = make_weight(mq, orc, w, 4)
+            assert_close16(host(mq.qlinear_w_only(dev(x), pw, residual=dev(r))),
+                           orc.linear_w_only(x, oc, os_, oz, None, residual=r), f"split res {M}x{K}x{N}")
+            y, acc, _ = mq.qlinear_w4a8(dev(x), pw, want_acc=True, residual=dev(r))
+            ry, racc, _ = orc.linear_a8(x, oc, os_, oz, residual=r)
+            assert np.array_equal(host(acc), racc)
+            assert_close16(host(y), ry, f"split res a8 {M}x{K}x{N}")
+    finally:
+        mq.tune_force_splits(-1)
+
+
+def test_feed_forward_output_linear_adds_the_skip_connection(mq, orc):
+    """The linear on 8-bit codes (second half of a feed-forward) with the block's skip connection as residual."""
+    M, K, N = 300, 1280, 320
+    rng = np.random.default_rng(85)
+    codes = rng.integers(0, 256, (M, K)).astype(np.uint8)
+    act = (np.float32(0.031), 117)
+    w = si.weights_f16(85, "rc/w", N, K)
+    b = si.bias_f16(85, "rc/b", N)
+    r = si.normal(85, "rc/r", (M, N)).astype(np.float16)
+    d_act = (dev(np.array([act[0]], np.float32)), dev(np.array([act[1]], np.int32)))
+    for bits, sym in ((8, True), (4, False)):
+        pw, oc, os_, oz = make_weight(mq, orc, w, bits, sym)
+        for tile in (-1, 1, 2):
+            mq.tune_force_tile(tile)
+            try:
+                y, acc = mq.qlinear_a8_codes(dev(a8_layout(codes)), K, d_act, pw, bias=dev(b), want_acc=True,
+                                             residual=dev(r))
+            finally:
+                mq.tune_force_tile(-1)
+            ry, racc = orc.linear_a8_codes(codes, act, oc, os_, oz, w_signed=sym, bias=b, residual=r)
+            assert np.array_equal(host(acc), racc)
+            assert_close16(host(y), ry, f"codes + residual b{bits} tile{tile}")
+
+
+@pytest.mark.parametrize("tile", (-1, 0, 1, 2))
+def test_conv_residual_and_split_shortcut(mq, orc, tile):
+    """Residual block tail (conv + skip), and the first convolution of an up block whose input is the channel
+    concatenation [trunk | shortcut], run as two convolutions with separate quantisation parameters (Sec. 4.1): the
+    second adds the first one's output, on the weight-only and on the 8-bit-activation path."""
+    mq.tune_force_tile(tile)
+    try:
+        for (B, H, W, C1, C2, N) in ((2, 8, 8, 128, 64, 64), (1, 16, 16, 320, 64, 320), (2, 5, 7, 64, 64, 40)):
+            if tile == 0 and B * H * W * N > 200000:
+                continue
+            xa = si.activations_f16(86, f"sp/xa{B}x{H}x{C1}", B * H * W, C1).reshape(B, H, W, C1)
+            xb = (3.0 * si.activations_f16(86, f"sp/xb{B}x{H}x{C2}", B * H * W, C2).astype(np.float32)).astype(
+                np.float16).reshape(B, H, W, C2)          # the shortcut has another range than the trunk
+            b = si.bias_f16(86, f"sp/b{N}", N)
+            what = f"tile{tile} {B}x{H}x{W} {C1}+{C2}->{N}"
+            pa, ca, sa, za, ta = conv_weight(mq, orc, 86, N, C1, 4)
+            pb, cb, sb, zb, tb = conv_weight(mq, orc, 87, N, C2, 8)
+            first = mq.conv3x3_w_only(dev(xa), pa, dev(b))
+            second = mq.conv3x3_w_only(dev(xb), pb, None, residual=first)
+            rfirst = orc.conv3x3_w_only(xa, ca, sa, za, b)
+            rsecond = orc.conv3x3_w_only(xb, cb, sb, zb, None, residual=rfirst.reshape(B, H, W, N))
+            assert_close16(host(second).reshape(-1, N), rsecond, "split weight-only " + what)
+            mq.conv3x3_w_only(dev(xb), pb, None, out=first, residual=first)     # in place
+            assert_close16(host(first).reshape(-1, N), rsecond, "split weight-only in place " + what)
+            if tile != 0:
+                y1, acc1, _ = mq.conv3x3_a8(dev(xa), pa, ta, bias=dev(b), want_acc=True)
+                y2, acc2, _ = mq.conv3x3_a8(dev(xb), pb, tb, want_acc=True, residual=y1)
+                r1, racc1, _ = orc.conv3x3_a8(xa, ca, sa, za, bias=b)
+                r2, racc2, _ = orc.conv3x3_a8(xb, cb, sb, zb, residual=r1.reshape(B, H, W, N))
+                assert np.array_equal(host(acc1), racc1) and np.array_equal(host(acc2), racc2)
+                assert_close16(host(y2).reshape(-1, N), r2, "split a8 " + what)
+    finally:
+        mq.tune_force_tile(-1)
+
+
 # ----------------------------------------------------------------------------------------------- BOS-aware K/V
 
 @pytest.mark.parametrize("N", (640, 1280))

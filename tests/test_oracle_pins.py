@@ -666,6 +666,16 @@ def test_residual_enters_the_sum_once_before_the_single_rounding(orc):
         r.astype(np.float64)
     assert np.array_equal(ya.view(np.float16), yf.astype(np.float16))
     assert np.array_equal(orc.linear_a8(x, c, s, z, bias=b, rows=rows, residual=r)[0], ya[rows])
+    # the same on pre-quantised codes, and on the unquantised 16-bit layer (exact rationals again)
+    yc, accc = orc.linear_a8_codes(orc.act_quantize(x, *act), act, c, s, z, bias=b, residual=r)
+    assert np.array_equal(accc, acc) and np.array_equal(yc, ya)
+    w = rng.normal(0, 0.5, (N, K)).astype(np.float16)
+    yf = orc.linear_fp(x, w, b, residual=r).view(np.float16)
+    for m in range(M):
+        for n in range(N):
+            tot = sum((Fraction(float(x[m, k])) * Fraction(float(w[n, k])) for k in range(K)),
+                      Fraction(float(b[n])) + Fraction(float(r[m, n])))
+            assert yf[m, n] == np.float16(float(tot)), (m, n)
 
 
 def test_conv_residual_is_indexed_by_pixel(orc):
