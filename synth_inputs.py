@@ -181,3 +181,70 @@ def sweep_layers(seed: int = 0, batch: int = 4, latent: int = 128, bits_choices=
     bits, mean = _assign_bits(layers, seed, bits_choices, target_bits)
     layers = [replace(l, bits=bt) for l, bt in zip(layers, bits)]
     return layers, mean
+
+
+# ----------------------------------------------------------------------------------------------
+# Inputs of the bit-width allocation: a layer table with element counts and groups, and a synthetic
+# sensitivity table (the real one needs the model, prompts and image metrics)
+# ----------------------------------------------------------------------------------------------
+
+def unet_allocation_layers(ctx_dim: int = 2048):
+    """(name, group, weight elements) for the linear and convolution layers of an SDXL-shaped UNet: channel widths
+    320/640/1280, transformer depths 0/2/10 per level (encoder 2 stages per level, middle 1, decoder 3), residual
+    blocks with two 3x3 convolutions, a time-embedding linear and a 1x1 shortcut where the width changes.
+    group: "content" for cross-attention and feed-forward layers, "quality" for the rest (Sec. 3.2)."""
+    rows = []
+
+    def transformer(prefix, C, depth):
+        rows.append((f"{prefix}.proj_in", "quality", C * C))
+        for d in range(depth):
+            for L in transformer_block_linears(f"{prefix}.block{d}", 1, C, 1, ctx_dim):
+                grp = "content" if (".attn2." in L.name or ".ff." in L.name) else "quality"
+                rows.append((L.name, grp, L.N * L.K))
+        rows.append((f"{prefix}.proj_out", "quality", C * C))
+
+    def resblock(prefix, cin, cout):
+        rows.append((f"{prefix}.conv1", "quality", 9 * cin * cout))
+        rows.append((f"{prefix}.time_emb", "quality", 1280 * cout))
+        rows.append((f"{prefix}.conv2", "quality", 9 * cout * cout))
+        if cin != cout:
+            rows.append((f"{prefix}.shortcut", "quality", cin * cout))
+
+    widths, depths = (320, 640, 1280), (0, 2, 10)
+    rows.append(("conv_in", "quality", 9 * 4 * 320))
+    prev = 320
+    skips = [320]
+    for lvl, (C, dep) in enumerate(zip(widths, depths)):
+        for s in range(2):
+            resblock(f"down{lvl}.res{s}", prev, C)
+            if dep:
+                transformer(f"down{lvl}.attn{s}", C, dep)
+            prev = C
+            skips.append(C)
+        if lvl < 2:
+            rows.append((f"down{lvl}.downsample", "quality", 9 * C * C))
+            skips.append(C)
+    resblock("mid.res0", 1280, 1280)
+    transformer("mid.attn", 1280, 10)
+    resblock("mid.res1", 1280, 1280)
+    for lvl in (2, 1, 0):
+        C, dep = widths[lvl], depths[lvl]
+        for s in range(3):
+            resblock(f"up{lvl}.res{s}", prev + skips.pop(), C)
+            if dep:
+                transformer(f"up{lvl}.attn{s}", C, dep)
+            prev = C
+        if lvl > 0:
+            rows.append((f"up{lvl}.upsample", "quality", 9 * C * C))
+    rows.append(("conv_out", "quality", 9 * 320 * 4))
+    return rows
+
+
+def sensitivity_table(seed: int, name: str, n_layers: int, bits=(2, 4, 8)) -> np.ndarray:
+    """Synthetic scores S[i][b] in dB-like units: about 6 dB per bit times a per-layer gain in [0.5, 1.5], on a
+    per-layer offset, with a little noise, and non-decreasing in b (more bits never score worse)."""
+    gain = 0.5 + uniform01(seed, name + "/gain", n_layers)
+    offset = 20.0 * uniform01(seed, name + "/offset", n_layers)
+    noise = normal(seed, name + "/noise", (n_layers, len(bits)), 0.5)
+    s = offset[:, None] + 6.02 * gain[:, None] * np.asarray(bits, np.float64)[None, :] + noise
+    return np.maximum.accumulate(s, axis=1)
