@@ -37,6 +37,8 @@ extern "C" {
 #define MQ_ERR_HIP (-5)                 /* a HIP runtime call failed; see mq_last_hip_error() */
 #define MQ_ERR_UNSUPPORTED_LAYOUT (-6)  /* the GEMM entry points take MQ_LAYOUT_KERNEL only */
 #define MQ_ERR_OVERFLOW_RISK (-7)       /* K so large that an int32 accumulator could overflow (255*255*K >= 2^31) */
+#define MQ_ERR_INFEASIBLE (-8)          /* bit-width allocation: no assignment fits the budget */
+#define MQ_ERR_TOO_LARGE (-9)           /* bit-width allocation: the exact search outgrew its state limit */
 
 #define MQ_LAYOUT_CANONICAL 0 /* interchange format: each row a little-endian bit stream, code k at bits [k*b, k*b+b) */
 #define MQ_LAYOUT_KERNEL 1    /* opaque tile-major format consumed by the GEMMs; needs K % 64 == 0 */
@@ -282,6 +284,43 @@ int mq_bos_aware_kv_proj(const void* ctx, int B, int T, int K, const void* packe
                          const void* w_f16, const void* bos_out, const float* act_scale, const int32_t* act_zp,
                          const void* bias, void* y, int naive_all_rows, float* act_scale_out, int32_t* act_zp_out,
                          void* ws, size_t ws_bytes, void* stream);
+
+/* ------------------------------------------------------------------------------------------------
+ * Bit-width allocation (host only: every pointer in this section is a HOST pointer, no GPU is touched, nothing is
+ * enqueued).  It produces the per-layer `bits` that the entry points above take.
+ * ---------------------------------------------------------------------------------------------- */
+
+/* The integer programme of paper Sec. 3.3, Eq. 2, solved exactly: choose one candidate per layer,
+ *     maximise  sum_i sens[i][c_i]   subject to  sum_i cost[i][c_i] <= budget.
+ *   sens_host [n_layers][n_choices] sensitivity scores (higher is better, any finite values),
+ *   cost_host [n_layers][n_choices] non-negative resource costs (for an average-bit-width budget: elements * bits).
+ *   choice_host [n_layers] out: index of the chosen candidate per layer.  objective_host, cost_used_host: nullable
+ *   scalars out: the objective (scores added in layer order, double precision) and the cost of the choice.
+ * Where several assignments reach the maximum, one of them is returned.
+ * Errors: MQ_ERR_INFEASIBLE when even the cheapest assignment exceeds the budget; MQ_ERR_TOO_LARGE. */
+int mq_alloc_solve(int n_layers, int n_choices, const double* sens_host, const int64_t* cost_host, int64_t budget,
+                   int32_t* choice_host, double* objective_host, int64_t* cost_used_host);
+
+/* SplitBudget of paper App. A, Alg. 1.  The ratio k is read as the ratio of the two groups' average bit-widths:
+ *     avg_quality = budget_all / (k * params_content + params_quality),  budget_content = floor(k * avg_quality * params_content),
+ *     budget_quality = budget_all - budget_content. */
+int mq_alloc_split_budget(int64_t budget_all, int64_t params_content, int64_t params_quality, double k,
+                          int64_t* budget_content_host, int64_t* budget_quality_host);
+
+/* The two loops of paper App. A, Alg. 1 up to (not including) image generation and scoring, which need the model:
+ * n_budgets budgets spaced linearly in [B_all - dB, B_all] (B_all = floor(avg_bits_target * P), dB =
+ * floor(delta_avg_bits * P), P = all elements of both groups) times n_ratios ratios spaced linearly in [k_lo, k_hi];
+ * for each pair the budget is split, Eq. 2 is solved per group with cost = elements * bits, and the two
+ * configurations are returned for the caller to score.  Candidate e = budget index * n_ratios + ratio index.
+ *   sens_*_host [n][n_choices], params_*_host [n] element counts, bits_host [n_choices].
+ *   budgets_host [E][3] out: budget, content budget, quality budget.  k_host [E] out.  feasible_host [E] out: 1 when
+ *   both groups fit.  objectives_host [E][2] out (content, quality).  choice_content_host [E][n_content],
+ *   choice_quality_host [E][n_quality] out: candidate indices, -1 where infeasible.  E = n_budgets * n_ratios. */
+int mq_alloc_search(int n_content, const double* sens_content_host, const int64_t* params_content_host, int n_quality,
+                    const double* sens_quality_host, const int64_t* params_quality_host, int n_choices,
+                    const int32_t* bits_host, double avg_bits_target, double delta_avg_bits, int n_budgets, double k_lo,
+                    double k_hi, int n_ratios, int64_t* budgets_host, double* k_host, int32_t* feasible_host,
+                    double* objectives_host, int32_t* choice_content_host, int32_t* choice_quality_host);
 
 #ifdef __cplusplus
 }

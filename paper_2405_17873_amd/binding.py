@@ -17,7 +17,8 @@ LAYOUT_CANONICAL, LAYOUT_KERNEL = 0, 1
 
 _ERRORS = {
     -1: "MQ_ERR_BAD_ARG", -2: "MQ_ERR_BAD_SHAPE", -3: "MQ_ERR_UNSUPPORTED_BITS", -4: "MQ_ERR_WORKSPACE_TOO_SMALL",
-    -5: "MQ_ERR_HIP", -6: "MQ_ERR_UNSUPPORTED_LAYOUT", -7: "MQ_ERR_OVERFLOW_RISK",
+    -5: "MQ_ERR_HIP", -6: "MQ_ERR_UNSUPPORTED_LAYOUT", -7: "MQ_ERR_OVERFLOW_RISK", -8: "MQ_ERR_INFEASIBLE",
+    -9: "MQ_ERR_TOO_LARGE",
 }
 
 EXPORTS = ("mq_version", "mq_last_hip_error", "mq_tune_force_tile", "mq_tune_force_splits", "mq_prof_enable", "mq_prof_num_slots", "mq_prof_read",
@@ -25,7 +26,8 @@ EXPORTS = ("mq_version", "mq_last_hip_error", "mq_tune_force_tile", "mq_tune_for
            "mq_unpack_weights", "mq_qlinear_w_only", "mq_qlinear_a8_workspace_bytes", "mq_qlinear_w8a8",
            "mq_qlinear_w4a8", "mq_a8_row_bytes", "mq_qlinear_a8_geglu", "mq_qlinear_w_only_geglu", "mq_qlinear_a8_codes", "mq_conv3x3_w_only",
            "mq_conv_tap_sums", "mq_conv3x3_a8_workspace_bytes", "mq_conv3x3_a8",
-           "mq_bos_aware_kv_proj_workspace_bytes", "mq_bos_aware_kv_proj")
+           "mq_bos_aware_kv_proj_workspace_bytes", "mq_bos_aware_kv_proj", "mq_alloc_solve", "mq_alloc_split_budget",
+           "mq_alloc_search")
 
 
 class MixdqError(RuntimeError):
@@ -461,3 +463,60 @@ def plan_bos_aware_kv_proj(ctx, w: PackedWeight, out, ws, w_f16=None, bos_out=No
             _ptr(w.colsum), _ptr(w_f16), _ptr(bos_out), _ptr(a_s), _ptr(a_z), _ptr(bias), _ptr(out), 0, null, null,
             _ptr(ws), C.c_size_t(ws.numel()), _stream())
     return _planned(load().mq_bos_aware_kv_proj, "mq_bos_aware_kv_proj", args, (ctx, w, out, ws, w_f16, bos_out, bias, act))
+
+
+# ---------------------------------------------------------------------------------------------------------------
+# Bit-width allocation (host arrays, no GPU)
+# ---------------------------------------------------------------------------------------------------------------
+
+def _np_ptr(a):
+    return a.ctypes.data_as(C.c_void_p)
+
+
+def alloc_solve(sens, cost, budget: int):
+    """Eq. 2 solved exactly.  sens float64 [n_layers, n_choices], cost int64 [n_layers, n_choices].
+    Returns (choice int32 [n_layers], objective, cost used); raises MixdqError (code -8) when nothing fits."""
+    import numpy as np
+    sens = np.ascontiguousarray(sens, np.float64)
+    cost = np.ascontiguousarray(cost, np.int64)
+    assert sens.ndim == 2 and sens.shape == cost.shape
+    n, m = sens.shape
+    choice = np.empty(n, np.int32)
+    obj = C.c_double(0.0)
+    used = C.c_int64(0)
+    _check(load().mq_alloc_solve(n, m, _np_ptr(sens), _np_ptr(cost), C.c_int64(int(budget)), _np_ptr(choice),
+                                 C.byref(obj), C.byref(used)), "mq_alloc_solve")
+    return choice, obj.value, used.value
+
+
+def alloc_split_budget(budget_all: int, params_content: int, params_quality: int, k: float):
+    bc, bq = C.c_int64(0), C.c_int64(0)
+    _check(load().mq_alloc_split_budget(C.c_int64(int(budget_all)), C.c_int64(int(params_content)),
+                                        C.c_int64(int(params_quality)), C.c_double(k), C.byref(bc), C.byref(bq)),
+           "mq_alloc_split_budget")
+    return bc.value, bq.value
+
+
+def alloc_search(sens_content, params_content, sens_quality, params_quality, bits, avg_bits_target: float,
+                 delta_avg_bits: float, n_budgets: int, k_lo: float, k_hi: float, n_ratios: int):
+    """The budget x ratio scan around Eq. 2.  Returns a dict of arrays over the n_budgets * n_ratios candidates:
+    budgets int64 [E,3] (all, content, quality), k [E], feasible [E], objectives [E,2], choice_content [E,n_c],
+    choice_quality [E,n_q]."""
+    import numpy as np
+    sc = np.ascontiguousarray(sens_content, np.float64)
+    sq = np.ascontiguousarray(sens_quality, np.float64)
+    pc = np.ascontiguousarray(params_content, np.int64)
+    pq = np.ascontiguousarray(params_quality, np.int64)
+    bits = np.ascontiguousarray(bits, np.int32)
+    nc, nq, m = sc.shape[0], sq.shape[0], bits.shape[0]
+    assert sc.shape == (nc, m) and sq.shape == (nq, m) and pc.shape == (nc,) and pq.shape == (nq,)
+    E = n_budgets * n_ratios
+    out = dict(budgets=np.empty((E, 3), np.int64), k=np.empty(E, np.float64), feasible=np.empty(E, np.int32),
+               objectives=np.empty((E, 2), np.float64), choice_content=np.empty((E, nc), np.int32),
+               choice_quality=np.empty((E, nq), np.int32))
+    _check(load().mq_alloc_search(nc, _np_ptr(sc), _np_ptr(pc), nq, _np_ptr(sq), _np_ptr(pq), m, _np_ptr(bits),
+                                  C.c_double(avg_bits_target), C.c_double(delta_avg_bits), n_budgets, C.c_double(k_lo),
+                                  C.c_double(k_hi), n_ratios, _np_ptr(out["budgets"]), _np_ptr(out["k"]),
+                                  _np_ptr(out["feasible"]), _np_ptr(out["objectives"]), _np_ptr(out["choice_content"]),
+                                  _np_ptr(out["choice_quality"])), "mq_alloc_search")
+    return out

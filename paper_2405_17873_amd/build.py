@@ -19,8 +19,9 @@ COMMON = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Xclang", "-ta
 PER_FILE = {
     "quant_pack.hip": ["-ffp-contract=off"],
     "act_quant.hip": ["-ffp-contract=off"],
+    "alloc.cpp": ["-ffp-contract=off"],  # budgets are floors of double products: no fused multiply-add
 }
-SOURCES = ["api.hip", "quant_pack.hip", "act_quant.hip", "gemm.hip", "bos.hip", "prof.hip"]
+SOURCES = ["api.hip", "quant_pack.hip", "act_quant.hip", "gemm.hip", "bos.hip", "prof.hip", "alloc.cpp"]
 
 
 def _compile(src: str, force: bool) -> str:

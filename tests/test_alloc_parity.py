@@ -1,0 +1,180 @@
+"""The library's bit-width allocation (host code, no GPU) against the CPU oracle: the optimum of Eq. 2 is unique as a
+value, so objectives are compared exactly (both sides add the chosen scores in layer order) and the returned choice is
+checked to be feasible and to reach that value; budgets of the scan are integers and compared exactly."""
+import math
+import time
+
+import numpy as np
+import pytest
+
+import synth_inputs as si
+from oracle import alloc as orc
+
+
+@pytest.fixture(scope="module")
+def mq():
+    import paper_2405_17873_amd as m
+    m.load()
+    return m
+
+
+def _check_choice(sens, cost, budget, choice, obj, used):
+    assert orc.total_cost(cost, choice) == used <= budget
+    assert orc.objective(sens, choice) == obj
+
+
+@pytest.mark.parametrize("seed", range(40))
+def test_solver_equals_enumeration(mq, seed):
+    rng = np.random.default_rng(1000 + seed)
+    n = int(rng.integers(1, 9))
+    m = int(rng.integers(1, 5))
+    params = rng.integers(1, 40, n) * int(rng.choice([1, 8, 4096]))
+    bits = sorted(rng.choice(np.arange(1, 17), m, replace=False).tolist())
+    cost = np.array(orc.layer_costs(params, bits), np.int64)
+    kind = seed % 4
+    if kind == 0:
+        S = rng.integers(0, 5, (n, m)).astype(np.float64)                 # ties everywhere
+    elif kind == 1:
+        S = rng.normal(0, 10, (n, m))                                      # not monotone in the bit-width
+    elif kind == 2:
+        S = si.sensitivity_table(seed, "ap/s", n, bits)                    # monotone, dB-like
+    else:
+        S = np.sort(rng.normal(0, 3, (n, m)), axis=1) - 50.0               # all negative
+    lo, hi = int(cost.min(1).sum()), int(cost.max(1).sum())
+    for budget in sorted({lo - 1, lo, lo + 1, (3 * lo + hi) // 4, (lo + hi) // 2, (lo + 3 * hi) // 4, hi - 1, hi, 2 * hi}):
+        ref = orc.allocate_bruteforce(S, cost, budget)
+        if ref is None:
+            with pytest.raises(mq.MixdqError) as e:
+                mq.alloc_solve(S, cost, budget)
+            assert e.value.code == -8
+            continue
+        choice, obj, used = mq.alloc_solve(S, cost, budget)
+        assert obj == ref[0], (budget, obj, ref)
+        _check_choice(S, cost, budget, choice, obj, used)
+
+
+def test_hand_worked_case_and_knapsack(mq):
+    S = np.array([[1, 5, 6], [1, 3, 9], [0, 4, 5]], np.float64)
+    cost = np.array(orc.layer_costs([10, 20, 5], (2, 4, 8)), np.int64)
+    c, v, u = mq.alloc_solve(S, cost, 170)
+    assert (c.tolist(), v, u) == ([1, 1, 2], 13.0, 160)
+    c, v, u = mq.alloc_solve(S, cost, 220)
+    assert (c.tolist(), v, u) == ([1, 2, 1], 18.0, 220)
+    assert mq.alloc_solve(S, cost, 219)[1] == 14.0
+    c, v, u = mq.alloc_solve(np.array([[0, 1], [0, 4], [0, 5], [0, 7]], np.float64),
+                             np.array([[0, 1], [0, 3], [0, 4], [0, 5]], np.int64), 7)
+    assert (c.tolist(), v) == ([0, 1, 1, 0], 9.0)
+
+
+@pytest.mark.parametrize("avg", (2.0, 2.7, 3.66, 4.0, 5.3, 7.9, 8.0))
+def test_solver_equals_the_knapsack_recurrence_on_the_linear_sweep(mq, avg):
+    """The 120 linears of the benchmark's sweep (element counts in multiples of 640*640) with bits {2,4,8}."""
+    layers, _ = si.sweep_layers()
+    params = [l.N * l.K for l in layers]
+    S = si.sensitivity_table(7, "ap/sweep", len(params))
+    cost = np.array(orc.layer_costs(params, (2, 4, 8)), np.int64)
+    budget = int(avg * sum(params))
+    ref = orc.allocate_dp(S, cost, budget)
+    choice, obj, used = mq.alloc_solve(S, cost, budget)
+    assert obj == ref[0]
+    _check_choice(S, cost, budget, choice, obj, used)
+
+
+def test_full_unet_table_bounds_and_time(mq):
+    """790 layers, 2.56 G elements, common divisor 1280: too large for the oracle's dense recurrence, so the result is
+    boxed in: feasible; no single-layer change and no pair exchange improves it within the budget (necessary for
+    optimality); and weak duality, OPT <= sum_i max_b(S - lam*M) + lam*B for every lam >= 0, bounds it from above to
+    within the gain of a single layer step."""
+    rows = si.unet_allocation_layers()
+    params = np.array([r[2] for r in rows], np.int64)
+    n = len(rows)
+    S = si.sensitivity_table(11, "ap/unet", n)
+    cost = np.array(orc.layer_costs(params, (2, 4, 8)), np.int64)
+    P = int(params.sum())
+    for avg in (3.0, 3.66, 5.0, 6.5):
+        budget = int(avg * P)
+        t = time.time()
+        choice, obj, used = mq.alloc_solve(S, cost, budget)
+        dt = time.time() - t
+        assert dt < 5.0, dt                                    # the paper: "in seconds"
+        _check_choice(S, cost, budget, choice, obj, used)
+        C = cost.astype(np.float64)
+        ub = min((S - lam * C).max(1).sum() + lam * budget for lam in np.geomspace(1e-9, 1e-3, 4000))
+        assert obj <= ub + 1e-6
+        assert ub - obj <= (S.max(1) - S.min(1)).max() + 1e-6, (ub, obj)
+        # single-layer moves
+        left = budget - used
+        cur_s = S[np.arange(n), choice]
+        cur_c = cost[np.arange(n), choice]
+        for b in range(3):
+            better = (S[:, b] > cur_s + 1e-12) & (cost[:, b] - cur_c <= left)
+            assert not better.any()
+        # pair exchanges: layer i one choice up, layer j one choice down
+        up = np.where(choice < 2)[0]
+        dn = np.where(choice > 0)[0]
+        gain_up = S[up, choice[up] + 1] - cur_s[up]
+        cost_up = cost[up, choice[up] + 1] - cur_c[up]
+        loss_dn = cur_s[dn] - S[dn, choice[dn] - 1]
+        save_dn = cur_c[dn] - cost[dn, choice[dn] - 1]
+        net = gain_up[:, None] - loss_dn[None, :]
+        fits = cost_up[:, None] - save_dn[None, :] <= left
+        same = up[:, None] == dn[None, :]
+        assert not ((net > 1e-9) & fits & ~same).any()
+
+
+def test_budget_split_matches_the_oracle(mq):
+    rng = np.random.default_rng(3)
+    for _ in range(200):
+        pc, pq = int(rng.integers(1, 10 ** 9)), int(rng.integers(1, 10 ** 9))
+        k = float(rng.uniform(0.3, 2.0))
+        b_all = int(rng.uniform(2, 8) * (pc + pq))
+        assert mq.alloc_split_budget(b_all, pc, pq, k) == orc.split_budget(b_all, pc, pq, k)
+
+
+def test_candidate_scan_matches_the_oracle(mq):
+    """The scan over budgets and ratios on a two-level transformer table (element counts in multiples of 640*640, so
+    the oracle's recurrence stays small), with the paper's ranges for the weight ratio."""
+    rows = []
+    for b in range(2):
+        rows += [(l.name, l.N * l.K) for l in si.transformer_block_linears(f"a{b}", 1, 640, 1)]
+    for b in range(3):
+        rows += [(l.name, l.N * l.K) for l in si.transformer_block_linears(f"b{b}", 1, 1280, 1)]
+    content = [(nm, p) for nm, p in rows if ".attn2." in nm or ".ff." in nm]
+    quality = [(nm, p) for nm, p in rows if not (".attn2." in nm or ".ff." in nm)]
+    pc, pq = [p for _, p in content], [p for _, p in quality]
+    sc = si.sensitivity_table(21, "ap/c", len(pc))
+    sq = si.sensitivity_table(21, "ap/q", len(pq))
+    args = (sc, pc, sq, pq, (2, 4, 8), 5.0, 0.4, 4, 0.45, 1.36, 6)
+    ref = orc.search_candidates(*args)
+    got = mq.alloc_search(*args)
+    assert len(ref) == 24 == got["k"].shape[0]
+    cc = np.array(orc.layer_costs(pc, (2, 4, 8)), np.int64)
+    cq = np.array(orc.layer_costs(pq, (2, 4, 8)), np.int64)
+    n_feasible = 0
+    for e, r in enumerate(ref):
+        assert got["budgets"][e].tolist() == [r["budget"], r["b_content"], r["b_quality"]]
+        assert got["k"][e] == r["k"]
+        assert bool(got["feasible"][e]) == r["feasible"]
+        if not r["feasible"]:
+            assert (got["choice_content"][e] == -1).all() and (got["choice_quality"][e] == -1).all()
+            continue
+        n_feasible += 1
+        assert got["objectives"][e].tolist() == [r["objective_c"], r["objective_q"]]
+        _check_choice(sc, cc, r["b_content"], got["choice_content"][e], r["objective_c"],
+                      orc.total_cost(cc, got["choice_content"][e]))
+        _check_choice(sq, cq, r["b_quality"], got["choice_quality"][e], r["objective_q"],
+                      orc.total_cost(cq, got["choice_quality"][e]))
+    assert n_feasible >= 20
+
+
+def test_bad_arguments(mq):
+    S = np.zeros((2, 3))
+    cost = np.ones((2, 3), np.int64)
+    with pytest.raises(mq.MixdqError):
+        mq.alloc_solve(S, -cost, 10)
+    with pytest.raises(mq.MixdqError):
+        mq.alloc_solve(np.full((2, 3), np.nan), cost, 10)
+    with pytest.raises(mq.MixdqError):
+        mq.alloc_split_budget(100, 0, 5, 1.0)
+    with pytest.raises(mq.MixdqError):
+        mq.alloc_split_budget(100, 5, 5, 0.0)
