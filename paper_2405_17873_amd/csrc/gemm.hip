@@ -26,6 +26,9 @@
 //     that every lane's global and LDS accesses are 16 bytes wide.
 //   * Few tiles and a long reduction: several workgroups per tile, partial sums through a scratch ring of the
 //     library, the last-arriving workgroup adds them in a fixed order (no waiting).
+//   * Optional residual operand (a skip connection, or the output of the other half of a split concatenated
+//     input, Sec. 4.1): a kernel variant (RES) loads it in the accumulator layout and adds it in fp32 before the
+//     one rounding; kernels without it contain none of this.
 #include <stdio.h>
 
 #include <mutex>
