@@ -53,18 +53,22 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--iters", type=int, default=200)
     ap.add_argument("--only", default="", help="comma-separated labels (c1,c2,c3,c4,c5,small-M,ff,conv)")
+    ap.add_argument("--tile", type=int, default=-1, help="force a tile of the GEMM's tile table (-1: the library's choice)")
     args = ap.parse_args()
 
     import torch
 
     import paper_2405_17873_amd as mq
     mq.load()
+    mq.tune_force_tile(args.tile)
     dev = torch.device("cuda:0")
     gen = torch.Generator(device=dev)
     gen.manual_seed(0)
     overhead_us = mq.prof_bracket_overhead_us()
     only = set(filter(None, args.only.split(",")))
 
+    if args.tile >= 0:
+        print(f"# tile {args.tile} forced")
     print(f"# per-shape report, {torch.cuda.get_device_name(0)}; iters per row {args.iters}; "
           f"event-bracket cost subtracted from the kernel column: {overhead_us:.2f} us")
     print(f"{'cfg':8s}{'M':>6s}{'K':>6s}{'N':>6s} {'mode':7s}{'us/call':>9s}{'kernel us':>10s}{'T(FL)OP/s':>10s}"

@@ -128,7 +128,7 @@ W_ONLY_SHAPES = [
 
 
 @pytest.mark.parametrize("bits", ALL_BITS)
-@pytest.mark.parametrize("tile", (-1, 0, 1, 2, 3, 4))
+@pytest.mark.parametrize("tile", (-1, 0, 1, 2, 3, 4, 5))
 def test_w_only_small_shapes(mq, orc, bits, tile):
     mq.tune_force_tile(tile)
     for (M, K, N) in W_ONLY_SHAPES:
@@ -162,7 +162,7 @@ def test_w_only_exact_integer_case(mq, orc):
 
 def test_w_only_bf16(mq, orc):
     """bfloat16 activations, bias and output (fp32 accumulate); weights quantised from bf16 as well."""
-    for (M, K, N, tile) in ((256, 320, 320, -1), (300, 640, 640, 1), (77, 128, 40, 2), (513, 2048, 264, 0)):
+    for (M, K, N, tile) in ((256, 320, 320, -1), (300, 640, 640, 1), (77, 128, 40, 2), (513, 2048, 264, 0), (300, 640, 264, 5)):
         mq.tune_force_tile(tile)
         xb = torch.from_numpy(si.normal(21, f"bf/x{M}", (M, K)).astype(np.float32)).to(torch.bfloat16)
         wb = torch.from_numpy(si.normal(21, f"bf/w{N}", (N, K), 0.02).astype(np.float32)).to(torch.bfloat16)
@@ -220,7 +220,7 @@ def test_w_only_transformer_block_shapes_sampled_rows(mq, orc, M, K, N):
 
 # ----------------------------------------------------------------------------------------------- layers kept at 16 bits
 
-@pytest.mark.parametrize("tile", (-1, 0, 1, 2, 3, 4))
+@pytest.mark.parametrize("tile", (-1, 0, 1, 2, 3, 4, 5))
 def test_unquantised_16bit_layer(mq, orc, tile):
     """bits = 16: the weights go through the same tile order and GEMM skeleton unquantised (fp16 and bf16)."""
     mq.tune_force_tile(tile)
@@ -267,7 +267,7 @@ def test_16bit_canonical_pack_is_the_matrix(mq):
 SPLIT_SHAPES = [(1, 5120, 1280), (16, 1280, 320), (77, 2048, 1280), (308, 2048, 640), (130, 640, 96), (33, 256, 40)]
 
 
-@pytest.mark.parametrize("tile", (-1, 1, 2, 3, 4))
+@pytest.mark.parametrize("tile", (-1, 1, 2, 3, 4, 5))
 @pytest.mark.parametrize("parts", (0, 2, 3, 7))
 def test_split_reduction_matches_oracle(mq, orc, tile, parts):
     """Few tiles, long reduction: several workgroups per tile, partial sums through the library's scratch ring.
@@ -313,7 +313,7 @@ A8_SHAPES = [(256, 320, 320), (1, 64, 32), (77, 128, 40), (608, 2048, 640), (300
 
 
 @pytest.mark.parametrize("mode", ("w8s", "w8a", "w4"))
-@pytest.mark.parametrize("tile", (-1, 0, 1, 2, 3, 4))
+@pytest.mark.parametrize("tile", (-1, 0, 1, 2, 3, 4, 5))
 def test_a8_small_shapes(mq, orc, mode, tile):
     mq.tune_force_tile(tile)
     bits, sym = {"w8s": (8, True), "w8a": (8, False), "w4": (4, False)}[mode]
@@ -604,7 +604,7 @@ def test_conv_a8(mq, orc, bits, sym, tile):
 RES_SHAPES = [(256, 320, 320), (77, 128, 40), (513, 192, 264), (300, 640, 640), (1, 64, 32)]
 
 
-@pytest.mark.parametrize("tile", (-1, 0, 1, 2, 3, 4))
+@pytest.mark.parametrize("tile", (-1, 0, 1, 2, 3, 4, 5))
 def test_residual_weight_only(mq, orc, tile):
     """y = linear(x) + residual with one rounding; the residual as its own tensor, as a strided view, and as the
     output tensor itself (in place)."""
@@ -647,7 +647,7 @@ def test_residual_is_added_before_the_rounding(mq, orc):
     assert np.array_equal(ref, (lin + r.astype(np.int64)).astype(np.float16))
     twice = (lin.astype(np.float16) + r).astype(np.float16)
     assert (twice != ref).any()
-    for tile in (-1, 0, 1, 2, 3, 4):
+    for tile in (-1, 0, 1, 2, 3, 4, 5):
         mq.tune_force_tile(tile)
         try:
             assert np.array_equal(host(mq.qlinear_w_only(dev(x), pw, residual=dev(r))), ref), tile
@@ -681,7 +681,7 @@ def test_residual_bf16_and_unquantised_layer(mq, orc):
 
 
 @pytest.mark.parametrize("mode", ("w8s", "w4"))
-@pytest.mark.parametrize("tile", (-1, 0, 1, 2, 3, 4))
+@pytest.mark.parametrize("tile", (-1, 0, 1, 2, 3, 4, 5))
 def test_residual_a8(mq, orc, mode, tile):
     bits, sym = (8, True) if mode == "w8s" else (4, False)
     mq.tune_force_tile(tile)
