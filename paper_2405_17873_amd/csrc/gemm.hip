@@ -1086,7 +1086,8 @@ void gemm_kernel(const GemmArgs g) {
 // Tile table.  index -> workgroup tile (rows x channels), waves, wave tile:
 //   0: 128x256, 4 waves (1x4) of 128x64     1: 128x128, 4 waves (2x2) of 64x64     2: 64x64, 4 waves of 32x32
 //   3: as 1 and 4: as 2, with a second wave group splitting k inside the workgroup (8 waves)
-//   5: 128x64, 4 waves (2x2) of 64x32, two LDS stages: the form of tile 1 that puts more workgroups on a compute unit
+//   5: 64x128, 4 waves (1x4) of 64x32, two or three LDS stages: the form of tile 1 that puts more workgroups on a
+//      compute unit
 // A tall wave tile pays: every widened weight fragment then feeds 4 MFMAs (measured: LDS reads into registers,
 // vector ALU instructions and MFMAs take turns on a SIMD, they do not overlap).  256x256 tiles with one wave per
 // SIMD and 128x128 tiles with two-wave workgroups were measured slower on every configured shape.
@@ -1155,7 +1156,7 @@ bool take_split_scratch(size_t bytes, int tiles, uint32_t** partial, uint32_t** 
 // k-split variants only pay where tiles are few and k is long (FF-out at the 640 level, the K/V projections).
 static int pick_tile(int M, int N, int K, bool wide_weights = false) {
     if (g_force_tile >= 0 && g_force_tile <= 4) return g_force_tile;
-    if (g_force_tile == 5) return 1;  // the narrow form of tile 1: the linear layers' dispatch decides (narrow_tile)
+    if (g_force_tile == 5) return 1;  // the half-height form of tile 1: the linear layers' dispatch decides (narrow_tile)
     const long t0 = (long)((M + 127) / 128) * ((N + 255) / 256);
     // (8-bit weights of the int8 path: the large tile leaves LDS for one workgroup per compute unit only, and two
     // co-resident 128x128 workgroups were measured faster on every configured shape)
@@ -1165,18 +1166,18 @@ static int pick_tile(int M, int N, int K, bool wide_weights = false) {
     return K >= 1024 ? 4 : 2;
 }
 
-// Tile 1 or its narrow form (tile 5: 128x64, two LDS stages, up to four workgroups per compute unit)?  The 128x128
-// problems of this path have 160 to 640 tiles, one or two workgroups on most compute units, and a wave's LDS reads,
-// code widening and MFMAs run one after the other: what is missing is other waves on the SIMD to fill the gaps.
-// Twice the workgroups at half the width fetch every activation tile twice as often.  Measured on operands that are
-// not cached: the int8 path (one byte per activation) gains 5 to 16 % except with 8-bit weights and a very long
-// reduction; the 16-bit-activation path loses up to 13 % (it only wins when the operands are already in the
-// last-level cache), so it keeps tile 1.
+// Tile 1 or its half-height form (tile 5: 64x128, four waves side by side, two or three LDS stages, three to five
+// workgroups per compute unit)?  The 128x128 problems of this path have 160 to 640 tiles, one or two workgroups on
+// most compute units, and a wave's LDS reads, code widening and MFMAs run one after the other: what is missing is
+// other waves on the SIMD to fill the gaps.  Twice the workgroups at half the height fetch every weight tile twice as
+// often (weights are the small operand; halving the width instead doubles the activation traffic and was measured
+// slower on the 16-bit-activation path).  Measured on operands that are not cached: 8 to 19 % faster on every such
+// shape of both paths, except with unquantised 16-bit weights (4 KB per weight tile), which keep tile 1.
 template <bool I8, int BITS>
-static int narrow_tile(int t, int K) {
+static int narrow_tile(int t) {
     if (t != 1 || g_force_tile == 1) return t;
     if (g_force_tile == 5) return 5;
-    return (I8 && !(BITS == 8 && K >= 4096)) ? 5 : 1;
+    return BITS == 16 ? 1 : 5;
 }
 
 template <bool I8, int BITS, int WGM, int WGN, int TM, int TN, int S, int KS>
@@ -1266,12 +1267,12 @@ static int dispatch_gemm(GemmArgs& g, hipStream_t st) {
     // large tile two workgroups per compute unit would not fit, so it runs one per compute unit with a deeper
     // pipeline (and is not chosen automatically)
     constexpr bool WIDE = (I8 && BITS == 8) || BITS == 16;
-    switch (narrow_tile<I8, BITS>(pick_tile(g.M, g.N, g.K, WIDE), g.K)) {
+    switch (narrow_tile<I8, BITS>(pick_tile(g.M, g.N, g.K, WIDE))) {
         case 0: return run_gemm<I8, BITS, 1, 4, 4, 2, 1, WIDE ? 160 * 1024 : 80 * 1024, 4>(g, 0, st);
         case 1: return run_gemm<I8, BITS, 2, 2, 2, 2, 1, 80 * 1024, 4>(g, 1, st);
         case 2: return run_gemm<I8, BITS, 2, 2, 1, 1, 1, 80 * 1024, 8>(g, 2, st);
         case 3: return run_gemm<I8, BITS, 2, 2, 2, 2, 2, 160 * 1024, 4>(g, 3, st);
-        case 5: return run_gemm<I8, BITS, 2, 2, 2, 1, 1, 52 * 1024, 4>(g, 5, st);
+        case 5: return run_gemm<I8, BITS, 1, 4, 2, 1, 1, I8 ? 40 * 1024 : 52 * 1024, 3>(g, 5, st);
         default: return run_gemm<I8, BITS, 2, 2, 1, 1, 2, 80 * 1024, 8>(g, 4, st);
     }
 }
@@ -1281,11 +1282,11 @@ template <int BITS>
 static int dispatch_gemm_bf16(GemmArgs& g, hipStream_t st) {
     constexpr bool WIDE = BITS == 16;
     int t = pick_tile(g.M, g.N, g.K, WIDE);
-    t = narrow_tile<false, BITS>(t >= 3 ? t - 2 : t, g.K);
+    t = narrow_tile<false, BITS>(t >= 3 ? t - 2 : t);
     switch (t) {
         case 0: return run_gemm<false, BITS, 1, 4, 4, 2, 1, WIDE ? 160 * 1024 : 80 * 1024, 4, true>(g, 0, st);
         case 1: return run_gemm<false, BITS, 2, 2, 2, 2, 1, 80 * 1024, 4, true>(g, 1, st);
-        case 5: return run_gemm<false, BITS, 2, 2, 2, 1, 1, 52 * 1024, 4, true>(g, 5, st);
+        case 5: return run_gemm<false, BITS, 1, 4, 2, 1, 1, 52 * 1024, 3, true>(g, 5, st);
         default: return run_gemm<false, BITS, 2, 2, 1, 1, 1, 80 * 1024, 8, true>(g, 2, st);
     }
 }
