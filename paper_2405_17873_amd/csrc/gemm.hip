@@ -1443,14 +1443,18 @@ int launch_gemm_a8_codes(const int8_t* a8, long lda, const float* act_scale, con
     g.act_scale_p = act_scale; g.act_zp_p = act_zp;
     g.acc_debug = acc_debug;
     // no in-workgroup k split here, and not the large tile (no registers to spare for the row sums; the layers this
-    // serves, the output linears of feed-forward blocks, are narrow)
+    // serves, the output linears of feed-forward blocks, are narrow); the half-height tile 5 in place of tile 1
     int t = pick_tile(M, N, K, true);
     t = t >= 3 ? t - 2 : t;
+    // (tile 5 doubles the row-sum work per MFMA: measured +8 % at K = 1280, +5 % at 2560, -9 % at 5120)
+    const bool half_height = g_force_tile == 5 || (g_force_tile < 0 && K < 4096);
     if (w_bits == 4) {
         g.w_off = 0;
         switch (t) {
             case 0:
-            case 1: return run_gemm<true, 4, 2, 2, 2, 2, 1, 80 * 1024, 4, false, 2>(g, 1, st);
+            case 1:
+                if (half_height) return run_gemm<true, 4, 1, 4, 2, 1, 1, 40 * 1024, 3, false, 2>(g, 5, st);
+                return run_gemm<true, 4, 2, 2, 2, 2, 1, 80 * 1024, 4, false, 2>(g, 1, st);
             default: return run_gemm<true, 4, 2, 2, 1, 1, 1, 80 * 1024, 8, false, 2>(g, 2, st);
         }
     }
@@ -1458,7 +1462,9 @@ int launch_gemm_a8_codes(const int8_t* a8, long lda, const float* act_scale, con
         g.w_off = w_signed ? 0 : 128;
         switch (t) {
             case 0:
-            case 1: return run_gemm<true, 8, 2, 2, 2, 2, 1, 80 * 1024, 4, false, 2>(g, 1, st);
+            case 1:
+                if (half_height) return run_gemm<true, 8, 1, 4, 2, 1, 1, 40 * 1024, 3, false, 2>(g, 5, st);
+                return run_gemm<true, 8, 2, 2, 2, 2, 1, 80 * 1024, 4, false, 2>(g, 1, st);
             default: return run_gemm<true, 8, 2, 2, 1, 1, 1, 80 * 1024, 8, false, 2>(g, 2, st);
         }
     }
@@ -1483,6 +1489,10 @@ static int dispatch_conv_w_only(GemmArgs& g, hipStream_t st) {
     constexpr bool WIDE = BITS == 16;
     int t = pick_tile(g.M, g.N, g.K, WIDE);
     t = t >= 3 ? t - 2 : t;
+    // (the large tile only where its 256 channels are filled: the UNet's 320-channel level is better served by 128)
+    if (g_force_tile < 0 && t == 0 && g.N < 512) t = 1;
+    if (g_force_tile == 5 || (g_force_tile < 0 && t == 1))
+        return run_gemm<false, BITS, 1, 4, 2, 1, 1, 52 * 1024, 3, false, 3>(g, 5, st);
     switch (t) {
         case 0: return run_gemm<false, BITS, 1, 4, 4, 2, 1, 80 * 1024, 4, false, 3>(g, 0, st);
         case 1: return run_gemm<false, BITS, 2, 2, 2, 2, 1, 80 * 1024, 4, false, 3>(g, 1, st);
@@ -1529,16 +1539,18 @@ int launch_conv3x3_a8(const int8_t* a8, const ActParams* params, int B, int H, i
     g.w_colsum = w_colsum; g.w_tapsum = w_tapsum;
     g.act_scale_p = &params->scale; g.act_zp_p = &params->zp;
     g.acc_debug = acc_debug;
-    // (not the large tile: no registers to spare for the row sums and the tap masks)
+    // (not the large tile: no registers to spare for the row sums and the tap masks; tile 5 in place of tile 1)
     int t = pick_tile(g.M, N, g.K, true);
     t = t >= 3 ? t - 2 : t;
     if (w_bits == 4) {
         g.w_off = 0;
+        if (t <= 1 && g_force_tile != 1) return run_gemm<true, 4, 1, 4, 2, 1, 1, 40 * 1024, 3, false, 4>(g, 5, st);
         if (t <= 1) return run_gemm<true, 4, 2, 2, 2, 2, 1, 80 * 1024, 4, false, 4>(g, 1, st);
         return run_gemm<true, 4, 2, 2, 1, 1, 1, 80 * 1024, 8, false, 4>(g, 2, st);
     }
     if (w_bits == 8) {
         g.w_off = w_signed ? 0 : 128;
+        if (t <= 1 && g_force_tile != 1) return run_gemm<true, 8, 1, 4, 2, 1, 1, 40 * 1024, 3, false, 4>(g, 5, st);
         if (t <= 1) return run_gemm<true, 8, 2, 2, 2, 2, 1, 80 * 1024, 4, false, 4>(g, 1, st);
         return run_gemm<true, 8, 2, 2, 1, 1, 1, 80 * 1024, 8, false, 4>(g, 2, st);
     }

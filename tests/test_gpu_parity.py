@@ -477,7 +477,7 @@ def test_geglu_projection_emits_the_oracles_codes(mq, orc, bits, sym, tile):
 
 
 @pytest.mark.parametrize("bits,sym", [(4, False), (8, True), (8, False)])
-@pytest.mark.parametrize("tile", (-1, 1, 2))
+@pytest.mark.parametrize("tile", (-1, 1, 2, 5))
 def test_a8_linear_on_codes(mq, orc, bits, sym, tile):
     mq.tune_force_tile(tile)
     try:
@@ -560,7 +560,7 @@ def conv_weight(mq, orc, seed, N, Cin, bits, sym=False):
 
 
 @pytest.mark.parametrize("bits", ALL_BITS)
-@pytest.mark.parametrize("tile", (-1, 0, 1, 2))
+@pytest.mark.parametrize("tile", (-1, 0, 1, 2, 5))
 def test_conv_w_only(mq, orc, bits, tile):
     mq.tune_force_tile(tile)
     try:
@@ -578,7 +578,7 @@ def test_conv_w_only(mq, orc, bits, tile):
 
 
 @pytest.mark.parametrize("bits,sym", [(4, False), (8, True), (8, False)])
-@pytest.mark.parametrize("tile", (-1, 1, 2))
+@pytest.mark.parametrize("tile", (-1, 1, 2, 5))
 def test_conv_a8(mq, orc, bits, sym, tile):
     """Integer accumulators bit-exact, also on the border pixels (taps outside the image) and with a zero point far
     from 128 (static parameters)."""
@@ -745,7 +745,7 @@ def test_feed_forward_output_linear_adds_the_skip_connection(mq, orc):
             assert_close16(host(y), ry, f"codes + residual b{bits} tile{tile}")
 
 
-@pytest.mark.parametrize("tile", (-1, 0, 1, 2))
+@pytest.mark.parametrize("tile", (-1, 0, 1, 2, 5))
 def test_conv_residual_and_split_shortcut(mq, orc, tile):
     """Residual block tail (conv + skip), and the first convolution of an up block whose input is the channel
     concatenation [trunk | shortcut], run as two convolutions with separate quantisation parameters (Sec. 4.1): the
