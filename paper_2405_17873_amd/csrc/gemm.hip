@@ -1172,12 +1172,13 @@ static int pick_tile(int M, int N, int K, bool wide_weights = false) {
 // other waves on the SIMD to fill the gaps.  Twice the workgroups at half the height fetch every weight tile twice as
 // often (weights are the small operand; halving the width instead doubles the activation traffic and was measured
 // slower on the 16-bit-activation path).  Measured on operands that are not cached: 8 to 19 % faster on every such
-// shape of both paths, except with unquantised 16-bit weights (4 KB per weight tile), which keep tile 1.
+// shape of both paths, except with unquantised 16-bit weights (4 KB per weight tile), which keep tile 1.  Two
+// stages instead of three, and eight waves on 64x256, were measured slower.
 template <bool I8, int BITS>
 static int narrow_tile(int t) {
-    if (t != 1 || g_force_tile == 1) return t;
     if (g_force_tile == 5) return 5;
-    return BITS == 16 ? 1 : 5;
+    if (g_force_tile >= 0 || (t != 1 && t != 3)) return t;
+    return BITS == 16 ? t : 5;  // (also in place of tile 3: 5 to 7 % faster on its one regime, 4096 x 2560 x 640)
 }
 
 template <bool I8, int BITS, int WGM, int WGN, int TM, int TN, int S, int KS>
@@ -1446,7 +1447,7 @@ int launch_gemm_a8_codes(const int8_t* a8, long lda, const float* act_scale, con
     // serves, the output linears of feed-forward blocks, are narrow); the half-height tile 5 in place of tile 1
     int t = pick_tile(M, N, K, true);
     t = t >= 3 ? t - 2 : t;
-    // (tile 5 doubles the row-sum work per MFMA: measured +8 % at K = 1280, +5 % at 2560, -9 % at 5120)
+    // (tile 5 doubles the row-sum work per MFMA: measured 8 % faster at K = 1280, 5 % at 2560, 9 % slower at 5120)
     const bool half_height = g_force_tile == 5 || (g_force_tile < 0 && K < 4096);
     if (w_bits == 4) {
         g.w_off = 0;
