@@ -90,6 +90,22 @@ __global__ __launch_bounds__(256) void act_quantize_kernel(const _Float16* __res
     const int r0 = blockIdx.x * R;
     const int Rr = M - r0 < R ? M - r0 : R;
     if (threadIdx.x < Q_MAX_ROWS) lsum[threadIdx.x] = 0;
+    const uint32_t K8 = K >> 3;
+    const uint32_t Kp = (K + 127) / 128 * 128;  // row stride of the int8 copy; the padding is zero
+    const uint32_t Kp8 = Kp >> 3;               // a multiple of 16: an aligned group of 8 lanes never straddles rows
+    const uint32_t nvo = (uint32_t)Rr * Kp8;
+    half8 v[Q_U];
+    uint32_t lr[Q_U], pp[Q_U];
+    auto request = [&](uint32_t base) {
+#pragma unroll
+        for (int u = 0; u < Q_U; ++u) {
+            const uint32_t i = base + u * 256u + threadIdx.x;
+            lr[u] = i / Kp8;
+            pp[u] = i - lr[u] * Kp8;
+            if (i < nvo && pp[u] < K8) v[u] = ((const half8*)(x + map.phys(r0 + lr[u]) * ldx))[pp[u]];
+        }
+    };
+    request(0);  // on its way while the parameters are derived (most workgroups have a single round)
     float s, zf;
     if (partials) {
         float mn = INFINITY, mx = -INFINITY;
@@ -127,20 +143,8 @@ __global__ __launch_bounds__(256) void act_quantize_kernel(const _Float16* __res
         if (act_scale_out) *act_scale_out = s;
         if (act_zp_out) *act_zp_out = (int)zf;
     }
-    const uint32_t K8 = K >> 3;
-    const uint32_t Kp = (K + 127) / 128 * 128;  // row stride of the int8 copy; the padding is zero
-    const uint32_t Kp8 = Kp >> 3;               // a multiple of 16: an aligned group of 8 lanes never straddles rows
-    const uint32_t nvo = (uint32_t)Rr * Kp8;
     for (uint32_t base = 0; base < nvo; base += 256u * Q_U) {
-        half8 v[Q_U];
-        uint32_t lr[Q_U], pp[Q_U];
-#pragma unroll
-        for (int u = 0; u < Q_U; ++u) {
-            const uint32_t i = base + u * 256u + threadIdx.x;
-            lr[u] = i / Kp8;
-            pp[u] = i - lr[u] * Kp8;
-            if (i < nvo && pp[u] < K8) v[u] = ((const half8*)(x + map.phys(r0 + lr[u]) * ldx))[pp[u]];
-        }
+        if (base) request(base);
 #pragma unroll
         for (int u = 0; u < Q_U; ++u) {
             const uint32_t i = base + u * 256u + threadIdx.x;
