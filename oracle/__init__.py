@@ -270,8 +270,9 @@ def linear_a8_codes(qx, act, wcodes, w_scale, w_zp, w_signed=False, bias=None, w
     return y, acc
 
 
-def conv3x3_w_only(x, codes, w_scale, w_zp, bias=None, dtype=F16, pix=None, residual=None):
-    """x [B,H,W,Cin] 16-bit; codes [N, 9*Cin] with k = (r*3+s)*Cin + c.  Returns y uint16 [B*H*W or len(pix), N]."""
+def conv3x3_w_only(x, codes, w_scale, w_zp, bias=None, dtype=F16, pix=None, residual=None, stride=1):
+    """x [B,H,W,Cin] 16-bit; codes [N, 9*Cin] with k = (r*3+s)*Cin + c.  Returns y uint16 [B*Ho*Wo or len(pix), N]
+    (Ho = (H-1)//stride + 1, likewise Wo; pix and residual index output pixels)."""
     x = _u16(x)
     bias = _u16(bias)
     codes = np.ascontiguousarray(codes, np.uint8)
@@ -279,15 +280,16 @@ def conv3x3_w_only(x, codes, w_scale, w_zp, bias=None, dtype=F16, pix=None, resi
     N = codes.shape[0]
     assert codes.shape[1] == 9 * Cin
     pix, npx = _rows(pix)
-    R = npx if pix is not None else B * H * W
+    R = npx if pix is not None else B * ((H - 1) // stride + 1) * ((W - 1) // stride + 1)
     y = np.empty((R, N), np.uint16)
     _check(lib().orc_conv3x3_w_only(_p(x), B, H, W, Cin, _p(codes), N, _p(np.ascontiguousarray(w_scale, np.float32)),
                                     _p(np.ascontiguousarray(w_zp, np.int32)), _p(bias), dtype, _p(y), _p(pix),
-                                    C.c_long(npx), _p(_u16(residual))), "conv3x3_w_only")
+                                    C.c_long(npx), _p(_u16(residual)), int(stride)), "conv3x3_w_only")
     return y
 
 
-def conv3x3_a8(x, wcodes, w_scale, w_zp, w_signed=False, act=None, bias=None, pix=None, want_acc=True, residual=None):
+def conv3x3_a8(x, wcodes, w_scale, w_zp, w_signed=False, act=None, bias=None, pix=None, want_acc=True, residual=None,
+               stride=1):
     """Returns (y uint16, acc int32 or None, (act_scale, act_zp))."""
     x = _u16(x)
     bias = _u16(bias)
@@ -296,7 +298,7 @@ def conv3x3_a8(x, wcodes, w_scale, w_zp, w_signed=False, act=None, bias=None, pi
     N = wcodes.shape[0]
     assert wcodes.shape[1] == 9 * Cin
     pix, npx = _rows(pix)
-    R = npx if pix is not None else B * H * W
+    R = npx if pix is not None else B * ((H - 1) // stride + 1) * ((W - 1) // stride + 1)
     y = np.empty((R, N), np.uint16)
     acc = np.empty((R, N), np.int32) if want_acc else None
     s = C.c_float(0.0 if act is None else act[0])
@@ -304,7 +306,7 @@ def conv3x3_a8(x, wcodes, w_scale, w_zp, w_signed=False, act=None, bias=None, pi
     _check(lib().orc_conv3x3_a8(_p(x), B, H, W, Cin, _p(wcodes), N, int(w_signed),
                                 _p(np.ascontiguousarray(w_scale, np.float32)), _p(np.ascontiguousarray(w_zp, np.int32)),
                                 int(act is None), C.byref(s), C.byref(z), _p(bias), _p(y), _p(acc), _p(pix),
-                                C.c_long(npx), _p(_u16(residual))), "conv3x3_a8")
+                                C.c_long(npx), _p(_u16(residual)), int(stride)), "conv3x3_a8")
     return y, acc, (np.float32(s.value), int(z.value))
 
 

@@ -598,13 +598,18 @@ int orc_linear_a8_codes(const uint8_t* qx, long M, int K, float act_scale, int32
 /* with x = 0 outside the image.  `pix` selects output pixels (flat index    */
 /* (b*H + i)*W + j), NULL = all.  residual: [B,H,W,N] or NULL, as for the    */
 /* linear layers.                                                            */
+/* stride 2 (the UNet's downsampling convolutions; same filter, padding 1):  */
+/* the output is [B,Ho,Wo,N] with Ho = (H-1)/2 + 1, Wo = (W-1)/2 + 1, and    */
+/*     y[b,i,j,n] = sum_{r,s,c} x[b,2i+r-1,2j+s-1,c] * w[n,r,s,c] + bias[n]; */
+/* pix and residual then index output pixels (b*Ho + i)*Wo + j.              */
 /* ------------------------------------------------------------------------- */
 int orc_conv3x3_w_only(const uint16_t* x, int B, int H, int W, int Cin, const uint8_t* codes, int N,
                        const float* w_scale, const int32_t* w_zp, const uint16_t* bias, int dtype, uint16_t* y,
-                       const int64_t* pix, long npix, const uint16_t* residual) {
+                       const int64_t* pix, long npix, const uint16_t* residual, int stride) {
     if (!x || !codes || !w_scale || !w_zp || !y || B <= 0 || H <= 0 || W <= 0 || Cin <= 0 || N <= 0) return ORC_BAD_ARG;
-    long M = (long)B * H * W;
-    long R = pix ? npix : M;
+    if (stride != 1 && stride != 2) return ORC_BAD_ARG;
+    const int Ho = (H - 1) / stride + 1, Wo = (W - 1) / stride + 1;
+    long R = pix ? npix : (long)B * Ho * Wo;
     if (R <= 0) return ORC_BAD_ARG;
     int K = 9 * Cin;
     double* what = (double*)malloc((size_t)N * K * sizeof(double));
@@ -615,11 +620,11 @@ int orc_conv3x3_w_only(const uint16_t* x, int B, int H, int W, int Cin, const ui
 #pragma omp parallel for schedule(static)
     for (long rr = 0; rr < R; ++rr) {
         long m = pix ? pix[rr] : rr;
-        int j = (int)(m % W), i = (int)((m / W) % H), b = (int)(m / ((long)W * H));
+        int j = (int)(m % Wo), i = (int)((m / Wo) % Ho), b = (int)(m / ((long)Wo * Ho));
         double* col = (double*)calloc((size_t)K, sizeof(double));
         for (int r = 0; r < 3; ++r)
             for (int s = 0; s < 3; ++s) {
-                int ii = i + r - 1, jj = j + s - 1;
+                int ii = stride * i + r - 1, jj = stride * j + s - 1;
                 if (ii < 0 || ii >= H || jj < 0 || jj >= W) continue;
                 const uint16_t* px = x + (((long)b * H + ii) * W + jj) * Cin;
                 for (int c = 0; c < Cin; ++c) col[(r * 3 + s) * Cin + c] = in16(px[c], dtype);
@@ -644,12 +649,13 @@ int orc_conv3x3_w_only(const uint16_t* x, int B, int H, int W, int Cin, const ui
 int orc_conv3x3_a8(const uint16_t* x, int B, int H, int W, int Cin, const uint8_t* wcodes, int N, int w_signed,
                    const float* w_scale, const int32_t* w_zp, int dynamic, float* act_scale, int32_t* act_zp,
                    const uint16_t* bias, uint16_t* y, int32_t* acc_out, const int64_t* pix, long npix,
-                   const uint16_t* residual) {
+                   const uint16_t* residual, int stride) {
     if (!x || !wcodes || !w_scale || !w_zp || !act_scale || !act_zp || !y || B <= 0 || H <= 0 || W <= 0 || Cin <= 0 ||
-        N <= 0)
+        N <= 0 || (stride != 1 && stride != 2))
         return ORC_BAD_ARG;
-    long M = (long)B * H * W;
-    long R = pix ? npix : M;
+    const int Ho = (H - 1) / stride + 1, Wo = (W - 1) / stride + 1;
+    long M = (long)B * H * W; /* input pixels: the activation parameters are those of the whole input tensor */
+    long R = pix ? npix : (long)B * Ho * Wo;
     if (R <= 0) return ORC_BAD_ARG;
     if (dynamic) {
         int rc = orc_act_params(x, M, Cin, Cin, ORC_F16, act_scale, act_zp);
@@ -664,11 +670,11 @@ int orc_conv3x3_a8(const uint16_t* x, int B, int H, int W, int Cin, const uint8_
 #pragma omp parallel for schedule(static) reduction(| : overflow)
     for (long rr = 0; rr < R; ++rr) {
         long m = pix ? pix[rr] : rr;
-        int j = (int)(m % W), i = (int)((m / W) % H), b = (int)(m / ((long)W * H));
+        int j = (int)(m % Wo), i = (int)((m / Wo) % Ho), b = (int)(m / ((long)Wo * Ho));
         int* col = (int*)calloc((size_t)K, sizeof(int));
         for (int r = 0; r < 3; ++r)
             for (int s = 0; s < 3; ++s) {
-                int ii = i + r - 1, jj = j + s - 1;
+                int ii = stride * i + r - 1, jj = stride * j + s - 1;
                 if (ii < 0 || ii >= H || jj < 0 || jj >= W) continue;
                 const uint16_t* px = x + (((long)b * H + ii) * W + jj) * Cin;
                 for (int c = 0; c < Cin; ++c)

@@ -734,3 +734,37 @@ def test_split_shortcut_equals_the_concatenated_layer_where_sums_are_exact(orc):
     yb = orc.conv3x3_a8(xb, wb.reshape(N, -1), one, zero, residual=ya)[0].view(np.float16).astype(np.float64)
     ref = whole.view(np.float16).astype(np.float64)
     assert np.abs(yb - ref).max() <= 0.02 * np.abs(ref).max()
+
+
+@pytest.mark.parametrize("H,W", [(6, 8), (5, 7), (1, 1), (2, 9)])
+def test_conv_stride_two_against_a_library_convolution(orc, H, W):
+    """Stride 2, padding 1 (the downsampling convolutions): weight-only against a float64 library convolution on
+    dequantised weights, the integer accumulators of the 8-bit-activation form against an integer convolution; odd
+    sizes included (Ho = (H-1)//2 + 1).  The activation parameters are those of the whole input, also of the pixels
+    a stride-2 filter never centres on."""
+    import torch
+    B, Cin, N = 2, 8, 5
+    x, w, b, c, s, z = _conv_case(orc, 120 + H, B, H, W, Cin, N, 4)
+    Ho, Wo = (H - 1) // 2 + 1, (W - 1) // 2 + 1
+    y = orc.conv3x3_w_only(x, c, s, z, b, stride=2).view(np.float16)
+    assert y.shape == (B * Ho * Wo, N)
+    what = (s.astype(np.float64)[:, None] * (c.astype(np.float64) - z[:, None])).reshape(N, 3, 3, Cin)
+    ref = torch.nn.functional.conv2d(torch.from_numpy(x.astype(np.float64)).permute(0, 3, 1, 2),
+                                     torch.from_numpy(what).permute(0, 3, 1, 2), torch.from_numpy(b.astype(np.float64)),
+                                     padding=1, stride=2).permute(0, 2, 3, 1).numpy().reshape(-1, N)
+    ref16 = ref.astype(np.float16)
+    ulp = np.abs(y.astype(np.float64) - ref16.astype(np.float64)) / np.spacing(np.abs(ref16)).astype(np.float64)
+    assert ulp.max() <= 1.0
+    # every output pixel of the stride-2 result is the stride-1 result at the even positions
+    full = orc.conv3x3_w_only(x, c, s, z, b).view(np.float16).reshape(B, H, W, N)
+    assert np.array_equal(y.reshape(B, Ho, Wo, N), full[:, ::2, ::2, :])
+    pix = [0, B * Ho * Wo - 1]
+    r = np.random.default_rng(9).normal(0, 1, (B, Ho, Wo, N)).astype(np.float16)
+    yr = orc.conv3x3_w_only(x, c, s, z, b, stride=2, residual=r).view(np.float16)
+    assert np.array_equal(orc.conv3x3_w_only(x, c, s, z, b, stride=2, residual=r, pix=pix).view(np.float16), yr[pix])
+    assert not np.array_equal(yr, y)
+    ya, acc, act = orc.conv3x3_a8(x, c, s, z, bias=b, stride=2)
+    ya1, acc1, act1 = orc.conv3x3_a8(x, c, s, z, bias=b)
+    assert act == act1 == orc.act_params(x.reshape(-1, Cin))
+    assert np.array_equal(acc.reshape(B, Ho, Wo, N), acc1.reshape(B, H, W, N)[:, ::2, ::2, :])
+    assert np.array_equal(ya.reshape(B, Ho, Wo, N), ya1.reshape(B, H, W, N)[:, ::2, ::2, :])
