@@ -213,17 +213,21 @@ def ff_pairs(mq, torch, iters, overhead_us):
 
 
 def convs(mq, torch, iters, overhead_us):
-    """3x3 convolutions of the UNet's residual blocks at latent 128x128, batch 4 (channels-last), W4A16 and W4A8."""
+    """3x3 convolutions of the UNet's residual blocks and its two downsamplers (stride 2) at latent 128x128, batch 4
+    (channels-last), W4A16 and W4A8."""
     dev = torch.device("cuda:0")
     gen = torch.Generator(device=dev)
     gen.manual_seed(2)
-    print("\n# 3x3 convolution (stride 1, padding 1), cold operands; ops = 2 M N 9 Cin, bytes = x once + weights + y once")
-    print(f"{'B':>3s}{'H':>5s}{'W':>5s}{'Cin':>6s}{'N':>6s} {'mode':5s}{'us/call':>9s}{'T(FL)OP/s':>10s}{'GB/s':>8s}{'t_HBM us':>9s}"
+    print("\n# 3x3 convolution (padding 1), cold operands; ops = 2 M N 9 Cin over the M output pixels, bytes = x once + "
+          "weights + y once")
+    print(f"{'B':>3s}{'H':>5s}{'W':>5s}{'Cin':>6s}{'N':>6s}{'str':>4s} {'mode':5s}{'us/call':>9s}{'T(FL)OP/s':>10s}{'GB/s':>8s}{'t_HBM us':>9s}"
           f"{'t_MFMA us':>10s}{'frac':>7s}")
-    for (B, H, W, Cin, N) in ((4, 128, 128, 320, 320), (4, 64, 64, 640, 640), (4, 32, 32, 1280, 1280), (4, 32, 32, 2560, 1280)):
-        M = B * H * W
+    for (B, H, W, Cin, N, stride) in ((4, 128, 128, 320, 320, 1), (4, 64, 64, 640, 640, 1), (4, 32, 32, 1280, 1280, 1),
+                                      (4, 32, 32, 2560, 1280, 1), (4, 128, 128, 320, 320, 2), (4, 64, 64, 640, 640, 2)):
+        Ho, Wo = (H - 1) // stride + 1, (W - 1) // stride + 1
+        M = B * Ho * Wo
         ops = 2.0 * M * N * 9 * Cin
-        alg = 2 * M * Cin + N * 9 * Cin // 2 + 10 * N + 2 * M * N
+        alg = 2 * B * H * W * Cin + N * 9 * Cin // 2 + 10 * N + 2 * M * N
         nsets = max(2, min(iters, -(-LLC_BYTES // alg)))
         for mode in ("w4", "a4"):
             calls = []
@@ -236,11 +240,11 @@ def convs(mq, torch, iters, overhead_us):
                 ts = mq.conv_tap_sums(c, Cin, 4)
                 del w, c
                 x = torch.randn(B, H, W, Cin, generator=gen, device=dev).half()
-                y = torch.empty(B, H, W, N, dtype=torch.float16, device=dev)
+                y = torch.empty(B, Ho, Wo, N, dtype=torch.float16, device=dev)
                 if mode == "w4":
-                    calls.append(lambda x=x, pw=pw, y=y: mq.conv3x3_w_only(x, pw, out=y))
+                    calls.append(lambda x=x, pw=pw, y=y: mq.conv3x3_w_only(x, pw, out=y, stride=stride))
                 else:
-                    calls.append(lambda x=x, pw=pw, ts=ts, y=y: mq.conv3x3_a8(x, pw, ts, out=y, ws=ws))
+                    calls.append(lambda x=x, pw=pw, ts=ts, y=y: mq.conv3x3_a8(x, pw, ts, out=y, ws=ws, stride=stride))
             for i in range(min(nsets, 4)):
                 calls[i]()
             torch.cuda.synchronize()
@@ -252,7 +256,7 @@ def convs(mq, torch, iters, overhead_us):
             torch.cuda.synchronize()
             us = e0.elapsed_time(e1) * 1e3 / iters
             t_hbm, t_mfma = alg / HBM * 1e6, ops / PEAK["w" if mode == "w4" else "a"] * 1e6
-            print(f"{B:3d}{H:5d}{W:5d}{Cin:6d}{N:6d} {mode:5s}{us:9.2f}{ops / us / 1e6:10.1f}{alg / us / 1e3:8.0f}{t_hbm:9.2f}"
+            print(f"{B:3d}{H:5d}{W:5d}{Cin:6d}{N:6d}{stride:4d} {mode:5s}{us:9.2f}{ops / us / 1e6:10.1f}{alg / us / 1e3:8.0f}{t_hbm:9.2f}"
                   f"{t_mfma:10.2f}{max(t_hbm, t_mfma) / us:7.3f}", flush=True)
             del calls
             torch.cuda.empty_cache()

@@ -241,15 +241,19 @@ int mq_qlinear_a8_codes(const int8_t* a8, int M, int K, int lda, const float* ac
  * mq_pack_weights is [N, 9*Cin] with k = (r*3 + s)*Cin + c (filter row r, filter column s, input channel c), in
  * MQ_LAYOUT_KERNEL.  No im2col copy is made: the GEMM's activation loads address the taps themselves, and taps
  * outside the image read as zero.  Cin % 64 == 0, N % 8 == 0, B*H*W*Cin*2 < 2^31.
+ * stride: 1, or 2 for the UNet's downsampling convolutions: the output is then [B,Ho,Wo,N] with Ho = (H-1)/2 + 1,
+ * Wo = (W-1)/2 + 1, output pixel (i,j) centred on input pixel (2i,2j); y, residual and acc_debug have that shape.
+ * A 1x1 convolution needs no entry point of its own: on channels-last tensors it is the linear layer over the
+ * [B*H*W, Cin] matrix.
  * residual: nullable [B,H,W,N] fp16, contiguous, added before the rounding (may be y itself): the skip connection of
  * a residual block, or the output of the convolution over the other part of a split channel-concatenated input.
  * ---------------------------------------------------------------------------------------------- */
 
 /* Weight-only convolution, W{2,3,4,8}A16:
  *     y = fp16( sum_{r,s,c} x[b,i+r-1,j+s-1,c] * scale[n]*(code - zp[n]) + bias[n] + residual[b,i,j,n] ). */
-int mq_conv3x3_w_only(const void* x, int B, int H, int W, int Cin, const void* packed, int N, int bits, int layout,
-                      const float* w_scale, const int32_t* w_zp, const void* bias, void* y, const void* residual,
-                      void* stream);
+int mq_conv3x3_w_only(const void* x, int B, int H, int W, int Cin, int stride, const void* packed, int N, int bits,
+                      int layout, const float* w_scale, const int32_t* w_zp, const void* bias, void* y,
+                      const void* residual, void* stream);
 
 /* Sums of the weight codes per filter tap, [9][N] int32 (tap = r*3 + s): needed by mq_conv3x3_a8 for the output
  * pixels whose filter reaches outside the image.  codes [N, 9*Cin] as handed to mq_pack_weights. */
@@ -261,9 +265,10 @@ size_t mq_conv3x3_a8_workspace_bytes(int B, int H, int W, int Cin);
  * parameters) as in mq_qlinear_w8a8; a padded position holds the value 0, whose code is the zero point:
  *     ACC[m,n] = sum over in-image (r,s), c of (qx - z_x)(qw - z_w[n]),
  *     y = fp16(ACC * s_x * s_w[n] + bias[n] + residual[m,n]).
- * acc_debug nullable [B*H*W, N] int32. */
-int mq_conv3x3_a8(const void* x, int B, int H, int W, int Cin, const void* packed, int N, int w_bits, int layout,
-                  int w_signed, const float* w_scale, const int32_t* w_zp, const int32_t* w_colsum,
+ * The activation parameters are those of the whole input tensor, whatever the stride.
+ * acc_debug nullable [B*Ho*Wo, N] int32. */
+int mq_conv3x3_a8(const void* x, int B, int H, int W, int Cin, int stride, const void* packed, int N, int w_bits,
+                  int layout, int w_signed, const float* w_scale, const int32_t* w_zp, const int32_t* w_colsum,
                   const int32_t* w_tapsum, const float* act_scale, const int32_t* act_zp, const void* bias, void* y,
                   int32_t* acc_debug, const void* residual, float* act_scale_out, int32_t* act_zp_out, void* ws,
                   size_t ws_bytes, void* stream);

@@ -349,14 +349,21 @@ def _res4(residual, shape):
     return _ptr(residual)
 
 
-def conv3x3_w_only(x: torch.Tensor, w: PackedWeight, bias=None, out=None, residual=None) -> torch.Tensor:
-    """x [B,H,W,Cin] fp16 channels-last contiguous; w packed from the [N, 9*Cin] matrix.  Returns y [B,H,W,N]
-    (+ residual [B,H,W,N], added before the rounding)."""
+def _conv_out_hw(H: int, W: int, stride: int):
+    assert stride in (1, 2)
+    return (H - 1) // stride + 1, (W - 1) // stride + 1
+
+
+def conv3x3_w_only(x: torch.Tensor, w: PackedWeight, bias=None, out=None, residual=None, stride: int = 1) -> torch.Tensor:
+    """x [B,H,W,Cin] fp16 channels-last contiguous; w packed from the [N, 9*Cin] matrix.  Returns y [B,Ho,Wo,N]
+    (+ residual of that shape, added before the rounding); stride 1 or 2."""
     assert x.is_cuda and x.dim() == 4 and x.is_contiguous() and x.dtype == torch.float16
     B, H, W, Cin = x.shape
     assert w.K == 9 * Cin
-    y = out if out is not None else torch.empty((B, H, W, w.N), dtype=torch.float16, device=x.device)
-    _check(load().mq_conv3x3_w_only(_ptr(x), B, H, W, Cin, _ptr(w.packed), w.N, w.bits, w.layout, _ptr(w.scale),
+    Ho, Wo = _conv_out_hw(H, W, stride)
+    y = out if out is not None else torch.empty((B, Ho, Wo, w.N), dtype=torch.float16, device=x.device)
+    assert tuple(y.shape) == (B, Ho, Wo, w.N) and y.is_contiguous()
+    _check(load().mq_conv3x3_w_only(_ptr(x), B, H, W, Cin, stride, _ptr(w.packed), w.N, w.bits, w.layout, _ptr(w.scale),
                                     _ptr(w.zp), _ptr(bias), _ptr(y), _res4(residual, y.shape), _stream()),
            "mq_conv3x3_w_only")
     return y
@@ -367,18 +374,20 @@ def conv3x3_a8_workspace_bytes(B: int, H: int, W: int, Cin: int) -> int:
 
 
 def conv3x3_a8(x, w: PackedWeight, tapsum, act=None, bias=None, out=None, ws=None, want_acc=False, want_act=False,
-               residual=None):
-    """Returns (y [B,H,W,N], acc int32 [B*H*W,N] or None, (act_scale, act_zp) or None)."""
+               residual=None, stride: int = 1):
+    """Returns (y [B,Ho,Wo,N], acc int32 [B*Ho*Wo,N] or None, (act_scale, act_zp) or None)."""
     assert x.is_cuda and x.dim() == 4 and x.is_contiguous() and x.dtype == torch.float16
     B, H, W, Cin = x.shape
     assert w.K == 9 * Cin
-    y = out if out is not None else torch.empty((B, H, W, w.N), dtype=torch.float16, device=x.device)
-    acc = torch.empty((B * H * W, w.N), dtype=torch.int32, device=x.device) if want_acc else None
+    Ho, Wo = _conv_out_hw(H, W, stride)
+    y = out if out is not None else torch.empty((B, Ho, Wo, w.N), dtype=torch.float16, device=x.device)
+    assert tuple(y.shape) == (B, Ho, Wo, w.N) and y.is_contiguous()
+    acc = torch.empty((B * Ho * Wo, w.N), dtype=torch.int32, device=x.device) if want_acc else None
     ws = _workspace(conv3x3_a8_workspace_bytes(B, H, W, Cin), x.device, ws)
     a_s, a_z = (None, None) if act is None else act
     so = torch.empty(1, dtype=torch.float32, device=x.device) if want_act else None
     zo = torch.empty(1, dtype=torch.int32, device=x.device) if want_act else None
-    _check(load().mq_conv3x3_a8(_ptr(x), B, H, W, Cin, _ptr(w.packed), w.N, w.bits, w.layout, int(w.signed),
+    _check(load().mq_conv3x3_a8(_ptr(x), B, H, W, Cin, stride, _ptr(w.packed), w.N, w.bits, w.layout, int(w.signed),
                                 _ptr(w.scale), _ptr(w.zp), _ptr(w.colsum), _ptr(tapsum), _ptr(a_s), _ptr(a_z), _ptr(bias),
                                 _ptr(y), _ptr(acc), _res4(residual, y.shape), _ptr(so), _ptr(zo), _ptr(ws),
                                 C.c_size_t(ws.numel()), _stream()), "mq_conv3x3_a8")

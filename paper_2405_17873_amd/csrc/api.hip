@@ -224,10 +224,10 @@ int mq_qlinear_a8_codes(const int8_t* a8, int M, int K, int lda, const float* ac
                                 w_colsum, bias, y, ldy, acc_debug, residual, ldr, (hipStream_t)stream);
 }
 
-static int check_conv_common(const void* x, int B, int H, int W, int Cin, const void* packed, int N, int layout,
-                             const float* w_scale, const int32_t* w_zp, const void* bias, const void* y) {
+static int check_conv_common(const void* x, int B, int H, int W, int Cin, int stride, const void* packed, int N,
+                             int layout, const float* w_scale, const int32_t* w_zp, const void* bias, const void* y) {
     if (!x || !packed || !w_scale || !w_zp || !y) return MQ_ERR_BAD_ARG;
-    if (B <= 0 || H <= 0 || W <= 0 || Cin <= 0 || N <= 0) return MQ_ERR_BAD_SHAPE;
+    if (B <= 0 || H <= 0 || W <= 0 || Cin <= 0 || N <= 0 || (stride != 1 && stride != 2)) return MQ_ERR_BAD_SHAPE;
     if (layout != MQ_LAYOUT_KERNEL) return MQ_ERR_UNSUPPORTED_LAYOUT;
     if (Cin % 64 != 0 || N % 8 != 0) return MQ_ERR_BAD_SHAPE;
     const long M = (long)B * H * W;
@@ -239,14 +239,14 @@ static int check_conv_common(const void* x, int B, int H, int W, int Cin, const 
     return MQ_OK;
 }
 
-int mq_conv3x3_w_only(const void* x, int B, int H, int W, int Cin, const void* packed, int N, int bits, int layout,
-                      const float* w_scale, const int32_t* w_zp, const void* bias, void* y, const void* residual,
-                      void* stream) {
+int mq_conv3x3_w_only(const void* x, int B, int H, int W, int Cin, int stride, const void* packed, int N, int bits,
+                      int layout, const float* w_scale, const int32_t* w_zp, const void* bias, void* y,
+                      const void* residual, void* stream) {
     if (!bits_ok(bits)) return MQ_ERR_UNSUPPORTED_BITS;
-    int rc = check_conv_common(x, B, H, W, Cin, packed, N, layout, w_scale, w_zp, bias, y);
+    int rc = check_conv_common(x, B, H, W, Cin, stride, packed, N, layout, w_scale, w_zp, bias, y);
     if (rc) return rc;
     if ((rc = check_residual(residual, N, N))) return rc;
-    return launch_conv3x3_w_only(x, B, H, W, Cin, packed, N, bits, w_scale, w_zp, bias, y, residual,
+    return launch_conv3x3_w_only(x, B, H, W, Cin, stride, packed, N, bits, w_scale, w_zp, bias, y, residual,
                                  (hipStream_t)stream);
 }
 
@@ -263,13 +263,13 @@ size_t mq_conv3x3_a8_workspace_bytes(int B, int H, int W, int Cin) {
     return A8Workspace::bytes((long)B * H * W, Cin);
 }
 
-int mq_conv3x3_a8(const void* x, int B, int H, int W, int Cin, const void* packed, int N, int w_bits, int layout,
-                  int w_signed, const float* w_scale, const int32_t* w_zp, const int32_t* w_colsum,
+int mq_conv3x3_a8(const void* x, int B, int H, int W, int Cin, int stride, const void* packed, int N, int w_bits,
+                  int layout, int w_signed, const float* w_scale, const int32_t* w_zp, const int32_t* w_colsum,
                   const int32_t* w_tapsum, const float* act_scale, const int32_t* act_zp, const void* bias, void* y,
                   int32_t* acc_debug, const void* residual, float* act_scale_out, int32_t* act_zp_out, void* ws,
                   size_t ws_bytes, void* stream) {
     if (w_bits != 4 && w_bits != 8) return MQ_ERR_UNSUPPORTED_BITS;
-    int rc = check_conv_common(x, B, H, W, Cin, packed, N, layout, w_scale, w_zp, bias, y);
+    int rc = check_conv_common(x, B, H, W, Cin, stride, packed, N, layout, w_scale, w_zp, bias, y);
     if (rc) return rc;
     if ((rc = check_residual(residual, N, N))) return rc;
     if (!w_colsum || !w_tapsum || !ws) return MQ_ERR_BAD_ARG;
@@ -285,7 +285,7 @@ int mq_conv3x3_a8(const void* x, int B, int H, int W, int Cin, const void* packe
     rc = launch_act_quant(x, (int)M, Cin, Cin, RowMap{0, 0, 0}, act_scale, act_zp, w.a8, w.rowsum, w.params, w.partials,
                           act_scale_out, act_zp_out, st);
     if (rc) return rc;
-    return launch_conv3x3_a8(w.a8, w.params, B, H, W, Cin, packed, N, w_bits, w_signed ? 1 : 0, w_scale, w_zp, w_colsum,
+    return launch_conv3x3_a8(w.a8, w.params, B, H, W, Cin, stride, packed, N, w_bits, w_signed ? 1 : 0, w_scale, w_zp, w_colsum,
                              w_tapsum, bias, y, acc_debug, residual, st);
 }
 

@@ -351,7 +351,9 @@ struct GemmArgs {
     const int32_t* act_zp_p;
     // MODE 3 / 4 (3x3 convolution, stride 1, zero padding 1, channels-last): a is the [B*H*W, Cin] activation tensor
     // (a_row_bytes per pixel), K = 9 * Cin, row m is output pixel m; the k order is (filter row, filter column, c)
-    int conv_h, conv_w;
+    int conv_h, conv_w;      // input image
+    int conv_ho, conv_wo;    // output image: (H - 1) / stride + 1, likewise W; M = B * conv_ho * conv_wo
+    int conv_stride;         // 1 or 2: output pixel (i, j) is centred on input pixel (stride * i, stride * j)
     int conv_cpt;            // 64-channel chunks per filter tap (Cin / 64)
     uint32_t conv_cpt_inv;   // ceil(2^32 / conv_cpt) for conv_cpt > 1
     const int32_t* w_tapsum; // MODE 4: [9][N] sums of the weight codes per filter tap
@@ -466,7 +468,7 @@ void gemm_kernel(const GemmArgs g) {
     // convolution: which of the 9 filter taps (bit r * 3 + s) of output pixel m read inside the image
     auto tap_mask = [&](int m) -> uint32_t {
         if (m >= g.M) return 0u;
-        const int j = m % g.conv_w, i = (m / g.conv_w) % g.conv_h;
+        const int j = (m % g.conv_wo) * g.conv_stride, i = ((m / g.conv_wo) % g.conv_ho) * g.conv_stride;
         const uint32_t rows = (i > 0 ? 1u : 0u) | 2u | (i + 1 < g.conv_h ? 4u : 0u);
         const uint32_t cols = (j > 0 ? 1u : 0u) | 2u | (j + 1 < g.conv_w ? 4u : 0u);
         uint32_t mk = 0;
@@ -487,7 +489,12 @@ void gemm_kernel(const GemmArgs g) {
             // row = output pixel; the lane's 16 bytes of a stage lie in one 64-channel chunk (int8: piece / 4 says
             // which of the stage's two), i.e. in one filter tap: per stage it adds that tap's pixel offset, or
             // reads nothing (zero) where the tap falls outside the image
-            a_voff[i] = (int)((long)(m0 + row) * g.a_row_bytes) + (I8 ? (piece & 3) : piece) * 16;
+            const int mo = m0 + row < g.M ? m0 + row : g.M - 1;  // (rows past M read nothing: their tap mask is empty)
+            const int per_image = g.conv_ho * g.conv_wo;
+            const int bi = mo / per_image, rem = mo - bi * per_image;
+            const int io = rem / g.conv_wo, jo = rem - io * g.conv_wo;
+            const long centre = ((long)bi * g.conv_h + io * g.conv_stride) * g.conv_w + jo * g.conv_stride;
+            a_voff[i] = (int)(centre * g.a_row_bytes) + (I8 ? (piece & 3) : piece) * 16;
             a_half[i] = I8 ? piece >> 2 : 0;
             a_taps[i] = tap_mask(m0 + row);
         }
@@ -1249,8 +1256,9 @@ static int run_gemm_r(GemmArgs& g, int tile_index, hipStream_t st) {
             prepared[dev] = true;
         }
     }
-    const double kin = MODE >= 3 ? g.K / 9.0 : (double)g.K;  // a convolution reads each activation once, not nine times
-    const double abytes = I8 ? 1.0 * g.M * kin + (MODE == 0 ? 4.0 * g.M : 0.0) : 2.0 * g.M * kin;
+    // (a convolution reads each input pixel once, not nine times: the whole input tensor)
+    const double abytes = MODE >= 3 ? (double)g.a_bytes
+                                    : (I8 ? 1.0 * g.M * g.K + (MODE == 0 ? 4.0 * g.M : 0.0) : 2.0 * g.M * g.K);
     const double ybytes = MODE == 1 ? 1.0 * g.M * g.ld8 + (g.y ? 1.0 * g.M * g.N : 0.0) : 2.0 * g.M * g.N;
     ProfScope prof(st, slot, 2.0 * g.M * g.N * g.K,
                    abytes + (double)g.N * g.K * BITS / 8 + (I8 ? 14.0 : 10.0) * g.N + ybytes);
@@ -1478,10 +1486,13 @@ int launch_gemm_a8_codes(const int8_t* a8, long lda, const float* act_scale, con
 
 
 // 3x3 convolution, stride 1, zero padding 1, channels-last (MODE 3 weight-only, MODE 4 int8 activations).
-static void conv_args(GemmArgs& g, int B, int H, int W, int Cin, long pix_bytes) {
+static void conv_args(GemmArgs& g, int B, int H, int W, int Cin, int stride, long pix_bytes) {
     g.a_row_bytes = pix_bytes;
     g.a_bytes = (uint32_t)((long)B * H * W * pix_bytes);
-    g.M = B * H * W;
+    g.conv_stride = stride;
+    g.conv_ho = (H - 1) / stride + 1;
+    g.conv_wo = (W - 1) / stride + 1;
+    g.M = B * g.conv_ho * g.conv_wo;
     g.K = 9 * Cin;
     g.conv_h = H;
     g.conv_w = W;
@@ -1505,12 +1516,12 @@ static int dispatch_conv_w_only(GemmArgs& g, hipStream_t st) {
     }
 }
 
-int launch_conv3x3_w_only(const void* x, int B, int H, int W, int Cin, const void* packed, int N, int bits,
+int launch_conv3x3_w_only(const void* x, int B, int H, int W, int Cin, int stride, const void* packed, int N, int bits,
                           const float* w_scale, const int32_t* w_zp, const void* bias, void* y, const void* res,
                           hipStream_t st) {
     GemmArgs g{};
     g.a = x;
-    conv_args(g, B, H, W, Cin, (long)Cin * 2);
+    conv_args(g, B, H, W, Cin, stride, (long)Cin * 2);
     g.packed = (const uint8_t*)packed;
     g.packed_bytes = (uint32_t)((long)((N + 31) / 32) * (g.K / 64) * 256 * bits);
     g.N = N;
@@ -1527,13 +1538,13 @@ int launch_conv3x3_w_only(const void* x, int B, int H, int W, int Cin, const voi
     return MQ_ERR_UNSUPPORTED_BITS;
 }
 
-int launch_conv3x3_a8(const int8_t* a8, const ActParams* params, int B, int H, int W, int Cin, const void* packed, int N,
+int launch_conv3x3_a8(const int8_t* a8, const ActParams* params, int B, int H, int W, int Cin, int stride, const void* packed, int N,
                       int w_bits, int w_signed, const float* w_scale, const int32_t* w_zp, const int32_t* w_colsum,
                       const int32_t* w_tapsum, const void* bias, void* y, int32_t* acc_debug, const void* res,
                       hipStream_t st) {
     GemmArgs g{};
     g.a = a8;
-    conv_args(g, B, H, W, Cin, (long)(Cin + 127) / 128 * 128);
+    conv_args(g, B, H, W, Cin, stride, (long)(Cin + 127) / 128 * 128);
     g.packed = (const uint8_t*)packed;
     g.packed_bytes = (uint32_t)((long)((N + 31) / 32) * (g.K / 64) * 256 * w_bits);
     g.N = N;

@@ -98,10 +98,10 @@ int launch_gemm_a8_codes(const int8_t* a8, long lda, const float* act_scale, con
                          const int32_t* w_colsum, const void* bias, void* y, int ldy, int32_t* acc_debug,
                          const void* res, int ldr, hipStream_t st);
 
-int launch_conv3x3_w_only(const void* x, int B, int H, int W, int Cin, const void* packed, int N, int bits,
+int launch_conv3x3_w_only(const void* x, int B, int H, int W, int Cin, int stride, const void* packed, int N, int bits,
                           const float* w_scale, const int32_t* w_zp, const void* bias, void* y, const void* res,
                           hipStream_t st);
-int launch_conv3x3_a8(const int8_t* a8, const ActParams* params, int B, int H, int W, int Cin, const void* packed, int N,
+int launch_conv3x3_a8(const int8_t* a8, const ActParams* params, int B, int H, int W, int Cin, int stride, const void* packed, int N,
                       int w_bits, int w_signed, const float* w_scale, const int32_t* w_zp, const int32_t* w_colsum,
                       const int32_t* w_tapsum, const void* bias, void* y, int32_t* acc_debug, const void* res,
                       hipStream_t st);

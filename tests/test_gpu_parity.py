@@ -599,6 +599,41 @@ def test_conv_a8(mq, orc, bits, sym, tile):
         mq.tune_force_tile(-1)
 
 
+@pytest.mark.parametrize("tile", (-1, 0, 1, 2, 5))
+def test_conv_stride_two(mq, orc, tile):
+    """The downsampling convolutions (stride 2, padding 1), odd image sizes included: weight-only outputs within
+    tolerance, int32 accumulators of the 8-bit-activation form bit-exact (borders included), with and without a
+    residual of the output's shape."""
+    mq.tune_force_tile(tile)
+    try:
+        for (B, H, W, Cin, N) in CONV_SHAPES:
+            if tile == 0 and B * H * W * N > 800000:
+                continue
+            Ho, Wo = (H - 1) // 2 + 1, (W - 1) // 2 + 1
+            x = si.activations_f16(73, f"cs/x{B}x{H}x{W}x{Cin}", B * H * W, Cin, outlier_prob=0.01).reshape(B, H, W, Cin)
+            b = si.bias_f16(73, f"cs/b{N}", N)
+            r = si.normal(73, f"cs/r{B}x{Ho}x{Wo}x{N}", (B, Ho, Wo, N)).astype(np.float16)
+            what = f"tile{tile} {B}x{H}x{W}x{Cin}->{N}"
+            pw, oc, os_, oz, tapsum = conv_weight(mq, orc, 73, N, Cin, 4)
+            y = mq.conv3x3_w_only(dev(x), pw, dev(b), stride=2)
+            assert tuple(y.shape) == (B, Ho, Wo, N)
+            assert_close16(host(y).reshape(-1, N), orc.conv3x3_w_only(x, oc, os_, oz, b, stride=2), "stride 2 w4 " + what)
+            y = mq.conv3x3_w_only(dev(x), pw, dev(b), residual=dev(r), stride=2)
+            assert_close16(host(y).reshape(-1, N), orc.conv3x3_w_only(x, oc, os_, oz, b, stride=2, residual=r),
+                           "stride 2 w4 + residual " + what)
+            if tile != 0:
+                for act in (None, (np.float32(0.05), 31)):
+                    d_act = None if act is None else (dev(np.array([act[0]], np.float32)), dev(np.array([act[1]], np.int32)))
+                    y, acc, got = mq.conv3x3_a8(dev(x), pw, tapsum, act=d_act, bias=dev(b), want_acc=True, want_act=True,
+                                                residual=dev(r), stride=2)
+                    ry, racc, ract = orc.conv3x3_a8(x, oc, os_, oz, act=act, bias=b, residual=r, stride=2)
+                    assert host(got[0])[0] == ract[0] and host(got[1])[0] == ract[1]
+                    assert np.array_equal(host(acc), racc), "stride 2 acc " + what
+                    assert_close16(host(y).reshape(-1, N), ry, "stride 2 a8 " + what)
+    finally:
+        mq.tune_force_tile(-1)
+
+
 # ----------------------------------------------------------------------------------------------- residual operand
 
 RES_SHAPES = [(256, 320, 320), (77, 128, 40), (513, 192, 264), (300, 640, 640), (1, 64, 32)]
