@@ -74,10 +74,19 @@ struct WChunk {
     uint32_t w[WORDS];
 };
 
+// (w & mask) | magic in one instruction.  The compiler emits v_and + v_or here, each with its own 32-bit literal: the
+// three-operand form takes no literals on this target, so the mask is handed over in a scalar register and the magic
+// number in a vector register (both loop invariant).  It is a third of the widening work of the 2/3/4-bit codes.
+__device__ __forceinline__ uint32_t and_or(uint32_t w, uint32_t mask, uint32_t magic) {
+    uint32_t r;
+    asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(r) : "v"(w), "s"(mask), "v"(magic));
+    return r;
+}
+
 template <int SHIFT>
 __device__ __forceinline__ half2v field_to_h2(uint32_t w, uint32_t mask, int z) {
     // field value sits at bit SHIFT of each half: magic|field = 1024 + 2^SHIFT q
-    const half2v v = as_h2((w & mask) | 0x64006400u);
+    const half2v v = as_h2(and_or(w, mask, 0x64006400u));
     if constexpr (SHIFT == 0) {
         return v - splat((float)(1024 + z));
     } else {
