@@ -874,3 +874,25 @@ def test_sweep_640_level_shapes_sampled_rows(mq, orc, K, N):
     ry, racc, _ = orc.linear_a8(x, oc, os_, oz, rows=rows)
     assert np.array_equal(host(acc)[rows], racc)
     assert_close16(host(y)[rows], ry, "c5 W4A8")
+
+
+@pytest.mark.parametrize("B,H,W,Cin,N,stride", [(4, 128, 128, 320, 320, 1), (4, 128, 128, 320, 320, 2), (4, 32, 32, 1280, 1280, 1)])
+def test_conv_unet_sizes_sampled_pixels(mq, orc, B, H, W, Cin, N, stride):
+    """The UNet's convolutions at latent 128x128, batch 4, in the launch configuration of the per-shape report (the
+    library's own tile choice): oracle on sampled output pixels, corners and edges among them; W4A16 within tolerance,
+    W4A8 accumulators bit-exact with the dynamic parameters of the whole input tensor."""
+    x = si.activations_f16(90, f"cu/x{H}x{Cin}", B * H * W, Cin, outlier_prob=0.01).reshape(B, H, W, Cin)
+    b = si.bias_f16(90, f"cu/b{N}", N)
+    Ho, Wo = (H - 1) // stride + 1, (W - 1) // stride + 1
+    Mo = B * Ho * Wo
+    pix = np.unique(np.concatenate([[0, Wo - 1, (Ho - 1) * Wo, Ho * Wo - 1, Mo - 1, Mo - Wo, Ho * Wo, Ho * Wo + Wo - 1],
+                                    np.random.default_rng(H + Cin + stride).integers(0, Mo, 40)]))
+    pw, oc, os_, oz, tapsum = conv_weight(mq, orc, 90, N, Cin, 4)
+    xd = dev(x)
+    y = host(mq.conv3x3_w_only(xd, pw, dev(b), stride=stride)).reshape(-1, N)
+    assert_close16(y[pix], orc.conv3x3_w_only(x, oc, os_, oz, b, pix=pix, stride=stride), "conv W4A16 full size")
+    y, acc, got = mq.conv3x3_a8(xd, pw, tapsum, bias=dev(b), want_acc=True, want_act=True, stride=stride)
+    ry, racc, ract = orc.conv3x3_a8(x, oc, os_, oz, bias=b, pix=pix, stride=stride)
+    assert host(got[0])[0] == ract[0] and host(got[1])[0] == ract[1]
+    assert np.array_equal(host(acc)[pix], racc)
+    assert_close16(host(y).reshape(-1, N)[pix], ry, "conv W4A8 full size")
