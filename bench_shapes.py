@@ -52,7 +52,7 @@ def shapes():
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--iters", type=int, default=200)
-    ap.add_argument("--only", default="", help="comma-separated labels (c1,c2,c3,c4,c5,small-M,ff,conv)")
+    ap.add_argument("--only", default="", help="comma-separated labels (c1,c2,c3,c4,c5,small-M,ff,conv,qkv)")
     ap.add_argument("--tile", type=int, default=-1, help="force a tile of the GEMM's tile table (-1: the library's choice)")
     args = ap.parse_args()
 
@@ -153,6 +153,8 @@ def main():
         ff_pairs(mq, torch, min(args.iters, 100), overhead_us)
     if not only or "conv" in only:
         convs(mq, torch, min(args.iters, 100), overhead_us)
+    if not only or "qkv" in only:
+        stacked_qkv(mq, torch, min(args.iters, 120))
 
 
 def ff_pairs(mq, torch, iters, overhead_us):
@@ -259,6 +261,58 @@ def convs(mq, torch, iters, overhead_us):
             print(f"{B:3d}{H:5d}{W:5d}{Cin:6d}{N:6d}{stride:4d} {mode:5s}{us:9.2f}{ops / us / 1e6:10.1f}{alg / us / 1e3:8.0f}{t_hbm:9.2f}"
                   f"{t_mfma:10.2f}{max(t_hbm, t_mfma) / us:7.3f}", flush=True)
             del calls
+            torch.cuda.empty_cache()
+
+
+def stacked_qkv(mq, torch, iters):
+    """The q, k, v projections of a self-attention block (same input, three C x C weights) as three calls and as one
+    call on the stacked weight (binding.stack_weights): W4A16 and W4A8 with dynamic activation parameters."""
+    dev = torch.device("cuda:0")
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(3)
+    print("\n# q, k, v projections of one block: three calls against one call on the stacked weight, cold operands")
+    print(f"{'M':>6s}{'C':>6s} {'mode':5s}{'3 calls us':>11s}{'stacked us':>11s}")
+    for (M, Cc) in ((4096, 1280), (16384, 640)):
+        per_set = 2 * M * Cc + 3 * Cc * Cc // 2 + 3 * 2 * M * Cc
+        nsets = max(2, min(iters // 3, -(-LLC_BYTES // per_set)))
+        for mode in ("w4", "a4"):
+            sets = []
+            ws = torch.empty(mq.qlinear_a8_workspace_bytes(M, Cc), dtype=torch.uint8, device=dev)
+            for _ in range(nsets):
+                parts = []
+                for _i in range(3):
+                    w = (torch.randn(Cc, Cc, generator=gen, device=dev) * 0.02).half()
+                    c, s_, z = mq.quantize_weights(w, 4)
+                    p, cs = mq.pack_weights(c, 4, mq.LAYOUT_KERNEL)
+                    parts.append(mq.PackedWeight(p, s_, z, cs, Cc, Cc, 4, mq.LAYOUT_KERNEL, False))
+                    del w, c
+                x = torch.randn(M, Cc, generator=gen, device=dev).half()
+                y3 = [torch.empty(M, Cc, dtype=torch.float16, device=dev) for _i in range(3)]
+                y1 = torch.empty(M, 3 * Cc, dtype=torch.float16, device=dev)
+                st = mq.stack_weights(parts)
+                if mode == "w4":
+                    three = [mq.plan_qlinear_w_only(x, p, None, y) for p, y in zip(parts, y3)]
+                    one = mq.plan_qlinear_w_only(x, st, None, y1)
+                else:
+                    three = [mq.plan_qlinear_a8(x, p, None, y, ws) for p, y in zip(parts, y3)]
+                    one = mq.plan_qlinear_a8(x, st, None, y1, ws)
+                sets.append((three, one))
+            res = []
+            for which in (0, 1):
+                run = (lambda s: [f() for f in s[0]]) if which == 0 else (lambda s: s[1]())
+                for i in range(min(nsets, 3)):
+                    run(sets[i])
+                torch.cuda.synchronize()
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                n = max(nsets, iters // 3)
+                e0.record()
+                for i in range(n):
+                    run(sets[i % nsets])
+                e1.record()
+                torch.cuda.synchronize()
+                res.append(e0.elapsed_time(e1) * 1e3 / n)
+            print(f"{M:6d}{Cc:6d} {mode:5s}{res[0]:11.2f}{res[1]:11.2f}", flush=True)
+            del sets
             torch.cuda.empty_cache()
 
 

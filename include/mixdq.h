@@ -137,6 +137,12 @@ int mq_unpack_weights(const void* packed, int N, int K, int bits, int layout, ui
  * Hot path
  * ---------------------------------------------------------------------------------------------- */
 
+/* Layers that share their input (the q, k, v projections of a block; K and V of the text context) can run as one
+ * call: in MQ_LAYOUT_KERNEL a weight matrix is stored in tiles of 32 output channels, so the packed form of the
+ * row-stacked matrix [N1 + N2 + ..., K] is the concatenation of the parts' packed buffers (every Ni % 32 == 0, same
+ * K and bits), and scale / zero point / colsum concatenate likewise.  One launch instead of three fills the chip
+ * better, and the activations are quantised once. */
+
 /* Weight-only linear, W{2,3,4,8}A16 (paper App. C item 2: low-bit weights, 16-bit floating-point compute):
  *     Y[m,n] = round16( sum_k X[m,k] * scale[n] * (code[n,k] - zp[n]) + bias[n] ),  fp32 accumulation.
  *   x      [M,K] row stride ldx, 16-byte aligned, ldx % 8 == 0.     y [M,N] row stride ldy, 16-byte aligned, ldy % 8 == 0.

@@ -151,6 +151,20 @@ def keep_weights_16bit(w: torch.Tensor) -> PackedWeight:
     return PackedWeight(packed, None, None, None, w.shape[0], w.shape[1], 16, LAYOUT_KERNEL, False)
 
 
+def stack_weights(parts) -> PackedWeight:
+    """Layers that share their input (a block's q, k, v projections; the K and V projections of the text context) as
+    one layer: in the kernel layout the packed form of the row-stacked matrix is the concatenation of the parts'
+    packed buffers (tiles are 32 output channels tall, so every part's N must be a multiple of 32), and the
+    per-channel parameters concatenate likewise.  One call on the stacked weight writes [M, N1 + N2 + ...]."""
+    first = parts[0]
+    for p in parts:
+        assert p.N % 32 == 0 and (p.K, p.bits, p.layout, p.signed) == (first.K, first.bits, LAYOUT_KERNEL, first.signed)
+    cat = lambda ts: None if ts[0] is None else torch.cat(ts)
+    return PackedWeight(torch.cat([p.packed for p in parts]), cat([p.scale for p in parts]), cat([p.zp for p in parts]),
+                        cat([p.colsum for p in parts]), sum(p.N for p in parts), first.K, first.bits, LAYOUT_KERNEL,
+                        first.signed)
+
+
 def quantize_weights(w: torch.Tensor, bits: int, symmetric: bool = False):
     """W [N,K] fp16/bf16 -> (codes uint8 [N,K], scale float32 [N], zp int32 [N])."""
     assert w.is_cuda and w.dim() == 2 and w.is_contiguous()

@@ -896,3 +896,28 @@ def test_conv_unet_sizes_sampled_pixels(mq, orc, B, H, W, Cin, N, stride):
     assert host(got[0])[0] == ract[0] and host(got[1])[0] == ract[1]
     assert np.array_equal(host(acc)[pix], racc)
     assert_close16(host(y).reshape(-1, N)[pix], ry, "conv W4A8 full size")
+
+
+def test_stacked_layers_that_share_their_input(mq, orc):
+    """q, k, v as one call: the concatenated packed buffers are the packed form of the stacked matrix (bit for bit),
+    and one launch writes the three outputs side by side, equal to the three separate calls (int32 accumulators and,
+    with the same dynamic activation parameters, every output bit)."""
+    M, K, N = 300, 640, 320
+    x = si.activations_f16(95, "st/x", M, K, outlier_prob=0.01)
+    ws = [si.weights_f16(95, f"st/w{i}", N, K) for i in range(3)]
+    for bits, sym in ((4, False), (8, True), (2, False), (3, False)):
+        parts = [make_weight(mq, orc, w, bits, sym)[0] for w in ws]
+        stacked = mq.stack_weights(parts)
+        whole = make_weight(mq, orc, np.concatenate(ws, 0), bits, sym)[0]
+        assert torch.equal(stacked.packed, whole.packed) and torch.equal(stacked.scale, whole.scale)
+        assert torch.equal(stacked.zp, whole.zp) and torch.equal(stacked.colsum, whole.colsum)
+        y = mq.qlinear_w_only(dev(x), stacked)
+        for i, p in enumerate(parts):   # (the tile choice, and with it the order of the fp32 sums, may differ)
+            yi = mq.qlinear_w_only(dev(x), p).float()
+            assert (y[:, i * N:(i + 1) * N].float() - yi).abs().max() <= 2e-3 * yi.abs().max()
+        if bits in (4, 8):
+            fn = mq.qlinear_w4a8 if bits == 4 else mq.qlinear_w8a8
+            y, acc, _ = fn(dev(x), stacked, want_acc=True)
+            for i, p in enumerate(parts):
+                yi, acci, _ = fn(dev(x), p, want_acc=True)
+                assert torch.equal(acc[:, i * N:(i + 1) * N], acci) and torch.equal(y[:, i * N:(i + 1) * N], yi)
