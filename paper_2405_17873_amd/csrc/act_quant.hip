@@ -14,6 +14,7 @@
 namespace mq {
 
 typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+typedef uint32_t uint2v __attribute__((ext_vector_type(2)));
 
 static constexpr int kPartialSlots = 512;  // upper bound of pass-1 workgroups
 int act_quant_partial_slots() { return kPartialSlots; }
@@ -166,7 +167,11 @@ __global__ __launch_bounds__(256) void act_quantize_kernel(const _Float16* __res
                     w1 |= ((uint32_t)(q[k8_perm(4 + b)] & 255)) << (8 * b);
                 }
             }
-            if (valid) ((uint2*)(a8 + (long)(r0 + lr[u]) * Kp))[pp[u]] = make_uint2(w0, w1);
+            // (streaming store: read next by another kernel, nothing gained by keeping it in this XCD's L2)
+            if (valid) {
+                const uint2v out = {w0, w1};
+                __builtin_nontemporal_store(out, (uint2v*)(a8 + (long)(r0 + lr[u]) * Kp) + pp[u]);
+            }
             sum += __shfl_xor(sum, 1, 64);
             sum += __shfl_xor(sum, 2, 64);
             sum += __shfl_xor(sum, 4, 64);
