@@ -37,7 +37,7 @@ def shapes():
     for (K, N) in ((640, 640), (640, 5120), (2560, 640)):
         S.append(("c2", 4096, K, N, ("w16", "w8", "w4", "w3", "w2")))
     for (K, N) in ((1280, 1280), (1280, 10240), (5120, 1280)):
-        S.append(("c3", 4096, K, N, ("a4", "a8sym", "s4", "w4", "w16")))
+        S.append(("c3", 4096, K, N, ("a4", "a2", "a8sym", "s4", "w4", "w16")))
     for N in (640, 1280):
         S.append(("c4", 8 * 77, 2048, N, ("bos8", "bos4")))
     for (K, N) in ((640, 640), (640, 5120), (2560, 640)):

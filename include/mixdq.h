@@ -192,6 +192,15 @@ int mq_qlinear_w4a8(const void* x, int M, int K, int ldx, const void* packed, in
                     const void* residual, int ldr, float* act_scale_out, int32_t* act_zp_out, void* ws,
                     size_t ws_bytes, void* stream);
 
+/* W2A8 linear: as above with asymmetric unsigned 2-bit weight codes.  The paper's W4A8 configurations are mixed:
+ * their weight bit-widths come from {2,4,8} (Sec. 3.3) under 8-bit activations, so 2-bit layers meet the integer
+ * GEMM too; the codes are widened to int8 in registers like the 4-bit ones. */
+int mq_qlinear_w2a8(const void* x, int M, int K, int ldx, const void* packed, int N, int layout,
+                    const float* w_scale, const int32_t* w_zp, const int32_t* w_colsum, const float* act_scale,
+                    const int32_t* act_zp, const void* bias, void* y, int ldy, int32_t* acc_debug,
+                    const void* residual, int ldr, float* act_scale_out, int32_t* act_zp_out, void* ws,
+                    size_t ws_bytes, void* stream);
+
 /* ------------------------------------------------------------------------------------------------
  * Feed-forward pair with the activation kept in 8 bits between its two linears (an extension: paper Sec. 4.3
  * names the separate FP16->INT8 conversion layers as the overhead of the W8A8 path; this removes the one between
@@ -283,7 +292,7 @@ size_t mq_bos_aware_kv_proj_workspace_bytes(int B, int T, int K);
 
 /* BOS-aware cross-attention K/V projection (paper Sec. 3.1).  ctx is the text embedding [B,T,K] fp16,
  * contiguous; token 0 of every prompt is the outlier BOS row.
- *   - tokens 1..T-1: 8-bit-activation linear as above (w_bits 8 or 4); dynamic activation parameters are the
+ *   - tokens 1..T-1: 8-bit-activation linear as above (w_bits 8, 4 or 2); dynamic activation parameters are the
  *     min/max over those tokens only.
  *   - token 0: exactly one of
  *         w_f16   [N,K] unquantised fp16 weights -> Y[b,0,:] = fp16(ctx[b,0,:] . w_f16^T + bias), fp32 accumulate

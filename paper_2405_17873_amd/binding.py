@@ -24,7 +24,7 @@ _ERRORS = {
 EXPORTS = ("mq_version", "mq_last_hip_error", "mq_tune_force_tile", "mq_tune_force_splits", "mq_prof_enable", "mq_prof_num_slots", "mq_prof_read",
            "mq_prof_reset", "mq_prof_phase_buffer", "mq_prof_filter", "mq_prof_bracket_overhead_us", "mq_prof_copy", "mq_quantize_weights", "mq_packed_bytes", "mq_pack_weights",
            "mq_unpack_weights", "mq_qlinear_w_only", "mq_qlinear_a8_workspace_bytes", "mq_qlinear_w8a8",
-           "mq_qlinear_w4a8", "mq_a8_row_bytes", "mq_qlinear_a8_geglu", "mq_qlinear_w_only_geglu", "mq_qlinear_a8_codes", "mq_conv3x3_w_only",
+           "mq_qlinear_w4a8", "mq_qlinear_w2a8", "mq_a8_row_bytes", "mq_qlinear_a8_geglu", "mq_qlinear_w_only_geglu", "mq_qlinear_a8_codes", "mq_conv3x3_w_only",
            "mq_conv_tap_sums", "mq_conv3x3_a8_workspace_bytes", "mq_conv3x3_a8",
            "mq_bos_aware_kv_proj_workspace_bytes", "mq_bos_aware_kv_proj", "mq_alloc_solve", "mq_alloc_split_budget",
            "mq_alloc_search")
@@ -255,7 +255,8 @@ def _qlinear_a8(fn_name, x, w: PackedWeight, act, bias, out, ws, want_acc, want_
                                _ptr(acc), rp, ldr, _ptr(s_out), _ptr(z_out), _ptr(ws), C.c_size_t(ws.numel()),
                                _stream())
     else:
-        rc = L.mq_qlinear_w4a8(_ptr(x), M, K, x.stride(0), _ptr(w.packed), w.N, w.layout, _ptr(w.scale), _ptr(w.zp),
+        fn = L.mq_qlinear_w4a8 if fn_name == "mq_qlinear_w4a8" else L.mq_qlinear_w2a8
+        rc = fn(_ptr(x), M, K, x.stride(0), _ptr(w.packed), w.N, w.layout, _ptr(w.scale), _ptr(w.zp),
                                _ptr(w.colsum), _ptr(a_s), _ptr(a_z), _ptr(bias), _ptr(y), y.stride(0), _ptr(acc),
                                rp, ldr, _ptr(s_out), _ptr(z_out), _ptr(ws), C.c_size_t(ws.numel()), _stream())
     _check(rc, fn_name)
@@ -274,6 +275,12 @@ def qlinear_w4a8(x, w: PackedWeight, act=None, bias=None, out=None, ws=None, wan
                  residual=None):
     assert w.bits == 4 and not w.signed
     return _qlinear_a8("mq_qlinear_w4a8", x, w, act, bias, out, ws, want_acc, want_act, residual)
+
+
+def qlinear_w2a8(x, w: PackedWeight, act=None, bias=None, out=None, ws=None, want_acc=False, want_act=False,
+                 residual=None):
+    assert w.bits == 2 and not w.signed
+    return _qlinear_a8("mq_qlinear_w2a8", x, w, act, bias, out, ws, want_acc, want_act, residual)
 
 
 def a8_row_bytes(K: int) -> int:
@@ -470,7 +477,7 @@ def plan_qlinear_a8(x, w: PackedWeight, bias, out, ws, act=None, residual=None):
                 _ptr(w.colsum), _ptr(a_s), _ptr(a_z), _ptr(bias), _ptr(out), out.stride(0), null, rp, ldr, null, null,
                 _ptr(ws), C.c_size_t(ws.numel()), _stream())
     else:
-        fn, what = load().mq_qlinear_w4a8, "mq_qlinear_w4a8"
+        fn, what = (load().mq_qlinear_w4a8, "mq_qlinear_w4a8") if w.bits == 4 else (load().mq_qlinear_w2a8, "mq_qlinear_w2a8")
         args = (_ptr(x), M, K, x.stride(0), _ptr(w.packed), w.N, w.layout, _ptr(w.scale), _ptr(w.zp), _ptr(w.colsum),
                 _ptr(a_s), _ptr(a_z), _ptr(bias), _ptr(out), out.stride(0), null, rp, ldr, null, null, _ptr(ws),
                 C.c_size_t(ws.numel()), _stream())

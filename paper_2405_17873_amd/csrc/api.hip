@@ -313,6 +313,15 @@ int mq_qlinear_w4a8(const void* x, int M, int K, int ldx, const void* packed, in
                       residual, ldr, (hipStream_t)stream);
 }
 
+int mq_qlinear_w2a8(const void* x, int M, int K, int ldx, const void* packed, int N, int layout, const float* w_scale,
+                    const int32_t* w_zp, const int32_t* w_colsum, const float* act_scale, const int32_t* act_zp,
+                    const void* bias, void* y, int ldy, int32_t* acc_debug, const void* residual, int ldr,
+                    float* act_scale_out, int32_t* act_zp_out, void* ws, size_t ws_bytes, void* stream) {
+    return qlinear_a8(x, M, K, ldx, RowMap{0, 0, 0}, packed, N, layout, 2, 0, w_scale, w_zp, w_colsum, act_scale,
+                      act_zp, bias, y, ldy, RowMap{0, 0, 0}, acc_debug, act_scale_out, act_zp_out, ws, ws_bytes,
+                      residual, ldr, (hipStream_t)stream);
+}
+
 size_t mq_bos_aware_kv_proj_workspace_bytes(int B, int T, int K) {
     if (B <= 0 || T <= 0 || K <= 0) return 0;
     return A8Workspace::bytes((long)B * T, K);
@@ -324,8 +333,8 @@ int mq_bos_aware_kv_proj(const void* ctx, int B, int T, int K, const void* packe
                          const void* bias, void* y, int naive_all_rows, float* act_scale_out, int32_t* act_zp_out,
                          void* ws, size_t ws_bytes, void* stream) {
     if (B <= 0 || T <= 0) return MQ_ERR_BAD_SHAPE;
-    if (w_bits != 4 && w_bits != 8) return MQ_ERR_UNSUPPORTED_BITS;
-    if (w_bits == 4 && w_signed) return MQ_ERR_BAD_ARG;
+    if (w_bits != 2 && w_bits != 4 && w_bits != 8) return MQ_ERR_UNSUPPORTED_BITS;
+    if (w_bits != 8 && w_signed) return MQ_ERR_BAD_ARG;
     hipStream_t st = (hipStream_t)stream;
     if (naive_all_rows)
         return qlinear_a8(ctx, B * T, K, K, RowMap{0, 0, 0}, packed, N, layout, w_bits, w_signed ? 1 : 0, w_scale, w_zp,

@@ -272,6 +272,18 @@ __device__ __forceinline__ int4v widen_step(const WChunk<WBITS>& c, int s /*0..1
     if constexpr (WBITS == 8) {
         return int4v{(int)(c.w[4 * s] ^ xflip), (int)(c.w[4 * s + 1] ^ xflip), (int)(c.w[4 * s + 2] ^ xflip),
                      (int)(c.w[4 * s + 3] ^ xflip)};
+    } else if constexpr (WBITS == 2) {
+        // Word s holds codes 16s..16s+15, pair (c[2p], c[2p+1]) in bits [2p, 2p+2) and [16+2p, 16+2p+2):
+        // (w >> 2t) & 0x03030303 = bytes c[2t], c[2t+8], c[2t+1], c[2t+9].  The activations of a group of 8 sit in
+        // the order 0,4,1,5,2,6,3,7: two byte permutes per pair of extracts put the codes in that order.
+        const uint32_t w = c.w[s];
+        const uint32_t e0 = w & 0x03030303u, e1 = (w >> 2) & 0x03030303u, e2 = (w >> 4) & 0x03030303u,
+                       e3 = (w >> 6) & 0x03030303u;
+        // v_perm_b32: selector bytes 0..3 pick bytes of the second source, 4..7 of the first
+        return int4v{(int)__builtin_amdgcn_perm(e2, e0, 0x06020400u),   // c0,c4,c1,c5
+                     (int)__builtin_amdgcn_perm(e3, e1, 0x06020400u),   // c2,c6,c3,c7
+                     (int)__builtin_amdgcn_perm(e2, e0, 0x07030501u),   // c8,c12,c9,c13
+                     (int)__builtin_amdgcn_perm(e3, e1, 0x07030501u)};  // c10,c14,c11,c15
     } else {
         const uint32_t w0 = c.w[2 * s], w1 = c.w[2 * s + 1];
         return int4v{(int)(w0 & 0x0F0F0F0Fu), (int)((w0 >> 4) & 0x0F0F0F0Fu), (int)(w1 & 0x0F0F0F0Fu),
@@ -1368,9 +1380,9 @@ int launch_gemm_a8(const int8_t* a8, const int32_t* rowsum, const ActParams* par
     g.res = (const uint16_t*)res; g.ldr = ldr;
     g.rowsum = rowsum; g.params = params; g.w_colsum = w_colsum;
     g.out_map = out_map; g.acc_debug = acc_debug;
-    if (w_bits == 4) {
+    if (w_bits == 4 || w_bits == 2) {
         g.w_off = 0;
-        return dispatch_gemm<true, 4>(g, st);
+        return w_bits == 4 ? dispatch_gemm<true, 4>(g, st) : dispatch_gemm<true, 2>(g, st);
     }
     if (w_bits == 8) {
         // Unsigned 8-bit codes do not fit a signed MFMA operand: the kernel flips their top bit in registers,

@@ -98,7 +98,7 @@ def test_error_codes_without_a_gpu(lib):
                        o.get("bo", null), null, null, null, p, 0, null, null, p, C.c_size_t(1 << 20), st]
     assert lib.mq_bos_aware_kv_proj(*bos()) == -1            # neither BOS source
     assert lib.mq_bos_aware_kv_proj(*bos(wf=p, bo=p)) == -1  # both
-    assert lib.mq_bos_aware_kv_proj(*bos(wb=2, wf=p)) == -3
+    assert lib.mq_bos_aware_kv_proj(*bos(wb=3, wf=p)) == -3
     assert lib.mq_bos_aware_kv_proj(*bos(B=0, wf=p)) == -2
 
 

@@ -312,12 +312,12 @@ def test_split_reduction_is_deterministic_and_reuses_its_scratch(mq, orc):
 A8_SHAPES = [(256, 320, 320), (1, 64, 32), (77, 128, 40), (608, 2048, 640), (300, 1280, 264), (130, 192, 64)]
 
 
-@pytest.mark.parametrize("mode", ("w8s", "w8a", "w4"))
+@pytest.mark.parametrize("mode", ("w8s", "w8a", "w4", "w2"))
 @pytest.mark.parametrize("tile", (-1, 0, 1, 2, 3, 4, 5))
 def test_a8_small_shapes(mq, orc, mode, tile):
     mq.tune_force_tile(tile)
-    bits, sym = {"w8s": (8, True), "w8a": (8, False), "w4": (4, False)}[mode]
-    fn = mq.qlinear_w8a8 if bits == 8 else mq.qlinear_w4a8
+    bits, sym = {"w8s": (8, True), "w8a": (8, False), "w4": (4, False), "w2": (2, False)}[mode]
+    fn = {8: mq.qlinear_w8a8, 4: mq.qlinear_w4a8, 2: mq.qlinear_w2a8}[bits]
     for (M, K, N) in A8_SHAPES:
         x = si.activations_f16(13, f"a8/x{M}x{K}", M, K, outlier_prob=0.01)
         w = si.weights_f16(13, f"a8/w{N}x{K}", N, K)
@@ -359,7 +359,7 @@ def test_a8_transformer_block_shapes_sampled_rows(mq, orc, K, N):
     rng = np.random.default_rng(K + N)
     rows = np.unique(np.concatenate([[0, M - 1, int(np.argmax(x.max(1))), int(np.argmin(x.min(1)))],
                                      rng.integers(0, M, 28)]))
-    for bits, sym, fn in ((4, False, mq.qlinear_w4a8), (8, True, mq.qlinear_w8a8)):
+    for bits, sym, fn in ((4, False, mq.qlinear_w4a8), (8, True, mq.qlinear_w8a8), (2, False, mq.qlinear_w2a8)):
         pw, oc, os_, oz = make_weight(mq, orc, w, bits, sym)
         y, acc, (s_out, z_out) = fn(dev(x), pw, bias=dev(b), want_acc=True, want_act=True)
         ry, racc, (rs, rz) = orc.linear_a8(x, oc, os_, oz, w_signed=sym, bias=b, rows=rows)
@@ -818,7 +818,7 @@ def test_conv_residual_and_split_shortcut(mq, orc, tile):
 # ----------------------------------------------------------------------------------------------- BOS-aware K/V
 
 @pytest.mark.parametrize("N", (640, 1280))
-@pytest.mark.parametrize("bits,sym", [(8, True), (4, False)])
+@pytest.mark.parametrize("bits,sym", [(8, True), (4, False), (2, False)])
 def test_bos_aware_kv_projection(mq, orc, N, bits, sym):
     B, T, K = 8, 77, 2048
     ctx = si.bos_context_f16(0, "c4/ctx", B, T, K)
