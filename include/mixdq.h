@@ -221,7 +221,7 @@ size_t mq_a8_row_bytes(int K);
  * gelu(g) = 0.5 g (1 + erf(g / sqrt 2)); every step is one IEEE fp32 operation: erf(x) = 1 - exp(-x P(x)) with a
  * fitted degree-6 polynomial P (|error| < 2e-7) over an exponential by range reduction and a degree-6 polynomial,
  * so that the codes are reproducible bit for bit.
- *   x [M,K] fp16 (as in mq_qlinear_w8a8, dynamic or static activation parameters), packed: w_bits = 4 or 8,
+ *   x [M,K] fp16 (as in mq_qlinear_w8a8, dynamic or static activation parameters), packed: w_bits = 2, 4 or 8,
  *   MQ_LAYOUT_KERNEL, 2H rows; w_scale, w_zp, w_colsum, bias [2H].  H % 32 == 0.
  *   out_scale, out_zp: device pointers to the static parameters (s_o, z_o) of the gated product.
  *   a8_out  [M, mq_a8_row_bytes(H)] int8 out, A8 layout, 16-byte aligned.
@@ -240,7 +240,7 @@ int mq_qlinear_w_only_geglu(const void* x, int M, int K, int ldx, const void* pa
                             const float* w_scale, const int32_t* w_zp, const void* bias, void* h, int ldh,
                             void* stream);
 
-/* W8A8 / W4A8 linear on activations that arrive as codes in the A8 layout (row stride lda bytes) together with
+/* W8A8 / W4A8 / W2A8 linear on activations that arrive as codes in the A8 layout (row stride lda bytes) together with
  * their parameters (device pointers act_scale, act_zp): ACC and Y as in mq_qlinear_w8a8.  The row sums of the
  * codes, which the zero-point correction needs, are taken inside the GEMM; no workspace.  residual: nullable fp16
  * [M,N], row stride ldr, added before the rounding (the block's skip connection after a feed-forward). */
@@ -276,7 +276,7 @@ int mq_conv_tap_sums(const uint8_t* codes, int N, int Cin, int bits, int codes_s
 
 size_t mq_conv3x3_a8_workspace_bytes(int B, int H, int W, int Cin);
 
-/* W8A8 / W4A8 convolution: activations quantised per tensor (dynamic min/max over x, or the given static
+/* W8A8 / W4A8 / W2A8 convolution: activations quantised per tensor (dynamic min/max over x, or the given static
  * parameters) as in mq_qlinear_w8a8; a padded position holds the value 0, whose code is the zero point:
  *     ACC[m,n] = sum over in-image (r,s), c of (qx - z_x)(qw - z_w[n]),
  *     y = fp16(ACC * s_x * s_w[n] + bias[n] + residual[m,n]).

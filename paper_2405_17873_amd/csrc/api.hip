@@ -171,7 +171,8 @@ int mq_qlinear_a8_geglu(const void* x, int M, int K, int ldx, const void* packed
                         const float* act_scale, const int32_t* act_zp, const void* bias, const float* out_scale,
                         const int32_t* out_zp, int8_t* a8_out, void* h16_out, int ldh, float* act_scale_out,
                         int32_t* act_zp_out, void* ws, size_t ws_bytes, void* stream) {
-    if (w_bits != 4 && w_bits != 8) return MQ_ERR_UNSUPPORTED_BITS;
+    if (w_bits != 2 && w_bits != 4 && w_bits != 8) return MQ_ERR_UNSUPPORTED_BITS;
+    if (w_bits != 8 && w_signed) return MQ_ERR_BAD_ARG;
     if (H <= 0 || H % 32 != 0 || H > (1 << 29)) return MQ_ERR_BAD_SHAPE;
     // x, weights of 2H rows; the fp16 product (if asked for) stands in for y in the common checks
     int rc = check_linear_common(x, M, K, ldx, packed, 2 * H, layout, w_scale, w_zp, bias, a8_out, 2 * H);
@@ -207,7 +208,8 @@ int mq_qlinear_a8_codes(const int8_t* a8, int M, int K, int lda, const float* ac
                         const void* packed, int N, int w_bits, int layout, int w_signed, const float* w_scale,
                         const int32_t* w_zp, const int32_t* w_colsum, const void* bias, void* y, int ldy,
                         int32_t* acc_debug, const void* residual, int ldr, void* stream) {
-    if (w_bits != 4 && w_bits != 8) return MQ_ERR_UNSUPPORTED_BITS;
+    if (w_bits != 2 && w_bits != 4 && w_bits != 8) return MQ_ERR_UNSUPPORTED_BITS;
+    if (w_bits != 8 && w_signed) return MQ_ERR_BAD_ARG;
     if (!a8 || !act_scale || !act_zp || !packed || !w_scale || !w_zp || !w_colsum || !y) return MQ_ERR_BAD_ARG;
     if (M <= 0 || K <= 0 || N <= 0 || ldy < N) return MQ_ERR_BAD_SHAPE;
     if (layout != MQ_LAYOUT_KERNEL) return MQ_ERR_UNSUPPORTED_LAYOUT;
@@ -268,7 +270,8 @@ int mq_conv3x3_a8(const void* x, int B, int H, int W, int Cin, int stride, const
                   const int32_t* w_tapsum, const float* act_scale, const int32_t* act_zp, const void* bias, void* y,
                   int32_t* acc_debug, const void* residual, float* act_scale_out, int32_t* act_zp_out, void* ws,
                   size_t ws_bytes, void* stream) {
-    if (w_bits != 4 && w_bits != 8) return MQ_ERR_UNSUPPORTED_BITS;
+    if (w_bits != 2 && w_bits != 4 && w_bits != 8) return MQ_ERR_UNSUPPORTED_BITS;
+    if (w_bits != 8 && w_signed) return MQ_ERR_BAD_ARG;
     int rc = check_conv_common(x, B, H, W, Cin, stride, packed, N, layout, w_scale, w_zp, bias, y);
     if (rc) return rc;
     if ((rc = check_residual(residual, N, N))) return rc;

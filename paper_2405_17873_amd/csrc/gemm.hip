@@ -1420,6 +1420,11 @@ int launch_gemm_a8_geglu(const int8_t* a8, const int32_t* rowsum, const ActParam
         if (big) return run_gemm<true, 4, 1, 4, 4, 2, 1, 80 * 1024, 4, false, 1>(g, 0, st);
         return run_gemm<true, 4, 2, 2, 2, 2, 1, 80 * 1024, 4, false, 1>(g, 1, st);
     }
+    if (w_bits == 2) {
+        g.w_off = 0;
+        if (big) return run_gemm<true, 2, 1, 4, 4, 2, 1, 80 * 1024, 4, false, 1>(g, 0, st);
+        return run_gemm<true, 2, 2, 2, 2, 2, 1, 80 * 1024, 4, false, 1>(g, 1, st);
+    }
     if (w_bits == 8) {
         g.w_off = w_signed ? 0 : 128;
         if (g_force_tile == 0) return run_gemm<true, 8, 1, 4, 4, 2, 1, 160 * 1024, 4, false, 1>(g, 0, st);
@@ -1493,6 +1498,16 @@ int launch_gemm_a8_codes(const int8_t* a8, long lda, const float* act_scale, con
                 if (half_height) return run_gemm<true, 4, 1, 4, 2, 1, 1, 40 * 1024, 3, false, 2>(g, 5, st);
                 return run_gemm<true, 4, 2, 2, 2, 2, 1, 80 * 1024, 4, false, 2>(g, 1, st);
             default: return run_gemm<true, 4, 2, 2, 1, 1, 1, 80 * 1024, 8, false, 2>(g, 2, st);
+        }
+    }
+    if (w_bits == 2) {
+        g.w_off = 0;
+        switch (t) {
+            case 0:
+            case 1:
+                if (half_height) return run_gemm<true, 2, 1, 4, 2, 1, 1, 40 * 1024, 3, false, 2>(g, 5, st);
+                return run_gemm<true, 2, 2, 2, 2, 2, 1, 80 * 1024, 4, false, 2>(g, 1, st);
+            default: return run_gemm<true, 2, 2, 2, 1, 1, 1, 80 * 1024, 8, false, 2>(g, 2, st);
         }
     }
     if (w_bits == 8) {
@@ -1587,6 +1602,12 @@ int launch_conv3x3_a8(const int8_t* a8, const ActParams* params, int B, int H, i
         if (t <= 1 && g_force_tile != 1) return run_gemm<true, 4, 1, 4, 2, 1, 1, 40 * 1024, 3, false, 4>(g, 5, st);
         if (t <= 1) return run_gemm<true, 4, 2, 2, 2, 2, 1, 80 * 1024, 4, false, 4>(g, 1, st);
         return run_gemm<true, 4, 2, 2, 1, 1, 1, 80 * 1024, 8, false, 4>(g, 2, st);
+    }
+    if (w_bits == 2) {
+        g.w_off = 0;
+        if (t <= 1 && g_force_tile != 1) return run_gemm<true, 2, 1, 4, 2, 1, 1, 40 * 1024, 3, false, 4>(g, 5, st);
+        if (t <= 1) return run_gemm<true, 2, 2, 2, 2, 2, 1, 80 * 1024, 4, false, 4>(g, 1, st);
+        return run_gemm<true, 2, 2, 2, 1, 1, 1, 80 * 1024, 8, false, 4>(g, 2, st);
     }
     if (w_bits == 8) {
         g.w_off = w_signed ? 0 : 128;

@@ -449,7 +449,7 @@ def a8_unlayout(a8, K):
     return (lin[:, :K].astype(np.int16) + 128).astype(np.uint8), lin[:, K:]
 
 
-@pytest.mark.parametrize("bits,sym", [(4, False), (8, True), (8, False)])
+@pytest.mark.parametrize("bits,sym", [(4, False), (8, True), (8, False), (2, False)])
 @pytest.mark.parametrize("tile", (-1, 0, 1))
 def test_geglu_projection_emits_the_oracles_codes(mq, orc, bits, sym, tile):
     """value * gelu(gate) -> 8-bit codes: bit-exact (exact int32 accumulators, then the same fp32 operations)."""
@@ -476,7 +476,7 @@ def test_geglu_projection_emits_the_oracles_codes(mq, orc, bits, sym, tile):
         mq.tune_force_tile(-1)
 
 
-@pytest.mark.parametrize("bits,sym", [(4, False), (8, True), (8, False)])
+@pytest.mark.parametrize("bits,sym", [(4, False), (8, True), (8, False), (2, False)])
 @pytest.mark.parametrize("tile", (-1, 1, 2, 5))
 def test_a8_linear_on_codes(mq, orc, bits, sym, tile):
     mq.tune_force_tile(tile)
@@ -577,7 +577,7 @@ def test_conv_w_only(mq, orc, bits, tile):
         mq.tune_force_tile(-1)
 
 
-@pytest.mark.parametrize("bits,sym", [(4, False), (8, True), (8, False)])
+@pytest.mark.parametrize("bits,sym", [(4, False), (8, True), (8, False), (2, False)])
 @pytest.mark.parametrize("tile", (-1, 1, 2, 5))
 def test_conv_a8(mq, orc, bits, sym, tile):
     """Integer accumulators bit-exact, also on the border pixels (taps outside the image) and with a zero point far
