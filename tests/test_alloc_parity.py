@@ -13,7 +13,12 @@ from oracle import alloc as orc
 
 @pytest.fixture(scope="module")
 def mq():
+    import os
+
     import paper_2405_17873_amd as m
+    if not os.path.exists(m.lib_path()):
+        from paper_2405_17873_amd import build
+        build.build()
     m.load()
     return m
 
