@@ -921,3 +921,46 @@ def test_stacked_layers_that_share_their_input(mq, orc):
             for i, p in enumerate(parts):
                 yi, acci, _ = fn(dev(x), p, want_acc=True)
                 assert torch.equal(acc[:, i * N:(i + 1) * N], acci) and torch.equal(y[:, i * N:(i + 1) * N], yi)
+
+
+def test_side_streams_and_two_streams_at_once(mq, orc):
+    """The library launches on the stream it is handed and keeps no state that two streams could trample: the results
+    on a side stream, and on two streams that run different layers at the same time (split reduction with its shared
+    scratch ring, dynamic 8-bit activations with their workspaces), equal those of the default stream bit for bit."""
+    xa = dev(si.activations_f16(96, "ss/xa", 64, 5120))
+    wa, *_ = make_weight(mq, orc, si.weights_f16(96, "ss/wa", 1280, 5120), 4)
+    xb = dev(si.activations_f16(96, "ss/xb", 2048, 1280, outlier_prob=0.01))
+    wb, *_ = make_weight(mq, orc, si.weights_f16(96, "ss/wb", 640, 1280), 4)
+    xc = dev(si.activations_f16(96, "ss/xc", 308, 2048))
+    wc, *_ = make_weight(mq, orc, si.weights_f16(96, "ss/wc", 640, 2048), 8, True)
+
+    def layer_a():
+        return mq.qlinear_w_only(xa, wa)
+
+    def layer_b():
+        return mq.qlinear_w4a8(xb, wb)[0]
+
+    def layer_c():
+        return mq.qlinear_w8a8(xc, wc)[0]
+
+    ref = [f().clone() for f in (layer_a, layer_b, layer_c)]
+    torch.cuda.synchronize()
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    for f, r in zip((layer_a, layer_b, layer_c), ref):
+        with torch.cuda.stream(s1):
+            y = f()
+        s1.synchronize()
+        assert torch.equal(y, r), "side stream"
+    for it in range(8):
+        with torch.cuda.stream(s1):
+            ya = [layer_a() for _ in range(3)]
+            yc = layer_c()
+        with torch.cuda.stream(s2):
+            yb = [layer_b() for _ in range(3)]
+            ya2 = layer_a()
+        torch.cuda.synchronize()
+        for y in ya + [ya2]:
+            assert torch.equal(y, ref[0]), f"two streams, split reduction, round {it}"
+        for y in yb:
+            assert torch.equal(y, ref[1]), f"two streams, W4A8, round {it}"
+        assert torch.equal(yc, ref[2]), f"two streams, W8A8, round {it}"
