@@ -54,6 +54,7 @@ def main():
     ap.add_argument("--iters", type=int, default=200)
     ap.add_argument("--only", default="", help="comma-separated labels (c1,c2,c3,c4,c5,small-M,ff,conv,qkv)")
     ap.add_argument("--tile", type=int, default=-1, help="force a tile of the GEMM's tile table (-1: the library's choice)")
+    ap.add_argument("--band", type=int, default=0, help="force the band height of the workgroup -> tile map (0: the library's choice)")
     args = ap.parse_args()
 
     import torch
@@ -61,6 +62,7 @@ def main():
     import paper_2405_17873_amd as mq
     mq.load()
     mq.tune_force_tile(args.tile)
+    mq.tune_force_band(args.band)
     dev = torch.device("cuda:0")
     gen = torch.Generator(device=dev)
     gen.manual_seed(0)

@@ -64,6 +64,12 @@ void mq_tune_force_tile(int tile);
  * Process-wide, not thread safe. */
 void mq_tune_force_splits(int parts);
 
+/* Tuning and test hook: height, in row blocks, of the bands in which a GEMM's workgroups walk the output tiles
+ * (0: automatic; 1: row block by row block; n: n row blocks side by side, column by column).  It decides which
+ * operand tiles the workgroups that run at the same time share in a cache, never a result.  Process-wide, not thread
+ * safe. */
+void mq_tune_force_band(int rows);
+
 /* Per-kernel timing for benchmarks.  While enabled, every kernel launch of the library is bracketed by two HIP
  * events recorded on the stream it is launched on.  mq_prof_read waits for the pending events of one slot and
  * returns, accumulated since the last reset: the kernel's name (host buffer), number of launches, elapsed

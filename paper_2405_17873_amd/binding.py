@@ -21,7 +21,7 @@ _ERRORS = {
     -9: "MQ_ERR_TOO_LARGE",
 }
 
-EXPORTS = ("mq_version", "mq_last_hip_error", "mq_tune_force_tile", "mq_tune_force_splits", "mq_prof_enable", "mq_prof_num_slots", "mq_prof_read",
+EXPORTS = ("mq_version", "mq_last_hip_error", "mq_tune_force_tile", "mq_tune_force_splits", "mq_tune_force_band", "mq_prof_enable", "mq_prof_num_slots", "mq_prof_read",
            "mq_prof_reset", "mq_prof_phase_buffer", "mq_prof_filter", "mq_prof_bracket_overhead_us", "mq_prof_copy", "mq_quantize_weights", "mq_packed_bytes", "mq_pack_weights",
            "mq_unpack_weights", "mq_qlinear_w_only", "mq_qlinear_a8_workspace_bytes", "mq_qlinear_w8a8",
            "mq_qlinear_w4a8", "mq_qlinear_w2a8", "mq_a8_row_bytes", "mq_qlinear_a8_geglu", "mq_qlinear_w_only_geglu", "mq_qlinear_a8_codes", "mq_conv3x3_w_only",
@@ -66,6 +66,10 @@ def tune_force_tile(tile: int) -> None:
 
 def tune_force_splits(parts: int) -> None:
     load().mq_tune_force_splits(int(parts))
+
+
+def tune_force_band(rows: int) -> None:
+    load().mq_tune_force_band(int(rows))
 
 
 def prof_phase_buffer(buf: Optional[torch.Tensor]) -> None:

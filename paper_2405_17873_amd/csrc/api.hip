@@ -92,6 +92,7 @@ int mq_version(void) { return 1; }
 int mq_last_hip_error(void) { return g_last_hip_error.load(); }
 void mq_tune_force_tile(int tile) { set_force_tile(tile); }
 void mq_tune_force_splits(int parts) { set_force_splits(parts); }
+void mq_tune_force_band(int rows) { set_force_band(rows); }
 void mq_prof_phase_buffer(long long* clk, long workgroups) { set_phase_buffer(clk, workgroups); }
 int mq_prof_enable(int on) { return prof_enable(on); }
 int mq_prof_num_slots(void) { return prof_num_slots(); }

@@ -109,6 +109,7 @@ int launch_tap_sums(const uint8_t* codes, int N, int Cin, int bits, int codes_si
 
 void set_force_tile(int t);
 void set_force_splits(int n);
+void set_force_band(int n);
 void set_phase_buffer(long long* p, long workgroups);
 
 // ---- optional per-kernel event timing (prof.hip) ----

@@ -964,3 +964,35 @@ def test_side_streams_and_two_streams_at_once(mq, orc):
         for y in yb:
             assert torch.equal(y, ref[1]), f"two streams, W4A8, round {it}"
         assert torch.equal(yc, ref[2]), f"two streams, W8A8, round {it}"
+
+
+@pytest.mark.parametrize("tile", (-1, 2, 5))
+def test_band_height_of_the_tile_walk_changes_no_result(mq, orc, tile):
+    """The order in which workgroups take the output tiles (bands of row blocks, a ragged last band, bands higher than
+    the problem) decides cache behaviour only: every output bit equals that of the row-by-row walk, and the int32
+    accumulators equal the oracle's."""
+    M, K, N = 1100, 320, 520            # 64-row tiles: 18 row blocks (ragged), 64x64 tiles: 9 column blocks
+    x = si.activations_f16(97, "band/x", M, K, outlier_prob=0.01)
+    w = si.weights_f16(97, "band/w", N, K)
+    p4, oc, os_, oz = make_weight(mq, orc, w, 4)
+    img = si.activations_f16(97, "band/img", 2 * 20 * 24, 64).reshape(2, 20, 24, 64)
+    cw, *_, tapsum = conv_weight(mq, orc, 97, 96, 64, 4, False)
+    _, racc, _ = orc.linear_a8(x, oc, os_, oz, w_signed=False)
+    mq.tune_force_tile(tile)
+    try:
+        ref = None
+        for band in (1, 2, 5, 7, 16, 1000):
+            mq.tune_force_band(band)
+            y = mq.qlinear_w_only(dev(x), p4)
+            y8, acc, _ = mq.qlinear_w4a8(dev(x), p4, want_acc=True)
+            yc = mq.conv3x3_w_only(dev(img), cw)
+            yc8 = mq.conv3x3_a8(dev(img), cw, tapsum)[0]
+            got = [t.clone() for t in (y, y8, acc, yc, yc8)]
+            assert np.array_equal(host(acc), racc), f"band {band}"
+            if ref is None:
+                ref = got
+            for a, b in zip(got, ref):
+                assert torch.equal(a, b), f"band {band} tile {tile}"
+    finally:
+        mq.tune_force_band(0)
+        mq.tune_force_tile(-1)
