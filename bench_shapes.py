@@ -52,7 +52,7 @@ def shapes():
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--iters", type=int, default=200)
-    ap.add_argument("--only", default="", help="comma-separated labels (c1,c2,c3,c4,c5,small-M,ff,conv,qkv)")
+    ap.add_argument("--only", default="", help="comma-separated labels (c1,c2,c3,c4,c5,small-M,ff,conv,qkv,kvall)")
     ap.add_argument("--tile", type=int, default=-1, help="force a tile of the GEMM's tile table (-1: the library's choice)")
     ap.add_argument("--band", type=int, default=0, help="force the band height of the workgroup -> tile map (0: the library's choice)")
     args = ap.parse_args()
@@ -157,6 +157,8 @@ def main():
         convs(mq, torch, min(args.iters, 100), overhead_us)
     if not only or "qkv" in only:
         stacked_qkv(mq, torch, min(args.iters, 120))
+    if not only or "kvall" in only:
+        all_kv_projections(mq, torch, min(args.iters, 40))
 
 
 def ff_pairs(mq, torch, iters, overhead_us):
@@ -316,6 +318,57 @@ def stacked_qkv(mq, torch, iters):
             print(f"{M:6d}{Cc:6d} {mode:5s}{res[0]:11.2f}{res[1]:11.2f}", flush=True)
             del sets
             torch.cuda.empty_cache()
+
+
+
+
+def all_kv_projections(mq, torch, iters):
+    """Every cross-attention K and V projection of the UNet reads the same text context, so all of them can run as
+    one stacked layer before the first block: 10 blocks at 640 channels and 60 at 1280 give N = 166 400 output
+    channels over K = 2048, 341 M weights.  With M = 77 (one prompt) or 308 (four) this is the one SDXL shape that is
+    bound by the weight stream from HBM; packed weights of consecutive calls differ, so nothing is cached.
+    Modes: w<bits> weight-only, bos<bits> the BOS-aware projection (pre-computed BOS rows, dynamic parameters)."""
+    dev = torch.device("cuda:0")
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(4)
+    N, K = 10 * 2 * 640 + 60 * 2 * 1280, 2048
+    print("\n# all K/V projections of the UNet as one stacked layer (N = 166400, K = 2048), weights from HBM")
+    print(f"{'M':>6s} {'mode':6s}{'us/call':>9s}{'W MB':>8s}{'GB/s':>8s}{'of 8 TB/s':>10s}{'T(FL)OP/s':>10s}")
+    for bits, sym in ((8, True), (4, False), (2, False)):
+        sets = []
+        for _ in range(2 if bits == 8 else 3):
+            w = (torch.randn(N, K, generator=gen, device=dev) * 0.02).half()
+            c, s_, z = mq.quantize_weights(w, bits, sym)
+            pk, cs = mq.pack_weights(c, bits, mq.LAYOUT_KERNEL, codes_signed=sym)
+            sets.append(mq.PackedWeight(pk, s_, z, cs, N, K, bits, mq.LAYOUT_KERNEL, sym))
+            del w, c
+        wbytes = N * K * bits / 8
+        bos_out = torch.zeros(N, dtype=torch.float16, device=dev)
+        for B in (1, 4):
+            M = B * 77
+            ctx = torch.randn(B, 77, K, generator=gen, device=dev).half()
+            y = torch.empty(B, 77, N, dtype=torch.float16, device=dev)
+            ws = torch.empty(mq.bos_aware_kv_proj_workspace_bytes(B, 77, K), dtype=torch.uint8, device=dev)
+            for mode in ("w", "bos"):
+                if mode == "w":
+                    fns = [mq.plan_qlinear_w_only(ctx.view(M, K), pw, None, y.view(M, N)) for pw in sets]
+                else:
+                    fns = [mq.plan_bos_aware_kv_proj(ctx, pw, y, ws, bos_out=bos_out) for pw in sets]
+                for f in fns:
+                    f()
+                torch.cuda.synchronize()
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                for i in range(iters):
+                    fns[i % len(fns)]()
+                e1.record()
+                torch.cuda.synchronize()
+                us = e0.elapsed_time(e1) * 1e3 / iters
+                tot = wbytes + 10 * N + (2 if mode == "w" else 3) * M * K + 2 * M * N
+                print(f"{M:6d} {mode + str(bits):6s}{us:9.1f}{wbytes / 1e6:8.1f}{tot / us / 1e3:8.0f}{tot / us / 1e6 / 8:10.3f}"
+                      f"{2.0 * M * N * K / us / 1e6:10.1f}", flush=True)
+        del sets
+        torch.cuda.empty_cache()
 
 
 if __name__ == "__main__":

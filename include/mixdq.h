@@ -51,8 +51,9 @@ int mq_version(void);
 int mq_last_hip_error(void);
 
 /* Tuning and test hook: force the GEMM workgroup tile (0: 128x256, 1: 128x128, 2: 64x64, 3 and 4: as 1 and 2 with the
- * reduction split over two wave groups inside the workgroup; -1: automatic choice
- * from the problem shape).  Process-wide, not thread safe; results do not depend on the tile. */
+ * reduction split over two wave groups inside the workgroup, 5: 64x128, 6: 96x256; -1: automatic choice
+ * from the problem shape; a mode that does not have the tile takes its nearest one).  Process-wide, not thread safe;
+ * results do not depend on the tile beyond the order of the fp32 sums. */
 void mq_tune_force_tile(int tile);
 
 /* Tuning and test hook: split of a GEMM's reduction over several workgroups per output tile (0: automatic, for

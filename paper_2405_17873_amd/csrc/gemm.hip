@@ -1196,9 +1196,13 @@ bool take_split_scratch(size_t bytes, int tiles, uint32_t** partial, uint32_t** 
 // Measured on the SDXL shapes: the large tile wins once it yields two or more workgroups per compute unit; the
 // k-split variants only pay where tiles are few and k is long (FF-out at the 640 level, the K/V projections).
 static int pick_tile(int M, int N, int K, bool wide_weights = false) {
-    if (g_force_tile >= 0 && g_force_tile <= 4) return g_force_tile;
+    if ((g_force_tile >= 0 && g_force_tile <= 4) || g_force_tile == 6) return g_force_tile;
     if (g_force_tile == 5) return 1;  // the half-height form of tile 1: the linear layers' dispatch decides (narrow_tile)
     const long t0 = (long)((M + 127) / 128) * ((N + 255) / 256);
+    // One row block of 65 to 96 rows over very many column tiles (one prompt's 77 text tokens through all K/V
+    // projections of the UNet, stacked): the 96x256 tile does three quarters of the large tile's MFMA and widening work
+    // on the same weight stream (measured at N = 166400: 13 to 18 % faster with 2- and 4-bit weights, equal at 8).
+    if (M > 64 && M <= 96 && t0 >= 256) return 6;
     // (8-bit weights of the int8 path: the large tile leaves LDS for one workgroup per compute unit only, and two
     // co-resident 128x128 workgroups were measured faster on every configured shape)
     if (t0 >= 512 && !wide_weights) return 0;
@@ -1327,6 +1331,7 @@ static int dispatch_gemm(GemmArgs& g, hipStream_t st) {
         case 2: return run_gemm<I8, BITS, 2, 2, 1, 1, 1, 80 * 1024, 8>(g, 2, st);
         case 3: return run_gemm<I8, BITS, 2, 2, 2, 2, 2, 160 * 1024, 4>(g, 3, st);
         case 5: return run_gemm<I8, BITS, 1, 4, 2, 1, 1, I8 ? 40 * 1024 : 52 * 1024, 3>(g, 5, st);
+        case 6: return run_gemm<I8, BITS, 1, 4, 3, 2, 1, WIDE ? 160 * 1024 : 80 * 1024, 4>(g, 6, st);
         default: return run_gemm<I8, BITS, 2, 2, 1, 1, 2, 80 * 1024, 8>(g, 4, st);
     }
 }
@@ -1336,7 +1341,7 @@ template <int BITS>
 static int dispatch_gemm_bf16(GemmArgs& g, hipStream_t st) {
     constexpr bool WIDE = BITS == 16;
     int t = pick_tile(g.M, g.N, g.K, WIDE);
-    t = narrow_tile<false, BITS>(t >= 3 ? t - 2 : t, g.N, g.K);
+    t = narrow_tile<false, BITS>(t == 6 ? 0 : (t >= 3 ? t - 2 : t), g.N, g.K);
     switch (t) {
         case 0: return run_gemm<false, BITS, 1, 4, 4, 2, 1, WIDE ? 160 * 1024 : 80 * 1024, 4, true>(g, 0, st);
         case 1: return run_gemm<false, BITS, 2, 2, 2, 2, 1, 80 * 1024, 4, true>(g, 1, st);
@@ -1504,7 +1509,7 @@ int launch_gemm_a8_codes(const int8_t* a8, long lda, const float* act_scale, con
     // no in-workgroup k split here, and not the large tile (no registers to spare for the row sums; the layers this
     // serves, the output linears of feed-forward blocks, are narrow); the half-height tile 5 in place of tile 1
     int t = pick_tile(M, N, K, true);
-    t = t >= 3 ? t - 2 : t;
+    t = t == 6 ? 1 : (t >= 3 ? t - 2 : t);
     // (tile 5 doubles the row-sum work per MFMA: measured 8 % faster at K = 1280, 5 % at 2560, 9 % slower at 5120)
     const bool half_height = g_force_tile == 5 || (g_force_tile < 0 && K < 4096);
     if (w_bits == 4) {
@@ -1560,7 +1565,7 @@ template <int BITS>
 static int dispatch_conv_w_only(GemmArgs& g, hipStream_t st) {
     constexpr bool WIDE = BITS == 16;
     int t = pick_tile(g.M, g.N, g.K, WIDE);
-    t = t >= 3 ? t - 2 : t;
+    t = t == 6 ? 1 : (t >= 3 ? t - 2 : t);
     // (the large tile only where its 256 channels are filled: the UNet's 320-channel level is better served by 128)
     if (g_force_tile < 0 && t == 0 && g.N < 512) t = 1;
     if (g_force_tile == 5 || (g_force_tile < 0 && t == 1))
@@ -1613,7 +1618,7 @@ int launch_conv3x3_a8(const int8_t* a8, const ActParams* params, int B, int H, i
     g.acc_debug = acc_debug;
     // (not the large tile: no registers to spare for the row sums and the tap masks; tile 5 in place of tile 1)
     int t = pick_tile(g.M, N, g.K, true);
-    t = t >= 3 ? t - 2 : t;
+    t = t == 6 ? 1 : (t >= 3 ? t - 2 : t);
     if (w_bits == 4) {
         g.w_off = 0;
         if (t <= 1 && g_force_tile != 1) return run_gemm<true, 4, 1, 4, 2, 1, 1, 40 * 1024, 3, false, 4>(g, 5, st);

@@ -113,7 +113,7 @@ void set_force_band(int n);
 void set_phase_buffer(long long* p, long workgroups);
 
 // ---- optional per-kernel event timing (prof.hip) ----
-enum { PROF_GEMM_TILES = 6, PROF_GEMM_BITS = 5, PROF_GEMM_FAMILIES = 7, PROF_ACT_MINMAX = PROF_GEMM_FAMILIES * PROF_GEMM_BITS * PROF_GEMM_TILES, PROF_ACT_QUANTIZE, PROF_BOS_ROWS };
+enum { PROF_GEMM_TILES = 7, PROF_GEMM_BITS = 5, PROF_GEMM_FAMILIES = 7, PROF_ACT_MINMAX = PROF_GEMM_FAMILIES * PROF_GEMM_BITS * PROF_GEMM_TILES, PROF_ACT_QUANTIZE, PROF_BOS_ROWS };
 int prof_num_slots();
 int prof_gemm_slot(int family /*0 weight-only fp16, 1 int8, 2 weight-only bf16, 3 int8 gated projection, 4 int8 on codes, 5 weight-only convolution, 6 int8 convolution*/,
                    int bits, int tile);

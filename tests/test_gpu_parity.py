@@ -128,7 +128,7 @@ W_ONLY_SHAPES = [
 
 
 @pytest.mark.parametrize("bits", ALL_BITS)
-@pytest.mark.parametrize("tile", (-1, 0, 1, 2, 3, 4, 5))
+@pytest.mark.parametrize("tile", (-1, 0, 1, 2, 3, 4, 5, 6))
 def test_w_only_small_shapes(mq, orc, bits, tile):
     mq.tune_force_tile(tile)
     for (M, K, N) in W_ONLY_SHAPES:
@@ -220,7 +220,7 @@ def test_w_only_transformer_block_shapes_sampled_rows(mq, orc, M, K, N):
 
 # ----------------------------------------------------------------------------------------------- layers kept at 16 bits
 
-@pytest.mark.parametrize("tile", (-1, 0, 1, 2, 3, 4, 5))
+@pytest.mark.parametrize("tile", (-1, 0, 1, 2, 3, 4, 5, 6))
 def test_unquantised_16bit_layer(mq, orc, tile):
     """bits = 16: the weights go through the same tile order and GEMM skeleton unquantised (fp16 and bf16)."""
     mq.tune_force_tile(tile)
@@ -313,7 +313,7 @@ A8_SHAPES = [(256, 320, 320), (1, 64, 32), (77, 128, 40), (608, 2048, 640), (300
 
 
 @pytest.mark.parametrize("mode", ("w8s", "w8a", "w4", "w2"))
-@pytest.mark.parametrize("tile", (-1, 0, 1, 2, 3, 4, 5))
+@pytest.mark.parametrize("tile", (-1, 0, 1, 2, 3, 4, 5, 6))
 def test_a8_small_shapes(mq, orc, mode, tile):
     mq.tune_force_tile(tile)
     bits, sym = {"w8s": (8, True), "w8a": (8, False), "w4": (4, False), "w2": (2, False)}[mode]
@@ -639,7 +639,7 @@ def test_conv_stride_two(mq, orc, tile):
 RES_SHAPES = [(256, 320, 320), (77, 128, 40), (513, 192, 264), (300, 640, 640), (1, 64, 32)]
 
 
-@pytest.mark.parametrize("tile", (-1, 0, 1, 2, 3, 4, 5))
+@pytest.mark.parametrize("tile", (-1, 0, 1, 2, 3, 4, 5, 6))
 def test_residual_weight_only(mq, orc, tile):
     """y = linear(x) + residual with one rounding; the residual as its own tensor, as a strided view, and as the
     output tensor itself (in place)."""
@@ -716,7 +716,7 @@ def test_residual_bf16_and_unquantised_layer(mq, orc):
 
 
 @pytest.mark.parametrize("mode", ("w8s", "w4"))
-@pytest.mark.parametrize("tile", (-1, 0, 1, 2, 3, 4, 5))
+@pytest.mark.parametrize("tile", (-1, 0, 1, 2, 3, 4, 5, 6))
 def test_residual_a8(mq, orc, mode, tile):
     bits, sym = (8, True) if mode == "w8s" else (4, False)
     mq.tune_force_tile(tile)
@@ -996,3 +996,27 @@ def test_band_height_of_the_tile_walk_changes_no_result(mq, orc, tile):
     finally:
         mq.tune_force_band(0)
         mq.tune_force_tile(-1)
+
+
+def test_one_prompt_through_many_stacked_projections(mq, orc):
+    """One prompt's 77 text tokens through a stack of K/V projections wide enough for the 96-row tile that the library
+    picks for a single row block of 65 to 96 rows over very many column tiles (here 257 of 256 channels; the reduction
+    is kept short for the oracle's sake): weight-only, W4A8 (int32 accumulators bit-exact) and the BOS-aware call."""
+    B, T, K, N = 1, 77, 128, 257 * 256
+    ctx = si.bos_context_f16(98, "kvall/ctx", B, T, K, n_outlier=4)
+    w = si.weights_f16(98, "kvall/w", N, K)
+    b = si.bias_f16(98, "kvall/b", N)
+    x = ctx.reshape(T, K)
+    pw, oc, os_, oz = make_weight(mq, orc, w, 4)
+    assert_close16(host(mq.qlinear_w_only(dev(x), pw, bias=dev(b))), orc.linear_w_only(x, oc, os_, oz, bias=b), "w4a16")
+    y, acc, _ = mq.qlinear_w4a8(dev(x), pw, bias=dev(b), want_acc=True)
+    ry, racc, _ = orc.linear_a8(x, oc, os_, oz, w_signed=False, bias=b)
+    assert np.array_equal(host(acc), racc)
+    assert_close16(host(y), ry, "w4a8")
+    y, _ = mq.bos_aware_kv_proj(dev(ctx), pw, w_f16=dev(w), bias=dev(b))
+    ry, _ = orc.bos_aware_kv_proj(ctx, oc, os_, oz, w_signed=False, w_f16=w, bias=b)
+    assert_close16(host(y)[0], ry[0], "bos-aware")
+    # (3 x 32 rows: the third slab holds rows 64..76 and 19 rows of padding that must not be stored)
+    guard = torch.full((T + 8, N), 7.0, dtype=torch.float16, device="cuda")
+    mq.qlinear_w_only(dev(x), pw, out=guard[:T])
+    assert bool((guard[T:] == 7.0).all())
