@@ -154,7 +154,8 @@ int mq_unpack_weights(const void* packed, int N, int K, int bits, int layout, ui
  *     Y[m,n] = round16( sum_k X[m,k] * scale[n] * (code[n,k] - zp[n]) + bias[n] ),  fp32 accumulation.
  *   x      [M,K] row stride ldx, 16-byte aligned, ldx % 8 == 0.     y [M,N] row stride ldy, 16-byte aligned, ldy % 8 == 0.
  *   packed MQ_LAYOUT_KERNEL, unsigned codes.   bias nullable [N] (same 16-bit dtype as x and y).
- *   K % 64 == 0, N % 8 == 0, M*ldx*2 < 2^31 bytes.  No workspace is needed.
+ *   K % 64 == 0, N % 8 == 0, M*ldx*2 < 2^31 bytes, (N+31)*K < 2^31 elements and, at bits = 16, < 2^30.  No workspace is
+ *   needed.
  *   bits = 16: the layer is kept at 16 bits; packed holds the weights themselves (same dtype as x) in
  *   MQ_LAYOUT_KERNEL, w_scale and w_zp are ignored (may be null):  Y = round16( sum_k X[m,k] * W[n,k] + bias[n] ).
  *   residual nullable [M,N] of the same 16-bit dtype, row stride ldr (ldr % 4 == 0, 8-byte aligned): added in fp32

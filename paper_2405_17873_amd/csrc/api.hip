@@ -160,6 +160,8 @@ int mq_qlinear_w_only(const void* x, int M, int K, int ldx, const void* packed, 
     int rc = check_linear_common(x, M, K, ldx, packed, N, layout, w_scale, w_zp, bias, y, ldy, bits != 16);
     if (rc) return rc;
     if ((rc = check_residual(residual, ldr, N))) return rc;
+    // (lane offsets into the weights are 32-bit byte offsets: unquantised weights take two bytes per element)
+    if (bits == 16 && (long)(N + 31) * K * 2 >= (1L << 31)) return MQ_ERR_BAD_SHAPE;
     if (bits == 16) w_scale = nullptr, w_zp = nullptr;  // 16-bit weights are used as they are
     return launch_gemm_w_only(x, M, K, ldx, packed, N, bits, w_scale, w_zp, bias, y, ldy, dtype, residual, ldr,
                               (hipStream_t)stream);

@@ -82,6 +82,8 @@ def test_error_codes_without_a_gpu(lib):
     assert lib.mq_qlinear_w_only(*args(res=p, ldr=16)) == -2              # residual rows shorter than N
     assert lib.mq_qlinear_w_only(*args(res=p, ldr=34)) == -2
     assert lib.mq_qlinear_w_only(*args(res=C.c_void_p(p.value + 4), ldr=32)) == -1
+    # unquantised weights of 2 GiB and more: their byte offsets would not fit 32 bits
+    assert lib.mq_qlinear_w_only(*args(M=1, K=40960, ldx=40960, N=32768, ldy=32768, bits=16)) == -2
     # a8
     a8 = lambda **o: [p, 8, o.get("K", 64), o.get("K", 64), p, 32, 1, 1, p, p, o.get("colsum", p),
                       o.get("a_s", null), o.get("a_z", null), null, p, 32, null, o.get("res", null), o.get("ldr", 0), null,
