@@ -97,9 +97,9 @@ def layer_costs(params, bits):
 
 
 def split_budget(b_all: int, p_content: int, p_quality: int, k: float):
-    """App. A, Alg. 1, SplitBudget.  Reading taken (the paper names K "the ratio between budgets assigned for the
-    content-related and quality-related groups" and scans it around 1): K is the ratio of the two groups' average
-    bit-widths, avg_content = K * avg_quality, with B_content + B_quality = B_all.
+    """App. A, Alg. 1, SplitBudget.  The paper defines K only as the ratio in which the budget is shared between the
+    content group and the quality group, and scans values near one.  Reading taken: K is the ratio of the two groups'
+    average bit-widths, avg_content = K * avg_quality, with B_content + B_quality = B_all.
     Returns (B_content, B_quality) in bits; B_content is rounded down, the rest goes to the quality group."""
     avg_q = b_all / (k * p_content + p_quality)
     b_content = int(math.floor(k * avg_q * p_content))
