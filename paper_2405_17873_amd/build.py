@@ -27,7 +27,8 @@ SOURCES = ["api.hip", "quant_pack.hip", "act_quant.hip", "gemm.hip", "bos.hip", 
 def _compile(src: str, force: bool) -> str:
     path = os.path.join(CSRC, src)
     obj = os.path.join(OBJ, src + ".o")
-    deps = [path, os.path.join(CSRC, "mq_common.h"), os.path.join(HERE, "..", "include", "mixdq.h"), __file__]
+    deps = [path, os.path.join(CSRC, "mq_common.h"), os.path.join(CSRC, "bos_rows.h"),
+            os.path.join(HERE, "..", "include", "mixdq.h"), __file__]
     if not force and os.path.exists(obj) and all(os.path.getmtime(obj) >= os.path.getmtime(d) for d in deps):
         return obj
     cmd = [HIPCC, *COMMON, *PER_FILE.get(src, []), "-c", path, "-o", obj]

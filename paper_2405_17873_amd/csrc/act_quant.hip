@@ -9,7 +9,7 @@
 //               0,4,1,5,2,6,3,7, rows padded with zeros to a multiple of 128, and rowsum[m] = sum_k a'[m,k].
 //
 // Compiled with -ffp-contract=off: each fp32 operation rounds once.
-#include "mq_common.h"
+#include "bos_rows.h"
 
 namespace mq {
 
@@ -77,6 +77,9 @@ __global__ __launch_bounds__(256) void act_minmax_kernel(const _Float16* __restr
 static constexpr int Q_MAX_ROWS = 128;  // rows per workgroup, pass 2 (1024 output vectors of at least 8 per row)
 
 // A workgroup converts R whole rows (so that it owns their row sums): R * Kp/8 output vectors, 1024 per round.
+// BOS: workgroups from index qgrid on compute the BOS rows of a BOS-aware K/V projection instead (they depend on
+// nothing this kernel produces; one launch less on a path whose kernels are all bound by launch latency).
+template <bool BOS>
 __global__ __launch_bounds__(256) void act_quantize_kernel(const _Float16* __restrict__ x, int M, int K, long ldx,
                                                            RowMap map, int R, const float* __restrict__ partials,
                                                            int n_partials, const float* __restrict__ act_scale,
@@ -84,7 +87,16 @@ __global__ __launch_bounds__(256) void act_quantize_kernel(const _Float16* __res
                                                            int8_t* __restrict__ a8, int32_t* __restrict__ rowsum,
                                                            ActParams* __restrict__ params,
                                                            float* __restrict__ act_scale_out,
-                                                           int32_t* __restrict__ act_zp_out) {
+                                                           int32_t* __restrict__ act_zp_out, int qgrid, BosWork bw) {
+    if constexpr (BOS) {
+        if ((int)blockIdx.x >= qgrid) {  // (whole workgroups: none of them reaches a barrier below)
+            if (bw.bos_out)
+                bos_copy_block((int)blockIdx.x - qgrid, (int)threadIdx.x, bw);
+            else
+                bos_rows_block<4>((int)blockIdx.x - qgrid, (int)threadIdx.x, bw);
+            return;
+        }
+    }
     const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
     __shared__ float smn[4], smx[4];
     __shared__ int lsum[Q_MAX_ROWS];
@@ -184,7 +196,7 @@ __global__ __launch_bounds__(256) void act_quantize_kernel(const _Float16* __res
 
 int launch_act_quant(const void* x, int M, int K, int ldx, RowMap in_map, const float* act_scale,
                      const int32_t* act_zp, int8_t* a8, int32_t* rowsum, ActParams* params, float* partials,
-                     float* act_scale_out, int32_t* act_zp_out, hipStream_t st) {
+                     float* act_scale_out, int32_t* act_zp_out, const BosWork* bos, hipStream_t st) {
     const uint32_t K8 = (uint32_t)K >> 3;
     const uint32_t nv = (uint32_t)M * K8;  // M * ldx * 2 < 2^31 has been checked: this fits easily
     long g1 = ((long)nv + 256 * MM_U - 1) / (256 * MM_U);
@@ -202,9 +214,14 @@ int launch_act_quant(const void* x, int M, int K, int ldx, RowMap in_map, const 
     R = R < 1 ? 1 : (R > Q_MAX_ROWS ? Q_MAX_ROWS : R);
     const int qgrid = (M + R - 1) / R;
     ProfScope prof(st, PROF_ACT_QUANTIZE, 0.0, 3.0 * M * K + 4.0 * M);
-    hipLaunchKernelGGL(act_quantize_kernel, dim3(qgrid), dim3(256), 0, st, (const _Float16*)x, M, K, (long)ldx, in_map,
-                       R, dynamic ? partials : (const float*)nullptr, grid, act_scale, act_zp, a8, rowsum, params,
-                       act_scale_out, act_zp_out);
+    if (bos)
+        hipLaunchKernelGGL(act_quantize_kernel<true>, dim3(qgrid + bos_blocks(*bos)), dim3(256), 0, st,
+                           (const _Float16*)x, M, K, (long)ldx, in_map, R, dynamic ? partials : (const float*)nullptr,
+                           grid, act_scale, act_zp, a8, rowsum, params, act_scale_out, act_zp_out, qgrid, *bos);
+    else
+        hipLaunchKernelGGL(act_quantize_kernel<false>, dim3(qgrid), dim3(256), 0, st, (const _Float16*)x, M, K,
+                           (long)ldx, in_map, R, dynamic ? partials : (const float*)nullptr, grid, act_scale, act_zp,
+                           a8, rowsum, params, act_scale_out, act_zp_out, qgrid, BosWork{});
     MQ_HIP_CHECK_LAUNCH();
     return MQ_OK;
 }

@@ -66,7 +66,7 @@ static int qlinear_a8(const void* x, int M, int K, int ldx, RowMap in_map, const
                       int w_bits, int w_signed, const float* w_scale, const int32_t* w_zp, const int32_t* w_colsum,
                       const float* act_scale, const int32_t* act_zp, const void* bias, void* y, int ldy, RowMap out_map,
                       int32_t* acc_debug, float* act_scale_out, int32_t* act_zp_out, void* ws, size_t ws_bytes,
-                      const void* residual, int ldr, hipStream_t st) {
+                      const void* residual, int ldr, hipStream_t st, const BosWork* bos = nullptr) {
     int rc = check_linear_common(x, M, K, ldx, packed, N, layout, w_scale, w_zp, bias, y, ldy);
     if (rc) return rc;
     if ((rc = check_residual(residual, ldr, N))) return rc;
@@ -77,7 +77,7 @@ static int qlinear_a8(const void* x, int M, int K, int ldx, RowMap in_map, const
     if (ws_bytes < A8Workspace::bytes(M, K)) return MQ_ERR_WORKSPACE_TOO_SMALL;
     A8Workspace w(ws, M, K);
     rc = launch_act_quant(x, M, K, ldx, in_map, act_scale, act_zp, w.a8, w.rowsum, w.params, w.partials,
-                          act_scale_out, act_zp_out, st);
+                          act_scale_out, act_zp_out, bos, st);
     if (rc) return rc;
     return launch_gemm_a8(w.a8, w.rowsum, w.params, M, K, packed, N, w_bits, w_signed, w_scale, w_zp, w_colsum, bias,
                           y, ldy, out_map, acc_debug, residual, ldr, st);
@@ -190,7 +190,7 @@ int mq_qlinear_a8_geglu(const void* x, int M, int K, int ldx, const void* packed
     hipStream_t st = (hipStream_t)stream;
     A8Workspace w(ws, M, K);
     rc = launch_act_quant(x, M, K, ldx, RowMap{0, 0, 0}, act_scale, act_zp, w.a8, w.rowsum, w.params, w.partials,
-                          act_scale_out, act_zp_out, st);
+                          act_scale_out, act_zp_out, nullptr, st);
     if (rc) return rc;
     return launch_gemm_a8_geglu(w.a8, w.rowsum, w.params, M, K, packed, H, w_bits, w_signed ? 1 : 0, w_scale, w_zp,
                                 w_colsum, bias, out_scale, out_zp, a8_out, h16_out, ldh, st);
@@ -289,7 +289,7 @@ int mq_conv3x3_a8(const void* x, int B, int H, int W, int Cin, int stride, const
     hipStream_t st = (hipStream_t)stream;
     A8Workspace w(ws, M, Cin);
     rc = launch_act_quant(x, (int)M, Cin, Cin, RowMap{0, 0, 0}, act_scale, act_zp, w.a8, w.rowsum, w.params, w.partials,
-                          act_scale_out, act_zp_out, st);
+                          act_scale_out, act_zp_out, nullptr, st);
     if (rc) return rc;
     return launch_conv3x3_a8(w.a8, w.params, B, H, W, Cin, stride, packed, N, w_bits, w_signed ? 1 : 0, w_scale, w_zp, w_colsum,
                              w_tapsum, bias, y, acc_debug, residual, st);
@@ -349,17 +349,18 @@ int mq_bos_aware_kv_proj(const void* ctx, int B, int T, int K, const void* packe
     if ((w_f16 == nullptr) == (bos_out == nullptr)) return MQ_ERR_BAD_ARG;
     if (w_f16 && !aligned(w_f16, 16)) return MQ_ERR_BAD_ARG;
     if (ws_bytes < mq_bos_aware_kv_proj_workspace_bytes(B, T, K)) return MQ_ERR_WORKSPACE_TOO_SMALL;
+    const BosWork bw{(const _Float16*)ctx, B, T, K, N, (const _Float16*)w_f16, (const _Float16*)bos_out,
+                     (const _Float16*)bias, (_Float16*)y};
     if (T > 1) {
+        // (the BOS rows ride along as extra workgroups of the activation-quantise launch)
         const RowMap body{T - 1, T, 1};  // logical row r -> token 1 + r % (T-1) of prompt r / (T-1)
-        int rc = qlinear_a8(ctx, B * (T - 1), K, K, body, packed, N, layout, w_bits, w_signed ? 1 : 0, w_scale, w_zp,
-                            w_colsum, act_scale, act_zp, bias, y, N, body, nullptr, act_scale_out, act_zp_out, ws,
-                            ws_bytes, nullptr, 0, st);
-        if (rc) return rc;
-    } else {
-        int rc = check_linear_common(ctx, B, K, K, packed, N, layout, w_scale, w_zp, bias, y, N);
-        if (rc) return rc;
+        return qlinear_a8(ctx, B * (T - 1), K, K, body, packed, N, layout, w_bits, w_signed ? 1 : 0, w_scale, w_zp,
+                          w_colsum, act_scale, act_zp, bias, y, N, body, nullptr, act_scale_out, act_zp_out, ws,
+                          ws_bytes, nullptr, 0, st, &bw);
     }
-    return launch_bos_rows(ctx, B, T, K, w_f16, bos_out, bias, y, N, st);
+    int rc = check_linear_common(ctx, B, K, K, packed, N, layout, w_scale, w_zp, bias, y, N);
+    if (rc) return rc;
+    return launch_bos_rows(bw, st);
 }
 
 }  // extern "C"

@@ -70,11 +70,22 @@ int launch_pack(const uint8_t* codes, int N, int K, int bits, int layout, int co
                 int32_t* colsum, hipStream_t st);
 int launch_unpack(const void* packed, int N, int K, int bits, int layout, uint8_t* codes, hipStream_t st);
 
+// BOS rows of one BOS-aware K/V projection: ctx [B,T,K] fp16, unquantised weights [N,K] fp16 or the pre-computed
+// vector [N] (exactly one of the two), optional bias, output [B,T,N] (only token 0 of each prompt is written).
+struct BosWork {
+    const _Float16* ctx;
+    int B, T, K, N;
+    const _Float16* w_f16;
+    const _Float16* bos_out;
+    const _Float16* bias;
+    _Float16* y;
+};
+
 // Activation min/max partials -> parameters -> int8 copy (a' = code - 128, groups of 8 in k8_perm order)
-// and per-row sums of a'.
+// and per-row sums of a'.  bos (optional): BOS rows computed by extra workgroups of the quantise launch.
 int launch_act_quant(const void* x, int M, int K, int ldx, RowMap in_map, const float* act_scale,
                      const int32_t* act_zp, int8_t* a8, int32_t* rowsum, ActParams* params, float* partials,
-                     float* act_scale_out, int32_t* act_zp_out, hipStream_t st);
+                     float* act_scale_out, int32_t* act_zp_out, const BosWork* bos, hipStream_t st);
 int act_quant_partial_slots();
 
 int launch_gemm_w_only(const void* x, int M, int K, int ldx, const void* packed, int N, int bits,
@@ -143,7 +154,6 @@ struct ProfScope {
     }
 };
 
-int launch_bos_rows(const void* ctx, int B, int T, int K, const void* w_f16, const void* bos_out, const void* bias,
-                    void* y, int N, hipStream_t st);
+int launch_bos_rows(const BosWork& bw, hipStream_t st);
 
 }  // namespace mq
