@@ -567,18 +567,25 @@ void gemm_kernel(const GemmArgs g) {
     // BEFORE the first LDS-writing load, so that they are the oldest entries of the vector-memory counter and the
     // hand-counted waits below see only the stage loads behind them.
     static_assert(BN <= NT, "one thread per channel");
-    float c_scale = 0.0f, c_bias = 0.0f, c_sx = 1.0f;
-    int c_zp = 0, c_colsum = 0, c_zx = 0;
+    float c_scale = 0.0f;
+    uint32_t c_bias_bits = 0;  // converted where it is used, after the loop: a conversion here would wait for the load
+    int c_zp = 0, c_colsum = 0;
+    // (the activation parameters are the same for every thread: loaded outside the divergent branch they stay in
+    // scalar registers, and nothing waits for them before the epilogue)
+    float c_sx = 1.0f;
+    int c_zx = 0;
+    if constexpr (I8) {
+        c_sx = RS_INLINE ? *g.act_scale_p : g.params->scale;
+        c_zx = RS_INLINE ? *g.act_zp_p : g.params->zp;
+    }
     if (threadIdx.x < BN) {
         int n = group_of((int)threadIdx.x >> 5) * 32 + ((int)threadIdx.x & 31);
         n = n < g.N ? n : g.N - 1;
         c_scale = BITS == 16 ? 1.0f : g.w_scale[n];
-        if (g.bias) c_bias = BF ? bf16_bits_to_float(g.bias[n]) : (float)__builtin_bit_cast(_Float16, g.bias[n]);
+        if (g.bias) c_bias_bits = g.bias[n];
         if constexpr (I8) {
             c_zp = g.w_zp[n];
             c_colsum = g.w_colsum[n];
-            c_sx = RS_INLINE ? *g.act_scale_p : g.params->scale;
-            c_zx = RS_INLINE ? *g.act_zp_p : g.params->zp;
         }
     }
     int rsum[TM];
@@ -772,13 +779,18 @@ void gemm_kernel(const GemmArgs g) {
     if (threadIdx.x < BN) {
         const int t = threadIdx.x;
         if constexpr (I8) {
+            // (nothing derived from the activation parameters is computed before this point: the arithmetic would
+            // wait for their load at the top of the kernel, ahead of the first stage's requests)
+            asm volatile("" : "+s"(c_zx), "+s"(c_sx));
             const int dx = 128 - c_zx;
             const int dw = g.w_off - c_zp;
             ch_dw[t] = dw;
             ch_cn[t] = dx * (c_colsum - g.K * g.w_off + g.K * dw);
         }
         ch_mul[t] = c_scale * c_sx;
-        ch_add[t] = c_bias;
+        asm volatile("" : "+v"(c_bias_bits));  // (keeps the compiler from moving the conversion up to the load)
+        ch_add[t] = BF ? bf16_bits_to_float((uint16_t)c_bias_bits)
+                       : (float)__builtin_bit_cast(_Float16, (uint16_t)c_bias_bits);
     }
 
     // k-split: the two groups' partial sums meet through LDS ([register quad][lane], 16 bytes per lane).  With an
