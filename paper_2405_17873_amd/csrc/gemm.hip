@@ -349,6 +349,9 @@ struct GemmArgs {
     long ldy;
     int tiles_m, tiles_n;
     int band_rows;        // row blocks per band of the workgroup -> tile map (>= 1)
+    FastDiv fd_band_tiles, fd_band_rows, fd_last_rows;  // divisors of that map: tiles per band, rows of a band, of the last
+    FastDiv fd_splits;
+    int kt_q, kt_r;       // pipeline stages per part of a split reduction: kt_q, and one more for the first kt_r parts
     // int8 only
     const int32_t* rowsum;
     const ActParams* params;
@@ -389,17 +392,19 @@ struct GemmArgs {
 // `band_rows` row blocks, inside a band column by column: the workgroups an XCD runs at the same time then cover
 // band_rows row blocks times a few column blocks, the band's activation rows stay in that L2 while the band walks
 // along N, and every weight tile is fetched once per band instead of once per row block.
-__device__ __forceinline__ void tile_of_block(int bid, int tiles_m, int tiles_n, int band_rows, int& bm, int& bn) {
-    const int total = tiles_m * tiles_n;
+__device__ __forceinline__ void tile_of_block(int bid, const GemmArgs& g, int& bm, int& bn) {
+    const int total = g.tiles_m * g.tiles_n;
     const int per = total >> 3;  // tiles of the leftover (total % 8) keep their own index
-    const int t = bid < (per << 3) ? (bid & 7) * per + (bid >> 3) : bid;
-    const int band_tiles = band_rows * tiles_n;
-    const int band = t / band_tiles;
-    const int first = band * band_rows;
-    const int rows = tiles_m - first < band_rows ? tiles_m - first : band_rows;  // (the last band may be lower)
-    const int r = t - band * band_tiles;
-    bn = r / rows;
-    bm = first + (r - bn * rows);
+    const uint32_t t = (uint32_t)(bid < (per << 3) ? (bid & 7) * per + (bid >> 3) : bid);
+    uint32_t band, r, col, row;
+    g.fd_band_tiles.divmod(t, band, r);
+    const int first = (int)band * g.band_rows;
+    if (g.tiles_m - first < g.band_rows)  // (the last band may be lower)
+        g.fd_last_rows.divmod(r, col, row);
+    else
+        g.fd_band_rows.divmod(r, col, row);
+    bn = (int)col;
+    bm = first + (int)row;
 }
 
 // LDS plan of one workgroup: S stages, each KS sub-stages of [activation tile BM x 128 B][weight tiles]; a 1 KB sink
@@ -466,9 +471,10 @@ void gemm_kernel(const GemmArgs g) {
     // for it: its problems have hundreds of tiles)
     constexpr bool CAN_SPLIT = TM * TN <= 4 && MODE == 0;
     const int splits = CAN_SPLIT ? g.splits : 1;
-    const int tile_id = splits > 1 ? (int)blockIdx.x / splits : (int)blockIdx.x;
-    const int sp = (int)blockIdx.x - tile_id * splits;  // which part of the reduction this workgroup takes
-    tile_of_block(tile_id, g.tiles_m, g.tiles_n, g.band_rows, bm, bn);
+    uint32_t tile_u = blockIdx.x, sp_u = 0;  // sp: which part of the reduction this workgroup takes
+    if (splits > 1) g.fd_splits.divmod(blockIdx.x, tile_u, sp_u);
+    const int tile_id = (int)tile_u, sp = (int)sp_u;
+    tile_of_block(tile_id, g, bm, bn);
     // n0: first output column of the workgroup (MODE 1: first gated column; it covers BN / 2 of them)
     const int m0 = bm * BM, n0 = GEGLU ? bn * (BN / 2) : bn * BN;
     const int KC = g.K >> 6;
@@ -599,8 +605,8 @@ void gemm_kernel(const GemmArgs g) {
     // outstanding" means "all but the n youngest stages have landed" for every wave alike.
     const int KSTEPS = g.k_stages;                // 128-byte k steps
     const int KT_ALL = (KSTEPS + KS - 1) / KS;    // pipeline stages of the whole reduction
-    const int kt0 = splits > 1 ? (int)((long)sp * KT_ALL / splits) : 0;
-    const int KT = (splits > 1 ? (int)((long)(sp + 1) * KT_ALL / splits) : KT_ALL) - kt0;  // ... of this workgroup
+    const int kt0 = splits > 1 ? sp * g.kt_q + (sp < g.kt_r ? sp : g.kt_r) : 0;
+    const int KT = splits > 1 ? g.kt_q + (sp < g.kt_r ? 1 : 0) : KT_ALL;  // ... of this workgroup
     auto issue = [&](int stage, int buf) {
         const int soff_a = __builtin_amdgcn_readfirstlane((kt0 + stage) * KS * 128);
         const int soff_b = __builtin_amdgcn_readfirstlane((kt0 + stage) * KS * CH * TILE_B);
@@ -1288,6 +1294,12 @@ static int run_gemm_r(GemmArgs& g, int tile_index, hipStream_t st) {
     g.splits = 1;
     if (MODE == 0 && TM * TN <= 4 && splits > 1 && take_split_scratch((size_t)tiles * splits * P::BM * P::BN * 4, (int)tiles, &g.partial, &g.counters))
         g.splits = splits;
+    g.fd_band_tiles = FastDiv::make((uint32_t)(g.band_rows * g.tiles_n));
+    g.fd_band_rows = FastDiv::make((uint32_t)g.band_rows);
+    g.fd_last_rows = FastDiv::make((uint32_t)(g.tiles_m % g.band_rows ? g.tiles_m % g.band_rows : g.band_rows));
+    g.fd_splits = FastDiv::make((uint32_t)g.splits);
+    g.kt_q = KT / g.splits;
+    g.kt_r = KT % g.splits;
     g.phase_clk = (tiles * g.splits <= g_phase_cap) ? g_phase_clk : nullptr;
     auto kern = gemm_kernel<I8, BITS, WGM, WGN, TM, TN, S, KS, BF, MODE, RES>;
     // Once per instantiation and device (callers may be on several host threads): allow more than 64 KB of dynamic

@@ -63,6 +63,28 @@ struct RowMap {
     }
 };
 
+// Division of a 32-bit unsigned number by a divisor that the host knows: the quotient estimate from the high half
+// of t * floor(2^32 / d) is at most one too small (for any t < 2^32, d >= 1), which one comparison corrects.  An
+// integer division in device code costs about forty instructions, and a kernel's prologue has several of them on its
+// critical path.
+struct FastDiv {
+    uint32_t d, inv;
+    static FastDiv make(uint32_t d_) {
+        FastDiv f;
+        f.d = d_ ? d_ : 1;
+        f.inv = f.d == 1 ? 0xFFFFFFFFu : (uint32_t)((1ULL << 32) / f.d);
+        return f;
+    }
+    __device__ inline void divmod(uint32_t t, uint32_t& q, uint32_t& r) const {
+        q = __umulhi(t, inv);
+        r = t - q * d;
+        if (r >= d) {
+            q += 1;
+            r -= d;
+        }
+    }
+};
+
 // ---- launchers implemented in the .hip files (all validate nothing: api.cpp has done it) ----
 int launch_quantize_weights(const void* w, int N, int K, int bits, int symmetric, int dtype, uint8_t* codes,
                             float* scale, int32_t* zp, hipStream_t st);
