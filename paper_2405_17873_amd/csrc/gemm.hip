@@ -233,6 +233,17 @@ __device__ __forceinline__ void dma_to_lds_b128(int4s rsrc, uint32_t lds_wave_ba
         : "memory");  // m0 is a reserved register: the compiler rewrites it before each of its own uses
 }
 
+// The same for 4 bytes per lane (256 contiguous bytes per wave).
+__device__ __forceinline__ void dma_to_lds_b32(int4s rsrc, uint32_t lds_wave_base, int voff, int soff) {
+    asm volatile(
+        "s_mov_b32 m0, %0\n\t"
+        "s_nop 0\n\t"
+        "buffer_load_dword %1, %2, %3 offen lds"
+        :
+        : "s"(lds_wave_base), "v"(voff), "s"(rsrc), "s"(soff)
+        : "memory");
+}
+
 template <int N>
 __device__ __forceinline__ void wait_vmcnt() {
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
@@ -553,12 +564,25 @@ void gemm_kernel(const GemmArgs g) {
             j < P::NBI ? (uint32_t)(sub * P::SUB_BYTES + P::A_BYTES + t * P::BSLOT + piece * 1024) : (uint32_t)0xFFFFFFFFu);
     }
 
+    // Weight zero points of the 16-bit-activation path (the int8 path corrects for them in the epilogue): an ordinary
+    // load here would be waited for by the compiler with a count that ignores the LDS-writing loads, i.e. until all
+    // prologue stages have landed.  So the zero points of the workgroup's channels travel like a stage: one
+    // LDS-writing load per 64 channels, issued first (the oldest entry of the counter), into the slot that the int8
+    // epilogue uses for its own constants; every lane picks its channel's value up after the first barrier.
+    constexpr bool ZP_LDS = !I8 && BITS != 16;
+    constexpr int ZP_SLOT = P::CONSTS + 2 * BN * 4;
+    if constexpr (ZP_LDS) {
+        if (wv < BN / 64) {
+            const int ch = wv * 64 + lane;
+            int n = group_of(ch >> 5) * 32 + (ch & 31);
+            n = n < g.N ? n : g.N - 1;
+            const int4s rz = make_rsrc(g.w_zp, (uint32_t)g.N * 4u);
+            dma_to_lds_b32(rz, __builtin_amdgcn_readfirstlane(lds_base + ZP_SLOT + wv * 256), n * 4, 0);
+        }
+    }
     int zc[TN];
 #pragma unroll
-    for (int tn = 0; tn < TN; ++tn) {
-        const int n = group_of(wn * TN + tn) * 32 + l31;
-        zc[tn] = (I8 || BITS == 16) ? 0 : g.w_zp[n < g.N ? n : g.N - 1];
-    }
+    for (int tn = 0; tn < TN; ++tn) zc[tn] = 0;
 
     acc_t acc[TM][TN];
 #pragma unroll
@@ -714,6 +738,10 @@ void gemm_kernel(const GemmArgs g) {
     else
         wait_vmcnt<0>();
     __syncthreads();
+    if constexpr (ZP_LDS) {
+#pragma unroll
+        for (int tn = 0; tn < TN; ++tn) zc[tn] = *(const int*)(lds + ZP_SLOT + ((wn * TN + tn) * 32 + l31) * 4);
+    }
     request_first(lds + grp * P::SUB_BYTES);
 
     int buf = 0;
