@@ -226,9 +226,10 @@ size_t mq_a8_row_bytes(int K);
  *     lin[m,n]  = fma( (float)ACC[m,n], s_x * s_w[n], bias[n] )            ACC as in mq_qlinear_w8a8
  *     h[m,j]    = lin[m,j] * gelu( lin[m,H+j] )                            j in [0,H)
  *     code[m,j] = clamp( rne(h / s_o) + z_o, 0, 255 )                      h / s_o as a multiply by the fp32 1/s_o
- * gelu(g) = 0.5 g (1 + erf(g / sqrt 2)); every step is one IEEE fp32 operation: erf(x) = 1 - exp(-x P(x)) with a
- * fitted degree-6 polynomial P (|error| < 2e-7) over an exponential by range reduction and a degree-6 polynomial,
- * so that the codes are reproducible bit for bit.
+ * gelu(g) = 0.5 g (1 + erf(g / sqrt 2)).  ACC is exact; everything after it is evaluated in fp32 (erf as
+ * 1 - exp(-x P(x)) with a fitted degree-6 polynomial P, |error| < 2e-7), so a code equals the one the same formulas
+ * give in exact arithmetic except where h / s_o lies within that fp32 error (about 1e-5 of a code step for typical
+ * values) of a rounding boundary, where it may be the neighbouring code.
  *   x [M,K] fp16 (as in mq_qlinear_w8a8, dynamic or static activation parameters), packed: w_bits = 2, 4 or 8,
  *   MQ_LAYOUT_KERNEL, 2H rows; w_scale, w_zp, w_colsum, bias [2H].  H % 32 == 0.
  *   out_scale, out_zp: device pointers to the static parameters (s_o, z_o) of the gated product.

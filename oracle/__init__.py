@@ -221,17 +221,12 @@ def bos_aware_kv_proj(ctx, wcodes, w_scale, w_zp, w_signed=False, w_f16=None, bo
     return y, (np.float32(s.value), int(z.value))
 
 
-def gelu32(g):
-    """The fp32 GELU of the fused feed-forward epilogue, element by element."""
-    g = np.ascontiguousarray(g, np.float32)
-    out = np.empty_like(g)
-    _check(lib().orc_gelu32(_p(g), C.c_long(g.size), _p(out)), "gelu32")
-    return out
-
-
-def linear_a8_geglu(x, wcodes, w_scale, w_zp, out_act, w_signed=False, act=None, bias=None, rows=None, want_h16=True):
-    """GEGLU projection, 8-bit activations in and out.  wcodes [2H,K]; out_act = (scale, zp) of the gated product.
-    Returns (codes uint8 [R,H], h16 uint16 [R,H] or None, (act_scale, act_zp))."""
+def linear_a8_geglu(x, wcodes, w_scale, w_zp, out_act, w_signed=False, act=None, bias=None, rows=None, want_h16=True,
+                    want_pre=False):
+    """GEGLU projection, 8-bit activations in and out, in fp64 with the library erf.  wcodes [2H,K]; out_act = (scale,
+    zp) of the gated product.  Returns (codes uint8 [R,H], h16 uint16 [R,H] or None, (act_scale, act_zp)) and, with
+    want_pre, also (u float64 [R,H] = h / s_o before the rounding, lin float64 [R,2H] = the projection before the
+    gate): what a checker needs to tell a borderline rounding from a wrong code."""
     x = _u16(x)
     bias = _u16(bias)
     wcodes = np.ascontiguousarray(wcodes, np.uint8)
@@ -242,13 +237,17 @@ def linear_a8_geglu(x, wcodes, w_scale, w_zp, out_act, w_signed=False, act=None,
     R = nr if rows is not None else M
     codes = np.empty((R, H), np.uint8)
     h16 = np.empty((R, H), np.uint16) if want_h16 else None
+    u = np.empty((R, H), np.float64) if want_pre else None
+    lin = np.empty((R, 2 * H), np.float64) if want_pre else None
     s = C.c_float(0.0 if act is None else act[0])
     z = C.c_int32(0 if act is None else act[1])
     _check(lib().orc_linear_a8_geglu(_p(x), C.c_long(M), K, C.c_long(K), _p(wcodes), H, int(w_signed),
                                      _p(np.ascontiguousarray(w_scale, np.float32)),
                                      _p(np.ascontiguousarray(w_zp, np.int32)), int(act is None), C.byref(s),
                                      C.byref(z), _p(bias), C.c_float(out_act[0]), C.c_int32(out_act[1]), _p(codes),
-                                     _p(h16), _p(rows), C.c_long(nr)), "linear_a8_geglu")
+                                     _p(h16), _p(u), _p(lin), _p(rows), C.c_long(nr)), "linear_a8_geglu")
+    if want_pre:
+        return codes, h16, (np.float32(s.value), int(z.value)), u, lin
     return codes, h16, (np.float32(s.value), int(z.value))
 
 

@@ -26,8 +26,10 @@
  *   - packing: per row a little-endian bit stream, code k at bits [k*b, k*b+b);
  *   - floating point accumulation in fp64, one rounding to the 16-bit output.
  *
- * Every quantiser operation that decides an integer code is a single IEEE
- * fp32 operation; build with -ffp-contract=off and without -ffast-math.
+ * Every operation of the weight and activation quantisers that decides an
+ * integer code is a single IEEE fp32 operation; build with -ffp-contract=off
+ * and without -ffast-math.  The gated feed-forward extension is stated in
+ * fp64 with the C library's erf (see there for how its codes are compared).
  *
  * All functions return 0 on success, a negative value on a bad argument.
  */
@@ -456,63 +458,31 @@ int orc_bos_aware_kv_proj(const uint16_t* ctx, int B, int T, int K, const uint8_
 /* linears (an extension; the paper's Sec. 4.3 names the separate FP16->INT8 */
 /* conversion layers as the overhead of the W8A8 path, this removes the one  */
 /* between the GEGLU projection and the output linear of a transformer       */
-/* block's feed-forward).                                                     */
+/* block's feed-forward).  Stated by the mathematics, in fp64:               */
 /*                                                                           */
-/*   lin[m,n] = fma((float)ACC[m,n], s_x * s_w[n], bias[n])     n in [0, 2H)  */
-/*   h[m,j]   = lin[m,j] * gelu(lin[m,H+j])                     j in [0, H)   */
-/*   code     = clamp(rne(h * (1/s_o)) + z_o, 0, 255)                         */
+/*   lin[m,n] = ACC[m,n] * (s_x * s_w[n]) + bias[n]            n in [0, 2H)   */
+/*   h[m,j]   = lin[m,j] * gelu(lin[m,H+j])                    j in [0, H)    */
+/*   gelu(g)  = 0.5 g (1 + erf(g / sqrt 2))                    C library erf  */
+/*   u[m,j]   = h / s_o                                                       */
+/*   code     = clamp(rne(u) + z_o, 0, 255)                    Sec. 4.1       */
 /*                                                                           */
-/* (first half of the projection = value, second half = gate).  A code is an */
-/* integer decided by floating point, so every operation is spelt out: all   */
-/* are single IEEE fp32 operations; the error function is 1 - exp(-x P(x))   */
-/* with a fitted degree-6 P (|error| < 2e-7, no division) over an exponential*/
-/* computed by range reduction and a degree-6 polynomial.                    */
+/* (first half of the projection = value, second half = gate).  ACC is the   */
+/* exact integer accumulator of the A8 linear above.  A code is an integer   */
+/* decided by floating point: an implementation that evaluates h in a lower  */
+/* precision reaches the same code except where u lies within its own error  */
+/* of a rounding boundary, so the un-rounded u and lin are handed back for a */
+/* checker to apply that rule element by element.                            */
 /* ------------------------------------------------------------------------- */
 
-/* exp(y) for -64 < y <= 0 in fp32: y = n ln2 + r, |r| <= ln2/2; e^r by Horner; scaled by 2^n. */
-static float exp32_nonpos(float y) {
-    float n = rintf(y * 1.44269504f);
-    float r = fmaf(n, -0.693145752f, y);
-    r = fmaf(n, -1.42860677e-6f, r);
-    float p = 1.0f / 720.0f;
-    p = fmaf(p, r, 1.0f / 120.0f);
-    p = fmaf(p, r, 1.0f / 24.0f);
-    p = fmaf(p, r, 1.0f / 6.0f);
-    p = fmaf(p, r, 0.5f);
-    p = fmaf(p, r, 1.0f);
-    p = fmaf(p, r, 1.0f);
-    return ldexpf(p, (int)n);
-}
-
-/* gelu(g) = 0.5 g (1 + erf(g / sqrt 2)) with erf(x) = 1 - exp(-x P(x)) for 0 <= x <= 4.3 (beyond, x is held at 4.3,
- * where erf is 1 to 1e-9) and odd symmetry; P is a degree-6 polynomial fitted to -ln(erfc(x)) / x, which keeps the
- * absolute error of erf below 2e-7 without any division. */
-static float gelu32(float g) {
-    float x = fminf(fabsf(g) * 0.70710678f, 4.3f);
-    float p = -5.95750535e-05f;
-    p = fmaf(p, x, 0.000253331062f);
-    p = fmaf(p, x, 0.00176583871f);
-    p = fmaf(p, x, -0.0206223261f);
-    p = fmaf(p, x, 0.103378408f);
-    p = fmaf(p, x, 0.636503041f);
-    p = fmaf(p, x, 1.12838686f);
-    float e = exp32_nonpos(-(p * x));
-    float erf_g = copysignf(1.0f - e, g);
-    return (0.5f * g) * (1.0f + erf_g);
-}
-
-int orc_gelu32(const float* g, long n, float* out) {
-    if (!g || !out || n <= 0) return ORC_BAD_ARG;
-    for (long i = 0; i < n; ++i) out[i] = gelu32(g[i]);
-    return ORC_OK;
-}
+static double gelu64(double g) { return 0.5 * g * (1.0 + erf(g / sqrt(2.0))); }
 
 /* GEGLU projection with 8-bit activations in and out.  wcodes [2H,K]; codes_out [R,H] unsigned codes of the
- * gated product under the given static output parameters; h16_out nullable [R,H]: the same product rounded to fp16. */
+ * gated product under the given static output parameters; h16_out nullable [R,H]: the same product rounded to fp16;
+ * u_out nullable [R,H]: h / s_o before the rounding; lin_out nullable [R,2H]: the projection before the gate. */
 int orc_linear_a8_geglu(const uint16_t* x, long M, int K, long ldx, const uint8_t* wcodes, int H, int w_signed,
                         const float* w_scale, const int32_t* w_zp, int dynamic, float* act_scale, int32_t* act_zp,
                         const uint16_t* bias, float out_scale, int32_t out_zp, uint8_t* codes_out, uint16_t* h16_out,
-                        const int64_t* rows, long nrows) {
+                        double* u_out, double* lin_out, const int64_t* rows, long nrows) {
     if (!x || !wcodes || !w_scale || !w_zp || !act_scale || !act_zp || !codes_out || M <= 0 || K <= 0 || H <= 0 ||
         ldx < K || !(out_scale > 0.0f) || out_zp < 0 || out_zp > 255)
         return ORC_BAD_ARG;
@@ -526,15 +496,13 @@ int orc_linear_a8_geglu(const uint16_t* x, long M, int K, long ldx, const uint8_
     int32_t zx = *act_zp;
     if (!(sx > 0.0f) || zx < 0 || zx > 255) return ORC_BAD_ARG;
     float inv = 1.0f / sx;
-    float inv_o = 1.0f / out_scale;
-    float zf_o = (float)out_zp;
     int N = 2 * H;
     int overflow = 0;
 #pragma omp parallel for schedule(static) reduction(| : overflow)
     for (long r = 0; r < R; ++r) {
         long m = rows ? rows[r] : r;
         int* xd = (int*)malloc((size_t)K * sizeof(int));
-        float* lin = (float*)malloc((size_t)N * sizeof(float));
+        double* lin = (double*)malloc((size_t)N * sizeof(double));
         for (int k = 0; k < K; ++k) xd[k] = asym_code((float)half_to_double(x[m * ldx + k]), inv, zx, 255) - zx;
         for (int n = 0; n < N; ++n) {
             int64_t acc = 0;
@@ -543,16 +511,17 @@ int orc_linear_a8_geglu(const uint16_t* x, long M, int K, long ldx, const uint8_
                 acc += (int64_t)xd[k] * (q - w_zp[n]);
             }
             if (acc > INT32_MAX || acc < INT32_MIN) overflow |= 1;
-            float mul = sx * w_scale[n];
-            float add = bias ? (float)half_to_double(bias[n]) : 0.0f;
-            lin[n] = fmaf((float)(int32_t)acc, mul, add);
+            lin[n] = (double)acc * ((double)sx * (double)w_scale[n]) + (bias ? half_to_double(bias[n]) : 0.0);
+            if (lin_out) lin_out[r * (long)N + n] = lin[n];
         }
         for (int j = 0; j < H; ++j) {
-            float h = lin[j] * gelu32(lin[H + j]);
-            float t = rintf(h * inv_o) + zf_o;
-            t = t < 0.0f ? 0.0f : (t > 255.0f ? 255.0f : t);
+            double h = lin[j] * gelu64(lin[H + j]);
+            double u = h / (double)out_scale;
+            double t = rint(u) + (double)out_zp; /* round-half-to-even (the default rounding mode) */
+            t = t < 0.0 ? 0.0 : (t > 255.0 ? 255.0 : t);
             codes_out[r * (long)H + j] = (uint8_t)(int)t;
-            if (h16_out) h16_out[r * (long)H + j] = double_to_half((double)h);
+            if (h16_out) h16_out[r * (long)H + j] = double_to_half(h);
+            if (u_out) u_out[r * (long)H + j] = u;
         }
         free(xd);
         free(lin);
@@ -721,7 +690,7 @@ int orc_linear_w_only_geglu(const uint16_t* x, long M, int K, long ldx, const ui
         }
         for (int j = 0; j < H; ++j) {
             double g = lin[H + j];
-            h16[r * (long)H + j] = out16(lin[j] * (0.5 * g * (1.0 + erf(g / sqrt(2.0)))), dtype);
+            h16[r * (long)H + j] = out16(lin[j] * gelu64(g), dtype);
         }
         free(lin);
     }

@@ -496,16 +496,26 @@ def test_generators_are_deterministic_and_have_the_stated_moments():
 
 # ----------------------------------------------------------------------------------------------- fused feed-forward pair
 
-def test_gelu32_against_the_error_function(orc):
-    import math
-    g = np.concatenate([np.linspace(-9, 9, 40001), [0.0, -0.0, 1e-8, -1e-8, 50.0, -50.0]]).astype(np.float32)
-    out = orc.gelu32(g).astype(np.float64)
-    ref = np.array([0.5 * float(v) * (1.0 + math.erf(float(v) / math.sqrt(2.0))) for v in g])
-    assert np.abs(out - ref).max() < 1e-6          # the rational approximation is good to 1.5e-7 in erf
-    assert (out[g == 0] == 0).all() and orc.gelu32(np.float32([50.0]))[0] == 50.0
-    assert orc.gelu32(np.float32([-50.0]))[0] == 0.0
-    pos = np.sort(g[g > 0.1])
-    assert (np.diff(orc.gelu32(pos)) >= 0).all()   # increasing right of its minimum
+def test_geglu_gate_function_through_the_layer_closed_forms(orc):
+    """With zero weights lin = bias, so the layer exposes its gate function: gelu(0) = 0, gelu(g) - gelu(-g) = g,
+    gelu(g) -> g for large g and -> 0 for large -g, and tabulated values of the normal distribution
+    (gelu(g) = g Phi(g): Phi(1) = 0.8413447461, Phi(2) = 0.9772498681, Phi(0.5) = 0.6914624613)."""
+    gates = np.array([0.0, 1.0, -1.0, 2.0, -2.0, 0.5, -0.5, 12.0, -12.0, 3.0, -3.0, 0.25], np.float16)
+    H, K = len(gates), 64
+    codes = np.zeros((2 * H, K), np.uint8)
+    s, z = np.ones(2 * H, np.float32), np.zeros(2 * H, np.int32)
+    bias = np.concatenate([np.ones(H, np.float16), gates])          # value 1 | gate g
+    x = np.ones((1, K), np.float16)
+    q, h16, _, u, lin = orc.linear_a8_geglu(x, codes, s, z, (np.float32(1.0), 0), act=(np.float32(1.0), 0), bias=bias,
+                                            want_pre=True)
+    gelu = dict(zip(gates.astype(np.float64).tolist(), u[0].tolist()))      # s_o = 1, value = 1: u is gelu(gate)
+    assert np.array_equal(lin[0, :H], np.ones(H)) and np.array_equal(lin[0, H:], gates.astype(np.float64))
+    assert gelu[0.0] == 0.0
+    for g in (1.0, 2.0, 0.5, 3.0, 12.0):
+        assert abs(gelu[g] - gelu[-g] - g) < 1e-15 * max(1.0, g)
+    assert abs(gelu[12.0] - 12.0) < 1e-12 and abs(gelu[-12.0]) < 1e-12
+    for g, phi in ((1.0, 0.8413447461), (2.0, 0.9772498681), (0.5, 0.6914624613)):
+        assert abs(gelu[g] - g * phi) < 1e-9 * 4
 
 
 def test_a8_from_codes_is_the_a8_linear_after_its_quantiser(orc):
@@ -535,25 +545,49 @@ def test_geglu_order_bias_and_output_quantiser_by_hand(orc):
 
 
 @pytest.mark.parametrize("bits,symmetric", [(4, False), (8, True)])
-def test_geglu_requant_against_float64_rederivation(orc, bits, symmetric):
+def test_geglu_requant_from_the_pinned_integer_accumulators(orc, bits, symmetric):
+    """From the pinned A8 linear's exact accumulators: value half times the Gaussian gate of the gate half (math.erf),
+    then the affine output quantiser with round-half-to-even.  A swapped half, a missing 0.5, the gate applied to the
+    value, a zero point added before the division or half-away rounding would each move most codes."""
     import math
     M, K, H = 21, 128, 40
     x, w, b, c, s, z = _random_quantised_layer(orc, 72 + bits, M, K, 2 * H, bits, symmetric)
     out_act = (np.float32(0.004), 30)
-    q, h16, act = orc.linear_a8_geglu(x, c, s, z, out_act, w_signed=symmetric, bias=b)
+    q, h16, act, u, lin = orc.linear_a8_geglu(x, c, s, z, out_act, w_signed=symmetric, bias=b, want_pre=True)
     _, acc, act2 = orc.linear_a8(x, c, s, z, w_signed=symmetric, bias=b)
     assert act == act2
-    lin = acc.astype(np.float64) * (np.float64(act[0]) * s.astype(np.float64))[None, :] + b.astype(np.float64)[None, :]
+    lin_ref = acc.astype(np.float64) * (np.float64(act[0]) * s.astype(np.float64))[None, :] + b.astype(np.float64)[None, :]
+    assert np.allclose(lin, lin_ref, rtol=1e-14, atol=0)
     erf = np.vectorize(math.erf)
-    h = lin[:, :H] * 0.5 * lin[:, H:] * (1.0 + erf(lin[:, H:] / math.sqrt(2.0)))
-    want = np.clip(np.rint(h / np.float64(out_act[0])) + out_act[1], 0, 255)
-    d = q.astype(np.int64) - want.astype(np.int64)
-    assert np.abs(d).max() <= 1 and (d != 0).mean() < 0.02     # fp32 versus fp64 only moves borderline roundings
+    h = lin_ref[:, :H] * 0.5 * lin_ref[:, H:] * (1.0 + erf(lin_ref[:, H:] / math.sqrt(2.0)))
+    assert np.allclose(u, h / np.float64(out_act[0]), rtol=1e-12, atol=1e-300)
+    want = np.clip(np.rint(h / np.float64(out_act[0])) + out_act[1], 0, 255).astype(np.int64)
+    far = np.abs(np.abs(u - np.floor(u)) - 0.5) > 1e-9            # (not within rounding noise of a tie)
+    assert far.mean() > 0.999 and np.array_equal(q.astype(np.int64)[far], want[far])
     assert len(np.unique(q)) > 20                               # the codes are spread, not saturated
-    assert np.allclose(h16.view(np.float16).astype(np.float64), h, rtol=2e-3, atol=2e-4)
+    assert np.array_equal(h16.view(np.float16), h.astype(np.float16)) or \
+        np.abs(h16.view(np.float16).astype(np.float64) - h).max() <= np.abs(h).max() * 2.0 ** -10
+    swapped = lin_ref[:, H:] * 0.5 * lin_ref[:, :H] * (1.0 + erf(lin_ref[:, :H] / math.sqrt(2.0)))
+    assert np.abs(h - swapped).max() > 0.05                     # value and gate are not interchangeable here
     rows = [0, 5, 20]
     q2, _, _ = orc.linear_a8_geglu(x, c, s, z, out_act, w_signed=symmetric, bias=b, rows=rows, act=act)
     assert np.array_equal(q2, q[rows])
+
+
+def test_geglu_output_quantiser_rounds_half_to_even_and_saturates(orc):
+    """Zero weights leave lin = bias; gate 12 (gelu(12) = 12 exactly in fp64) and s_o = 3 put u = value * 4 on exact
+    ties: 0.5 -> 0, 1.5 -> 2, 2.5 -> 2, -0.5 -> -0 (half-away would give 1, 2, 3, -1); +-100 saturate."""
+    vals = np.array([0.125, 0.375, 0.625, -0.125, 100.0, -100.0], np.float16)     
+    H, K = len(vals), 64
+    codes = np.zeros((2 * H, K), np.uint8)
+    s, z = np.ones(2 * H, np.float32), np.zeros(2 * H, np.int32)
+    bias = np.concatenate([vals, np.full(H, 12.0, np.float16)])
+    x = np.ones((1, K), np.float16)
+    q, _, _, u, _ = orc.linear_a8_geglu(x, codes, s, z, (np.float32(3.0), 7), act=(np.float32(1.0), 0), bias=bias,
+                                        want_pre=True)
+    assert np.array_equal(u[0, :4], [0.5, 1.5, 2.5, -0.5])       # exact ties
+    assert q[0, :4].tolist() == [7 + 0, 7 + 2, 7 + 2, 7 - 0]
+    assert q[0, 4] == 255 and q[0, 5] == 0                        # saturation at both ends
 
 
 # ----------------------------------------------------------------------------------------------- 3x3 convolution
