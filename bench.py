@@ -50,13 +50,13 @@ def build_workload(mq, torch, si, seed=0):
             bos[ch] = torch.randn(16, generator=gen, device=dev) * 60.0
             x[:, 0, :] = bos  # the BOS feature does not depend on the prompt
             x = x.to(torch.float16)
-            ws_bytes = max(ws_bytes, mq.bos_aware_kv_proj_workspace_bytes(L.B, L.T, L.K))
+            ws_bytes = max(ws_bytes, mq.bos_aware_kv_proj_workspace_bytes(L.B, L.T, L.K) + mq.split_workspace_bytes(L.M, L.N, L.K))
             wf16 = w
         else:
             x = torch.randn(L.M, L.K, generator=gen, device=dev)
             outl = torch.rand(L.M, L.K, generator=gen, device=dev) < 0.01
             x = torch.where(outl, x * 10.0, x).to(torch.float16)
-            ws_bytes = max(ws_bytes, mq.qlinear_a8_workspace_bytes(L.M, L.K))
+            ws_bytes = max(ws_bytes, mq.qlinear_a8_workspace_bytes(L.M, L.K) + mq.split_workspace_bytes(L.M, L.N, L.K))
             wf16 = None
             del outl
         y = torch.empty(L.M, L.N, dtype=torch.float16, device=dev)
@@ -74,7 +74,7 @@ def plan_step(mq, work, ws):
     # pass 1: weight-only at the mixed per-layer bit-widths
     for it in work:
         L = it["L"]
-        calls.append(mq.plan_qlinear_w_only(it["x"].view(L.M, L.K), it["w_mixed"], it["bias"], it["y"]))
+        calls.append(mq.plan_qlinear_w_only(it["x"].view(L.M, L.K), it["w_mixed"], it["bias"], it["y"], ws=ws))
     # pass 2: W4A8, dynamic activation quantisation; K/V projections BOS-aware
     for it in work:
         L = it["L"]

@@ -106,7 +106,8 @@ def main():
                     x[:, 0, :16] *= 60.0
                     x = x.half()
                     y = torch.empty(B, T, N, dtype=torch.float16, device=dev)
-                    ws = ws if ws is not None else torch.empty(mq.bos_aware_kv_proj_workspace_bytes(B, T, K),
+                    ws = ws if ws is not None else torch.empty(mq.bos_aware_kv_proj_workspace_bytes(B, T, K) +
+                                                                mq.split_workspace_bytes(M, N, K),
                                                                 dtype=torch.uint8, device=dev)
                     sets.append(mq.plan_bos_aware_kv_proj(x, pw, y, ws, w_f16=w, bias=bias))
                     continue
@@ -114,9 +115,12 @@ def main():
                 x = torch.randn(M, K, generator=gen, device=dev).half()
                 y = torch.empty(M, N, dtype=torch.float16, device=dev)
                 if kind == "w":
-                    sets.append(mq.plan_qlinear_w_only(x, pw, bias, y))
+                    need = mq.split_workspace_bytes(M, N, K)
+                    ws = ws if ws is not None or not need else torch.empty(need, dtype=torch.uint8, device=dev)
+                    sets.append(mq.plan_qlinear_w_only(x, pw, bias, y, ws=ws))
                 else:
-                    ws = ws if ws is not None else torch.empty(mq.qlinear_a8_workspace_bytes(M, K), dtype=torch.uint8,
+                    ws = ws if ws is not None else torch.empty(mq.qlinear_a8_workspace_bytes(M, K) +
+                                                                mq.split_workspace_bytes(M, N, K), dtype=torch.uint8,
                                                                 device=dev)
                     act = None
                     if mode[0] == "s":

@@ -8,7 +8,10 @@
  *   - Return value: MQ_OK (0) or a negative MQ_ERR_* code.  Nothing is printed, nothing aborts.
  *   - Every pointer is a DEVICE pointer unless its name ends in _host.  The caller owns every buffer;
  *     the library allocates no device memory.  Scratch memory is a caller-provided workspace whose
- *     size comes from the matching *_workspace_bytes() query.
+ *     size comes from the matching *_workspace_bytes() query (256-byte aligned, contents on entry
+ *     irrelevant, contents on return unspecified).  A workspace is in use from the call until the
+ *     work the call enqueued has finished: calls on ONE stream may share a workspace, calls that
+ *     may run at the same time on different streams need a workspace each.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls enqueue work on
  *     that stream and return without synchronising.  Arguments are validated on the host before any
  *     launch; a call that returns an error has launched nothing.
@@ -58,12 +61,17 @@ void mq_tune_force_tile(int tile);
 
 /* Tuning and test hook: split of a GEMM's reduction over several workgroups per output tile (0: automatic, for
  * problems with few tiles and a long reduction; 1: never; n > 1: n parts wherever the reduction has that many
- * pipeline stages).  The partial sums pass through 32 MB of device memory that the library owns (a ring, one
- * stretch per launch).  Launches on one stream never share live scratch; launches running at the same time on
- * different streams are safe while their combined need fits the ring.  A split result is deterministic (the parts
- * are added in a fixed order) but may differ from the unsplit one in the last bit of a 16-bit output.
+ * pipeline stages).  The partial sums pass through the caller's workspace (mq_split_workspace_bytes).  In the
+ * automatic mode a call whose workspace is absent or too small splits into fewer parts or not at all; with a forced
+ * part count such a call returns MQ_ERR_WORKSPACE_TOO_SMALL.  A split result is deterministic (the parts are added
+ * in a fixed order) but may differ from the unsplit one in the last bit of a 16-bit output.
  * Process-wide, not thread safe. */
 void mq_tune_force_splits(int parts);
+
+/* Workspace that lets the weight-only and 8-bit-activation linears split the reduction of an [M,K] x [N,K] problem
+ * over several workgroups per output tile (an upper bound over the tile choices; 0 for shapes that are never split:
+ * more than 64 tiles of 128 x 128, or K < 1024).  It depends on the current mq_tune_force_splits setting. */
+size_t mq_split_workspace_bytes(int M, int N, int K);
 
 /* Tuning and test hook: height, in row blocks, of the bands in which a GEMM's workgroups walk the output tiles
  * (0: automatic; 1: row block by row block; n: n row blocks side by side, column by column).  It decides which
@@ -154,8 +162,9 @@ int mq_unpack_weights(const void* packed, int N, int K, int bits, int layout, ui
  *     Y[m,n] = round16( sum_k X[m,k] * scale[n] * (code[n,k] - zp[n]) + bias[n] ),  fp32 accumulation.
  *   x      [M,K] row stride ldx, 16-byte aligned, ldx % 8 == 0.     y [M,N] row stride ldy, 16-byte aligned, ldy % 8 == 0.
  *   packed MQ_LAYOUT_KERNEL, unsigned codes.   bias nullable [N] (same 16-bit dtype as x and y).
- *   K % 64 == 0, N % 8 == 0, M*ldx*2 < 2^31 bytes, (N+31)*K < 2^31 elements and, at bits = 16, < 2^30.  No workspace is
- *   needed.
+ *   K % 64 == 0, N % 8 == 0, M*ldx*2 < 2^31 bytes, (N+31)*K < 2^31 elements and, at bits = 16, < 2^30.
+ *   ws, ws_bytes  optional workspace (ws may be NULL) of mq_split_workspace_bytes(M, N, K) bytes: with it, a problem of
+ *   few output tiles and a long reduction (a handful of rows against K >= 1024) is spread over more workgroups.
  *   bits = 16: the layer is kept at 16 bits; packed holds the weights themselves (same dtype as x) in
  *   MQ_LAYOUT_KERNEL, w_scale and w_zp are ignored (may be null):  Y = round16( sum_k X[m,k] * W[n,k] + bias[n] ).
  *   residual nullable [M,N] of the same 16-bit dtype, row stride ldr (ldr % 4 == 0, 8-byte aligned): added in fp32
@@ -165,9 +174,11 @@ int mq_unpack_weights(const void* packed, int N, int K, int bits, int layout, ui
  *   output.  The same operand, with the same meaning, exists on the entry points below that take `residual`. */
 int mq_qlinear_w_only(const void* x, int M, int K, int ldx, const void* packed, int N, int bits, int layout,
                       const float* w_scale, const int32_t* w_zp, const void* bias, void* y, int ldy, int dtype,
-                      const void* residual, int ldr, void* stream);
+                      const void* residual, int ldr, void* ws, size_t ws_bytes, void* stream);
 
-/* Workspace for the 8-bit-activation entry points below (M rows of K activations). */
+/* Workspace for the 8-bit-activation entry points below (M rows of K activations): the int8 copy of the activations,
+ * their row sums, the min/max partials and the activation parameters.  A workspace larger than this is welcome: what
+ * lies beyond serves the split of the reduction (add mq_split_workspace_bytes(M, N, K)). */
 size_t mq_qlinear_a8_workspace_bytes(int M, int K);
 
 /* W8A8 linear (paper Sec. 4.3 / App. C item 4: integer GEMM behind an FP16->INT8 conversion):

@@ -23,7 +23,7 @@ _ERRORS = {
 
 EXPORTS = ("mq_version", "mq_last_hip_error", "mq_tune_force_tile", "mq_tune_force_splits", "mq_tune_force_band", "mq_prof_enable", "mq_prof_num_slots", "mq_prof_read",
            "mq_prof_reset", "mq_prof_phase_buffer", "mq_prof_filter", "mq_prof_bracket_overhead_us", "mq_prof_copy", "mq_quantize_weights", "mq_packed_bytes", "mq_pack_weights",
-           "mq_unpack_weights", "mq_qlinear_w_only", "mq_qlinear_a8_workspace_bytes", "mq_qlinear_w8a8",
+           "mq_unpack_weights", "mq_split_workspace_bytes", "mq_qlinear_w_only", "mq_qlinear_a8_workspace_bytes", "mq_qlinear_w8a8",
            "mq_qlinear_w4a8", "mq_qlinear_w2a8", "mq_a8_row_bytes", "mq_qlinear_a8_geglu", "mq_qlinear_w_only_geglu", "mq_qlinear_a8_codes", "mq_conv3x3_w_only",
            "mq_conv_tap_sums", "mq_conv3x3_a8_workspace_bytes", "mq_conv3x3_a8",
            "mq_bos_aware_kv_proj_workspace_bytes", "mq_bos_aware_kv_proj", "mq_alloc_solve", "mq_alloc_split_budget",
@@ -50,7 +50,7 @@ def load():
         if not os.path.exists(_LIB_PATH):
             raise RuntimeError(f"{_LIB_PATH} is missing: run `python -c 'import __graft_entry__ as g; g.build()'`")
         _lib = C.CDLL(_LIB_PATH)
-        for name in ("mq_a8_row_bytes", "mq_conv3x3_a8_workspace_bytes", "mq_packed_bytes", "mq_qlinear_a8_workspace_bytes", "mq_bos_aware_kv_proj_workspace_bytes"):
+        for name in ("mq_a8_row_bytes", "mq_split_workspace_bytes", "mq_conv3x3_a8_workspace_bytes", "mq_packed_bytes", "mq_qlinear_a8_workspace_bytes", "mq_bos_aware_kv_proj_workspace_bytes"):
             getattr(_lib, name).restype = C.c_size_t
         _lib.mq_prof_bracket_overhead_us.restype = C.c_double
     return _lib
@@ -216,17 +216,30 @@ def _res(residual, M, N, dtype):
     return _ptr(residual), residual.stride(0)
 
 
+def split_workspace_bytes(M: int, N: int, K: int) -> int:
+    return int(load().mq_split_workspace_bytes(M, N, K))
+
+
+def _ws_args(ws: Optional[torch.Tensor]):
+    return (C.c_void_p(0), C.c_size_t(0)) if ws is None else (_ptr(ws), C.c_size_t(ws.numel() * ws.element_size()))
+
+
 def qlinear_w_only(x: torch.Tensor, w: PackedWeight, bias: Optional[torch.Tensor] = None,
-                   out: Optional[torch.Tensor] = None, residual: Optional[torch.Tensor] = None) -> torch.Tensor:
-    """Y = X . dequant(W)^T + bias (+ residual) with 16-bit floating-point compute (weight-only quantisation)."""
+                   out: Optional[torch.Tensor] = None, residual: Optional[torch.Tensor] = None,
+                   ws: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Y = X . dequant(W)^T + bias (+ residual) with 16-bit floating-point compute (weight-only quantisation).
+    ws: optional uint8 workspace of split_workspace_bytes(M, N, K) bytes; allocated here when the shape can use one."""
     assert x.is_cuda and x.dim() == 2 and x.stride(1) == 1
     M, K = x.shape
     assert K == w.K
     y = out if out is not None else torch.empty((M, w.N), dtype=x.dtype, device=x.device)
     rp, ldr = _res(residual, M, w.N, x.dtype)
+    if ws is None:
+        need = split_workspace_bytes(M, w.N, K)
+        ws = torch.empty(need, dtype=torch.uint8, device=x.device) if need else None
     _check(load().mq_qlinear_w_only(_ptr(x), M, K, x.stride(0), _ptr(w.packed), w.N, w.bits, w.layout, _ptr(w.scale),
-                                    _ptr(w.zp), _ptr(bias), _ptr(y), y.stride(0), _dtype_code(x), rp, ldr, _stream()),
-           "mq_qlinear_w_only")
+                                    _ptr(w.zp), _ptr(bias), _ptr(y), y.stride(0), _dtype_code(x), rp, ldr, *_ws_args(ws),
+                                    _stream()), "mq_qlinear_w_only")
     return y
 
 
@@ -246,7 +259,7 @@ def _qlinear_a8(fn_name, x, w: PackedWeight, act, bias, out, ws, want_acc, want_
     assert K == w.K
     dev = x.device
     y = out if out is not None else torch.empty((M, w.N), dtype=torch.float16, device=dev)
-    ws = _workspace(qlinear_a8_workspace_bytes(M, K), dev, ws)
+    ws = _workspace(qlinear_a8_workspace_bytes(M, K) + split_workspace_bytes(M, w.N, K), dev, ws)
     acc = torch.empty((M, w.N), dtype=torch.int32, device=dev) if want_acc else None
     s_out = torch.empty(1, dtype=torch.float32, device=dev) if want_act else None
     z_out = torch.empty(1, dtype=torch.int32, device=dev) if want_act else None
@@ -432,7 +445,7 @@ def bos_aware_kv_proj(ctx: torch.Tensor, w: PackedWeight, w_f16: Optional[torch.
     assert K == w.K
     dev = ctx.device
     y = out if out is not None else torch.empty((B, T, w.N), dtype=torch.float16, device=dev)
-    ws = _workspace(bos_aware_kv_proj_workspace_bytes(B, T, K), dev, ws)
+    ws = _workspace(bos_aware_kv_proj_workspace_bytes(B, T, K) + split_workspace_bytes(B * T, w.N, K), dev, ws)
     s_out = torch.empty(1, dtype=torch.float32, device=dev) if want_act else None
     z_out = torch.empty(1, dtype=torch.int32, device=dev) if want_act else None
     a_s, a_z = (None, None) if act is None else act
@@ -459,13 +472,14 @@ def _planned(fn, what, args, keep):
     return call
 
 
-def plan_qlinear_w_only(x, w: PackedWeight, bias, out, residual=None):
+def plan_qlinear_w_only(x, w: PackedWeight, bias, out, residual=None, ws=None):
+    """ws: optional workspace (see qlinear_w_only); without one the call never splits its reduction."""
     assert x.is_cuda and x.dim() == 2 and x.stride(1) == 1 and out.shape == (x.shape[0], w.N)
     M, K = x.shape
     rp, ldr = _res(residual, M, w.N, x.dtype)
     args = (_ptr(x), M, K, x.stride(0), _ptr(w.packed), w.N, w.bits, w.layout, _ptr(w.scale), _ptr(w.zp), _ptr(bias),
-            _ptr(out), out.stride(0), _dtype_code(x), rp, ldr, _stream())
-    return _planned(load().mq_qlinear_w_only, "mq_qlinear_w_only", args, (x, w, bias, out, residual))
+            _ptr(out), out.stride(0), _dtype_code(x), rp, ldr, *_ws_args(ws), _stream())
+    return _planned(load().mq_qlinear_w_only, "mq_qlinear_w_only", args, (x, w, bias, out, residual, ws))
 
 
 def plan_qlinear_a8(x, w: PackedWeight, bias, out, ws, act=None, residual=None):

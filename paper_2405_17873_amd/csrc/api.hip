@@ -38,6 +38,24 @@ struct A8Workspace {
     }
 };
 
+// Upper bound of what the split of an [M,K] x [N,K] GEMM's reduction over workgroups can use: arrival counters of the
+// smallest tile (64 x 64) plus `parts` partial accumulator sets over the output padded to the largest splitting tile
+// (128 x 128).  The automatic choice splits only where there are at most 64 tiles and at least 16 pipeline stages, into
+// at most min(16, stages / 4) parts; a forced part count (test hook) is taken as it is.
+size_t split_workspace_bytes(long M, long N, long K) {
+    if (M <= 0 || N <= 0 || K <= 0) return 0;
+    const long Mp = (M + 127) / 128 * 128, Np = (N + 127) / 128 * 128;
+    long parts = 0;
+    if (forced_splits() > 1) {
+        parts = forced_splits();
+    } else if (forced_splits() == 0 && (Mp / 128) * (Np / 128) <= 64 && K / 64 >= 16) {
+        parts = K / 64 / 4;
+        parts = parts > 16 ? 16 : parts;
+    }
+    if (parts <= 1) return 0;
+    return up256((size_t)(Mp / 64) * (Np / 64) * 4) + (size_t)parts * Mp * Np * 4 + 256;
+}
+
 static int check_linear_common(const void* x, int M, int K, int ldx, const void* packed, int N, int layout,
                                const float* w_scale, const int32_t* w_zp, const void* bias, const void* y, int ldy,
                                bool need_params = true) {
@@ -74,13 +92,17 @@ static int qlinear_a8(const void* x, int M, int K, int ldx, RowMap in_map, const
     if ((act_scale == nullptr) != (act_zp == nullptr)) return MQ_ERR_BAD_ARG;
     if (!aligned(w_colsum, 16) || !aligned(ws, 256) || (acc_debug && !aligned(acc_debug, 16))) return MQ_ERR_BAD_ARG;
     if ((long)255 * 255 * K >= (1L << 31)) return MQ_ERR_OVERFLOW_RISK;
-    if (ws_bytes < A8Workspace::bytes(M, K)) return MQ_ERR_WORKSPACE_TOO_SMALL;
+    const size_t base = A8Workspace::bytes(M, K);
+    if (ws_bytes < base) return MQ_ERR_WORKSPACE_TOO_SMALL;
+    // (a forced split that the rest of the workspace cannot hold must fail before anything is launched)
+    if (forced_splits() > 1 && ws_bytes - base < split_workspace_bytes(M, N, K)) return MQ_ERR_WORKSPACE_TOO_SMALL;
     A8Workspace w(ws, M, K);
     rc = launch_act_quant(x, M, K, ldx, in_map, act_scale, act_zp, w.a8, w.rowsum, w.params, w.partials,
                           act_scale_out, act_zp_out, bos, st);
     if (rc) return rc;
+    // what lies beyond the activation workspace serves the split of the reduction over workgroups
     return launch_gemm_a8(w.a8, w.rowsum, w.params, M, K, packed, N, w_bits, w_signed, w_scale, w_zp, w_colsum, bias,
-                          y, ldy, out_map, acc_debug, residual, ldr, st);
+                          y, ldy, out_map, acc_debug, residual, ldr, (uint8_t*)ws + base, ws_bytes - base, st);
 }
 }  // namespace mq
 
@@ -152,9 +174,11 @@ int mq_unpack_weights(const void* packed, int N, int K, int bits, int layout, ui
     return launch_unpack(packed, N, K, bits, layout, codes, (hipStream_t)stream);
 }
 
+size_t mq_split_workspace_bytes(int M, int N, int K) { return split_workspace_bytes(M, N, K); }
+
 int mq_qlinear_w_only(const void* x, int M, int K, int ldx, const void* packed, int N, int bits, int layout,
                       const float* w_scale, const int32_t* w_zp, const void* bias, void* y, int ldy, int dtype,
-                      const void* residual, int ldr, void* stream) {
+                      const void* residual, int ldr, void* ws, size_t ws_bytes, void* stream) {
     if (!bits_ok16(bits)) return MQ_ERR_UNSUPPORTED_BITS;
     if (dtype != MQ_F16 && dtype != MQ_BF16) return MQ_ERR_BAD_ARG;
     int rc = check_linear_common(x, M, K, ldx, packed, N, layout, w_scale, w_zp, bias, y, ldy, bits != 16);
@@ -163,8 +187,11 @@ int mq_qlinear_w_only(const void* x, int M, int K, int ldx, const void* packed, 
     // (lane offsets into the weights are 32-bit byte offsets: unquantised weights take two bytes per element)
     if (bits == 16 && (long)(N + 31) * K * 2 >= (1L << 31)) return MQ_ERR_BAD_SHAPE;
     if (bits == 16) w_scale = nullptr, w_zp = nullptr;  // 16-bit weights are used as they are
-    return launch_gemm_w_only(x, M, K, ldx, packed, N, bits, w_scale, w_zp, bias, y, ldy, dtype, residual, ldr,
-                              (hipStream_t)stream);
+    if (ws && !aligned(ws, 256)) return MQ_ERR_BAD_ARG;
+    if (!ws) ws_bytes = 0;
+    if (forced_splits() > 1 && ws_bytes < split_workspace_bytes(M, N, K)) return MQ_ERR_WORKSPACE_TOO_SMALL;
+    return launch_gemm_w_only(x, M, K, ldx, packed, N, bits, w_scale, w_zp, bias, y, ldy, dtype, residual, ldr, ws,
+                              ws_bytes, (hipStream_t)stream);
 }
 
 size_t mq_a8_row_bytes(int K) { return K > 0 ? ((size_t)K + 127) / 128 * 128 : 0; }

@@ -24,8 +24,8 @@
 //     16-byte row segments.
 //   * k-order inside a stage is permuted identically for both operands (a sum does not care), chosen so
 //     that every lane's global and LDS accesses are 16 bytes wide.
-//   * Few tiles and a long reduction: several workgroups per tile, partial sums through a scratch ring of the
-//     library, the last-arriving workgroup adds them in a fixed order (no waiting).
+//   * Few tiles and a long reduction: several workgroups per tile, partial sums through the caller's workspace,
+//     the last-arriving workgroup adds them in a fixed order (no waiting).
 //   * Optional residual operand (a skip connection, or the output of the other half of a split concatenated
 //     input, Sec. 4.1): a kernel variant (RES) loads it in the accumulator layout and adds it in fp32 before the
 //     one rounding; kernels without it contain none of this.
@@ -372,10 +372,13 @@ struct GemmArgs {
     RowMap out_map;
     int32_t* acc_debug;
     // split of the reduction over `splits` workgroups per tile (1 = none): partial accumulators in `partial`
-    // ([tile][split][BM * BN] 4-byte values, register order), one arrival counter per tile (zero between launches)
+    // ([tile][split][BM * BN] 4-byte values, register order), one arrival counter per tile (cleared before the launch)
     int splits;
     uint32_t* partial;
     uint32_t* counters;
+    // (host side only) the caller's workspace that partial sums and counters are carved from; may be null
+    void* split_ws;
+    size_t split_ws_bytes;
     // MODE 1 (gated feed-forward projection, 8-bit output): N = 2H weight rows; codes of the gated product go to
     // a8_out (row stride ld8 bytes, the int8 activation layout), optionally the product itself as fp16 to y
     const float* out_scale_p;
@@ -509,6 +512,7 @@ void gemm_kernel(const GemmArgs g) {
     // Rows past M get an offset past the end of the buffer and therefore read as zero.
     int a_voff[P::DMA_A];
     uint32_t a_lds[P::DMA_A];
+    int a_sub[KS == 2 ? P::DMA_A : 1];  // k-split tiles: which of the stage's two k steps the load belongs to
     int a_half[CONV ? P::DMA_A : 1];
     uint32_t a_taps[CONV ? P::DMA_A : 1];
     // convolution: which of the 9 filter taps (bit r * 3 + s) of output pixel m read inside the image
@@ -530,6 +534,7 @@ void gemm_kernel(const GemmArgs g) {
         const int row = row0 + (lane >> 3);
         const int piece = (lane & 7) ^ swz(row);
         a_voff[i] = m0 + row < g.M ? (int)((long)(m0 + row) * g.a_row_bytes + sub * 128 + piece * 16) : OOB;
+        if constexpr (KS == 2) a_sub[i] = sub;
         a_lds[i] = __builtin_amdgcn_readfirstlane((uint32_t)(sub * P::SUB_BYTES + row0 * 128));
         if constexpr (CONV) {
             // row = output pixel; the lane's 16 bytes of a stage lie in one 64-channel chunk (int8: piece / 4 says
@@ -551,6 +556,8 @@ void gemm_kernel(const GemmArgs g) {
     constexpr int VALID_LANES = BITS >= 8 ? 64 : 16 * BITS;  // lanes of a 16-byte-per-lane copy that hold tile data
     int b_voff[P::DMA_B];
     uint32_t b_lds[P::DMA_B];
+    constexpr bool B_TAIL = I8 || KS == 2;  // a stage may reach past the last 64-k weight tile of the reduction
+    int b_chunk[B_TAIL ? P::DMA_B : 1];     // the load's 64-k tile inside its stage
 #pragma unroll
     for (int i = 0; i < P::DMA_B; ++i) {
         const int j = i * NW + wv;
@@ -560,6 +567,7 @@ void gemm_kernel(const GemmArgs g) {
         const int gi = group_of(gt);
         const bool on = j < P::NBI && lane < VALID_LANES;
         b_voff[i] = on ? (gi * KC + sub * CH + cc) * TILE_B + piece * 1024 + lane * 16 : OOB;
+        if constexpr (B_TAIL) b_chunk[i] = sub * CH + cc;
         b_lds[i] = __builtin_amdgcn_readfirstlane(
             j < P::NBI ? (uint32_t)(sub * P::SUB_BYTES + P::A_BYTES + t * P::BSLOT + piece * 1024) : (uint32_t)0xFFFFFFFFu);
     }
@@ -631,10 +639,18 @@ void gemm_kernel(const GemmArgs g) {
     const int KT_ALL = (KSTEPS + KS - 1) / KS;    // pipeline stages of the whole reduction
     const int kt0 = splits > 1 ? sp * g.kt_q + (sp < g.kt_r ? sp : g.kt_r) : 0;
     const int KT = splits > 1 ? g.kt_q + (sp < g.kt_r ? 1 : 0) : KT_ALL;  // ... of this workgroup
+    // The k advance of a stage travels in the load's scalar offset, which the hardware leaves out of its range check
+    // (only the lane's own offset is compared with the extent of the buffer).  The last stage may hold a 64-k weight
+    // tile or (k-split tiles) a whole k step that does not exist: int8 stages are two weight tiles long and K / 64 may
+    // be odd, a k-split stage is two k steps long and their number may be odd.  Loads of such phantom pieces get the
+    // out-of-range lane offset, so nothing outside the operands is ever addressed.
     auto issue = [&](int stage, int buf) {
-        const int soff_a = __builtin_amdgcn_readfirstlane((kt0 + stage) * KS * 128);
-        const int soff_b = __builtin_amdgcn_readfirstlane((kt0 + stage) * KS * CH * TILE_B);
+        const int step0 = (kt0 + stage) * KS;  // first k step of the stage
+        const int soff_a = __builtin_amdgcn_readfirstlane(step0 * 128);
+        const int soff_b = __builtin_amdgcn_readfirstlane(step0 * CH * TILE_B);
         const uint32_t sb = lds_base + buf * STAGE_BYTES;
+        const bool tail_a = KS == 2 && step0 + 1 >= KSTEPS;
+        const bool tail_b = B_TAIL && (step0 + KS) * CH > KC;
         if constexpr (CONV) {
             // the stage's 64-channel chunks -> (filter tap, chunk inside the tap) -> byte offset from the output pixel
             int tap[CH], delta[CH];
@@ -653,15 +669,31 @@ void gemm_kernel(const GemmArgs g) {
                 const int voff = (a_taps[i] >> t) & 1u ? a_voff[i] + d : OOB;
                 dma_to_lds_b128(ra, __builtin_amdgcn_readfirstlane(sb + a_lds[i]), voff, 0);
             }
+        } else if (tail_a) {
+            if constexpr (KS == 2) {
+#pragma unroll
+                for (int i = 0; i < P::DMA_A; ++i)
+                    dma_to_lds_b128(ra, __builtin_amdgcn_readfirstlane(sb + a_lds[i]),
+                                    step0 + a_sub[i] < KSTEPS ? a_voff[i] : OOB, soff_a);
+            }
         } else {
 #pragma unroll
             for (int i = 0; i < P::DMA_A; ++i)
                 dma_to_lds_b128(ra, __builtin_amdgcn_readfirstlane(sb + a_lds[i]), a_voff[i], soff_a);
         }
+        if (tail_b) {
+            if constexpr (B_TAIL) {
 #pragma unroll
-        for (int i = 0; i < P::DMA_B; ++i)
-            dma_to_lds_b128(rb, __builtin_amdgcn_readfirstlane(b_lds[i] == 0xFFFFFFFFu ? lds_base + P::SINK : sb + b_lds[i]),
-                            b_voff[i], soff_b);
+                for (int i = 0; i < P::DMA_B; ++i)
+                    dma_to_lds_b128(rb, __builtin_amdgcn_readfirstlane(b_lds[i] == 0xFFFFFFFFu ? lds_base + P::SINK : sb + b_lds[i]),
+                                    step0 * CH + b_chunk[i] < KC ? b_voff[i] : OOB, soff_b);
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < P::DMA_B; ++i)
+                dma_to_lds_b128(rb, __builtin_amdgcn_readfirstlane(b_lds[i] == 0xFFFFFFFFu ? lds_base + P::SINK : sb + b_lds[i]),
+                                b_voff[i], soff_b);
+        }
     };
 
     // LDS read offsets of this lane: row l31 of the wave's first tile, one register per MFMA step
@@ -876,8 +908,9 @@ void gemm_kernel(const GemmArgs g) {
     // adds the partial sums of all parts, its own included, in part order (so the result does not depend on which
     // workgroup came last) and goes on to the epilogue; the others are done.  Nobody waits for anybody.
     // The partial sums are written and read with device-scope atomic accesses (write-through stores, loads that
-    // bypass the L2 of the reader's XCD), so no cache has to be flushed: the wait for the stores' completion before
-    // the ticket is all the ordering that is needed.
+    // bypass the L2 of the reader's XCD); every wave waits for its stores to complete, the workgroup meets at a
+    // barrier, and one thread draws the ticket with a device-scope acquire-release read-modify-write, which orders
+    // the stores of this workgroup before the ticket and the loads of the last workgroup after it.
     if (CAN_SPLIT && splits > 1) {
         using elem_t = typename std::conditional<I8, int, float>::type;
         const size_t tile_elems = (size_t)BM * BN;
@@ -897,10 +930,9 @@ void gemm_kernel(const GemmArgs g) {
         __syncthreads();
         uint32_t* ticket = (uint32_t*)(lds + P::SINK);  // the sink of padding loads is idle by now
         if (threadIdx.x == 0)
-            *ticket = __hip_atomic_fetch_add(g.counters + tile_id, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            *ticket = __hip_atomic_fetch_add(g.counters + tile_id, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
         __syncthreads();
-        if (*ticket != (uint32_t)(splits - 1)) return;
-        if (threadIdx.x == 0) g.counters[tile_id] = 0;  // ready for the next launch that is handed this counter
+        if (*ticket != (uint32_t)(splits - 1)) return;  // (the counters are cleared on the stream before every launch)
 #pragma unroll
         for (int tm = 0; tm < TM; ++tm)
 #pragma unroll
@@ -1187,57 +1219,25 @@ void set_phase_buffer(long long* p, long workgroups) {
 }
 void set_force_tile(int t) { g_force_tile = t; }
 
-// ---- reduction split over workgroups: scratch of the library --------------------------------------------------
+// ---- reduction split over workgroups ------------------------------------------------------------------------
 // Problems with few tiles and a long reduction (K/V projections, a handful of activation rows) are bound by memory
-// latency: the only remedy is to have more workgroups request the operands at once.  Their partial sums go through
-// a ring of device memory that belongs to the library, with one arrival counter per tile.  A launch is handed the
-// next stretch of both rings; counters are zero when handed out and the kernel leaves them zero.  Launches on one
-// stream run one after the other, so they never share live scratch; launches that run at the same time on several
-// streams are safe as long as what they need together fits the ring (a stretch is reused one full turn later).
-static constexpr size_t kSplitRingBytes = 32u << 20;
-static constexpr int kSplitCounters = 16384;
-static __device__ __attribute__((aligned(256))) uint32_t g_split_ring[kSplitRingBytes / 4];
-static __device__ __attribute__((aligned(256))) uint32_t g_split_counters[kSplitCounters];
+// latency: the only remedy is to have more workgroups request the operands at once.  Their partial sums and one
+// arrival counter per tile live in the CALLER's workspace: [counters: tiles x 4 bytes, rounded up to 256]
+// [partial sums: tiles x parts x BM x BN x 4 bytes].  The counters are cleared by a small kernel on the same stream
+// right before the GEMM (the workspace arrives with unknown contents); whoever owns the workspace owns the hazard,
+// as with any workspace: one stream at a time.
 static int g_force_splits = 0;  // 0: automatic, 1: never, n > 1: n parts wherever the reduction is long enough
 void set_force_splits(int n) { g_force_splits = n < 0 ? 0 : n; }
+int forced_splits() { return g_force_splits; }
 static int g_force_band = 0;  // 0: automatic, n >= 1: n row blocks per band of the workgroup -> tile map
 void set_force_band(int n) { g_force_band = n < 0 ? 0 : n; }
 
-namespace {
-struct SplitScratch {
-    uint32_t* ring = nullptr;
-    uint32_t* counters = nullptr;
-    size_t ring_cursor = 0;  // bytes
-    int counter_cursor = 0;
-};
-std::mutex g_split_mutex;
-SplitScratch g_split_dev[16];
-
-// Hands out `bytes` of the ring and `tiles` counters of the current device; false if the request cannot be served.
-bool take_split_scratch(size_t bytes, int tiles, uint32_t** partial, uint32_t** counters) {
-    int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 16) return false;
-    if (bytes > kSplitRingBytes / 2 || tiles > kSplitCounters / 2) return false;
-    std::lock_guard<std::mutex> lock(g_split_mutex);
-    SplitScratch& sc = g_split_dev[dev];
-    if (!sc.ring) {
-        void *r = nullptr, *c = nullptr;
-        if (hipGetSymbolAddress(&r, HIP_SYMBOL(g_split_ring)) != hipSuccess ||
-            hipGetSymbolAddress(&c, HIP_SYMBOL(g_split_counters)) != hipSuccess)
-            return false;
-        sc.ring = (uint32_t*)r;
-        sc.counters = (uint32_t*)c;
-    }
-    bytes = (bytes + 255) & ~(size_t)255;
-    if (sc.ring_cursor + bytes > kSplitRingBytes) sc.ring_cursor = 0;
-    if (sc.counter_cursor + tiles > kSplitCounters) sc.counter_cursor = 0;
-    *partial = sc.ring + sc.ring_cursor / 4;
-    *counters = sc.counters + sc.counter_cursor;
-    sc.ring_cursor += bytes;
-    sc.counter_cursor += tiles;
-    return true;
+__global__ void split_clear_kernel(uint32_t* counters, int n) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) counters[i] = 0;
 }
-}  // namespace
+
+static inline size_t split_counter_bytes(long tiles) { return ((size_t)tiles * 4 + 255) / 256 * 256; }
 
 // Measured on the SDXL shapes: the large tile wins once it yields two or more workgroups per compute unit; the
 // k-split variants only pay where tiles are few and k is long (FF-out at the 640 level, the K/V projections).
@@ -1320,8 +1320,18 @@ static int run_gemm_r(GemmArgs& g, int tile_index, hipStream_t st) {
         if (splits > 16) splits = 16;
     }
     g.splits = 1;
-    if (MODE == 0 && TM * TN <= 4 && splits > 1 && take_split_scratch((size_t)tiles * splits * P::BM * P::BN * 4, (int)tiles, &g.partial, &g.counters))
-        g.splits = splits;
+    if (MODE == 0 && TM * TN <= 4 && splits > 1) {
+        // as many parts as the caller's workspace holds (forced part counts are for tests: they must fit)
+        const size_t cbytes = split_counter_bytes(tiles), part_bytes = (size_t)tiles * P::BM * P::BN * 4;
+        const size_t room = g.split_ws && g.split_ws_bytes > cbytes ? (g.split_ws_bytes - cbytes) / part_bytes : 0;
+        if (g_force_splits > 1 && room < (size_t)splits) return MQ_ERR_WORKSPACE_TOO_SMALL;
+        if (room < (size_t)splits) splits = (int)room;
+        if (splits > 1) {
+            g.splits = splits;
+            g.counters = (uint32_t*)g.split_ws;
+            g.partial = (uint32_t*)((uint8_t*)g.split_ws + cbytes);
+        }
+    }
     g.fd_band_tiles = FastDiv::make((uint32_t)(g.band_rows * g.tiles_n));
     g.fd_band_rows = FastDiv::make((uint32_t)g.band_rows);
     g.fd_last_rows = FastDiv::make((uint32_t)(g.tiles_m % g.band_rows ? g.tiles_m % g.band_rows : g.band_rows));
@@ -1359,6 +1369,10 @@ static int run_gemm_r(GemmArgs& g, int tile_index, hipStream_t st) {
     const double ybytes = MODE == 1 ? 1.0 * g.M * g.ld8 + (g.y ? 1.0 * g.M * g.N : 0.0) : 2.0 * g.M * g.N;
     ProfScope prof(st, slot, 2.0 * g.M * g.N * g.K,
                    abytes + (double)g.N * g.K * BITS / 8 + (I8 ? 14.0 : 10.0) * g.N + ybytes);
+    if (g.splits > 1) {
+        hipLaunchKernelGGL(split_clear_kernel, dim3((unsigned)((tiles + 255) / 256)), dim3(256), 0, st, g.counters, (int)tiles);
+        MQ_HIP_CHECK_LAUNCH();
+    }
     hipLaunchKernelGGL(kern, dim3(g.tiles_m * g.tiles_n * g.splits), dim3(P::NT), P::LDS_BYTES, st, g);
     MQ_HIP_CHECK_LAUNCH();
     return MQ_OK;
@@ -1404,8 +1418,9 @@ static int dispatch_gemm_bf16(GemmArgs& g, hipStream_t st) {
 
 int launch_gemm_w_only(const void* x, int M, int K, int ldx, const void* packed, int N, int bits,
                        const float* w_scale, const int32_t* w_zp, const void* bias, void* y, int ldy, int dtype,
-                       const void* res, int ldr, hipStream_t st) {
+                       const void* res, int ldr, void* split_ws, size_t split_ws_bytes, hipStream_t st) {
     GemmArgs g{};
+    g.split_ws = split_ws; g.split_ws_bytes = split_ws_bytes;
     g.a = x;
     g.a_row_bytes = (long)ldx * 2;
     g.a_bytes = (uint32_t)(((long)(M - 1) * ldx + K) * 2);
@@ -1439,9 +1454,10 @@ int launch_gemm_w_only(const void* x, int M, int K, int ldx, const void* packed,
 int launch_gemm_a8(const int8_t* a8, const int32_t* rowsum, const ActParams* params, int M, int K,
                    const void* packed, int N, int w_bits, int w_signed, const float* w_scale, const int32_t* w_zp,
                    const int32_t* w_colsum, const void* bias, void* y, int ldy, RowMap out_map, int32_t* acc_debug,
-                   const void* res, int ldr, hipStream_t st) {
+                   const void* res, int ldr, void* split_ws, size_t split_ws_bytes, hipStream_t st) {
     const int Kp = (K + 127) / 128 * 128;
     GemmArgs g{};
+    g.split_ws = split_ws; g.split_ws_bytes = split_ws_bytes;
     g.a = a8;
     g.a_row_bytes = Kp;
     g.a_bytes = (uint32_t)((long)M * Kp);

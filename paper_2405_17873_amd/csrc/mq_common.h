@@ -112,12 +112,12 @@ int act_quant_partial_slots();
 
 int launch_gemm_w_only(const void* x, int M, int K, int ldx, const void* packed, int N, int bits,
                        const float* w_scale, const int32_t* w_zp, const void* bias, void* y, int ldy, int dtype,
-                       const void* res, int ldr, hipStream_t st);
+                       const void* res, int ldr, void* split_ws, size_t split_ws_bytes, hipStream_t st);
 
 int launch_gemm_a8(const int8_t* a8, const int32_t* rowsum, const ActParams* params, int M, int K,
                    const void* packed, int N, int w_bits, int w_signed, const float* w_scale, const int32_t* w_zp,
                    const int32_t* w_colsum, const void* bias, void* y, int ldy, RowMap out_map, int32_t* acc_debug,
-                   const void* res, int ldr, hipStream_t st);
+                   const void* res, int ldr, void* split_ws, size_t split_ws_bytes, hipStream_t st);
 
 int launch_gemm_a8_geglu(const int8_t* a8, const int32_t* rowsum, const ActParams* params, int M, int K,
                          const void* packed, int H, int w_bits, int w_signed, const float* w_scale, const int32_t* w_zp,
@@ -142,6 +142,7 @@ int launch_tap_sums(const uint8_t* codes, int N, int Cin, int bits, int codes_si
 
 void set_force_tile(int t);
 void set_force_splits(int n);
+int forced_splits();
 void set_force_band(int n);
 void set_phase_buffer(long long* p, long workgroups);
 

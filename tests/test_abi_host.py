@@ -46,6 +46,10 @@ def test_size_queries(lib):
     assert mq.packed_bytes(320, 320, 5, mq.LAYOUT_CANONICAL) == 0
     assert mq.qlinear_a8_workspace_bytes(4096, 1280) >= 4096 * 1280 + 4 * 4096
     assert mq.bos_aware_kv_proj_workspace_bytes(8, 77, 2048) >= 8 * 77 * 2048
+    # split of the reduction: shapes with many tiles or a short reduction never split
+    assert mq.split_workspace_bytes(4096, 1280, 1280) == 0 and mq.split_workspace_bytes(64, 1280, 640) == 0
+    assert mq.split_workspace_bytes(64, 1280, 5120) >= 16 * 128 * 1280 * 4
+    assert mq.split_workspace_bytes(308, 640, 2048) >= 8 * 384 * 640 * 4
 
 
 def test_error_codes_without_a_gpu(lib):
@@ -71,7 +75,7 @@ def test_error_codes_without_a_gpu(lib):
     # w_only
     args = lambda **o: [o.get("x", p), o.get("M", 8), o.get("K", 64), o.get("ldx", 64), p, o.get("N", 32),
                         o.get("bits", 4), o.get("layout", 1), p, p, null, p, o.get("ldy", 32), 0, o.get("res", null),
-                        o.get("ldr", 0), st]
+                        o.get("ldr", 0), o.get("ws", null), C.c_size_t(o.get("wsb", 0)), st]
     assert lib.mq_qlinear_w_only(*args(x=null)) == -1
     assert lib.mq_qlinear_w_only(*args(bits=5)) == -3
     assert lib.mq_qlinear_w_only(*args(K=96, ldx=96)) == -2
@@ -82,6 +86,16 @@ def test_error_codes_without_a_gpu(lib):
     assert lib.mq_qlinear_w_only(*args(res=p, ldr=16)) == -2              # residual rows shorter than N
     assert lib.mq_qlinear_w_only(*args(res=p, ldr=34)) == -2
     assert lib.mq_qlinear_w_only(*args(res=C.c_void_p(p.value + 4), ldr=32)) == -1
+    assert lib.mq_qlinear_w_only(*args(ws=C.c_void_p(p.value + 64), wsb=4096)) == -1   # workspace not 256-byte aligned
+    # a forced split of the reduction needs its workspace: absent or too small is an error, nothing is launched
+    lib.mq_tune_force_splits(4)
+    try:
+        need = lib.mq_split_workspace_bytes(8, 32, 2048)
+        assert need >= 4 * 128 * 128 * 4
+        assert lib.mq_qlinear_w_only(*args(K=2048, ldx=2048)) == -4
+        assert lib.mq_qlinear_w_only(*args(K=2048, ldx=2048, ws=p, wsb=need - 1)) == -4
+    finally:
+        lib.mq_tune_force_splits(0)
     # unquantised weights of 2 GiB and more: their byte offsets would not fit 32 bits
     assert lib.mq_qlinear_w_only(*args(M=1, K=40960, ldx=40960, N=32768, ldy=32768, bits=16)) == -2
     # a8

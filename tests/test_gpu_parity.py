@@ -43,6 +43,16 @@ def assert_close16(y, ref_bits, what=""):
     assert fro <= FRO_TOL and elt <= ELT_TOL, f"{what}: fro={fro:.3e} elt={elt:.3e}"
 
 
+def sample_rows(x, n=512, seed=0):
+    """A seeded sample of at least n distinct rows that always holds the first row, the last row and the rows with the
+    tensor's largest and smallest value (output rows are independent given the activation parameters)."""
+    M = x.shape[0]
+    rng = np.random.default_rng(seed)
+    fixed = [0, M - 1, int(np.argmax(x.max(1))), int(np.argmin(x.min(1)))]
+    rows = np.unique(np.concatenate([fixed, rng.choice(M, size=min(M, n), replace=False)]))
+    return rows.astype(np.int64)
+
+
 def make_weight(mq, orc, w, bits, symmetric=False):
     """Quantise + pack on the GPU, checking both against the oracle bit for bit; returns (PackedWeight, codes...)."""
     wd = dev(w)
@@ -205,9 +215,7 @@ def test_w_only_transformer_block_shapes_sampled_rows(mq, orc, M, K, N):
     x = si.activations_f16(0, f"c2/x{K}", M, K, outlier_prob=0.01)
     w = si.weights_f16(0, f"c2/w{N}x{K}", N, K)
     b = si.bias_f16(0, f"c2/b{N}", N)
-    rng = np.random.default_rng(M + K + N)
-    rows = np.unique(np.concatenate([[0, M - 1, int(np.argmax(x.max(1))), int(np.argmin(x.min(1)))],
-                                     rng.integers(0, M, 60)]))
+    rows = sample_rows(x, 512, M + K + N)
     for bits in (8, 4, 3):
         pw, oc, os_, oz = make_weight(mq, orc, w, bits)
         y = host(mq.qlinear_w_only(dev(x), pw, dev(b)))
@@ -270,7 +278,7 @@ SPLIT_SHAPES = [(1, 5120, 1280), (16, 1280, 320), (77, 2048, 1280), (308, 2048, 
 @pytest.mark.parametrize("tile", (-1, 1, 2, 3, 4, 5))
 @pytest.mark.parametrize("parts", (0, 2, 3, 7))
 def test_split_reduction_matches_oracle(mq, orc, tile, parts):
-    """Few tiles, long reduction: several workgroups per tile, partial sums through the library's scratch ring.
+    """Few tiles, long reduction: several workgroups per tile, partial sums through the caller's workspace.
     parts = 0 is the automatic choice; forced part counts also cover uneven splits and the k-split tiles."""
     mq.tune_force_tile(tile)
     mq.tune_force_splits(parts)
@@ -293,16 +301,65 @@ def test_split_reduction_matches_oracle(mq, orc, tile, parts):
         mq.tune_force_tile(-1)
 
 
-def test_split_reduction_is_deterministic_and_reuses_its_scratch(mq, orc):
-    """Many launches in a row walk the scratch ring several times round; every result is bit-identical."""
+def test_split_reduction_is_deterministic_and_reuses_its_workspace(mq, orc):
+    """Many launches in a row through ONE workspace whose contents start as garbage (the counters are cleared on the
+    stream before every launch): every result is bit-identical.  Without a workspace the same call does not split and
+    still matches the oracle; a workspace that holds only some of the parts is used for as many as fit."""
     M, K, N = 64, 5120, 1280
-    x = dev(si.activations_f16(32, "sp/det", M, K))
-    pw, *_ = make_weight(mq, orc, si.weights_f16(32, "sp/detw", N, K), 4)
-    mq.tune_force_splits(16)  # 20 tiles x 16 parts x 16 KB = 5 MB per launch: the 32 MB ring wraps every 6 launches
+    xh = si.activations_f16(32, "sp/det", M, K)
+    x = dev(xh)
+    pw, oc, os_, oz = make_weight(mq, orc, si.weights_f16(32, "sp/detw", N, K), 4)
+    ref = orc.linear_w_only(xh, oc, os_, oz)
+    mq.tune_force_splits(16)
     try:
-        y0 = mq.qlinear_w_only(x, pw).clone()
+        ws = torch.full((mq.split_workspace_bytes(M, N, K),), 0xA5, dtype=torch.uint8, device="cuda")
+        y0 = mq.qlinear_w_only(x, pw, ws=ws).clone()
+        assert_close16(host(y0), ref, "forced 16 parts")
         for _ in range(40):
-            assert torch.equal(mq.qlinear_w_only(x, pw), y0)
+            assert torch.equal(mq.qlinear_w_only(x, pw, ws=ws), y0)
+        with pytest.raises(mq.MixdqError) as e:
+            mq.qlinear_w_only(x, pw, ws=ws[:1 << 20])
+        assert e.value.code == -4
+    finally:
+        mq.tune_force_splits(0)
+    need = mq.split_workspace_bytes(M, N, K)
+    assert need > 0
+    full = mq.plan_qlinear_w_only(x, pw, None, torch.empty_like(y0), ws=torch.empty(need, dtype=torch.uint8, device="cuda"))
+    none = mq.plan_qlinear_w_only(x, pw, None, torch.empty_like(y0), ws=None)
+    some = mq.plan_qlinear_w_only(x, pw, None, torch.empty_like(y0), ws=torch.empty(need // 5 // 256 * 256, dtype=torch.uint8,
+                                                                                  device="cuda"))
+    for plan in (full, none, some):
+        plan()
+        assert_close16(host(plan.keepalive[3]), ref, "automatic split, full / no / small workspace")
+
+
+def test_split_reductions_on_two_streams_with_a_workspace_each(mq, orc):
+    """Split launches queued on two streams at once, each stream with its own workspace, one of them behind a long
+    kernel so that the launches of the other overtake it: all results equal the single-stream result bit for bit.
+    (One workspace per stream is the contract; nothing of the library is shared between the launches.)"""
+    M, K, N = 64, 5120, 1280
+    x = dev(si.activations_f16(33, "sp2/x", M, K))
+    pw, *_ = make_weight(mq, orc, si.weights_f16(33, "sp2/w", N, K), 4)
+    big_x = dev(si.activations_f16(33, "sp2/bx", 4096, 1280))
+    big_w, *_ = make_weight(mq, orc, si.weights_f16(33, "sp2/bw", 5120, 1280), 4)
+    mq.tune_force_splits(16)
+    try:
+        need = mq.split_workspace_bytes(M, N, K)
+        wsa = torch.empty(need, dtype=torch.uint8, device="cuda")
+        wsb = torch.empty(need, dtype=torch.uint8, device="cuda")
+        ref = mq.qlinear_w_only(x, pw, ws=wsa).clone()
+        torch.cuda.synchronize()
+        s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+        for it in range(6):
+            with torch.cuda.stream(s1):
+                for _ in range(4):
+                    mq.qlinear_w_only(big_x, big_w)           # long kernels ahead of the split launch
+                ya = [mq.qlinear_w_only(x, pw, ws=wsa) for _ in range(3)]
+            with torch.cuda.stream(s2):
+                yb = [mq.qlinear_w_only(x, pw, ws=wsb) for _ in range(12)]
+            torch.cuda.synchronize()
+            for y in ya + yb:
+                assert torch.equal(y, ref), f"round {it}"
     finally:
         mq.tune_force_splits(0)
 
@@ -356,9 +413,7 @@ def test_a8_transformer_block_shapes_sampled_rows(mq, orc, K, N):
     x = si.activations_f16(0, f"c3/x{K}", M, K)
     w = si.weights_f16(0, f"c3/w{N}x{K}", N, K)
     b = si.bias_f16(0, f"c3/b{N}", N)
-    rng = np.random.default_rng(K + N)
-    rows = np.unique(np.concatenate([[0, M - 1, int(np.argmax(x.max(1))), int(np.argmin(x.min(1)))],
-                                     rng.integers(0, M, 28)]))
+    rows = sample_rows(x, 512, K + N)
     for bits, sym, fn in ((4, False, mq.qlinear_w4a8), (8, True, mq.qlinear_w8a8), (2, False, mq.qlinear_w2a8)):
         pw, oc, os_, oz = make_weight(mq, orc, w, bits, sym)
         y, acc, (s_out, z_out) = fn(dev(x), pw, bias=dev(b), want_acc=True, want_act=True)
@@ -887,6 +942,43 @@ def test_bos_aware_kv_projection(mq, orc, N, bits, sym):
     assert_close16(host(y3), ry3, "naive all rows")
 
 
+@pytest.mark.parametrize("N", (640, 1280))
+@pytest.mark.parametrize("bits,sym", [(8, True), (4, False)])
+def test_bos_aware_kv_projection_static_parameters_and_bias(mq, orc, N, bits, sym):
+    """Eight prompts at full size with calibrated (static) activation parameters and a bias: the parameters are the given
+    ones (narrower than the data, so body codes saturate), the BOS rows stay in fp16 and carry the bias too; the naive
+    comparator under the same static parameters; the pre-computed BOS vector with a bias on the body rows."""
+    B, T, K = 8, 77, 2048
+    ctx = si.bos_context_f16(0, "c4/ctx", B, T, K)
+    w = si.weights_f16(0, f"c4/w{N}", N, K)
+    b = si.bias_f16(0, f"c4/b{N}", N)
+    pw, oc, os_, oz = make_weight(mq, orc, w, bits, sym)
+    act = (np.float32(0.03), 120)
+    d_act = (dev(np.array([act[0]], np.float32)), dev(np.array([act[1]], np.int32)))
+    y, (s_out, z_out) = mq.bos_aware_kv_proj(dev(ctx), pw, w_f16=dev(w), act=d_act, bias=dev(b), want_act=True)
+    ry, (rs, rz) = orc.bos_aware_kv_proj(ctx, oc, os_, oz, w_signed=sym, w_f16=w, act=act, bias=b)
+    assert host(s_out)[0] == act[0] == rs and host(z_out)[0] == act[1] == rz
+    yh = host(y)
+    assert_close16(yh[:, 1:], ry[:, 1:], "static + bias, body rows")
+    assert_close16(yh[:, 0], ry[:, 0], "static + bias, BOS rows")
+    # dynamic parameters with a bias at full size
+    y, (s_out, z_out) = mq.bos_aware_kv_proj(dev(ctx), pw, w_f16=dev(w), bias=dev(b), want_act=True)
+    ry, (rs, rz) = orc.bos_aware_kv_proj(ctx, oc, os_, oz, w_signed=sym, w_f16=w, bias=b)
+    assert host(s_out)[0] == rs and host(z_out)[0] == rz
+    assert_close16(host(y)[:, 1:], ry[:, 1:], "dynamic + bias, body rows")
+    assert_close16(host(y)[:, 0], ry[:, 0], "dynamic + bias, BOS rows")
+    # pre-computed BOS output (it already holds its bias), static parameters, bias on the body rows
+    bos_out = orc.linear_fp(ctx[0, 0:1], w, b)[0]
+    y2, _ = mq.bos_aware_kv_proj(dev(ctx), pw, bos_out=dev(bos_out.view(np.float16)), act=d_act, bias=dev(b))
+    ry2, _ = orc.bos_aware_kv_proj(ctx, oc, os_, oz, w_signed=sym, bos_out=bos_out, act=act, bias=b)
+    assert np.array_equal(host(y2)[:, 0].view(np.uint16), np.broadcast_to(bos_out, (B, N)))
+    assert_close16(host(y2)[:, 1:], ry2[:, 1:], "pre-computed + static + bias, body rows")
+    # comparator under the same static parameters
+    y3, _ = mq.bos_aware_kv_proj(dev(ctx), pw, act=d_act, bias=dev(b), naive_all_rows=True)
+    ry3, _ = orc.bos_aware_kv_proj(ctx, oc, os_, oz, w_signed=sym, act=act, bias=b, naive_all_rows=True)
+    assert_close16(host(y3), ry3, "naive all rows, static + bias")
+
+
 def test_bos_distinct_rows_small_and_degenerate(mq, orc):
     for (B, T, K, N) in ((3, 9, 128, 40), (1, 2, 64, 32), (2, 1, 64, 32)):
         ctx = si.bos_context_f16(3, f"bos/{B}{T}", B, T, K, n_outlier=4, shared_bos=False)
@@ -900,23 +992,49 @@ def test_bos_distinct_rows_small_and_degenerate(mq, orc):
 
 # ----------------------------------------------------------------------------------------------- full-size sweep shapes
 
-@pytest.mark.parametrize("K,N", [(640, 5120), (2560, 640)])
+@pytest.mark.parametrize("K,N", [(640, 640), (640, 5120), (2560, 640)])
 def test_sweep_640_level_shapes_sampled_rows(mq, orc, K, N):
-    """M = 16384 (latent 128x128, batch 4): weight-only at 2 bits and W4A8, oracle on sampled rows."""
+    """M = 16384 (latent 128x128, batch 4), all three shapes of the level, in the launch configuration of the benchmark:
+    weight-only at 2 and 4 bits and W4A8, oracle on 512 sampled rows."""
     M = 16384
     x = si.activations_f16(0, f"c5/x{K}", M, K, outlier_prob=0.01)
     w = si.weights_f16(0, f"c5/w{N}x{K}", N, K)
-    rows = np.unique(np.concatenate([[0, M - 1, int(np.argmax(x.max(1))), int(np.argmin(x.min(1)))],
-                                     np.random.default_rng(K).integers(0, M, 28)]))
+    b = si.bias_f16(0, f"c5/b{N}", N)
+    rows = sample_rows(x, 512, K + N)
     xd = dev(x)
-    pw, oc, os_, oz = make_weight(mq, orc, w, 2)
-    y = host(mq.qlinear_w_only(xd, pw))
-    assert_close16(y[rows], orc.linear_w_only(x, oc, os_, oz, rows=rows), "c5 W2A16")
-    pw, oc, os_, oz = make_weight(mq, orc, w, 4)
-    y, acc, _ = mq.qlinear_w4a8(xd, pw, want_acc=True)
-    ry, racc, _ = orc.linear_a8(x, oc, os_, oz, rows=rows)
+    for bits in (2, 4):
+        pw, oc, os_, oz = make_weight(mq, orc, w, bits)
+        y = host(mq.qlinear_w_only(xd, pw, dev(b)))
+        assert_close16(y[rows], orc.linear_w_only(x, oc, os_, oz, b, rows=rows), f"c5 W{bits}A16 {K}->{N}")
+        assert np.isfinite(y).all()
+    y, acc, (s_out, z_out) = mq.qlinear_w4a8(xd, pw, bias=dev(b), want_acc=True, want_act=True)
+    ry, racc, (rs, rz) = orc.linear_a8(x, oc, os_, oz, bias=b, rows=rows)
+    assert host(s_out)[0] == rs and host(z_out)[0] == rz
     assert np.array_equal(host(acc)[rows], racc)
-    assert_close16(host(y)[rows], ry, "c5 W4A8")
+    assert_close16(host(y)[rows], ry, f"c5 W4A8 {K}->{N}")
+
+
+@pytest.mark.parametrize("N", (640, 1280))
+def test_sweep_kv_projection_four_prompts(mq, orc, N):
+    """The cross-attention K/V call of the sweep as the benchmark launches it: four prompts (M = 4 * 77 = 308 rows, 304 of
+    them quantised), W4A8 with the BOS rows in fp16, dynamic and static activation parameters, with a bias."""
+    B, T, K = 4, 77, 2048
+    ctx = si.bos_context_f16(0, "c5/ctx", B, T, K)
+    w = si.weights_f16(0, f"c5/kvw{N}", N, K)
+    b = si.bias_f16(0, f"c5/kvb{N}", N)
+    pw, oc, os_, oz = make_weight(mq, orc, w, 4)
+    y, (s_out, z_out) = mq.bos_aware_kv_proj(dev(ctx), pw, w_f16=dev(w), bias=dev(b), want_act=True)
+    ry, (rs, rz) = orc.bos_aware_kv_proj(ctx, oc, os_, oz, w_f16=w, bias=b)
+    assert host(s_out)[0] == rs and host(z_out)[0] == rz
+    assert_close16(host(y)[:, 1:], ry[:, 1:], f"kv B=4 N={N} body rows")
+    assert_close16(host(y)[:, 0], ry[:, 0], f"kv B=4 N={N} BOS rows")
+    act = (np.float32(0.035), 131)
+    d_act = (dev(np.array([act[0]], np.float32)), dev(np.array([act[1]], np.int32)))
+    y, (s_out, z_out) = mq.bos_aware_kv_proj(dev(ctx), pw, w_f16=dev(w), bias=dev(b), act=d_act, want_act=True)
+    ry, _ = orc.bos_aware_kv_proj(ctx, oc, os_, oz, w_f16=w, bias=b, act=act)
+    assert host(s_out)[0] == act[0] and host(z_out)[0] == act[1]
+    assert_close16(host(y)[:, 1:], ry[:, 1:], f"kv B=4 N={N} static, body rows")
+    assert_close16(host(y)[:, 0], ry[:, 0], f"kv B=4 N={N} static, BOS rows")
 
 
 @pytest.mark.parametrize("B,H,W,Cin,N,stride", [(4, 128, 128, 320, 320, 1), (4, 128, 128, 320, 320, 2), (4, 32, 32, 1280, 1280, 1)])
@@ -968,8 +1086,8 @@ def test_stacked_layers_that_share_their_input(mq, orc):
 
 def test_side_streams_and_two_streams_at_once(mq, orc):
     """The library launches on the stream it is handed and keeps no state that two streams could trample: the results
-    on a side stream, and on two streams that run different layers at the same time (split reduction with its shared
-    scratch ring, dynamic 8-bit activations with their workspaces), equal those of the default stream bit for bit."""
+    on a side stream, and on two streams that run different layers at the same time (each call with a workspace of its
+    own), equal those of the default stream bit for bit."""
     xa = dev(si.activations_f16(96, "ss/xa", 64, 5120))
     wa, *_ = make_weight(mq, orc, si.weights_f16(96, "ss/wa", 1280, 5120), 4)
     xb = dev(si.activations_f16(96, "ss/xb", 2048, 1280, outlier_prob=0.01))
