@@ -14,6 +14,10 @@ GEMM kernel alone (bracket cost subtracted).
 
 Algorithmic bytes per call: X once (2 M K) + packed weights (N K bits / 8) + 10 N (scale, zero point, bias) + Y once
 (2 M N); ops = 2 M N K.
+
+The last two columns repeat the two fractions against what THIS machine reaches in microbenchmarks run at the start
+(mq_prof_microbench: MFMA-only loops for the two operand types, a read-only stream over 2 GiB), printed in the header:
+the published peaks assume a clock the chip does not hold under load.
 """
 from __future__ import annotations
 
@@ -55,6 +59,8 @@ def main():
     ap.add_argument("--only", default="", help="comma-separated labels (c1,c2,c3,c4,c5,small-M,ff,conv,qkv,kvall)")
     ap.add_argument("--tile", type=int, default=-1, help="force a tile of the GEMM's tile table (-1: the library's choice)")
     ap.add_argument("--band", type=int, default=0, help="force the band height of the workgroup -> tile map (0: the library's choice)")
+    ap.add_argument("--modes", default="", help="comma-separated modes to keep (w4,a4,a8sym,...); empty: all")
+    ap.add_argument("--no-peaks", action="store_true", help="skip the microbenchmarks (measured-peak columns read 0)")
     args = ap.parse_args()
 
     import torch
@@ -68,18 +74,31 @@ def main():
     gen.manual_seed(0)
     overhead_us = mq.prof_bracket_overhead_us()
     only = set(filter(None, args.only.split(",")))
+    keep_modes = set(filter(None, args.modes.split(",")))
+    mpk = None
+    if not args.no_peaks:
+        mpk = mq.machine_peaks()
+        print(f"# measured on this machine: int8 MFMA {mpk['int8_TOPs']:.0f} TOP/s, fp16 MFMA {mpk['f16_TFLOPs']:.0f} TFLOP/s, "
+              f"read-only stream {mpk['read_GBps']:.0f} GB/s, LDS reads {mpk['lds_read_TBps']:.1f} TB/s; matrix and vector "
+              f"instructions together take {mpk['serial_share_same_wave']:.2f} (one wave) / {mpk['serial_share_two_waves']:.2f} "
+              f"(two waves of a SIMD) of the sum of their separate times (0.50 = full overlap, 1.00 = none)")
+        torch.cuda.empty_cache()
+    m_hbm = mpk["read_GBps"] * 1e9 if mpk else 0.0
+    m_peak = {"w": mpk["f16_TFLOPs"] * 1e12, "a": mpk["int8_TOPs"] * 1e12} if mpk else {"w": 0.0, "a": 0.0}
 
     if args.tile >= 0:
         print(f"# tile {args.tile} forced")
     print(f"# per-shape report, {torch.cuda.get_device_name(0)}; iters per row {args.iters}; "
           f"event-bracket cost subtracted from the kernel column: {overhead_us:.2f} us")
     print(f"{'cfg':8s}{'M':>6s}{'K':>6s}{'N':>6s} {'mode':7s}{'us/call':>9s}{'kernel us':>10s}{'T(FL)OP/s':>10s}"
-          f"{'GB/s':>8s}{'t_HBM us':>9s}{'t_MFMA us':>10s} {'binds':5s}{'frac':>6s}{'k.frac':>7s}")
+          f"{'GB/s':>8s}{'t_HBM us':>9s}{'t_MFMA us':>10s} {'binds':5s}{'frac':>6s}{'k.frac':>7s}{'m.frac':>7s}{'m.kfrac':>8s}")
 
     for (cfg, M, K, N, modes) in shapes():
         if only and cfg not in only:
             continue
         for mode in modes:
+            if keep_modes and mode not in keep_modes:
+                continue
             bos = mode.startswith("bos")
             sym = mode.endswith("sym")
             kind = "w" if mode[0] == "w" else "a"
@@ -150,9 +169,10 @@ def main():
             t_hbm = alg_bytes / HBM * 1e6
             t_mfma = ops / PEAK[kind] * 1e6
             bind = "HBM" if t_hbm >= t_mfma else "MFMA"
+            t_meas = max(alg_bytes / m_hbm, ops / m_peak[kind]) * 1e6 if mpk else 0.0   # against the measured rates
             print(f"{cfg:8s}{M:6d}{K:6d}{N:6d} {mode:7s}{us:9.2f}{k_us:10.2f}{ops / us / 1e6:10.1f}"
                   f"{alg_bytes / us / 1e3:8.0f}{t_hbm:9.2f}{t_mfma:10.2f} {bind:5s}{max(t_hbm, t_mfma) / us:6.3f}"
-                  f"{max(t_hbm, t_mfma) / k_us:7.3f}", flush=True)
+                  f"{max(t_hbm, t_mfma) / k_us:7.3f}{t_meas / us:7.3f}{t_meas / k_us:8.3f}", flush=True)
             del sets
             torch.cuda.empty_cache()
     if not only or "ff" in only:

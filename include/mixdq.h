@@ -102,6 +102,20 @@ double mq_prof_bracket_overhead_us(void* stream);
  * aligned pointers): the known-size reference that hardware HBM traffic counters are scaled by. */
 int mq_prof_copy(void* dst, const void* src, size_t bytes, void* stream);
 
+/* Microbenchmarks of the chip, for reporting results against what this machine can reach (the published peaks assume
+ * the highest clock).  Runs one kernel of fixed work five times between events on `stream`, synchronises, and writes
+ * the best elapsed time in milliseconds to *ms_host.  buf: device memory, 16-byte aligned, at least 4 KiB (kind 5: the
+ * region that is streamed; make it larger than the last-level cache).  Work per launch:
+ *   0  int8 MFMA only: 512 workgroups x 4 waves x 4096 x 4 MFMAs of 32x32x32 (65536 operations each)
+ *   1  fp16 MFMA only: the same count of 32x32x16 MFMAs (32768 operations each)
+ *   2  vector ALU only: 512 x 4 waves x 4096 x 32 instructions (the cycles of kind 0's MFMAs)
+ *   3  the MFMAs of 0 and the ALU instructions of 2 interleaved in ONE wave (1 MFMA, 8 ALU instructions, ...)
+ *   4  the MFMA waves of 0 and the ALU waves of 2 side by side, one of each on every SIMD
+ *   5  read-only stream over buf: buf_bytes - 4096 bytes read
+ *   6  LDS reads (ds_read_b128, the GEMMs' swizzled row pattern): 1024 workgroups x 4 waves x 4000 x 8 KiB
+ * Kinds 2 to 4 show how far matrix and vector instructions overlap on one SIMD. */
+int mq_prof_microbench(int kind, void* buf, size_t buf_bytes, double* ms_host, void* stream);
+
 /* Phase timing inside the GEMM kernels: while clk != NULL every GEMM launch with at most `workgroups` workgroups
  * writes four shader-clock samples per workgroup (start, main loop entered, epilogue entered, end) to
  * clk[4*workgroup .. 4*workgroup+3] (device memory, caller owned).  Clocks of different XCDs are not comparable;

@@ -22,7 +22,7 @@ _ERRORS = {
 }
 
 EXPORTS = ("mq_version", "mq_last_hip_error", "mq_tune_force_tile", "mq_tune_force_splits", "mq_tune_force_band", "mq_prof_enable", "mq_prof_num_slots", "mq_prof_read",
-           "mq_prof_reset", "mq_prof_phase_buffer", "mq_prof_filter", "mq_prof_bracket_overhead_us", "mq_prof_copy", "mq_quantize_weights", "mq_packed_bytes", "mq_pack_weights",
+           "mq_prof_reset", "mq_prof_phase_buffer", "mq_prof_filter", "mq_prof_bracket_overhead_us", "mq_prof_copy", "mq_prof_microbench", "mq_quantize_weights", "mq_packed_bytes", "mq_pack_weights",
            "mq_unpack_weights", "mq_split_workspace_bytes", "mq_qlinear_w_only", "mq_qlinear_a8_workspace_bytes", "mq_qlinear_w8a8",
            "mq_qlinear_w4a8", "mq_qlinear_w2a8", "mq_a8_row_bytes", "mq_qlinear_a8_geglu", "mq_qlinear_w_only_geglu", "mq_qlinear_a8_codes", "mq_conv3x3_w_only",
            "mq_conv_tap_sums", "mq_conv3x3_a8_workspace_bytes", "mq_conv3x3_a8",
@@ -93,6 +93,34 @@ def prof_copy(dst: torch.Tensor, src: torch.Tensor) -> None:
     nbytes = src.numel() * src.element_size()
     assert dst.numel() * dst.element_size() == nbytes
     _check(load().mq_prof_copy(_ptr(dst), _ptr(src), C.c_size_t(nbytes), _stream()), "mq_prof_copy")
+
+
+def prof_microbench(kind: int, buf: torch.Tensor) -> float:
+    """Elapsed milliseconds (best of five) of microbenchmark `kind` (see include/mixdq.h); buf: device scratch."""
+    ms = C.c_double(0.0)
+    _check(load().mq_prof_microbench(int(kind), _ptr(buf), C.c_size_t(buf.numel() * buf.element_size()), C.byref(ms),
+                                     _stream()), "mq_prof_microbench")
+    return ms.value
+
+
+def machine_peaks(buf: Optional[torch.Tensor] = None) -> dict:
+    """Measured rates of this machine: int8 and fp16 MFMA (T(FL)OP/s), read-only stream (GB/s), LDS reads (bytes per
+    second over the chip), and the overlap of matrix and vector instructions on a SIMD: elapsed time of both kinds of
+    work together divided by the sum of their separate times (0.5 = perfect overlap of equal halves, 1.0 = none), in
+    one wave and in two waves of one SIMD."""
+    if buf is None:
+        buf = torch.empty(2 << 30, dtype=torch.uint8, device="cuda")
+    small = buf[:1 << 20]
+    t = {k: prof_microbench(k, small if k != 5 else buf) for k in range(7)}
+    n_mfma = 512 * 4 * 4096 * 4
+    return {
+        "int8_TOPs": n_mfma * 65536.0 / (t[0] * 1e-3) / 1e12,
+        "f16_TFLOPs": n_mfma * 32768.0 / (t[1] * 1e-3) / 1e12,
+        "read_GBps": (buf.numel() - 4096) / (t[5] * 1e-3) / 1e9,
+        "lds_read_TBps": 1024 * 4 * 4000 * 8192.0 / (t[6] * 1e-3) / 1e12,
+        "mfma_ms": t[0], "valu_ms": t[2], "same_wave_ms": t[3], "two_waves_ms": t[4],
+        "serial_share_same_wave": t[3] / (t[0] + t[2]), "serial_share_two_waves": t[4] / (t[0] + t[2]),
+    }
 
 
 def prof_reset() -> None:

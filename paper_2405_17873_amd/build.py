@@ -9,8 +9,9 @@ from concurrent.futures import ThreadPoolExecutor
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
-OBJ = os.path.join(HERE, "_build")
-LIB = os.path.join(HERE, "libmixdq.so")
+OBJ = os.environ.get("MQ_OBJ_DIR", os.path.join(HERE, "_build"))
+LIB = os.environ.get("MQ_LIB_OUT", os.path.join(HERE, "libmixdq.so"))
+EXTRA = os.environ.get("MQ_EXTRA_FLAGS", "").split()
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
 COMMON = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Xclang", "-target-feature", "-Xclang",
@@ -21,7 +22,7 @@ PER_FILE = {
     "act_quant.hip": ["-ffp-contract=off"],
     "alloc.cpp": ["-ffp-contract=off"],  # budgets are floors of double products: no fused multiply-add
 }
-SOURCES = ["api.hip", "quant_pack.hip", "act_quant.hip", "gemm.hip", "bos.hip", "prof.hip", "alloc.cpp"]
+SOURCES = ["api.hip", "quant_pack.hip", "act_quant.hip", "gemm.hip", "bos.hip", "prof.hip", "peaks.hip", "alloc.cpp"]
 
 
 def _compile(src: str, force: bool) -> str:
@@ -31,7 +32,7 @@ def _compile(src: str, force: bool) -> str:
             os.path.join(HERE, "..", "include", "mixdq.h"), __file__]
     if not force and os.path.exists(obj) and all(os.path.getmtime(obj) >= os.path.getmtime(d) for d in deps):
         return obj
-    cmd = [HIPCC, *COMMON, *PER_FILE.get(src, []), "-c", path, "-o", obj]
+    cmd = [HIPCC, *COMMON, *EXTRA, *PER_FILE.get(src, []), "-c", path, "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         errs = [l for l in (r.stdout + r.stderr).splitlines() if "error" in l]

@@ -104,6 +104,7 @@ static int qlinear_a8(const void* x, int M, int K, int ldx, RowMap in_map, const
     return launch_gemm_a8(w.a8, w.rowsum, w.params, M, K, packed, N, w_bits, w_signed, w_scale, w_zp, w_colsum, bias,
                           y, ldy, out_map, acc_debug, residual, ldr, (uint8_t*)ws + base, ws_bytes - base, st);
 }
+
 }  // namespace mq
 
 using namespace mq;
@@ -126,6 +127,9 @@ int mq_prof_reset(void) { return prof_reset(); }
 int mq_prof_filter(int slot, int stride) { return prof_filter(slot, stride); }
 int mq_prof_copy(void* dst, const void* src, size_t bytes, void* stream) {
     return prof_copy(dst, src, bytes, (hipStream_t)stream);
+}
+int mq_prof_microbench(int kind, void* buf, size_t buf_bytes, double* ms_host, void* stream) {
+    return prof_microbench(kind, buf, buf_bytes, ms_host, (hipStream_t)stream);
 }
 double mq_prof_bracket_overhead_us(void* stream) { return prof_bracket_overhead_us((hipStream_t)stream); }
 

@@ -1305,8 +1305,9 @@ static int run_gemm_r(GemmArgs& g, int tile_index, hipStream_t st) {
     // Height of the bands of the tile walk, measured on operands that are not cached over 1 to 64 row blocks: the
     // int8 path gains 4 to 23 % at 8 to 16 (every shape of the sweep, most at 16384 x 640 x 640 and with 8-bit
     // weights) and loses again from 32 on; unquantised 16-bit weights (the largest weight tiles) gain up to 15 % at
-    // 8; quantised weights under 16-bit activations move by +-2 % either way and keep the row-by-row walk.
-    g.band_rows = g_force_band > 0 ? g_force_band : (I8 ? 16 : (BITS == 16 ? 8 : 1));
+    // 8; quantised weights under 16-bit activations move by -10 (8-bit, 4096 x 2560 x 640) to +2 % at 8, and every
+    // weight tile is then fetched once per eight row blocks instead of once per row block.
+    g.band_rows = g_force_band > 0 ? g_force_band : (I8 ? 16 : 8);
     if (g.band_rows > g.tiles_m) g.band_rows = g.tiles_m;
     if (g.band_rows < 1) g.band_rows = 1;
     const int KT = (g.k_stages + KS - 1) / KS;

@@ -162,6 +162,7 @@ int prof_read(int slot, char* name, int name_cap, long long* launches, double* m
 int prof_reset();
 double prof_bracket_overhead_us(hipStream_t st);
 int prof_copy(void* dst, const void* src, size_t bytes, hipStream_t st);
+int prof_microbench(int kind, void* buf, size_t buf_bytes, double* ms_host, hipStream_t st);
 
 struct ProfScope {
     bool open = false;
