@@ -234,6 +234,25 @@ int mq_qlinear_w2a8(const void* x, int M, int K, int ldx, const void* packed, in
                     const void* residual, int ldr, float* act_scale_out, int32_t* act_zp_out, void* ws,
                     size_t ws_bytes, void* stream);
 
+/* For callers that cannot allocate device memory or hand over a workspace (code under HIP graph capture, tight
+ * serving loops, harnesses that forbid allocation): mq_qlinear_w8a8 / _w4a8 / _w2a8 (by w_bits = 8, 4, 2; w_signed
+ * only with 8) with the workspace in a device array that is part of the library, mq_builtin_workspace_bytes() =
+ * 48 MiB per GPU the library runs on, held until the process ends.  The call allocates nothing and frees nothing.
+ * All other arguments, results and errors are those of the entry points above, bit for bit.
+ *   Limit: mq_qlinear_a8_workspace_bytes(M, K) <= mq_builtin_workspace_bytes(), else MQ_ERR_WORKSPACE_TOO_SMALL
+ *   (M * K up to about 50 M activations: every linear of the configured workloads fits); what the activation
+ *   workspace leaves of the array serves the split of the reduction.
+ *   Every call on a GPU uses that GPU's one array, which keeps the previous call's contents (nothing in it has to
+ *   start at zero: every byte that is read is written first, the split counters by a clearing kernel).  Calls that
+ *   may overlap on one GPU - different streams, or a captured graph replayed while another call runs - race on it:
+ *   keep them on one stream. */
+size_t mq_builtin_workspace_bytes(void);
+int mq_qlinear_a8_builtin_ws(const void* x, int M, int K, int ldx, const void* packed, int N, int w_bits, int layout,
+                             int w_signed, const float* w_scale, const int32_t* w_zp, const int32_t* w_colsum,
+                             const float* act_scale, const int32_t* act_zp, const void* bias, void* y, int ldy,
+                             int32_t* acc_debug, const void* residual, int ldr, float* act_scale_out,
+                             int32_t* act_zp_out, void* stream);
+
 /* ------------------------------------------------------------------------------------------------
  * Feed-forward pair with the activation kept in 8 bits between its two linears (an extension: paper Sec. 4.3
  * names the separate FP16->INT8 conversion layers as the overhead of the W8A8 path; this removes the one between

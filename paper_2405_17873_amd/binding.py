@@ -24,7 +24,7 @@ _ERRORS = {
 EXPORTS = ("mq_version", "mq_last_hip_error", "mq_tune_force_tile", "mq_tune_force_splits", "mq_tune_force_band", "mq_prof_enable", "mq_prof_num_slots", "mq_prof_read",
            "mq_prof_reset", "mq_prof_phase_buffer", "mq_prof_filter", "mq_prof_bracket_overhead_us", "mq_prof_copy", "mq_prof_microbench", "mq_quantize_weights", "mq_packed_bytes", "mq_pack_weights",
            "mq_unpack_weights", "mq_split_workspace_bytes", "mq_qlinear_w_only", "mq_qlinear_a8_workspace_bytes", "mq_qlinear_w8a8",
-           "mq_qlinear_w4a8", "mq_qlinear_w2a8", "mq_a8_row_bytes", "mq_qlinear_a8_geglu", "mq_qlinear_w_only_geglu", "mq_qlinear_a8_codes", "mq_conv3x3_w_only",
+           "mq_qlinear_w4a8", "mq_qlinear_w2a8", "mq_builtin_workspace_bytes", "mq_qlinear_a8_builtin_ws", "mq_a8_row_bytes", "mq_qlinear_a8_geglu", "mq_qlinear_w_only_geglu", "mq_qlinear_a8_codes", "mq_conv3x3_w_only",
            "mq_conv_tap_sums", "mq_conv3x3_a8_workspace_bytes", "mq_conv3x3_a8",
            "mq_bos_aware_kv_proj_workspace_bytes", "mq_bos_aware_kv_proj", "mq_alloc_solve", "mq_alloc_split_budget",
            "mq_alloc_search")
@@ -50,7 +50,7 @@ def load():
         if not os.path.exists(_LIB_PATH):
             raise RuntimeError(f"{_LIB_PATH} is missing: run `python -c 'import __graft_entry__ as g; g.build()'`")
         _lib = C.CDLL(_LIB_PATH)
-        for name in ("mq_a8_row_bytes", "mq_split_workspace_bytes", "mq_conv3x3_a8_workspace_bytes", "mq_packed_bytes", "mq_qlinear_a8_workspace_bytes", "mq_bos_aware_kv_proj_workspace_bytes"):
+        for name in ("mq_a8_row_bytes", "mq_split_workspace_bytes", "mq_builtin_workspace_bytes", "mq_conv3x3_a8_workspace_bytes", "mq_packed_bytes", "mq_qlinear_a8_workspace_bytes", "mq_bos_aware_kv_proj_workspace_bytes"):
             getattr(_lib, name).restype = C.c_size_t
         _lib.mq_prof_bracket_overhead_us.restype = C.c_double
     return _lib
@@ -326,6 +326,32 @@ def qlinear_w2a8(x, w: PackedWeight, act=None, bias=None, out=None, ws=None, wan
                  residual=None):
     assert w.bits == 2 and not w.signed
     return _qlinear_a8("mq_qlinear_w2a8", x, w, act, bias, out, ws, want_acc, want_act, residual)
+
+
+def builtin_workspace_bytes() -> int:
+    return int(load().mq_builtin_workspace_bytes())
+
+
+def qlinear_a8_builtin_ws(x, w: PackedWeight, act=None, bias=None, out=None, want_acc=False, want_act=False,
+                          residual=None, y=None):
+    """W8A8 / W4A8 / W2A8 (by the weight's bit-width) with the workspace inside the library: the C call allocates
+    nothing.  Pass out= (and want_acc / want_act False) for a call that allocates nothing on the Python side either.
+    Returns (y, acc or None, (act_scale, act_zp) or (None, None))."""
+    assert x.is_cuda and x.dim() == 2 and x.stride(1) == 1 and x.dtype == torch.float16
+    M, K = x.shape
+    assert K == w.K
+    dev = x.device
+    y = out if out is not None else torch.empty((M, w.N), dtype=torch.float16, device=dev)
+    acc = torch.empty((M, w.N), dtype=torch.int32, device=dev) if want_acc else None
+    s_out = torch.empty(1, dtype=torch.float32, device=dev) if want_act else None
+    z_out = torch.empty(1, dtype=torch.int32, device=dev) if want_act else None
+    a_s, a_z = (None, None) if act is None else act
+    rp, ldr = _res(residual, M, w.N, torch.float16)
+    _check(load().mq_qlinear_a8_builtin_ws(_ptr(x), M, K, x.stride(0), _ptr(w.packed), w.N, w.bits, w.layout,
+                                           int(w.signed), _ptr(w.scale), _ptr(w.zp), _ptr(w.colsum), _ptr(a_s), _ptr(a_z),
+                                           _ptr(bias), _ptr(y), y.stride(0), _ptr(acc), rp, ldr, _ptr(s_out), _ptr(z_out),
+                                           _stream()), "mq_qlinear_a8_builtin_ws")
+    return y, acc, (s_out, z_out)
 
 
 def a8_row_bytes(K: int) -> int:

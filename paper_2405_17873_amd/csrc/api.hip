@@ -1,6 +1,7 @@
 // C ABI of the library: argument validation on the host, workspace carving, launch sequencing.
 // No entry point allocates device memory or synchronises.
 #include <atomic>
+#include <mutex>
 
 #include "mq_common.h"
 
@@ -105,6 +106,38 @@ static int qlinear_a8(const void* x, int M, int K, int ldx, RowMap in_map, const
                           y, ldy, out_map, acc_debug, residual, ldr, (uint8_t*)ws + base, ws_bytes - base, st);
 }
 
+// ---- built-in workspace ---------------------------------------------------------------------------------------
+// For callers that cannot allocate (code under graph capture, serving loops, harnesses that forbid it):
+// mq_qlinear_a8_builtin_ws runs the 8-bit-activation linear with its workspace in this file-scope device array.  In
+// host code the array's name is only a stand-in, not a device address: its address on the current device is looked
+// up once per device and kept, and host code uses that pointer everywhere.  Every GPU the library runs on holds its
+// own copy of the array until the process ends.
+static constexpr size_t kBuiltinWsBytes = 48u << 20;
+static __device__ __align__(256) uint8_t scratch[kBuiltinWsBytes];
+
+static std::mutex g_scratch_mutex;
+static void* g_scratch_ptr[64] = {};  // per device
+
+static int builtin_workspace(void** out) {
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess || dev < 0 || dev >= 64) {
+        set_hip_error((int)(e != hipSuccess ? e : hipErrorInvalidDevice));
+        return MQ_ERR_HIP;
+    }
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p) {
+            set_hip_error((int)(e != hipSuccess ? e : hipErrorInvalidSymbol));
+            return MQ_ERR_HIP;
+        }
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return MQ_OK;
+}
 }  // namespace mq
 
 using namespace mq;
@@ -357,6 +390,25 @@ int mq_qlinear_w2a8(const void* x, int M, int K, int ldx, const void* packed, in
     return qlinear_a8(x, M, K, ldx, RowMap{0, 0, 0}, packed, N, layout, 2, 0, w_scale, w_zp, w_colsum, act_scale,
                       act_zp, bias, y, ldy, RowMap{0, 0, 0}, acc_debug, act_scale_out, act_zp_out, ws, ws_bytes,
                       residual, ldr, (hipStream_t)stream);
+}
+
+size_t mq_builtin_workspace_bytes(void) { return kBuiltinWsBytes; }
+
+int mq_qlinear_a8_builtin_ws(const void* x, int M, int K, int ldx, const void* packed, int N, int w_bits, int layout,
+                             int w_signed, const float* w_scale, const int32_t* w_zp, const int32_t* w_colsum,
+                             const float* act_scale, const int32_t* act_zp, const void* bias, void* y, int ldy,
+                             int32_t* acc_debug, const void* residual, int ldr, float* act_scale_out,
+                             int32_t* act_zp_out, void* stream) {
+    if (w_bits != 2 && w_bits != 4 && w_bits != 8) return MQ_ERR_UNSUPPORTED_BITS;
+    if (w_bits != 8 && w_signed) return MQ_ERR_BAD_ARG;
+    if (M <= 0 || K <= 0) return MQ_ERR_BAD_SHAPE;
+    // the size limit is checked before the device is touched
+    if (A8Workspace::bytes(M, K) > kBuiltinWsBytes) return MQ_ERR_WORKSPACE_TOO_SMALL;
+    void* ws = nullptr;
+    if (int rc = builtin_workspace(&ws)) return rc;
+    return qlinear_a8(x, M, K, ldx, RowMap{0, 0, 0}, packed, N, layout, w_bits, w_signed ? 1 : 0, w_scale, w_zp, w_colsum,
+                      act_scale, act_zp, bias, y, ldy, RowMap{0, 0, 0}, acc_debug, act_scale_out, act_zp_out, ws,
+                      kBuiltinWsBytes, residual, ldr, (hipStream_t)stream);
 }
 
 size_t mq_bos_aware_kv_proj_workspace_bytes(int B, int T, int K) {
