@@ -8,7 +8,7 @@ import sys
 from concurrent.futures import ThreadPoolExecutor
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-CSRC = os.path.join(HERE, "csrc")
+CSRC = os.environ.get("MQ_CSRC_DIR", os.path.join(HERE, "csrc"))
 OBJ = os.environ.get("MQ_OBJ_DIR", os.path.join(HERE, "_build"))
 LIB = os.environ.get("MQ_LIB_OUT", os.path.join(HERE, "libmixdq.so"))
 EXTRA = os.environ.get("MQ_EXTRA_FLAGS", "").split()

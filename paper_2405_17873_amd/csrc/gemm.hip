@@ -592,13 +592,18 @@ void gemm_kernel(const GemmArgs g) {
 #pragma unroll
     for (int tn = 0; tn < TN; ++tn) zc[tn] = 0;
 
+    // Without an in-workgroup k split every wave's first k step exists, so its MFMAs take the constant zero as their
+    // third operand and the accumulators need no clearing (16 vector instructions per MFMA tile otherwise).
+    constexpr bool ZERO_C = KS == 1 && !CONV;  // (the convolution kernels have no registers to spare for the second copy of step 0)
     acc_t acc[TM][TN];
+    if constexpr (!ZERO_C) {
 #pragma unroll
-    for (int tm = 0; tm < TM; ++tm)
+        for (int tm = 0; tm < TM; ++tm)
 #pragma unroll
-        for (int tn = 0; tn < TN; ++tn)
+            for (int tn = 0; tn < TN; ++tn)
 #pragma unroll
-            for (int i = 0; i < 16; ++i) acc[tm][tn][i] = 0;
+                for (int i = 0; i < 16; ++i) acc[tm][tn][i] = 0;
+    }
 
     // Per-channel epilogue inputs of the workgroup's BN channels: thread t fetches those of channel n0 + t now and
     // keeps them in registers; they are combined and parked in LDS after the loop.  These ordinary loads are issued
@@ -740,18 +745,26 @@ void gemm_kernel(const GemmArgs g) {
             if constexpr (BF && BITS != 16) wf[tn] = __builtin_bit_cast(half8, half8_to_bf16x8(wf[tn]));  // bf16 bits now
         }
     };
-    auto multiply = [&](const frag_t (&wf)[TN], int s) {
+    auto multiply = [&](const frag_t (&wf)[TN], int s, auto fresh_c) {
+        constexpr bool FRESH = decltype(fresh_c)::value;  // the accumulators start here: C = 0
 #pragma unroll
         for (int tm = 0; tm < TM; ++tm)
 #pragma unroll
             for (int tn = 0; tn < TN; ++tn) {
+                acc_t c;
+                if constexpr (FRESH) {
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) c[i] = 0;
+                } else {
+                    c = acc[tm][tn];
+                }
                 if constexpr (I8)
-                    acc[tm][tn] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wf[tn], xf[s][tm], acc[tm][tn], 0, 0, 0);
+                    acc[tm][tn] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wf[tn], xf[s][tm], c, 0, 0, 0);
                 else if constexpr (BF)
                     acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                        __builtin_bit_cast(bf16x8, wf[tn]), __builtin_bit_cast(bf16x8, xf[s][tm]), acc[tm][tn], 0, 0, 0);
+                        __builtin_bit_cast(bf16x8, wf[tn]), __builtin_bit_cast(bf16x8, xf[s][tm]), c, 0, 0, 0);
                 else
-                    acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_f16(wf[tn], xf[s][tm], acc[tm][tn], 0, 0, 0);
+                    acc[tm][tn] = __builtin_amdgcn_mfma_f32_32x32x16_f16(wf[tn], xf[s][tm], c, 0, 0, 0);
             }
         if constexpr (RS_INLINE) {  // this lane's share of the row sums of the stored activations (bytes a' = code - 128)
 #pragma unroll
@@ -787,7 +800,10 @@ void gemm_kernel(const GemmArgs g) {
         for (int tm = 0; tm < TM; ++tm) xf[1][tm] = *(const frag_t*)(abuf + rd[1] + tm * 32 * 128);
         __builtin_amdgcn_sched_barrier(0);
         widen(wf[0], 0);
-        if (live) multiply(wf[0], 0);
+        if (ZERO_C && kt == 0)
+            multiply(wf[0], 0, std::true_type{});
+        else if (live)
+            multiply(wf[0], 0, std::false_type{});
         __builtin_amdgcn_sched_barrier(0);
         // step 1: the last LDS reads of this stage
 #pragma unroll
@@ -796,7 +812,7 @@ void gemm_kernel(const GemmArgs g) {
         for (int tm = 0; tm < TM; ++tm) xf[3][tm] = *(const frag_t*)(abuf + rd[3] + tm * 32 * 128);
         __builtin_amdgcn_sched_barrier(0);
         widen(wf[1], 1);
-        if (live) multiply(wf[1], 1);
+        if (live) multiply(wf[1], 1, std::false_type{});
         __builtin_amdgcn_sched_barrier(0);
         // the packed weights of this stage are widened completely before their registers are reused
         widen(wf[0], 2);
@@ -819,8 +835,8 @@ void gemm_kernel(const GemmArgs g) {
         }
         __builtin_amdgcn_sched_barrier(0);
         if (live) {
-            multiply(wf[0], 2);
-            multiply(wf[1], 3);
+            multiply(wf[0], 2, std::false_type{});
+            multiply(wf[1], 3, std::false_type{});
         }
         __builtin_amdgcn_sched_barrier(0);
         buf = nb;
@@ -1095,6 +1111,10 @@ void gemm_kernel(const GemmArgs g) {
         constexpr int TN0 = decltype(tn0_c)::value, GS = decltype(gs_c)::value;
         constexpr int CPR = GS * 4;              // 16-byte chunks per staged row
         constexpr int ROWS_PER_PASS = 64 / CPR;  // rows one store instruction covers
+        // The chunk index is XOR-ed with the row bits ABOVE those that already separate rows inside one 256-byte
+        // turn of the banks (16 / CPR rows): the 8-byte writes of 32 rows then fall on 16 different bank pairs instead
+        // of 4 (64-byte rows) or 8 (128-byte rows), and the 16-byte reads of whole rows stay conflict free.
+        constexpr int RSH = CPR == 4 ? 2 : (CPR == 8 ? 1 : 0);
         const int mt0 = m0 + (wm * TM + tm) * 32;  // first row of this 32-row slab
 #pragma unroll
         for (int tn = TN0; tn < TN0 + GS; ++tn)
@@ -1153,13 +1173,13 @@ void gemm_kernel(const GemmArgs g) {
                     }
                 }
                 const int chunk = (tn - TN0) * 4 + q;
-                *(half4*)(ep + l31 * (CPR * 16) + (((chunk ^ l31) & (CPR - 1)) << 4) + kb * 8) = o;
+                *(half4*)(ep + l31 * (CPR * 16) + (((chunk ^ (l31 >> RSH)) & (CPR - 1)) << 4) + kb * 8) = o;
             }
         __builtin_amdgcn_wave_barrier();
 #pragma unroll
         for (int i = 0; i < 32 / ROWS_PER_PASS; ++i) {
             const int row = i * ROWS_PER_PASS + lane / CPR, c = lane % CPR;
-            const uint4v v = *(const uint4v*)(ep + row * (CPR * 16) + (((c ^ row) & (CPR - 1)) << 4));
+            const uint4v v = *(const uint4v*)(ep + row * (CPR * 16) + (((c ^ (row >> RSH)) & (CPR - 1)) << 4));
             const int m = mt0 + row, n = nw0 + TN0 * 32 + c * 8;
             if (m < g.M && n < g.N) {
                 long yr = m;
