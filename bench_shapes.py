@@ -79,7 +79,8 @@ def main():
     if not args.no_peaks:
         mpk = mq.machine_peaks()
         print(f"# measured on this machine: int8 MFMA {mpk['int8_TOPs']:.0f} TOP/s, fp16 MFMA {mpk['f16_TFLOPs']:.0f} TFLOP/s, "
-              f"read-only stream {mpk['read_GBps']:.0f} GB/s, LDS reads {mpk['lds_read_TBps']:.1f} TB/s; matrix and vector "
+              f"read-only stream {mpk['read_GBps']:.0f} GB/s, LDS reads {mpk['lds_read_TBps']:.1f} TB/s, L2 -> LDS copies "
+              f"{mpk['l2_to_lds_TBps']:.1f} TB/s; matrix and vector "
               f"instructions together take {mpk['serial_share_same_wave']:.2f} (one wave) / {mpk['serial_share_two_waves']:.2f} "
               f"(two waves of a SIMD) of the sum of their separate times (0.50 = full overlap, 1.00 = none)")
         torch.cuda.empty_cache()
@@ -183,6 +184,8 @@ def main():
         stacked_qkv(mq, torch, min(args.iters, 120))
     if not only or "kvall" in only:
         all_kv_projections(mq, torch, min(args.iters, 40))
+    if not only or "c4" in only or "boserr" in only:
+        bos_error_report(mq, torch)
 
 
 def ff_pairs(mq, torch, iters, overhead_us):
@@ -344,6 +347,31 @@ def stacked_qkv(mq, torch, iters):
             torch.cuda.empty_cache()
 
 
+
+
+def bos_error_report(mq, torch):
+    """What keeping the BOS row out of activation quantisation buys at the eight-prompt size: output error on tokens
+    1..76 of the BOS-aware call and of the naive all-row call, both against the unquantised layer (fp16 weights, fp32
+    accumulation: the library's own 16-bit path), as relative Frobenius error.  Weight bit-width 8 (symmetric) and 4."""
+    import synth_inputs as si
+    dev = torch.device("cuda:0")
+    B, T, K = 8, 77, 2048
+    ctx = torch.from_numpy(si.bos_context_f16(0, "c4/ctx", B, T, K)).to(dev)
+    print("\n# BOS-aware against naive all-row activation quantisation, eight prompts [8,77,2048]: relative Frobenius error on "
+          "tokens 1..76 against the unquantised layer; activation scale of each")
+    print(f"{'N':>6s} {'w bits':>7s}{'err BOS-aware':>15s}{'err naive':>12s}{'ratio':>8s}{'s_x BOS-aware':>15s}{'s_x naive':>11s}")
+    for N in (640, 1280):
+        w = torch.from_numpy(si.weights_f16(0, f"c4/w{N}", N, K)).to(dev)
+        ref = mq.qlinear_w_only(ctx.view(B * T, K), mq.keep_weights_16bit(w)).view(B, T, N)[:, 1:].float()
+        for bits, sym in ((8, True), (4, False)):
+            c, s_, z = mq.quantize_weights(w, bits, sym)
+            p, cs = mq.pack_weights(c, bits, mq.LAYOUT_KERNEL, codes_signed=sym)
+            pw = mq.PackedWeight(p, s_, z, cs, N, K, bits, mq.LAYOUT_KERNEL, sym)
+            y1, (s1, _) = mq.bos_aware_kv_proj(ctx, pw, w_f16=w, want_act=True)
+            y2, (s2, _) = mq.bos_aware_kv_proj(ctx, pw, naive_all_rows=True, want_act=True)
+            e1 = ((y1[:, 1:].float() - ref).norm() / ref.norm()).item()
+            e2 = ((y2[:, 1:].float() - ref).norm() / ref.norm()).item()
+            print(f"{N:6d} {bits:7d}{e1:15.4f}{e2:12.4f}{e2 / e1:8.1f}{s1.item():15.5f}{s2.item():11.5f}", flush=True)
 
 
 def all_kv_projections(mq, torch, iters):

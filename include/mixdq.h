@@ -113,6 +113,8 @@ int mq_prof_copy(void* dst, const void* src, size_t bytes, void* stream);
  *   4  the MFMA waves of 0 and the ALU waves of 2 side by side, one of each on every SIMD
  *   5  read-only stream over buf: buf_bytes - 4096 bytes read
  *   6  LDS reads (ds_read_b128, the GEMMs' swizzled row pattern): 1024 workgroups x 4 waves x 4000 x 8 KiB
+ *   7  L2 -> LDS copies (the LDS-writing buffer loads of the GEMMs' operand pipeline) out of the first 2 MiB of buf
+ *      (buf_bytes >= 2 MiB), which stay in every XCD's L2: 768 workgroups x 4 waves x 2048 x 8 KiB
  * Kinds 2 to 4 show how far matrix and vector instructions overlap on one SIMD. */
 int mq_prof_microbench(int kind, void* buf, size_t buf_bytes, double* ms_host, void* stream);
 

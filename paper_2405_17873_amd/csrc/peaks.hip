@@ -126,6 +126,36 @@ __global__ __launch_bounds__(256) void lds_read_kernel(int iters, uint32_t* out)
 
 static constexpr int kLdsIters = 4000;
 
+// L2 -> LDS rate: what the GEMMs' operand pipeline can draw at best.  Every wave copies 1 KB pieces (16 bytes per
+// lane, the LDS-writing buffer load of the GEMMs) from a region small enough to stay in the L2 of every XCD (2 MiB)
+// into its workgroup's LDS, 8 loads in flight per wave, three workgroups of 4 waves per compute unit.
+static constexpr int kFillIters = 2048;  // rounds of 8 loads per wave
+__global__ __launch_bounds__(256) void l2_to_lds_kernel(const uint8_t* __restrict__ src, uint32_t region_bytes, int iters) {
+    __shared__ __attribute__((aligned(16))) uint8_t lds[32768];
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    const uint64_t a = (uint64_t)(uintptr_t)src;
+    typedef int int4s __attribute__((ext_vector_type(4)));
+    int4s rsrc;
+    rsrc[0] = __builtin_amdgcn_readfirstlane((int)(uint32_t)a);
+    rsrc[1] = __builtin_amdgcn_readfirstlane((int)(uint32_t)((a >> 32) & 0xFFFFu));
+    rsrc[2] = __builtin_amdgcn_readfirstlane((int)region_bytes);
+    rsrc[3] = 0x00020000;
+    const uint32_t lds_wave = (uint32_t)(uintptr_t)lds + wv * 8192;
+    uint32_t off = ((blockIdx.x * 4 + wv) * 8192u) % region_bytes;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const uint32_t m0 = __builtin_amdgcn_readfirstlane(lds_wave + j * 1024);
+            const int voff = (int)((off + j * 1024u) % region_bytes) + lane * 16;
+            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds" ::"s"(m0), "v"(voff), "s"(rsrc) : "memory");
+        }
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        off = (off + 8192u * 4u * 97u) % region_bytes;  // another piece of the region every round
+    }
+    __syncthreads();
+    if (lds[threadIdx.x] == 0xA5 && src[0] == 0x5A) ((volatile uint8_t*)lds)[0] = 1;
+}
+
 // kind                           work of the one kernel launch
 //  0  int8 MFMA only             512 workgroups x 4 waves x kMfmaIters x 4 MFMAs x 65536 operations
 //  1  fp16 MFMA only             ... x 32768 operations
@@ -134,9 +164,11 @@ static constexpr int kLdsIters = 4000;
 //  4  int8 MFMA waves and vector ALU waves side by side on every SIMD: the work of 0 plus 2
 //  5  read-only stream over buf (buf_bytes, at least 1 GiB to defeat the last-level cache): buf_bytes read
 //  6  LDS reads: 1024 workgroups x 4 waves x kLdsIters x 8 KB
+//  7  L2 -> LDS: 768 workgroups x 4 waves x kFillIters x 8 KB copied from the first 2 MiB of buf into LDS
 // Returns elapsed milliseconds (best of five) in *ms_host.
 int prof_microbench(int kind, void* buf, size_t buf_bytes, double* ms_host, hipStream_t st) {
-    if (!ms_host || kind < 0 || kind > 6) return MQ_ERR_BAD_ARG;
+    if (!ms_host || kind < 0 || kind > 7) return MQ_ERR_BAD_ARG;
+    if (kind == 7 && buf_bytes < (2u << 20)) return MQ_ERR_BAD_ARG;
     if (!buf || buf_bytes < 4096 || (uintptr_t)buf % 16) return MQ_ERR_BAD_ARG;
     hipEvent_t a, b;
     if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) return MQ_ERR_HIP;
@@ -155,8 +187,12 @@ int prof_microbench(int kind, void* buf, size_t buf_bytes, double* ms_host, hipS
                 hipLaunchKernelGGL(read_stream_kernel, dim3(4096), dim3(256), 0, st, (const uint4v*)buf + 256,
                                    (buf_bytes - 4096) / 16, (uint32_t*)buf);
                 break;
-            default:
+            case 6:
                 hipLaunchKernelGGL(lds_read_kernel, dim3(1024), dim3(256), 0, st, rep == 0 ? 16 : kLdsIters, (uint32_t*)buf);
+                break;
+            default:
+                hipLaunchKernelGGL(l2_to_lds_kernel, dim3(768), dim3(256), 0, st, (const uint8_t*)buf, 2u << 20,
+                                   rep == 0 ? 16 : kFillIters);
         }
         if (hipGetLastError() != hipSuccess) rc = MQ_ERR_HIP;
         (void)hipEventRecord(b, st);
