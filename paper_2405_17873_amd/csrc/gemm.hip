@@ -1077,20 +1077,31 @@ void gemm_kernel(const GemmArgs g) {
         }
     } else {
     static_assert(TN == 1 || TN == 2 || TN == 4, "channel tiles per wave: 1, 2 or 4");
-    constexpr int G0 = TN >= 4 ? 4 : TN;         // channel tiles staged at a time
-    constexpr int EP_BYTES = 32 * G0 * 64;       // staging bytes per storing wave
-    static_assert((SPLIT_EPI ? NW : P::NWG) * EP_BYTES <= S * STAGE_BYTES, "epilogue staging must fit the LDS stages");
-    uint8_t* ep = lds + (SPLIT_EPI ? wv : wvg) * EP_BYTES;
+    constexpr int EP_BYTES = 32 * TN * 64;          // staging bytes of one 32-row slab of a wave
+    constexpr int EW = SPLIT_EPI ? NW : P::NWG;     // storing waves
+    // Where the idle stages have the room, a wave stages all its slabs at once: the per-channel constants of a
+    // register quad are then read from LDS once and serve every slab (a wave that reads them again for each slab
+    // spends most of its epilogue waiting for LDS), and one pass of stores follows one pass of conversions.
+    constexpr bool ALL_SLABS = KS == 1 && !RES && EW * TM * EP_BYTES <= S * STAGE_BYTES;
+    constexpr int WAVE_EP = ALL_SLABS ? TM * EP_BYTES : EP_BYTES;
+    static_assert(EW * WAVE_EP <= S * STAGE_BYTES, "epilogue staging must fit the LDS stages");
+    uint8_t* ep = lds + (SPLIT_EPI ? wv : wvg) * WAVE_EP;
     const int nw0 = n0 + wn * TN * 32;  // first channel of this wave
+    constexpr int CPR = TN * 4;              // 16-byte chunks per staged row
+    constexpr int ROWS_PER_PASS = 64 / CPR;  // rows one store instruction covers
+    // The chunk index is XOR-ed with the row bits ABOVE those that already separate rows inside one 256-byte
+    // turn of the banks (16 / CPR rows): the 8-byte writes of 32 rows then fall on 16 different bank pairs instead
+    // of 4 (64-byte rows) or 8 (128-byte rows), and the 16-byte reads of whole rows stay conflict free.
+    constexpr int RSH = CPR == 4 ? 2 : (CPR == 8 ? 1 : 0);
 
     // Residual pieces arrive in the accumulator layout (8 bytes per lane: four channels of the lane's row), all of a
     // 32-row slab at once and, where a wave stores several slabs, one slab ahead of the stores.
-    auto load_res = [&](int tm, half4 (&dst)[G0][4]) {
+    auto load_res = [&](int tm, half4 (&dst)[TN][4]) {
         const int m = m0 + (wm * TM + tm) * 32 + l31;
         long rr = m;
         if constexpr (I8) rr = g.out_map.phys(m);
 #pragma unroll
-        for (int tn = 0; tn < G0; ++tn)
+        for (int tn = 0; tn < TN; ++tn)
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
                 const int n = nw0 + tn * 32 + 8 * q + 4 * kb;
@@ -1107,105 +1118,145 @@ void gemm_kernel(const GemmArgs g) {
     // RES: a residual operand is present.  A kernel of its own, so that calls without one pay nothing for it.
     constexpr bool has_res = RES;
 
-    auto store_cols = [&](auto tn0_c, auto gs_c, int tm, const half4 (&rs)[G0][4]) {
-        constexpr int TN0 = decltype(tn0_c)::value, GS = decltype(gs_c)::value;
-        constexpr int CPR = GS * 4;              // 16-byte chunks per staged row
-        constexpr int ROWS_PER_PASS = 64 / CPR;  // rows one store instruction covers
-        // The chunk index is XOR-ed with the row bits ABOVE those that already separate rows inside one 256-byte
-        // turn of the banks (16 / CPR rows): the 8-byte writes of 32 rows then fall on 16 different bank pairs instead
-        // of 4 (64-byte rows) or 8 (128-byte rows), and the 16-byte reads of whole rows stay conflict free.
-        constexpr int RSH = CPR == 4 ? 2 : (CPR == 8 ? 1 : 0);
+    // The constants of result quad q of channel tile tn: four consecutive channels.
+    struct QuadConst {
+        float4v mul, add;
+        int4v dw, cn;
+    };
+    auto quad_const = [&](int tn, int q) {
+        const int cl = (wn * TN + tn) * 32 + 8 * q + 4 * kb;  // channel inside the workgroup tile
+        QuadConst k;
+        k.mul = *(const float4v*)(ch_mul + cl);
+        k.add = *(const float4v*)(ch_add + cl);
+        if constexpr (I8) {
+            k.dw = *(const int4v*)(ch_dw + cl);
+            k.cn = *(const int4v*)(ch_cn + cl);
+        }
+        return k;
+    };
+    // Finishes result quad q of tile (tm, tn) and writes it into the slab image at `slab`.
+    auto finish_quad = [&](uint8_t* slab, int tm, int tn, int q, const QuadConst& k, const half4& rq) {
+        const int cl = (wn * TN + tn) * 32 + 8 * q + 4 * kb;
         const int mt0 = m0 + (wm * TM + tm) * 32;  // first row of this 32-row slab
+        float4v add = k.add;
+        if constexpr (has_res) {  // joins the bias term
 #pragma unroll
-        for (int tn = TN0; tn < TN0 + GS; ++tn)
+            for (int r = 0; r < 4; ++r) add[r] += res_f32(rq[r]);
+        }
+        half4 o;
+        if constexpr (I8) {
+            int4v a;
+            int4v border = {0, 0, 0, 0};
+            if constexpr (MODE == 4) {
+                // Convolution: a filter tap outside the image reads zero bytes, which stand for the code
+                // 128, not for the value 0 (code z_x).  The constant term cn counts every tap; take back
+                // dx * sum_c (q_w - z_w) of the taps this pixel does not have.
+                const uint32_t have = tap_mask(mt0 + l31);
+                if (have != 0x1FFu) {
+                    const int n_real = n0 + cl;
+                    const int dxv = 128 - *g.act_zp_p;
+                    const int cin = g.conv_cpt * 64;
+                    for (int t = 0; t < 9; ++t) {
+                        if (have >> t & 1u) continue;
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const int cl = (wn * TN + tn) * 32 + 8 * q + 4 * kb;  // channel inside the workgroup tile
-                const float4v mul = *(const float4v*)(ch_mul + cl);
-                float4v add = *(const float4v*)(ch_add + cl);
-                if constexpr (has_res) {  // joins the bias term
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) add[r] += res_f32(rs[tn - TN0][q][r]);
-                }
-                half4 o;
-                if constexpr (I8) {
-                    const int4v dw = *(const int4v*)(ch_dw + cl);
-                    const int4v cn = *(const int4v*)(ch_cn + cl);
-                    int4v a;
-                    int4v border = {0, 0, 0, 0};
-                    if constexpr (MODE == 4) {
-                        // Convolution: a filter tap outside the image reads zero bytes, which stand for the code
-                        // 128, not for the value 0 (code z_x).  The constant term cn counts every tap; take back
-                        // dx * sum_c (q_w - z_w) of the taps this pixel does not have.
-                        const uint32_t have = tap_mask(mt0 + l31);
-                        if (have != 0x1FFu) {
-                            const int n_real = n0 + cl;
-                            const int dxv = 128 - *g.act_zp_p;
-                            const int cin = g.conv_cpt * 64;
-                            for (int t = 0; t < 9; ++t) {
-                                if (have >> t & 1u) continue;
-#pragma unroll
-                                for (int r = 0; r < 4; ++r) {
-                                    const int n = n_real + r < g.N ? n_real + r : g.N - 1;
-                                    border[r] += dxv * (g.w_tapsum[t * g.N + n] - cin * (g.w_off - dw[r]));
-                                }
-                            }
+                        for (int r = 0; r < 4; ++r) {
+                            const int n = n_real + r < g.N ? n_real + r : g.N - 1;
+                            border[r] += dxv * (g.w_tapsum[t * g.N + n] - cin * (g.w_off - k.dw[r]));
                         }
                     }
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) {
-                        // |dw| <= 255 and |rowsum| <= 128 * K < 2^23: a 24-bit multiply (full rate) is exact
-                        a[r] = acc[tm][tn][4 * q + r] + __mul24(dw[r], rsum[tm]) + cn[r] - border[r];
-                        o[r] = (_Float16)((float)a[r] * mul[r] + add[r]);
-                    }
-                    if (g.acc_debug) {
-                        const int m = mt0 + l31, n_real = n0 + cl;
-                        if (m < g.M && n_real < g.N) *(int4v*)(g.acc_debug + (long)m * g.N + n_real) = a;
-                    }
-                } else {
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) {
-                        const float v = acc[tm][tn][4 * q + r] * mul[r] + add[r];
-                        if constexpr (BF)
-                            o[r] = __builtin_bit_cast(_Float16, float_to_bf16_bits(v));  // bits only
-                        else
-                            o[r] = (_Float16)v;
-                    }
                 }
-                const int chunk = (tn - TN0) * 4 + q;
-                *(half4*)(ep + l31 * (CPR * 16) + (((chunk ^ (l31 >> RSH)) & (CPR - 1)) << 4) + kb * 8) = o;
             }
-        __builtin_amdgcn_wave_barrier();
 #pragma unroll
-        for (int i = 0; i < 32 / ROWS_PER_PASS; ++i) {
-            const int row = i * ROWS_PER_PASS + lane / CPR, c = lane % CPR;
-            const uint4v v = *(const uint4v*)(ep + row * (CPR * 16) + (((c ^ (row >> RSH)) & (CPR - 1)) << 4));
-            const int m = mt0 + row, n = nw0 + TN0 * 32 + c * 8;
-            if (m < g.M && n < g.N) {
-                long yr = m;
-                if constexpr (I8) yr = g.out_map.phys(m);
-                // Streaming store: the output is not read again by this kernel, and a line that is written through as
-                // it is produced does not wait in the XCD's L2 for the write-back at the end of the kernel (worth 7 %
-                // of the dominant kernel's time).
-                __builtin_nontemporal_store(v, (uint4v*)(g.y + yr * g.ldy + n));
+            for (int r = 0; r < 4; ++r) {
+                // |dw| <= 255 and |rowsum| <= 128 * K < 2^23: a 24-bit multiply (full rate) is exact
+                a[r] = acc[tm][tn][4 * q + r] + __mul24(k.dw[r], rsum[tm]) + k.cn[r] - border[r];
+                o[r] = (_Float16)((float)a[r] * k.mul[r] + add[r]);
+            }
+            if (g.acc_debug) {
+                const int m = mt0 + l31, n_real = n0 + cl;
+                if (m < g.M && n_real < g.N) *(int4v*)(g.acc_debug + (long)m * g.N + n_real) = a;
+            }
+        } else {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const float v = acc[tm][tn][4 * q + r] * k.mul[r] + add[r];
+                if constexpr (BF)
+                    o[r] = __builtin_bit_cast(_Float16, float_to_bf16_bits(v));  // bits only
+                else
+                    o[r] = (_Float16)v;
             }
         }
-        __builtin_amdgcn_wave_barrier();
+        const int chunk = tn * 4 + q;
+        *(half4*)(slab + l31 * (CPR * 16) + (((chunk ^ (l31 >> RSH)) & (CPR - 1)) << 4) + kb * 8) = o;
     };
-    constexpr bool RES_AHEAD = KS == 1 && TM > 1;
-    half4 rs[2][G0][4] = {};
-    if constexpr (RES_AHEAD && has_res) load_res(0, rs[0]);
+    // Reads the slab image back as 16 bytes per lane along rows and stores it: CPR lanes cover one contiguous row
+    // segment of TN * 64 bytes.  All reads are requested before the first store (a store that waits for its own read
+    // pays the LDS latency every time), and with the identity row map the addresses advance by a constant.
+    auto store_slab = [&](const uint8_t* slab, int tm) {
+        constexpr int NP = 32 / ROWS_PER_PASS;
+        const int r0 = lane / CPR, c = lane % CPR;
+        const int m_first = m0 + (wm * TM + tm) * 32 + r0, n = nw0 + c * 8;
+        uint4v v[NP];
 #pragma unroll
-    for (int tm = 0; tm < TM; ++tm) {
-        if (KS > 1 && owner(tm) != grp) continue;  // the finished sums of this slab live in the other group
-        if constexpr (has_res) {
-            if constexpr (RES_AHEAD) {
-                if (tm + 1 < TM) load_res(tm + 1, rs[(tm + 1) & 1]);
-            } else {
-                load_res(tm, rs[tm & 1]);
+        for (int i = 0; i < NP; ++i) {
+            const int row = i * ROWS_PER_PASS + r0;
+            v[i] = *(const uint4v*)(slab + row * (CPR * 16) + (((c ^ (row >> RSH)) & (CPR - 1)) << 4));
+        }
+        if (n >= g.N) return;
+        // Streaming stores: the output is not read again by this kernel, and a line that is written through as it is
+        // produced does not wait in the XCD's L2 for the write-back at the end of the kernel (worth 7 % of the
+        // dominant kernel's time).
+        bool identity = true;
+        if constexpr (I8) identity = g.out_map.rows_per_group <= 0;
+        if (identity) {
+            uint16_t* yp = g.y + (long)m_first * g.ldy + n;
+            const long step = (long)ROWS_PER_PASS * g.ldy;
+#pragma unroll
+            for (int i = 0; i < NP; ++i)
+                if (m_first + i * ROWS_PER_PASS < g.M) __builtin_nontemporal_store(v[i], (uint4v*)(yp + i * step));
+        } else {
+#pragma unroll
+            for (int i = 0; i < NP; ++i) {
+                const int m = m_first + i * ROWS_PER_PASS;
+                if (m < g.M) __builtin_nontemporal_store(v[i], (uint4v*)(g.y + g.out_map.phys(m) * g.ldy + n));
             }
         }
-        store_cols(std::integral_constant<int, 0>{}, std::integral_constant<int, G0>{}, tm, rs[tm & 1]);
+    };
+    if constexpr (ALL_SLABS) {
+        const half4 none = {0, 0, 0, 0};
+#pragma unroll
+        for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const QuadConst k = quad_const(tn, q);
+#pragma unroll
+                for (int tm = 0; tm < TM; ++tm) finish_quad(ep + tm * EP_BYTES, tm, tn, q, k, none);
+            }
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int tm = 0; tm < TM; ++tm) store_slab(ep + tm * EP_BYTES, tm);
+    } else {
+        constexpr bool RES_AHEAD = KS == 1 && TM > 1;
+        half4 rs[2][TN][4] = {};
+        if constexpr (RES_AHEAD && has_res) load_res(0, rs[0]);
+#pragma unroll
+        for (int tm = 0; tm < TM; ++tm) {
+            if (KS > 1 && owner(tm) != grp) continue;  // the finished sums of this slab live in the other group
+            if constexpr (has_res) {
+                if constexpr (RES_AHEAD) {
+                    if (tm + 1 < TM) load_res(tm + 1, rs[(tm + 1) & 1]);
+                } else {
+                    load_res(tm, rs[tm & 1]);
+                }
+            }
+#pragma unroll
+            for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) finish_quad(ep, tm, tn, q, quad_const(tn, q), rs[tm & 1][tn][q]);
+            __builtin_amdgcn_wave_barrier();
+            store_slab(ep, tm);
+            __builtin_amdgcn_wave_barrier();
+        }
     }
     }
     if (g.phase_clk && threadIdx.x == 0) {
