@@ -1134,26 +1134,18 @@ void gemm_kernel(const GemmArgs g) {
         }
         return k;
     };
-    // Finishes result quad q of tile (tm, tn) and writes it into the slab image at `slab`.
-    auto finish_quad = [&](uint8_t* slab, int tm, int tn, int q, const QuadConst& k, const half4& rq) {
-        const int cl = (wn * TN + tn) * 32 + 8 * q + 4 * kb;
-        const int mt0 = m0 + (wm * TM + tm) * 32;  // first row of this 32-row slab
-        float4v add = k.add;
-        if constexpr (has_res) {  // joins the bias term
-#pragma unroll
-            for (int r = 0; r < 4; ++r) add[r] += res_f32(rq[r]);
-        }
-        half4 o;
+    // int8 path: the exact integer sums of result quad q of tile (tm, tn) with both zero-point corrections.
+    auto int_quad = [&](int tm, int tn, int q, const QuadConst& k) {
+        int4v a = {0, 0, 0, 0};
         if constexpr (I8) {
-            int4v a;
             int4v border = {0, 0, 0, 0};
             if constexpr (MODE == 4) {
                 // Convolution: a filter tap outside the image reads zero bytes, which stand for the code
                 // 128, not for the value 0 (code z_x).  The constant term cn counts every tap; take back
                 // dx * sum_c (q_w - z_w) of the taps this pixel does not have.
-                const uint32_t have = tap_mask(mt0 + l31);
+                const uint32_t have = tap_mask(m0 + (wm * TM + tm) * 32 + l31);
                 if (have != 0x1FFu) {
-                    const int n_real = n0 + cl;
+                    const int n_real = n0 + (wn * TN + tn) * 32 + 8 * q + 4 * kb;
                     const int dxv = 128 - *g.act_zp_p;
                     const int cin = g.conv_cpt * 64;
                     for (int t = 0; t < 9; ++t) {
@@ -1167,15 +1159,24 @@ void gemm_kernel(const GemmArgs g) {
                 }
             }
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
+            for (int r = 0; r < 4; ++r)
                 // |dw| <= 255 and |rowsum| <= 128 * K < 2^23: a 24-bit multiply (full rate) is exact
                 a[r] = acc[tm][tn][4 * q + r] + __mul24(k.dw[r], rsum[tm]) + k.cn[r] - border[r];
-                o[r] = (_Float16)((float)a[r] * k.mul[r] + add[r]);
-            }
-            if (g.acc_debug) {
-                const int m = mt0 + l31, n_real = n0 + cl;
-                if (m < g.M && n_real < g.N) *(int4v*)(g.acc_debug + (long)m * g.N + n_real) = a;
-            }
+        }
+        return a;
+    };
+    // Finishes result quad q of tile (tm, tn) and writes it into the slab image at `slab`.
+    auto finish_quad = [&](uint8_t* slab, int tm, int tn, int q, const QuadConst& k, const half4& rq) {
+        float4v add = k.add;
+        if constexpr (has_res) {  // joins the bias term
+#pragma unroll
+            for (int r = 0; r < 4; ++r) add[r] += res_f32(rq[r]);
+        }
+        half4 o;
+        if constexpr (I8) {
+            const int4v a = int_quad(tm, tn, q, k);
+#pragma unroll
+            for (int r = 0; r < 4; ++r) o[r] = (_Float16)((float)a[r] * k.mul[r] + add[r]);
         } else {
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
@@ -1189,6 +1190,25 @@ void gemm_kernel(const GemmArgs g) {
         const int chunk = tn * 4 + q;
         *(half4*)(slab + l31 * (CPR * 16) + (((chunk ^ (l31 >> RSH)) & (CPR - 1)) << 4) + kb * 8) = o;
     };
+    // The integer sums themselves, for the tests that pin them (a pass of its own: the ordinary epilogue carries no
+    // trace of it).
+    if constexpr (I8) {
+        if (g.acc_debug) {
+#pragma unroll
+            for (int tm = 0; tm < TM; ++tm) {
+                if (KS > 1 && owner(tm) != grp) continue;
+                const int m = m0 + (wm * TM + tm) * 32 + l31;
+#pragma unroll
+                for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const int n_real = n0 + (wn * TN + tn) * 32 + 8 * q + 4 * kb;
+                        const int4v a = int_quad(tm, tn, q, quad_const(tn, q));
+                        if (m < g.M && n_real < g.N) *(int4v*)(g.acc_debug + (long)m * g.N + n_real) = a;
+                    }
+            }
+        }
+    }
     // Reads the slab image back as 16 bytes per lane along rows and stores it: CPR lanes cover one contiguous row
     // segment of TN * 64 bytes.  All reads are requested before the first store (a store that waits for its own read
     // pays the LDS latency every time), and with the identity row map the addresses advance by a constant.
