@@ -80,9 +80,10 @@ def main():
         mpk = mq.machine_peaks()
         print(f"# measured on this machine: int8 MFMA {mpk['int8_TOPs']:.0f} TOP/s, fp16 MFMA {mpk['f16_TFLOPs']:.0f} TFLOP/s, "
               f"read-only stream {mpk['read_GBps']:.0f} GB/s, LDS reads {mpk['lds_read_TBps']:.1f} TB/s, L2 -> LDS copies "
-              f"{mpk['l2_to_lds_TBps']:.1f} TB/s; matrix and vector "
+              f"{mpk['l2_to_lds_TBps']:.1f} TB/s; 8 vector instructions per MFMA: matrix and vector "
               f"instructions together take {mpk['serial_share_same_wave']:.2f} (one wave) / {mpk['serial_share_two_waves']:.2f} "
-              f"(two waves of a SIMD) of the sum of their separate times (0.50 = full overlap, 1.00 = none)")
+              f"(two waves of a SIMD) of the sum of their separate times (0.50 = full overlap, 1.00 = none); 4 per MFMA: "
+              f"{mpk['four_valu_per_mfma_over_mfma_only']:.2f} of the time of the MFMAs alone")
         torch.cuda.empty_cache()
     m_hbm = mpk["read_GBps"] * 1e9 if mpk else 0.0
     m_peak = {"w": mpk["f16_TFLOPs"] * 1e12, "a": mpk["int8_TOPs"] * 1e12} if mpk else {"w": 0.0, "a": 0.0}

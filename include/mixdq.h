@@ -115,7 +115,9 @@ int mq_prof_copy(void* dst, const void* src, size_t bytes, void* stream);
  *   6  LDS reads (ds_read_b128, the GEMMs' swizzled row pattern): 1024 workgroups x 4 waves x 4000 x 8 KiB
  *   7  L2 -> LDS copies (the LDS-writing buffer loads of the GEMMs' operand pipeline) out of the first 2 MiB of buf
  *      (buf_bytes >= 2 MiB), which stay in every XCD's L2: 768 workgroups x 4 waves x 2048 x 8 KiB
- * Kinds 2 to 4 show how far matrix and vector instructions overlap on one SIMD. */
+ *   8  as 3 with 4 ALU instructions behind every MFMA instead of 8
+ * Kinds 2 to 4 and 8 show how far matrix and vector instructions overlap on one SIMD: how many vector instructions
+ * fit under a 32-cycle MFMA before they cost time of their own. */
 int mq_prof_microbench(int kind, void* buf, size_t buf_bytes, double* ms_host, void* stream);
 
 /* Phase timing inside the GEMM kernels: while clk != NULL every GEMM launch with at most `workgroups` workgroups

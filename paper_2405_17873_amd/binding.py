@@ -105,13 +105,15 @@ def prof_microbench(kind: int, buf: torch.Tensor) -> float:
 
 def machine_peaks(buf: Optional[torch.Tensor] = None) -> dict:
     """Measured rates of this machine: int8 and fp16 MFMA (T(FL)OP/s), read-only stream (GB/s), LDS reads and L2 -> LDS
-    copies (bytes per second over the chip), and the overlap of matrix and vector instructions on a SIMD: elapsed time of both kinds of
-    work together divided by the sum of their separate times (0.5 = perfect overlap of equal halves, 1.0 = none), in
-    one wave and in two waves of one SIMD."""
+    copies (bytes per second over the chip), and the overlap of matrix and vector instructions on a SIMD: with 8 vector
+    instructions per MFMA (as many cycles as the MFMA itself) the elapsed time of both kinds of work together divided
+    by the sum of their separate times (0.5 = perfect overlap of equal halves, 1.0 = none), in one wave and in two
+    waves of one SIMD; and with 4 vector instructions per MFMA the elapsed time divided by that of the MFMAs alone
+    (1.0: the vector instructions are hidden completely)."""
     if buf is None:
         buf = torch.empty(2 << 30, dtype=torch.uint8, device="cuda")
     small = buf[:4 << 20]
-    t = {k: prof_microbench(k, small if k != 5 else buf) for k in range(8)}
+    t = {k: prof_microbench(k, small if k != 5 else buf) for k in range(9)}
     n_mfma = 512 * 4 * 4096 * 4
     return {
         "int8_TOPs": n_mfma * 65536.0 / (t[0] * 1e-3) / 1e12,
@@ -121,6 +123,7 @@ def machine_peaks(buf: Optional[torch.Tensor] = None) -> dict:
         "l2_to_lds_TBps": 768 * 4 * 2048 * 8192.0 / (t[7] * 1e-3) / 1e12,
         "mfma_ms": t[0], "valu_ms": t[2], "same_wave_ms": t[3], "two_waves_ms": t[4],
         "serial_share_same_wave": t[3] / (t[0] + t[2]), "serial_share_two_waves": t[4] / (t[0] + t[2]),
+        "four_valu_per_mfma_ms": t[8], "four_valu_per_mfma_over_mfma_only": t[8] / t[0],
     }
 
 

@@ -717,8 +717,9 @@ void gemm_kernel(const GemmArgs g) {
         if (s < KT) issue(s, s);
     if (g.phase_clk) t1 = clock64();
 
-    // Main loop.  On this hardware an LDS read into registers, a vector ALU instruction and an MFMA take turns on
-    // the SIMD, and a workgroup has one wave per SIMD, so every latency has to be covered by the wave's own MFMAs:
+    // Main loop.  A 32-cycle MFMA leaves room for about five vector ALU instructions on its SIMD (measured: four
+    // behind every MFMA cost nothing, eight cost 37 % more time than the MFMAs alone), and a workgroup has one wave
+    // per SIMD, so the widening work is spread between the MFMAs and every latency is covered by the wave's own MFMAs:
     //   * the activation fragments of steps 1..3 are requested one or two steps ahead (four register sets);
     //   * the hand-over to the next stage (wait for its loads, barrier, refill of the buffer just read, request of
     //     its first fragments) sits in the MIDDLE of a stage, after the last LDS read of the current stage has
@@ -1296,8 +1297,8 @@ void gemm_kernel(const GemmArgs g) {
 //   3: as 1 and 4: as 2, with a second wave group splitting k inside the workgroup (8 waves)
 //   5: 64x128, 4 waves (1x4) of 64x32, two or three LDS stages: the form of tile 1 that puts more workgroups on a
 //      compute unit
-// A tall wave tile pays: every widened weight fragment then feeds 4 MFMAs (measured: LDS reads into registers,
-// vector ALU instructions and MFMAs take turns on a SIMD, they do not overlap).  256x256 tiles with one wave per
+// A tall wave tile pays: every widened weight fragment then feeds 4 MFMAs (measured: an MFMA hides about five vector
+// ALU instructions on its SIMD; what a wave needs beyond that costs time of its own).  256x256 tiles with one wave per
 // SIMD and 128x128 tiles with two-wave workgroups were measured slower on every configured shape.
 // The number of LDS stages is the largest (<= 4; <= 8 for tile 2, whose problems are latency bound) that lets two
 // workgroups share a compute unit and keeps the hand-counted loads within the 6-bit vmcnt.

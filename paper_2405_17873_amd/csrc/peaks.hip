@@ -21,9 +21,10 @@ static constexpr int kValuPerIter = 32;  // vector ALU instructions a VALU wave 
 // One vector ALU instruction that the compiler can neither remove nor merge.
 __device__ __forceinline__ void valu_op(uint32_t& x, uint32_t y) { asm volatile("v_xor_b32 %0, %0, %1" : "+v"(x) : "v"(y)); }
 
-// ROLE of a wave: 1 = MFMA only, 2 = VALU only, 3 = both in one instruction stream (1 MFMA, then 8 VALU, ...), 0 = exit.
-// Per iteration: 4 independent MFMAs (128 cycles of the matrix pipe) and / or 32 vector ALU instructions (128 cycles).
-template <bool I8, int ROLE>
+// ROLE of a wave: 1 = MFMA only, 2 = VALU only, 3 = both in one instruction stream (1 MFMA, then NV VALU, ...), 0 = exit.
+// Per iteration: 4 independent MFMAs (128 cycles of the matrix pipe) and / or 4 * NV vector ALU instructions (NV = 8:
+// 128 cycles).
+template <bool I8, int ROLE, int NV = kValuPerIter / 4>
 __device__ __forceinline__ void role_loop(int iters, int* out) {
     if constexpr (ROLE == 0) return;
     int4v a = {(int)threadIdx.x, 1, 2, 3}, b = {3, 2, 1, (int)blockIdx.x};
@@ -59,7 +60,7 @@ __device__ __forceinline__ void role_loop(int iters, int* out) {
             }
             if constexpr ((ROLE & 2) != 0) {
 #pragma unroll
-                for (int v = 0; v < kValuPerIter / 4; ++v) valu_op(x[v], y);
+                for (int v = 0; v < NV; ++v) valu_op(x[v], y);
             }
             __builtin_amdgcn_sched_barrier(0);  // keep the order as written: MFMA, its share of the VALU work, next MFMA
         }
@@ -75,12 +76,12 @@ __device__ __forceinline__ void role_loop(int iters, int* out) {
 }
 
 // Waves 0..3 of the 512-thread workgroup take ROLE_LO, waves 4..7 ROLE_HI; wave w and wave w + 4 share a SIMD.
-template <bool I8, int ROLE_LO, int ROLE_HI>
+template <bool I8, int ROLE_LO, int ROLE_HI, int NV = kValuPerIter / 4>
 __global__ __launch_bounds__(512) void mfma_valu_kernel(int iters, int* out) {
     if (__builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6)) < 4)
-        role_loop<I8, ROLE_LO>(iters, out);
+        role_loop<I8, ROLE_LO, NV>(iters, out);
     else
-        role_loop<I8, ROLE_HI>(iters, out);
+        role_loop<I8, ROLE_HI, NV>(iters, out);
 }
 
 // Read-only stream: every lane reads 16 bytes x 8 per round, grid stride, nothing is written.
@@ -165,9 +166,10 @@ __global__ __launch_bounds__(256) void l2_to_lds_kernel(const uint8_t* __restric
 //  5  read-only stream over buf (buf_bytes, at least 1 GiB to defeat the last-level cache): buf_bytes read
 //  6  LDS reads: 1024 workgroups x 4 waves x kLdsIters x 8 KB
 //  7  L2 -> LDS: 768 workgroups x 4 waves x kFillIters x 8 KB copied from the first 2 MiB of buf into LDS
+//  8  as 3 with 4 instead of 8 vector ALU instructions behind every MFMA: the work of 0 plus half the work of 2
 // Returns elapsed milliseconds (best of five) in *ms_host.
 int prof_microbench(int kind, void* buf, size_t buf_bytes, double* ms_host, hipStream_t st) {
-    if (!ms_host || kind < 0 || kind > 7) return MQ_ERR_BAD_ARG;
+    if (!ms_host || kind < 0 || kind > 8) return MQ_ERR_BAD_ARG;
     if (kind == 7 && buf_bytes < (2u << 20)) return MQ_ERR_BAD_ARG;
     if (!buf || buf_bytes < 4096 || (uintptr_t)buf % 16) return MQ_ERR_BAD_ARG;
     hipEvent_t a, b;
@@ -190,6 +192,7 @@ int prof_microbench(int kind, void* buf, size_t buf_bytes, double* ms_host, hipS
             case 6:
                 hipLaunchKernelGGL(lds_read_kernel, dim3(1024), dim3(256), 0, st, rep == 0 ? 16 : kLdsIters, (uint32_t*)buf);
                 break;
+            case 8: hipLaunchKernelGGL((mfma_valu_kernel<true, 3, 0, 4>), dim3(kGrid), dim3(512), 0, st, it, (int*)buf); break;
             default:
                 hipLaunchKernelGGL(l2_to_lds_kernel, dim3(768), dim3(256), 0, st, (const uint8_t*)buf, 2u << 20,
                                    rep == 0 ? 16 : kFillIters);
