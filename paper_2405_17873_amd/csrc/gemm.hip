@@ -1245,14 +1245,16 @@ void gemm_kernel(const GemmArgs g) {
     };
     if constexpr (ALL_SLABS) {
         const half4 none = {0, 0, 0, 0};
+        // (the constants of the next quad are requested before the conversions of the current one: the compiler does
+        // not move an LDS read above the staging writes by itself)
+        QuadConst k = quad_const(0, 0);
 #pragma unroll
-        for (int tn = 0; tn < TN; ++tn)
+        for (int i = 0; i < TN * 4; ++i) {
+            const QuadConst kn = quad_const((i + 1 < TN * 4 ? i + 1 : i) >> 2, (i + 1 < TN * 4 ? i + 1 : i) & 3);
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const QuadConst k = quad_const(tn, q);
-#pragma unroll
-                for (int tm = 0; tm < TM; ++tm) finish_quad(ep + tm * EP_BYTES, tm, tn, q, k, none);
-            }
+            for (int tm = 0; tm < TM; ++tm) finish_quad(ep + tm * EP_BYTES, tm, i >> 2, i & 3, k, none);
+            k = kn;
+        }
         __builtin_amdgcn_wave_barrier();
 #pragma unroll
         for (int tm = 0; tm < TM; ++tm) store_slab(ep + tm * EP_BYTES, tm);
