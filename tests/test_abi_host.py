@@ -118,6 +118,24 @@ def test_error_codes_without_a_gpu(lib):
     assert lib.mq_bos_aware_kv_proj(*bos(B=0, wf=p)) == -2
 
 
+def test_microbenchmark_entry_rejects_bad_arguments_without_a_gpu(lib):
+    """mq_prof_microbench validates before it touches the device."""
+    buf = (C.c_uint8 * 8192)()
+    p = C.c_void_p((C.addressof(buf) + 255) // 256 * 256)
+    ms = C.c_double(-1.0)
+    st = C.c_void_p(0)
+    f = lib.mq_prof_microbench
+    f.argtypes = [C.c_int, C.c_void_p, C.c_size_t, C.POINTER(C.c_double), C.c_void_p]
+    assert f(-1, p, 4096, C.byref(ms), st) == -1
+    assert f(9, p, 4096, C.byref(ms), st) == -1          # kinds are 0..8
+    assert f(0, p, 4096, None, st) == -1                  # nowhere to write the time
+    assert f(0, None, 4096, C.byref(ms), st) == -1
+    assert f(0, p, 1024, C.byref(ms), st) == -1           # scratch below 4 KiB
+    assert f(0, C.c_void_p(p.value + 8), 4096, C.byref(ms), st) == -1   # not 16-byte aligned
+    assert f(7, p, 4096, C.byref(ms), st) == -1           # the L2 -> LDS kind needs 2 MiB to copy from
+    assert ms.value == -1.0
+
+
 def test_missing_library_is_loud(monkeypatch):
     from paper_2405_17873_amd import binding
     monkeypatch.setattr(binding, "_lib", None)

@@ -1181,3 +1181,17 @@ def test_one_prompt_through_many_stacked_projections(mq, orc):
     guard = torch.full((T + 8, N), 7.0, dtype=torch.float16, device="cuda")
     mq.qlinear_w_only(dev(x), pw, out=guard[:T])
     assert bool((guard[T:] == 7.0).all())
+
+
+def test_microbenchmarks_of_the_machine_report_plausible_rates(mq):
+    """The measured-peak columns of the per-shape report come from these kernels: every kind runs, and its rate lies
+    between a tenth of the published peak and the published peak (int8 5.0 POP/s, fp16 2.5 PFLOP/s, HBM 8 TB/s); four
+    vector instructions behind every MFMA cost less than eight."""
+    buf = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
+    pk = mq.machine_peaks(buf)
+    assert 500.0 < pk["int8_TOPs"] <= 5000.0
+    assert 250.0 < pk["f16_TFLOPs"] <= 2500.0
+    assert 800.0 < pk["read_GBps"] <= 8000.0
+    assert pk["lds_read_TBps"] > 10.0 and pk["l2_to_lds_TBps"] > 3.0
+    assert 0.5 <= pk["serial_share_same_wave"] <= 1.05 and 0.5 <= pk["serial_share_two_waves"] <= 1.05
+    assert pk["four_valu_per_mfma_ms"] < pk["same_wave_ms"]
