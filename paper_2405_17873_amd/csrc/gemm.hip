@@ -996,10 +996,10 @@ void gemm_kernel(const GemmArgs g) {
     // ---------------------------------------------------------------- epilogue
     // Result element v of a lane is channel 8*(v/4) + 4*kb + v%4 of its 32-channel tile, activation row l31:
     // four consecutive channels of ONE row per lane, so a direct store would scatter 8-byte pieces over 32 rows.
-    // Instead every wave transposes through its own slice of the (now idle) LDS stages, 32 rows and up to 4 channel
-    // tiles at a time: finished fp16 values are written as 8-byte pieces into a [32 rows][GS*32 channels] image
-    // (16-byte chunks XOR-swizzled by row), read back as 16 bytes per lane along rows, and stored with 4*GS lanes
-    // covering one contiguous row segment of GS*64 bytes.
+    // Instead every wave transposes through its own slice of the (now idle) LDS stages, in slabs of 32 rows by the
+    // wave's TN channel tiles: finished fp16 values are written as 8-byte pieces into a [32 rows][TN*32 channels]
+    // image (16-byte chunks XOR-swizzled by row), read back as 16 bytes per lane along rows, and stored with 4*TN
+    // lanes covering one contiguous row segment of TN*64 bytes.
     if constexpr (GEGLU) {
         // value * gelu(gate) -> 8-bit codes in the int8 activation layout (a' = code - 128, groups of 8 columns in
         // the order 0,4,1,5,2,6,3,7, columns from H to the row stride zero), optionally the product itself as fp16.
