@@ -243,6 +243,51 @@ def ff_pairs(mq, torch, iters, overhead_us):
         print(f"{M:6d}{Cc:6d} {res[0]:9.2f}{res[1]:12.2f}{ops / res[0] / 1e6:13.1f}{t_mfma:10.2f}{t_mfma / res[0]:6.3f}",
               flush=True)
         del fused, sep
+    # the same pair with DYNAMIC parameters of the activation between the two linears (and of the input)
+    print("\n# feed-forward pair, W4A8, dynamic activation parameters: us per block, cold operands; fused = gated "
+          "projection that leaves the fp16 product with its range + quantise + linear on codes; separate = two ordinary "
+          "dynamic calls (8C-wide fp16 tensor in between, GEGLU kernel not included)")
+    print(f"{'M':>6s}{'C':>6s} {'fused us':>9s}{'separate us':>12s}")
+    for (M, Cc) in ((4096, 1280), (16384, 640)):
+        per_set = 2 * M * Cc + 4 * Cc * Cc + M * 4 * Cc * 2 + 2 * Cc * Cc + 2 * M * Cc + M * 8 * Cc * 2
+        nsets = max(2, min(iters, -(-LLC_BYTES // per_set)))
+        fused, sep = [], []
+        ws = torch.empty(max(mq.qlinear_a8_geglu_dynamic_workspace_bytes(M, Cc, 4 * Cc),
+                             mq.qlinear_a8_workspace_bytes(M, 4 * Cc)), dtype=torch.uint8, device=dev)
+        for _ in range(nsets):
+            packs = []
+            for (N, K) in ((8 * Cc, Cc), (Cc, 4 * Cc)):
+                w = (torch.randn(N, K, generator=gen, device=dev) * 0.02).half()
+                c, s_, z = mq.quantize_weights(w, 4)
+                p, cs = mq.pack_weights(c, 4, mq.LAYOUT_KERNEL)
+                packs.append(mq.PackedWeight(p, s_, z, cs, N, K, 4, mq.LAYOUT_KERNEL, False))
+                del w, c
+            x = torch.randn(M, Cc, generator=gen, device=dev).half()
+            a8 = torch.empty((M, mq.a8_row_bytes(4 * Cc)), dtype=torch.int8, device=dev)
+            h16 = torch.empty(M, 4 * Cc, dtype=torch.float16, device=dev)
+            y = torch.empty(M, Cc, dtype=torch.float16, device=dev)
+            mid = (torch.empty(1, dtype=torch.float32, device=dev), torch.empty(1, dtype=torch.int32, device=dev))
+            f1 = mq.plan_qlinear_a8_geglu_dynamic(x, packs[0], None, h16, a8, mid, ws)
+            f2 = mq.plan_qlinear_a8_codes(a8, 4 * Cc, mid, packs[1], None, y)
+            fused.append((f1, f2))
+            y8 = torch.empty(M, 8 * Cc, dtype=torch.float16, device=dev)
+            s1 = mq.plan_qlinear_a8(x, packs[0], None, y8, ws)
+            s2 = mq.plan_qlinear_a8(y8[:, :4 * Cc], packs[1], None, y, ws)
+            sep.append((s1, s2))
+        res = []
+        for calls in (fused, sep):
+            for i in range(min(nsets, 4)):
+                calls[i][0](), calls[i][1]()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for i in range(iters):
+                calls[i % nsets][0](), calls[i % nsets][1]()
+            e1.record()
+            torch.cuda.synchronize()
+            res.append(e0.elapsed_time(e1) * 1e3 / iters)
+        print(f"{M:6d}{Cc:6d} {res[0]:9.2f}{res[1]:12.2f}", flush=True)
+        del fused, sep
         torch.cuda.empty_cache()
 
 

@@ -290,6 +290,21 @@ int mq_qlinear_a8_geglu(const void* x, int M, int K, int ldx, const void* packed
                         const int32_t* out_zp, int8_t* a8_out, void* h16_out, int ldh, float* act_scale_out,
                         int32_t* act_zp_out, void* ws, size_t ws_bytes, void* stream);
 
+/* The same gated projection with DYNAMIC parameters of its 8-bit output: the range of the gated product is only
+ * known once all of it exists, so the product is written as fp16 (h16, required, [M,H], row stride ldh) while every
+ * workgroup of the projection leaves the minimum and maximum of what it wrote; a second kernel turns h16 into
+ * codes exactly as the dynamic activation quantisation of mq_qlinear_w8a8 would (min/max over the fp16 values, the
+ * same fp32 formulas), without reading h16 a first time for its range.  The 8C-wide projection output still never
+ * reaches memory.  out_scale_out / out_zp_out: device pointers (required) that receive the parameters; they and
+ * a8_out are what mq_qlinear_a8_codes takes.  ws: mq_qlinear_a8_geglu_dynamic_workspace_bytes(M, K, H). */
+size_t mq_qlinear_a8_geglu_dynamic_workspace_bytes(int M, int K, int H);
+int mq_qlinear_a8_geglu_dynamic(const void* x, int M, int K, int ldx, const void* packed, int H, int w_bits,
+                                int layout, int w_signed, const float* w_scale, const int32_t* w_zp,
+                                const int32_t* w_colsum, const float* act_scale, const int32_t* act_zp,
+                                const void* bias, void* h16, int ldh, int8_t* a8_out, float* out_scale_out,
+                                int32_t* out_zp_out, float* act_scale_out, int32_t* act_zp_out, void* ws,
+                                size_t ws_bytes, void* stream);
+
 /* The gated projection on the weight-only path, W{2,3,4,8}A16, fp16 in and out:
  *     h[m,j] = fp16( lin[m,j] * gelu(lin[m,H+j]) ),  lin = X . dequant(W)^T + bias over the 2H weight rows
  * (fp32 accumulation, the same fp32 gelu as above).  h [M,H] row stride ldh (ldh % 8 == 0).  H % 32 == 0. */

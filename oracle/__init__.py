@@ -251,6 +251,18 @@ def linear_a8_geglu(x, wcodes, w_scale, w_zp, out_act, w_signed=False, act=None,
     return codes, h16, (np.float32(s.value), int(z.value))
 
 
+def linear_a8_geglu_dynamic(x, wcodes, w_scale, w_zp, w_signed=False, act=None, bias=None):
+    """GEGLU projection whose 8-bit output takes its parameters from the gated product itself: the product is rounded
+    to fp16 (the tensor that is handed on), and that tensor is quantised like any dynamically quantised activation
+    (paper Sec. 4.1, per-tensor min-max).  Returns (codes uint8 [M,H], h16 uint16 [M,H], (out_scale, out_zp),
+    (act_scale, act_zp))."""
+    # (the static parameters handed to the projection below are not used: only its fp16 product is)
+    _, h16, act_used = linear_a8_geglu(x, wcodes, w_scale, w_zp, (np.float32(1.0), 0), w_signed=w_signed, act=act,
+                                       bias=bias, want_h16=True)
+    s_o, z_o = act_params(h16)
+    return act_quantize(h16, s_o, z_o), h16, (s_o, z_o), act_used
+
+
 def linear_a8_codes(qx, act, wcodes, w_scale, w_zp, w_signed=False, bias=None, want_acc=True, residual=None):
     """A8 linear on activations that arrive as unsigned 8-bit codes with act = (scale, zp).
     Returns (y uint16 [M,N], acc int32 or None)."""

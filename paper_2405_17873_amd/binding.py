@@ -24,7 +24,7 @@ _ERRORS = {
 EXPORTS = ("mq_version", "mq_last_hip_error", "mq_tune_force_tile", "mq_tune_force_splits", "mq_tune_force_band", "mq_prof_enable", "mq_prof_num_slots", "mq_prof_read",
            "mq_prof_reset", "mq_prof_phase_buffer", "mq_prof_filter", "mq_prof_bracket_overhead_us", "mq_prof_copy", "mq_prof_microbench", "mq_quantize_weights", "mq_packed_bytes", "mq_pack_weights",
            "mq_unpack_weights", "mq_split_workspace_bytes", "mq_qlinear_w_only", "mq_qlinear_a8_workspace_bytes", "mq_qlinear_w8a8",
-           "mq_qlinear_w4a8", "mq_qlinear_w2a8", "mq_builtin_workspace_bytes", "mq_qlinear_a8_builtin_ws", "mq_a8_row_bytes", "mq_qlinear_a8_geglu", "mq_qlinear_w_only_geglu", "mq_qlinear_a8_codes", "mq_conv3x3_w_only",
+           "mq_qlinear_w4a8", "mq_qlinear_w2a8", "mq_builtin_workspace_bytes", "mq_qlinear_a8_builtin_ws", "mq_a8_row_bytes", "mq_qlinear_a8_geglu", "mq_qlinear_a8_geglu_dynamic_workspace_bytes", "mq_qlinear_a8_geglu_dynamic", "mq_qlinear_w_only_geglu", "mq_qlinear_a8_codes", "mq_conv3x3_w_only",
            "mq_conv_tap_sums", "mq_conv3x3_a8_workspace_bytes", "mq_conv3x3_a8",
            "mq_bos_aware_kv_proj_workspace_bytes", "mq_bos_aware_kv_proj", "mq_alloc_solve", "mq_alloc_split_budget",
            "mq_alloc_search")
@@ -50,7 +50,7 @@ def load():
         if not os.path.exists(_LIB_PATH):
             raise RuntimeError(f"{_LIB_PATH} is missing: run `python -c 'import __graft_entry__ as g; g.build()'`")
         _lib = C.CDLL(_LIB_PATH)
-        for name in ("mq_a8_row_bytes", "mq_split_workspace_bytes", "mq_builtin_workspace_bytes", "mq_conv3x3_a8_workspace_bytes", "mq_packed_bytes", "mq_qlinear_a8_workspace_bytes", "mq_bos_aware_kv_proj_workspace_bytes"):
+        for name in ("mq_a8_row_bytes", "mq_split_workspace_bytes", "mq_builtin_workspace_bytes", "mq_conv3x3_a8_workspace_bytes", "mq_packed_bytes", "mq_qlinear_a8_workspace_bytes", "mq_qlinear_a8_geglu_dynamic_workspace_bytes", "mq_bos_aware_kv_proj_workspace_bytes"):
             getattr(_lib, name).restype = C.c_size_t
         _lib.mq_prof_bracket_overhead_us.restype = C.c_double
     return _lib
@@ -381,6 +381,33 @@ def qlinear_a8_geglu(x, w: PackedWeight, out_act, act=None, bias=None, ws=None, 
     return a8, h16, ((so, zo) if want_act else None)
 
 
+def qlinear_a8_geglu_dynamic_workspace_bytes(M: int, K: int, H: int) -> int:
+    return int(load().mq_qlinear_a8_geglu_dynamic_workspace_bytes(int(M), int(K), int(H)))
+
+
+def qlinear_a8_geglu_dynamic(x, w: PackedWeight, act=None, bias=None, ws=None, want_act=False):
+    """Gated projection with 8-bit output whose parameters are taken from the range of the gated product itself.
+    w has 2H rows.  Returns (a8 int8 [M, a8_row_bytes(H)], h16 fp16 [M,H], (out_scale, out_zp) one-element device
+    tensors, (act_scale, act_zp) of the input or None)."""
+    assert x.is_cuda and x.dim() == 2 and x.stride(1) == 1 and x.dtype == torch.float16
+    M, K = x.shape
+    H = w.N // 2
+    a8 = torch.empty((M, a8_row_bytes(H)), dtype=torch.int8, device=x.device)
+    h16 = torch.empty((M, H), dtype=torch.float16, device=x.device)
+    ws = _workspace(qlinear_a8_geglu_dynamic_workspace_bytes(M, K, H), x.device, ws)
+    a_s, a_z = (None, None) if act is None else act
+    o_s = torch.empty(1, dtype=torch.float32, device=x.device)
+    o_z = torch.empty(1, dtype=torch.int32, device=x.device)
+    so = torch.empty(1, dtype=torch.float32, device=x.device) if want_act else None
+    zo = torch.empty(1, dtype=torch.int32, device=x.device) if want_act else None
+    _check(load().mq_qlinear_a8_geglu_dynamic(_ptr(x), M, K, x.stride(0), _ptr(w.packed), H, w.bits, w.layout,
+                                              int(w.signed), _ptr(w.scale), _ptr(w.zp), _ptr(w.colsum), _ptr(a_s),
+                                              _ptr(a_z), _ptr(bias), _ptr(h16), H, _ptr(a8), _ptr(o_s), _ptr(o_z),
+                                              _ptr(so), _ptr(zo), _ptr(ws), C.c_size_t(ws.numel()), _stream()),
+           "mq_qlinear_a8_geglu_dynamic")
+    return a8, h16, (o_s, o_z), ((so, zo) if want_act else None)
+
+
 def qlinear_w_only_geglu(x, w: PackedWeight, bias=None, out=None):
     """Weight-only gated projection: w has 2H rows; returns value * gelu(gate) as fp16 [M,H]."""
     assert x.is_cuda and x.dim() == 2 and x.stride(1) == 1 and x.dtype == torch.float16
@@ -416,6 +443,19 @@ def plan_qlinear_a8_geglu(x, w: PackedWeight, out_act, bias, a8_out, ws, act=Non
             _ptr(w.colsum), _ptr(a_s), _ptr(a_z), _ptr(bias), _ptr(out_act[0]), _ptr(out_act[1]), _ptr(a8_out), null, H,
             null, null, _ptr(ws), C.c_size_t(ws.numel()), _stream())
     return _planned(load().mq_qlinear_a8_geglu, "mq_qlinear_a8_geglu", args, (x, w, out_act, bias, a8_out, ws, act))
+
+
+def plan_qlinear_a8_geglu_dynamic(x, w: PackedWeight, bias, h16, a8_out, out_act, ws, act=None):
+    """out_act = (scale, zp) one-element device tensors that RECEIVE the parameters of the gated product."""
+    M, K = x.shape
+    H = w.N // 2
+    a_s, a_z = (None, None) if act is None else act
+    null = C.c_void_p(0)
+    args = (_ptr(x), M, K, x.stride(0), _ptr(w.packed), H, w.bits, w.layout, int(w.signed), _ptr(w.scale), _ptr(w.zp),
+            _ptr(w.colsum), _ptr(a_s), _ptr(a_z), _ptr(bias), _ptr(h16), h16.stride(0), _ptr(a8_out), _ptr(out_act[0]),
+            _ptr(out_act[1]), null, null, _ptr(ws), C.c_size_t(ws.numel()), _stream())
+    return _planned(load().mq_qlinear_a8_geglu_dynamic, "mq_qlinear_a8_geglu_dynamic", args,
+                    (x, w, bias, h16, a8_out, out_act, ws, act))
 
 
 def plan_qlinear_a8_codes(a8, K, act, w: PackedWeight, bias, out, residual=None):

@@ -196,13 +196,18 @@ __global__ __launch_bounds__(256) void act_quantize_kernel(const _Float16* __res
 
 int launch_act_quant(const void* x, int M, int K, int ldx, RowMap in_map, const float* act_scale,
                      const int32_t* act_zp, int8_t* a8, int32_t* rowsum, ActParams* params, float* partials,
-                     float* act_scale_out, int32_t* act_zp_out, const BosWork* bos, hipStream_t st) {
+                     float* act_scale_out, int32_t* act_zp_out, const BosWork* bos, hipStream_t st,
+                     int given_partials) {
     const uint32_t K8 = (uint32_t)K >> 3;
     const uint32_t nv = (uint32_t)M * K8;  // M * ldx * 2 < 2^31 has been checked: this fits easily
     long g1 = ((long)nv + 256 * MM_U - 1) / (256 * MM_U);
-    const int grid = (int)(g1 > kPartialSlots ? kPartialSlots : g1);
+    int grid = (int)(g1 > kPartialSlots ? kPartialSlots : g1);
     const bool dynamic = act_scale == nullptr;
-    if (dynamic) {
+    // given_partials > 0: the producer of x has left that many (min, max) pairs in `partials` already (the gated
+    // projection's epilogue does), so the pass over x that would find them is skipped
+    if (dynamic && given_partials > 0) {
+        grid = given_partials;
+    } else if (dynamic) {
         const int flat = in_map.rows_per_group <= 0 && ldx == K;
         ProfScope prof(st, PROF_ACT_MINMAX, 0.0, 2.0 * M * K);
         hipLaunchKernelGGL(act_minmax_kernel, dim3(grid), dim3(256), 0, st, (const _Float16*)x, nv, K8, (long)ldx,

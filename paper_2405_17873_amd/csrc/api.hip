@@ -257,7 +257,54 @@ int mq_qlinear_a8_geglu(const void* x, int M, int K, int ldx, const void* packed
                           act_scale_out, act_zp_out, nullptr, st);
     if (rc) return rc;
     return launch_gemm_a8_geglu(w.a8, w.rowsum, w.params, M, K, packed, H, w_bits, w_signed ? 1 : 0, w_scale, w_zp,
-                                w_colsum, bias, out_scale, out_zp, a8_out, h16_out, ldh, st);
+                                w_colsum, bias, out_scale, out_zp, a8_out, h16_out, ldh, nullptr, nullptr, st);
+}
+
+// Dynamic output parameters: behind the input's workspace lie the parameters of the output pass, one (min, max)
+// pair per workgroup of the gated projection (at most one per 128 rows x 64 gated columns) and the row sums that
+// the quantise kernel writes beside its codes (the consumer takes its own inside its main loop).
+static size_t geglu_dynamic_pairs(long M, long H) { return (size_t)((M + 127) / 128) * (size_t)((H + 127) / 128 * 2); }
+
+size_t mq_qlinear_a8_geglu_dynamic_workspace_bytes(int M, int K, int H) {
+    if (M <= 0 || K <= 0 || H <= 0) return 0;
+    return A8Workspace::bytes(M, K) + 256 + up256(8 * geglu_dynamic_pairs(M, H)) + up256(4 * (size_t)M);
+}
+
+int mq_qlinear_a8_geglu_dynamic(const void* x, int M, int K, int ldx, const void* packed, int H, int w_bits,
+                                int layout, int w_signed, const float* w_scale, const int32_t* w_zp,
+                                const int32_t* w_colsum, const float* act_scale, const int32_t* act_zp,
+                                const void* bias, void* h16, int ldh, int8_t* a8_out, float* out_scale_out,
+                                int32_t* out_zp_out, float* act_scale_out, int32_t* act_zp_out, void* ws,
+                                size_t ws_bytes, void* stream) {
+    if (w_bits != 2 && w_bits != 4 && w_bits != 8) return MQ_ERR_UNSUPPORTED_BITS;
+    if (w_bits != 8 && w_signed) return MQ_ERR_BAD_ARG;
+    if (H <= 0 || H % 32 != 0 || H > (1 << 29)) return MQ_ERR_BAD_SHAPE;
+    int rc = check_linear_common(x, M, K, ldx, packed, 2 * H, layout, w_scale, w_zp, bias, a8_out, 2 * H);
+    if (rc) return rc;
+    if (!w_colsum || !ws || !h16 || !out_scale_out || !out_zp_out) return MQ_ERR_BAD_ARG;
+    if ((act_scale == nullptr) != (act_zp == nullptr)) return MQ_ERR_BAD_ARG;
+    if (!aligned(w_colsum, 16) || !aligned(ws, 256) || !aligned(h16, 16)) return MQ_ERR_BAD_ARG;
+    if (ldh < H || ldh % 8 != 0) return MQ_ERR_BAD_SHAPE;
+    if ((long)M * (long)mq_a8_row_bytes(H) >= (1L << 31) || (long)M * ldh * 2 >= (1L << 31)) return MQ_ERR_BAD_SHAPE;
+    if ((long)255 * 255 * K >= (1L << 31)) return MQ_ERR_OVERFLOW_RISK;
+    if (ws_bytes < mq_qlinear_a8_geglu_dynamic_workspace_bytes(M, K, H)) return MQ_ERR_WORKSPACE_TOO_SMALL;
+    hipStream_t st = (hipStream_t)stream;
+    A8Workspace w(ws, M, K);
+    uint8_t* q = (uint8_t*)ws + A8Workspace::bytes(M, K);
+    ActParams* out_params = (ActParams*)q;
+    float* pairs = (float*)(q + 256);
+    int32_t* out_rowsum = (int32_t*)(q + 256 + up256(8 * geglu_dynamic_pairs(M, H)));
+    rc = launch_act_quant(x, M, K, ldx, RowMap{0, 0, 0}, act_scale, act_zp, w.a8, w.rowsum, w.params, w.partials,
+                          act_scale_out, act_zp_out, nullptr, st);
+    if (rc) return rc;
+    int n_pairs = 0;
+    rc = launch_gemm_a8_geglu(w.a8, w.rowsum, w.params, M, K, packed, H, w_bits, w_signed ? 1 : 0, w_scale, w_zp,
+                              w_colsum, bias, nullptr, nullptr, nullptr, h16, ldh, pairs, &n_pairs, st);
+    if (rc) return rc;
+    if (n_pairs <= 0 || (size_t)n_pairs > geglu_dynamic_pairs(M, H)) return MQ_ERR_BAD_SHAPE;  // (cannot happen)
+    // the ordinary dynamic quantisation of the fp16 product, minus its pass for the range
+    return launch_act_quant(h16, M, H, ldh, RowMap{0, 0, 0}, nullptr, nullptr, a8_out, out_rowsum, out_params, pairs,
+                            out_scale_out, out_zp_out, nullptr, st, n_pairs);
 }
 
 int mq_qlinear_w_only_geglu(const void* x, int M, int K, int ldx, const void* packed, int H, int bits, int layout,

@@ -384,6 +384,8 @@ struct GemmArgs {
     const float* out_scale_p;
     const int32_t* out_zp_p;
     int8_t* a8_out;
+    // optional (int8 gated projection): one (min, max) pair per workgroup over the fp16 gated products it wrote
+    float* mm_out;
     long ld8;
     // MODE 2 (activations arrive as int8 codes): their parameters; row sums are taken inside the main loop
     const float* act_scale_p;
@@ -457,16 +459,20 @@ struct GemmPlan {
 // MODE 0: Y = linear(X).  MODE 1 (int8, two channel tiles per wave): gated feed-forward projection; the wave's first
 // channel tile is a value tile, its second the gate tile of the same 32 columns, and the epilogue emits
 // value * gelu(gate) as 8-bit codes for the next integer GEMM.  MODE 2 (int8): the activations arrive as codes with
-// their parameters; the row sums the epilogue needs are accumulated in the main loop.
+// their parameters; the row sums the epilogue needs are accumulated in the main loop.  MODE 3 / 4: 3x3 convolution
+// (16-bit / 8-bit activations).  MODE 5 (int8): the gated projection of MODE 1 without output parameters: it writes
+// the fp16 product and one (min, max) pair per workgroup, from which the codes follow in a pass of their own.
 template <bool I8, int BITS, int WGM, int WGN, int TM, int TN, int S, int KS, bool BF = false, int MODE = 0,
           bool RES = false>
 __global__ __launch_bounds__(WGM* WGN* KS * 64,
                              (TM * TN <= 8 && GemmPlan<I8, BITS, WGM, WGN, TM, TN, S, KS>::LDS_BYTES <= 80 * 1024) ? 2 : 1)
 void gemm_kernel(const GemmArgs g) {
     static_assert(!(I8 && BF), "the int8 path writes fp16");
-    constexpr bool GEGLU = MODE == 1, RS_INLINE = MODE == 2 || MODE == 4, CONV = MODE == 3 || MODE == 4;
+    constexpr bool GEGLU = MODE == 1 || MODE == 5, RS_INLINE = MODE == 2 || MODE == 4, CONV = MODE == 3 || MODE == 4;
+    constexpr bool RANGE = MODE == 5;  // gated projection that leaves the fp16 product and its range, no codes
     static_assert(MODE == 0 || KS == 1, "the special modes have no in-workgroup k split");
-    static_assert(!(RES && MODE == 1), "the gated projection takes no residual");
+    static_assert(!(RES && GEGLU), "the gated projection takes no residual");
+    static_assert(!RANGE || (I8 && !BF), "the range output belongs to the int8 gated projection");
     static_assert((MODE != 2 && MODE != 4) || I8, "int8 modes");
     static_assert(MODE != 3 || !I8, "MODE 3 is the weight-only convolution");
     static_assert(!GEGLU || TN == 2, "value tile and gate tile per wave");
@@ -1006,8 +1012,15 @@ void gemm_kernel(const GemmArgs g) {
         // A lane holds four consecutive columns of one row; the lane 32 further on holds the other four of the same
         // group of 8, so the two swap their packed words and each keeps one of the group's two output words.
         // Rows are staged through LDS (32 rows x 32 bytes per wave) and leave as 16-byte pieces.
-        const float inv_o = I8 ? __fdiv_rn(1.0f, *g.out_scale_p) : 0.0f;
-        const float zf_o = I8 ? (float)*g.out_zp_p : 0.0f;
+        // (without output parameters the kernel only writes the product and its range: the codes follow in a pass of
+        // their own once the range of the whole tensor is known)
+        constexpr bool want_codes = I8 && !RANGE;
+        float inv_o = 0.0f, zf_o = 0.0f;
+        if constexpr (want_codes) {
+            inv_o = __fdiv_rn(1.0f, *g.out_scale_p);
+            zf_o = (float)*g.out_zp_p;
+        }
+        float hmn = INFINITY, hmx = -INFINITY;
         static_assert(P::NWG * 3072 <= S * STAGE_BYTES, "epilogue staging must fit the LDS stages");
         uint8_t* ep8 = lds + wvg * 3072;
         uint8_t* ep16 = ep8 + 1024;
@@ -1040,7 +1053,7 @@ void gemm_kernel(const GemmArgs g) {
                         lg = __fmaf_rn(acc[tm][1][4 * q + r], mul_g[r], add_g[r]);
                     }
                     const float h = __fmul_rn(lv, gelu32(lg));
-                    if constexpr (I8) {
+                    if constexpr (want_codes) {
                         float t = __fadd_rn(rintf(__fmul_rn(h, inv_o)), zf_o);
                         t = fminf(fmaxf(t, 0.0f), 255.0f);
                         const int code = col0 + 8 * q + 4 * kb + r < H ? (int)t - 128 : 0;
@@ -1051,15 +1064,27 @@ void gemm_kernel(const GemmArgs g) {
                     else
                         hh[r] = (_Float16)h;
                 }
-                const uint32_t other = (uint32_t)__shfl_xor((int)word, 32, 64);
-                const uint32_t lo = kb ? other : word, hi = kb ? word : other;  // columns 0..3 and 4..7 of the group
-                // v_perm_b32: selector bytes 0..3 pick bytes of the second source, 4..7 of the first
-                const uint32_t out = kb ? __builtin_amdgcn_perm(hi, lo, 0x07030602u) : __builtin_amdgcn_perm(hi, lo, 0x05010400u);
-                if constexpr (I8) *(uint32_t*)(ep8 + l31 * 32 + q * 8 + kb * 4) = out;
+                if constexpr (RANGE) {  // range of the values as they are stored (fp16), real rows and columns only
+                    const bool row_ok = mt0 + l31 < g.M;
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        const bool ok = row_ok && col0 + 8 * q + 4 * kb + r < H;
+                        const float hv = (float)hh[r];
+                        hmn = fminf(hmn, ok ? hv : INFINITY);
+                        hmx = fmaxf(hmx, ok ? hv : -INFINITY);
+                    }
+                }
+                if constexpr (want_codes) {
+                    const uint32_t other = (uint32_t)__shfl_xor((int)word, 32, 64);
+                    const uint32_t lo = kb ? other : word, hi = kb ? word : other;  // columns 0..3 and 4..7 of the group
+                    // v_perm_b32: selector bytes 0..3 pick bytes of the second source, 4..7 of the first
+                    const uint32_t out = kb ? __builtin_amdgcn_perm(hi, lo, 0x07030602u) : __builtin_amdgcn_perm(hi, lo, 0x05010400u);
+                    *(uint32_t*)(ep8 + l31 * 32 + q * 8 + kb * 4) = out;
+                }
                 if (g.y) *(half4*)(ep16 + l31 * 64 + q * 16 + kb * 8) = hh;
             }
             __builtin_amdgcn_wave_barrier();
-            if constexpr (I8) {
+            if constexpr (want_codes) {
                 const int row = lane >> 1, half = lane & 1;
                 const uint4v v = *(const uint4v*)(ep8 + row * 32 + half * 16);
                 const int m = mt0 + row, col = col0 + half * 16;
@@ -1075,6 +1100,29 @@ void gemm_kernel(const GemmArgs g) {
                 }
             }
             __builtin_amdgcn_wave_barrier();
+        }
+        if constexpr (RANGE) {  // one pair per workgroup: waves meet through the (idle) sink of the padding loads
+#pragma unroll
+            for (int off = 32; off > 0; off >>= 1) {
+                hmn = fminf(hmn, __shfl_xor(hmn, off, 64));
+                hmx = fmaxf(hmx, __shfl_xor(hmx, off, 64));
+            }
+            float* mm = (float*)(lds + P::SINK);
+            if (lane == 0) {
+                mm[2 * wv] = hmn;
+                mm[2 * wv + 1] = hmx;
+            }
+            __syncthreads();
+            if (threadIdx.x == 0) {
+                float a = mm[0], b = mm[1];
+#pragma unroll
+                for (int i = 1; i < NW; ++i) {
+                    a = fminf(a, mm[2 * i]);
+                    b = fmaxf(b, mm[2 * i + 1]);
+                }
+                g.mm_out[2 * blockIdx.x] = a;
+                g.mm_out[2 * blockIdx.x + 1] = b;
+            }
         }
     } else {
     static_assert(TN == 1 || TN == 2 || TN == 4, "channel tiles per wave: 1, 2 or 4");
@@ -1392,7 +1440,7 @@ static int run_gemm_r(GemmArgs& g, int tile_index, hipStream_t st) {
     static_assert(P::LDS_BYTES <= 160 * 1024, "LDS plan exceeds the compute unit");
     g.tiles_m = (g.M + P::BM - 1) / P::BM;
     g.tiles_n = (g.N + P::BN - 1) / P::BN;
-    if (MODE == 1) g.tiles_n = (int)((g.ld8 + P::BN / 2 - 1) / (P::BN / 2));  // gated columns up to the padded row end
+    if (MODE == 1 || MODE == 5) g.tiles_n = (int)((g.ld8 + P::BN / 2 - 1) / (P::BN / 2));  // gated columns up to the padded row end
     // Split the reduction over workgroups where the tiles alone would leave most compute units idle and the reduction
     // is long: as many parts as fill about two workgroups per compute unit, each at least four pipeline stages long.
     const long tiles = (long)g.tiles_m * g.tiles_n;
@@ -1437,7 +1485,7 @@ static int run_gemm_r(GemmArgs& g, int tile_index, hipStream_t st) {
     auto kern = gemm_kernel<I8, BITS, WGM, WGN, TM, TN, S, KS, BF, MODE, RES>;
     // Once per instantiation and device (callers may be on several host threads): allow more than 64 KB of dynamic
     // LDS, name the profiling slot.
-    const int slot = prof_gemm_slot(MODE ? 2 + MODE : (I8 ? 1 : (BF ? 2 : 0)), BITS, tile_index);
+    const int slot = prof_gemm_slot(MODE == 5 ? 3 : (MODE ? 2 + MODE : (I8 ? 1 : (BF ? 2 : 0))), BITS, tile_index);
     static std::mutex prep_mutex;
     static bool prepared[16] = {};
     int dev = 0;
@@ -1459,9 +1507,10 @@ static int run_gemm_r(GemmArgs& g, int tile_index, hipStream_t st) {
         }
     }
     // (a convolution reads each input pixel once, not nine times: the whole input tensor)
-    const double abytes = MODE >= 3 ? (double)g.a_bytes
+    const double abytes = MODE == 3 || MODE == 4 ? (double)g.a_bytes
                                     : (I8 ? 1.0 * g.M * g.K + (MODE == 0 ? 4.0 * g.M : 0.0) : 2.0 * g.M * g.K);
-    const double ybytes = MODE == 1 ? 1.0 * g.M * g.ld8 + (g.y ? 1.0 * g.M * g.N : 0.0) : 2.0 * g.M * g.N;
+    const double ybytes = MODE == 1 ? 1.0 * g.M * g.ld8 + (g.y ? 1.0 * g.M * g.N : 0.0)
+                                    : (MODE == 5 ? 1.0 * g.M * g.N : 2.0 * g.M * g.N);
     ProfScope prof(st, slot, 2.0 * g.M * g.N * g.K,
                    abytes + (double)g.N * g.K * BITS / 8 + (I8 ? 14.0 : 10.0) * g.N + ybytes);
     if (g.splits > 1) {
@@ -1475,7 +1524,7 @@ static int run_gemm_r(GemmArgs& g, int tile_index, hipStream_t st) {
 
 template <bool I8, int BITS, int WGM, int WGN, int TM, int TN, int KS, int BUDGET, int MAXS, bool BF = false, int MODE = 0>
 static int run_gemm(GemmArgs& g, int tile_index, hipStream_t st) {
-    if constexpr (MODE != 1)
+    if constexpr (MODE != 1 && MODE != 5)
         if (g.res) return run_gemm_r<I8, BITS, WGM, WGN, TM, TN, KS, BUDGET, MAXS, BF, MODE, true>(g, tile_index, st);
     return run_gemm_r<I8, BITS, WGM, WGN, TM, TN, KS, BUDGET, MAXS, BF, MODE, false>(g, tile_index, st);
 }
@@ -1583,9 +1632,10 @@ int launch_gemm_a8(const int8_t* a8, const int32_t* rowsum, const ActParams* par
 int launch_gemm_a8_geglu(const int8_t* a8, const int32_t* rowsum, const ActParams* params, int M, int K,
                          const void* packed, int H, int w_bits, int w_signed, const float* w_scale, const int32_t* w_zp,
                          const int32_t* w_colsum, const void* bias, const float* out_scale, const int32_t* out_zp,
-                         int8_t* a8_out, void* h16, int ldh, hipStream_t st) {
+                         int8_t* a8_out, void* h16, int ldh, float* mm_out, int* mm_pairs, hipStream_t st) {
     const int Kp = (K + 127) / 128 * 128;
     GemmArgs g{};
+    g.mm_out = mm_out;
     g.a = a8;
     g.a_row_bytes = Kp;
     g.a_bytes = (uint32_t)((long)M * Kp);
@@ -1600,22 +1650,42 @@ int launch_gemm_a8_geglu(const int8_t* a8, const int32_t* rowsum, const ActParam
     g.a8_out = a8_out; g.ld8 = (H + 127) / 128 * 128;
     // the large tile (128 gated columns per workgroup) once it yields two workgroups per compute unit
     const bool big = g_force_tile == 0 || (g_force_tile < 0 && (long)((M + 127) / 128) * ((H + 127) / 128) >= 512);
-    if (w_bits == 4) {
-        g.w_off = 0;
-        if (big) return run_gemm<true, 4, 1, 4, 4, 2, 1, 80 * 1024, 4, false, 1>(g, 0, st);
-        return run_gemm<true, 4, 2, 2, 2, 2, 1, 80 * 1024, 4, false, 1>(g, 1, st);
+    int rc = MQ_ERR_UNSUPPORTED_BITS;
+    if (mm_out) {  // fp16 product and its range, no codes
+        if (w_bits == 4) {
+            g.w_off = 0;
+            if (big) rc = run_gemm<true, 4, 1, 4, 4, 2, 1, 80 * 1024, 4, false, 5>(g, 0, st);
+            else rc = run_gemm<true, 4, 2, 2, 2, 2, 1, 80 * 1024, 4, false, 5>(g, 1, st);
+        }
+        if (w_bits == 2) {
+            g.w_off = 0;
+            if (big) rc = run_gemm<true, 2, 1, 4, 4, 2, 1, 80 * 1024, 4, false, 5>(g, 0, st);
+            else rc = run_gemm<true, 2, 2, 2, 2, 2, 1, 80 * 1024, 4, false, 5>(g, 1, st);
+        }
+        if (w_bits == 8) {
+            g.w_off = w_signed ? 0 : 128;
+            if (g_force_tile == 0) rc = run_gemm<true, 8, 1, 4, 4, 2, 1, 160 * 1024, 4, false, 5>(g, 0, st);
+            else rc = run_gemm<true, 8, 2, 2, 2, 2, 1, 80 * 1024, 4, false, 5>(g, 1, st);
+        }
+    } else {
+        if (w_bits == 4) {
+            g.w_off = 0;
+            if (big) rc = run_gemm<true, 4, 1, 4, 4, 2, 1, 80 * 1024, 4, false, 1>(g, 0, st);
+            else rc = run_gemm<true, 4, 2, 2, 2, 2, 1, 80 * 1024, 4, false, 1>(g, 1, st);
+        }
+        if (w_bits == 2) {
+            g.w_off = 0;
+            if (big) rc = run_gemm<true, 2, 1, 4, 4, 2, 1, 80 * 1024, 4, false, 1>(g, 0, st);
+            else rc = run_gemm<true, 2, 2, 2, 2, 2, 1, 80 * 1024, 4, false, 1>(g, 1, st);
+        }
+        if (w_bits == 8) {
+            g.w_off = w_signed ? 0 : 128;
+            if (g_force_tile == 0) rc = run_gemm<true, 8, 1, 4, 4, 2, 1, 160 * 1024, 4, false, 1>(g, 0, st);
+            else rc = run_gemm<true, 8, 2, 2, 2, 2, 1, 80 * 1024, 4, false, 1>(g, 1, st);
+        }
     }
-    if (w_bits == 2) {
-        g.w_off = 0;
-        if (big) return run_gemm<true, 2, 1, 4, 4, 2, 1, 80 * 1024, 4, false, 1>(g, 0, st);
-        return run_gemm<true, 2, 2, 2, 2, 2, 1, 80 * 1024, 4, false, 1>(g, 1, st);
-    }
-    if (w_bits == 8) {
-        g.w_off = w_signed ? 0 : 128;
-        if (g_force_tile == 0) return run_gemm<true, 8, 1, 4, 4, 2, 1, 160 * 1024, 4, false, 1>(g, 0, st);
-        return run_gemm<true, 8, 2, 2, 2, 2, 1, 80 * 1024, 4, false, 1>(g, 1, st);
-    }
-    return MQ_ERR_UNSUPPORTED_BITS;
+    if (mm_pairs) *mm_pairs = g.tiles_m * g.tiles_n;  // workgroups of the launch: one pair each
+    return rc;
 }
 
 template <int BITS>

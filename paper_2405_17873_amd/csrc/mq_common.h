@@ -107,7 +107,8 @@ struct BosWork {
 // and per-row sums of a'.  bos (optional): BOS rows computed by extra workgroups of the quantise launch.
 int launch_act_quant(const void* x, int M, int K, int ldx, RowMap in_map, const float* act_scale,
                      const int32_t* act_zp, int8_t* a8, int32_t* rowsum, ActParams* params, float* partials,
-                     float* act_scale_out, int32_t* act_zp_out, const BosWork* bos, hipStream_t st);
+                     float* act_scale_out, int32_t* act_zp_out, const BosWork* bos, hipStream_t st,
+                     int given_partials = 0);
 int act_quant_partial_slots();
 
 int launch_gemm_w_only(const void* x, int M, int K, int ldx, const void* packed, int N, int bits,
@@ -122,7 +123,7 @@ int launch_gemm_a8(const int8_t* a8, const int32_t* rowsum, const ActParams* par
 int launch_gemm_a8_geglu(const int8_t* a8, const int32_t* rowsum, const ActParams* params, int M, int K,
                          const void* packed, int H, int w_bits, int w_signed, const float* w_scale, const int32_t* w_zp,
                          const int32_t* w_colsum, const void* bias, const float* out_scale, const int32_t* out_zp,
-                         int8_t* a8_out, void* h16, int ldh, hipStream_t st);
+                         int8_t* a8_out, void* h16, int ldh, float* mm_out, int* mm_pairs, hipStream_t st);
 int launch_gemm_w_only_geglu(const void* x, int M, int K, int ldx, const void* packed, int H, int bits,
                              const float* w_scale, const int32_t* w_zp, const void* bias, void* h16, int ldh,
                              hipStream_t st);

@@ -109,6 +109,15 @@ def test_error_codes_without_a_gpu(lib):
     assert lib.mq_qlinear_w8a8(*a8(K=33088)) == -7     # 255*255*K >= 2^31
     assert lib.mq_qlinear_w8a8(*a8(ws=null)) == -1
     assert lib.mq_qlinear_w8a8(*a8(res=p, ldr=8)) == -2
+    # gated projection with dynamic output parameters
+    gd = lambda **o: [p, 8, 64, 64, p, o.get("H", 32), 4, 1, 0, p, p, p, null, null, null, o.get("h16", p), o.get("ldh", 32), p,
+                      o.get("so", p), o.get("zo", p), null, null, p, C.c_size_t(o.get("wsb", 1 << 20)), st]
+    assert lib.mq_qlinear_a8_geglu_dynamic(*gd(h16=null)) == -1     # the fp16 product is not optional here
+    assert lib.mq_qlinear_a8_geglu_dynamic(*gd(so=null)) == -1
+    assert lib.mq_qlinear_a8_geglu_dynamic(*gd(H=48)) == -2
+    assert lib.mq_qlinear_a8_geglu_dynamic(*gd(ldh=16)) == -2
+    assert lib.mq_qlinear_a8_geglu_dynamic(*gd(wsb=lib.mq_qlinear_a8_workspace_bytes(8, 64))) == -4
+    assert lib.mq_qlinear_a8_geglu_dynamic_workspace_bytes(8, 64, 32) > lib.mq_qlinear_a8_workspace_bytes(8, 64)
     # bos
     bos = lambda **o: [p, o.get("B", 2), 5, 64, p, 32, o.get("wb", 8), 1, 1, p, p, p, o.get("wf", null),
                        o.get("bo", null), null, null, null, p, 0, null, null, p, C.c_size_t(1 << 20), st]

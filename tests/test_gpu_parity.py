@@ -567,6 +567,63 @@ def test_geglu_projection_codes_against_the_fp64_oracle(mq, orc, bits, sym, tile
         mq.tune_force_tile(-1)
 
 
+@pytest.mark.parametrize("bits,sym", [(4, False), (8, True), (2, False)])
+@pytest.mark.parametrize("tile", (-1, 0, 1))
+def test_geglu_projection_with_dynamic_output_parameters(mq, orc, bits, sym, tile):
+    """The gated product leaves as fp16 with one (min, max) pair per workgroup; the codes follow from the range of
+    the whole product.  Checked in two steps: the fp16 product against the oracle's (16-bit tolerance), and, on the
+    kernel's own product, parameters and codes bit for bit against the oracle's dynamic quantiser; end to end the
+    scale may differ from the oracle's by one fp16 step of the extreme value at most."""
+    mq.tune_force_tile(tile)
+    try:
+        for (M, K, H) in ((256, 320, 320), (77, 128, 32), (300, 640, 96), (130, 1280, 160), (1, 64, 32)):
+            x = si.activations_f16(63, f"fd/x{M}x{K}", M, K, outlier_prob=0.01)
+            w = si.weights_f16(63, f"fd/w{H}x{K}", 2 * H, K)
+            b = si.bias_f16(63, f"fd/b{H}", 2 * H)
+            pw, oc, os_, oz = make_weight(mq, orc, w, bits, sym)
+            for act in (None, (np.float32(0.03), 117)):
+                d_act = None if act is None else (dev(np.array([act[0]], np.float32)), dev(np.array([act[1]], np.int32)))
+                a8, h16, (so, zo), got_act = mq.qlinear_a8_geglu_dynamic(dev(x), pw, act=d_act, bias=dev(b), want_act=True)
+                rq, rh, (rso, rzo), ract = orc.linear_a8_geglu_dynamic(x, oc, os_, oz, w_signed=sym, act=act, bias=b)
+                what = f"geglu dynamic b{bits} tile{tile} {M}x{K}x{H}"
+                assert host(got_act[0])[0] == ract[0] and host(got_act[1])[0] == ract[1], what
+                gh = host(h16)
+                assert_close16(gh, rh, what + " (gated product in fp16)")
+                s2, z2 = orc.act_params(gh)
+                assert host(so)[0] == s2 and host(zo)[0] == z2, what + " (parameters of the kernel's own product)"
+                codes, pad = a8_unlayout(host(a8), H)
+                assert a8.shape[1] == (H + 127) // 128 * 128 and not pad.any()
+                assert np.array_equal(codes, orc.act_quantize(gh, s2, z2)), what + " (codes)"
+                assert abs(float(s2) - float(rso)) <= 2.0 ** -9 * float(rso) and abs(z2 - rzo) <= 1, what
+                if s2 == rso and z2 == rzo:
+                    assert np.abs(codes.astype(np.int64) - rq.astype(np.int64)).max() <= 1, what
+    finally:
+        mq.tune_force_tile(-1)
+
+
+def test_feed_forward_pair_with_dynamic_parameters_in_between(mq, orc):
+    """Gated projection with dynamic output parameters, then the output linear on its codes: against the oracle run
+    on the kernel's own codes (accumulators bit for bit) and end to end within the 16-bit tolerance."""
+    M, C = 200, 320
+    x = si.activations_f16(64, "fp/x", M, C, outlier_prob=0.01)
+    w1 = si.weights_f16(64, "fp/w1", 8 * C, C)
+    b1 = si.bias_f16(64, "fp/b1", 8 * C)
+    w2 = si.weights_f16(64, "fp/w2", C, 4 * C)
+    b2 = si.bias_f16(64, "fp/b2", C)
+    pw1, c1, s1, z1 = make_weight(mq, orc, w1, 4)
+    pw2, c2, s2, z2 = make_weight(mq, orc, w2, 4)
+    a8, h16, (so, zo), _ = mq.qlinear_a8_geglu_dynamic(dev(x), pw1, bias=dev(b1))
+    y, acc = mq.qlinear_a8_codes(a8, 4 * C, (so, zo), pw2, bias=dev(b2), want_acc=True)
+    codes, _ = a8_unlayout(host(a8), 4 * C)
+    ry, racc = orc.linear_a8_codes(codes, (host(so)[0], int(host(zo)[0])), c2, s2, z2, bias=b2)
+    assert np.array_equal(host(acc), racc)
+    assert_close16(host(y), ry, "second linear on the kernel's codes")
+    rq, _, ro, _ = orc.linear_a8_geglu_dynamic(x, c1, s1, z1, bias=b1)
+    if ro[0] == host(so)[0] and ro[1] == int(host(zo)[0]):  # (the extreme product rounds the same way on both sides)
+        ry2, _ = orc.linear_a8_codes(rq, ro, c2, s2, z2, bias=b2)
+        assert_close16(host(y), ry2, "feed-forward pair end to end")
+
+
 @pytest.mark.parametrize("bits,sym", [(4, False), (8, True), (8, False), (2, False)])
 @pytest.mark.parametrize("tile", (-1, 1, 2, 5))
 def test_a8_linear_on_codes(mq, orc, bits, sym, tile):

@@ -518,6 +518,46 @@ def test_geglu_gate_function_through_the_layer_closed_forms(orc):
         assert abs(gelu[g] - g * phi) < 1e-9 * 4
 
 
+def test_geglu_dynamic_output_parameters_by_hand(orc):
+    """Zero weights leave lin = bias.  Values 1, gates 0, 8, 24, -12: the gated product is 0, 8, 24 and -12 Phi(-12),
+    which rounds to (minus) zero in fp16.  Range [0, 24] -> s_o = 24/255 in fp32, z_o = 0, codes 0, 85, 255, 0
+    (8 * 255/24 = 85, 24 * 255/24 = 255).  Where the product is exact in fp16 the static path with these parameters
+    gives the same codes."""
+    H, K = 4, 64
+    codes = np.zeros((2 * H, K), np.uint8)
+    s, z = np.ones(2 * H, np.float32), np.zeros(2 * H, np.int32)
+    bias = np.array([1.0, 1.0, 1.0, 1.0, 0.0, 8.0, 24.0, -12.0], np.float16)   # values | gates
+    x = np.ones((3, K), np.float16)
+    q, h16, out_act, _ = orc.linear_a8_geglu_dynamic(x, codes, s, z, act=(np.float32(1.0), 0), bias=bias)
+    assert out_act[0] == np.float32(24.0) / np.float32(255.0) and out_act[1] == 0
+    assert np.array_equal(q, np.tile(np.array([0, 85, 255, 0], np.uint8), (3, 1)))
+    assert np.array_equal(h16.view(np.float16)[:, :3], np.tile(np.array([0.0, 8.0, 24.0], np.float16), (3, 1)))
+    assert (h16[:, 3] & 0x7FFF == 0).all()
+    q_static, _, _ = orc.linear_a8_geglu(x, codes, s, z, out_act, act=(np.float32(1.0), 0), bias=bias)
+    assert np.array_equal(q, q_static)
+
+
+def test_geglu_dynamic_is_the_dynamic_quantiser_applied_to_the_fp16_product(orc):
+    """On a random layer: the parameters are those of the product's own range (zero included), every code is the
+    affine quantiser's, the extreme values take the codes 0 and 255, and a product scaled by 2 (value half of the
+    weight rows and bias doubled: exact in binary floating point) doubles the scale and keeps every code."""
+    x, w, b, c, s, z = _random_quantised_layer(orc, 72, 23, 128, 32, 4)
+    H = 16
+    act = (np.float32(0.031), 121)
+    q, h16, (so, zo), _ = orc.linear_a8_geglu_dynamic(x, c, s, z, act=act, bias=b)
+    h = h16.view(np.float16).astype(np.float64)
+    lo, hi = min(0.0, h.min()), max(0.0, h.max())
+    assert abs(float(so) - (hi - lo) / 255.0) <= 1e-6 * (hi - lo) / 255.0
+    assert zo == int(np.rint(-lo / float(so)))
+    assert q.reshape(-1)[h.argmax()] == 255 and q.reshape(-1)[h.argmin()] == 0
+    assert np.abs(q.astype(np.float64) - zo - h / float(so)).max() <= 0.5 + 1e-3
+    s2, b2 = s.copy(), b.copy()
+    s2[:H] *= 2.0
+    b2[:H] = (b[:H].astype(np.float32) * 2.0).astype(np.float16)
+    q2, h16_2, (so2, zo2), _ = orc.linear_a8_geglu_dynamic(x, c, s2, z, act=act, bias=b2)
+    assert so2 == np.float32(2.0) * so and zo2 == zo and np.array_equal(q2, q)
+
+
 def test_a8_from_codes_is_the_a8_linear_after_its_quantiser(orc):
     x, w, b, c, s, z = _random_quantised_layer(orc, 71, 19, 128, 24, 4)
     act = (np.float32(0.031), 121)
