@@ -275,7 +275,7 @@ size_t mq_a8_row_bytes(int K);
  *     h[m,j]    = lin[m,j] * gelu( lin[m,H+j] )                            j in [0,H)
  *     code[m,j] = clamp( rne(h / s_o) + z_o, 0, 255 )                      h / s_o as a multiply by the fp32 1/s_o
  * gelu(g) = 0.5 g (1 + erf(g / sqrt 2)).  ACC is exact; everything after it is evaluated in fp32 (erf as
- * 1 - exp(-x P(x)) with a fitted degree-6 polynomial P, |error| < 2e-7), so a code equals the one the same formulas
+ * 1 - exp(-x P(x)) with a fitted degree-6 polynomial P and the hardware's 2^t, |error| < 3e-7), so a code equals the one the same formulas
  * give in exact arithmetic except where h / s_o lies within that fp32 error (about 1e-5 of a code step for typical
  * values) of a rounding boundary, where it may be the neighbouring code.
  *   x [M,K] fp16 (as in mq_qlinear_w8a8, dynamic or static activation parameters), packed: w_bits = 2, 4 or 8,

@@ -508,7 +508,7 @@ def geglu_code_slack(u, lin, bias, H, out_scale):
     """How far the kernel's fp32 evaluation of u = value * gelu(gate) / s_o may lie from the oracle's fp64 one,
     element by element.  The integer accumulators are exact on both sides; the kernel then takes, each rounded once to
     fp32: s_x * s_w[n], (float)ACC, one fma per half (<= 4 roundings of 2^-24 on |lin| + |bias|), a GELU whose error
-    function is good to 2e-7 absolute (so gelu to 1e-7 |g| plus the slope 1.13 times the gate's error plus its own
+    function is good to 3e-7 absolute (so gelu to 1.5e-7 |g| plus the slope 1.13 times the gate's error plus its own
     rounding), the product, 1 / s_o and the multiplication by it (3 more roundings)."""
     e24 = 2.0 ** -24
     v, g = lin[:, :H], lin[:, H:]
