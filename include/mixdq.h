@@ -312,6 +312,16 @@ int mq_qlinear_w_only_geglu(const void* x, int M, int K, int ldx, const void* pa
                             const float* w_scale, const int32_t* w_zp, const void* bias, void* h, int ldh,
                             void* stream);
 
+/* The weight-only gated projection with 8-bit output, W{2,3,4,8}A16: for a feed-forward whose projection keeps
+ * 16-bit activations while its output linear takes 8-bit ones.  lin and h as above, code[m,j] = clamp(rne(h / s_o) +
+ * z_o, 0, 255) from the fp32 product (the accumulation is the fp16 MFMA's, so a code may be the neighbour of the one
+ * exact arithmetic gives where h / s_o lies within that arithmetic's error of a rounding boundary).
+ * out_scale, out_zp: device pointers to the static parameters; a8_out [M, mq_a8_row_bytes(H)] in the A8 layout;
+ * h16_out nullable [M,H] fp16 (row stride ldh). */
+int mq_qlinear_w_only_geglu_a8(const void* x, int M, int K, int ldx, const void* packed, int H, int bits, int layout,
+                               const float* w_scale, const int32_t* w_zp, const void* bias, const float* out_scale,
+                               const int32_t* out_zp, int8_t* a8_out, void* h16_out, int ldh, void* stream);
+
 /* W8A8 / W4A8 / W2A8 linear on activations that arrive as codes in the A8 layout (row stride lda bytes) together with
  * their parameters (device pointers act_scale, act_zp): ACC and Y as in mq_qlinear_w8a8.  The row sums of the
  * codes, which the zero-point correction needs, are taken inside the GEMM; no workspace.  residual: nullable fp16

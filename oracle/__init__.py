@@ -321,8 +321,10 @@ def conv3x3_a8(x, wcodes, w_scale, w_zp, w_signed=False, act=None, bias=None, pi
     return y, acc, (np.float32(s.value), int(z.value))
 
 
-def linear_w_only_geglu(x, codes, w_scale, w_zp, bias=None, dtype=F16, rows=None):
-    """Weight-only gated projection; codes [2H,K].  Returns h uint16 [R,H]."""
+def linear_w_only_geglu(x, codes, w_scale, w_zp, bias=None, dtype=F16, rows=None, out_act=None, want_pre=False):
+    """Weight-only gated projection; codes [2H,K].  Returns h uint16 [R,H]; with out_act = (scale, zp) of the gated
+    product: (codes uint8 [R,H], h) and, with want_pre, also (u float64 [R,H] = h / s_o before the rounding,
+    lin float64 [R,2H] = the projection before the gate)."""
     x = _u16(x)
     bias = _u16(bias)
     codes = np.ascontiguousarray(codes, np.uint8)
@@ -332,8 +334,17 @@ def linear_w_only_geglu(x, codes, w_scale, w_zp, bias=None, dtype=F16, rows=None
     rows, nr = _rows(rows)
     R = nr if rows is not None else M
     h = np.empty((R, H), np.uint16)
+    q = np.empty((R, H), np.uint8) if out_act is not None else None
+    u = np.empty((R, H), np.float64) if (want_pre and out_act is not None) else None
+    lin = np.empty((R, 2 * H), np.float64) if (want_pre and out_act is not None) else None
+    so, zo = (0.0, 0) if out_act is None else out_act
     _check(lib().orc_linear_w_only_geglu(_p(x), C.c_long(M), K, C.c_long(K), _p(codes), H,
                                          _p(np.ascontiguousarray(w_scale, np.float32)),
-                                         _p(np.ascontiguousarray(w_zp, np.int32)), _p(bias), dtype, _p(h), _p(rows),
+                                         _p(np.ascontiguousarray(w_zp, np.int32)), _p(bias), dtype, _p(h),
+                                         C.c_float(so), C.c_int32(zo), _p(q), _p(u), _p(lin), _p(rows),
                                          C.c_long(nr)), "linear_w_only_geglu")
-    return h
+    if out_act is None:
+        return h
+    if want_pre:
+        return q, h, u, lin
+    return q, h

@@ -669,11 +669,17 @@ int orc_conv3x3_a8(const uint16_t* x, int B, int H, int W, int Cin, const uint8_
 
 /* Weight-only gated projection: h[m,j] = lin[m,j] * gelu(lin[m,H+j]) with lin the weight-only linear over the 2H rows
  * of the weight matrix (first half value, second half gate), everything in fp64 with the library erf, one rounding to
- * the 16-bit output. */
+ * the 16-bit output.  With codes_out the gated product also leaves as 8-bit codes of the affine quantiser with the
+ * given static parameters, taken from the un-rounded product exactly as orc_linear_a8_geglu does:
+ * code = clamp(rne(h / s_o) + z_o, 0, 255); u_out (h / s_o before the rounding) and lin_out (the projection before the
+ * gate) are what a checker needs to tell a borderline rounding from a wrong code.  h16 may be NULL then. */
 int orc_linear_w_only_geglu(const uint16_t* x, long M, int K, long ldx, const uint8_t* codes, int H,
                             const float* w_scale, const int32_t* w_zp, const uint16_t* bias, int dtype, uint16_t* h16,
+                            float out_scale, int32_t out_zp, uint8_t* codes_out, double* u_out, double* lin_out,
                             const int64_t* rows, long nrows) {
-    if (!x || !codes || !w_scale || !w_zp || !h16 || M <= 0 || K <= 0 || H <= 0 || ldx < K) return ORC_BAD_ARG;
+    if (!x || !codes || !w_scale || !w_zp || (!h16 && !codes_out) || M <= 0 || K <= 0 || H <= 0 || ldx < K)
+        return ORC_BAD_ARG;
+    if (codes_out && !(out_scale > 0.0f)) return ORC_BAD_ARG;
     long R = rows ? nrows : M;
     if (R <= 0) return ORC_BAD_ARG;
     int N = 2 * H;
@@ -687,10 +693,20 @@ int orc_linear_w_only_geglu(const uint16_t* x, long M, int K, long ldx, const ui
                 acc += in16(x[m * ldx + k], dtype) * ((double)w_scale[n] * (double)((int)codes[(size_t)n * K + k] - w_zp[n]));
             if (bias) acc += in16(bias[n], dtype);
             lin[n] = acc;
+            if (lin_out) lin_out[r * (long)N + n] = acc;
         }
         for (int j = 0; j < H; ++j) {
             double g = lin[H + j];
-            h16[r * (long)H + j] = out16(lin[j] * gelu64(g), dtype);
+            double h = lin[j] * gelu64(g);
+            if (h16) h16[r * (long)H + j] = out16(h, dtype);
+            if (codes_out) {
+                double u = h / (double)out_scale;
+                double t = rint(u) + (double)out_zp;
+                if (t < 0.0) t = 0.0;
+                if (t > 255.0) t = 255.0;
+                codes_out[r * (long)H + j] = (uint8_t)t;
+                if (u_out) u_out[r * (long)H + j] = u;
+            }
         }
         free(lin);
     }

@@ -24,7 +24,7 @@ _ERRORS = {
 EXPORTS = ("mq_version", "mq_last_hip_error", "mq_tune_force_tile", "mq_tune_force_splits", "mq_tune_force_band", "mq_prof_enable", "mq_prof_num_slots", "mq_prof_read",
            "mq_prof_reset", "mq_prof_phase_buffer", "mq_prof_filter", "mq_prof_bracket_overhead_us", "mq_prof_copy", "mq_prof_microbench", "mq_quantize_weights", "mq_packed_bytes", "mq_pack_weights",
            "mq_unpack_weights", "mq_split_workspace_bytes", "mq_qlinear_w_only", "mq_qlinear_a8_workspace_bytes", "mq_qlinear_w8a8",
-           "mq_qlinear_w4a8", "mq_qlinear_w2a8", "mq_builtin_workspace_bytes", "mq_qlinear_a8_builtin_ws", "mq_a8_row_bytes", "mq_qlinear_a8_geglu", "mq_qlinear_a8_geglu_dynamic_workspace_bytes", "mq_qlinear_a8_geglu_dynamic", "mq_qlinear_w_only_geglu", "mq_qlinear_a8_codes", "mq_conv3x3_w_only",
+           "mq_qlinear_w4a8", "mq_qlinear_w2a8", "mq_builtin_workspace_bytes", "mq_qlinear_a8_builtin_ws", "mq_a8_row_bytes", "mq_qlinear_a8_geglu", "mq_qlinear_a8_geglu_dynamic_workspace_bytes", "mq_qlinear_a8_geglu_dynamic", "mq_qlinear_w_only_geglu", "mq_qlinear_w_only_geglu_a8", "mq_qlinear_a8_codes", "mq_conv3x3_w_only",
            "mq_conv_tap_sums", "mq_conv3x3_a8_workspace_bytes", "mq_conv3x3_a8",
            "mq_bos_aware_kv_proj_workspace_bytes", "mq_bos_aware_kv_proj", "mq_alloc_solve", "mq_alloc_split_budget",
            "mq_alloc_search")
@@ -418,6 +418,20 @@ def qlinear_w_only_geglu(x, w: PackedWeight, bias=None, out=None):
                                           _ptr(w.zp), _ptr(bias), _ptr(h), h.stride(0), _stream()),
            "mq_qlinear_w_only_geglu")
     return h
+
+
+def qlinear_w_only_geglu_a8(x, w: PackedWeight, out_act, bias=None, want_h16=False):
+    """Weight-only gated projection with 8-bit output; out_act = (scale, zp) one-element device tensors.
+    Returns (a8 int8 [M, a8_row_bytes(H)], h16 fp16 [M,H] or None)."""
+    assert x.is_cuda and x.dim() == 2 and x.stride(1) == 1 and x.dtype == torch.float16
+    M, K = x.shape
+    H = w.N // 2
+    a8 = torch.empty((M, a8_row_bytes(H)), dtype=torch.int8, device=x.device)
+    h16 = torch.empty((M, H), dtype=torch.float16, device=x.device) if want_h16 else None
+    _check(load().mq_qlinear_w_only_geglu_a8(_ptr(x), M, K, x.stride(0), _ptr(w.packed), H, w.bits, w.layout,
+                                             _ptr(w.scale), _ptr(w.zp), _ptr(bias), _ptr(out_act[0]), _ptr(out_act[1]),
+                                             _ptr(a8), _ptr(h16), H, _stream()), "mq_qlinear_w_only_geglu_a8")
+    return a8, h16
 
 
 def qlinear_a8_codes(a8, K: int, act, w: PackedWeight, bias=None, out=None, want_acc=False, residual=None):

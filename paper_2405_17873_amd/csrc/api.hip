@@ -315,7 +315,22 @@ int mq_qlinear_w_only_geglu(const void* x, int M, int K, int ldx, const void* pa
     int rc = check_linear_common(x, M, K, ldx, packed, 2 * H, layout, w_scale, w_zp, bias, h, 2 * H);
     if (rc) return rc;
     if (ldh < H || ldh % 8 != 0) return MQ_ERR_BAD_SHAPE;
-    return launch_gemm_w_only_geglu(x, M, K, ldx, packed, H, bits, w_scale, w_zp, bias, h, ldh, (hipStream_t)stream);
+    return launch_gemm_w_only_geglu(x, M, K, ldx, packed, H, bits, w_scale, w_zp, bias, h, ldh, nullptr, nullptr,
+                                    nullptr, (hipStream_t)stream);
+}
+
+int mq_qlinear_w_only_geglu_a8(const void* x, int M, int K, int ldx, const void* packed, int H, int bits, int layout,
+                               const float* w_scale, const int32_t* w_zp, const void* bias, const float* out_scale,
+                               const int32_t* out_zp, int8_t* a8_out, void* h16_out, int ldh, void* stream) {
+    if (!bits_ok(bits) || bits == 16) return MQ_ERR_UNSUPPORTED_BITS;
+    if (H <= 0 || H % 32 != 0 || H > (1 << 29)) return MQ_ERR_BAD_SHAPE;
+    int rc = check_linear_common(x, M, K, ldx, packed, 2 * H, layout, w_scale, w_zp, bias, a8_out, 2 * H);
+    if (rc) return rc;
+    if (!out_scale || !out_zp) return MQ_ERR_BAD_ARG;
+    if (h16_out && (!aligned(h16_out, 16) || ldh < H || ldh % 8 != 0)) return MQ_ERR_BAD_ARG;
+    if ((long)M * (long)mq_a8_row_bytes(H) >= (1L << 31)) return MQ_ERR_BAD_SHAPE;
+    return launch_gemm_w_only_geglu(x, M, K, ldx, packed, H, bits, w_scale, w_zp, bias, h16_out, ldh, out_scale, out_zp,
+                                    a8_out, (hipStream_t)stream);
 }
 
 int mq_qlinear_a8_codes(const int8_t* a8, int M, int K, int lda, const float* act_scale, const int32_t* act_zp,

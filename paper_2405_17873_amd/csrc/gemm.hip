@@ -451,17 +451,20 @@ struct GemmPlan {
 // their parameters; the row sums the epilogue needs are accumulated in the main loop.  MODE 3 / 4: 3x3 convolution
 // (16-bit / 8-bit activations).  MODE 5 (int8): the gated projection of MODE 1 without output parameters: it writes
 // the fp16 product and one (min, max) pair per workgroup, from which the codes follow in a pass of their own.
+// MODE 6 (16-bit activations): the gated projection of the weight-only path with MODE 1's 8-bit output.
 template <bool I8, int BITS, int WGM, int WGN, int TM, int TN, int S, int KS, bool BF = false, int MODE = 0,
           bool RES = false>
 __global__ __launch_bounds__(WGM* WGN* KS * 64,
                              (TM * TN <= 8 && GemmPlan<I8, BITS, WGM, WGN, TM, TN, S, KS>::LDS_BYTES <= 80 * 1024) ? 2 : 1)
 void gemm_kernel(const GemmArgs g) {
     static_assert(!(I8 && BF), "the int8 path writes fp16");
-    constexpr bool GEGLU = MODE == 1 || MODE == 5, RS_INLINE = MODE == 2 || MODE == 4, CONV = MODE == 3 || MODE == 4;
-    constexpr bool RANGE = MODE == 5;  // gated projection that leaves the fp16 product and its range, no codes
+    constexpr bool GEGLU = MODE == 1 || MODE == 5 || MODE == 6, RS_INLINE = MODE == 2 || MODE == 4, CONV = MODE == 3 || MODE == 4;
+    constexpr bool RANGE = MODE == 5;    // gated projection that leaves the fp16 product and its range, no codes
+    constexpr bool CODES16 = MODE == 6;  // gated projection of the 16-bit-activation path that emits 8-bit codes
     static_assert(MODE == 0 || KS == 1, "the special modes have no in-workgroup k split");
     static_assert(!(RES && GEGLU), "the gated projection takes no residual");
     static_assert(!RANGE || (I8 && !BF), "the range output belongs to the int8 gated projection");
+    static_assert(!CODES16 || (!I8 && !BF), "MODE 6 is the fp16 weight-only gated projection with 8-bit output");
     static_assert((MODE != 2 && MODE != 4) || I8, "int8 modes");
     static_assert(MODE != 3 || !I8, "MODE 3 is the weight-only convolution");
     static_assert(!GEGLU || TN == 2, "value tile and gate tile per wave");
@@ -1003,7 +1006,7 @@ void gemm_kernel(const GemmArgs g) {
         // Rows are staged through LDS (32 rows x 32 bytes per wave) and leave as 16-byte pieces.
         // (without output parameters the kernel only writes the product and its range: the codes follow in a pass of
         // their own once the range of the whole tensor is known)
-        constexpr bool want_codes = I8 && !RANGE;
+        constexpr bool want_codes = (I8 && !RANGE) || CODES16;
         float inv_o = 0.0f, zf_o = 0.0f;
         if constexpr (want_codes) {
             inv_o = __fdiv_rn(1.0f, *g.out_scale_p);
@@ -1429,7 +1432,7 @@ static int run_gemm_r(GemmArgs& g, int tile_index, hipStream_t st) {
     static_assert(P::LDS_BYTES <= 160 * 1024, "LDS plan exceeds the compute unit");
     g.tiles_m = (g.M + P::BM - 1) / P::BM;
     g.tiles_n = (g.N + P::BN - 1) / P::BN;
-    if (MODE == 1 || MODE == 5) g.tiles_n = (int)((g.ld8 + P::BN / 2 - 1) / (P::BN / 2));  // gated columns up to the padded row end
+    if (MODE == 1 || MODE == 5 || MODE == 6) g.tiles_n = (int)((g.ld8 + P::BN / 2 - 1) / (P::BN / 2));  // gated columns up to the padded row end
     // Split the reduction over workgroups where the tiles alone would leave most compute units idle and the reduction
     // is long: as many parts as fill about two workgroups per compute unit, each at least four pipeline stages long.
     const long tiles = (long)g.tiles_m * g.tiles_n;
@@ -1474,7 +1477,7 @@ static int run_gemm_r(GemmArgs& g, int tile_index, hipStream_t st) {
     auto kern = gemm_kernel<I8, BITS, WGM, WGN, TM, TN, S, KS, BF, MODE, RES>;
     // Once per instantiation and device (callers may be on several host threads): allow more than 64 KB of dynamic
     // LDS, name the profiling slot.
-    const int slot = prof_gemm_slot(MODE == 5 ? 3 : (MODE ? 2 + MODE : (I8 ? 1 : (BF ? 2 : 0))), BITS, tile_index);
+    const int slot = prof_gemm_slot(MODE >= 5 ? 3 : (MODE ? 2 + MODE : (I8 ? 1 : (BF ? 2 : 0))), BITS, tile_index);
     static std::mutex prep_mutex;
     static bool prepared[16] = {};
     int dev = 0;
@@ -1498,7 +1501,7 @@ static int run_gemm_r(GemmArgs& g, int tile_index, hipStream_t st) {
     // (a convolution reads each input pixel once, not nine times: the whole input tensor)
     const double abytes = MODE == 3 || MODE == 4 ? (double)g.a_bytes
                                     : (I8 ? 1.0 * g.M * g.K + (MODE == 0 ? 4.0 * g.M : 0.0) : 2.0 * g.M * g.K);
-    const double ybytes = MODE == 1 ? 1.0 * g.M * g.ld8 + (g.y ? 1.0 * g.M * g.N : 0.0)
+    const double ybytes = MODE == 1 || MODE == 6 ? 1.0 * g.M * g.ld8 + (g.y ? 1.0 * g.M * g.N : 0.0)
                                     : (MODE == 5 ? 1.0 * g.M * g.N : 2.0 * g.M * g.N);
     ProfScope prof(st, slot, 2.0 * g.M * g.N * g.K,
                    abytes + (double)g.N * g.K * BITS / 8 + (I8 ? 14.0 : 10.0) * g.N + ybytes);
@@ -1513,7 +1516,7 @@ static int run_gemm_r(GemmArgs& g, int tile_index, hipStream_t st) {
 
 template <bool I8, int BITS, int WGM, int WGN, int TM, int TN, int KS, int BUDGET, int MAXS, bool BF = false, int MODE = 0>
 static int run_gemm(GemmArgs& g, int tile_index, hipStream_t st) {
-    if constexpr (MODE != 1 && MODE != 5)
+    if constexpr (MODE != 1 && MODE != 5 && MODE != 6)
         if (g.res) return run_gemm_r<I8, BITS, WGM, WGN, TM, TN, KS, BUDGET, MAXS, BF, MODE, true>(g, tile_index, st);
     return run_gemm_r<I8, BITS, WGM, WGN, TM, TN, KS, BUDGET, MAXS, BF, MODE, false>(g, tile_index, st);
 }
@@ -1680,6 +1683,10 @@ int launch_gemm_a8_geglu(const int8_t* a8, const int32_t* rowsum, const ActParam
 template <int BITS>
 static int dispatch_w_only_geglu(GemmArgs& g, int H, hipStream_t st) {
     const bool big = g_force_tile == 0 || (g_force_tile < 0 && (long)((g.M + 127) / 128) * ((H + 127) / 128) >= 512);
+    if (g.a8_out) {  // 8-bit codes out
+        if (big) return run_gemm<false, BITS, 1, 4, 4, 2, 1, 80 * 1024, 4, false, 6>(g, 0, st);
+        return run_gemm<false, BITS, 2, 2, 2, 2, 1, 80 * 1024, 4, false, 6>(g, 1, st);
+    }
     if (big) return run_gemm<false, BITS, 1, 4, 4, 2, 1, 80 * 1024, 4, false, 1>(g, 0, st);
     return run_gemm<false, BITS, 2, 2, 2, 2, 1, 80 * 1024, 4, false, 1>(g, 1, st);
 }
@@ -1687,8 +1694,9 @@ static int dispatch_w_only_geglu(GemmArgs& g, int H, hipStream_t st) {
 // Weight-only gated projection, fp16 out (MODE 1 on the fp16 path).
 int launch_gemm_w_only_geglu(const void* x, int M, int K, int ldx, const void* packed, int H, int bits,
                              const float* w_scale, const int32_t* w_zp, const void* bias, void* h16, int ldh,
-                             hipStream_t st) {
+                             const float* out_scale, const int32_t* out_zp, int8_t* a8_out, hipStream_t st) {
     GemmArgs g{};
+    g.out_scale_p = out_scale; g.out_zp_p = out_zp; g.a8_out = a8_out;
     g.a = x;
     g.a_row_bytes = (long)ldx * 2;
     g.a_bytes = (uint32_t)(((long)(M - 1) * ldx + K) * 2);
@@ -1698,7 +1706,7 @@ int launch_gemm_w_only_geglu(const void* x, int M, int K, int ldx, const void* p
     g.k_stages = K / 64;
     g.w_scale = w_scale; g.w_zp = w_zp; g.bias = (const uint16_t*)bias;
     g.y = (uint16_t*)h16; g.ldy = ldh;
-    g.ld8 = H;  // no code output: the grid covers the H gated columns
+    g.ld8 = a8_out ? (H + 127) / 128 * 128 : H;  // without code output the grid covers the H gated columns only
     switch (bits) {
         case 2: return dispatch_w_only_geglu<2>(g, H, st);
         case 3: return dispatch_w_only_geglu<3>(g, H, st);

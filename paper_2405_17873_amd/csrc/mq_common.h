@@ -126,7 +126,7 @@ int launch_gemm_a8_geglu(const int8_t* a8, const int32_t* rowsum, const ActParam
                          int8_t* a8_out, void* h16, int ldh, float* mm_out, int* mm_pairs, hipStream_t st);
 int launch_gemm_w_only_geglu(const void* x, int M, int K, int ldx, const void* packed, int H, int bits,
                              const float* w_scale, const int32_t* w_zp, const void* bias, void* h16, int ldh,
-                             hipStream_t st);
+                             const float* out_scale, const int32_t* out_zp, int8_t* a8_out, hipStream_t st);
 int launch_gemm_a8_codes(const int8_t* a8, long lda, const float* act_scale, const int32_t* act_zp, int M, int K,
                          const void* packed, int N, int w_bits, int w_signed, const float* w_scale, const int32_t* w_zp,
                          const int32_t* w_colsum, const void* bias, void* y, int ldy, int32_t* acc_debug,

@@ -118,6 +118,11 @@ def test_error_codes_without_a_gpu(lib):
     assert lib.mq_qlinear_a8_geglu_dynamic(*gd(ldh=16)) == -2
     assert lib.mq_qlinear_a8_geglu_dynamic(*gd(wsb=lib.mq_qlinear_a8_workspace_bytes(8, 64))) == -4
     assert lib.mq_qlinear_a8_geglu_dynamic_workspace_bytes(8, 64, 32) > lib.mq_qlinear_a8_workspace_bytes(8, 64)
+    # weight-only gated projection with 8-bit output
+    wg = lambda **o: [p, 8, 64, 64, p, o.get("H", 32), o.get("bits", 4), 1, p, p, null, o.get("so", p), p, p, null, 32, st]
+    assert lib.mq_qlinear_w_only_geglu_a8(*wg(so=null)) == -1
+    assert lib.mq_qlinear_w_only_geglu_a8(*wg(bits=16)) == -3
+    assert lib.mq_qlinear_w_only_geglu_a8(*wg(H=40)) == -2
     # bos
     bos = lambda **o: [p, o.get("B", 2), 5, 64, p, 32, o.get("wb", 8), 1, 1, p, p, p, o.get("wf", null),
                        o.get("bo", null), null, null, null, p, 0, null, null, p, C.c_size_t(1 << 20), st]

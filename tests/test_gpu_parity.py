@@ -504,17 +504,21 @@ def a8_unlayout(a8, K):
     return (lin[:, :K].astype(np.int16) + 128).astype(np.uint8), lin[:, K:]
 
 
-def geglu_code_slack(u, lin, bias, H, out_scale):
+def geglu_code_slack(u, lin, bias, H, out_scale, acc_err=None):
     """How far the kernel's fp32 evaluation of u = value * gelu(gate) / s_o may lie from the oracle's fp64 one,
     element by element.  The integer accumulators are exact on both sides; the kernel then takes, each rounded once to
     fp32: s_x * s_w[n], (float)ACC, one fma per half (<= 4 roundings of 2^-24 on |lin| + |bias|), a GELU whose error
     function is good to 3e-7 absolute (so gelu to 1.5e-7 |g| plus the slope 1.13 times the gate's error plus its own
-    rounding), the product, 1 / s_o and the multiplication by it (3 more roundings)."""
+    rounding), the product, 1 / s_o and the multiplication by it (3 more roundings).
+    acc_err [R, 2H]: what the accumulation itself may be off by where it is not exact (the fp16 MFMA path)."""
     e24 = 2.0 ** -24
     v, g = lin[:, :H], lin[:, H:]
     bv, bg = np.abs(bias[:H].astype(np.float64))[None, :], np.abs(bias[H:].astype(np.float64))[None, :]
     e_v = 4 * e24 * (np.abs(v) + bv)
     e_g = 4 * e24 * (np.abs(g) + bg)
+    if acc_err is not None:
+        e_v = e_v + acc_err[:, :H]
+        e_g = e_g + acc_err[:, H:]
     from scipy.special import erf
     gelu = 0.5 * g * (1.0 + erf(g / np.sqrt(2.0)))
     e_gelu = 1.13 * e_g + 1.5e-7 * np.maximum(np.abs(g), 1.0) + 2 * e24 * np.abs(gelu)
@@ -563,6 +567,37 @@ def test_geglu_projection_codes_against_the_fp64_oracle(mq, orc, bits, sym, tile
                 what = f"geglu codes b{bits} tile{tile} {M}x{K}x{H}"
                 assert_geglu_codes(codes, rq, u, geglu_code_slack(u, lin, b, H, out_act[0]), out_act[1], what)
                 assert_close16(host(h16), rh, what + " (gated product in fp16)")
+    finally:
+        mq.tune_force_tile(-1)
+
+
+@pytest.mark.parametrize("bits", (2, 3, 4, 8))
+@pytest.mark.parametrize("tile", (-1, 0, 1))
+def test_w_only_geglu_projection_with_8_bit_output(mq, orc, bits, tile):
+    """The gated projection of the 16-bit-activation path emitting 8-bit codes.  Same rule as for the int8 projection
+    (equal codes, or neighbours at a rounding boundary), with the error of the fp32 accumulation of the fp16 MFMA
+    added to the bound: the products are exact, every MFMA adds a 16-term dot product to an fp32 accumulator, so a
+    sum of K terms is off by at most (K/16 + 4) 2^-24 times the sum of their magnitudes."""
+    mq.tune_force_tile(tile)
+    try:
+        for (M, K, H) in ((256, 320, 320), (77, 128, 32), (300, 640, 96), (130, 1280, 160)):
+            x = si.activations_f16(65, f"wg/x{M}x{K}", M, K, outlier_prob=0.01)
+            w = si.weights_f16(65, f"wg/w{H}x{K}", 2 * H, K)
+            b = si.bias_f16(65, f"wg/b{H}", 2 * H)
+            pw, oc, os_, oz = make_weight(mq, orc, w, bits)
+            out_act = (np.float32(0.006), 28)
+            d_out = (dev(np.array([out_act[0]], np.float32)), dev(np.array([out_act[1]], np.int32)))
+            a8, h16 = mq.qlinear_w_only_geglu_a8(dev(x), pw, d_out, bias=dev(b), want_h16=True)
+            rq, rh, u, lin = orc.linear_w_only_geglu(x, oc, os_, oz, bias=b, out_act=out_act, want_pre=True)
+            wmag = np.abs(oc.astype(np.float64) - oz[:, None]) * os_[:, None].astype(np.float64)
+            acc_err = (K / 16 + 4) * 2.0 ** -24 * (np.abs(x.astype(np.float64)) @ wmag.T)
+            codes, pad = a8_unlayout(host(a8), H)
+            assert a8.shape[1] == (H + 127) // 128 * 128 and not pad.any()
+            what = f"w-only geglu codes b{bits} tile{tile} {M}x{K}x{H}"
+            assert_geglu_codes(codes, rq, u, geglu_code_slack(u, lin, b, H, out_act[0], acc_err), out_act[1], what)
+            assert_close16(host(h16), rh, what + " (gated product in fp16)")
+            a8b, none = mq.qlinear_w_only_geglu_a8(dev(x), pw, d_out, bias=dev(b))   # without the fp16 product
+            assert none is None and torch.equal(a8b, a8)
     finally:
         mq.tune_force_tile(-1)
 

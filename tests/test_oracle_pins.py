@@ -518,6 +518,36 @@ def test_geglu_gate_function_through_the_layer_closed_forms(orc):
         assert abs(gelu[g] - g * phi) < 1e-9 * 4
 
 
+def test_w_only_geglu_codes_by_hand_and_against_the_a8_projection(orc):
+    """(i) Zero weights leave lin = bias: values 1, gates 0, 8, 24, -12 with s_o = 0.1, z_o = 3 give the codes
+    3, 83, 243, 3.  (ii) Activations that ARE 8-bit codes times a power-of-two scale make the 8-bit path's linear
+    outputs equal to the weight-only path's (both exact up to the fp64 sum): the two oracle functions, written
+    separately, must then agree on every code and on the fp16 product."""
+    H, K = 4, 64
+    codes = np.zeros((2 * H, K), np.uint8)
+    s, z = np.ones(2 * H, np.float32), np.zeros(2 * H, np.int32)
+    bias = np.array([1.0, 1.0, 1.0, 1.0, 0.0, 8.0, 24.0, -12.0], np.float16)
+    x = np.ones((2, K), np.float16)
+    q, h = orc.linear_w_only_geglu(x, codes, s, z, bias=bias, out_act=(np.float32(0.1), 3))
+    assert np.array_equal(q, np.tile(np.array([3, 83, 243, 3], np.uint8), (2, 1)))
+    # (ii)
+    rng = np.random.default_rng(5)
+    M, K, H = 9, 128, 8
+    w = si.weights_f16(73, "pin/gw", 2 * H, K)
+    b = si.bias_f16(73, "pin/gb", 2 * H)
+    c, sw, zw = orc.quantize_weights(w, 4)
+    qx = rng.integers(0, 256, (M, K)).astype(np.uint8)
+    act = (np.float32(2.0 ** -5), 131)
+    x = ((qx.astype(np.float32) - act[1]) * act[0]).astype(np.float16)          # exact in fp16: |q - z| < 2^8
+    assert np.array_equal(orc.act_quantize(x, *act), qx)
+    out_act = (np.float32(0.004), 17)
+    q16, h16, u16, lin16 = orc.linear_w_only_geglu(x, c, sw, zw, bias=b, out_act=out_act, want_pre=True)
+    q8, h8, _, u8, lin8 = orc.linear_a8_geglu(x, c, sw, zw, out_act, act=act, bias=b, want_pre=True)
+    assert np.abs(lin16 - lin8).max() <= 1e-12 * max(1.0, np.abs(lin8).max())
+    near = np.abs(u8 - np.floor(u8) - 0.5) < 1e-9                                # (none in practice)
+    assert np.array_equal(q16[~near], q8[~near]) and np.array_equal(h16, h8)
+
+
 def test_geglu_dynamic_output_parameters_by_hand(orc):
     """Zero weights leave lin = bias.  Values 1, gates 0, 8, 24, -12: the gated product is 0, 8, 24 and -12 Phi(-12),
     which rounds to (minus) zero in fp16.  Range [0, 24] -> s_o = 24/255 in fp32, z_o = 0, codes 0, 85, 255, 0
